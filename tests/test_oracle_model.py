@@ -1,0 +1,199 @@
+"""Pins for the whole-model oracle: two independent formulations must agree
+(full-sequence forward vs incremental paged rollout), plus paging, chunking,
+sharing, replay and finish-rule invariants.  CPU only."""
+import numpy as np
+import pytest
+
+import oracle as O
+import rollout_inputs as RI
+
+DENSE = RI.TINY_DENSE.replace(n_layers=2, vocab=512)
+DENSE_QKN = DENSE.replace(name="tiny_dense_qkn", qk_norm=True)
+MOE = RI.TINY_MOE.replace(n_layers=2, vocab=512, d_model=128, n_experts=16, d_ff_expert=48)
+
+
+def _prompts(shape, lens, seed=7):
+    return RI.workload_tiny(shape, lens=lens, prompt_seed=seed).prompt_tokens
+
+
+@pytest.mark.parametrize("shape", [DENSE, DENSE_QKN, MOE], ids=lambda s: s.name)
+def test_incremental_equals_full_forward(shape):
+    model = O.OracleModel(shape, model_seed=3)
+    toks = _prompts(shape, (9, 21))
+    n_dec = 6
+    ro = O.OracleRollout(model, n_blocks=16)
+    ids = [ro.add_sequence(seed=100 + i) for i in range(2)]
+    got_logits = [[], []]
+    seqs = [list(t) for t in toks]
+    routes = [[], []]
+    r = ro.prefill_chunk(ids, toks, want_logits=True)
+    for step in range(n_dec):
+        for j in range(2):
+            got_logits[j].append(r["logits"][j])
+            seqs[j].append(r["tokens"][j])
+            if shape.is_moe:
+                routes[j].append(r["routing"][j])
+        r = ro.decode_step(ids, want_logits=True)
+    full = O.forward_full(model, [np.array(s[:-1], np.int32) for s in seqs])
+    for j in range(2):
+        n0 = len(toks[j])
+        z_full = full[j]["logits"][n0 - 1:]
+        np.testing.assert_allclose(np.stack(got_logits[j]), z_full, atol=1e-4, rtol=0)
+        if shape.is_moe:
+            np.testing.assert_array_equal(np.concatenate(routes[j], 0), full[j]["routing"][: n0 + n_dec - 1])
+
+
+def test_float32_oracle_close_to_float64():
+    toks = _prompts(MOE, (24,))
+    z32 = O.forward_full(O.OracleModel(MOE, 3, dtype=np.float32), toks)[0]
+    z64 = O.forward_full(O.OracleModel(MOE, 3, dtype=np.float64), toks)[0]
+    assert np.abs(z32["logits"] - z64["logits"]).max() < 2e-4
+    stable = z64["gate_gap"] > 1e-3
+    assert stable.mean() > 0.9
+    same = (np.sort(z32["routing"], -1) == np.sort(z64["routing"], -1)).all(-1)
+    assert same[stable].all()
+
+
+@pytest.mark.parametrize("shape", [DENSE, MOE], ids=lambda s: s.name)
+def test_chunked_prefill_invariance(shape):
+    model = O.OracleModel(shape, 5)
+    tok = _prompts(shape, (37,))[0]
+    outs = []
+    for chunks in ([37], [16, 16, 5], [1] * 37, [7, 30]):
+        ro = O.OracleRollout(model, n_blocks=8)
+        i = ro.add_sequence(seed=1)
+        p = 0
+        routes = []
+        for c in chunks:
+            last = p + c == 37
+            r = ro.prefill_chunk([i], [tok[p:p + c]], sample_last=[last], want_logits=True)
+            routes.append(r["routing"][0])
+            p += c
+        outs.append((r["logits"][0], r["tokens"][0], r["logprobs"][0], np.concatenate(routes, 0)))
+    for o in outs[1:]:
+        np.testing.assert_allclose(o[0], outs[0][0], atol=1e-4)
+        assert o[1] == outs[0][1]
+        assert abs(o[2] - outs[0][2]) < 1e-4
+        if shape.is_moe:
+            np.testing.assert_array_equal(o[3], outs[0][3])
+
+
+def test_paging_invariants():
+    model = O.OracleModel(DENSE, 5)
+    toks = _prompts(DENSE, (19, 33))
+    def run(block_size, order=None, n_blocks=64):
+        ro = O.OracleRollout(model, n_blocks=n_blocks, block_size=block_size, alloc_order=order)
+        ids = [ro.add_sequence(seed=10 + i) for i in range(2)]
+        res = [ro.prefill_chunk(ids, toks, want_logits=True)]
+        for _ in range(4):
+            res.append(ro.decode_step(ids, want_logits=True))
+        return res
+    base = run(16)
+    perm = list(np.random.default_rng(0).permutation(64))
+    for other in (run(16, perm), run(1), run(64), run(5)):
+        for a, b in zip(base, other):
+            assert a["tokens"] == b["tokens"]
+            for za, zb in zip(a["logits"], b["logits"]):
+                np.testing.assert_allclose(za, zb, atol=1e-5)
+
+
+def test_shared_prefix_equals_private_copies_and_slot_independence():
+    model = O.OracleModel(DENSE, 5)
+    tok = _prompts(DENSE, (23,))[0]
+    # private: three sequences each prefill the same prompt
+    ro = O.OracleRollout(model, n_blocks=32)
+    ids = [ro.add_sequence(seed=s) for s in (50, 51, 52)]
+    priv = [ro.prefill_chunk(ids, [tok] * 3)]
+    for _ in range(5):
+        priv.append(ro.decode_step(ids))
+    # shared: prefill once without sampling the continuation of the last token, fork, then sample
+    ro2 = O.OracleRollout(model, n_blocks=32)
+    base = ro2.add_sequence(seed=0)
+    ro2.prefill_chunk([base], [tok[:-1]], sample_last=[False])
+    kids = [ro2.fork(base, seed=s) for s in (52, 50, 51)]            # different batch slots
+    sh = [ro2.prefill_chunk(kids, [tok[-1:]] * 3)]
+    for _ in range(5):
+        sh.append(ro2.decode_step(kids))
+    assert ro2.blocks[kids[0]][0] == ro2.blocks[base][0] and ro2.blocks[kids[0]][1] != ro2.blocks[base][1]
+    for a, b in zip(priv, sh):
+        assert [a["tokens"][0], a["tokens"][1], a["tokens"][2]] == [b["tokens"][1], b["tokens"][2], b["tokens"][0]]
+        np.testing.assert_allclose([a["logprobs"][i] for i in (0, 1, 2)], [b["logprobs"][i] for i in (1, 2, 0)],
+                                   atol=1e-5)
+    # group members with different seeds diverge
+    assert len({tuple(r["tokens"]) for r in priv}) > 1 and priv[1]["tokens"][0] != priv[1]["tokens"][1]
+
+
+def test_logprob_is_log_softmax_of_logits_and_sampling_rule():
+    model = O.OracleModel(DENSE, 5)
+    tok = _prompts(DENSE, (12,))[0]
+    ro = O.OracleRollout(model, n_blocks=8)
+    i = ro.add_sequence(seed=77, temperature=0.8)
+    r = ro.prefill_chunk([i], [tok], want_logits=True)
+    z = r["logits"][0].astype(np.float64)
+    lp = z / 0.8 - np.log(np.exp(z / 0.8).sum())
+    assert abs(lp[r["tokens"][0]] - r["logprobs"][0]) < 1e-4
+    # the token that lands at position 12 is drawn with the noise of position 12
+    assert r["tokens"][0] == O.sample_gumbel_max(r["logits"][0], 0.8, 77, 12)
+    r2 = ro.decode_step([i], want_logits=True)
+    assert r2["tokens"][0] == O.sample_gumbel_max(r2["logits"][0], 0.8, 77, 13)
+
+
+def test_teacher_forcing_and_finish_rules():
+    model = O.OracleModel(DENSE, 5)
+    s = DENSE
+    tok = _prompts(DENSE, (10,))[0]
+    ro = O.OracleRollout(model, n_blocks=8)
+    i = ro.add_sequence(seed=1, max_ctx=10 + 3)          # prompt 10 + three response tokens
+    free = ro.prefill_chunk([i], [tok], want_logits=True)
+    # forcing: the forced token is appended and scored, the sampled one still reported
+    ro2 = O.OracleRollout(model, n_blocks=8)
+    j = ro2.add_sequence(seed=1, max_ctx=10 + 3)
+    forced = (free["tokens"][0] + 5) % (s.vocab - 2)
+    f = ro2.prefill_chunk([j], [tok], forced_tokens=[forced], want_logits=True)
+    assert f["sampled"][0] == free["tokens"][0] and f["tokens"][0] == forced
+    assert abs(f["logprobs"][0] - O.log_softmax(f["logits"][0])[forced]) < 1e-6
+    # length cap: third response token (position 12) is forced to EOS and scored as EOS
+    a = ro.decode_step([i])
+    assert not ro.finished[i] and a["tokens"][0] != s.eos_token_id
+    b = ro.decode_step([i], want_logits=True)
+    assert ro.finished[i] and b["tokens"][0] == s.eos_token_id
+    assert abs(b["logprobs"][0] - O.log_softmax(b["logits"][0])[s.eos_token_id]) < 1e-6
+    ctx = ro.ctx[i]
+    c = ro.decode_step([i])                               # finished rows are inert
+    assert c["tokens"][0] == s.pad_token_id and c["logprobs"][0] == 0.0 and ro.ctx[i] == ctx == 12
+    # a natural EOS (here: forced in) also finishes the sequence
+    ro3 = O.OracleRollout(model, n_blocks=8)
+    k = ro3.add_sequence(seed=1)
+    ro3.prefill_chunk([k], [tok], forced_tokens=[s.eos_token_id])
+    assert ro3.finished[k]
+
+
+def test_injected_embeddings_and_multi_turn_state():
+    model = O.OracleModel(MOE, 9)
+    wl = RI.workload_omni_agentic(MOE, batch=2, mm_lo=5, mm_hi=9, n_text=6, n_turns=2, tool_len=4, turn_decode=3)
+    # an injected row equal to a token's embedding row must behave exactly like that token
+    tok = wl.prompt_tokens[0].copy()
+    n_mm = int((tok < 0).sum())
+    emb_bits = RI.tensor_bf16(MOE, 9, RI.GLOBAL_LAYER, "embed")
+    ids_as_tokens = np.arange(n_mm, dtype=np.int32) + 3
+    a = O.forward_full(model, [tok], [emb_bits[ids_as_tokens]])[0]["logits"]
+    tok2 = tok.copy(); tok2[:n_mm] = ids_as_tokens
+    b = O.forward_full(model, [tok2])[0]["logits"]
+    np.testing.assert_array_equal(a, b)
+    # multi-turn: KV carried across turns == one teacher-forced pass over the whole transcript
+    ro = O.OracleRollout(model, n_blocks=16)
+    i = ro.add_sequence(seed=5)
+    ro.prefill_chunk([i], [wl.prompt_tokens[0]], [wl.prompt_embeds[0]], sample_last=[False])
+    transcript = list(wl.prompt_tokens[0])
+    logits = []
+    for turn in wl.turns[0]:
+        r = ro.prefill_chunk([i], [turn.tool_tokens], want_logits=True)
+        transcript += list(turn.tool_tokens)
+        for _ in range(turn.n_decode):
+            logits.append((len(transcript) - 1, r["logits"][0]))
+            transcript.append(r["tokens"][0])
+            r = ro.decode_step([i], want_logits=True)
+    # the last sampled token of a turn is still fed (its KV is needed by the next turn's tool chunk)
+    full = O.forward_full(model, [np.array(transcript, np.int32)], [wl.prompt_embeds[0]])[0]["logits"]
+    for pos, z in logits:
+        np.testing.assert_allclose(z, full[pos], atol=1e-4)
