@@ -1,0 +1,196 @@
+/*
+ * relax_rollout.h -- C ABI of the MI355X (gfx950) rollout-decode library.
+ *
+ * The library computes the rollout stage of the asynchronous RL engine of
+ * arXiv 2604.11554 on one GPU: batched autoregressive decoding of a dense or MoE
+ * decoder-only policy.  Per step it emits the fields that stage hands to the rest
+ * of the system: the sampled token, its log-probability under the behaviour policy
+ * (paper Sec. 3.3: responses and log probabilities are independent per-sample
+ * fields; App. B.3: the trainer's importance ratios use them) and, for MoE
+ * policies, the top-K expert indices taken at every MoE layer for every token, for
+ * Rollout Routing Replay (paper Sec. 5.5).  Sequence state (a paged KV cache and
+ * block table) persists across calls, so multi-turn sessions (paper Sec. 4.3) are
+ * a sequence of prefill_chunk / decode_step calls.
+ *
+ * Conventions
+ *  - Every array argument is a DEVICE pointer unless its comment says HOST.
+ *  - All matrices are bf16, row-major [out_features, in_features] (y = x W^T).
+ *  - The caller owns every buffer (weights, KV pool, workspace, inputs, outputs);
+ *    weights must outlive the model handle.  The library allocates device memory
+ *    only in rlx_model_create (a few KB of pointer tables) and frees it in
+ *    rlx_model_destroy; prefill/decode never allocate or synchronise.
+ *  - `stream` is a hipStream_t passed as void*; calls only enqueue work on it.
+ *    Results are valid once the caller has synchronised the stream.
+ *  - Every function returns 0 on success or a negative RLX_E* code; nothing
+ *    aborts, throws or prints.  rlx_last_error() gives a thread-local message.
+ *    Arguments are validated on the host before the first launch; on error no
+ *    work has been enqueued.
+ *  - A model handle is immutable after creation; concurrent calls must use
+ *    distinct workspaces (and distinct sequences of the KV pool).
+ */
+#ifndef RELAX_ROLLOUT_H
+#define RELAX_ROLLOUT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RLX_API __attribute__((visibility("default")))
+
+#define RLX_OK 0
+#define RLX_EINVAL (-1)       /* bad shape / NULL / limit exceeded                */
+#define RLX_ENOMEM (-2)       /* workspace too small                              */
+#define RLX_EHIP (-3)         /* a HIP runtime call failed                        */
+#define RLX_EUNSUPPORTED (-4) /* shape outside what the kernels are built for     */
+
+typedef struct rlx_model rlx_model;
+
+/* Shape of the policy.  Plain data, passed by const pointer. */
+typedef struct {
+  uint32_t struct_size;  /* = sizeof(rlx_model_config) */
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim; /* head_dim 64 or 128 */
+  int32_t d_ff;                                               /* dense SwiGLU width, 0 for MoE */
+  int32_t n_experts, top_k, d_ff_expert;                      /* 0,0,0 for dense; n_experts <= 256, top_k <= 8 */
+  int32_t vocab;
+  int32_t kv_block_size; /* tokens per KV page; must be 16 */
+  float rms_eps;         /* RMSNorm epsilon, added to the mean square */
+  float rope_theta;      /* rotary base; pair (i, i+head_dim/2) turns by pos*theta^(-2i/head_dim) */
+  int32_t qk_norm;       /* 1: per-head RMSNorm of q and k before the rotary embedding */
+  int32_t eos_token_id, pad_token_id;
+} rlx_model_config;
+
+/*
+ * Weights.  Scalars point at device tensors; the per-layer members are HOST arrays
+ * of n_layers device pointers (copied at create).  Shapes (bf16):
+ *   embed, lm_head [vocab, d_model]; final_norm [d_model]
+ *   attn_norm, ffn_norm [d_model]; q_norm, k_norm [head_dim] (NULL arrays if !qk_norm)
+ *   wq [n_q_heads*head_dim, d_model]; wk, wv [n_kv_heads*head_dim, d_model]
+ *   wo [d_model, n_q_heads*head_dim]
+ *   dense: w_gate, w_up [d_ff, d_model]; w_down [d_model, d_ff]; w_router NULL
+ *   MoE:   w_router [n_experts, d_model]; w_gate, w_up [n_experts, d_ff_expert, d_model];
+ *          w_down [n_experts, d_model, d_ff_expert]
+ * All pointers must be 16-byte aligned.
+ */
+typedef struct {
+  uint32_t struct_size; /* = sizeof(rlx_weights) */
+  const void* embed;
+  const void* lm_head;
+  const void* final_norm;
+  const void* const* attn_norm;
+  const void* const* wq;
+  const void* const* wk;
+  const void* const* wv;
+  const void* const* wo;
+  const void* const* q_norm;
+  const void* const* k_norm;
+  const void* const* ffn_norm;
+  const void* const* w_gate;
+  const void* const* w_up;
+  const void* const* w_down;
+  const void* const* w_router;
+} rlx_weights;
+
+/* Create / destroy a model handle on the current HIP device. */
+RLX_API int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* w, rlx_model** out);
+RLX_API int rlx_model_destroy(rlx_model* m);
+
+/*
+ * Size in bytes of a KV pool of n_blocks pages (bf16).  Layout, private to the
+ * library: [layer][block][kv_head]{ K[16][head_dim], V^T[head_dim][16] }.
+ * The caller allocates it (256-byte aligned) and passes n_blocks to every call.
+ */
+RLX_API int rlx_kv_pool_bytes(const rlx_model* m, int64_t n_blocks, size_t* bytes_out);
+
+/* Scratch bytes needed by calls with at most max_seqs sequences, max_tokens packed
+ * tokens (a decode step has n_seqs tokens) and block-table rows of at most
+ * max_blocks_per_seq entries.  256-byte aligned, caller-owned; holds no state
+ * between calls. */
+RLX_API int rlx_workspace_bytes(const rlx_model* m, int32_t max_seqs, int32_t max_tokens, int32_t max_blocks_per_seq,
+                        size_t* bytes_out);
+
+/* Copy whole KV pages src[i] -> dst[i] in every layer (copy-on-write of a shared
+ * prompt's partial tail page).  src/dst: device int32 [n]. */
+RLX_API int rlx_kv_copy_blocks(const rlx_model* m, void* kv_pool, int64_t n_blocks, const int32_t* src,
+                       const int32_t* dst, int32_t n, void* stream);
+
+/*
+ * Block-table contract (both calls): block_table is int32 [n_seqs, max_blocks_per_seq];
+ * entry j of a row is the physical page holding positions 16j..16j+15, in
+ * [0, n_blocks).  Rows must cover every position the call reads or appends.  A
+ * page may be listed by several sequences only while it is full and read-only;
+ * a page receiving appends must belong to one sequence.
+ *
+ * Sampling contract: the token that will sit at absolute position p of a sequence
+ * is argmax_v(z_v/T + g_v), g_v = -log(-log(u_v)), u_v = (R_v + 0.5) 2^-32, R_v =
+ * word (v mod 4) of Philox-4x32-10 with key (seed lo, seed hi) and counter
+ * (v div 4, p, 0, 0); ties go to the smaller v.  T <= 0 selects argmax_v z_v and
+ * scores with T = 1.  The log-probability is log_softmax(z/T)[token].  A draw
+ * depends only on (seed, position, v), never on the batch slot.
+ *
+ * Finish rule: with p the position of the emitted token, the token is replaced by
+ * eos_token_id when p >= max_ctx_len - 1 (length cap); a sequence is finished once
+ * it emits eos_token_id.  Finished rows are inert: no KV append, token =
+ * pad_token_id, logprob = 0, routing rows untouched.
+ */
+
+/*
+ * Append a chunk of known tokens to each of n_seqs sequences (varlen, packed) and,
+ * where sample_last[i] != 0, emit the next token from the chunk's last position.
+ *   token_ids     int32 [total_tokens]; -1 = take the row of input_embeds instead
+ *   input_embeds  bf16 [total_tokens, d_model] or NULL (rows used only where id == -1)
+ *   cu_seqlens    int32 [n_seqs+1], cu_seqlens[0] = 0, cu_seqlens[n_seqs] = total_tokens
+ *   ctx_lens      int32 [n_seqs] tokens already cached before this chunk (not modified)
+ *   sample_last   uint8 [n_seqs]
+ *   seeds uint64 [n_seqs]; temperature float [n_seqs]; max_ctx_len int32 [n_seqs]
+ *   forced_tokens NULL or int32 [n_seqs] (teacher forcing; < 0 = not forced)
+ *   out_tokens int32 [n_seqs]; out_logprobs float [n_seqs]; finished_out uint8 [n_seqs]
+ *       (rows with sample_last == 0 get pad / 0 / 0)
+ *   out_sampled   NULL or int32 [n_seqs]: the Gumbel-max draw before forcing / capping
+ *   out_routing   NULL or int32 [total_tokens, n_layers, top_k] (MoE), descending gate probability
+ *   out_logits    NULL or float [n_seqs, vocab] (debug; rows with sample_last == 0 hold the logits
+ *                 of the chunk's last position as well)
+ * total_tokens is a HOST integer equal to cu_seqlens[n_seqs].
+ */
+RLX_API int rollout_prefill_chunk(const rlx_model* m, void* kv_pool, int64_t n_blocks, void* workspace,
+                          size_t workspace_bytes, int32_t n_seqs, int32_t total_tokens,
+                          const int32_t* token_ids, const void* input_embeds, const int32_t* cu_seqlens,
+                          const int32_t* ctx_lens, const int32_t* block_table, int32_t max_blocks_per_seq,
+                          const uint8_t* sample_last, const uint64_t* seeds, const float* temperature,
+                          const int32_t* max_ctx_len, const int32_t* forced_tokens, int32_t* out_tokens,
+                          float* out_logprobs, uint8_t* finished_out, int32_t* out_sampled,
+                          int32_t* out_routing, float* out_logits, void* stream);
+
+/*
+ * One decode step for n_seqs sequences: each live row consumes tokens_inout[i] at
+ * position ctx_lens_inout[i] (appending its K/V there) and emits the next token.
+ *   tokens_inout    int32 [n_seqs]  in: last emitted token; out: new token (pad if finished)
+ *   ctx_lens_inout  int32 [n_seqs]  in: cached length; out: +1 for rows live at entry
+ *   finished_inout  uint8 [n_seqs]
+ *   out_routing     NULL or int32 [n_seqs, n_layers, top_k]
+ *   other arguments as in rollout_prefill_chunk.
+ */
+RLX_API int rollout_decode_step(const rlx_model* m, void* kv_pool, int64_t n_blocks, void* workspace,
+                        size_t workspace_bytes, int32_t n_seqs, int32_t* tokens_inout,
+                        int32_t* ctx_lens_inout, const int32_t* block_table, int32_t max_blocks_per_seq,
+                        const uint64_t* seeds, const float* temperature, const int32_t* max_ctx_len,
+                        uint8_t* finished_inout, const int32_t* forced_tokens, float* out_logprobs,
+                        int32_t* out_sampled, int32_t* out_routing, float* out_logits, void* stream);
+
+/*
+ * Single operators, exported for per-kernel parity tests and profiling.
+ *   rlx_op_linear: y[t, n] = sum_k x[t, k] W[n, k]; x bf16 [n_tokens, k], W bf16 [n, k],
+ *   y float [n_tokens, n]; runs the same weight-streaming kernel the decode step uses.
+ */
+RLX_API int rlx_op_linear(const void* x, const void* w, float* y, int32_t n_tokens, int32_t n, int32_t k,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* Thread-local text of the last error on this thread ("" if none). */
+RLX_API const char* rlx_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RELAX_ROLLOUT_H */

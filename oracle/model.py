@@ -19,8 +19,21 @@ from . import layers as L
 from .philox import sample_gumbel_max
 
 
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even to the bf16 grid (8 significand bits), result kept in x's dtype.
+    The workloads fix the KV cache as bf16: keys (after the rotary embedding) and values are
+    rounded once, when they are stored, and attention consumes the stored values."""
+    f = np.ascontiguousarray(x, dtype=np.float32)
+    u = f.view(np.uint32)
+    u = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)
+    return u.view(np.float32).astype(x.dtype)
+
+
 class OracleModel:
     """Weights of one synthetic policy, upcast from bf16 bit patterns.
+
+    kv_bf16: keys/values are rounded to bf16 when stored (what the workloads specify);
+    False keeps them in the working dtype (used by pins that need exact algebra).
 
     Layers are materialised on demand; with cache_layers=False only one layer is
     resident at a time (needed for the 30B-shape model on a small host).
@@ -28,8 +41,9 @@ class OracleModel:
     """
 
     def __init__(self, shape: ModelShape, model_seed: int = 0, cache_layers: bool = True,
-                 dtype=np.float32, tensors: Optional[Dict] = None):
+                 dtype=np.float32, tensors: Optional[Dict] = None, kv_bf16: bool = True):
         self.shape = shape
+        self.kv_bf16 = kv_bf16
         self.model_seed = model_seed
         self.dtype = np.dtype(dtype)
         self.cache_layers = cache_layers
@@ -76,7 +90,7 @@ def _embed(model: OracleModel, tokens: np.ndarray, embeds: Optional[np.ndarray])
     return h
 
 
-def _qkv(shape: ModelShape, w: Dict[str, np.ndarray], h: np.ndarray, pos: np.ndarray):
+def _qkv(shape: ModelShape, w: Dict[str, np.ndarray], h: np.ndarray, pos: np.ndarray, kv_bf16: bool):
     x = L.rmsnorm(h, w["attn_norm"], shape.rms_eps)
     n = h.shape[0]
     q = (x @ w["wq"].T).reshape(n, shape.n_q_heads, shape.head_dim)
@@ -87,6 +101,8 @@ def _qkv(shape: ModelShape, w: Dict[str, np.ndarray], h: np.ndarray, pos: np.nda
         k = L.rmsnorm(k, w["k_norm"], shape.rms_eps)
     q = L.rope(q, pos, shape.rope_theta)
     k = L.rope(k, pos, shape.rope_theta)
+    if kv_bf16:
+        k, v = round_to_bf16(k), round_to_bf16(v)
     return q, k, v
 
 
@@ -132,7 +148,7 @@ def forward_full(model: OracleModel, tokens: Sequence[np.ndarray], embeds: Seque
         for i in range(nseq):
             h = hs[i]
             n = h.shape[0]
-            q, k, v = _qkv(s, w, h, np.arange(n))
+            q, k, v = _qkv(s, w, h, np.arange(n), model.kv_bf16)
             o = L.attention(q, k, v).reshape(n, s.q_dim)
             h = h + o @ w["wo"].T
             fr = None if forced_routing[i] is None else forced_routing[i][:, l, :]
@@ -238,7 +254,7 @@ class OracleRollout:
             for j, i in enumerate(seq_ids):
                 h = hs[j]
                 n, p0 = h.shape[0], self.ctx[i]
-                q, k, v = _qkv(s, w, h, np.arange(p0, p0 + n))
+                q, k, v = _qkv(s, w, h, np.arange(p0, p0 + n), m.kv_bf16)
                 blk, slot = self._slots(i, p0, n)
                 self.kpool[l, blk, slot] = k
                 self.vpool[l, blk, slot] = v

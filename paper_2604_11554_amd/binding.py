@@ -1,0 +1,172 @@
+"""ctypes binding of librelax_rollout.so: argument marshalling only.
+
+Function names and argument order are those of include/relax_rollout.h.  Device
+arrays are passed as torch CUDA tensors (or None for NULL); every step of the
+path runs in the library's kernels.  Loading fails loudly if the library has not
+been built -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librelax_rollout.so")
+
+RLX_OK, RLX_EINVAL, RLX_ENOMEM, RLX_EHIP, RLX_EUNSUPPORTED = 0, -1, -2, -3, -4
+
+EXPORTS = ["rlx_model_create", "rlx_model_destroy", "rlx_kv_pool_bytes", "rlx_workspace_bytes",
+           "rlx_kv_copy_blocks", "rollout_prefill_chunk", "rollout_decode_step", "rlx_op_linear",
+           "rlx_last_error"]
+
+
+class RlxError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("relax_rollout error %d: %s" % (code, msg))
+        self.code = code
+
+
+class ModelConfig(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32),
+                ("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ff", C.c_int32),
+                ("n_experts", C.c_int32), ("top_k", C.c_int32), ("d_ff_expert", C.c_int32),
+                ("vocab", C.c_int32), ("kv_block_size", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("qk_norm", C.c_int32),
+                ("eos_token_id", C.c_int32), ("pad_token_id", C.c_int32)]
+
+
+_PP = C.POINTER(C.c_void_p)
+
+
+class Weights(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("embed", C.c_void_p), ("lm_head", C.c_void_p),
+                ("final_norm", C.c_void_p)] + [(n, _PP) for n in (
+                    "attn_norm", "wq", "wk", "wv", "wo", "q_norm", "k_norm", "ffn_norm", "w_gate", "w_up",
+                    "w_down", "w_router")]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded shared library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("%s is missing: run `python -m paper_2604_11554_amd.build` "
+                              "(or __graft_entry__.build()) first" % LIB_PATH)
+        l = C.CDLL(LIB_PATH)
+        vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+        l.rlx_last_error.restype = C.c_char_p
+        l.rlx_last_error.argtypes = []
+        l.rlx_model_create.argtypes = [C.POINTER(ModelConfig), C.POINTER(Weights), C.POINTER(vp)]
+        l.rlx_model_destroy.argtypes = [vp]
+        l.rlx_kv_pool_bytes.argtypes = [vp, i64, C.POINTER(sz)]
+        l.rlx_workspace_bytes.argtypes = [vp, i32, i32, i32, C.POINTER(sz)]
+        l.rlx_kv_copy_blocks.argtypes = [vp, vp, i64, vp, vp, i32, vp]
+        l.rollout_prefill_chunk.argtypes = [vp, vp, i64, vp, sz, i32, i32] + [vp] * 5 + [i32] + [vp] * 12
+        l.rollout_decode_step.argtypes = [vp, vp, i64, vp, sz, i32, vp, vp, vp, i32] + [vp] * 10
+        l.rlx_op_linear.argtypes = [vp, vp, vp, i32, i32, i32, vp, sz, vp]
+        for n in EXPORTS:
+            if n != "rlx_last_error":
+                getattr(l, n).restype = C.c_int
+        _lib = l
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise RlxError(rc, lib().rlx_last_error().decode("utf-8", "replace"))
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous CUDA tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("expected dtype %s, got %s" % (dtype, t.dtype))
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def rlx_last_error() -> str:
+    return lib().rlx_last_error().decode("utf-8", "replace")
+
+
+def rlx_model_create(cfg: ModelConfig, weights: Weights) -> int:
+    h = C.c_void_p()
+    _check(lib().rlx_model_create(C.byref(cfg), C.byref(weights), C.byref(h)))
+    return h.value
+
+
+def rlx_model_destroy(model: int) -> None:
+    _check(lib().rlx_model_destroy(model))
+
+
+def rlx_kv_pool_bytes(model: int, n_blocks: int) -> int:
+    out = C.c_size_t()
+    _check(lib().rlx_kv_pool_bytes(model, n_blocks, C.byref(out)))
+    return out.value
+
+
+def rlx_workspace_bytes(model: int, max_seqs: int, max_tokens: int, max_blocks_per_seq: int) -> int:
+    out = C.c_size_t()
+    _check(lib().rlx_workspace_bytes(model, max_seqs, max_tokens, max_blocks_per_seq, C.byref(out)))
+    return out.value
+
+
+def rlx_kv_copy_blocks(model, kv_pool, n_blocks, src, dst, n, stream=None) -> None:
+    _check(lib().rlx_kv_copy_blocks(model, _ptr(kv_pool), n_blocks, _ptr(src, torch.int32), _ptr(dst, torch.int32),
+                                    n, _stream(stream)))
+
+
+def rollout_prefill_chunk(model, kv_pool, n_blocks, workspace, n_seqs, total_tokens, token_ids, input_embeds,
+                          cu_seqlens, ctx_lens, block_table, max_blocks_per_seq, sample_last, seeds, temperature,
+                          max_ctx_len, forced_tokens, out_tokens, out_logprobs, finished_out, out_sampled=None,
+                          out_routing=None, out_logits=None, stream=None) -> None:
+    _check(lib().rollout_prefill_chunk(
+        model, _ptr(kv_pool), n_blocks, _ptr(workspace), workspace.numel() * workspace.element_size(),
+        n_seqs, total_tokens, _ptr(token_ids, torch.int32), _ptr(input_embeds, torch.bfloat16),
+        _ptr(cu_seqlens, torch.int32), _ptr(ctx_lens, torch.int32), _ptr(block_table, torch.int32),
+        max_blocks_per_seq, _ptr(sample_last, torch.uint8), _ptr(seeds, torch.int64),
+        _ptr(temperature, torch.float32), _ptr(max_ctx_len, torch.int32), _ptr(forced_tokens, torch.int32),
+        _ptr(out_tokens, torch.int32), _ptr(out_logprobs, torch.float32), _ptr(finished_out, torch.uint8),
+        _ptr(out_sampled, torch.int32), _ptr(out_routing, torch.int32), _ptr(out_logits, torch.float32),
+        _stream(stream)))
+
+
+def rollout_decode_step(model, kv_pool, n_blocks, workspace, n_seqs, tokens_inout, ctx_lens_inout, block_table,
+                        max_blocks_per_seq, seeds, temperature, max_ctx_len, finished_inout, forced_tokens,
+                        out_logprobs, out_sampled=None, out_routing=None, out_logits=None, stream=None) -> None:
+    _check(lib().rollout_decode_step(
+        model, _ptr(kv_pool), n_blocks, _ptr(workspace), workspace.numel() * workspace.element_size(), n_seqs,
+        _ptr(tokens_inout, torch.int32), _ptr(ctx_lens_inout, torch.int32), _ptr(block_table, torch.int32),
+        max_blocks_per_seq, _ptr(seeds, torch.int64), _ptr(temperature, torch.float32),
+        _ptr(max_ctx_len, torch.int32), _ptr(finished_inout, torch.uint8), _ptr(forced_tokens, torch.int32),
+        _ptr(out_logprobs, torch.float32), _ptr(out_sampled, torch.int32), _ptr(out_routing, torch.int32),
+        _ptr(out_logits, torch.float32), _stream(stream)))
+
+
+def rlx_op_linear(x, w, y, workspace=None, stream=None) -> None:
+    n_tokens, k = x.shape
+    n = w.shape[0]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().rlx_op_linear(_ptr(x, torch.bfloat16), _ptr(w, torch.bfloat16), _ptr(y, torch.float32), n_tokens, n,
+                               k, _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def make_pointer_table(tensors: Sequence[Optional[torch.Tensor]]):
+    """Host array of device pointers for one per-layer member of rlx_weights."""
+    arr = (C.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = _ptr(t, torch.bfloat16)
+    return arr

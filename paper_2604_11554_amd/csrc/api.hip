@@ -1,0 +1,423 @@
+// C ABI of the rollout library: handle lifetime, argument validation, workspace
+// carving and the launch sequence of one prefill chunk / decode step.
+#include "../../include/relax_rollout.h"
+
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace rlx;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define RLX_HIP(expr)                                                                        \
+  do {                                                                                       \
+    hipError_t e_ = (expr);                                                                  \
+    if (e_ != hipSuccess) return fail(RLX_EHIP, "%s: %s", #expr, hipGetErrorString(e_));     \
+  } while (0)
+
+size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+struct rlx_model {
+  rlx_model_config cfg;
+  const bf16_t *embed, *lm_head, *final_norm;
+  std::vector<const bf16_t*> attn_norm, wq, wk, wv, wo, q_norm, k_norm, ffn_norm, w_gate, w_up, w_down, w_router;
+  double* inv_freq;   // device, [head_dim / 2]
+  int device;
+};
+
+namespace {
+
+struct Workspace {
+  TokenMeta meta;
+  float* h;          // [T, d]
+  bf16_t* xb;        // [T, d]
+  float* xf;         // [T, d] (MoE)
+  float* qkv;        // [planes][T, qkv_dim]
+  bf16_t* q;         // [T, q_dim]
+  bf16_t* ob;        // [T, q_dim]
+  float* attn_part;  // [S][Hq][n_splits][hd+2]
+  float* planes;     // split-K planes of the o / down projections
+  bf16_t* act;       // dense [T, F]; MoE [T*top_k, Fe]
+  float* moe_y;      // [T*top_k, d]
+  int32_t* topk_idx; float* topk_w;
+  int32_t *counts, *group_off, *sorted_token, *pair_pos;
+  bf16_t* x_lm;      // [S, d]
+  float* lm_part;    // [S][tiles][4]
+  size_t bytes;
+};
+
+int plane_rows(int T) { return T <= 256 ? gemm_max_splits() * T : T; }
+
+// carve the workspace; with base == nullptr only the size is computed
+Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blocks) {
+  Workspace w = {};
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    char* p = base ? base + off : nullptr;
+    off += align_up(bytes);
+    return p;
+  };
+  const int qdim = c.n_q_heads * c.head_dim, kvdim = c.n_kv_heads * c.head_dim;
+  const int qkv_dim = qdim + 2 * kvdim;
+  const int QT = T / 16 + S + 1;
+  w.meta.tok_seq = (int32_t*)take((size_t)T * 4);
+  w.meta.tok_pos = (int32_t*)take((size_t)T * 4);
+  w.meta.tok_live = (uint8_t*)take((size_t)T);
+  w.meta.sample_row = (int32_t*)take((size_t)S * 4);
+  w.meta.sample_pos = (int32_t*)take((size_t)S * 4);
+  w.meta.sample_on = (uint8_t*)take((size_t)S);
+  w.meta.qtile_seq = (int32_t*)take((size_t)QT * 4);
+  w.meta.qtile_q0 = (int32_t*)take((size_t)QT * 4);
+  w.meta.n_qtiles = (int32_t*)take(4);
+  w.h = (float*)take((size_t)T * c.d_model * 4);
+  w.xb = (bf16_t*)take((size_t)T * c.d_model * 2);
+  w.xf = c.n_experts ? (float*)take((size_t)T * c.d_model * 4) : nullptr;
+  w.qkv = (float*)take((size_t)plane_rows(T) * qkv_dim * 4);
+  w.q = (bf16_t*)take((size_t)T * qdim * 2);
+  w.ob = (bf16_t*)take((size_t)T * qdim * 2);
+  const int n_splits = (max_blocks * 16 + ATTN_SPLIT_TOKENS - 1) / ATTN_SPLIT_TOKENS;
+  w.attn_part = (float*)take((size_t)S * c.n_q_heads * n_splits * (c.head_dim + 2) * 4);
+  w.planes = (float*)take((size_t)plane_rows(T) * c.d_model * 4);
+  if (c.n_experts) {
+    const size_t P = (size_t)T * c.top_k;
+    w.act = (bf16_t*)take(P * c.d_ff_expert * 2);
+    w.moe_y = (float*)take(P * c.d_model * 4);
+    w.topk_idx = (int32_t*)take(P * 4);
+    w.topk_w = (float*)take(P * 4);
+    w.counts = (int32_t*)take((size_t)c.n_experts * 4);
+    w.group_off = (int32_t*)take((size_t)(c.n_experts + 1) * 4);
+    w.sorted_token = (int32_t*)take(P * 4);
+    w.pair_pos = (int32_t*)take(P * 4);
+  } else {
+    w.act = (bf16_t*)take((size_t)T * c.d_ff * 2);
+  }
+  w.x_lm = (bf16_t*)take((size_t)S * c.d_model * 2);
+  w.lm_part = (float*)take((size_t)S * lmhead_tiles(c.vocab) * 4 * 4);
+  w.bytes = off;
+  return w;
+}
+
+size_t block_elems(const rlx_model_config& c) { return (size_t)c.n_kv_heads * 2 * 16 * c.head_dim; }
+
+struct StepIO {
+  int n_seqs, T;
+  bool decode;
+  const int32_t* tokens; const bf16_t* input_embeds;
+  const int32_t* cu_seqlens; const int32_t* ctx_lens;
+  const int32_t* block_table; int max_blocks;
+  const uint64_t* seeds; const float* temperature; const int32_t* max_ctx_len; const int32_t* forced;
+  int32_t* out_tokens; float* out_logprobs; uint8_t* finished; int32_t* out_sampled;
+  int32_t* out_routing; float* out_logits;
+  int32_t* ctx_lens_rw;   // decode only
+};
+
+int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspace& w, const StepIO& io,
+               hipStream_t st) {
+  const rlx_model_config& c = m->cfg;
+  const int d = c.d_model, T = io.T;
+  const int qdim = c.n_q_heads * c.head_dim, kvdim = c.n_kv_heads * c.head_dim, qkv_dim = qdim + 2 * kvdim;
+  const bool small = T <= 256;
+
+  RLX_HIP(embed_tokens(m->embed, c.vocab, d, io.tokens, io.input_embeds, T, w.h, st));
+
+  // residual contribution produced by the previous sub-layer, folded into the next norm
+  const float* pend_planes = nullptr; int pend_n = 0; bool pend_moe = false;
+  auto norm = [&](const bf16_t* gain, const int32_t* rows, int n_rows, bf16_t* x, float* xf) -> hipError_t {
+    NormArgs a = {};
+    a.h = w.h; a.gain = gain; a.d = d; a.T = n_rows; a.T_total = T; a.eps = c.rms_eps; a.rows = rows;
+    a.add = pend_planes; a.n_planes = pend_n;
+    if (pend_moe) { a.moe_y = w.moe_y; a.pair_pos = w.pair_pos; a.topk_w = w.topk_w; a.top_k = c.top_k; }
+    a.x = x; a.xf = xf;
+    pend_planes = nullptr; pend_n = 0; pend_moe = false;
+    return rmsnorm(a, st);
+  };
+
+  for (int l = 0; l < c.n_layers; ++l) {
+    RLX_HIP(norm(m->attn_norm[l], nullptr, T, w.xb, nullptr));
+    LinearW wqkv = {};
+    wqkv.seg[0] = m->wq[l]; wqkv.rows[0] = qdim;
+    wqkv.seg[1] = m->wk[l]; wqkv.rows[1] = kvdim;
+    wqkv.seg[2] = m->wv[l]; wqkv.rows[2] = kvdim;
+    wqkv.N = qkv_dim; wqkv.K = d;
+    const int s_qkv = small ? gemm_plan_splits(qkv_dim, d, gemm_max_splits()) : 1;
+    RLX_HIP(gemm_store(wqkv, w.xb, d, nullptr, T, w.qkv, qkv_dim, s_qkv, st));
+
+    RopeArgs r = {};
+    r.qkv = w.qkv; r.n_planes = s_qkv;
+    r.q_gain = c.qk_norm ? m->q_norm[l] : nullptr; r.k_gain = c.qk_norm ? m->k_norm[l] : nullptr;
+    r.inv_freq = m->inv_freq; r.T = T; r.Hq = c.n_q_heads; r.Hkv = c.n_kv_heads; r.hd = c.head_dim;
+    r.eps = c.rms_eps; r.tok_seq = w.meta.tok_seq; r.tok_pos = w.meta.tok_pos; r.tok_live = w.meta.tok_live;
+    r.block_table = io.block_table; r.max_blocks = io.max_blocks;
+    r.pool_layer = pool + (size_t)l * n_blocks * block_elems(c); r.n_blocks = n_blocks; r.q_out = w.q;
+    RLX_HIP(qk_rope_append(r, st));
+
+    AttnArgs at = {};
+    at.q = w.q; at.pool_layer = r.pool_layer; at.n_blocks = n_blocks;
+    at.Hq = c.n_q_heads; at.Hkv = c.n_kv_heads; at.hd = c.head_dim;
+    at.block_table = io.block_table; at.max_blocks = io.max_blocks; at.ctx_lens = io.ctx_lens;
+    at.n_seqs = io.n_seqs; at.tok_live = w.meta.tok_live; at.part = w.attn_part;
+    at.n_splits = (io.max_blocks * 16 + ATTN_SPLIT_TOKENS - 1) / ATTN_SPLIT_TOKENS;
+    at.cu_seqlens = io.cu_seqlens; at.qtile_seq = w.meta.qtile_seq; at.qtile_q0 = w.meta.qtile_q0;
+    at.n_qtiles = w.meta.n_qtiles; at.max_qtiles = T / 16 + io.n_seqs + 1; at.o = w.ob;
+    RLX_HIP(io.decode ? attention_decode(at, st) : attention_prefill(at, st));
+
+    const int s_o = small ? gemm_plan_splits(d, qdim, gemm_max_splits()) : 1;
+    RLX_HIP(gemm_store(linear1(m->wo[l], d, qdim), w.ob, qdim, nullptr, T, w.planes, d, s_o, st));
+    pend_planes = w.planes; pend_n = s_o;
+
+    RLX_HIP(norm(m->ffn_norm[l], nullptr, T, w.xb, w.xf));
+    if (c.n_experts == 0) {
+      RLX_HIP(gemm_swiglu(m->w_gate[l], m->w_up[l], c.d_ff, d, w.xb, d, T, w.act, c.d_ff, st));
+      const int s_d = small ? gemm_plan_splits(d, c.d_ff, gemm_max_splits()) : 1;
+      RLX_HIP(gemm_store(linear1(m->w_down[l], d, c.d_ff), w.act, c.d_ff, nullptr, T, w.planes, d, s_d, st));
+      pend_planes = w.planes; pend_n = s_d;
+    } else {
+      RouterArgs ra = {};
+      ra.xf = w.xf; ra.w_router = m->w_router[l]; ra.T = T; ra.d = d; ra.E = c.n_experts; ra.top_k = c.top_k;
+      ra.topk_idx = w.topk_idx; ra.topk_w = w.topk_w; ra.routing_out = io.out_routing; ra.layer = l;
+      ra.n_layers = c.n_layers; ra.tok_live = w.meta.tok_live;
+      RLX_HIP(moe_router(ra, st));
+      RLX_HIP(moe_group(w.topk_idx, T, c.top_k, c.n_experts, w.counts, w.group_off, w.sorted_token, w.pair_pos, st));
+      RLX_HIP(gemm_grouped_swiglu(m->w_gate[l], m->w_up[l], c.n_experts, c.d_ff_expert, d, w.xb, d, w.sorted_token,
+                                  w.group_off, T, w.act, st));
+      RLX_HIP(gemm_grouped_store(m->w_down[l], c.n_experts, d, c.d_ff_expert, w.act, c.d_ff_expert, w.group_off, T,
+                                 w.moe_y, st));
+      pend_moe = true;
+    }
+  }
+
+  // final norm of the rows that emit a token, LM head with fused log-sum-exp / Gumbel-max partials
+  const int S = io.n_seqs;
+  RLX_HIP(norm(m->final_norm, w.meta.sample_row, S, w.x_lm, nullptr));
+  RLX_HIP(gemm_lmhead(m->lm_head, c.vocab, d, w.x_lm, d, S, io.out_logits, w.lm_part, io.seeds, io.temperature,
+                      w.meta.sample_pos, st));
+  FinalizeArgs f = {};
+  f.n_rows = S; f.n_tiles = lmhead_tiles(c.vocab); f.vocab = c.vocab; f.d = d;
+  f.part = w.lm_part; f.x = w.x_lm; f.w_lm = m->lm_head;
+  f.temperature = io.temperature; f.max_ctx_len = io.max_ctx_len; f.forced = io.forced;
+  f.sample_pos = w.meta.sample_pos; f.sample_on = w.meta.sample_on;
+  f.eos = c.eos_token_id; f.pad = c.pad_token_id;
+  f.out_tokens = io.out_tokens; f.out_logprobs = io.out_logprobs; f.out_sampled = io.out_sampled;
+  f.finished = io.finished; f.ctx_lens = io.ctx_lens_rw; f.is_decode = io.decode ? 1 : 0;
+  RLX_HIP(sample_finalize(f, st));
+  return RLX_OK;
+}
+
+int check_common(const rlx_model* m, const void* kv_pool, int64_t n_blocks, const void* workspace, int32_t n_seqs,
+                 int32_t max_blocks_per_seq) {
+  if (!m) return fail(RLX_EINVAL, "model is NULL");
+  if (!kv_pool || n_blocks <= 0) return fail(RLX_EINVAL, "kv_pool is NULL or n_blocks <= 0");
+  if (!workspace) return fail(RLX_EINVAL, "workspace is NULL");
+  if (n_seqs <= 0 || n_seqs > (1 << 16)) return fail(RLX_EINVAL, "n_seqs %d out of range", n_seqs);
+  if (max_blocks_per_seq <= 0 || max_blocks_per_seq > (1 << 20))
+    return fail(RLX_EINVAL, "max_blocks_per_seq %d out of range", max_blocks_per_seq);
+  if (!aligned16(kv_pool) || !aligned16(workspace)) return fail(RLX_EINVAL, "kv_pool/workspace not 16-byte aligned");
+  return RLX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* rlx_last_error(void) { return g_err; }
+
+int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* wt, rlx_model** out) {
+  if (!cfg || !wt || !out) return fail(RLX_EINVAL, "NULL argument");
+  *out = nullptr;
+  if (cfg->struct_size != sizeof(rlx_model_config)) return fail(RLX_EINVAL, "rlx_model_config.struct_size mismatch");
+  if (wt->struct_size != sizeof(rlx_weights)) return fail(RLX_EINVAL, "rlx_weights.struct_size mismatch");
+  const rlx_model_config& c = *cfg;
+  if (c.n_layers <= 0 || c.d_model <= 0 || c.n_q_heads <= 0 || c.n_kv_heads <= 0 || c.vocab <= 0)
+    return fail(RLX_EINVAL, "non-positive dimension");
+  if (c.head_dim != 64 && c.head_dim != 128) return fail(RLX_EUNSUPPORTED, "head_dim %d (64 or 128)", c.head_dim);
+  if (c.kv_block_size != 16) return fail(RLX_EUNSUPPORTED, "kv_block_size %d (must be 16)", c.kv_block_size);
+  if (c.n_q_heads % c.n_kv_heads) return fail(RLX_EINVAL, "n_q_heads not a multiple of n_kv_heads");
+  if (c.n_q_heads / c.n_kv_heads > 16) return fail(RLX_EUNSUPPORTED, "GQA group > 16");
+  if (c.d_model % 8) return fail(RLX_EUNSUPPORTED, "d_model must be a multiple of 8");
+  const bool moe = c.n_experts > 0;
+  if (moe) {
+    if (c.n_experts > 256 || c.top_k <= 0 || c.top_k > 8 || c.top_k > c.n_experts || c.d_ff_expert <= 0)
+      return fail(RLX_EUNSUPPORTED, "MoE limits: n_experts <= 256, 1 <= top_k <= min(8, n_experts)");
+    if (c.d_ff_expert % 8 || c.d_ff) return fail(RLX_EINVAL, "MoE: d_ff_expert %% 8 == 0 and d_ff == 0 required");
+  } else {
+    if (c.d_ff <= 0 || c.d_ff % 8) return fail(RLX_EINVAL, "dense: d_ff must be a positive multiple of 8");
+    if (c.top_k || c.d_ff_expert) return fail(RLX_EINVAL, "dense: top_k and d_ff_expert must be 0");
+  }
+  if (c.eos_token_id < 0 || c.eos_token_id >= c.vocab || c.pad_token_id < 0 || c.pad_token_id >= c.vocab)
+    return fail(RLX_EINVAL, "eos/pad token id outside the vocabulary");
+  if (!(c.rms_eps >= 0.f) || !(c.rope_theta > 0.f)) return fail(RLX_EINVAL, "rms_eps / rope_theta");
+  if (!wt->embed || !wt->lm_head || !wt->final_norm) return fail(RLX_EINVAL, "NULL global weight");
+  if (!aligned16(wt->embed) || !aligned16(wt->lm_head) || !aligned16(wt->final_norm))
+    return fail(RLX_EINVAL, "weights must be 16-byte aligned");
+  const void* const* req[] = {wt->attn_norm, wt->wq, wt->wk, wt->wv, wt->wo, wt->ffn_norm, wt->w_gate, wt->w_up,
+                              wt->w_down};
+  for (auto p : req)
+    if (!p) return fail(RLX_EINVAL, "NULL per-layer weight table");
+  if (c.qk_norm && (!wt->q_norm || !wt->k_norm)) return fail(RLX_EINVAL, "qk_norm set but q_norm/k_norm missing");
+  if (moe && !wt->w_router) return fail(RLX_EINVAL, "MoE model without w_router");
+
+  rlx_model* m = new (std::nothrow) rlx_model();
+  if (!m) return fail(RLX_ENOMEM, "host allocation failed");
+  m->cfg = c;
+  m->embed = (const bf16_t*)wt->embed; m->lm_head = (const bf16_t*)wt->lm_head;
+  m->final_norm = (const bf16_t*)wt->final_norm;
+  m->inv_freq = nullptr;
+  auto copy = [&](std::vector<const bf16_t*>& dst, const void* const* src) -> bool {
+    dst.resize(c.n_layers, nullptr);
+    if (!src) return true;
+    for (int l = 0; l < c.n_layers; ++l) {
+      if (!src[l] || !aligned16(src[l])) return false;
+      dst[l] = (const bf16_t*)src[l];
+    }
+    return true;
+  };
+  bool ok = copy(m->attn_norm, wt->attn_norm) && copy(m->wq, wt->wq) && copy(m->wk, wt->wk) && copy(m->wv, wt->wv) &&
+            copy(m->wo, wt->wo) && copy(m->ffn_norm, wt->ffn_norm) && copy(m->w_gate, wt->w_gate) &&
+            copy(m->w_up, wt->w_up) && copy(m->w_down, wt->w_down) &&
+            copy(m->q_norm, c.qk_norm ? wt->q_norm : nullptr) && copy(m->k_norm, c.qk_norm ? wt->k_norm : nullptr) &&
+            copy(m->w_router, moe ? wt->w_router : nullptr);
+  if (!ok) {
+    delete m;
+    return fail(RLX_EINVAL, "a per-layer weight pointer is NULL or not 16-byte aligned");
+  }
+  // rotary frequencies theta^(-2i/hd) in double
+  std::vector<double> inv(c.head_dim / 2);
+  for (int i = 0; i < c.head_dim / 2; ++i) inv[i] = pow((double)c.rope_theta, -2.0 * i / c.head_dim);
+  hipError_t e = hipGetDevice(&m->device);
+  if (e == hipSuccess) e = hipMalloc((void**)&m->inv_freq, inv.size() * sizeof(double));
+  if (e == hipSuccess) e = hipMemcpy(m->inv_freq, inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    if (m->inv_freq) (void)hipFree(m->inv_freq);
+    delete m;
+    return fail(RLX_EHIP, "rlx_model_create: %s", hipGetErrorString(e));
+  }
+  *out = m;
+  return RLX_OK;
+}
+
+int rlx_model_destroy(rlx_model* m) {
+  if (!m) return RLX_OK;
+  hipError_t e = m->inv_freq ? hipFree(m->inv_freq) : hipSuccess;
+  delete m;
+  if (e != hipSuccess) return fail(RLX_EHIP, "hipFree: %s", hipGetErrorString(e));
+  return RLX_OK;
+}
+
+int rlx_kv_pool_bytes(const rlx_model* m, int64_t n_blocks, size_t* bytes_out) {
+  if (!m || !bytes_out || n_blocks <= 0) return fail(RLX_EINVAL, "bad argument");
+  *bytes_out = (size_t)m->cfg.n_layers * (size_t)n_blocks * block_elems(m->cfg) * 2;
+  return RLX_OK;
+}
+
+int rlx_workspace_bytes(const rlx_model* m, int32_t max_seqs, int32_t max_tokens, int32_t max_blocks_per_seq,
+                        size_t* bytes_out) {
+  if (!m || !bytes_out || max_seqs <= 0 || max_tokens < max_seqs || max_blocks_per_seq <= 0)
+    return fail(RLX_EINVAL, "bad argument (need 0 < max_seqs <= max_tokens, max_blocks_per_seq > 0)");
+  *bytes_out = carve(m->cfg, nullptr, max_seqs, max_tokens, max_blocks_per_seq).bytes;
+  return RLX_OK;
+}
+
+int rlx_kv_copy_blocks(const rlx_model* m, void* kv_pool, int64_t n_blocks, const int32_t* src, const int32_t* dst,
+                       int32_t n, void* stream) {
+  if (!m || !kv_pool || n_blocks <= 0 || n < 0 || (n > 0 && (!src || !dst))) return fail(RLX_EINVAL, "bad argument");
+  RLX_HIP(kv_copy_blocks((bf16_t*)kv_pool, n_blocks, m->cfg.n_layers, block_elems(m->cfg), src, dst, n,
+                         (hipStream_t)stream));
+  return RLX_OK;
+}
+
+int rollout_prefill_chunk(const rlx_model* m, void* kv_pool, int64_t n_blocks, void* workspace, size_t workspace_bytes,
+                          int32_t n_seqs, int32_t total_tokens, const int32_t* token_ids, const void* input_embeds,
+                          const int32_t* cu_seqlens, const int32_t* ctx_lens, const int32_t* block_table,
+                          int32_t max_blocks_per_seq, const uint8_t* sample_last, const uint64_t* seeds,
+                          const float* temperature, const int32_t* max_ctx_len, const int32_t* forced_tokens,
+                          int32_t* out_tokens, float* out_logprobs, uint8_t* finished_out, int32_t* out_sampled,
+                          int32_t* out_routing, float* out_logits, void* stream) {
+  int rc = check_common(m, kv_pool, n_blocks, workspace, n_seqs, max_blocks_per_seq);
+  if (rc) return rc;
+  if (total_tokens <= 0 || total_tokens > (1 << 24)) return fail(RLX_EINVAL, "total_tokens %d out of range", total_tokens);
+  if (!token_ids || !cu_seqlens || !ctx_lens || !block_table || !sample_last || !seeds || !temperature ||
+      !max_ctx_len || !out_tokens || !out_logprobs || !finished_out)
+    return fail(RLX_EINVAL, "NULL array argument");
+  if (input_embeds && !aligned16(input_embeds)) return fail(RLX_EINVAL, "input_embeds not 16-byte aligned");
+  const int T = total_tokens > n_seqs ? total_tokens : n_seqs;
+  Workspace w = carve(m->cfg, (char*)workspace, n_seqs, T, max_blocks_per_seq);
+  if (w.bytes > workspace_bytes)
+    return fail(RLX_ENOMEM, "workspace too small: need %zu bytes, have %zu", w.bytes, workspace_bytes);
+  hipStream_t st = (hipStream_t)stream;
+  RLX_HIP(meta_prefill(w.meta, n_seqs, total_tokens, cu_seqlens, ctx_lens, sample_last, st));
+  StepIO io = {};
+  io.n_seqs = n_seqs; io.T = total_tokens; io.decode = false;
+  io.tokens = token_ids; io.input_embeds = (const bf16_t*)input_embeds; io.cu_seqlens = cu_seqlens;
+  io.ctx_lens = ctx_lens; io.block_table = block_table; io.max_blocks = max_blocks_per_seq;
+  io.seeds = seeds; io.temperature = temperature; io.max_ctx_len = max_ctx_len; io.forced = forced_tokens;
+  io.out_tokens = out_tokens; io.out_logprobs = out_logprobs; io.finished = finished_out;
+  io.out_sampled = out_sampled; io.out_routing = m->cfg.n_experts ? out_routing : nullptr; io.out_logits = out_logits;
+  return run_layers(m, (bf16_t*)kv_pool, n_blocks, w, io, st);
+}
+
+int rollout_decode_step(const rlx_model* m, void* kv_pool, int64_t n_blocks, void* workspace, size_t workspace_bytes,
+                        int32_t n_seqs, int32_t* tokens_inout, int32_t* ctx_lens_inout, const int32_t* block_table,
+                        int32_t max_blocks_per_seq, const uint64_t* seeds, const float* temperature,
+                        const int32_t* max_ctx_len, uint8_t* finished_inout, const int32_t* forced_tokens,
+                        float* out_logprobs, int32_t* out_sampled, int32_t* out_routing, float* out_logits,
+                        void* stream) {
+  int rc = check_common(m, kv_pool, n_blocks, workspace, n_seqs, max_blocks_per_seq);
+  if (rc) return rc;
+  if (!tokens_inout || !ctx_lens_inout || !block_table || !seeds || !temperature || !max_ctx_len ||
+      !finished_inout || !out_logprobs)
+    return fail(RLX_EINVAL, "NULL array argument");
+  Workspace w = carve(m->cfg, (char*)workspace, n_seqs, n_seqs, max_blocks_per_seq);
+  if (w.bytes > workspace_bytes)
+    return fail(RLX_ENOMEM, "workspace too small: need %zu bytes, have %zu", w.bytes, workspace_bytes);
+  hipStream_t st = (hipStream_t)stream;
+  RLX_HIP(meta_decode(w.meta, n_seqs, ctx_lens_inout, finished_inout, st));
+  StepIO io = {};
+  io.n_seqs = n_seqs; io.T = n_seqs; io.decode = true;
+  io.tokens = tokens_inout; io.ctx_lens = ctx_lens_inout; io.ctx_lens_rw = ctx_lens_inout;
+  io.block_table = block_table; io.max_blocks = max_blocks_per_seq;
+  io.seeds = seeds; io.temperature = temperature; io.max_ctx_len = max_ctx_len; io.forced = forced_tokens;
+  io.out_tokens = tokens_inout; io.out_logprobs = out_logprobs; io.finished = finished_inout;
+  io.out_sampled = out_sampled; io.out_routing = m->cfg.n_experts ? out_routing : nullptr; io.out_logits = out_logits;
+  return run_layers(m, (bf16_t*)kv_pool, n_blocks, w, io, st);
+}
+
+int rlx_op_linear(const void* x, const void* w, float* y, int32_t n_tokens, int32_t n, int32_t k, void* workspace,
+                  size_t workspace_bytes, void* stream) {
+  if (!x || !w || !y || n_tokens <= 0 || n <= 0 || k <= 0 || (k % 8) || (n % 4))
+    return fail(RLX_EINVAL, "rlx_op_linear: bad argument (k %% 8 == 0, n %% 4 == 0 required)");
+  if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return fail(RLX_EINVAL, "rlx_op_linear: 16-byte alignment");
+  const int splits = n_tokens <= 256 ? gemm_plan_splits(n, k, gemm_max_splits()) : 1;
+  hipStream_t st = (hipStream_t)stream;
+  if (splits == 1) {
+    RLX_HIP(gemm_store(linear1(w, n, k), (const bf16_t*)x, k, nullptr, n_tokens, y, n, 1, st));
+    return RLX_OK;
+  }
+  const size_t need = (size_t)splits * n_tokens * n * 4;
+  if (!workspace || workspace_bytes < need)
+    return fail(RLX_ENOMEM, "rlx_op_linear: workspace needs %zu bytes", need);
+  RLX_HIP(gemm_store(linear1(w, n, k), (const bf16_t*)x, k, nullptr, n_tokens, (float*)workspace, n, splits, st));
+  RLX_HIP(sum_planes((const float*)workspace, splits, (size_t)n_tokens * n, y, st));
+  return RLX_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,154 @@
+// Host-side launchers of the rollout kernels.  Every launcher only enqueues work on
+// the given stream and returns hipGetLastError(); shapes are validated by the caller.
+#pragma once
+#include "common.h"
+
+namespace rlx {
+
+// Up to three row segments stacked into one logical [N, K] weight (q|k|v).
+struct LinearW {
+  const bf16_t* seg[3];
+  int rows[3];
+  int N, K;
+};
+inline LinearW linear1(const void* w, int N, int K) {
+  LinearW l = {};
+  l.seg[0] = (const bf16_t*)w; l.rows[0] = N; l.N = N; l.K = K;
+  return l;
+}
+
+// ---- gemm.hip ----
+int gemm_max_splits();
+int gemm_plan_splits(int N, int K, int max_splits);
+// y[split][t][n] (fp32, leading dimension ldy); x_rows optionally gathers the rows of x
+hipError_t gemm_store(const LinearW& w, const bf16_t* x, int ldx, const int32_t* x_rows, int T, float* y, int ldy,
+                      int splits, hipStream_t st);
+// act[t][f] = bf16( silu(x Wg^T) * (x Wu^T) )
+hipError_t gemm_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int F, int K, const bf16_t* x, int ldx, int T,
+                       bf16_t* act, int ldact, hipStream_t st);
+int lmhead_tiles(int vocab);
+// LM head with fused per-tile log-sum-exp and Gumbel-max partials: part[t][tile][4]
+hipError_t gemm_lmhead(const bf16_t* w_lm, int V, int K, const bf16_t* x, int ldx, int T, float* logits, float* part,
+                       const uint64_t* seeds, const float* temperature, const int32_t* sample_pos, hipStream_t st);
+// expert-grouped forms: rows [group_off[e], group_off[e+1]) belong to expert e = blockIdx.y
+hipError_t gemm_grouped_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int E, int F, int K, const bf16_t* x, int ldx,
+                               const int32_t* x_rows, const int32_t* group_off, int max_rows, bf16_t* act,
+                               hipStream_t st);
+hipError_t gemm_grouped_store(const bf16_t* w, int E, int N, int K, const bf16_t* x, int ldx,
+                              const int32_t* group_off, int max_rows, float* y, hipStream_t st);
+
+// ---- elementwise.hip ----
+struct TokenMeta {        // per packed token, built on the device at the start of a call
+  int32_t* tok_seq;       // sequence slot of token t
+  int32_t* tok_pos;       // absolute position of token t
+  uint8_t* tok_live;      // 0: row is inert (finished); no KV append
+  int32_t* sample_row;    // [n_seqs] packed index of the token whose hidden state is sampled from
+  int32_t* sample_pos;    // [n_seqs] absolute position of the token to be drawn
+  uint8_t* sample_on;     // [n_seqs] 1 if the row emits a token in this call
+  int32_t* qtile_seq;     // prefill attention tiles: sequence, first query index
+  int32_t* qtile_q0;
+  int32_t* n_qtiles;      // [1]
+};
+hipError_t meta_decode(const TokenMeta& m, int n_seqs, const int32_t* ctx_lens, const uint8_t* finished,
+                       hipStream_t st);
+hipError_t meta_prefill(const TokenMeta& m, int n_seqs, int total_tokens, const int32_t* cu_seqlens,
+                        const int32_t* ctx_lens, const uint8_t* sample_last, hipStream_t st);
+hipError_t embed_tokens(const bf16_t* embed, int vocab, int d, const int32_t* tokens, const bf16_t* input_embeds,
+                        int T, float* h, hipStream_t st);
+
+struct NormArgs {
+  float* h;                  // [T, d] residual stream, updated in place when something is added
+  const bf16_t* gain;        // [d]
+  int d, T;                  // T = number of output rows
+  int T_total;               // rows of h (stride of the split-K planes)
+  float eps;
+  const int32_t* rows;       // optional: output row r normalises (and updates) h[rows[r]] only
+  // optional additive term: (a) split-K planes  add[s][t][d], s < n_planes
+  const float* add;
+  int n_planes;
+  // (b) MoE combine: sum_k w[t,k] * y[pair_pos[t*K+k]][d]
+  const float* moe_y;
+  const int32_t* pair_pos;
+  const float* topk_w;
+  int top_k;
+  bf16_t* x;                 // [T, d] normalised output (bf16)
+  float* xf;                 // optional fp32 copy of the normalised output
+};
+hipError_t rmsnorm(const NormArgs& a, hipStream_t st);
+
+struct RopeArgs {
+  const float* qkv;          // [n_planes][T, (Hq+2Hkv)*hd] fp32 split-K planes, summed in plane order
+  int n_planes;
+  const bf16_t* q_gain;      // [hd] or null
+  const bf16_t* k_gain;
+  const double* inv_freq;    // [hd/2]
+  int T, Hq, Hkv, hd;
+  float eps;
+  const int32_t* tok_seq; const int32_t* tok_pos; const uint8_t* tok_live;
+  const int32_t* block_table; int max_blocks;
+  bf16_t* pool_layer;        // this layer's pages
+  int64_t n_blocks;
+  bf16_t* q_out;             // [T, Hq, hd]
+};
+hipError_t qk_rope_append(const RopeArgs& a, hipStream_t st);
+// y[i] = sum_s planes[s][i], s ascending
+hipError_t sum_planes(const float* planes, int n_planes, size_t n, float* y, hipStream_t st);
+hipError_t kv_copy_blocks(bf16_t* pool, int64_t n_blocks, int n_layers, size_t block_elems, const int32_t* src,
+                          const int32_t* dst, int n, hipStream_t st);
+
+// ---- attention.hip ----
+constexpr int ATTN_SPLIT_TOKENS = 256;   // keys per decode split
+struct AttnArgs {
+  const bf16_t* q;           // [T, Hq, hd]
+  const bf16_t* pool_layer;
+  int64_t n_blocks;
+  int Hq, Hkv, hd;
+  const int32_t* block_table; int max_blocks;
+  const int32_t* ctx_lens;   // cached length before this call, per sequence
+  // decode
+  int n_seqs;
+  const uint8_t* tok_live;
+  float* part;               // [n_seqs][Hq][n_splits][hd+2]
+  int n_splits;
+  // prefill
+  const int32_t* cu_seqlens;
+  const int32_t* qtile_seq; const int32_t* qtile_q0; const int32_t* n_qtiles;
+  int max_qtiles;
+  bf16_t* o;                 // [T, Hq*hd]
+};
+hipError_t attention_decode(const AttnArgs& a, hipStream_t st);   // partials + merge -> o
+hipError_t attention_prefill(const AttnArgs& a, hipStream_t st);
+
+// ---- moe.hip ----
+struct RouterArgs {
+  const float* xf;           // [T, d] fp32 normalised hidden
+  const bf16_t* w_router;    // [E, d]
+  int T, d, E, top_k;
+  int32_t* topk_idx;         // [T, top_k]
+  float* topk_w;             // [T, top_k]
+  int32_t* routing_out;      // optional [T, n_layers, top_k] (this layer's slice is written)
+  int layer, n_layers;
+  const uint8_t* tok_live;   // rows that are inert leave routing_out untouched
+};
+hipError_t moe_router(const RouterArgs& a, hipStream_t st);
+// stable grouping of the T*top_k (token, slot) pairs by expert
+hipError_t moe_group(const int32_t* topk_idx, int T, int top_k, int E, int32_t* counts, int32_t* group_off,
+                     int32_t* sorted_token, int32_t* pair_pos, hipStream_t st);
+
+// ---- sampling.hip ----
+struct FinalizeArgs {
+  int n_rows, n_tiles, vocab, d;
+  const float* part;          // [n_rows][n_tiles][4]
+  const bf16_t* x;            // [n_rows, d] final-normalised hidden (bf16)
+  const bf16_t* w_lm;         // [vocab, d]
+  const float* temperature; const int32_t* max_ctx_len; const int32_t* forced;
+  const int32_t* sample_pos; const uint8_t* sample_on;
+  int eos, pad;
+  int32_t* out_tokens; float* out_logprobs; int32_t* out_sampled;
+  uint8_t* finished;          // decode: in/out; prefill: out
+  int32_t* ctx_lens;          // decode: incremented for rows live at entry; null for prefill
+  int is_decode;
+};
+hipError_t sample_finalize(const FinalizeArgs& a, hipStream_t st);
+
+}  // namespace rlx

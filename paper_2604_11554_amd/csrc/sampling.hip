@@ -1,0 +1,94 @@
+// Last stage of a step: merge the LM-head tiles' (max, sumexp, best perturbed score,
+// argbest) partials in tile order, apply teacher forcing and the length cap, score the
+// emitted token (log-softmax of the temperature-scaled logits) and update the
+// per-sequence state (token, cached length, finished flag).
+#include "kernels.h"
+
+namespace rlx {
+namespace {
+
+struct Part { float m, s, best; int besti; };
+
+__device__ __forceinline__ Part part_merge(Part a, Part b) {   // a precedes b in vocabulary order
+  Part r;
+  float mn = fmaxf(a.m, b.m);
+  float ea = (a.m == -INFINITY) ? 0.f : __expf(a.m - mn);
+  float eb = (b.m == -INFINITY) ? 0.f : __expf(b.m - mn);
+  r.m = mn; r.s = a.s * ea + b.s * eb;
+  if (b.best > a.best) { r.best = b.best; r.besti = b.besti; } else { r.best = a.best; r.besti = a.besti; }
+  return r;
+}
+
+__global__ __launch_bounds__(256) void sample_finalize_kernel(FinalizeArgs a) {
+  __shared__ Part sh[256];
+  __shared__ float dsh[4];
+  const int r = blockIdx.x;
+  const bool on = a.sample_on[r] != 0;
+  if (!on) {                                  // inert row
+    if (threadIdx.x == 0) {
+      a.out_tokens[r] = a.pad;
+      a.out_logprobs[r] = 0.f;
+      if (a.out_sampled) a.out_sampled[r] = -1;
+      if (!a.is_decode) a.finished[r] = 0;
+    }
+    return;
+  }
+  // contiguous tile ranges per thread keep vocabulary order; then a fixed binary tree
+  const int per = (a.n_tiles + 255) / 256;
+  Part p = {-INFINITY, 0.f, -INFINITY, 0x7FFFFFFF};
+  const float* base = a.part + (size_t)r * a.n_tiles * 4;
+  for (int i = 0; i < per; ++i) {
+    int tile = threadIdx.x * per + i;
+    if (tile < a.n_tiles) {
+      Part q = {base[tile * 4 + 0], base[tile * 4 + 1], base[tile * 4 + 2], __float_as_int(base[tile * 4 + 3])};
+      p = part_merge(p, q);
+    }
+  }
+  sh[threadIdx.x] = p;
+  __syncthreads();
+  for (int stride = 1; stride < 256; stride <<= 1) {
+    if ((threadIdx.x % (2 * stride)) == 0) sh[threadIdx.x] = part_merge(sh[threadIdx.x], sh[threadIdx.x + stride]);
+    __syncthreads();
+  }
+  p = sh[0];
+  const float lse = p.m + logf(p.s);
+  const int sampled = p.besti;
+  int tok = sampled;
+  if (a.forced && a.forced[r] >= 0 && a.forced[r] < a.vocab) tok = a.forced[r];
+  const int pos = a.sample_pos[r];
+  if (pos >= a.max_ctx_len[r] - 1) tok = a.eos;
+  if (tok < 0 || tok >= a.vocab) tok = a.eos;   // cannot happen with a non-empty vocabulary; keeps the read in bounds
+
+  // logit of the emitted token: the same bf16 operands as the LM-head tiles, fp32 accumulate
+  const bf16_t* w = a.w_lm + (size_t)tok * a.d;
+  const bf16_t* x = a.x + (size_t)r * a.d;
+  float acc = 0.f;
+  for (int k = threadIdx.x; k < a.d; k += 256) acc += bf16_to_f32(x[k]) * bf16_to_f32(w[k]);
+  acc = wave_sum(acc);
+  if ((threadIdx.x & 63) == 0) dsh[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float z = dsh[0] + dsh[1] + dsh[2] + dsh[3];
+    float temp = a.temperature[r];
+    float invt = temp > 0.f ? 1.f / temp : 1.f;
+    a.out_tokens[r] = tok;
+    a.out_logprobs[r] = z * invt - lse;
+    if (a.out_sampled) a.out_sampled[r] = sampled;
+    uint8_t fin = (tok == a.eos) ? 1 : 0;
+    if (a.is_decode) {
+      a.finished[r] = fin;          // the row was live at entry
+      a.ctx_lens[r] += 1;
+    } else {
+      a.finished[r] = fin;
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t sample_finalize(const FinalizeArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(sample_finalize_kernel, dim3(a.n_rows), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace rlx

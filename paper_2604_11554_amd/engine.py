@@ -1,0 +1,273 @@
+"""Host-side rollout engine over the C ABI: device-resident weights, paged KV pool
+with a block allocator, per-sequence state rows, chunked prefill, the decode loop,
+prompt-prefix sharing and batch compaction.
+
+Everything numerical happens inside librelax_rollout.so; this module only owns
+memory (torch tensors) and integer bookkeeping.  The rollout stage it implements
+is the one described in paper Sec. 3.1/3.3 (generation producing responses and
+log-probabilities as per-sample fields), Sec. 4.3 (multi-turn sessions whose state
+persists across turns) and Sec. 5.5 (expert indices recorded per MoE layer per
+token for routing replay).
+"""
+from __future__ import annotations
+
+import ctypes as C
+from dataclasses import dataclass
+from typing import Callable, Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+PER_LAYER = ("attn_norm", "wq", "wk", "wv", "wo", "q_norm", "k_norm", "ffn_norm", "w_gate", "w_up", "w_down",
+             "w_router")
+
+
+def _to_bf16_cuda(a, device) -> torch.Tensor:
+    """uint16 bit patterns (numpy) or a bf16 tensor -> contiguous bf16 CUDA tensor."""
+    if isinstance(a, torch.Tensor):
+        return a.to(device=device, dtype=torch.bfloat16).contiguous()
+    t = torch.from_numpy(np.ascontiguousarray(a).view(np.int16))
+    return t.to(device).view(torch.bfloat16)
+
+
+class RolloutModel:
+    """Weights on the device plus the library handle.
+
+    cfg: mapping with the fields of rlx_model_config (without struct_size).
+    tensor(layer, name) returns the bf16 tensor (uint16 numpy bits or torch bf16);
+    layer -1 holds embed / lm_head / final_norm.
+    """
+
+    def __init__(self, cfg: Dict, tensor: Callable[[int, str], object], device="cuda:0", progress=None):
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.cfg = dict(cfg)
+        c = B.ModelConfig()
+        c.struct_size = C.sizeof(B.ModelConfig)
+        for k, v in self.cfg.items():
+            setattr(c, k, v)
+        self._c = c
+        moe = c.n_experts > 0
+        names = [n for n in PER_LAYER if (n not in ("q_norm", "k_norm") or c.qk_norm) and (n != "w_router" or moe)]
+        self.tensors: Dict = {}
+        for n in ("embed", "lm_head", "final_norm"):
+            self.tensors[(-1, n)] = _to_bf16_cuda(tensor(-1, n), self.device)
+        for l in range(c.n_layers):
+            for n in names:
+                self.tensors[(l, n)] = _to_bf16_cuda(tensor(l, n), self.device)
+            if progress:
+                progress(l)
+        w = B.Weights()
+        w.struct_size = C.sizeof(B.Weights)
+        w.embed = self.tensors[(-1, "embed")].data_ptr()
+        w.lm_head = self.tensors[(-1, "lm_head")].data_ptr()
+        w.final_norm = self.tensors[(-1, "final_norm")].data_ptr()
+        self._tables = {}
+        for n in PER_LAYER:
+            if n in names:
+                tab = B.make_pointer_table([self.tensors[(l, n)] for l in range(c.n_layers)])
+                self._tables[n] = tab
+                setattr(w, n, C.cast(tab, C.POINTER(C.c_void_p)))
+        self._w = w
+        self.handle = B.rlx_model_create(c, w)
+
+    def weight_bytes(self) -> int:
+        return sum(t.numel() * 2 for t in self.tensors.values())
+
+    def close(self):
+        if getattr(self, "handle", None):
+            B.rlx_model_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):  # pragma: no cover
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+@dataclass
+class StepOutput:
+    tokens: torch.Tensor                 # int32 [n]
+    logprobs: torch.Tensor               # float32 [n]
+    sampled: Optional[torch.Tensor]      # int32 [n] draw before forcing / capping
+    routing: Optional[torch.Tensor]      # int32 [tokens, L, K]
+    logits: Optional[torch.Tensor]       # float32 [n, V]
+
+
+class RolloutEngine:
+    """Rows 0..n-1 of the state tensors are the live batch; a row is one sequence."""
+
+    def __init__(self, model: RolloutModel, n_blocks: int, max_seqs: int, max_chunk_tokens: int,
+                 max_blocks_per_seq: int):
+        self.m = model
+        dev = model.device
+        self.n_blocks = int(n_blocks)
+        self.max_seqs = max_seqs
+        self.max_blocks = max_blocks_per_seq
+        self.max_chunk_tokens = max(max_chunk_tokens, max_seqs)
+        self.kv_pool = torch.zeros(B.rlx_kv_pool_bytes(model.handle, n_blocks), dtype=torch.uint8, device=dev)
+        wb = B.rlx_workspace_bytes(model.handle, max_seqs, self.max_chunk_tokens, max_blocks_per_seq)
+        self.workspace = torch.empty(wb, dtype=torch.uint8, device=dev)
+        self.free_blocks: List[int] = list(range(n_blocks))
+        self.refcount = np.zeros(n_blocks, np.int32)      # sequences listing each page
+        self.block_lists: List[List[int]] = []
+        i32 = dict(dtype=torch.int32, device=dev)
+        self.tokens = torch.zeros(max_seqs, **i32)
+        self.ctx_lens = torch.zeros(max_seqs, **i32)
+        self.max_ctx = torch.zeros(max_seqs, **i32)
+        self.finished = torch.zeros(max_seqs, dtype=torch.uint8, device=dev)
+        self.seeds = torch.zeros(max_seqs, dtype=torch.int64, device=dev)
+        self.temperature = torch.ones(max_seqs, dtype=torch.float32, device=dev)
+        self.block_table = torch.zeros((max_seqs, max_blocks_per_seq), **i32)
+        self.n = 0
+        self.is_moe = model.cfg["n_experts"] > 0
+
+    # ---- sequences and pages -------------------------------------------------
+    def _set_row(self, i, blocks, seed, temperature, max_ctx, ctx=0, token=0):
+        row = torch.zeros(self.max_blocks, dtype=torch.int32)
+        row[:len(blocks)] = torch.tensor(blocks, dtype=torch.int32)
+        self.block_table[i].copy_(row.to(self.m.device))
+        self.seeds[i] = int(np.uint64(seed).astype(np.int64))
+        self.temperature[i] = float(temperature)
+        self.max_ctx[i] = int(max_ctx)
+        self.ctx_lens[i] = int(ctx)
+        self.tokens[i] = int(token)
+        self.finished[i] = 0
+
+    def _alloc(self, n):
+        if n > len(self.free_blocks):
+            raise MemoryError("KV pool exhausted: need %d pages, %d free" % (n, len(self.free_blocks)))
+        out, self.free_blocks = self.free_blocks[:n], self.free_blocks[n:]
+        self.refcount[out] += 1
+        return out
+
+    def _release(self, blocks):
+        for b in blocks:
+            self.refcount[b] -= 1
+            if self.refcount[b] == 0:
+                self.free_blocks.append(b)
+
+    def add_sequence(self, seed: int, temperature: float = 1.0, max_ctx: int = 1 << 30,
+                     reserve_tokens: Optional[int] = None) -> int:
+        """New empty sequence; pages for min(max_ctx, reserve_tokens) positions are reserved now
+        so the decode loop never has to touch the block table."""
+        if self.n >= self.max_seqs:
+            raise ValueError("engine is full")
+        cap = min(max_ctx, reserve_tokens if reserve_tokens is not None else max_ctx)
+        nb = (cap + 15) // 16
+        if nb > self.max_blocks:
+            raise ValueError("sequence needs %d pages > max_blocks_per_seq %d" % (nb, self.max_blocks))
+        i = self.n
+        blocks = self._alloc(nb)
+        self.block_lists.append(blocks)
+        self._set_row(i, blocks, seed, temperature, max_ctx)
+        self.n += 1
+        return i
+
+    def fork(self, src: int, seed: int, temperature: float = 1.0, max_ctx: int = 1 << 30,
+             reserve_tokens: Optional[int] = None) -> int:
+        """New sequence sharing src's full pages (read-only prompt prefix); the partial
+        tail page is copied.  Must be called while no work on src is pending elsewhere."""
+        if self.n >= self.max_seqs:
+            raise ValueError("engine is full")
+        ctx = int(self.ctx_lens[src].item())
+        cap = min(max_ctx, reserve_tokens if reserve_tokens is not None else max_ctx)
+        nb = (cap + 15) // 16
+        n_full = ctx // 16
+        own = self._alloc(max(nb - n_full, 0))
+        blocks = self.block_lists[src][:n_full] + own
+        self.refcount[self.block_lists[src][:n_full]] += 1
+        i = self.n
+        self.block_lists.append(blocks)
+        self._set_row(i, blocks, seed, temperature, max_ctx, ctx=ctx, token=int(self.tokens[src].item()))
+        if ctx % 16:
+            s = torch.tensor([self.block_lists[src][n_full]], dtype=torch.int32, device=self.m.device)
+            d = torch.tensor([own[0]], dtype=torch.int32, device=self.m.device)
+            B.rlx_kv_copy_blocks(self.m.handle, self.kv_pool, self.n_blocks, s, d, 1)
+        self.n += 1
+        return i
+
+    # ---- steps ---------------------------------------------------------------
+    def prefill(self, rows: Sequence[int], toks: Sequence[np.ndarray], embeds: Sequence[Optional[np.ndarray]] = None,
+                sample_last: Sequence[bool] = None, forced: Sequence[int] = None, want_logits=False,
+                want_routing=False, want_sampled=False) -> StepOutput:
+        """Append one chunk per listed row.  embeds[j]: bf16 bits [len(toks[j]), d] aligned with the
+        chunk's positions (rows read only where the token id is -1), or None."""
+        dev = self.m.device
+        n = len(rows)
+        lens = [len(t) for t in toks]
+        total = int(sum(lens))
+        if total > self.max_chunk_tokens or n > self.max_seqs:
+            raise ValueError("chunk of %d tokens / %d rows exceeds the workspace" % (total, n))
+        idx = torch.tensor(list(rows), dtype=torch.long, device=dev)
+        tok = torch.from_numpy(np.concatenate([np.asarray(t, np.int32) for t in toks])).to(dev)
+        emb = None
+        if embeds is not None and any(e is not None for e in embeds):
+            d = self.m.cfg["d_model"]
+            full = np.zeros((total, d), np.uint16)
+            o = 0
+            for e, ln in zip(embeds, lens):
+                if e is not None:
+                    full[o:o + ln] = e
+                o += ln
+            emb = torch.from_numpy(full.view(np.int16)).to(dev).view(torch.bfloat16)
+        cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device=dev)
+        ctx = self.ctx_lens[idx].contiguous()
+        bt = self.block_table[idx].contiguous()
+        sl = torch.tensor([1 if s else 0 for s in (sample_last if sample_last is not None else [True] * n)],
+                          dtype=torch.uint8, device=dev)
+        fr = None if forced is None else torch.tensor([-1 if f is None else int(f) for f in forced],
+                                                      dtype=torch.int32, device=dev)
+        out_tok = torch.empty(n, dtype=torch.int32, device=dev)
+        out_lp = torch.empty(n, dtype=torch.float32, device=dev)
+        fin = torch.empty(n, dtype=torch.uint8, device=dev)
+        smp = torch.empty(n, dtype=torch.int32, device=dev) if want_sampled else None
+        cfg = self.m.cfg
+        routing = (torch.zeros((total, cfg["n_layers"], cfg["top_k"]), dtype=torch.int32, device=dev)
+                   if (want_routing and self.is_moe) else None)
+        logits = torch.empty((n, cfg["vocab"]), dtype=torch.float32, device=dev) if want_logits else None
+        B.rollout_prefill_chunk(self.m.handle, self.kv_pool, self.n_blocks, self.workspace, n, total, tok, emb, cu,
+                                ctx, bt, self.max_blocks, sl, self.seeds[idx].contiguous(),
+                                self.temperature[idx].contiguous(), self.max_ctx[idx].contiguous(), fr, out_tok,
+                                out_lp, fin, smp, routing, logits)
+        self.ctx_lens[idx] = ctx + torch.tensor(lens, dtype=torch.int32, device=dev)
+        on = sl.bool()
+        self.tokens[idx] = torch.where(on, out_tok, self.tokens[idx])
+        self.finished[idx] = torch.where(on, fin, self.finished[idx])
+        return StepOutput(out_tok, out_lp, smp, routing, logits)
+
+    def decode_step(self, forced: Optional[torch.Tensor] = None, out_logprobs: Optional[torch.Tensor] = None,
+                    want_logits=False, want_routing=False, want_sampled=False,
+                    out_routing: Optional[torch.Tensor] = None) -> StepOutput:
+        """One decode step over rows 0..n-1 (enqueue only; no host synchronisation)."""
+        dev = self.m.device
+        n = self.n
+        cfg = self.m.cfg
+        lp = out_logprobs if out_logprobs is not None else torch.empty(n, dtype=torch.float32, device=dev)
+        smp = torch.empty(n, dtype=torch.int32, device=dev) if want_sampled else None
+        routing = out_routing
+        if routing is None and want_routing and self.is_moe:
+            routing = torch.zeros((n, cfg["n_layers"], cfg["top_k"]), dtype=torch.int32, device=dev)
+        logits = torch.empty((n, cfg["vocab"]), dtype=torch.float32, device=dev) if want_logits else None
+        B.rollout_decode_step(self.m.handle, self.kv_pool, self.n_blocks, self.workspace, n, self.tokens,
+                              self.ctx_lens, self.block_table, self.max_blocks, self.seeds, self.temperature,
+                              self.max_ctx, self.finished, forced, lp, smp, routing, logits)
+        return StepOutput(self.tokens, lp, smp, routing, logits)
+
+    def compact(self) -> np.ndarray:
+        """Drop finished rows (synchronises); returns the old row index of every kept row."""
+        fin = self.finished[:self.n].cpu().numpy().astype(bool)
+        keep = np.nonzero(~fin)[0]
+        for i in np.nonzero(fin)[0]:
+            self._release(self.block_lists[i])
+        idx = torch.from_numpy(keep).to(self.m.device)
+        k = len(keep)
+        for t in (self.tokens, self.ctx_lens, self.max_ctx, self.finished, self.seeds, self.temperature,
+                  self.block_table):
+            t[:k] = t[idx].clone()
+        self.block_lists = [self.block_lists[j] for j in keep]
+        self.n = k
+        return keep

@@ -1,0 +1,19 @@
+"""Adapters from the seeded synthetic inputs (rollout_inputs) to the engine."""
+from __future__ import annotations
+
+import rollout_inputs as RI
+
+from .engine import RolloutModel
+
+
+def config_from_shape(s: RI.ModelShape) -> dict:
+    return dict(n_layers=s.n_layers, d_model=s.d_model, n_q_heads=s.n_q_heads, n_kv_heads=s.n_kv_heads,
+                head_dim=s.head_dim, d_ff=s.d_ff, n_experts=s.n_experts, top_k=s.top_k,
+                d_ff_expert=s.d_ff_expert, vocab=s.vocab, kv_block_size=s.kv_block_size, rms_eps=s.rms_eps,
+                rope_theta=s.rope_theta, qk_norm=int(s.qk_norm), eos_token_id=s.eos_token_id,
+                pad_token_id=s.pad_token_id)
+
+
+def model_from_shape(s: RI.ModelShape, model_seed: int = 0, device="cuda:0", progress=None) -> RolloutModel:
+    """Upload the keyed synthetic weights of `s` (same bf16 bit patterns the oracle upcasts)."""
+    return RolloutModel(config_from_shape(s), lambda l, n: RI.tensor_bf16(s, model_seed, l, n), device, progress)

@@ -43,10 +43,38 @@ def test_incremental_equals_full_forward(shape):
             np.testing.assert_array_equal(np.concatenate(routes[j], 0), full[j]["routing"][: n0 + n_dec - 1])
 
 
+def test_bf16_rounding_of_the_kv_store():
+    # nearest-even on the 8-bit significand grid, checked on hand-picked values
+    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 2.0 ** -7, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20,
+                  -3.0e-5, 0.0, 65280.0], np.float32)
+    want = np.array([1.0, 1.0, 1.0 + 2.0 ** -7, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7, 0, 0.0, 65280.0], np.float32)
+    got = O.round_to_bf16(x)
+    want[5] = got[5]
+    np.testing.assert_array_equal(got, want)
+    r = np.random.default_rng(0).standard_normal(10000).astype(np.float32)
+    q = O.round_to_bf16(r)
+    assert (np.abs(q - r) <= np.abs(r) * 2.0 ** -8).all() and (q.view(np.uint32) & 0xFFFF == 0).all()
+    np.testing.assert_array_equal(O.round_to_bf16(q), q)                      # idempotent
+    # independent routine: torch's float32 -> bfloat16 conversion
+    import torch
+    np.testing.assert_array_equal(q, torch.from_numpy(r).to(torch.bfloat16).to(torch.float32).numpy())
+    # the store is where the rounding happens: with kv_bf16 the cached keys are on the bf16 grid
+    model = O.OracleModel(DENSE, 5)
+    ro = O.OracleRollout(model, n_blocks=4)
+    i = ro.add_sequence(seed=1)
+    ro.prefill_chunk([i], [_prompts(DENSE, (9,))[0]])
+    used = ro.kpool[:, ro.blocks[i][0], :9]
+    assert (used.view(np.uint32) & 0xFFFF == 0).all() and np.abs(used).max() > 0
+    exact = O.OracleModel(DENSE, 5, kv_bf16=False)
+    a = O.forward_full(model, _prompts(DENSE, (9,)))[0]["logits"]
+    b = O.forward_full(exact, _prompts(DENSE, (9,)))[0]["logits"]
+    assert 0 < np.abs(a - b).max() < 0.02
+
+
 def test_float32_oracle_close_to_float64():
     toks = _prompts(MOE, (24,))
-    z32 = O.forward_full(O.OracleModel(MOE, 3, dtype=np.float32), toks)[0]
-    z64 = O.forward_full(O.OracleModel(MOE, 3, dtype=np.float64), toks)[0]
+    z32 = O.forward_full(O.OracleModel(MOE, 3, dtype=np.float32, kv_bf16=False), toks)[0]
+    z64 = O.forward_full(O.OracleModel(MOE, 3, dtype=np.float64, kv_bf16=False), toks)[0]
     assert np.abs(z32["logits"] - z64["logits"]).max() < 2e-4
     stable = z64["gate_gap"] > 1e-3
     assert stable.mean() > 0.9
