@@ -60,6 +60,8 @@ typedef struct {
   float rope_theta;      /* rotary base; pair (i, i+head_dim/2) turns by pos*theta^(-2i/head_dim) */
   int32_t qk_norm;       /* 1: per-head RMSNorm of q and k before the rotary embedding */
   int32_t eos_token_id, pad_token_id;
+  int32_t activation_split; /* 0: activations enter every matrix product as one bf16 value;
+                               1: as two bf16 terms (hi + lo, 16 significand bits, twice the MFMA work) */
 } rlx_model_config;
 
 /*

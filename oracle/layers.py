@@ -113,18 +113,21 @@ def moe_ffn_bruteforce(x: np.ndarray, w_router: np.ndarray, w_gate: np.ndarray, 
                        w_down: np.ndarray, top_k: int, forced_idx: np.ndarray = None):
     """Sparse MoE FFN for tokens x [n, d], one token and one expert at a time.
 
-    Returns (y [n, d], idx [n, k] int32, gap [n]).  With forced_idx [n, k] the given
-    experts are used (routing replay, paper Sec. 5.5) while the mixing weights
-    still come from this model's own router probabilities, renormalised over them.
+    Returns (y [n, d], idx [n, k] int32 experts used, gap [n], own [n, k] int32 the
+    router's own choice).  With forced_idx [n, k] the given experts are used (routing
+    replay, paper Sec. 5.5) while the mixing weights still come from this model's
+    own router probabilities, renormalised over them.
     """
     n = x.shape[0]
     y = np.zeros_like(x)
     idx_out = np.empty((n, top_k), dtype=np.int32)
+    own_out = np.empty((n, top_k), dtype=np.int32)
     gaps = np.empty(n, dtype=np.float64)
     r_all = x @ w_router.T
     for t in range(n):
         r = r_all[t]
         idx, w, gap = moe_gate(r, top_k)
+        own_out[t] = idx
         if forced_idx is not None:
             idx = np.asarray(forced_idx[t], dtype=np.int32)
             p = np.exp(r - r.max())
@@ -135,7 +138,7 @@ def moe_ffn_bruteforce(x: np.ndarray, w_router: np.ndarray, w_gate: np.ndarray, 
             y[t] += w[j] * swiglu_ffn(x[t:t + 1], w_gate[e], w_up[e], w_down[e])[0]
         idx_out[t] = idx
         gaps[t] = gap
-    return y, idx_out, gaps
+    return y, idx_out, gaps, own_out
 
 
 def moe_ffn(x: np.ndarray, w_router: np.ndarray, w_gate: np.ndarray, w_up: np.ndarray, w_down: np.ndarray,
@@ -147,11 +150,13 @@ def moe_ffn(x: np.ndarray, w_router: np.ndarray, w_gate: np.ndarray, w_up: np.nd
     n = x.shape[0]
     r_all = x @ w_router.T
     idx_out = np.empty((n, top_k), dtype=np.int32)
+    own_out = np.empty((n, top_k), dtype=np.int32)
     w_out = np.empty((n, top_k), dtype=x.dtype)
     gaps = np.empty(n, dtype=np.float64)
     for t in range(n):
         r = r_all[t]
         idx, w, gaps[t] = moe_gate(r, top_k)
+        own_out[t] = idx
         if forced_idx is not None:
             idx = np.asarray(forced_idx[t], dtype=np.int32)
             p = np.exp(r - r.max())
@@ -163,7 +168,7 @@ def moe_ffn(x: np.ndarray, w_router: np.ndarray, w_gate: np.ndarray, w_up: np.nd
         for e in np.unique(idx_out[:, j]):
             rows = np.nonzero(idx_out[:, j] == e)[0]
             y[rows] += w_out[rows, j:j + 1] * swiglu_ffn(x[rows], w_gate[e], w_up[e], w_down[e])
-    return y, idx_out, gaps
+    return y, idx_out, gaps, own_out
 
 
 def log_softmax(z: np.ndarray) -> np.ndarray:

@@ -109,9 +109,9 @@ def _qkv(shape: ModelShape, w: Dict[str, np.ndarray], h: np.ndarray, pos: np.nda
 def _ffn(shape: ModelShape, w: Dict[str, np.ndarray], h: np.ndarray, forced_idx: Optional[np.ndarray]):
     x = L.rmsnorm(h, w["ffn_norm"], shape.rms_eps)
     if shape.is_moe:
-        y, idx, gap = L.moe_ffn(x, w["w_router"], w["w_gate"], w["w_up"], w["w_down"], shape.top_k, forced_idx)
-        return h + y, idx, gap
-    return h + L.swiglu_ffn(x, w["w_gate"], w["w_up"], w["w_down"]), None, None
+        y, idx, gap, own = L.moe_ffn(x, w["w_router"], w["w_gate"], w["w_up"], w["w_down"], shape.top_k, forced_idx)
+        return h + y, idx, gap, own
+    return h + L.swiglu_ffn(x, w["w_gate"], w["w_up"], w["w_down"]), None, None, None
 
 
 def _logits(model: OracleModel, h: np.ndarray) -> np.ndarray:
@@ -134,7 +134,8 @@ def forward_full(model: OracleModel, tokens: Sequence[np.ndarray], embeds: Seque
     int32 [n_i, L, K] expert indices to replay.  logits_at[i]: positions whose
     logits are wanted (None = all).  Returns per sequence a dict with
       logits  [len(logits_at[i]), V]   logits predicting the token AFTER each listed position
-      routing [n_i, L, K] int32, gate_gap [n_i, L]   (MoE only)
+      routing [n_i, L, K] int32 (experts used), own_routing (the router's own choice, which
+      differs from routing only under replay), gate_gap [n_i, L]   (MoE only)
     """
     s = model.shape
     nseq = len(tokens)
@@ -142,6 +143,7 @@ def forward_full(model: OracleModel, tokens: Sequence[np.ndarray], embeds: Seque
     forced_routing = forced_routing or [None] * nseq
     hs = [_embed(model, tokens[i], embeds[i]) for i in range(nseq)]
     routing = [np.zeros((len(tokens[i]), s.n_layers, max(s.top_k, 1)), np.int32) for i in range(nseq)]
+    own = [np.zeros((len(tokens[i]), s.n_layers, max(s.top_k, 1)), np.int32) for i in range(nseq)]
     gaps = [np.full((len(tokens[i]), s.n_layers), np.inf) for i in range(nseq)]
     for l in range(s.n_layers):
         w = model.layer(l)
@@ -152,9 +154,10 @@ def forward_full(model: OracleModel, tokens: Sequence[np.ndarray], embeds: Seque
             o = L.attention(q, k, v).reshape(n, s.q_dim)
             h = h + o @ w["wo"].T
             fr = None if forced_routing[i] is None else forced_routing[i][:, l, :]
-            h, idx, gap = _ffn(s, w, h, fr)
+            h, idx, gap, own_idx = _ffn(s, w, h, fr)
             if idx is not None:
                 routing[i][:, l, :] = idx
+                own[i][:, l, :] = own_idx
                 gaps[i][:, l] = gap
             hs[i] = h
         if progress:
@@ -164,7 +167,7 @@ def forward_full(model: OracleModel, tokens: Sequence[np.ndarray], embeds: Seque
         at = np.arange(len(tokens[i])) if logits_at is None or logits_at[i] is None else np.asarray(logits_at[i])
         res = {"logits": _logits(model, hs[i][at]), "positions": at}
         if s.is_moe:
-            res["routing"], res["gate_gap"] = routing[i], gaps[i]
+            res["routing"], res["gate_gap"], res["own_routing"] = routing[i], gaps[i], own[i]
         out.append(res)
     return out
 
@@ -248,6 +251,7 @@ class OracleRollout:
         forced_routing = forced_routing or [None] * len(seq_ids)
         hs = [_embed(m, toks[j], embeds[j]) for j in range(len(seq_ids))]
         routing = [np.zeros((len(toks[j]), s.n_layers, max(s.top_k, 1)), np.int32) for j in range(len(seq_ids))]
+        own = [np.zeros((len(toks[j]), s.n_layers, max(s.top_k, 1)), np.int32) for j in range(len(seq_ids))]
         gaps = [np.full((len(toks[j]), s.n_layers), np.inf) for j in range(len(seq_ids))]
         for l in range(s.n_layers):
             w = m.layer(l)
@@ -262,14 +266,15 @@ class OracleRollout:
                 o = L.attention(q, kk, vv).reshape(n, s.q_dim)
                 h = h + o @ w["wo"].T
                 fr = None if forced_routing[j] is None else forced_routing[j][:, l, :]
-                h, idx, gap = _ffn(s, w, h, fr)
+                h, idx, gap, own_idx = _ffn(s, w, h, fr)
                 if idx is not None:
                     routing[j][:, l, :] = idx
+                    own[j][:, l, :] = own_idx
                     gaps[j][:, l] = gap
                 hs[j] = h
         for j, i in enumerate(seq_ids):
             self.ctx[i] += hs[j].shape[0]
-        return hs, routing, gaps
+        return hs, routing, gaps, own
 
     def _emit(self, i: int, z: np.ndarray, forced: Optional[int]):
         """Sample the token for position ctx[i] from logits z; apply forcing, the
@@ -298,8 +303,9 @@ class OracleRollout:
         embeds = embeds or [None] * n
         sample_last = sample_last if sample_last is not None else [True] * n
         forced_tokens = forced_tokens if forced_tokens is not None else [None] * n
-        hs, routing, gaps = self._advance(seq_ids, toks, embeds, forced_routing)
-        out = {"tokens": [], "logprobs": [], "sampled": [], "routing": routing, "gate_gap": gaps, "logits": []}
+        hs, routing, gaps, own = self._advance(seq_ids, toks, embeds, forced_routing)
+        out = {"tokens": [], "logprobs": [], "sampled": [], "routing": routing, "gate_gap": gaps,
+               "own_routing": own, "logits": []}
         for j, i in enumerate(seq_ids):
             if sample_last[j]:
                 z = _logits(self.model, hs[j][-1:])[0]
@@ -326,14 +332,14 @@ class OracleRollout:
         ids = [seq_ids[j] for j in live]
         toks = [np.array([self.last_token[i]], np.int32) for i in ids]
         fr = None if forced_routing is None else [forced_routing[j] for j in live]
-        hs, routing, gaps = self._advance(ids, toks, [None] * len(ids), fr)
+        hs, routing, gaps, own = self._advance(ids, toks, [None] * len(ids), fr)
         out = {"tokens": [s.pad_token_id] * n, "logprobs": [0.0] * n, "sampled": [-1] * n,
-               "routing": [None] * n, "gate_gap": [None] * n, "logits": [None] * n}
+               "routing": [None] * n, "gate_gap": [None] * n, "own_routing": [None] * n, "logits": [None] * n}
         for jj, j in enumerate(live):
             i = seq_ids[j]
             z = _logits(self.model, hs[jj][-1:])[0]
             tok, lp, smp = self._emit(i, z, forced_tokens[j])
             out["tokens"][j], out["logprobs"][j], out["sampled"][j] = tok, lp, smp
-            out["routing"][j], out["gate_gap"][j] = routing[jj], gaps[jj]
+            out["routing"][j], out["gate_gap"][j], out["own_routing"][j] = routing[jj], gaps[jj], own[jj]
             out["logits"][j] = z if want_logits else None
         return out

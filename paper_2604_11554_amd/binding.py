@@ -36,7 +36,7 @@ class ModelConfig(C.Structure):
                 ("n_experts", C.c_int32), ("top_k", C.c_int32), ("d_ff_expert", C.c_int32),
                 ("vocab", C.c_int32), ("kv_block_size", C.c_int32),
                 ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("qk_norm", C.c_int32),
-                ("eos_token_id", C.c_int32), ("pad_token_id", C.c_int32)]
+                ("eos_token_id", C.c_int32), ("pad_token_id", C.c_int32), ("activation_split", C.c_int32)]
 
 
 _PP = C.POINTER(C.c_void_p)

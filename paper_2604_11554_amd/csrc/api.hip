@@ -50,7 +50,7 @@ namespace {
 struct Workspace {
   TokenMeta meta;
   float* h;          // [T, d]
-  bf16_t* xb;        // [T, d]
+  bf16_t* xb;        // [planes][T, d]; every bf16 activation buffer below has `planes` copies
   float* xf;         // [T, d] (MoE)
   float* qkv;        // [planes][T, qkv_dim]
   bf16_t* q;         // [T, q_dim]
@@ -90,17 +90,18 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
   w.meta.qtile_q0 = (int32_t*)take((size_t)QT * 4);
   w.meta.n_qtiles = (int32_t*)take(4);
   w.h = (float*)take((size_t)T * c.d_model * 4);
-  w.xb = (bf16_t*)take((size_t)T * c.d_model * 2);
+  const size_t PL = c.activation_split ? 2 : 1;
+  w.xb = (bf16_t*)take(PL * T * c.d_model * 2);
   w.xf = c.n_experts ? (float*)take((size_t)T * c.d_model * 4) : nullptr;
   w.qkv = (float*)take((size_t)plane_rows(T) * qkv_dim * 4);
-  w.q = (bf16_t*)take((size_t)T * qdim * 2);
-  w.ob = (bf16_t*)take((size_t)T * qdim * 2);
+  w.q = (bf16_t*)take(PL * T * qdim * 2);
+  w.ob = (bf16_t*)take(PL * T * qdim * 2);
   const int n_splits = (max_blocks * 16 + ATTN_SPLIT_TOKENS - 1) / ATTN_SPLIT_TOKENS;
   w.attn_part = (float*)take((size_t)S * c.n_q_heads * n_splits * (c.head_dim + 2) * 4);
   w.planes = (float*)take((size_t)plane_rows(T) * c.d_model * 4);
   if (c.n_experts) {
     const size_t P = (size_t)T * c.top_k;
-    w.act = (bf16_t*)take(P * c.d_ff_expert * 2);
+    w.act = (bf16_t*)take(PL * P * c.d_ff_expert * 2);
     w.moe_y = (float*)take(P * c.d_model * 4);
     w.topk_idx = (int32_t*)take(P * 4);
     w.topk_w = (float*)take(P * 4);
@@ -109,9 +110,9 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
     w.sorted_token = (int32_t*)take(P * 4);
     w.pair_pos = (int32_t*)take(P * 4);
   } else {
-    w.act = (bf16_t*)take((size_t)T * c.d_ff * 2);
+    w.act = (bf16_t*)take(PL * T * c.d_ff * 2);
   }
-  w.x_lm = (bf16_t*)take((size_t)S * c.d_model * 2);
+  w.x_lm = (bf16_t*)take(PL * S * c.d_model * 2);
   w.lm_part = (float*)take((size_t)S * lmhead_tiles(c.vocab) * 4 * 4);
   w.bytes = off;
   return w;
@@ -137,12 +138,14 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
   const int d = c.d_model, T = io.T;
   const int qdim = c.n_q_heads * c.head_dim, kvdim = c.n_kv_heads * c.head_dim, qkv_dim = qdim + 2 * kvdim;
   const bool small = T <= 256;
+  const int PL = c.activation_split ? 2 : 1;
+  const Act xb = make_act(w.xb, T, d, PL), qb = make_act(w.q, T, qdim, PL), ob = make_act(w.ob, T, qdim, PL);
 
   RLX_HIP(embed_tokens(m->embed, c.vocab, d, io.tokens, io.input_embeds, T, w.h, st));
 
   // residual contribution produced by the previous sub-layer, folded into the next norm
   const float* pend_planes = nullptr; int pend_n = 0; bool pend_moe = false;
-  auto norm = [&](const bf16_t* gain, const int32_t* rows, int n_rows, bf16_t* x, float* xf) -> hipError_t {
+  auto norm = [&](const bf16_t* gain, const int32_t* rows, int n_rows, const Act& x, float* xf) -> hipError_t {
     NormArgs a = {};
     a.h = w.h; a.gain = gain; a.d = d; a.T = n_rows; a.T_total = T; a.eps = c.rms_eps; a.rows = rows;
     a.add = pend_planes; a.n_planes = pend_n;
@@ -153,14 +156,14 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
   };
 
   for (int l = 0; l < c.n_layers; ++l) {
-    RLX_HIP(norm(m->attn_norm[l], nullptr, T, w.xb, nullptr));
+    RLX_HIP(norm(m->attn_norm[l], nullptr, T, xb, nullptr));
     LinearW wqkv = {};
     wqkv.seg[0] = m->wq[l]; wqkv.rows[0] = qdim;
     wqkv.seg[1] = m->wk[l]; wqkv.rows[1] = kvdim;
     wqkv.seg[2] = m->wv[l]; wqkv.rows[2] = kvdim;
     wqkv.N = qkv_dim; wqkv.K = d;
     const int s_qkv = small ? gemm_plan_splits(qkv_dim, d, gemm_max_splits()) : 1;
-    RLX_HIP(gemm_store(wqkv, w.xb, d, nullptr, T, w.qkv, qkv_dim, s_qkv, st));
+    RLX_HIP(gemm_store(wqkv, xb, nullptr, T, w.qkv, qkv_dim, s_qkv, st));
 
     RopeArgs r = {};
     r.qkv = w.qkv; r.n_planes = s_qkv;
@@ -168,28 +171,29 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
     r.inv_freq = m->inv_freq; r.T = T; r.Hq = c.n_q_heads; r.Hkv = c.n_kv_heads; r.hd = c.head_dim;
     r.eps = c.rms_eps; r.tok_seq = w.meta.tok_seq; r.tok_pos = w.meta.tok_pos; r.tok_live = w.meta.tok_live;
     r.block_table = io.block_table; r.max_blocks = io.max_blocks;
-    r.pool_layer = pool + (size_t)l * n_blocks * block_elems(c); r.n_blocks = n_blocks; r.q_out = w.q;
+    r.pool_layer = pool + (size_t)l * n_blocks * block_elems(c); r.n_blocks = n_blocks; r.q_out = qb;
     RLX_HIP(qk_rope_append(r, st));
 
     AttnArgs at = {};
-    at.q = w.q; at.pool_layer = r.pool_layer; at.n_blocks = n_blocks;
+    at.q = qb; at.pool_layer = r.pool_layer; at.n_blocks = n_blocks;
     at.Hq = c.n_q_heads; at.Hkv = c.n_kv_heads; at.hd = c.head_dim;
     at.block_table = io.block_table; at.max_blocks = io.max_blocks; at.ctx_lens = io.ctx_lens;
     at.n_seqs = io.n_seqs; at.tok_live = w.meta.tok_live; at.part = w.attn_part;
     at.n_splits = (io.max_blocks * 16 + ATTN_SPLIT_TOKENS - 1) / ATTN_SPLIT_TOKENS;
     at.cu_seqlens = io.cu_seqlens; at.qtile_seq = w.meta.qtile_seq; at.qtile_q0 = w.meta.qtile_q0;
-    at.n_qtiles = w.meta.n_qtiles; at.max_qtiles = T / 16 + io.n_seqs + 1; at.o = w.ob;
+    at.n_qtiles = w.meta.n_qtiles; at.max_qtiles = T / 16 + io.n_seqs + 1; at.o = ob;
     RLX_HIP(io.decode ? attention_decode(at, st) : attention_prefill(at, st));
 
     const int s_o = small ? gemm_plan_splits(d, qdim, gemm_max_splits()) : 1;
-    RLX_HIP(gemm_store(linear1(m->wo[l], d, qdim), w.ob, qdim, nullptr, T, w.planes, d, s_o, st));
+    RLX_HIP(gemm_store(linear1(m->wo[l], d, qdim), ob, nullptr, T, w.planes, d, s_o, st));
     pend_planes = w.planes; pend_n = s_o;
 
-    RLX_HIP(norm(m->ffn_norm[l], nullptr, T, w.xb, w.xf));
+    RLX_HIP(norm(m->ffn_norm[l], nullptr, T, xb, w.xf));
     if (c.n_experts == 0) {
-      RLX_HIP(gemm_swiglu(m->w_gate[l], m->w_up[l], c.d_ff, d, w.xb, d, T, w.act, c.d_ff, st));
+      const Act act = make_act(w.act, T, c.d_ff, PL);
+      RLX_HIP(gemm_swiglu(m->w_gate[l], m->w_up[l], c.d_ff, d, xb, T, act, st));
       const int s_d = small ? gemm_plan_splits(d, c.d_ff, gemm_max_splits()) : 1;
-      RLX_HIP(gemm_store(linear1(m->w_down[l], d, c.d_ff), w.act, c.d_ff, nullptr, T, w.planes, d, s_d, st));
+      RLX_HIP(gemm_store(linear1(m->w_down[l], d, c.d_ff), act, nullptr, T, w.planes, d, s_d, st));
       pend_planes = w.planes; pend_n = s_d;
     } else {
       RouterArgs ra = {};
@@ -198,22 +202,23 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
       ra.n_layers = c.n_layers; ra.tok_live = w.meta.tok_live;
       RLX_HIP(moe_router(ra, st));
       RLX_HIP(moe_group(w.topk_idx, T, c.top_k, c.n_experts, w.counts, w.group_off, w.sorted_token, w.pair_pos, st));
-      RLX_HIP(gemm_grouped_swiglu(m->w_gate[l], m->w_up[l], c.n_experts, c.d_ff_expert, d, w.xb, d, w.sorted_token,
-                                  w.group_off, T, w.act, st));
-      RLX_HIP(gemm_grouped_store(m->w_down[l], c.n_experts, d, c.d_ff_expert, w.act, c.d_ff_expert, w.group_off, T,
-                                 w.moe_y, st));
+      const Act act = make_act(w.act, T * c.top_k, c.d_ff_expert, PL);
+      RLX_HIP(gemm_grouped_swiglu(m->w_gate[l], m->w_up[l], c.n_experts, c.d_ff_expert, d, xb, w.sorted_token,
+                                  w.group_off, T, act, st));
+      RLX_HIP(gemm_grouped_store(m->w_down[l], c.n_experts, d, c.d_ff_expert, act, w.group_off, T, w.moe_y, st));
       pend_moe = true;
     }
   }
 
   // final norm of the rows that emit a token, LM head with fused log-sum-exp / Gumbel-max partials
   const int S = io.n_seqs;
-  RLX_HIP(norm(m->final_norm, w.meta.sample_row, S, w.x_lm, nullptr));
-  RLX_HIP(gemm_lmhead(m->lm_head, c.vocab, d, w.x_lm, d, S, io.out_logits, w.lm_part, io.seeds, io.temperature,
+  const Act x_lm = make_act(w.x_lm, S, d, PL);
+  RLX_HIP(norm(m->final_norm, w.meta.sample_row, S, x_lm, nullptr));
+  RLX_HIP(gemm_lmhead(m->lm_head, c.vocab, d, x_lm, S, io.out_logits, w.lm_part, io.seeds, io.temperature,
                       w.meta.sample_pos, st));
   FinalizeArgs f = {};
   f.n_rows = S; f.n_tiles = lmhead_tiles(c.vocab); f.vocab = c.vocab; f.d = d;
-  f.part = w.lm_part; f.x = w.x_lm; f.w_lm = m->lm_head;
+  f.part = w.lm_part; f.x = x_lm; f.w_lm = m->lm_head;
   f.temperature = io.temperature; f.max_ctx_len = io.max_ctx_len; f.forced = io.forced;
   f.sample_pos = w.meta.sample_pos; f.sample_on = w.meta.sample_on;
   f.eos = c.eos_token_id; f.pad = c.pad_token_id;
@@ -266,6 +271,8 @@ int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* wt, rlx_mod
   if (c.eos_token_id < 0 || c.eos_token_id >= c.vocab || c.pad_token_id < 0 || c.pad_token_id >= c.vocab)
     return fail(RLX_EINVAL, "eos/pad token id outside the vocabulary");
   if (!(c.rms_eps >= 0.f) || !(c.rope_theta > 0.f)) return fail(RLX_EINVAL, "rms_eps / rope_theta");
+  if (c.activation_split != 0 && c.activation_split != 1) return fail(RLX_EINVAL, "activation_split must be 0 or 1");
+  if (c.qk_norm != 0 && c.qk_norm != 1) return fail(RLX_EINVAL, "qk_norm must be 0 or 1");
   if (!wt->embed || !wt->lm_head || !wt->final_norm) return fail(RLX_EINVAL, "NULL global weight");
   if (!aligned16(wt->embed) || !aligned16(wt->lm_head) || !aligned16(wt->final_norm))
     return fail(RLX_EINVAL, "weights must be 16-byte aligned");
@@ -408,14 +415,15 @@ int rlx_op_linear(const void* x, const void* w, float* y, int32_t n_tokens, int3
   if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return fail(RLX_EINVAL, "rlx_op_linear: 16-byte alignment");
   const int splits = n_tokens <= 256 ? gemm_plan_splits(n, k, gemm_max_splits()) : 1;
   hipStream_t st = (hipStream_t)stream;
+  const Act xa = make_act((const bf16_t*)x, n_tokens, k, 1);
   if (splits == 1) {
-    RLX_HIP(gemm_store(linear1(w, n, k), (const bf16_t*)x, k, nullptr, n_tokens, y, n, 1, st));
+    RLX_HIP(gemm_store(linear1(w, n, k), xa, nullptr, n_tokens, y, n, 1, st));
     return RLX_OK;
   }
   const size_t need = (size_t)splits * n_tokens * n * 4;
   if (!workspace || workspace_bytes < need)
     return fail(RLX_ENOMEM, "rlx_op_linear: workspace needs %zu bytes", need);
-  RLX_HIP(gemm_store(linear1(w, n, k), (const bf16_t*)x, k, nullptr, n_tokens, (float*)workspace, n, splits, st));
+  RLX_HIP(gemm_store(linear1(w, n, k), xa, nullptr, n_tokens, (float*)workspace, n, splits, st));
   RLX_HIP(sum_planes((const float*)workspace, splits, (size_t)n_tokens * n, y, st));
   return RLX_OK;
 }

@@ -58,7 +58,7 @@ __device__ __forceinline__ void store_to_lds(const WaveState<HD, NCT>& st, float
   }
 }
 
-template <int HD, int NCT, bool DECODE>
+template <int HD, int NCT, bool DECODE, int PL>
 __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
   constexpr int DT = HD / 16, KS = HD / 32;
   __shared__ f32x4 lds_o[2][NCT * DT * WAVE];
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
   }
 
   // ---- query fragments and per-column limits ----
-  bf16x8 qf[NCT][KS];
+  bf16x8 qf[PL][NCT][KS];
   int pos_col[NCT];
   bool col_ok[NCT];
   int trow[NCT], head[NCT];
@@ -110,9 +110,12 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
       pos_col[c] = ctx + q0 + c16;
     }
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-      qf[c][ks] = col_ok[c] ? load_bf16x8(a.q + ((size_t)trow[c] * a.Hq + head[c]) * HD + 32 * ks + 8 * g)
-                            : zero_bf16x8();
+    for (int p = 0; p < PL; ++p)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        qf[p][c][ks] = col_ok[c] ? load_bf16x8(a.q.p + p * a.q.plane + ((size_t)trow[c] * a.Hq + head[c]) * HD +
+                                               32 * ks + 8 * g)
+                                 : zero_bf16x8();
   }
 
   WaveState<HD, NCT> st;
@@ -151,10 +154,12 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
       bf16x8 k0 = load_bf16x8(kp0 + c16 * HD + 32 * ks + 8 * g);
       bf16x8 k1 = load_bf16x8(kp1 + c16 * HD + 32 * ks + 8 * g);
 #pragma unroll
-      for (int c = 0; c < NCT; ++c) {
-        s0[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[c][ks], s0[c], 0, 0, 0);
-        s1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[c][ks], s1[c], 0, 0, 0);
-      }
+      for (int c = 0; c < NCT; ++c)
+#pragma unroll
+        for (int p = PL - 1; p >= 0; --p) {
+          s0[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[p][c][ks], s0[c], 0, 0, 0);
+          s1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[p][c][ks], s1[c], 0, 0, 0);
+        }
     }
     // V^T fragments: rows d = 16 dt + c16, tokens 4g..4g+3 of each of the two pages
     bf16x8 vf[DT];
@@ -162,7 +167,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     for (int dt = 0; dt < DT; ++dt)
       vf[dt] = load_2x4(vp0 + (size_t)(16 * dt + c16) * 16 + 4 * g, vp1 + (size_t)(16 * dt + c16) * 16 + 4 * g);
 
-    bf16x8 pf[NCT];
+    bf16x8 pf[PL][NCT];
 #pragma unroll
     for (int c = 0; c < NCT; ++c) {
       float mx = -INFINITY;
@@ -190,15 +195,25 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
       st.m[c] = mn;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) st.o[c][dt] *= alpha;
-      u32x4 pk = {pack_bf16x2(p0[0], p0[1]), pack_bf16x2(p0[2], p0[3]), pack_bf16x2(p1[0], p1[1]),
-                  pack_bf16x2(p1[2], p1[3])};
-      pf[c] = __builtin_bit_cast(bf16x8, pk);
+      bf16_t ph[8], pl[8];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) { split_bf16(p0[v], ph[v], pl[v]); split_bf16(p1[v], ph[4 + v], pl[4 + v]); }
+      u32x4 pk = {(uint32_t)ph[0] | ((uint32_t)ph[1] << 16), (uint32_t)ph[2] | ((uint32_t)ph[3] << 16),
+                  (uint32_t)ph[4] | ((uint32_t)ph[5] << 16), (uint32_t)ph[6] | ((uint32_t)ph[7] << 16)};
+      pf[0][c] = __builtin_bit_cast(bf16x8, pk);
+      if (PL == 2) {
+        u32x4 pk2 = {(uint32_t)pl[0] | ((uint32_t)pl[1] << 16), (uint32_t)pl[2] | ((uint32_t)pl[3] << 16),
+                     (uint32_t)pl[4] | ((uint32_t)pl[5] << 16), (uint32_t)pl[6] | ((uint32_t)pl[7] << 16)};
+        pf[PL - 1][c] = __builtin_bit_cast(bf16x8, pk2);
+      }
     }
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int c = 0; c < NCT; ++c)
-        st.o[c][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf[c], st.o[c][dt], 0, 0, 0);
+#pragma unroll
+        for (int p = PL - 1; p >= 0; --p)
+          st.o[c][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf[p][c], st.o[c][dt], 0, 0, 0);
   }
 
   // denominators: sum the four lane groups' partial sums of each column
@@ -229,12 +244,19 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
       if (g == 0) { dst[HD] = st.m[c]; dst[HD + 1] = st.l[c]; }
     } else {
       const float inv = st.l[c] > 0.f ? 1.f / st.l[c] : 0.f;
-      bf16_t* dst = a.o + ((size_t)trow[c] * a.Hq + head[c]) * HD;
+      bf16_t* dst = const_cast<bf16_t*>(a.o.p) + ((size_t)trow[c] * a.Hq + head[c]) * HD;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
         f32x4 v = st.o[c][dt] * inv;
-        u32x2 p = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+        bf16_t hi[4], lo[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) split_bf16(v[j], hi[j], lo[j]);
+        u32x2 p = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
         *reinterpret_cast<u32x2*>(dst + 16 * dt + 4 * g) = p;
+        if (PL == 2) {
+          u32x2 p2 = {(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
+          *reinterpret_cast<u32x2*>(dst + a.o.plane + 16 * dt + 4 * g) = p2;
+        }
       }
     }
   }
@@ -245,8 +267,12 @@ template <int HD>
 __global__ void attn_merge_kernel(AttnArgs a) {
   const int seq = blockIdx.x, head = blockIdx.y;
   const int d = threadIdx.x;   // HD threads
-  bf16_t* dst = a.o + ((size_t)seq * a.Hq + head) * HD;
-  if (!a.tok_live[seq]) { dst[d] = 0; return; }
+  bf16_t* dst = const_cast<bf16_t*>(a.o.p) + ((size_t)seq * a.Hq + head) * HD;
+  if (!a.tok_live[seq]) {
+    dst[d] = 0;
+    if (a.o.planes == 2) dst[a.o.plane + d] = 0;
+    return;
+  }
   const int n_keys = a.ctx_lens[seq] + 1;
   const int ns = min(a.n_splits, (n_keys + ATTN_SPLIT_TOKENS - 1) / ATTN_SPLIT_TOKENS);
   const float* base = a.part + ((size_t)seq * a.Hq + head) * a.n_splits * (HD + 2);
@@ -262,18 +288,24 @@ __global__ void attn_merge_kernel(AttnArgs a) {
     l = l * aa + ls * ab;
     m = mn;
   }
-  dst[d] = f32_to_bf16(l > 0.f ? o / l : 0.f);
+  bf16_t hi, lo;
+  split_bf16(l > 0.f ? o / l : 0.f, hi, lo);
+  dst[d] = hi;
+  if (a.o.planes == 2) dst[a.o.plane + d] = lo;
 }
 
 }  // namespace
 
 hipError_t attention_decode(const AttnArgs& a, hipStream_t st) {
   dim3 grid(a.n_seqs * a.Hkv, a.n_splits);
+  const bool two = a.q.planes == 2;
   if (a.hd == 128) {
-    hipLaunchKernelGGL((attn_kernel<128, 1, true>), grid, dim3(256), 0, st, a);
+    if (two) hipLaunchKernelGGL((attn_kernel<128, 1, true, 2>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((attn_kernel<128, 1, true, 1>), grid, dim3(256), 0, st, a);
     hipLaunchKernelGGL((attn_merge_kernel<128>), dim3(a.n_seqs, a.Hq), dim3(128), 0, st, a);
   } else {
-    hipLaunchKernelGGL((attn_kernel<64, 1, true>), grid, dim3(256), 0, st, a);
+    if (two) hipLaunchKernelGGL((attn_kernel<64, 1, true, 2>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((attn_kernel<64, 1, true, 1>), grid, dim3(256), 0, st, a);
     hipLaunchKernelGGL((attn_merge_kernel<64>), dim3(a.n_seqs, a.Hq), dim3(64), 0, st, a);
   }
   return hipGetLastError();
@@ -284,8 +316,14 @@ hipError_t attention_prefill(const AttnArgs& a, hipStream_t st) {
   const int group = a.Hq / a.Hkv;
   const int passes = (group + NCT - 1) / NCT;
   dim3 grid(a.max_qtiles, a.Hkv * passes);
-  if (a.hd == 128) hipLaunchKernelGGL((attn_kernel<128, NCT, false>), grid, dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((attn_kernel<64, NCT, false>), grid, dim3(256), 0, st, a);
+  const bool two = a.q.planes == 2;
+  if (a.hd == 128) {
+    if (two) hipLaunchKernelGGL((attn_kernel<128, NCT, false, 2>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((attn_kernel<128, NCT, false, 1>), grid, dim3(256), 0, st, a);
+  } else {
+    if (two) hipLaunchKernelGGL((attn_kernel<64, NCT, false, 2>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((attn_kernel<64, NCT, false, 1>), grid, dim3(256), 0, st, a);
+  }
   return hipGetLastError();
 }
 

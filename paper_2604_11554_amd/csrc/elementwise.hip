@@ -112,7 +112,11 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(NormArgs a) {
   float rstd = 1.0f / sqrtf(tot / (float)a.d + a.eps);
   for (int i = threadIdx.x; i < a.d; i += 256) {
     float v = hrow[i] * rstd * bf16_to_f32(a.gain[i]);   // own writes: visible to the same thread
-    if (a.x) a.x[(size_t)r * a.d + i] = f32_to_bf16(v);
+    bf16_t hi, lo;
+    split_bf16(v, hi, lo);
+    bf16_t* xo = const_cast<bf16_t*>(a.x.p) + (size_t)r * a.x.ld + i;
+    xo[0] = hi;
+    if (a.x.planes == 2) xo[a.x.plane] = lo;
     if (a.xf) a.xf[(size_t)r * a.d + i] = v;
   }
 }
@@ -167,9 +171,13 @@ __global__ __launch_bounds__(256) void qk_rope_append_kernel(RopeArgs a) {
       float y0 = x0 * c - x1 * s, y1 = x1 * c + x0 * s;
       if (lane < half) {
         if (is_q) {
-          bf16_t* dst = a.q_out + ((size_t)t * a.Hq + h) * hd;
-          dst[lane] = f32_to_bf16(y0);
-          dst[lane + half] = f32_to_bf16(y1);
+          bf16_t* dst = const_cast<bf16_t*>(a.q_out.p) + ((size_t)t * a.Hq + h) * hd;
+          bf16_t h0, l0, h1, l1;
+          split_bf16(y0, h0, l0);
+          split_bf16(y1, h1, l1);
+          dst[lane] = h0;
+          dst[lane + half] = h1;
+          if (a.q_out.planes == 2) { dst[a.q_out.plane + lane] = l0; dst[a.q_out.plane + lane + half] = l1; }
         } else if (blk >= 0) {
           int kvh = h - a.Hq;
           bf16_t* dst = a.pool_layer + (((size_t)blk * a.Hkv + kvh) * 2) * 16 * hd + (size_t)slot * hd;

@@ -18,7 +18,8 @@ constexpr int GEMM_WAVES = 4;
 constexpr int GEMM_THREADS = GEMM_WAVES * WAVE;
 
 struct GemmArgs {
-  const bf16_t* x;        // [T, ldx]
+  const bf16_t* x;        // [planes][T, ldx]: activations as a sum of `planes` bf16 terms
+  size_t x_plane;         // elements between planes
   const int32_t* x_rows;  // optional gather: logical token t reads row x_rows[t]
   int ldx;
   const bf16_t* w[3];     // up to three stacked row segments
@@ -28,7 +29,8 @@ struct GemmArgs {
   int ksteps_per_wave;    // k-steps (16 wide) per wave
   float* y;               // EPI_STORE: [splits][T][ldy]
   int ldy;
-  bf16_t* act;            // EPI_SWIGLU: [T][ldy]
+  bf16_t* act;            // EPI_SWIGLU: [planes][T][ldy]
+  size_t act_plane;
   // LM-head epilogue
   float* logits;          // optional [T][N]
   float* part;            // [T][n_tiles][4] = max, sumexp, best score, best index (as float bits)
@@ -78,7 +80,7 @@ __device__ __forceinline__ float gumbel_from_u32(uint32_t r) {
   return -logf(nl);
 }
 
-template <int MT, int EPI>
+template <int MT, int EPI, int PL>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
   constexpr int NW = (EPI == EPI_SWIGLU) ? 2 : 1;
   __shared__ float red[GEMM_WAVES][NW * MT][4][WAVE][4];
@@ -127,7 +129,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
 
   constexpr int U = 4;
   for (int ks = ks_begin; ks < ks_end; ks += U) {
-    bf16x8 wf[U], wf2[U], xf[U][MT];
+    bf16x8 wf[U], wf2[U], xf[U][MT][PL];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       int k = (ks + u) * 16 + half * 8;
@@ -135,16 +137,21 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
       wf[u] = (ok && wrow) ? load_bf16x8(wrow + k) : zero_bf16x8();
       if (EPI == EPI_SWIGLU) wf2[u] = (ok && wrow2) ? load_bf16x8(wrow2 + k) : zero_bf16x8();
 #pragma unroll
-      for (int m = 0; m < MT; ++m) xf[u][m] = (ok && xrow[m]) ? load_bf16x8(xrow[m] + k) : zero_bf16x8();
+      for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int p = 0; p < PL; ++p)
+          xf[u][m][p] = (ok && xrow[m]) ? load_bf16x8(xrow[m] + p * a.x_plane + k) : zero_bf16x8();
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
-      for (int m = 0; m < MT; ++m) {
-        acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u], xf[u][m], acc[m], 0, 0, 0);
-        if (EPI == EPI_SWIGLU)
-          acc[MT + m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf2[u], xf[u][m], acc[MT + m], 0, 0, 0);
-      }
+      for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int p = PL - 1; p >= 0; --p) {   // small term first
+          acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u], xf[u][m][p], acc[m], 0, 0, 0);
+          if (EPI == EPI_SWIGLU)
+            acc[MT + m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf2[u], xf[u][m][p], acc[MT + m], 0, 0, 0);
+        }
     }
   }
 
@@ -198,13 +205,23 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
           float g = s[m][j], u = s[MT + m][j];
           o[j] = g / (1.f + __expf(-g)) * u;
         }
+        bf16_t hi[4], lo[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) split_bf16(o[j], hi[j], lo[j]);
         if (nrow + 3 < a.N) {
-          u32x2 p = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+          u32x2 p = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
           *reinterpret_cast<u32x2*>(dst) = p;
+          if (PL == 2) {
+            u32x2 q2 = {(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
+            *reinterpret_cast<u32x2*>(dst + a.act_plane) = q2;
+          }
         } else {
 #pragma unroll
           for (int j = 0; j < 4; ++j)
-            if (nrow + j < a.N) dst[j] = f32_to_bf16(o[j]);
+            if (nrow + j < a.N) {
+              dst[j] = hi[j];
+              if (PL == 2) dst[a.act_plane + j] = lo[j];
+            }
         }
       }
     }
@@ -273,14 +290,16 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
 }
 
 template <int EPI>
-void launch_mt(const GemmArgs& a, dim3 grid_xy, int mt, hipStream_t st) {
+void launch_mt(const GemmArgs& a, dim3 grid_xy, int mt, int planes, hipStream_t st) {
   // tokens are covered by grid.z super-tiles of 32*MT
   if (mt == 1) {
     dim3 g(grid_xy.x, grid_xy.y, (a.T + 31) / 32);
-    hipLaunchKernelGGL((gemm_skinny_kernel<1, EPI>), g, dim3(GEMM_THREADS), 0, st, a);
+    if (planes == 2) hipLaunchKernelGGL((gemm_skinny_kernel<1, EPI, 2>), g, dim3(GEMM_THREADS), 0, st, a);
+    else hipLaunchKernelGGL((gemm_skinny_kernel<1, EPI, 1>), g, dim3(GEMM_THREADS), 0, st, a);
   } else {
     dim3 g(grid_xy.x, grid_xy.y, (a.T + 63) / 64);
-    hipLaunchKernelGGL((gemm_skinny_kernel<2, EPI>), g, dim3(GEMM_THREADS), 0, st, a);
+    if (planes == 2) hipLaunchKernelGGL((gemm_skinny_kernel<2, EPI, 2>), g, dim3(GEMM_THREADS), 0, st, a);
+    else hipLaunchKernelGGL((gemm_skinny_kernel<2, EPI, 1>), g, dim3(GEMM_THREADS), 0, st, a);
   }
 }
 
@@ -299,72 +318,72 @@ int gemm_plan_splits(int N, int K, int max_splits) {
   return pick_splits((N + 31) / 32, (K + 15) / 16, max_splits);
 }
 
-hipError_t gemm_store(const LinearW& w, const bf16_t* x, int ldx, const int32_t* x_rows, int T, float* y, int ldy,
+hipError_t gemm_store(const LinearW& w, const Act& x, const int32_t* x_rows, int T, float* y, int ldy,
                       int splits, hipStream_t st) {
   GemmArgs a = {};
-  a.x = x; a.x_rows = x_rows; a.ldx = ldx;
+  a.x = x.p; a.x_plane = x.plane; a.x_rows = x_rows; a.ldx = x.ld;
   for (int i = 0; i < 3; ++i) { a.w[i] = w.seg[i]; a.w_rows[i] = w.rows[i]; }
   a.N = w.N; a.K = w.K; a.T = T;
   int ksteps = (w.K + 15) / 16;
   a.ksteps_per_wave = (ksteps + splits * GEMM_WAVES - 1) / (splits * GEMM_WAVES);
   a.y = y; a.ldy = ldy;
-  launch_mt<EPI_STORE>(a, dim3((w.N + 31) / 32, splits), T > 32 ? 2 : 1, st);
+  launch_mt<EPI_STORE>(a, dim3((w.N + 31) / 32, splits), T > 32 ? 2 : 1, x.planes, st);
   return hipGetLastError();
 }
 
-hipError_t gemm_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int F, int K, const bf16_t* x, int ldx, int T,
-                       bf16_t* act, int ldact, hipStream_t st) {
+hipError_t gemm_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int F, int K, const Act& x, int T,
+                       const Act& act, hipStream_t st) {
   GemmArgs a = {};
-  a.x = x; a.ldx = ldx;
+  a.x = x.p; a.x_plane = x.plane; a.ldx = x.ld;
   a.w[0] = w_gate; a.w_rows[0] = F; a.w2 = w_up;
   a.N = F; a.K = K; a.T = T;
   int ksteps = (K + 15) / 16;
   a.ksteps_per_wave = (ksteps + GEMM_WAVES - 1) / GEMM_WAVES;
-  a.act = act; a.ldy = ldact;
-  launch_mt<EPI_SWIGLU>(a, dim3((F + 31) / 32, 1), T > 32 ? 2 : 1, st);
+  a.act = const_cast<bf16_t*>(act.p); a.act_plane = act.plane; a.ldy = act.ld;
+  launch_mt<EPI_SWIGLU>(a, dim3((F + 31) / 32, 1), T > 32 ? 2 : 1, x.planes, st);
   return hipGetLastError();
 }
 
-hipError_t gemm_grouped_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int E, int F, int K, const bf16_t* x, int ldx,
-                               const int32_t* x_rows, const int32_t* group_off, int max_rows, bf16_t* act,
+hipError_t gemm_grouped_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int E, int F, int K, const Act& x,
+                               const int32_t* x_rows, const int32_t* group_off, int max_rows, const Act& act,
                                hipStream_t st) {
   GemmArgs a = {};
-  a.x = x; a.x_rows = x_rows; a.ldx = ldx;
+  a.x = x.p; a.x_plane = x.plane; a.x_rows = x_rows; a.ldx = x.ld;
   a.w[0] = w_gate; a.w_rows[0] = F; a.w2 = w_up;
   a.N = F; a.K = K; a.T = max_rows;
   a.ksteps_per_wave = ((K + 15) / 16 + GEMM_WAVES - 1) / GEMM_WAVES;
-  a.act = act; a.ldy = F;
+  a.act = const_cast<bf16_t*>(act.p); a.act_plane = act.plane; a.ldy = act.ld;
   a.group_off = group_off; a.w_expert_stride = (size_t)F * K;
-  launch_mt<EPI_SWIGLU>(a, dim3((F + 31) / 32, E), max_rows > 32 ? 2 : 1, st);
+  launch_mt<EPI_SWIGLU>(a, dim3((F + 31) / 32, E), max_rows > 32 ? 2 : 1, x.planes, st);
   return hipGetLastError();
 }
 
-hipError_t gemm_grouped_store(const bf16_t* w, int E, int N, int K, const bf16_t* x, int ldx,
+hipError_t gemm_grouped_store(const bf16_t* w, int E, int N, int K, const Act& x,
                               const int32_t* group_off, int max_rows, float* y, hipStream_t st) {
   GemmArgs a = {};
-  a.x = x; a.ldx = ldx;
+  a.x = x.p; a.x_plane = x.plane; a.ldx = x.ld;
   a.w[0] = w; a.w_rows[0] = N;
   a.N = N; a.K = K; a.T = max_rows;
   a.ksteps_per_wave = ((K + 15) / 16 + GEMM_WAVES - 1) / GEMM_WAVES;
   a.y = y; a.ldy = N;
   a.group_off = group_off; a.w_expert_stride = (size_t)N * K;
-  launch_mt<EPI_STORE>(a, dim3((N + 31) / 32, E), max_rows > 32 ? 2 : 1, st);
+  launch_mt<EPI_STORE>(a, dim3((N + 31) / 32, E), max_rows > 32 ? 2 : 1, x.planes, st);
   return hipGetLastError();
 }
 
 int lmhead_tiles(int vocab) { return (vocab + 31) / 32; }
 
-hipError_t gemm_lmhead(const bf16_t* w_lm, int V, int K, const bf16_t* x, int ldx, int T, float* logits, float* part,
+hipError_t gemm_lmhead(const bf16_t* w_lm, int V, int K, const Act& x, int T, float* logits, float* part,
                        const uint64_t* seeds, const float* temperature, const int32_t* sample_pos,
                        hipStream_t st) {
   GemmArgs a = {};
-  a.x = x; a.ldx = ldx;
+  a.x = x.p; a.x_plane = x.plane; a.ldx = x.ld;
   a.w[0] = w_lm; a.w_rows[0] = V;
   a.N = V; a.K = K; a.T = T;
   int ksteps = (K + 15) / 16;
   a.ksteps_per_wave = (ksteps + GEMM_WAVES - 1) / GEMM_WAVES;
   a.logits = logits; a.part = part; a.seeds = seeds; a.temperature = temperature; a.sample_pos = sample_pos;
-  launch_mt<EPI_LMHEAD>(a, dim3((V + 31) / 32, 1), T > 32 ? 2 : 1, st);
+  launch_mt<EPI_LMHEAD>(a, dim3((V + 31) / 32, 1), T > 32 ? 2 : 1, x.planes, st);
   return hipGetLastError();
 }
 

@@ -17,24 +17,37 @@ inline LinearW linear1(const void* w, int N, int K) {
   return l;
 }
 
+// A bf16 activation matrix carried as the sum of `planes` (1 or 2) bf16 terms:
+// value[t][i] = sum_p  p[p*plane + t*ld + i].  Two terms keep 16 significand bits.
+struct Act {
+  const bf16_t* p;
+  size_t plane;
+  int ld;
+  int planes;
+};
+inline Act make_act(const bf16_t* p, int rows, int ld, int planes) {
+  Act a = {p, (size_t)rows * ld, ld, planes};
+  return a;
+}
+
 // ---- gemm.hip ----
 int gemm_max_splits();
 int gemm_plan_splits(int N, int K, int max_splits);
 // y[split][t][n] (fp32, leading dimension ldy); x_rows optionally gathers the rows of x
-hipError_t gemm_store(const LinearW& w, const bf16_t* x, int ldx, const int32_t* x_rows, int T, float* y, int ldy,
+hipError_t gemm_store(const LinearW& w, const Act& x, const int32_t* x_rows, int T, float* y, int ldy,
                       int splits, hipStream_t st);
 // act[t][f] = bf16( silu(x Wg^T) * (x Wu^T) )
-hipError_t gemm_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int F, int K, const bf16_t* x, int ldx, int T,
-                       bf16_t* act, int ldact, hipStream_t st);
+hipError_t gemm_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int F, int K, const Act& x, int T,
+                       const Act& act, hipStream_t st);
 int lmhead_tiles(int vocab);
 // LM head with fused per-tile log-sum-exp and Gumbel-max partials: part[t][tile][4]
-hipError_t gemm_lmhead(const bf16_t* w_lm, int V, int K, const bf16_t* x, int ldx, int T, float* logits, float* part,
+hipError_t gemm_lmhead(const bf16_t* w_lm, int V, int K, const Act& x, int T, float* logits, float* part,
                        const uint64_t* seeds, const float* temperature, const int32_t* sample_pos, hipStream_t st);
 // expert-grouped forms: rows [group_off[e], group_off[e+1]) belong to expert e = blockIdx.y
-hipError_t gemm_grouped_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int E, int F, int K, const bf16_t* x, int ldx,
-                               const int32_t* x_rows, const int32_t* group_off, int max_rows, bf16_t* act,
+hipError_t gemm_grouped_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int E, int F, int K, const Act& x,
+                               const int32_t* x_rows, const int32_t* group_off, int max_rows, const Act& act,
                                hipStream_t st);
-hipError_t gemm_grouped_store(const bf16_t* w, int E, int N, int K, const bf16_t* x, int ldx,
+hipError_t gemm_grouped_store(const bf16_t* w, int E, int N, int K, const Act& x,
                               const int32_t* group_off, int max_rows, float* y, hipStream_t st);
 
 // ---- elementwise.hip ----
@@ -71,7 +84,7 @@ struct NormArgs {
   const int32_t* pair_pos;
   const float* topk_w;
   int top_k;
-  bf16_t* x;                 // [T, d] normalised output (bf16)
+  Act x;                     // [planes][T, d] normalised output
   float* xf;                 // optional fp32 copy of the normalised output
 };
 hipError_t rmsnorm(const NormArgs& a, hipStream_t st);
@@ -88,7 +101,7 @@ struct RopeArgs {
   const int32_t* block_table; int max_blocks;
   bf16_t* pool_layer;        // this layer's pages
   int64_t n_blocks;
-  bf16_t* q_out;             // [T, Hq, hd]
+  Act q_out;                 // [planes][T, Hq*hd]
 };
 hipError_t qk_rope_append(const RopeArgs& a, hipStream_t st);
 // y[i] = sum_s planes[s][i], s ascending
@@ -99,7 +112,7 @@ hipError_t kv_copy_blocks(bf16_t* pool, int64_t n_blocks, int n_layers, size_t b
 // ---- attention.hip ----
 constexpr int ATTN_SPLIT_TOKENS = 256;   // keys per decode split
 struct AttnArgs {
-  const bf16_t* q;           // [T, Hq, hd]
+  Act q;                     // [planes][T, Hq*hd]
   const bf16_t* pool_layer;
   int64_t n_blocks;
   int Hq, Hkv, hd;
@@ -114,7 +127,7 @@ struct AttnArgs {
   const int32_t* cu_seqlens;
   const int32_t* qtile_seq; const int32_t* qtile_q0; const int32_t* n_qtiles;
   int max_qtiles;
-  bf16_t* o;                 // [T, Hq*hd]
+  Act o;                     // [planes][T, Hq*hd]
 };
 hipError_t attention_decode(const AttnArgs& a, hipStream_t st);   // partials + merge -> o
 hipError_t attention_prefill(const AttnArgs& a, hipStream_t st);
@@ -139,7 +152,7 @@ hipError_t moe_group(const int32_t* topk_idx, int T, int top_k, int E, int32_t* 
 struct FinalizeArgs {
   int n_rows, n_tiles, vocab, d;
   const float* part;          // [n_rows][n_tiles][4]
-  const bf16_t* x;            // [n_rows, d] final-normalised hidden (bf16)
+  Act x;                      // [planes][n_rows, d] final-normalised hidden
   const bf16_t* w_lm;         // [vocab, d]
   const float* temperature; const int32_t* max_ctx_len; const int32_t* forced;
   const int32_t* sample_pos; const uint8_t* sample_on;

@@ -61,9 +61,13 @@ __global__ __launch_bounds__(256) void sample_finalize_kernel(FinalizeArgs a) {
 
   // logit of the emitted token: the same bf16 operands as the LM-head tiles, fp32 accumulate
   const bf16_t* w = a.w_lm + (size_t)tok * a.d;
-  const bf16_t* x = a.x + (size_t)r * a.d;
+  const bf16_t* x = a.x.p + (size_t)r * a.x.ld;
   float acc = 0.f;
-  for (int k = threadIdx.x; k < a.d; k += 256) acc += bf16_to_f32(x[k]) * bf16_to_f32(w[k]);
+  for (int k = threadIdx.x; k < a.d; k += 256) {
+    float xv = bf16_to_f32(x[k]);
+    if (a.x.planes == 2) xv += bf16_to_f32(x[a.x.plane + k]);
+    acc += xv * bf16_to_f32(w[k]);
+  }
   acc = wave_sum(acc);
   if ((threadIdx.x & 63) == 0) dsh[threadIdx.x >> 6] = acc;
   __syncthreads();

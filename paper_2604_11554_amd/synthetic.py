@@ -6,14 +6,16 @@ import rollout_inputs as RI
 from .engine import RolloutModel
 
 
-def config_from_shape(s: RI.ModelShape) -> dict:
-    return dict(n_layers=s.n_layers, d_model=s.d_model, n_q_heads=s.n_q_heads, n_kv_heads=s.n_kv_heads,
+def config_from_shape(s: RI.ModelShape, activation_split: int = 1) -> dict:
+    return dict(activation_split=activation_split, n_layers=s.n_layers, d_model=s.d_model, n_q_heads=s.n_q_heads, n_kv_heads=s.n_kv_heads,
                 head_dim=s.head_dim, d_ff=s.d_ff, n_experts=s.n_experts, top_k=s.top_k,
                 d_ff_expert=s.d_ff_expert, vocab=s.vocab, kv_block_size=s.kv_block_size, rms_eps=s.rms_eps,
                 rope_theta=s.rope_theta, qk_norm=int(s.qk_norm), eos_token_id=s.eos_token_id,
                 pad_token_id=s.pad_token_id)
 
 
-def model_from_shape(s: RI.ModelShape, model_seed: int = 0, device="cuda:0", progress=None) -> RolloutModel:
+def model_from_shape(s: RI.ModelShape, model_seed: int = 0, device="cuda:0", progress=None,
+                     activation_split: int = 1) -> RolloutModel:
     """Upload the keyed synthetic weights of `s` (same bf16 bit patterns the oracle upcasts)."""
-    return RolloutModel(config_from_shape(s), lambda l, n: RI.tensor_bf16(s, model_seed, l, n), device, progress)
+    return RolloutModel(config_from_shape(s, activation_split), lambda l, n: RI.tensor_bf16(s, model_seed, l, n),
+                        device, progress)

@@ -144,17 +144,19 @@ def test_moe_ffn_grouped_equals_bruteforce_and_dense_special_case():
     e, d, f, k, n = 16, 12, 10, 4, 9
     wr, wg, wu, wd = _experts(e, d, f)
     x = RNG.standard_normal((n, d))
-    y, idx, gap = O.moe_ffn(x, wr, wg, wu, wd, k)
-    yb, idxb, gapb = O.moe_ffn_bruteforce(x, wr, wg, wu, wd, k)
+    y, idx, gap, own = O.moe_ffn(x, wr, wg, wu, wd, k)
+    yb, idxb, gapb, ownb = O.moe_ffn_bruteforce(x, wr, wg, wu, wd, k)
+    np.testing.assert_array_equal(own, idx)
+    np.testing.assert_array_equal(ownb, idx)
     np.testing.assert_array_equal(idx, idxb)
     np.testing.assert_allclose(y, yb, rtol=1e-10, atol=1e-12)
     np.testing.assert_allclose(gap, gapb)
     # identical experts: mixture weights sum to one, so the layer equals one dense FFN
     wg1, wu1, wd1 = (np.repeat(a[:1], e, axis=0) for a in (wg, wu, wd))
-    y1, _, _ = O.moe_ffn(x, wr, wg1, wu1, wd1, k)
+    y1 = O.moe_ffn(x, wr, wg1, wu1, wd1, k)[0]
     np.testing.assert_allclose(y1, O.swiglu_ffn(x, wg[0], wu[0], wd[0]), rtol=1e-9, atol=1e-12)
     # K = E: the full softmax mixture
-    yf, _, _ = O.moe_ffn(x, wr, wg, wu, wd, e)
+    yf = O.moe_ffn(x, wr, wg, wu, wd, e)[0]
     p = scipy.special.softmax(x @ wr.T, axis=-1)
     want = sum(p[:, j:j + 1] * O.swiglu_ffn(x, wg[j], wu[j], wd[j]) for j in range(e))
     np.testing.assert_allclose(yf, want, rtol=1e-9, atol=1e-12)
@@ -164,13 +166,14 @@ def test_moe_replay():
     e, d, f, k, n = 16, 12, 10, 4, 6
     wr, wg, wu, wd = _experts(e, d, f)
     x = RNG.standard_normal((n, d))
-    y, idx, _ = O.moe_ffn(x, wr, wg, wu, wd, k)
-    y2, idx2, _ = O.moe_ffn(x, wr, wg, wu, wd, k, forced_idx=idx)       # own indices: idempotent
+    y, idx, _, _ = O.moe_ffn(x, wr, wg, wu, wd, k)
+    y2, idx2, _, _ = O.moe_ffn(x, wr, wg, wu, wd, k, forced_idx=idx)       # own indices: idempotent
     np.testing.assert_array_equal(idx, idx2)
     np.testing.assert_allclose(y, y2, rtol=1e-12)
     other = (idx + 1) % e
-    y3, idx3, _ = O.moe_ffn(x, wr, wg, wu, wd, k, forced_idx=other)
+    y3, idx3, _, own3 = O.moe_ffn(x, wr, wg, wu, wd, k, forced_idx=other)
     np.testing.assert_array_equal(idx3, other)
+    np.testing.assert_array_equal(own3, idx)                  # the router's own choice is still reported
     assert np.abs(y3 - y).max() > 1e-3
     # replay weights: own probabilities renormalised over the forced set
     p = scipy.special.softmax(x[0] @ wr.T)
