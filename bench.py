@@ -1,0 +1,293 @@
+#!/usr/bin/env python3
+"""Rollout-decode benchmark on one MI355X.
+
+A "step" is one rollout_decode_step over the whole batch (all layers, LM head,
+sampling, state update).  Workloads (synthetic, seeded):
+  dense_b64  Qwen3-4B-shaped dense policy, 64 sequences, prompts uniform 256..1024,
+             1024 decoded tokens each (default)
+  moe_b128   Qwen3-30B-A3B-shaped MoE policy, 128 sequences, 512-token prompts,
+             2048 decoded tokens, routing indices captured
+Prints ONE JSON line: decode tokens/s, ms/step, the roofline record of the dominant
+kernel (timed in situ with HIP events) and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def gpu_random_model(pkg, synthetic, shape, split, seed=0):
+    """Random-init weights of the named shape generated on the device (same distributions as
+    rollout_inputs: matrices N(0, 0.02), gains 1 + N(0, 0.02), router N(0, 1/d))."""
+    import torch
+    import rollout_inputs as RI
+    gen = torch.Generator(device="cuda:0")
+
+    def tensor(layer, name):
+        dims, kind = RI.tensor_names(shape, layer)[name]
+        gen.manual_seed((seed * 1000003 + (layer + 1) * 101 + sum(map(ord, name))) & 0x7FFFFFFF)
+        t = torch.randn(dims, generator=gen, device="cuda:0", dtype=torch.float32)
+        if kind == "matrix":
+            t.mul_(0.02)
+        elif kind == "gain":
+            t.mul_(0.02).add_(1.0)
+        else:
+            t.mul_(1.0 / np.sqrt(shape.d_model))
+        return t.to(torch.bfloat16)
+
+    return pkg.RolloutModel(synthetic.config_from_shape(shape, split), tensor)
+
+
+def kernel_bytes(shape, cls, ctx_sum_plus_b, touched=None):
+    """Algorithmic HBM bytes of one launch of a kernel class (bf16 operands read once)."""
+    s = shape
+    if cls == "attn":
+        return ctx_sum_plus_b * s.n_kv_heads * s.head_dim * 2 * 2
+    if cls == "qkv":
+        return (s.q_dim + 2 * s.kv_dim) * s.d_model * 2
+    if cls == "oproj":
+        return s.d_model * s.q_dim * 2
+    if cls == "gateup":
+        return 2 * s.d_ff * s.d_model * 2 if not s.is_moe else 2 * s.d_ff_expert * s.d_model * 2 * touched
+    if cls == "down":
+        return s.d_ff * s.d_model * 2 if not s.is_moe else s.d_ff_expert * s.d_model * 2 * touched
+    if cls == "lmhead":
+        return s.vocab * s.d_model * 2
+    raise KeyError(cls)
+
+
+def step_bytes(shape, ctx_sum_plus_b, batch, touched=None):
+    """Algorithmic bytes of one decode step: weights streamed once + KV read once + KV appended."""
+    s = shape
+    w = sum(kernel_bytes(s, c, 0, touched) for c in ("qkv", "oproj", "gateup", "down")) * s.n_layers
+    if s.is_moe:
+        w += s.n_experts * s.d_model * 2 * s.n_layers
+    w += kernel_bytes(s, "lmhead", 0)
+    kv_tok = s.n_layers * s.n_kv_heads * s.head_dim * 2 * 2
+    return w + kv_tok * ctx_sum_plus_b + kv_tok * batch
+
+
+def cpu_baseline(shape, wl, budget_s=25.0):
+    """The oracle's decode step timed on the host: 1- and 3-layer slices of the same shape with the
+    full batch and start-of-decode context lengths (synthetic KV contents), scaled to all layers."""
+    import oracle as O
+    import rollout_inputs as RI
+    cores = len(os.sched_getaffinity(0))
+    nl = 3
+    sub = shape.replace(n_layers=nl)
+    log("cpu baseline: generating %d-layer slice of %s" % (nl, shape.name))
+    tensors = {}
+    for l in [RI.GLOBAL_LAYER] + list(range(nl)):
+        for n in RI.tensor_names(sub, l):
+            tensors[(l, n)] = RI.tensor_bf16(sub, 0, l, n)
+    rng = np.random.default_rng(0)
+    times = {}
+    bs = min(wl.batch, 16)          # bounded sample: the first 16 sequences of the batch
+    for k in (1, nl):
+        shp = shape.replace(n_layers=k)
+        model = O.OracleModel(shp, 0, tensors={key: v for key, v in tensors.items() if key[0] < k})
+        model.globals
+        for l in range(k):
+            model.layer(l)
+        nb = int(sum((int(n) + 32) // 16 + 1 for n in wl.prompt_lens[:bs]))
+        ro = O.OracleRollout(model, n_blocks=nb)
+        for i in range(bs):
+            j = ro.add_sequence(int(wl.seeds[i]))
+            n = int(wl.prompt_lens[i])
+            ro._slots(j, 0, n + 8)
+            ro.ctx[j] = n
+            ro.last_token[j] = int(wl.prompt_tokens[i][-1])
+        ro.kpool[:] = rng.standard_normal(ro.kpool.shape, dtype=np.float32)
+        ro.vpool[:] = rng.standard_normal(ro.vpool.shape, dtype=np.float32)
+        ids = list(range(bs))
+        ro.decode_step(ids)                      # warm the BLAS threads
+        t0 = time.perf_counter()
+        n_steps = 0
+        while n_steps < 2 or (time.perf_counter() - t0 < budget_s / 4 and n_steps < 8):
+            ro.decode_step(ids)
+            n_steps += 1
+        times[k] = (time.perf_counter() - t0) / n_steps
+    per_layer = (times[nl] - times[1]) / (nl - 1)
+    full = times[1] + per_layer * (shape.n_layers - 1)
+    return {"value": bs / full, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": "%d of %d sequences, start-of-decode contexts, synthetic KV contents; 1- and %d-layer "
+                      "slices + LM head timed and scaled to %d layers (%.2f s/step)" % (
+                          bs, wl.batch, nl, shape.n_layers, full)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="decode steps to time (0 = the whole decode phase)")
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="dense_b64", choices=["dense_b64", "moe_b128"])
+    ap.add_argument("--split", type=int, default=-1, help="activation_split (default: 0 dense, 1 MoE)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel", default="auto", help="kernel class for the roofline record")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2604_11554_amd as pkg
+    import rollout_inputs as RI
+    from paper_2604_11554_amd import binding as B
+    from paper_2604_11554_amd import synthetic
+
+    B.lib()
+    dev = "cuda:0"
+    if args.workload == "dense_b64":
+        shape, wl = RI.QWEN3_4B, RI.workload_dense_batch()
+    else:
+        shape, wl = RI.QWEN3_30B_A3B, RI.workload_moe_batch()
+    split = args.split if args.split >= 0 else (1 if shape.is_moe else 0)
+    n_decode = int(wl.n_decode[0])
+    bsz = wl.batch
+    plen = wl.prompt_lens
+    log("workload %s: %s, batch %d, prompts %d..%d, decode %d, activation_split %d" % (
+        args.workload, shape.name, bsz, plen.min(), plen.max(), n_decode, split))
+
+    t0 = time.perf_counter()
+    model = gpu_random_model(pkg, synthetic, shape, split)
+    torch.cuda.synchronize()
+    log("weights on device: %.2f GB in %.1f s" % (model.weight_bytes() / 1e9, time.perf_counter() - t0))
+
+    max_blocks = (int(plen.max()) + n_decode + 15) // 16 + 1
+    n_blocks = int(sum((int(n) + n_decode + 15) // 16 for n in plen)) + 8
+    chunk_budget = 8192
+    eng = pkg.RolloutEngine(model, n_blocks=n_blocks, max_seqs=bsz, max_chunk_tokens=chunk_budget,
+                            max_blocks_per_seq=max_blocks)
+    for i in range(bsz):
+        eng.add_sequence(int(wl.seeds[i]), float(wl.temperature[i]), max_ctx=int(plen[i]) + n_decode)
+
+    # ---- prefill (untimed for the metric; reported) ----
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    i = 0
+    while i < bsz:
+        j, tot = i, 0
+        while j < bsz and tot + int(plen[j]) <= chunk_budget:
+            tot += int(plen[j])
+            j += 1
+        eng.prefill(list(range(i, j)), wl.prompt_tokens[i:j])
+        i = j
+    torch.cuda.synchronize()
+    t_prefill = time.perf_counter() - t0
+    log("prefill: %d tokens in %.2f s (%.0f tok/s)" % (plen.sum(), t_prefill, plen.sum() / t_prefill))
+
+    total_steps = n_decode - 1
+    K = args.steps if args.steps > 0 else total_steps - 0
+    K = min(K, total_steps)
+    W = args.warmup
+    lp_buf = torch.zeros((K + W + 64, bsz), dtype=torch.float32, device=dev)
+    routing = (torch.zeros((bsz, shape.n_layers, shape.top_k), dtype=torch.int32, device=dev)
+               if shape.is_moe else None)
+
+    def save():
+        return [t.clone() for t in (eng.tokens, eng.ctx_lens, eng.finished)]
+
+    def restore(st):
+        for t, s in zip((eng.tokens, eng.ctx_lens, eng.finished), st):
+            t.copy_(s)
+
+    # ---- warmup on a saved state (the KV written here is overwritten by the timed steps) ----
+    st = save()
+    for s in range(W):
+        eng.decode_step(out_logprobs=lp_buf[s], out_routing=routing)
+    torch.cuda.synchronize()
+
+    # ---- pick the dominant kernel class: time each class over two steps ----
+    classes = ["qkv", "attn", "oproj", "gateup", "down", "lmhead", "norm", "rope", "attn_merge"]
+    if shape.is_moe:
+        classes += ["router", "group"]
+    per_class = {}
+    for cls in classes:
+        kt = B.KernelTimer(cls, 4 * shape.n_layers, 1)
+        for s in range(2):
+            eng.decode_step(out_logprobs=lp_buf[s], out_routing=routing)
+        d = kt.finish()
+        per_class[cls] = float(np.sum(d)) / 2.0
+    restore(st)
+    dom = args.kernel if args.kernel != "auto" else max(per_class, key=per_class.get)
+    log("per-step kernel time by class (ms): " + ", ".join("%s %.3f" % kv for kv in sorted(
+        per_class.items(), key=lambda kv: -kv[1])) + " -> roofline kernel: " + dom)
+
+    # ---- timed region ----
+    stride = 16                                  # every 16th launch of the dominant class is bracketed
+    launches_per_step = 1 if dom == "lmhead" else shape.n_layers
+    n_ev = K * launches_per_step // stride + 1
+    kt = B.KernelTimer(dom, n_ev, stride)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for s in range(K):
+        eng.decode_step(out_logprobs=lp_buf[s], out_routing=routing)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    durs = kt.finish()
+    ms_total = ev0.elapsed_time(ev1)
+    ms_step = ms_total / K
+    toks_per_s = bsz * K / (ms_total / 1e3)
+
+    # ---- byte model ----
+    touched = None
+    if shape.is_moe:
+        e = shape.n_experts
+        touched = e * (1.0 - (1.0 - shape.top_k / e) ** bsz)   # expected distinct experts per layer
+    ctx0 = plen.astype(np.int64)
+    # launch i of the sampled class happened at step (i * stride) // launches_per_step
+    ach_bytes = []
+    for i in range(len(durs)):
+        step = (i * stride) // launches_per_step
+        ach_bytes.append(kernel_bytes(shape, dom, int((ctx0 + step + 1).sum()), touched)
+                         if dom in ("attn", "qkv", "oproj", "gateup", "down", "lmhead") else 0)
+    kern_ms = float(np.mean(durs)) if durs else float("nan")
+    achieved = float(np.sum(ach_bytes)) / (float(np.sum(durs)) * 1e-3) / 1e9 if durs else float("nan")
+    step_b = np.mean([step_bytes(shape, int((ctx0 + s + 1).sum()), bsz, touched) for s in range(K)])
+    step_gbs = step_b / (ms_step * 1e-3) / 1e9
+    fin = int(eng.finished[:bsz].sum().item())
+    log("decode: %d steps, %.3f ms/step, %.0f tok/s; step bytes %.2f GB -> %.0f GB/s (%.1f%% of 8 TB/s); "
+        "host wall %.2f s; finished rows %d" % (K, ms_step, toks_per_s, step_b / 1e9, step_gbs,
+                                                 100 * step_gbs / HBM_PEAK_GBS, wall, fin))
+
+    rec = {
+        "metric": "rollout decode tokens/sec on 1 MI355X; % of HBM roofline per step",
+        "value": toks_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %s, batch %d, prompts uniform %d..%d, %d decoded tokens, paged bf16 KV block 16, "
+                               "temperature 1 Gumbel-max" % (args.workload, shape.name, bsz, plen.min(), plen.max(),
+                                                              n_decode),
+                   "activation_split": split, "prefill_tokens_per_s": float(plen.sum() / t_prefill)},
+        "step_roofline": {"bound": "hbm", "achieved": step_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                          "frac": step_gbs / HBM_PEAK_GBS, "bytes_per_step": float(step_b)},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "avg_launch_ms": kern_ms,
+                     "launches_timed": len(durs), "per_step_ms_by_class": per_class},
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(shape, wl)
+    print(json.dumps(rec), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -14,7 +14,10 @@
  *
  * Conventions
  *  - Every array argument is a DEVICE pointer unless its comment says HOST.
- *  - All matrices are bf16, row-major [out_features, in_features] (y = x W^T).
+ *  - All matrices are bf16 with logical shape [out_features, in_features] (y = x W^T).
+ *    The projection matrices and the LM head are passed in the library's packed
+ *    streaming layout, produced from row-major storage by rlx_pack_weight; the
+ *    embedding table, the norm gains and the MoE router stay row-major.
  *  - The caller owns every buffer (weights, KV pool, workspace, inputs, outputs);
  *    weights must outlive the model handle.  The library allocates device memory
  *    only in rlx_model_create (a few KB of pointer tables) and frees it in
@@ -66,15 +69,17 @@ typedef struct {
 
 /*
  * Weights.  Scalars point at device tensors; the per-layer members are HOST arrays
- * of n_layers device pointers (copied at create).  Shapes (bf16):
- *   embed, lm_head [vocab, d_model]; final_norm [d_model]
+ * of n_layers device pointers (copied at create).  Logical shapes (bf16); (P) marks
+ * the tensors that must be in the packed layout (each expert matrix packed on its
+ * own, experts stored back to back):
+ *   embed [vocab, d_model]; lm_head (P) [vocab, d_model]; final_norm [d_model]
  *   attn_norm, ffn_norm [d_model]; q_norm, k_norm [head_dim] (NULL arrays if !qk_norm)
- *   wq [n_q_heads*head_dim, d_model]; wk, wv [n_kv_heads*head_dim, d_model]
- *   wo [d_model, n_q_heads*head_dim]
- *   dense: w_gate, w_up [d_ff, d_model]; w_down [d_model, d_ff]; w_router NULL
- *   MoE:   w_router [n_experts, d_model]; w_gate, w_up [n_experts, d_ff_expert, d_model];
- *          w_down [n_experts, d_model, d_ff_expert]
- * All pointers must be 16-byte aligned.
+ *   wq (P) [n_q_heads*head_dim, d_model]; wk, wv (P) [n_kv_heads*head_dim, d_model]
+ *   wo (P) [d_model, n_q_heads*head_dim]
+ *   dense: w_gate, w_up (P) [d_ff, d_model]; w_down (P) [d_model, d_ff]; w_router NULL
+ *   MoE:   w_router [n_experts, d_model]; w_gate, w_up (P) [n_experts, d_ff_expert, d_model];
+ *          w_down (P) [n_experts, d_model, d_ff_expert]
+ * d_model, d_ff and d_ff_expert must be multiples of 16.  All pointers must be 16-byte aligned.
  */
 typedef struct {
   uint32_t struct_size; /* = sizeof(rlx_weights) */
@@ -94,6 +99,19 @@ typedef struct {
   const void* const* w_down;
   const void* const* w_router;
 } rlx_weights;
+
+/*
+ * Packed streaming layout of a [n, k] matrix (k a multiple of 16): rows are padded
+ * to a multiple of 32 with zeros and stored as (n/32) x (k/16) blocks of 1 KB, block
+ * (i, j) holding rows 32i..32i+31, columns 16j..16j+15 in the operand order of the
+ * 32x32x16 bf16 MFMA (16-byte group g of a block = row 32i + g mod 32, columns
+ * 16j + 8 (g div 32) .. +7), so that a wavefront streams a row tile as one contiguous
+ * run.  rlx_pack_weight converts `count` row-major matrices stored back to back
+ * (src, device) into `count` packed matrices stored back to back (dst, device, of
+ * rlx_packed_weight_bytes(n, k) each).  src and dst must not overlap.
+ */
+RLX_API int rlx_packed_weight_bytes(int32_t n, int32_t k, size_t* bytes_out);
+RLX_API int rlx_pack_weight(const void* src, void* dst, int32_t count, int32_t n, int32_t k, void* stream);
 
 /* Create / destroy a model handle on the current HIP device. */
 RLX_API int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* w, rlx_model** out);
@@ -183,11 +201,37 @@ RLX_API int rollout_decode_step(const rlx_model* m, void* kv_pool, int64_t n_blo
 
 /*
  * Single operators, exported for per-kernel parity tests and profiling.
- *   rlx_op_linear: y[t, n] = sum_k x[t, k] W[n, k]; x bf16 [n_tokens, k], W bf16 [n, k],
- *   y float [n_tokens, n]; runs the same weight-streaming kernel the decode step uses.
+ *   rlx_op_linear: y[t, n] = sum_k x[t, k] W[n, k]; x bf16 [n_tokens, k] row-major, W bf16
+ *   [n, k] PACKED, y float [n_tokens, n]; runs the same weight-streaming kernel the decode
+ *   step uses.  workspace: at least 2*32*ceil(n_tokens/32)*k + 8*4*n_tokens*n + 512 bytes.
  */
 RLX_API int rlx_op_linear(const void* x, const void* w, float* y, int32_t n_tokens, int32_t n, int32_t k,
                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Timing aid for benchmarks.  Kernel classes of one layer of a step: */
+#define RLX_K_NORM 1        /* residual add + RMSNorm                         */
+#define RLX_K_QKV 2         /* q|k|v projection                               */
+#define RLX_K_ROPE 3        /* q/k norm + rotary embedding + KV append        */
+#define RLX_K_ATTN 4        /* paged attention (decode: per-split partials)   */
+#define RLX_K_ATTN_MERGE 5  /* decode: merge of the splits                    */
+#define RLX_K_OPROJ 6       /* output projection                              */
+#define RLX_K_GATEUP 7      /* gate/up projection + SwiGLU (dense or grouped) */
+#define RLX_K_DOWN 8        /* down projection (dense or grouped)             */
+#define RLX_K_ROUTER 9      /* MoE router + top-k + capture                   */
+#define RLX_K_GROUP 10      /* MoE grouping of (token, slot) pairs by expert  */
+#define RLX_K_LMHEAD 11     /* LM head + log-sum-exp / Gumbel-max partials    */
+/*
+ * From now on every stride-th launch of `kernel_class` is bracketed with
+ * hipEventRecord(start_events[i]) / hipEventRecord(stop_events[i]) on the call's
+ * stream, i = 0, 1, ... until n_events pairs are used.  The arrays are HOST arrays
+ * of caller-created hipEvent_t (timing enabled) that must stay alive until the
+ * facility is switched off.  kernel_class == 0 switches it off and returns the
+ * number of pairs recorded.  Process-wide state, not thread-safe; a debugging and
+ * measurement facility only.
+ */
+RLX_API int rlx_profile_kernel(int32_t kernel_class, void* const* start_events, void* const* stop_events,
+                               int32_t n_events, int32_t stride);
 
 /* Thread-local text of the last error on this thread ("" if none). */
 RLX_API const char* rlx_last_error(void);

@@ -18,9 +18,12 @@ LIB_PATH = os.path.join(_HERE, "librelax_rollout.so")
 
 RLX_OK, RLX_EINVAL, RLX_ENOMEM, RLX_EHIP, RLX_EUNSUPPORTED = 0, -1, -2, -3, -4
 
-EXPORTS = ["rlx_model_create", "rlx_model_destroy", "rlx_kv_pool_bytes", "rlx_workspace_bytes",
+EXPORTS = ["rlx_packed_weight_bytes", "rlx_pack_weight", "rlx_model_create", "rlx_model_destroy", "rlx_kv_pool_bytes", "rlx_workspace_bytes",
            "rlx_kv_copy_blocks", "rollout_prefill_chunk", "rollout_decode_step", "rlx_op_linear",
-           "rlx_last_error"]
+           "rlx_profile_kernel", "rlx_last_error"]
+
+KERNEL_CLASSES = dict(norm=1, qkv=2, rope=3, attn=4, attn_merge=5, oproj=6, gateup=7, down=8, router=9, group=10,
+                      lmhead=11)
 
 
 class RlxError(RuntimeError):
@@ -63,6 +66,8 @@ def lib() -> C.CDLL:
         vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
         l.rlx_last_error.restype = C.c_char_p
         l.rlx_last_error.argtypes = []
+        l.rlx_packed_weight_bytes.argtypes = [i32, i32, C.POINTER(sz)]
+        l.rlx_pack_weight.argtypes = [vp, vp, i32, i32, i32, vp]
         l.rlx_model_create.argtypes = [C.POINTER(ModelConfig), C.POINTER(Weights), C.POINTER(vp)]
         l.rlx_model_destroy.argtypes = [vp]
         l.rlx_kv_pool_bytes.argtypes = [vp, i64, C.POINTER(sz)]
@@ -71,6 +76,7 @@ def lib() -> C.CDLL:
         l.rollout_prefill_chunk.argtypes = [vp, vp, i64, vp, sz, i32, i32] + [vp] * 5 + [i32] + [vp] * 12
         l.rollout_decode_step.argtypes = [vp, vp, i64, vp, sz, i32, vp, vp, vp, i32] + [vp] * 10
         l.rlx_op_linear.argtypes = [vp, vp, vp, i32, i32, i32, vp, sz, vp]
+        l.rlx_profile_kernel.argtypes = [i32, vp, vp, i32, i32]
         for n in EXPORTS:
             if n != "rlx_last_error":
                 getattr(l, n).restype = C.c_int
@@ -100,6 +106,26 @@ def _stream(stream) -> int:
 
 def rlx_last_error() -> str:
     return lib().rlx_last_error().decode("utf-8", "replace")
+
+
+def rlx_packed_weight_bytes(n: int, k: int) -> int:
+    out = C.c_size_t()
+    _check(lib().rlx_packed_weight_bytes(n, k, C.byref(out)))
+    return out.value
+
+
+def rlx_pack_weight(src: torch.Tensor, dst: torch.Tensor, count: int, n: int, k: int, stream=None) -> None:
+    _check(lib().rlx_pack_weight(_ptr(src, torch.bfloat16), _ptr(dst, torch.bfloat16), count, n, k, _stream(stream)))
+
+
+def pack_matrix(w: torch.Tensor) -> torch.Tensor:
+    """Row-major bf16 [.., n, k] (leading dims = stacked matrices) -> packed streaming layout."""
+    n, k = w.shape[-2], w.shape[-1]
+    count = int(w.numel() // (n * k))
+    per = rlx_packed_weight_bytes(n, k) // 2
+    dst = torch.empty(count * per, dtype=torch.bfloat16, device=w.device)
+    rlx_pack_weight(w.contiguous(), dst, count, n, k)
+    return dst
 
 
 def rlx_model_create(cfg: ModelConfig, weights: Weights) -> int:
@@ -157,11 +183,47 @@ def rollout_decode_step(model, kv_pool, n_blocks, workspace, n_seqs, tokens_inou
 
 
 def rlx_op_linear(x, w, y, workspace=None, stream=None) -> None:
+    """x [n_tokens, k] row-major, w PACKED [n, k] (from pack_matrix), y [n_tokens, n] float32."""
     n_tokens, k = x.shape
-    n = w.shape[0]
+    n = y.shape[1]
+    # the library cannot see buffer sizes: check them here so a wrong shape can never reach a kernel
+    if y.shape[0] != n_tokens or w.numel() * 2 != rlx_packed_weight_bytes(n, k):
+        raise ValueError("rlx_op_linear: y must be [n_tokens, n] and w the packed [n, k] matrix")
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    need = 2 * 32 * ((n_tokens + 31) // 32) * k + 8 * 4 * n_tokens * n + 512
+    if ws_bytes < need:
+        raise ValueError("rlx_op_linear: workspace of %d bytes needed" % need)
     _check(lib().rlx_op_linear(_ptr(x, torch.bfloat16), _ptr(w, torch.bfloat16), _ptr(y, torch.float32), n_tokens, n,
                                k, _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+class KernelTimer:
+    """Brackets every stride-th launch of one kernel class with HIP events (rlx_profile_kernel)."""
+
+    def __init__(self, kernel_class: str, n_events: int, stride: int = 1):
+        self.events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                       for _ in range(n_events)]
+        # an event gets its handle when first recorded; record once so that cuda_event is valid
+        for a, b in self.events:
+            a.record()
+            b.record()
+        torch.cuda.synchronize()
+        self._start = (C.c_void_p * n_events)(*[e[0].cuda_event for e in self.events])
+        self._stop = (C.c_void_p * n_events)(*[e[1].cuda_event for e in self.events])
+        rlx_profile_kernel(KERNEL_CLASSES[kernel_class], self._start, self._stop, n_events, stride)
+
+    def finish(self):
+        """Switch the facility off; returns the per-launch durations in milliseconds."""
+        n = rlx_profile_kernel(0, None, None, 0, 1)
+        torch.cuda.synchronize()
+        return [self.events[i][0].elapsed_time(self.events[i][1]) for i in range(n)]
+
+
+def rlx_profile_kernel(kernel_class: int, start_events, stop_events, n_events: int, stride: int) -> int:
+    rc = lib().rlx_profile_kernel(kernel_class, start_events, stop_events, n_events, stride)
+    if rc < 0:
+        _check(rc)
+    return rc
 
 
 def make_pointer_table(tensors: Sequence[Optional[torch.Tensor]]):

@@ -31,6 +31,24 @@ int fail(int code, const char* fmt, ...) {
     if (e_ != hipSuccess) return fail(RLX_EHIP, "%s: %s", #expr, hipGetErrorString(e_));     \
   } while (0)
 
+// Optional timing aid: launches of one kernel class are bracketed with caller-owned events.
+struct ProfState {
+  int cls = 0;
+  void* const* start = nullptr;
+  void* const* stop = nullptr;
+  int n = 0, used = 0, stride = 1, seen = 0;
+};
+ProfState g_prof;
+
+#define RLX_LAUNCH(cls_, expr)                                                               \
+  do {                                                                                       \
+    bool p_ = false;                                                                         \
+    if (g_prof.cls == (cls_) && g_prof.used < g_prof.n) p_ = (g_prof.seen++ % g_prof.stride) == 0; \
+    if (p_) RLX_HIP(hipEventRecord((hipEvent_t)g_prof.start[g_prof.used], st));              \
+    RLX_HIP(expr);                                                                           \
+    if (p_) RLX_HIP(hipEventRecord((hipEvent_t)g_prof.stop[g_prof.used++], st));             \
+  } while (0)
+
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -90,18 +108,18 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
   w.meta.qtile_q0 = (int32_t*)take((size_t)QT * 4);
   w.meta.n_qtiles = (int32_t*)take(4);
   w.h = (float*)take((size_t)T * c.d_model * 4);
-  const size_t PL = c.activation_split ? 2 : 1;
-  w.xb = (bf16_t*)take(PL * T * c.d_model * 2);
+  const int PL = c.activation_split ? 2 : 1;
+  w.xb = (bf16_t*)take(frag_act_elems(T, c.d_model, PL) * 2);
   w.xf = c.n_experts ? (float*)take((size_t)T * c.d_model * 4) : nullptr;
   w.qkv = (float*)take((size_t)plane_rows(T) * qkv_dim * 4);
-  w.q = (bf16_t*)take(PL * T * qdim * 2);
-  w.ob = (bf16_t*)take(PL * T * qdim * 2);
+  w.q = (bf16_t*)take((size_t)PL * T * qdim * 2);
+  w.ob = (bf16_t*)take(frag_act_elems(T, qdim, PL) * 2);
   const int n_splits = (max_blocks * 16 + ATTN_SPLIT_TOKENS - 1) / ATTN_SPLIT_TOKENS;
   w.attn_part = (float*)take((size_t)S * c.n_q_heads * n_splits * (c.head_dim + 2) * 4);
   w.planes = (float*)take((size_t)plane_rows(T) * c.d_model * 4);
   if (c.n_experts) {
     const size_t P = (size_t)T * c.top_k;
-    w.act = (bf16_t*)take(PL * P * c.d_ff_expert * 2);
+    w.act = (bf16_t*)take(frag_act_elems((int)P, c.d_ff_expert, PL) * 2);
     w.moe_y = (float*)take(P * c.d_model * 4);
     w.topk_idx = (int32_t*)take(P * 4);
     w.topk_w = (float*)take(P * 4);
@@ -110,9 +128,9 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
     w.sorted_token = (int32_t*)take(P * 4);
     w.pair_pos = (int32_t*)take(P * 4);
   } else {
-    w.act = (bf16_t*)take(PL * T * c.d_ff * 2);
+    w.act = (bf16_t*)take(frag_act_elems(T, c.d_ff, PL) * 2);
   }
-  w.x_lm = (bf16_t*)take(PL * S * c.d_model * 2);
+  w.x_lm = (bf16_t*)take(frag_act_elems(S, c.d_model, PL) * 2);
   w.lm_part = (float*)take((size_t)S * lmhead_tiles(c.vocab) * 4 * 4);
   w.bytes = off;
   return w;
@@ -139,7 +157,8 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
   const int qdim = c.n_q_heads * c.head_dim, kvdim = c.n_kv_heads * c.head_dim, qkv_dim = qdim + 2 * kvdim;
   const bool small = T <= 256;
   const int PL = c.activation_split ? 2 : 1;
-  const Act xb = make_act(w.xb, T, d, PL), qb = make_act(w.q, T, qdim, PL), ob = make_act(w.ob, T, qdim, PL);
+  const Act xb = make_act(w.xb, T, d, PL), ob = make_act(w.ob, T, qdim, PL);
+  const RowAct qb = {w.q, (size_t)T * qdim, qdim, PL};
 
   RLX_HIP(embed_tokens(m->embed, c.vocab, d, io.tokens, io.input_embeds, T, w.h, st));
 
@@ -156,14 +175,14 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
   };
 
   for (int l = 0; l < c.n_layers; ++l) {
-    RLX_HIP(norm(m->attn_norm[l], nullptr, T, xb, nullptr));
+    RLX_LAUNCH(RLX_K_NORM, norm(m->attn_norm[l], nullptr, T, xb, nullptr));
     LinearW wqkv = {};
     wqkv.seg[0] = m->wq[l]; wqkv.rows[0] = qdim;
     wqkv.seg[1] = m->wk[l]; wqkv.rows[1] = kvdim;
     wqkv.seg[2] = m->wv[l]; wqkv.rows[2] = kvdim;
     wqkv.N = qkv_dim; wqkv.K = d;
     const int s_qkv = small ? gemm_plan_splits(qkv_dim, d, gemm_max_splits()) : 1;
-    RLX_HIP(gemm_store(wqkv, xb, nullptr, T, w.qkv, qkv_dim, s_qkv, st));
+    RLX_LAUNCH(RLX_K_QKV, gemm_store(wqkv, xb, T, w.qkv, qkv_dim, s_qkv, st));
 
     RopeArgs r = {};
     r.qkv = w.qkv; r.n_planes = s_qkv;
@@ -172,7 +191,7 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
     r.eps = c.rms_eps; r.tok_seq = w.meta.tok_seq; r.tok_pos = w.meta.tok_pos; r.tok_live = w.meta.tok_live;
     r.block_table = io.block_table; r.max_blocks = io.max_blocks;
     r.pool_layer = pool + (size_t)l * n_blocks * block_elems(c); r.n_blocks = n_blocks; r.q_out = qb;
-    RLX_HIP(qk_rope_append(r, st));
+    RLX_LAUNCH(RLX_K_ROPE, qk_rope_append(r, st));
 
     AttnArgs at = {};
     at.q = qb; at.pool_layer = r.pool_layer; at.n_blocks = n_blocks;
@@ -182,30 +201,33 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
     at.n_splits = (io.max_blocks * 16 + ATTN_SPLIT_TOKENS - 1) / ATTN_SPLIT_TOKENS;
     at.cu_seqlens = io.cu_seqlens; at.qtile_seq = w.meta.qtile_seq; at.qtile_q0 = w.meta.qtile_q0;
     at.n_qtiles = w.meta.n_qtiles; at.max_qtiles = T / 16 + io.n_seqs + 1; at.o = ob;
-    RLX_HIP(io.decode ? attention_decode(at, st) : attention_prefill(at, st));
+    RLX_LAUNCH(RLX_K_ATTN, io.decode ? attention_decode(at, st) : attention_prefill(at, st));
+    if (io.decode) RLX_LAUNCH(RLX_K_ATTN_MERGE, attention_decode_merge(at, st));
 
     const int s_o = small ? gemm_plan_splits(d, qdim, gemm_max_splits()) : 1;
-    RLX_HIP(gemm_store(linear1(m->wo[l], d, qdim), ob, nullptr, T, w.planes, d, s_o, st));
+    RLX_LAUNCH(RLX_K_OPROJ, gemm_store(linear1(m->wo[l], d, qdim), ob, T, w.planes, d, s_o, st));
     pend_planes = w.planes; pend_n = s_o;
 
-    RLX_HIP(norm(m->ffn_norm[l], nullptr, T, xb, w.xf));
+    RLX_LAUNCH(RLX_K_NORM, norm(m->ffn_norm[l], nullptr, T, xb, w.xf));
     if (c.n_experts == 0) {
       const Act act = make_act(w.act, T, c.d_ff, PL);
-      RLX_HIP(gemm_swiglu(m->w_gate[l], m->w_up[l], c.d_ff, d, xb, T, act, st));
+      RLX_LAUNCH(RLX_K_GATEUP, gemm_swiglu(m->w_gate[l], m->w_up[l], c.d_ff, d, xb, T, act, st));
       const int s_d = small ? gemm_plan_splits(d, c.d_ff, gemm_max_splits()) : 1;
-      RLX_HIP(gemm_store(linear1(m->w_down[l], d, c.d_ff), act, nullptr, T, w.planes, d, s_d, st));
+      RLX_LAUNCH(RLX_K_DOWN, gemm_store(linear1(m->w_down[l], d, c.d_ff), act, T, w.planes, d, s_d, st));
       pend_planes = w.planes; pend_n = s_d;
     } else {
       RouterArgs ra = {};
       ra.xf = w.xf; ra.w_router = m->w_router[l]; ra.T = T; ra.d = d; ra.E = c.n_experts; ra.top_k = c.top_k;
       ra.topk_idx = w.topk_idx; ra.topk_w = w.topk_w; ra.routing_out = io.out_routing; ra.layer = l;
       ra.n_layers = c.n_layers; ra.tok_live = w.meta.tok_live;
-      RLX_HIP(moe_router(ra, st));
-      RLX_HIP(moe_group(w.topk_idx, T, c.top_k, c.n_experts, w.counts, w.group_off, w.sorted_token, w.pair_pos, st));
+      RLX_LAUNCH(RLX_K_ROUTER, moe_router(ra, st));
+      RLX_LAUNCH(RLX_K_GROUP, moe_group(w.topk_idx, T, c.top_k, c.n_experts, w.counts, w.group_off, w.sorted_token,
+                                        w.pair_pos, st));
       const Act act = make_act(w.act, T * c.top_k, c.d_ff_expert, PL);
-      RLX_HIP(gemm_grouped_swiglu(m->w_gate[l], m->w_up[l], c.n_experts, c.d_ff_expert, d, xb, w.sorted_token,
-                                  w.group_off, T, act, st));
-      RLX_HIP(gemm_grouped_store(m->w_down[l], c.n_experts, d, c.d_ff_expert, act, w.group_off, T, w.moe_y, st));
+      RLX_LAUNCH(RLX_K_GATEUP, gemm_grouped_swiglu(m->w_gate[l], m->w_up[l], c.n_experts, c.d_ff_expert, d, xb,
+                                                   w.sorted_token, w.group_off, T, act, st));
+      RLX_LAUNCH(RLX_K_DOWN, gemm_grouped_store(m->w_down[l], c.n_experts, d, c.d_ff_expert, act, w.group_off, T,
+                                                w.moe_y, st));
       pend_moe = true;
     }
   }
@@ -214,8 +236,8 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
   const int S = io.n_seqs;
   const Act x_lm = make_act(w.x_lm, S, d, PL);
   RLX_HIP(norm(m->final_norm, w.meta.sample_row, S, x_lm, nullptr));
-  RLX_HIP(gemm_lmhead(m->lm_head, c.vocab, d, x_lm, S, io.out_logits, w.lm_part, io.seeds, io.temperature,
-                      w.meta.sample_pos, st));
+  RLX_LAUNCH(RLX_K_LMHEAD, gemm_lmhead(m->lm_head, c.vocab, d, x_lm, S, io.out_logits, w.lm_part, io.seeds,
+                                       io.temperature, w.meta.sample_pos, st));
   FinalizeArgs f = {};
   f.n_rows = S; f.n_tiles = lmhead_tiles(c.vocab); f.vocab = c.vocab; f.d = d;
   f.part = w.lm_part; f.x = x_lm; f.w_lm = m->lm_head;
@@ -258,14 +280,14 @@ int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* wt, rlx_mod
   if (c.kv_block_size != 16) return fail(RLX_EUNSUPPORTED, "kv_block_size %d (must be 16)", c.kv_block_size);
   if (c.n_q_heads % c.n_kv_heads) return fail(RLX_EINVAL, "n_q_heads not a multiple of n_kv_heads");
   if (c.n_q_heads / c.n_kv_heads > 16) return fail(RLX_EUNSUPPORTED, "GQA group > 16");
-  if (c.d_model % 8) return fail(RLX_EUNSUPPORTED, "d_model must be a multiple of 8");
+  if (c.d_model % 16) return fail(RLX_EUNSUPPORTED, "d_model must be a multiple of 16");
   const bool moe = c.n_experts > 0;
   if (moe) {
     if (c.n_experts > 256 || c.top_k <= 0 || c.top_k > 8 || c.top_k > c.n_experts || c.d_ff_expert <= 0)
       return fail(RLX_EUNSUPPORTED, "MoE limits: n_experts <= 256, 1 <= top_k <= min(8, n_experts)");
-    if (c.d_ff_expert % 8 || c.d_ff) return fail(RLX_EINVAL, "MoE: d_ff_expert %% 8 == 0 and d_ff == 0 required");
+    if (c.d_ff_expert % 16 || c.d_ff) return fail(RLX_EINVAL, "MoE: d_ff_expert %% 16 == 0 and d_ff == 0 required");
   } else {
-    if (c.d_ff <= 0 || c.d_ff % 8) return fail(RLX_EINVAL, "dense: d_ff must be a positive multiple of 8");
+    if (c.d_ff <= 0 || c.d_ff % 16) return fail(RLX_EINVAL, "dense: d_ff must be a positive multiple of 16");
     if (c.top_k || c.d_ff_expert) return fail(RLX_EINVAL, "dense: top_k and d_ff_expert must be 0");
   }
   if (c.eos_token_id < 0 || c.eos_token_id >= c.vocab || c.pad_token_id < 0 || c.pad_token_id >= c.vocab)
@@ -408,23 +430,59 @@ int rollout_decode_step(const rlx_model* m, void* kv_pool, int64_t n_blocks, voi
   return run_layers(m, (bf16_t*)kv_pool, n_blocks, w, io, st);
 }
 
+int rlx_profile_kernel(int32_t kernel_class, void* const* start_events, void* const* stop_events, int32_t n_events,
+                       int32_t stride) {
+  if (kernel_class == 0 || n_events <= 0) {
+    int used = g_prof.used;
+    g_prof = ProfState();
+    return used;
+  }
+  if (!start_events || !stop_events || stride <= 0 || kernel_class < 0 || kernel_class > RLX_K_LMHEAD)
+    return fail(RLX_EINVAL, "rlx_profile_kernel: bad argument");
+  g_prof = ProfState();
+  g_prof.cls = kernel_class; g_prof.start = start_events; g_prof.stop = stop_events; g_prof.n = n_events;
+  g_prof.stride = stride;
+  return 0;
+}
+
+int rlx_packed_weight_bytes(int32_t n, int32_t k, size_t* bytes_out) {
+  if (!bytes_out || n <= 0 || k <= 0 || (k % 16)) return fail(RLX_EINVAL, "rlx_packed_weight_bytes: k %% 16 == 0 required");
+  *bytes_out = packed_weight_elems(n, k) * 2;
+  return RLX_OK;
+}
+
+int rlx_pack_weight(const void* src, void* dst, int32_t count, int32_t n, int32_t k, void* stream) {
+  if (!src || !dst || count <= 0 || n <= 0 || k <= 0 || (k % 16))
+    return fail(RLX_EINVAL, "rlx_pack_weight: bad argument (k %% 16 == 0 required)");
+  if (!aligned16(src) || !aligned16(dst)) return fail(RLX_EINVAL, "rlx_pack_weight: 16-byte alignment");
+  const size_t pe = packed_weight_elems(n, k);
+  for (int i = 0; i < count; ++i)
+    RLX_HIP(pack_weight((const bf16_t*)src + (size_t)i * n * k, (bf16_t*)dst + (size_t)i * pe, n, k,
+                        (hipStream_t)stream));
+  return RLX_OK;
+}
+
 int rlx_op_linear(const void* x, const void* w, float* y, int32_t n_tokens, int32_t n, int32_t k, void* workspace,
                   size_t workspace_bytes, void* stream) {
-  if (!x || !w || !y || n_tokens <= 0 || n <= 0 || k <= 0 || (k % 8) || (n % 4))
-    return fail(RLX_EINVAL, "rlx_op_linear: bad argument (k %% 8 == 0, n %% 4 == 0 required)");
-  if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return fail(RLX_EINVAL, "rlx_op_linear: 16-byte alignment");
+  if (!x || !w || !y || n_tokens <= 0 || n <= 0 || k <= 0 || (k % 16) || (n % 4))
+    return fail(RLX_EINVAL, "rlx_op_linear: bad argument (k %% 16 == 0, n %% 4 == 0 required)");
+  if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !workspace || !aligned16(workspace))
+    return fail(RLX_EINVAL, "rlx_op_linear: NULL workspace or 16-byte alignment");
   const int splits = n_tokens <= 256 ? gemm_plan_splits(n, k, gemm_max_splits()) : 1;
   hipStream_t st = (hipStream_t)stream;
-  const Act xa = make_act((const bf16_t*)x, n_tokens, k, 1);
+  const size_t xb = align_up(frag_act_elems(n_tokens, k, 1) * 2);
+  const size_t pb = splits > 1 ? align_up((size_t)splits * n_tokens * n * 4) : 0;
+  if (workspace_bytes < xb + pb) return fail(RLX_ENOMEM, "rlx_op_linear: workspace needs %zu bytes", xb + pb);
+  bf16_t* xp = (bf16_t*)workspace;
+  float* planes = (float*)((char*)workspace + xb);
+  RLX_HIP(pack_activation((const bf16_t*)x, xp, n_tokens, k, st));
+  const Act xa = make_act(xp, n_tokens, k, 1);
   if (splits == 1) {
-    RLX_HIP(gemm_store(linear1(w, n, k), xa, nullptr, n_tokens, y, n, 1, st));
+    RLX_HIP(gemm_store(linear1(w, n, k), xa, n_tokens, y, n, 1, st));
     return RLX_OK;
   }
-  const size_t need = (size_t)splits * n_tokens * n * 4;
-  if (!workspace || workspace_bytes < need)
-    return fail(RLX_ENOMEM, "rlx_op_linear: workspace needs %zu bytes", need);
-  RLX_HIP(gemm_store(linear1(w, n, k), xa, nullptr, n_tokens, (float*)workspace, n, splits, st));
-  RLX_HIP(sum_planes((const float*)workspace, splits, (size_t)n_tokens * n, y, st));
+  RLX_HIP(gemm_store(linear1(w, n, k), xa, n_tokens, planes, n, splits, st));
+  RLX_HIP(sum_planes(planes, splits, (size_t)n_tokens * n, y, st));
   return RLX_OK;
 }
 

@@ -244,18 +244,20 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
       if (g == 0) { dst[HD] = st.m[c]; dst[HD + 1] = st.l[c]; }
     } else {
       const float inv = st.l[c] > 0.f ? 1.f / st.l[c] : 0.f;
-      bf16_t* dst = const_cast<bf16_t*>(a.o.p) + ((size_t)trow[c] * a.Hq + head[c]) * HD;
+      const int mtiles = a.o.mtiles();
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
         f32x4 v = st.o[c][dt] * inv;
         bf16_t hi[4], lo[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) split_bf16(v[j], hi[j], lo[j]);
+        const int col = head[c] * HD + 16 * dt + 4 * g;   // feature index of the output projection's K
+        bf16_t* dst = a.o.p + frag_act_offset(trow[c], col & ~7, 0, mtiles, PL) + (col & 7);
         u32x2 p = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
-        *reinterpret_cast<u32x2*>(dst + 16 * dt + 4 * g) = p;
+        *reinterpret_cast<u32x2*>(dst) = p;
         if (PL == 2) {
           u32x2 p2 = {(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
-          *reinterpret_cast<u32x2*>(dst + a.o.plane + 16 * dt + 4 * g) = p2;
+          *reinterpret_cast<u32x2*>(dst + 512) = p2;
         }
       }
     }
@@ -267,10 +269,11 @@ template <int HD>
 __global__ void attn_merge_kernel(AttnArgs a) {
   const int seq = blockIdx.x, head = blockIdx.y;
   const int d = threadIdx.x;   // HD threads
-  bf16_t* dst = const_cast<bf16_t*>(a.o.p) + ((size_t)seq * a.Hq + head) * HD;
+  const int col = head * HD + d;
+  bf16_t* dst = a.o.p + frag_act_offset(seq, col & ~7, 0, a.o.mtiles(), a.o.planes) + (col & 7);
   if (!a.tok_live[seq]) {
-    dst[d] = 0;
-    if (a.o.planes == 2) dst[a.o.plane + d] = 0;
+    dst[0] = 0;
+    if (a.o.planes == 2) dst[512] = 0;
     return;
   }
   const int n_keys = a.ctx_lens[seq] + 1;
@@ -290,8 +293,8 @@ __global__ void attn_merge_kernel(AttnArgs a) {
   }
   bf16_t hi, lo;
   split_bf16(l > 0.f ? o / l : 0.f, hi, lo);
-  dst[d] = hi;
-  if (a.o.planes == 2) dst[a.o.plane + d] = lo;
+  dst[0] = hi;
+  if (a.o.planes == 2) dst[512] = lo;
 }
 
 }  // namespace
@@ -302,12 +305,16 @@ hipError_t attention_decode(const AttnArgs& a, hipStream_t st) {
   if (a.hd == 128) {
     if (two) hipLaunchKernelGGL((attn_kernel<128, 1, true, 2>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((attn_kernel<128, 1, true, 1>), grid, dim3(256), 0, st, a);
-    hipLaunchKernelGGL((attn_merge_kernel<128>), dim3(a.n_seqs, a.Hq), dim3(128), 0, st, a);
   } else {
     if (two) hipLaunchKernelGGL((attn_kernel<64, 1, true, 2>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((attn_kernel<64, 1, true, 1>), grid, dim3(256), 0, st, a);
-    hipLaunchKernelGGL((attn_merge_kernel<64>), dim3(a.n_seqs, a.Hq), dim3(64), 0, st, a);
   }
+  return hipGetLastError();
+}
+
+hipError_t attention_decode_merge(const AttnArgs& a, hipStream_t st) {
+  if (a.hd == 128) hipLaunchKernelGGL((attn_merge_kernel<128>), dim3(a.n_seqs, a.Hq), dim3(128), 0, st, a);
+  else hipLaunchKernelGGL((attn_merge_kernel<64>), dim3(a.n_seqs, a.Hq), dim3(64), 0, st, a);
   return hipGetLastError();
 }
 

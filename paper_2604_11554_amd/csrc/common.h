@@ -54,4 +54,29 @@ __device__ __forceinline__ bf16x8 zero_bf16x8() {
   return __builtin_bit_cast(bf16x8, v);
 }
 
+// ---------------------------------------------------------------------------------
+// Streaming layouts.  Both operands of the skinny GEMM are kept in the order the
+// 32x32x16 MFMA consumes them, so that every wave-wide 16-byte load reads one
+// contiguous 1 KB block:
+//   fragment = 64 lanes x 8 bf16; lane = (row mod 32) + 32 * ((k mod 16) / 8); element = k mod 8
+// Weights  [N, K]: fragment index (n / 32) * (K / 16) + k / 16           (rows padded to 32)
+// Activations [T, K] as `planes` bf16 terms: fragment index ((k / 16) * ceil(T / 32) + t / 32) * planes + p
+// K must be a multiple of 16.
+// ---------------------------------------------------------------------------------
+__host__ __device__ __forceinline__ size_t packed_weight_elems(int N, int K) {
+  return (size_t)((N + 31) / 32) * (size_t)(K / 16) * 512;
+}
+__host__ __device__ __forceinline__ size_t packed_weight_offset(int n, int k, int K) {
+  return (((size_t)(n >> 5) * (size_t)(K >> 4) + (size_t)(k >> 4)) * 64 + (size_t)((n & 31) + 32 * ((k >> 3) & 1))) * 8 +
+         (size_t)(k & 7);
+}
+__host__ __device__ __forceinline__ size_t frag_act_elems(int T, int K, int planes) {
+  return (size_t)(K / 16) * (size_t)((T + 31) / 32) * (size_t)planes * 512;
+}
+// offset of the 8-element group holding (t, k..k+7), k a multiple of 8, of plane p
+__host__ __device__ __forceinline__ size_t frag_act_offset(int t, int k, int p, int mtiles, int planes) {
+  return ((((size_t)(k >> 4) * (size_t)mtiles + (size_t)(t >> 5)) * (size_t)planes + (size_t)p) * 64 +
+          (size_t)((t & 31) + 32 * ((k >> 3) & 1))) * 8;
+}
+
 }  // namespace rlx

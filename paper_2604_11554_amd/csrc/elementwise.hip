@@ -110,13 +110,14 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(NormArgs a) {
   }
   float tot = block_sum_256(ss, sh);
   float rstd = 1.0f / sqrtf(tot / (float)a.d + a.eps);
+  const int mtiles = a.x.mtiles();
   for (int i = threadIdx.x; i < a.d; i += 256) {
     float v = hrow[i] * rstd * bf16_to_f32(a.gain[i]);   // own writes: visible to the same thread
     bf16_t hi, lo;
     split_bf16(v, hi, lo);
-    bf16_t* xo = const_cast<bf16_t*>(a.x.p) + (size_t)r * a.x.ld + i;
+    bf16_t* xo = a.x.p + frag_act_offset(r, i & ~7, 0, mtiles, a.x.planes) + (i & 7);
     xo[0] = hi;
-    if (a.x.planes == 2) xo[a.x.plane] = lo;
+    if (a.x.planes == 2) xo[512] = lo;
     if (a.xf) a.xf[(size_t)r * a.d + i] = v;
   }
 }
@@ -171,7 +172,7 @@ __global__ __launch_bounds__(256) void qk_rope_append_kernel(RopeArgs a) {
       float y0 = x0 * c - x1 * s, y1 = x1 * c + x0 * s;
       if (lane < half) {
         if (is_q) {
-          bf16_t* dst = const_cast<bf16_t*>(a.q_out.p) + ((size_t)t * a.Hq + h) * hd;
+          bf16_t* dst = a.q_out.p + ((size_t)t * a.Hq + h) * hd;
           bf16_t h0, l0, h1, l1;
           split_bf16(y0, h0, l0);
           split_bf16(y1, h1, l1);
@@ -192,6 +193,31 @@ __global__ __launch_bounds__(256) void qk_rope_append_kernel(RopeArgs a) {
       dst[(size_t)(lane + half) * 16 + slot] = f32_to_bf16(x1);
     }
   }
+}
+
+__global__ void pack_weight_kernel(const bf16_t* src, bf16_t* dst, int N, int K) {
+  // one thread per 8-element group of the packed layout
+  const size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t total = packed_weight_elems(N, K) / 8;
+  if (g >= total) return;
+  const int lane = (int)(g & 63);
+  const size_t frag = g >> 6;
+  const int KS = K >> 4;
+  const int ks = (int)(frag % KS);
+  const int nt = (int)(frag / KS);
+  const int n = nt * 32 + (lane & 31), k = ks * 16 + 8 * (lane >> 5);
+  u32x4 v = {0u, 0u, 0u, 0u};
+  if (n < N) v = *reinterpret_cast<const u32x4*>(src + (size_t)n * K + k);
+  *reinterpret_cast<u32x4*>(dst + g * 8) = v;
+}
+
+__global__ void pack_activation_kernel(const bf16_t* src, bf16_t* dst, int T, int K) {
+  const size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // (t, k/8) pairs
+  const int kg = K >> 3;
+  if (g >= (size_t)T * kg) return;
+  const int t = (int)(g / kg), k = (int)(g % kg) * 8;
+  u32x4 v = *reinterpret_cast<const u32x4*>(src + (size_t)t * K + k);
+  *reinterpret_cast<u32x4*>(dst + frag_act_offset(t, k, 0, (T + 31) / 32, 1)) = v;
 }
 
 __global__ void sum_planes_kernel(const float* planes, int n_planes, size_t n, float* y) {
@@ -242,6 +268,18 @@ hipError_t rmsnorm(const NormArgs& a, hipStream_t st) {
 
 hipError_t qk_rope_append(const RopeArgs& a, hipStream_t st) {
   hipLaunchKernelGGL(qk_rope_append_kernel, dim3(a.T), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t pack_weight(const bf16_t* src, bf16_t* dst, int N, int K, hipStream_t st) {
+  const size_t groups = packed_weight_elems(N, K) / 8;
+  hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, src, dst, N, K);
+  return hipGetLastError();
+}
+
+hipError_t pack_activation(const bf16_t* src, bf16_t* dst, int T, int K, hipStream_t st) {
+  const size_t groups = (size_t)T * (K / 8);
+  hipLaunchKernelGGL(pack_activation_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, src, dst, T, K);
   return hipGetLastError();
 }
 

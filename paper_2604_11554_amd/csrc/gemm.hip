@@ -1,13 +1,20 @@
-// Weight-streaming skinny GEMM for decode and chunked prefill (gfx950, MFMA bf16).
+// Weight-streaming skinny GEMM for decode and chunked prefill (gfx950, MFMA bf16 32x32x16).
 //
-//   y[t, n] = sum_k x[t, k] * W[n, k]      x bf16 [T, K], W bf16 [N, K] row-major, fp32 accumulate
+//   y[t, n] = sum_k x[t, k] * W[n, k]        fp32 accumulate
 //
-// Every weight byte is read exactly once per 32*MT tokens.  A workgroup owns a
-// 32-row tile of W (two tiles, gate and up, in the SwiGLU form); its waves split
-// the K range, each wave runs v_mfma_f32_32x32x16_bf16 with the weight rows as the
-// A operand and 32 tokens as the B operand, and the partial tiles are summed
-// through LDS in a fixed order (deterministic).  Optional split-K across
-// workgroups writes partial planes that the consumer adds in plane order.
+// Both operands are stored in MFMA fragment order (see common.h), so a wave streams its
+// 32 weight rows as one contiguous run of 1 KB blocks: eight full cache lines per load
+// instruction, nothing wasted, and the texture-address path is left free for the
+// activations.  Each of the four waves of a workgroup owns one 32-row tile of W over the
+// workgroup's K range and keeps two batches of weight fragments in flight in registers
+// (HBM latency under load is several microseconds, so the bytes in flight per CU decide
+// the achieved bandwidth).  The activations of the current K chunk are shared by the four
+// waves through LDS (double buffered); the next chunk is fetched while the current one is
+// multiplied.  No reduction across waves is needed.  Optional split-K across workgroups
+// writes partial planes that the consumer adds in plane order (deterministic).
+//
+// Epilogues: plain store (q|k|v, o and down projections, expert down projection),
+// SwiGLU (gate/up), LM head with fused log-sum-exp and Gumbel-max partials per 32-row tile.
 #include "kernels.h"
 
 namespace rlx {
@@ -18,39 +25,30 @@ constexpr int GEMM_WAVES = 4;
 constexpr int GEMM_THREADS = GEMM_WAVES * WAVE;
 
 struct GemmArgs {
-  const bf16_t* x;        // [planes][T, ldx]: activations as a sum of `planes` bf16 terms
-  size_t x_plane;         // elements between planes
-  const int32_t* x_rows;  // optional gather: logical token t reads row x_rows[t]
-  int ldx;
-  const bf16_t* w[3];     // up to three stacked row segments
-  int w_rows[3];          // rows per segment (multiples of 32 except the last)
-  const bf16_t* w2;       // SwiGLU: the "up" matrix (same shape as w[0])
+  const bf16_t* x;        // fragment-ordered activations [T_x, K], `PL` planes
+  int x_mtiles;           // ceil(T_x / 32)
+  const int32_t* x_rows;  // grouped gate/up: logical row r of the group reads activation row x_rows[r]
+  const bf16_t* w[3];     // packed weights, up to three stacked row segments
+  int w_tiles[3];         // 32-row tiles per segment
+  const bf16_t* w2;       // SwiGLU: the packed "up" matrix
   int N, K, T;
-  int ksteps_per_wave;    // k-steps (16 wide) per wave
+  int ksteps_per_split;   // k-steps (16 wide) per blockIdx.y
   float* y;               // EPI_STORE: [splits][T][ldy]
   int ldy;
-  bf16_t* act;            // EPI_SWIGLU: [planes][T][ldy]
-  size_t act_plane;
+  bf16_t* act;            // EPI_SWIGLU: fragment-ordered [act_rows, N], `PL` planes
+  int act_mtiles;
   // LM-head epilogue
   float* logits;          // optional [T][N]
   float* part;            // [T][n_tiles][4] = max, sumexp, best score, best index (as float bits)
   const uint64_t* seeds;
   const float* temperature;
-  const int32_t* sample_pos;  // absolute position of the token being drawn, per row
+  const int32_t* sample_pos;
   // expert-grouped form: blockIdx.y is the expert, its rows are [group_off[e], group_off[e+1])
   const int32_t* group_off;
-  size_t w_expert_stride;     // elements between consecutive experts' matrices
+  size_t w_expert_stride;     // packed elements between consecutive experts' matrices
 };
 
 enum { EPI_STORE = 0, EPI_SWIGLU = 1, EPI_LMHEAD = 2 };
-
-__device__ __forceinline__ const bf16_t* seg_row(const GemmArgs& a, int n) {
-  // pointer to row n of the stacked weight, or nullptr past the end
-  if (n >= a.N) return nullptr;
-  int s = 0;
-  while (n >= a.w_rows[s]) { n -= a.w_rows[s]; ++s; }
-  return a.w[s] + (size_t)n * a.K;
-}
 
 // ---- Philox-4x32-10 (Salmon et al., SC'11), written from the published definition ----
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
@@ -80,267 +78,363 @@ __device__ __forceinline__ float gumbel_from_u32(uint32_t r) {
   return -logf(nl);
 }
 
+template <int MT, int PL>
+struct Tiling {
+  static constexpr int KC = (32 / (MT * PL)) > 16 ? 16 : (32 / (MT * PL));  // k-steps per LDS chunk
+  static constexpr int U = KC / 2;                                          // k-steps per weight batch (store form)
+  static constexpr int FRAGS = KC * MT * PL;                                // 1 KB fragments per chunk
+  static constexpr int PER_THREAD = FRAGS / GEMM_WAVES;                     // staged by each wave
+  static constexpr int LDS_BYTES = 2 * FRAGS * 1024;
+};
+
 template <int MT, int EPI, int PL>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
-  constexpr int NW = (EPI == EPI_SWIGLU) ? 2 : 1;
-  __shared__ float red[GEMM_WAVES][NW * MT][4][WAVE][4];
+  using TL = Tiling<MT, PL>;
+  constexpr bool SW = (EPI == EPI_SWIGLU);
+  // the SwiGLU form streams two matrices, so its batches hold half as many k-steps of each
+  constexpr int KC = TL::KC, U = (SW && TL::U > 1) ? TL::U / 2 : TL::U, FRAGS = TL::FRAGS, PT = TL::PER_THREAD;
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  u32x4* lds = reinterpret_cast<u32x4*>(lds_raw);   // [2][FRAGS][64 lanes]
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int n0 = blockIdx.x * 32;
-  const int t0 = blockIdx.z * (32 * MT);
   const int r32 = lane & 31, half = lane >> 5;
+  const int mt0 = blockIdx.z * MT;                  // first 32-token tile of this workgroup
   int split = blockIdx.y;
-  int row_base = 0;            // first logical row of this workgroup's row set
-  if (a.group_off) {           // grouped: one expert per blockIdx.y, no split-K
+  int row_base = 0;
+  const bool grouped = a.group_off != nullptr;
+  if (grouped) {
     const int e = blockIdx.y;
     row_base = a.group_off[e];
     a.T = a.group_off[e + 1] - row_base;
-    if (t0 >= a.T) return;     // uniform over the workgroup, before any barrier
+    if (mt0 * 32 >= a.T) return;                    // uniform over the workgroup, before any barrier
     a.w[0] += (size_t)e * a.w_expert_stride;
-    if (EPI == EPI_SWIGLU) a.w2 += (size_t)e * a.w_expert_stride;
+    if (SW) a.w2 += (size_t)e * a.w_expert_stride;
     split = 0;
   }
 
-  const bf16_t* wrow = seg_row(a, n0 + r32);
-  const bf16_t* wrow2 = nullptr;
-  if (EPI == EPI_SWIGLU) wrow2 = (n0 + r32 < a.N) ? a.w2 + (size_t)(n0 + r32) * a.K : nullptr;
-  const bf16_t* xrow[MT];
+  // ---- this wave's weight tile ----
+  // Every load below is unconditional (clamped address) and masked afterwards, so the main loop is
+  // straight-line code and the hardware counters, not branches, order loads against their uses.
+  const int KS = a.K >> 4;
+  const int n_tiles = (a.N + 31) >> 5;
+  const int nt = blockIdx.x * GEMM_WAVES + wave;
+  const bool have_tile = nt < n_tiles;
+  const bf16_t* wp;
+  const bf16_t* wp2 = nullptr;
+  {
+    int lt = have_tile ? nt : 0;                    // a wave without a tile re-reads tile 0 and stores nothing
+    const bf16_t* base = a.w[0];                    // static member picks keep the pointers in the global space
+    if (lt >= a.w_tiles[0]) {
+      lt -= a.w_tiles[0];
+      base = a.w[1];
+      if (lt >= a.w_tiles[1]) { lt -= a.w_tiles[1]; base = a.w[2]; }
+    }
+    wp = base + (size_t)lt * KS * 512 + lane * 8;
+    if (SW) wp2 = a.w2 + (size_t)lt * KS * 512 + lane * 8;
+  }
+  const int ks_b = split * a.ksteps_per_split;
+  int ks_e = ks_b + a.ksteps_per_split;
+  if (ks_e > KS) ks_e = KS;                          // the host never launches an empty split
+
+  // ---- activation staging: each wave moves PT fragments of a chunk ----
+  // fragment f of a chunk = (k-step f / (MT*PL), token tile (f / PL) % MT, plane f % PL)
+  const bf16_t* xsrc[MT];
+  bool xok[MT];
 #pragma unroll
   for (int m = 0; m < MT; ++m) {
-    int t = t0 + 32 * m + r32;
-    if (t < a.T) {
-      int row = a.x_rows ? a.x_rows[row_base + t] : row_base + t;
-      xrow[m] = a.x + (size_t)row * a.ldx;
+    if (grouped) {
+      const int r = (mt0 + m) * 32 + r32;
+      xok[m] = r < a.T;
+      const int rr = xok[m] ? r : 0;
+      const int row = a.x_rows ? a.x_rows[row_base + rr] : row_base + rr;
+      xsrc[m] = a.x + frag_act_offset(row, 8 * half, 0, a.x_mtiles, PL);
     } else {
-      xrow[m] = nullptr;
+      xok[m] = mt0 + m < a.x_mtiles;
+      const int mt = xok[m] ? mt0 + m : 0;
+      xsrc[m] = a.x + (size_t)mt * PL * 512 + lane * 8;
     }
   }
-
-  f32x16 acc[NW * MT];
+  const size_t x_kstride = (size_t)a.x_mtiles * PL * 512;   // elements between consecutive k-steps
+  auto stage_load = [&](int chunk, u32x4 (&r)[PT]) {
+    const int ks0 = ks_b + chunk * KC;
 #pragma unroll
-  for (int i = 0; i < NW * MT; ++i)
+    for (int i = 0; i < PT; ++i) {
+      const int f = wave + GEMM_WAVES * i;
+      const int ks = ks0 + f / (MT * PL), m = (f / PL) % MT, p = f % PL;
+      const int ksc = ks < ks_e ? ks : ks_e - 1;
+      const bf16_t* src = xsrc[0];
+      bool ok = xok[0];
+#pragma unroll
+      for (int mm = 1; mm < MT; ++mm)
+        if (m == mm) { src = xsrc[mm]; ok = xok[mm]; }
+      (void)ok;
+      r[i] = *reinterpret_cast<const u32x4*>(src + (size_t)ksc * x_kstride + (size_t)p * 512);
+    }
+  };
+  // the mask is applied when the fragments are written to LDS, long after the loads were issued
+  auto stage_store = [&](int chunk, const u32x4 (&r)[PT]) {
+    const int ks0 = ks_b + chunk * KC;
+    const int buf = chunk & 1;
+#pragma unroll
+    for (int i = 0; i < PT; ++i) {
+      const int f = wave + GEMM_WAVES * i;
+      const int ks = ks0 + f / (MT * PL), m = (f / PL) % MT;
+      bool ok = xok[0];
+#pragma unroll
+      for (int mm = 1; mm < MT; ++mm)
+        if (m == mm) ok = xok[mm];
+      const u32x4 z = {0u, 0u, 0u, 0u};
+      lds[(buf * FRAGS + f) * 64 + lane] = (ok && ks < ks_e) ? r[i] : z;
+    }
+  };
+
+  // ---- weight batches ----
+  auto load_w = [&](int ks0, u32x4 (&wf)[U], u32x4 (&wf2)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int ks = ks0 + u;
+      const int ksc = ks < ks_e ? ks : ks_e - 1;   // clamped: always a valid block; masked when used
+      wf[u] = *reinterpret_cast<const u32x4*>(wp + (size_t)ksc * 512);
+      if (SW) wf2[u] = *reinterpret_cast<const u32x4*>(wp2 + (size_t)ksc * 512);
+    }
+  };
+
+  constexpr int NACC = SW ? 2 * MT : MT;
+  f32x16 acc[NACC];
+#pragma unroll
+  for (int i = 0; i < NACC; ++i)
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
 
-  const int ks_begin = (split * GEMM_WAVES + wave) * a.ksteps_per_wave;
-  const int ks_total = (a.K + 15) >> 4;
-  int ks_end = ks_begin + a.ksteps_per_wave;
-  if (ks_end > ks_total) ks_end = ks_total;
-
-  constexpr int U = 4;
-  for (int ks = ks_begin; ks < ks_end; ks += U) {
-    bf16x8 wf[U], wf2[U], xf[U][MT][PL];
+  auto compute = [&](int buf, int kk0, int ks0, const u32x4 (&wf)[U], const u32x4 (&wf2)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      int k = (ks + u) * 16 + half * 8;
-      bool ok = (ks + u < ks_end) && (k < a.K);
-      wf[u] = (ok && wrow) ? load_bf16x8(wrow + k) : zero_bf16x8();
-      if (EPI == EPI_SWIGLU) wf2[u] = (ok && wrow2) ? load_bf16x8(wrow2 + k) : zero_bf16x8();
+      const bool ok = ks0 + u < ks_e;             // uniform; past the end the weights count as zero
+      const u32x4 z = {0u, 0u, 0u, 0u};
+      const bf16x8 w1 = __builtin_bit_cast(bf16x8, ok ? wf[u] : z);
+      const bf16x8 w2 = __builtin_bit_cast(bf16x8, (SW && ok) ? wf2[u] : z);
 #pragma unroll
       for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int p = 0; p < PL; ++p)
-          xf[u][m][p] = (ok && xrow[m]) ? load_bf16x8(xrow[m] + p * a.x_plane + k) : zero_bf16x8();
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-#pragma unroll
-      for (int m = 0; m < MT; ++m)
-#pragma unroll
-        for (int p = PL - 1; p >= 0; --p) {   // small term first
-          acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u], xf[u][m][p], acc[m], 0, 0, 0);
-          if (EPI == EPI_SWIGLU)
-            acc[MT + m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf2[u], xf[u][m][p], acc[MT + m], 0, 0, 0);
+        for (int p = PL - 1; p >= 0; --p) {       // small term first
+          u32x4 xv = lds[(buf * FRAGS + ((kk0 + u) * MT + m) * PL + p) * 64 + lane];
+          bf16x8 xf = __builtin_bit_cast(bf16x8, xv);
+          acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, xf, acc[m], 0, 0, 0);
+          if (SW) acc[MT + m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2, xf, acc[MT + m], 0, 0, 0);
         }
     }
-  }
+  };
 
-  // ---- sum the waves' partial tiles through LDS, fixed order 0..3 ----
+  // Ring of R weight batches in registers: while batch b is multiplied, batches b+1 .. b+R-1 are in
+  // flight.  A group of R batches spans R/NBC activation chunks; k-steps past the end are masked to zero.
+  constexpr int R = 4;
+  constexpr int NBC = KC / U;                       // batches per activation chunk (divides R)
+  const int n_groups = (ks_e - ks_b + R * U - 1) / (R * U);
+  u32x4 wr[R][U], wr2[R][U];
+  u32x4 xr[PT];
+  stage_load(0, xr);
 #pragma unroll
-  for (int i = 0; i < NW * MT; ++i)
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      f32x4 v = {acc[i][4 * q], acc[i][4 * q + 1], acc[i][4 * q + 2], acc[i][4 * q + 3]};
-      *reinterpret_cast<f32x4*>(&red[wave][i][q][lane][0]) = v;
-    }
+  for (int r = 0; r < R - 1; ++r) load_w(ks_b + r * U, wr[r], wr2[r]);
+  stage_store(0, xr);
   __syncthreads();
-  // wave w finishes register group q = w: weight rows n0 + 8w + 4*half + {0..3}, token r32 of each tile
-  const int q = wave;
-  const int nrow = n0 + 8 * q + 4 * half;
-  f32x4 s[NW * MT];
+  for (int g = 0; g < n_groups; ++g) {
 #pragma unroll
-  for (int i = 0; i < NW * MT; ++i) {
-    s[i] = *reinterpret_cast<f32x4*>(&red[0][i][q][lane][0]);
-#pragma unroll
-    for (int w = 1; w < GEMM_WAVES; ++w) {
-      f32x4 v = *reinterpret_cast<f32x4*>(&red[w][i][q][lane][0]);
-      s[i] += v;
+    for (int r = 0; r < R; ++r) {
+      const int b = g * R + r;
+      const int c = g * (R / NBC) + r / NBC;
+      if (r % NBC == 0) stage_load(c + 1, xr);
+      load_w(ks_b + (b + R - 1) * U, wr[(r + R - 1) % R], wr2[(r + R - 1) % R]);
+      compute(c & 1, (r % NBC) * U, ks_b + b * U, wr[r], wr2[r]);
+      if (r % NBC == NBC - 1) {
+        stage_store(c + 1, xr);
+        __syncthreads();
+      }
     }
   }
+  if (!have_tile) return;
 
+  // ---- epilogue: lane holds token r32 of each tile, rows n0 + 8q + 4*half + {0..3}, q = 0..3 ----
+  const int n0 = nt * 32;
   if (EPI == EPI_STORE) {
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
-      int t = t0 + 32 * m + r32;
-      if (t < a.T) {
-        float* dst = a.y + ((size_t)split * a.T + row_base + t) * a.ldy + nrow;
+      const int t = (mt0 + m) * 32 + r32;
+      if (t >= a.T) continue;
+      float* dst = a.y + ((size_t)split * a.T + row_base + t) * a.ldy;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int nrow = n0 + 8 * q + 4 * half;
+        f32x4 v = {acc[m][4 * q], acc[m][4 * q + 1], acc[m][4 * q + 2], acc[m][4 * q + 3]};
         if (nrow + 3 < a.N) {
-          *reinterpret_cast<f32x4*>(dst) = s[m];
+          *reinterpret_cast<f32x4*>(dst + nrow) = v;
         } else {
 #pragma unroll
           for (int j = 0; j < 4; ++j)
-            if (nrow + j < a.N) dst[j] = s[m][j];
+            if (nrow + j < a.N) dst[nrow + j] = v[j];
         }
       }
     }
   } else if (EPI == EPI_SWIGLU) {
+    // output feature n is the K index of the down projection: fragment order over (row, n)
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
-      int t = t0 + 32 * m + r32;
-      if (t < a.T) {
-        bf16_t* dst = a.act + (size_t)(row_base + t) * a.ldy + nrow;
-        float o[4];
+      const int t = (mt0 + m) * 32 + r32;
+      if (t >= a.T) continue;
+      const int orow = row_base + t;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          float g = s[m][j], u = s[MT + m][j];
-          o[j] = g / (1.f + __expf(-g)) * u;
-        }
+      for (int q = 0; q < 4; ++q) {
+        const int nrow = n0 + 8 * q + 4 * half;   // four consecutive features, inside one 8-group
+        if (nrow >= a.N) continue;                // N is a multiple of 16: whole groups only
         bf16_t hi[4], lo[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) split_bf16(o[j], hi[j], lo[j]);
-        if (nrow + 3 < a.N) {
-          u32x2 p = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
-          *reinterpret_cast<u32x2*>(dst) = p;
-          if (PL == 2) {
-            u32x2 q2 = {(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
-            *reinterpret_cast<u32x2*>(dst + a.act_plane) = q2;
-          }
-        } else {
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            if (nrow + j < a.N) {
-              dst[j] = hi[j];
-              if (PL == 2) dst[a.act_plane + j] = lo[j];
-            }
+        for (int j = 0; j < 4; ++j) {
+          float g = acc[m][4 * q + j], u = acc[MT + m][4 * q + j];
+          split_bf16(g / (1.f + __expf(-g)) * u, hi[j], lo[j]);
+        }
+        bf16_t* dst = a.act + frag_act_offset(orow, nrow & ~7, 0, a.act_mtiles, PL) + (nrow & 7);
+        u32x2 pk = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
+        *reinterpret_cast<u32x2*>(dst) = pk;
+        if (PL == 2) {
+          u32x2 pk2 = {(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
+          *reinterpret_cast<u32x2*>(dst + 512) = pk2;
         }
       }
     }
   } else {  // EPI_LMHEAD: per token, reduce this tile's 32 vocabulary rows to (max, sumexp, best, argbest)
-    __shared__ float lm[GEMM_WAVES][MT][WAVE][4];
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
-      int t = t0 + 32 * m + r32;
+      const int t = (mt0 + m) * 32 + r32;
+      const bool ok = t < a.T;
       float mx = -INFINITY, se = 0.f, best = -INFINITY;
       int besti = 0x7FFFFFFF;
-      if (t < a.T) {
-        float temp = a.temperature[t];
-        float invt = temp > 0.f ? 1.f / temp : 1.f;
-        uint64_t seed = a.seeds[t];
-        uint32_t rnd[4];
-        // nrow is a multiple of 4: one Philox block covers this lane's four vocabulary ids
-        philox4x32_10((uint32_t)(nrow >> 2), (uint32_t)a.sample_pos[t], 0u, 0u, (uint32_t)seed,
-                      (uint32_t)(seed >> 32), rnd);
-        if (a.logits && nrow + 3 < a.N) {
-          *reinterpret_cast<f32x4*>(a.logits + (size_t)t * a.N + nrow) = s[m];
-        } else if (a.logits) {
+      if (ok) {
+        const float temp = a.temperature[t];
+        const float invt = temp > 0.f ? 1.f / temp : 1.f;
+        const uint64_t seed = a.seeds[t];
+        const uint32_t pos = (uint32_t)a.sample_pos[t];
 #pragma unroll
-          for (int j = 0; j < 4; ++j)
-            if (nrow + j < a.N) a.logits[(size_t)t * a.N + nrow + j] = s[m][j];
-        }
+        for (int q = 0; q < 4; ++q) {
+          const int nrow = n0 + 8 * q + 4 * half;  // multiple of 4: one Philox block covers the four ids
+          if (nrow >= a.N) continue;
+          uint32_t rnd[4];
+          philox4x32_10((uint32_t)(nrow >> 2), pos, 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32), rnd);
+          f32x4 v = {acc[m][4 * q], acc[m][4 * q + 1], acc[m][4 * q + 2], acc[m][4 * q + 3]};
+          if (a.logits) {
+            if (nrow + 3 < a.N) {
+              *reinterpret_cast<f32x4*>(a.logits + (size_t)t * a.N + nrow) = v;
+            } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          if (nrow + j < a.N) {
-            float z = s[m][j] * invt;
-            float sc = temp > 0.f ? z + gumbel_from_u32(rnd[j]) : z;
-            if (sc > best) { best = sc; besti = nrow + j; }   // ascending j: ties keep the smaller id
-            float nm = fmaxf(mx, z);
-            se = se * __expf(mx - nm) + __expf(z - nm);
-            mx = nm;
+              for (int j = 0; j < 4; ++j)
+                if (nrow + j < a.N) a.logits[(size_t)t * a.N + nrow + j] = v[j];
+            }
+          }
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            if (nrow + j < a.N) {
+              const float z = v[j] * invt;
+              const float sc = temp > 0.f ? z + gumbel_from_u32(rnd[j]) : z;
+              if (sc > best) { best = sc; besti = nrow + j; }   // ascending ids: ties keep the smaller one
+              const float nm = fmaxf(mx, z);
+              se = se * __expf(mx - nm) + __expf(z - nm);
+              mx = nm;
+            }
           }
         }
       }
-      lm[wave][m][lane][0] = mx; lm[wave][m][lane][1] = se;
-      lm[wave][m][lane][2] = best; lm[wave][m][lane][3] = __int_as_float(besti);
-    }
-    __syncthreads();
-    // threads 0..32*MT-1 merge the 8 row groups of their token in ascending row order
-    if (threadIdx.x < 32 * MT) {
-      int m = threadIdx.x >> 5, r = threadIdx.x & 31;
-      int t = t0 + 32 * m + r;
-      if (t < a.T) {
-        float mx = -INFINITY, se = 0.f, best = -INFINITY;
-        int besti = 0x7FFFFFFF;
-#pragma unroll
-        for (int g = 0; g < 8; ++g) {  // rows n0 + 4g .. : wave = g / 2, half = g & 1
-          const float* p = lm[g >> 1][m][r + 32 * (g & 1)];
-          float pm = p[0], ps = p[1], pb = p[2];
-          int pi = __float_as_int(p[3]);
-          if (pb > best) { best = pb; besti = pi; }
-          if (pm > -INFINITY) {
-            float nm = fmaxf(mx, pm);
-            se = se * __expf(mx - nm) + ps * __expf(pm - nm);
-            mx = nm;
-          }
-        }
-        float* o = a.part + ((size_t)t * gridDim.x + blockIdx.x) * 4;
-        o[0] = mx; o[1] = se; o[2] = best; o[3] = __int_as_float(besti);
+      // merge the two half-waves (rows 8q+0..3 and 8q+4..7) of the same token
+      const float omx = __shfl_xor(mx, 32, WAVE), ose = __shfl_xor(se, 32, WAVE);
+      const float obest = __shfl_xor(best, 32, WAVE);
+      const int obesti = __shfl_xor(besti, 32, WAVE);
+      if (obest > best || (obest == best && obesti < besti)) { best = obest; besti = obesti; }
+      const float nm = fmaxf(mx, omx);
+      if (nm > -INFINITY) {
+        // fixed operand order (lower half first) so both half-waves compute the same bits
+        const float lo_m = half ? omx : mx, lo_s = half ? ose : se, hi_m = half ? mx : omx, hi_s = half ? se : ose;
+        se = lo_s * (lo_m == -INFINITY ? 0.f : __expf(lo_m - nm)) + hi_s * (hi_m == -INFINITY ? 0.f : __expf(hi_m - nm));
+        mx = nm;
+      }
+      if (ok && half == 0) {
+        float* o = a.part + ((size_t)t * n_tiles + nt) * 4;
+        f32x4 pv = {mx, se, best, __int_as_float(besti)};
+        *reinterpret_cast<f32x4*>(o) = pv;
       }
     }
   }
+}
+
+template <int MT, int EPI, int PL>
+void launch_one(const GemmArgs& a, dim3 grid, hipStream_t st) {
+  static bool attr_set = false;   // raise the dynamic LDS limit once per instantiation
+  constexpr int lds = Tiling<MT, PL>::LDS_BYTES;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_kernel<MT, EPI, PL>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI, PL>), grid, dim3(GEMM_THREADS), lds, st, a);
 }
 
 template <int EPI>
-void launch_mt(const GemmArgs& a, dim3 grid_xy, int mt, int planes, hipStream_t st) {
-  // tokens are covered by grid.z super-tiles of 32*MT
+void launch_mt(const GemmArgs& a, int n_tiles, int grid_y, int mt, int planes, hipStream_t st) {
+  const int gx = (n_tiles + GEMM_WAVES - 1) / GEMM_WAVES;
+  const int mtiles = (a.T + 31) / 32;
   if (mt == 1) {
-    dim3 g(grid_xy.x, grid_xy.y, (a.T + 31) / 32);
-    if (planes == 2) hipLaunchKernelGGL((gemm_skinny_kernel<1, EPI, 2>), g, dim3(GEMM_THREADS), 0, st, a);
-    else hipLaunchKernelGGL((gemm_skinny_kernel<1, EPI, 1>), g, dim3(GEMM_THREADS), 0, st, a);
+    dim3 g(gx, grid_y, mtiles);
+    if (planes == 2) launch_one<1, EPI, 2>(a, g, st); else launch_one<1, EPI, 1>(a, g, st);
+  } else if (mt == 2) {
+    dim3 g(gx, grid_y, (mtiles + 1) / 2);
+    if (planes == 2) launch_one<2, EPI, 2>(a, g, st); else launch_one<2, EPI, 1>(a, g, st);
   } else {
-    dim3 g(grid_xy.x, grid_xy.y, (a.T + 63) / 64);
-    if (planes == 2) hipLaunchKernelGGL((gemm_skinny_kernel<2, EPI, 2>), g, dim3(GEMM_THREADS), 0, st, a);
-    else hipLaunchKernelGGL((gemm_skinny_kernel<2, EPI, 1>), g, dim3(GEMM_THREADS), 0, st, a);
+    dim3 g(gx, grid_y, (mtiles + 3) / 4);
+    if (planes == 2) launch_one<4, EPI, 2>(a, g, st); else launch_one<4, EPI, 1>(a, g, st);
   }
 }
 
-int pick_splits(int n_tiles, int ksteps, int max_splits) {
-  // enough workgroups to cover 256 CUs a few times over, at least 4 k-steps per wave
-  int s = 1;
-  while (s < max_splits && n_tiles * s < 1024 && ksteps / (GEMM_WAVES * (s * 2)) >= 4) s *= 2;
-  return s;
+int pick_mt(int T) { return T <= 32 ? 1 : (T <= 64 ? 2 : 4); }
+
+void fill_x(GemmArgs& a, const Act& x) {
+  a.x = x.p; a.x_mtiles = x.mtiles();
 }
 
 }  // namespace
 
 int gemm_max_splits() { return 8; }
 
+// split-K planning in units of 32 k-steps (one group of the kernel's weight ring)
+static int split_units(int K) { return (K / 16 + 31) / 32; }
+
 int gemm_plan_splits(int N, int K, int max_splits) {
-  return pick_splits((N + 31) / 32, (K + 15) / 16, max_splits);
+  // workgroups cover 128 rows; aim for >= 512 of them; a split is a whole number of units, none empty
+  const int wgs = ((N + 31) / 32 + GEMM_WAVES - 1) / GEMM_WAVES;
+  const int units = split_units(K);
+  int want = 1;
+  while (want < max_splits && wgs * want < 512) want *= 2;
+  if (want > units) want = units;
+  const int per = (units + want - 1) / want;
+  return (units + per - 1) / per;
 }
 
-hipError_t gemm_store(const LinearW& w, const Act& x, const int32_t* x_rows, int T, float* y, int ldy,
-                      int splits, hipStream_t st) {
+hipError_t gemm_store(const LinearW& w, const Act& x, int T, float* y, int ldy, int splits, hipStream_t st) {
   GemmArgs a = {};
-  a.x = x.p; a.x_plane = x.plane; a.x_rows = x_rows; a.ldx = x.ld;
-  for (int i = 0; i < 3; ++i) { a.w[i] = w.seg[i]; a.w_rows[i] = w.rows[i]; }
+  fill_x(a, x);
+  int tiles = 0;
+  for (int i = 0; i < 3; ++i) { a.w[i] = w.seg[i]; a.w_tiles[i] = (w.rows[i] + 31) / 32; tiles += a.w_tiles[i]; }
   a.N = w.N; a.K = w.K; a.T = T;
-  int ksteps = (w.K + 15) / 16;
-  a.ksteps_per_wave = (ksteps + splits * GEMM_WAVES - 1) / (splits * GEMM_WAVES);
+  a.ksteps_per_split = (split_units(w.K) + splits - 1) / splits * 32;   // same rule as gemm_plan_splits
   a.y = y; a.ldy = ldy;
-  launch_mt<EPI_STORE>(a, dim3((w.N + 31) / 32, splits), T > 32 ? 2 : 1, x.planes, st);
+  launch_mt<EPI_STORE>(a, tiles, splits, pick_mt(T), x.planes, st);
   return hipGetLastError();
 }
 
-hipError_t gemm_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int F, int K, const Act& x, int T,
-                       const Act& act, hipStream_t st) {
+hipError_t gemm_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int F, int K, const Act& x, int T, const Act& act,
+                       hipStream_t st) {
   GemmArgs a = {};
-  a.x = x.p; a.x_plane = x.plane; a.ldx = x.ld;
-  a.w[0] = w_gate; a.w_rows[0] = F; a.w2 = w_up;
+  fill_x(a, x);
+  a.w[0] = w_gate; a.w_tiles[0] = (F + 31) / 32; a.w2 = w_up;
   a.N = F; a.K = K; a.T = T;
-  int ksteps = (K + 15) / 16;
-  a.ksteps_per_wave = (ksteps + GEMM_WAVES - 1) / GEMM_WAVES;
-  a.act = const_cast<bf16_t*>(act.p); a.act_plane = act.plane; a.ldy = act.ld;
-  launch_mt<EPI_SWIGLU>(a, dim3((F + 31) / 32, 1), T > 32 ? 2 : 1, x.planes, st);
+  a.ksteps_per_split = K / 16;
+  a.act = act.p; a.act_mtiles = act.mtiles();
+  launch_mt<EPI_SWIGLU>(a, a.w_tiles[0], 1, pick_mt(T), x.planes, st);
   return hipGetLastError();
 }
 
@@ -348,26 +442,27 @@ hipError_t gemm_grouped_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int E, 
                                const int32_t* x_rows, const int32_t* group_off, int max_rows, const Act& act,
                                hipStream_t st) {
   GemmArgs a = {};
-  a.x = x.p; a.x_plane = x.plane; a.x_rows = x_rows; a.ldx = x.ld;
-  a.w[0] = w_gate; a.w_rows[0] = F; a.w2 = w_up;
+  fill_x(a, x);
+  a.x_rows = x_rows;
+  a.w[0] = w_gate; a.w_tiles[0] = (F + 31) / 32; a.w2 = w_up;
   a.N = F; a.K = K; a.T = max_rows;
-  a.ksteps_per_wave = ((K + 15) / 16 + GEMM_WAVES - 1) / GEMM_WAVES;
-  a.act = const_cast<bf16_t*>(act.p); a.act_plane = act.plane; a.ldy = act.ld;
-  a.group_off = group_off; a.w_expert_stride = (size_t)F * K;
-  launch_mt<EPI_SWIGLU>(a, dim3((F + 31) / 32, E), max_rows > 32 ? 2 : 1, x.planes, st);
+  a.ksteps_per_split = K / 16;
+  a.act = act.p; a.act_mtiles = act.mtiles();
+  a.group_off = group_off; a.w_expert_stride = packed_weight_elems(F, K);
+  launch_mt<EPI_SWIGLU>(a, a.w_tiles[0], E, max_rows <= 32 ? 1 : 2, x.planes, st);
   return hipGetLastError();
 }
 
-hipError_t gemm_grouped_store(const bf16_t* w, int E, int N, int K, const Act& x,
-                              const int32_t* group_off, int max_rows, float* y, hipStream_t st) {
+hipError_t gemm_grouped_store(const bf16_t* w, int E, int N, int K, const Act& x, const int32_t* group_off,
+                              int max_rows, float* y, hipStream_t st) {
   GemmArgs a = {};
-  a.x = x.p; a.x_plane = x.plane; a.ldx = x.ld;
-  a.w[0] = w; a.w_rows[0] = N;
+  fill_x(a, x);
+  a.w[0] = w; a.w_tiles[0] = (N + 31) / 32;
   a.N = N; a.K = K; a.T = max_rows;
-  a.ksteps_per_wave = ((K + 15) / 16 + GEMM_WAVES - 1) / GEMM_WAVES;
+  a.ksteps_per_split = K / 16;
   a.y = y; a.ldy = N;
-  a.group_off = group_off; a.w_expert_stride = (size_t)N * K;
-  launch_mt<EPI_STORE>(a, dim3((N + 31) / 32, E), max_rows > 32 ? 2 : 1, x.planes, st);
+  a.group_off = group_off; a.w_expert_stride = packed_weight_elems(N, K);
+  launch_mt<EPI_STORE>(a, a.w_tiles[0], E, max_rows <= 32 ? 1 : 2, x.planes, st);
   return hipGetLastError();
 }
 
@@ -377,13 +472,12 @@ hipError_t gemm_lmhead(const bf16_t* w_lm, int V, int K, const Act& x, int T, fl
                        const uint64_t* seeds, const float* temperature, const int32_t* sample_pos,
                        hipStream_t st) {
   GemmArgs a = {};
-  a.x = x.p; a.x_plane = x.plane; a.ldx = x.ld;
-  a.w[0] = w_lm; a.w_rows[0] = V;
+  fill_x(a, x);
+  a.w[0] = w_lm; a.w_tiles[0] = (V + 31) / 32;
   a.N = V; a.K = K; a.T = T;
-  int ksteps = (K + 15) / 16;
-  a.ksteps_per_wave = (ksteps + GEMM_WAVES - 1) / GEMM_WAVES;
+  a.ksteps_per_split = K / 16;
   a.logits = logits; a.part = part; a.seeds = seeds; a.temperature = temperature; a.sample_pos = sample_pos;
-  launch_mt<EPI_LMHEAD>(a, dim3((V + 31) / 32, 1), T > 32 ? 2 : 1, x.planes, st);
+  launch_mt<EPI_LMHEAD>(a, a.w_tiles[0], 1, pick_mt(T), x.planes, st);
   return hipGetLastError();
 }
 

@@ -17,25 +17,29 @@ inline LinearW linear1(const void* w, int N, int K) {
   return l;
 }
 
-// A bf16 activation matrix carried as the sum of `planes` (1 or 2) bf16 terms:
-// value[t][i] = sum_p  p[p*plane + t*ld + i].  Two terms keep 16 significand bits.
+// A bf16 activation matrix [T, K] in MFMA fragment order (common.h), carried as the sum of
+// `planes` (1 or 2) bf16 terms; two terms keep 16 significand bits.
 struct Act {
-  const bf16_t* p;
-  size_t plane;
-  int ld;
-  int planes;
+  bf16_t* p;
+  int T, K, planes;
+  __host__ __device__ int mtiles() const { return (T + 31) / 32; }
 };
-inline Act make_act(const bf16_t* p, int rows, int ld, int planes) {
-  Act a = {p, (size_t)rows * ld, ld, planes};
+inline Act make_act(bf16_t* p, int T, int K, int planes) {
+  Act a = {p, T, K, planes};
   return a;
 }
+// Row-major variant [planes][T, ld] (queries of the attention kernel).
+struct RowAct {
+  bf16_t* p;
+  size_t plane;
+  int ld, planes;
+};
 
 // ---- gemm.hip ----
 int gemm_max_splits();
 int gemm_plan_splits(int N, int K, int max_splits);
-// y[split][t][n] (fp32, leading dimension ldy); x_rows optionally gathers the rows of x
-hipError_t gemm_store(const LinearW& w, const Act& x, const int32_t* x_rows, int T, float* y, int ldy,
-                      int splits, hipStream_t st);
+// y[split][t][n] (fp32, leading dimension ldy); weights packed (common.h), activations in fragment order
+hipError_t gemm_store(const LinearW& w, const Act& x, int T, float* y, int ldy, int splits, hipStream_t st);
 // act[t][f] = bf16( silu(x Wg^T) * (x Wu^T) )
 hipError_t gemm_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int F, int K, const Act& x, int T,
                        const Act& act, hipStream_t st);
@@ -101,9 +105,13 @@ struct RopeArgs {
   const int32_t* block_table; int max_blocks;
   bf16_t* pool_layer;        // this layer's pages
   int64_t n_blocks;
-  Act q_out;                 // [planes][T, Hq*hd]
+  RowAct q_out;              // [planes][T, Hq*hd]
 };
 hipError_t qk_rope_append(const RopeArgs& a, hipStream_t st);
+// row-major [N, K] bf16 -> packed streaming layout (rows padded to 32 with zeros); K % 16 == 0
+hipError_t pack_weight(const bf16_t* src, bf16_t* dst, int N, int K, hipStream_t st);
+// row-major [T, K] bf16 -> single-plane fragment order
+hipError_t pack_activation(const bf16_t* src, bf16_t* dst, int T, int K, hipStream_t st);
 // y[i] = sum_s planes[s][i], s ascending
 hipError_t sum_planes(const float* planes, int n_planes, size_t n, float* y, hipStream_t st);
 hipError_t kv_copy_blocks(bf16_t* pool, int64_t n_blocks, int n_layers, size_t block_elems, const int32_t* src,
@@ -112,7 +120,7 @@ hipError_t kv_copy_blocks(bf16_t* pool, int64_t n_blocks, int n_layers, size_t b
 // ---- attention.hip ----
 constexpr int ATTN_SPLIT_TOKENS = 256;   // keys per decode split
 struct AttnArgs {
-  Act q;                     // [planes][T, Hq*hd]
+  RowAct q;                  // [planes][T, Hq*hd]
   const bf16_t* pool_layer;
   int64_t n_blocks;
   int Hq, Hkv, hd;
@@ -127,9 +135,10 @@ struct AttnArgs {
   const int32_t* cu_seqlens;
   const int32_t* qtile_seq; const int32_t* qtile_q0; const int32_t* n_qtiles;
   int max_qtiles;
-  Act o;                     // [planes][T, Hq*hd]
+  Act o;                     // [T, Hq*hd] in fragment order (input of the output projection)
 };
-hipError_t attention_decode(const AttnArgs& a, hipStream_t st);   // partials + merge -> o
+hipError_t attention_decode(const AttnArgs& a, hipStream_t st);        // per-split partials
+hipError_t attention_decode_merge(const AttnArgs& a, hipStream_t st);  // splits -> o
 hipError_t attention_prefill(const AttnArgs& a, hipStream_t st);
 
 // ---- moe.hip ----
@@ -153,7 +162,7 @@ struct FinalizeArgs {
   int n_rows, n_tiles, vocab, d;
   const float* part;          // [n_rows][n_tiles][4]
   Act x;                      // [planes][n_rows, d] final-normalised hidden
-  const bf16_t* w_lm;         // [vocab, d]
+  const bf16_t* w_lm;         // [vocab, d] packed
   const float* temperature; const int32_t* max_ctx_len; const int32_t* forced;
   const int32_t* sample_pos; const uint8_t* sample_on;
   int eos, pad;

@@ -60,13 +60,13 @@ __global__ __launch_bounds__(256) void sample_finalize_kernel(FinalizeArgs a) {
   if (tok < 0 || tok >= a.vocab) tok = a.eos;   // cannot happen with a non-empty vocabulary; keeps the read in bounds
 
   // logit of the emitted token: the same bf16 operands as the LM-head tiles, fp32 accumulate
-  const bf16_t* w = a.w_lm + (size_t)tok * a.d;
-  const bf16_t* x = a.x.p + (size_t)r * a.x.ld;
+  const int mtiles = a.x.mtiles();
   float acc = 0.f;
   for (int k = threadIdx.x; k < a.d; k += 256) {
-    float xv = bf16_to_f32(x[k]);
-    if (a.x.planes == 2) xv += bf16_to_f32(x[a.x.plane + k]);
-    acc += xv * bf16_to_f32(w[k]);
+    const bf16_t* x = a.x.p + frag_act_offset(r, k & ~7, 0, mtiles, a.x.planes) + (k & 7);
+    float xv = bf16_to_f32(x[0]);
+    if (a.x.planes == 2) xv += bf16_to_f32(x[512]);
+    acc += xv * bf16_to_f32(a.w_lm[packed_weight_offset(tok, k, a.d)]);
   }
   acc = wave_sum(acc);
   if ((threadIdx.x & 63) == 0) dsh[threadIdx.x >> 6] = acc;

@@ -20,6 +20,7 @@ import torch
 
 from . import binding as B
 
+PACKED = ("lm_head", "wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")   # streamed by the skinny GEMM
 PER_LAYER = ("attn_norm", "wq", "wk", "wv", "wo", "q_norm", "k_norm", "ffn_norm", "w_gate", "w_up", "w_down",
              "w_router")
 
@@ -52,13 +53,21 @@ class RolloutModel:
         moe = c.n_experts > 0
         names = [n for n in PER_LAYER if (n not in ("q_norm", "k_norm") or c.qk_norm) and (n != "w_router" or moe)]
         self.tensors: Dict = {}
+
+        def put(layer, n):
+            t = _to_bf16_cuda(tensor(layer, n), self.device)
+            if n in PACKED:          # row-major copy is dropped once the packed one exists
+                t = B.pack_matrix(t)
+            self.tensors[(layer, n)] = t
+
         for n in ("embed", "lm_head", "final_norm"):
-            self.tensors[(-1, n)] = _to_bf16_cuda(tensor(-1, n), self.device)
+            put(-1, n)
         for l in range(c.n_layers):
             for n in names:
-                self.tensors[(l, n)] = _to_bf16_cuda(tensor(l, n), self.device)
+                put(l, n)
             if progress:
                 progress(l)
+        torch.cuda.synchronize()
         w = B.Weights()
         w.struct_size = C.sizeof(B.Weights)
         w.embed = self.tensors[(-1, "embed")].data_ptr()
