@@ -76,9 +76,11 @@ typedef struct {
  *   attn_norm, ffn_norm [d_model]; q_norm, k_norm [head_dim] (NULL arrays if !qk_norm)
  *   wq (P) [n_q_heads*head_dim, d_model]; wk, wv (P) [n_kv_heads*head_dim, d_model]
  *   wo (P) [d_model, n_q_heads*head_dim]
- *   dense: w_gate, w_up (P) [d_ff, d_model]; w_down (P) [d_model, d_ff]; w_router NULL
- *   MoE:   w_router [n_experts, d_model]; w_gate, w_up (P) [n_experts, d_ff_expert, d_model];
+ *   dense: w_gate_up (G) gate and up [d_ff, d_model] each; w_down (P) [d_model, d_ff]; w_router NULL
+ *   MoE:   w_router [n_experts, d_model]; w_gate_up (G) gate and up [n_experts, d_ff_expert, d_model] each;
  *          w_down (P) [n_experts, d_model, d_ff_expert]
+ * (G): the gate and up matrices of a SwiGLU block interleaved into one packed [2 f, k]
+ * matrix by rlx_pack_gate_up.
  * d_model, d_ff and d_ff_expert must be multiples of 16.  All pointers must be 16-byte aligned.
  */
 typedef struct {
@@ -94,8 +96,7 @@ typedef struct {
   const void* const* q_norm;
   const void* const* k_norm;
   const void* const* ffn_norm;
-  const void* const* w_gate;
-  const void* const* w_up;
+  const void* const* w_gate_up;
   const void* const* w_down;
   const void* const* w_router;
 } rlx_weights;
@@ -112,6 +113,15 @@ typedef struct {
  */
 RLX_API int rlx_packed_weight_bytes(int32_t n, int32_t k, size_t* bytes_out);
 RLX_API int rlx_pack_weight(const void* src, void* dst, int32_t count, int32_t n, int32_t k, void* stream);
+/*
+ * Gate/up pair of a SwiGLU block: `count` row-major gate matrices [f, k] and up matrices
+ * [f, k] (each set stored back to back) -> `count` packed [2 f, k] matrices whose 32-row
+ * block row t holds gate rows 16t..16t+15 followed by up rows 16t..16t+15, so that one
+ * wavefront produces both factors of silu(gate) * up for 16 features.  f %% 16 == 0.
+ * Each output matrix takes rlx_packed_weight_bytes(2 f, k) bytes.
+ */
+RLX_API int rlx_pack_gate_up(const void* gate, const void* up, void* dst, int32_t count, int32_t f, int32_t k,
+                             void* stream);
 
 /* Create / destroy a model handle on the current HIP device. */
 RLX_API int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* w, rlx_model** out);
@@ -203,7 +213,7 @@ RLX_API int rollout_decode_step(const rlx_model* m, void* kv_pool, int64_t n_blo
  * Single operators, exported for per-kernel parity tests and profiling.
  *   rlx_op_linear: y[t, n] = sum_k x[t, k] W[n, k]; x bf16 [n_tokens, k] row-major, W bf16
  *   [n, k] PACKED, y float [n_tokens, n]; runs the same weight-streaming kernel the decode
- *   step uses.  workspace: at least 2*32*ceil(n_tokens/32)*k + 8*4*n_tokens*n + 512 bytes.
+ *   step uses.  workspace: at least 2*32*ceil(n_tokens/32)*k + 16*4*n_tokens*n + 1024 bytes.
  */
 RLX_API int rlx_op_linear(const void* x, const void* w, float* y, int32_t n_tokens, int32_t n, int32_t k,
                   void* workspace, size_t workspace_bytes, void* stream);

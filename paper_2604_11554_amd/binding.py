@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "librelax_rollout.so")
 
 RLX_OK, RLX_EINVAL, RLX_ENOMEM, RLX_EHIP, RLX_EUNSUPPORTED = 0, -1, -2, -3, -4
 
-EXPORTS = ["rlx_packed_weight_bytes", "rlx_pack_weight", "rlx_model_create", "rlx_model_destroy", "rlx_kv_pool_bytes", "rlx_workspace_bytes",
+EXPORTS = ["rlx_packed_weight_bytes", "rlx_pack_weight", "rlx_pack_gate_up", "rlx_model_create", "rlx_model_destroy", "rlx_kv_pool_bytes", "rlx_workspace_bytes",
            "rlx_kv_copy_blocks", "rollout_prefill_chunk", "rollout_decode_step", "rlx_op_linear",
            "rlx_profile_kernel", "rlx_last_error"]
 
@@ -48,8 +48,8 @@ _PP = C.POINTER(C.c_void_p)
 class Weights(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("embed", C.c_void_p), ("lm_head", C.c_void_p),
                 ("final_norm", C.c_void_p)] + [(n, _PP) for n in (
-                    "attn_norm", "wq", "wk", "wv", "wo", "q_norm", "k_norm", "ffn_norm", "w_gate", "w_up",
-                    "w_down", "w_router")]
+                    "attn_norm", "wq", "wk", "wv", "wo", "q_norm", "k_norm", "ffn_norm", "w_gate_up", "w_down",
+                    "w_router")]
 
 
 _lib = None
@@ -68,6 +68,7 @@ def lib() -> C.CDLL:
         l.rlx_last_error.argtypes = []
         l.rlx_packed_weight_bytes.argtypes = [i32, i32, C.POINTER(sz)]
         l.rlx_pack_weight.argtypes = [vp, vp, i32, i32, i32, vp]
+        l.rlx_pack_gate_up.argtypes = [vp, vp, vp, i32, i32, i32, vp]
         l.rlx_model_create.argtypes = [C.POINTER(ModelConfig), C.POINTER(Weights), C.POINTER(vp)]
         l.rlx_model_destroy.argtypes = [vp]
         l.rlx_kv_pool_bytes.argtypes = [vp, i64, C.POINTER(sz)]
@@ -125,6 +126,23 @@ def pack_matrix(w: torch.Tensor) -> torch.Tensor:
     per = rlx_packed_weight_bytes(n, k) // 2
     dst = torch.empty(count * per, dtype=torch.bfloat16, device=w.device)
     rlx_pack_weight(w.contiguous(), dst, count, n, k)
+    return dst
+
+
+def rlx_pack_gate_up(gate, up, dst, count: int, f: int, k: int, stream=None) -> None:
+    _check(lib().rlx_pack_gate_up(_ptr(gate, torch.bfloat16), _ptr(up, torch.bfloat16), _ptr(dst, torch.bfloat16),
+                                  count, f, k, _stream(stream)))
+
+
+def pack_gate_up(gate: torch.Tensor, up: torch.Tensor) -> torch.Tensor:
+    """Row-major bf16 gate/up [.., f, k] -> interleaved packed [2f, k] matrices."""
+    f, k = gate.shape[-2], gate.shape[-1]
+    if up.shape != gate.shape:
+        raise ValueError("gate and up must have the same shape")
+    count = int(gate.numel() // (f * k))
+    per = rlx_packed_weight_bytes(2 * f, k) // 2
+    dst = torch.empty(count * per, dtype=torch.bfloat16, device=gate.device)
+    rlx_pack_gate_up(gate.contiguous(), up.contiguous(), dst, count, f, k)
     return dst
 
 
@@ -190,7 +208,7 @@ def rlx_op_linear(x, w, y, workspace=None, stream=None) -> None:
     if y.shape[0] != n_tokens or w.numel() * 2 != rlx_packed_weight_bytes(n, k):
         raise ValueError("rlx_op_linear: y must be [n_tokens, n] and w the packed [n, k] matrix")
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    need = 2 * 32 * ((n_tokens + 31) // 32) * k + 8 * 4 * n_tokens * n + 512
+    need = 2 * 32 * ((n_tokens + 31) // 32) * k + 16 * 4 * n_tokens * n + 1024
     if ws_bytes < need:
         raise ValueError("rlx_op_linear: workspace of %d bytes needed" % need)
     _check(lib().rlx_op_linear(_ptr(x, torch.bfloat16), _ptr(w, torch.bfloat16), _ptr(y, torch.float32), n_tokens, n,

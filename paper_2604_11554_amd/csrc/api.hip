@@ -58,7 +58,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 struct rlx_model {
   rlx_model_config cfg;
   const bf16_t *embed, *lm_head, *final_norm;
-  std::vector<const bf16_t*> attn_norm, wq, wk, wv, wo, q_norm, k_norm, ffn_norm, w_gate, w_up, w_down, w_router;
+  std::vector<const bf16_t*> attn_norm, wq, wk, wv, wo, q_norm, k_norm, ffn_norm, w_gate_up, w_down, w_router;
   double* inv_freq;   // device, [head_dim / 2]
   int device;
 };
@@ -211,7 +211,7 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
     RLX_LAUNCH(RLX_K_NORM, norm(m->ffn_norm[l], nullptr, T, xb, w.xf));
     if (c.n_experts == 0) {
       const Act act = make_act(w.act, T, c.d_ff, PL);
-      RLX_LAUNCH(RLX_K_GATEUP, gemm_swiglu(m->w_gate[l], m->w_up[l], c.d_ff, d, xb, T, act, st));
+      RLX_LAUNCH(RLX_K_GATEUP, gemm_swiglu(m->w_gate_up[l], c.d_ff, d, xb, T, act, st));
       const int s_d = small ? gemm_plan_splits(d, c.d_ff, gemm_max_splits()) : 1;
       RLX_LAUNCH(RLX_K_DOWN, gemm_store(linear1(m->w_down[l], d, c.d_ff), act, T, w.planes, d, s_d, st));
       pend_planes = w.planes; pend_n = s_d;
@@ -224,7 +224,7 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
       RLX_LAUNCH(RLX_K_GROUP, moe_group(w.topk_idx, T, c.top_k, c.n_experts, w.counts, w.group_off, w.sorted_token,
                                         w.pair_pos, st));
       const Act act = make_act(w.act, T * c.top_k, c.d_ff_expert, PL);
-      RLX_LAUNCH(RLX_K_GATEUP, gemm_grouped_swiglu(m->w_gate[l], m->w_up[l], c.n_experts, c.d_ff_expert, d, xb,
+      RLX_LAUNCH(RLX_K_GATEUP, gemm_grouped_swiglu(m->w_gate_up[l], c.n_experts, c.d_ff_expert, d, xb,
                                                    w.sorted_token, w.group_off, T, act, st));
       RLX_LAUNCH(RLX_K_DOWN, gemm_grouped_store(m->w_down[l], c.n_experts, d, c.d_ff_expert, act, w.group_off, T,
                                                 w.moe_y, st));
@@ -298,8 +298,7 @@ int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* wt, rlx_mod
   if (!wt->embed || !wt->lm_head || !wt->final_norm) return fail(RLX_EINVAL, "NULL global weight");
   if (!aligned16(wt->embed) || !aligned16(wt->lm_head) || !aligned16(wt->final_norm))
     return fail(RLX_EINVAL, "weights must be 16-byte aligned");
-  const void* const* req[] = {wt->attn_norm, wt->wq, wt->wk, wt->wv, wt->wo, wt->ffn_norm, wt->w_gate, wt->w_up,
-                              wt->w_down};
+  const void* const* req[] = {wt->attn_norm, wt->wq, wt->wk, wt->wv, wt->wo, wt->ffn_norm, wt->w_gate_up, wt->w_down};
   for (auto p : req)
     if (!p) return fail(RLX_EINVAL, "NULL per-layer weight table");
   if (c.qk_norm && (!wt->q_norm || !wt->k_norm)) return fail(RLX_EINVAL, "qk_norm set but q_norm/k_norm missing");
@@ -321,8 +320,8 @@ int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* wt, rlx_mod
     return true;
   };
   bool ok = copy(m->attn_norm, wt->attn_norm) && copy(m->wq, wt->wq) && copy(m->wk, wt->wk) && copy(m->wv, wt->wv) &&
-            copy(m->wo, wt->wo) && copy(m->ffn_norm, wt->ffn_norm) && copy(m->w_gate, wt->w_gate) &&
-            copy(m->w_up, wt->w_up) && copy(m->w_down, wt->w_down) &&
+            copy(m->wo, wt->wo) && copy(m->ffn_norm, wt->ffn_norm) && copy(m->w_gate_up, wt->w_gate_up) &&
+            copy(m->w_down, wt->w_down) &&
             copy(m->q_norm, c.qk_norm ? wt->q_norm : nullptr) && copy(m->k_norm, c.qk_norm ? wt->k_norm : nullptr) &&
             copy(m->w_router, moe ? wt->w_router : nullptr);
   if (!ok) {
@@ -459,6 +458,17 @@ int rlx_pack_weight(const void* src, void* dst, int32_t count, int32_t n, int32_
   for (int i = 0; i < count; ++i)
     RLX_HIP(pack_weight((const bf16_t*)src + (size_t)i * n * k, (bf16_t*)dst + (size_t)i * pe, n, k,
                         (hipStream_t)stream));
+  return RLX_OK;
+}
+
+int rlx_pack_gate_up(const void* gate, const void* up, void* dst, int32_t count, int32_t f, int32_t k, void* stream) {
+  if (!gate || !up || !dst || count <= 0 || f <= 0 || k <= 0 || (k % 16) || (f % 16))
+    return fail(RLX_EINVAL, "rlx_pack_gate_up: bad argument (f %% 16 == 0 and k %% 16 == 0 required)");
+  if (!aligned16(gate) || !aligned16(up) || !aligned16(dst)) return fail(RLX_EINVAL, "rlx_pack_gate_up: 16-byte alignment");
+  const size_t pe = packed_weight_elems(2 * f, k);
+  for (int i = 0; i < count; ++i)
+    RLX_HIP(pack_gate_up((const bf16_t*)gate + (size_t)i * f * k, (const bf16_t*)up + (size_t)i * f * k,
+                         (bf16_t*)dst + (size_t)i * pe, f, k, (hipStream_t)stream));
   return RLX_OK;
 }
 

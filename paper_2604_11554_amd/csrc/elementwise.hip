@@ -85,113 +85,194 @@ __device__ __forceinline__ float block_sum_256(float v, float* sh) {
   return r;
 }
 
+// One workgroup per row.  Every thread owns up to NV float4 slices of the row and issues all of its
+// loads (residual, split-K planes or the top-k expert rows) before the first add, so the kernel
+// costs about one memory round trip; the normalised row goes out in MFMA fragment order.
 __global__ __launch_bounds__(256) void rmsnorm_kernel(NormArgs a) {
+  constexpr int NV = 4;                      // d <= 4096 stays in registers; longer rows loop
   __shared__ float sh[4];
   const int r = blockIdx.x;
   const int t = a.rows ? a.rows[r] : r;
   float* hrow = a.h + (size_t)t * a.d;
+  const int nv = a.d >> 2;
   const bool adding = (a.add != nullptr) || (a.moe_y != nullptr);
+  const int mtiles = a.x.mtiles();
+  const bool single = nv <= 256 * NV;
+  f32x4 keep[NV];
   float ss = 0.f;
-  for (int i = threadIdx.x; i < a.d; i += 256) {
-    float v = hrow[i];
+  int pp[8];
+  float pw[8];
+  if (a.moe_y) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const bool ok = k < a.top_k;
+      pp[k] = ok ? a.pair_pos[t * a.top_k + k] : 0;
+      pw[k] = ok ? a.topk_w[t * a.top_k + k] : 0.f;
+    }
+  }
+  for (int base = 0; base < nv; base += 256 * NV) {
+    // loads are unconditional at clamped addresses (slices past the row end re-read the last slice
+    // and are never stored), so they all go out before the first add
+    f32x4 v[NV];
+    int ic[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int i = base + threadIdx.x + 256 * j;
+      ic[j] = i < nv ? i : nv - 1;
+      v[j] = *reinterpret_cast<const f32x4*>(hrow + 4 * ic[j]);
+    }
     if (a.add) {
-      for (int s = 0; s < a.n_planes; ++s) v += a.add[((size_t)s * a.T_total + t) * a.d + i];
+      for (int s0 = 0; s0 < a.n_planes; s0 += 4) {     // four planes per round, added in plane order
+        f32x4 p[4][NV];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int sc = s0 + q < a.n_planes ? s0 + q : a.n_planes - 1;
+#pragma unroll
+          for (int j = 0; j < NV; ++j)
+            p[q][j] = *reinterpret_cast<const f32x4*>(a.add + ((size_t)sc * a.T_total + t) * a.d + 4 * ic[j]);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (s0 + q < a.n_planes) {
+#pragma unroll
+            for (int j = 0; j < NV; ++j) v[j] += p[q][j];
+          }
+      }
     }
     if (a.moe_y) {
-      float acc = 0.f;
-      for (int k = 0; k < a.top_k; ++k) {
-        int p = a.pair_pos[t * a.top_k + k];
-        acc += a.topk_w[t * a.top_k + k] * a.moe_y[(size_t)p * a.d + i];
+      f32x4 y[8][NV];
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+#pragma unroll
+        for (int j = 0; j < NV; ++j) y[k][j] = *reinterpret_cast<const f32x4*>(a.moe_y + (size_t)pp[k] * a.d + 4 * ic[j]);
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc += y[k][j] * pw[k];     // slot order k = 0..K-1; unused slots weigh 0
+        v[j] += acc;
       }
-      v += acc;
     }
-    if (adding) hrow[i] = v;
-    ss += v * v;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int i = base + threadIdx.x + 256 * j;
+      if (i < nv) {
+        if (adding) *reinterpret_cast<f32x4*>(hrow + 4 * i) = v[j];
+        ss += v[j][0] * v[j][0] + v[j][1] * v[j][1] + v[j][2] * v[j][2] + v[j][3] * v[j][3];
+      }
+      if (single) keep[j] = v[j];
+    }
   }
-  float tot = block_sum_256(ss, sh);
-  float rstd = 1.0f / sqrtf(tot / (float)a.d + a.eps);
-  const int mtiles = a.x.mtiles();
-  for (int i = threadIdx.x; i < a.d; i += 256) {
-    float v = hrow[i] * rstd * bf16_to_f32(a.gain[i]);   // own writes: visible to the same thread
-    bf16_t hi, lo;
-    split_bf16(v, hi, lo);
-    bf16_t* xo = a.x.p + frag_act_offset(r, i & ~7, 0, mtiles, a.x.planes) + (i & 7);
-    xo[0] = hi;
-    if (a.x.planes == 2) xo[512] = lo;
-    if (a.xf) a.xf[(size_t)r * a.d + i] = v;
+  const float tot = block_sum_256(ss, sh);
+  const float rstd = 1.0f / sqrtf(tot / (float)a.d + a.eps);
+  for (int base = 0; base < nv; base += 256 * NV) {
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int i = base + threadIdx.x + 256 * j;
+      if (i >= nv) continue;
+      const f32x4 hv = single ? keep[j] : *reinterpret_cast<const f32x4*>(hrow + 4 * i);   // own writes
+      const u32x2 gb = *reinterpret_cast<const u32x2*>(a.gain + 4 * i);
+      f32x4 o;
+      o[0] = hv[0] * rstd * __uint_as_float(gb[0] << 16);
+      o[1] = hv[1] * rstd * __uint_as_float(gb[0] & 0xFFFF0000u);
+      o[2] = hv[2] * rstd * __uint_as_float(gb[1] << 16);
+      o[3] = hv[3] * rstd * __uint_as_float(gb[1] & 0xFFFF0000u);
+      bf16_t hi[4], lo[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) split_bf16(o[e], hi[e], lo[e]);
+      const int k = 4 * i;
+      bf16_t* xo = a.x.p + frag_act_offset(r, k & ~7, 0, mtiles, a.x.planes) + (k & 7);
+      u32x2 pk = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
+      *reinterpret_cast<u32x2*>(xo) = pk;
+      if (a.x.planes == 2) {
+        u32x2 pk2 = {(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
+        *reinterpret_cast<u32x2*>(xo + 512) = pk2;
+      }
+      if (a.xf) *reinterpret_cast<f32x4*>(a.xf + (size_t)r * a.d + 4 * i) = o;
+    }
   }
 }
 
-// one workgroup per token, waves take heads round-robin; lane i < hd/2 owns the pair (i, i + hd/2)
+// grid (token, head group): each of the four waves owns one head; lane i < hd/2 owns the pair (i, i + hd/2)
 __global__ __launch_bounds__(256) void qk_rope_append_kernel(RopeArgs a) {
   const int t = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int hd = a.hd, half = hd >> 1;
   const int n_heads = a.Hq + 2 * a.Hkv;
+  const int h = blockIdx.y * 4 + wave;
+  if (h >= n_heads) return;
   const int pos = a.tok_pos[t];
   const int seq = a.tok_seq[t];
   const bool live = a.tok_live[t] != 0;
-  const float* row = a.qkv + (size_t)t * n_heads * hd;
   const size_t plane = (size_t)a.T * n_heads * hd;
+  const float* src = a.qkv + ((size_t)t * n_heads + h) * hd;
+  const bool act = lane < half;
+  const int li = act ? lane : 0;
 
-  float c = 1.f, s = 0.f;
-  if (lane < half) {
-    double ang = (double)pos * a.inv_freq[lane];
-    double sd, cd;
-    sincos(ang, &sd, &cd);
-    c = (float)cd; s = (float)sd;
+  // all plane loads first, then the adds in plane order
+  float x0 = 0.f, x1 = 0.f;
+  for (int p0 = 0; p0 < a.n_planes; p0 += 8) {
+    float u0[8], u1[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const bool ok = act && p0 + q < a.n_planes;
+      const size_t off = ok ? (size_t)(p0 + q) * plane : 0;
+      u0[q] = src[off + li];
+      u1[q] = src[off + li + half];
+      if (!ok) { u0[q] = 0.f; u1[q] = 0.f; }
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { x0 += u0[q]; x1 += u1[q]; }
   }
+
+  const bool is_q = h < a.Hq, is_k = !is_q && h < a.Hq + a.Hkv;
   int64_t blk = -1;
-  if (live) {
+  if (live && !is_q) {
     int j = pos >> 4;
     if (j < a.max_blocks) blk = a.block_table[(size_t)seq * a.max_blocks + j];
     if (blk < 0 || blk >= a.n_blocks) blk = -1;   // bad table entry: drop the append instead of faulting
   }
   const int slot = pos & 15;
 
-  for (int h = wave; h < n_heads; h += 4) {
-    const float* src = row + (size_t)h * hd;
-    float x0 = 0.f, x1 = 0.f;
-    if (lane < half) {
-      for (int p = 0; p < a.n_planes; ++p) {
-        x0 += src[p * plane + lane];
-        x1 += src[p * plane + lane + half];
+  if (is_q || is_k) {
+    float c = 1.f, s = 0.f;
+    if (act) {
+      double ang = (double)pos * a.inv_freq[lane];
+      double sd, cd;
+      sincos(ang, &sd, &cd);
+      c = (float)cd; s = (float)sd;
+    }
+    const bf16_t* gain = is_q ? a.q_gain : a.k_gain;
+    if (gain) {
+      float ss = wave_sum(x0 * x0 + x1 * x1);
+      float rstd = 1.0f / sqrtf(ss / (float)hd + a.eps);
+      if (act) {
+        x0 = x0 * rstd * bf16_to_f32(gain[lane]);
+        x1 = x1 * rstd * bf16_to_f32(gain[lane + half]);
       }
     }
-    const bool is_q = h < a.Hq, is_k = !is_q && h < a.Hq + a.Hkv;
-    if (is_q || is_k) {
-      const bf16_t* gain = is_q ? a.q_gain : a.k_gain;
-      if (gain) {
-        float ss = wave_sum(x0 * x0 + x1 * x1);
-        float rstd = 1.0f / sqrtf(ss / (float)hd + a.eps);
-        if (lane < half) {
-          x0 = x0 * rstd * bf16_to_f32(gain[lane]);
-          x1 = x1 * rstd * bf16_to_f32(gain[lane + half]);
-        }
+    float y0 = x0 * c - x1 * s, y1 = x1 * c + x0 * s;
+    if (act) {
+      if (is_q) {
+        bf16_t* dst = a.q_out.p + ((size_t)t * a.Hq + h) * hd;
+        bf16_t h0, l0, h1, l1;
+        split_bf16(y0, h0, l0);
+        split_bf16(y1, h1, l1);
+        dst[lane] = h0;
+        dst[lane + half] = h1;
+        if (a.q_out.planes == 2) { dst[a.q_out.plane + lane] = l0; dst[a.q_out.plane + lane + half] = l1; }
+      } else if (blk >= 0) {
+        int kvh = h - a.Hq;
+        bf16_t* dst = a.pool_layer + (((size_t)blk * a.Hkv + kvh) * 2) * 16 * hd + (size_t)slot * hd;
+        dst[lane] = f32_to_bf16(y0);
+        dst[lane + half] = f32_to_bf16(y1);
       }
-      float y0 = x0 * c - x1 * s, y1 = x1 * c + x0 * s;
-      if (lane < half) {
-        if (is_q) {
-          bf16_t* dst = a.q_out.p + ((size_t)t * a.Hq + h) * hd;
-          bf16_t h0, l0, h1, l1;
-          split_bf16(y0, h0, l0);
-          split_bf16(y1, h1, l1);
-          dst[lane] = h0;
-          dst[lane + half] = h1;
-          if (a.q_out.planes == 2) { dst[a.q_out.plane + lane] = l0; dst[a.q_out.plane + lane + half] = l1; }
-        } else if (blk >= 0) {
-          int kvh = h - a.Hq;
-          bf16_t* dst = a.pool_layer + (((size_t)blk * a.Hkv + kvh) * 2) * 16 * hd + (size_t)slot * hd;
-          dst[lane] = f32_to_bf16(y0);
-          dst[lane + half] = f32_to_bf16(y1);
-        }
-      }
-    } else if (blk >= 0 && lane < half) {   // value head: stored transposed, [hd][16]
-      int kvh = h - a.Hq - a.Hkv;
-      bf16_t* dst = a.pool_layer + (((size_t)blk * a.Hkv + kvh) * 2 + 1) * 16 * hd;
-      dst[(size_t)lane * 16 + slot] = f32_to_bf16(x0);
-      dst[(size_t)(lane + half) * 16 + slot] = f32_to_bf16(x1);
     }
+  } else if (blk >= 0 && act) {   // value head: stored transposed, [hd][16]
+    int kvh = h - a.Hq - a.Hkv;
+    bf16_t* dst = a.pool_layer + (((size_t)blk * a.Hkv + kvh) * 2 + 1) * 16 * hd;
+    dst[(size_t)lane * 16 + slot] = f32_to_bf16(x0);
+    dst[(size_t)(lane + half) * 16 + slot] = f32_to_bf16(x1);
   }
 }
 
@@ -209,6 +290,20 @@ __global__ void pack_weight_kernel(const bf16_t* src, bf16_t* dst, int N, int K)
   u32x4 v = {0u, 0u, 0u, 0u};
   if (n < N) v = *reinterpret_cast<const u32x4*>(src + (size_t)n * K + k);
   *reinterpret_cast<u32x4*>(dst + g * 8) = v;
+}
+
+__global__ void pack_gate_up_kernel(const bf16_t* gate, const bf16_t* up, bf16_t* dst, int F, int K) {
+  const size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t total = packed_weight_elems(2 * F, K) / 8;
+  if (g >= total) return;
+  const int lane = (int)(g & 63);
+  const size_t frag = g >> 6;
+  const int KS = K >> 4;
+  const int ks = (int)(frag % KS);
+  const int nt = (int)(frag / KS);
+  const int r = lane & 31, k = ks * 16 + 8 * (lane >> 5);
+  const bf16_t* src = (r < 16 ? gate : up) + (size_t)(nt * 16 + (r & 15)) * K + k;
+  *reinterpret_cast<u32x4*>(dst + g * 8) = *reinterpret_cast<const u32x4*>(src);
 }
 
 __global__ void pack_activation_kernel(const bf16_t* src, bf16_t* dst, int T, int K) {
@@ -267,13 +362,19 @@ hipError_t rmsnorm(const NormArgs& a, hipStream_t st) {
 }
 
 hipError_t qk_rope_append(const RopeArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL(qk_rope_append_kernel, dim3(a.T), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(qk_rope_append_kernel, dim3(a.T, (a.Hq + 2 * a.Hkv + 3) / 4), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
 hipError_t pack_weight(const bf16_t* src, bf16_t* dst, int N, int K, hipStream_t st) {
   const size_t groups = packed_weight_elems(N, K) / 8;
   hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, src, dst, N, K);
+  return hipGetLastError();
+}
+
+hipError_t pack_gate_up(const bf16_t* gate, const bf16_t* up, bf16_t* dst, int F, int K, hipStream_t st) {
+  const size_t groups = packed_weight_elems(2 * F, K) / 8;
+  hipLaunchKernelGGL(pack_gate_up_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, gate, up, dst, F, K);
   return hipGetLastError();
 }
 

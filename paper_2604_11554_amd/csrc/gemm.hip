@@ -30,7 +30,6 @@ struct GemmArgs {
   const int32_t* x_rows;  // grouped gate/up: logical row r of the group reads activation row x_rows[r]
   const bf16_t* w[3];     // packed weights, up to three stacked row segments
   int w_tiles[3];         // 32-row tiles per segment
-  const bf16_t* w2;       // SwiGLU: the packed "up" matrix
   int N, K, T;
   int ksteps_per_split;   // k-steps (16 wide) per blockIdx.y
   float* y;               // EPI_STORE: [splits][T][ldy]
@@ -90,9 +89,7 @@ struct Tiling {
 template <int MT, int EPI, int PL>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
   using TL = Tiling<MT, PL>;
-  constexpr bool SW = (EPI == EPI_SWIGLU);
-  // the SwiGLU form streams two matrices, so its batches hold half as many k-steps of each
-  constexpr int KC = TL::KC, U = (SW && TL::U > 1) ? TL::U / 2 : TL::U, FRAGS = TL::FRAGS, PT = TL::PER_THREAD;
+  constexpr int KC = TL::KC, U = TL::U, FRAGS = TL::FRAGS, PT = TL::PER_THREAD;
   extern __shared__ __align__(16) unsigned char lds_raw[];
   u32x4* lds = reinterpret_cast<u32x4*>(lds_raw);   // [2][FRAGS][64 lanes]
 
@@ -108,7 +105,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
     a.T = a.group_off[e + 1] - row_base;
     if (mt0 * 32 >= a.T) return;                    // uniform over the workgroup, before any barrier
     a.w[0] += (size_t)e * a.w_expert_stride;
-    if (SW) a.w2 += (size_t)e * a.w_expert_stride;
     split = 0;
   }
 
@@ -120,7 +116,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
   const int nt = blockIdx.x * GEMM_WAVES + wave;
   const bool have_tile = nt < n_tiles;
   const bf16_t* wp;
-  const bf16_t* wp2 = nullptr;
   {
     int lt = have_tile ? nt : 0;                    // a wave without a tile re-reads tile 0 and stores nothing
     const bf16_t* base = a.w[0];                    // static member picks keep the pointers in the global space
@@ -130,7 +125,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
       if (lt >= a.w_tiles[1]) { lt -= a.w_tiles[1]; base = a.w[2]; }
     }
     wp = base + (size_t)lt * KS * 512 + lane * 8;
-    if (SW) wp2 = a.w2 + (size_t)lt * KS * 512 + lane * 8;
   }
   const int ks_b = split * a.ksteps_per_split;
   int ks_e = ks_b + a.ksteps_per_split;
@@ -189,30 +183,27 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
   };
 
   // ---- weight batches ----
-  auto load_w = [&](int ks0, u32x4 (&wf)[U], u32x4 (&wf2)[U]) {
+  auto load_w = [&](int ks0, u32x4 (&wf)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int ks = ks0 + u;
       const int ksc = ks < ks_e ? ks : ks_e - 1;   // clamped: always a valid block; masked when used
       wf[u] = *reinterpret_cast<const u32x4*>(wp + (size_t)ksc * 512);
-      if (SW) wf2[u] = *reinterpret_cast<const u32x4*>(wp2 + (size_t)ksc * 512);
     }
   };
 
-  constexpr int NACC = SW ? 2 * MT : MT;
-  f32x16 acc[NACC];
+  f32x16 acc[MT];
 #pragma unroll
-  for (int i = 0; i < NACC; ++i)
+  for (int i = 0; i < MT; ++i)
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
 
-  auto compute = [&](int buf, int kk0, int ks0, const u32x4 (&wf)[U], const u32x4 (&wf2)[U]) {
+  auto compute = [&](int buf, int kk0, int ks0, const u32x4 (&wf)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bool ok = ks0 + u < ks_e;             // uniform; past the end the weights count as zero
       const u32x4 z = {0u, 0u, 0u, 0u};
       const bf16x8 w1 = __builtin_bit_cast(bf16x8, ok ? wf[u] : z);
-      const bf16x8 w2 = __builtin_bit_cast(bf16x8, (SW && ok) ? wf2[u] : z);
 #pragma unroll
       for (int m = 0; m < MT; ++m)
 #pragma unroll
@@ -220,7 +211,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
           u32x4 xv = lds[(buf * FRAGS + ((kk0 + u) * MT + m) * PL + p) * 64 + lane];
           bf16x8 xf = __builtin_bit_cast(bf16x8, xv);
           acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, xf, acc[m], 0, 0, 0);
-          if (SW) acc[MT + m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2, xf, acc[MT + m], 0, 0, 0);
         }
     }
   };
@@ -230,11 +220,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
   constexpr int R = 4;
   constexpr int NBC = KC / U;                       // batches per activation chunk (divides R)
   const int n_groups = (ks_e - ks_b + R * U - 1) / (R * U);
-  u32x4 wr[R][U], wr2[R][U];
+  u32x4 wr[R][U];
   u32x4 xr[PT];
   stage_load(0, xr);
 #pragma unroll
-  for (int r = 0; r < R - 1; ++r) load_w(ks_b + r * U, wr[r], wr2[r]);
+  for (int r = 0; r < R - 1; ++r) load_w(ks_b + r * U, wr[r]);
+  __builtin_amdgcn_sched_barrier(0);
   stage_store(0, xr);
   __syncthreads();
   for (int g = 0; g < n_groups; ++g) {
@@ -243,8 +234,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
       const int b = g * R + r;
       const int c = g * (R / NBC) + r / NBC;
       if (r % NBC == 0) stage_load(c + 1, xr);
-      load_w(ks_b + (b + R - 1) * U, wr[(r + R - 1) % R], wr2[(r + R - 1) % R]);
-      compute(c & 1, (r % NBC) * U, ks_b + b * U, wr[r], wr2[r]);
+      load_w(ks_b + (b + R - 1) * U, wr[(r + R - 1) % R]);
+      // keep the issue order: the loads above go out before the multiply below starts waiting
+      __builtin_amdgcn_sched_barrier(0);
+      compute(c & 1, (r % NBC) * U, ks_b + b * U, wr[r]);
+      __builtin_amdgcn_sched_barrier(0);
       if (r % NBC == NBC - 1) {
         stage_store(c + 1, xr);
         __syncthreads();
@@ -275,23 +269,26 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
       }
     }
   } else if (EPI == EPI_SWIGLU) {
-    // output feature n is the K index of the down projection: fragment order over (row, n)
+    // The packed matrix interleaves gate and up: rows 0..15 of a tile are gate rows of features
+    // 16 nt .. 16 nt + 15, rows 16..31 the matching up rows, so a lane holds both halves of a pair
+    // (register groups q and q + 2).  The output feature is the K index of the down projection.
+    const int n_feat = a.N >> 1;
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
       const int t = (mt0 + m) * 32 + r32;
       if (t >= a.T) continue;
       const int orow = row_base + t;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int nrow = n0 + 8 * q + 4 * half;   // four consecutive features, inside one 8-group
-        if (nrow >= a.N) continue;                // N is a multiple of 16: whole groups only
+      for (int q = 0; q < 2; ++q) {
+        const int feat = nt * 16 + 8 * q + 4 * half;   // four consecutive features inside one 8-group
+        if (feat >= n_feat) continue;
         bf16_t hi[4], lo[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          float g = acc[m][4 * q + j], u = acc[MT + m][4 * q + j];
+          float g = acc[m][4 * q + j], u = acc[m][4 * (q + 2) + j];
           split_bf16(g / (1.f + __expf(-g)) * u, hi[j], lo[j]);
         }
-        bf16_t* dst = a.act + frag_act_offset(orow, nrow & ~7, 0, a.act_mtiles, PL) + (nrow & 7);
+        bf16_t* dst = a.act + frag_act_offset(orow, feat & ~7, 0, a.act_mtiles, PL) + (feat & 7);
         u32x2 pk = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
         *reinterpret_cast<u32x2*>(dst) = pk;
         if (PL == 2) {
@@ -398,17 +395,18 @@ void fill_x(GemmArgs& a, const Act& x) {
 
 }  // namespace
 
-int gemm_max_splits() { return 8; }
+int gemm_max_splits() { return 16; }
 
-// split-K planning in units of 32 k-steps (one group of the kernel's weight ring)
-static int split_units(int K) { return (K / 16 + 31) / 32; }
+// split-K planning in units of 16 k-steps (one activation chunk)
+static int split_units(int K) { return (K / 16 + 15) / 16; }
 
 int gemm_plan_splits(int N, int K, int max_splits) {
-  // workgroups cover 128 rows; aim for >= 512 of them; a split is a whole number of units, none empty
+  // workgroups cover 128 rows; aim for one per CU (measured: the kernel time is flat in the split count
+  // beyond that, and fewer planes mean less traffic); a split is a whole number of units, none empty
   const int wgs = ((N + 31) / 32 + GEMM_WAVES - 1) / GEMM_WAVES;
   const int units = split_units(K);
   int want = 1;
-  while (want < max_splits && wgs * want < 512) want *= 2;
+  while (want < max_splits && wgs * want < 256) want *= 2;
   if (want > units) want = units;
   const int per = (units + want - 1) / want;
   return (units + per - 1) / per;
@@ -420,35 +418,33 @@ hipError_t gemm_store(const LinearW& w, const Act& x, int T, float* y, int ldy, 
   int tiles = 0;
   for (int i = 0; i < 3; ++i) { a.w[i] = w.seg[i]; a.w_tiles[i] = (w.rows[i] + 31) / 32; tiles += a.w_tiles[i]; }
   a.N = w.N; a.K = w.K; a.T = T;
-  a.ksteps_per_split = (split_units(w.K) + splits - 1) / splits * 32;   // same rule as gemm_plan_splits
+  a.ksteps_per_split = (split_units(w.K) + splits - 1) / splits * 16;   // same rule as gemm_plan_splits
   a.y = y; a.ldy = ldy;
   launch_mt<EPI_STORE>(a, tiles, splits, pick_mt(T), x.planes, st);
   return hipGetLastError();
 }
 
-hipError_t gemm_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int F, int K, const Act& x, int T, const Act& act,
-                       hipStream_t st) {
+hipError_t gemm_swiglu(const bf16_t* w_gate_up, int F, int K, const Act& x, int T, const Act& act, hipStream_t st) {
   GemmArgs a = {};
   fill_x(a, x);
-  a.w[0] = w_gate; a.w_tiles[0] = (F + 31) / 32; a.w2 = w_up;
-  a.N = F; a.K = K; a.T = T;
+  a.w[0] = w_gate_up; a.w_tiles[0] = F / 16;
+  a.N = 2 * F; a.K = K; a.T = T;
   a.ksteps_per_split = K / 16;
   a.act = act.p; a.act_mtiles = act.mtiles();
   launch_mt<EPI_SWIGLU>(a, a.w_tiles[0], 1, pick_mt(T), x.planes, st);
   return hipGetLastError();
 }
 
-hipError_t gemm_grouped_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int E, int F, int K, const Act& x,
-                               const int32_t* x_rows, const int32_t* group_off, int max_rows, const Act& act,
-                               hipStream_t st) {
+hipError_t gemm_grouped_swiglu(const bf16_t* w_gate_up, int E, int F, int K, const Act& x, const int32_t* x_rows,
+                               const int32_t* group_off, int max_rows, const Act& act, hipStream_t st) {
   GemmArgs a = {};
   fill_x(a, x);
   a.x_rows = x_rows;
-  a.w[0] = w_gate; a.w_tiles[0] = (F + 31) / 32; a.w2 = w_up;
-  a.N = F; a.K = K; a.T = max_rows;
+  a.w[0] = w_gate_up; a.w_tiles[0] = F / 16;
+  a.N = 2 * F; a.K = K; a.T = max_rows;
   a.ksteps_per_split = K / 16;
   a.act = act.p; a.act_mtiles = act.mtiles();
-  a.group_off = group_off; a.w_expert_stride = packed_weight_elems(F, K);
+  a.group_off = group_off; a.w_expert_stride = packed_weight_elems(2 * F, K);
   launch_mt<EPI_SWIGLU>(a, a.w_tiles[0], E, max_rows <= 32 ? 1 : 2, x.planes, st);
   return hipGetLastError();
 }

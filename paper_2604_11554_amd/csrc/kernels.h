@@ -40,17 +40,15 @@ int gemm_max_splits();
 int gemm_plan_splits(int N, int K, int max_splits);
 // y[split][t][n] (fp32, leading dimension ldy); weights packed (common.h), activations in fragment order
 hipError_t gemm_store(const LinearW& w, const Act& x, int T, float* y, int ldy, int splits, hipStream_t st);
-// act[t][f] = bf16( silu(x Wg^T) * (x Wu^T) )
-hipError_t gemm_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int F, int K, const Act& x, int T,
-                       const Act& act, hipStream_t st);
+// act[t][f] = silu(x Wg^T) * (x Wu^T); w_gate_up is the interleaved packed pair (pack_gate_up)
+hipError_t gemm_swiglu(const bf16_t* w_gate_up, int F, int K, const Act& x, int T, const Act& act, hipStream_t st);
 int lmhead_tiles(int vocab);
 // LM head with fused per-tile log-sum-exp and Gumbel-max partials: part[t][tile][4]
 hipError_t gemm_lmhead(const bf16_t* w_lm, int V, int K, const Act& x, int T, float* logits, float* part,
                        const uint64_t* seeds, const float* temperature, const int32_t* sample_pos, hipStream_t st);
 // expert-grouped forms: rows [group_off[e], group_off[e+1]) belong to expert e = blockIdx.y
-hipError_t gemm_grouped_swiglu(const bf16_t* w_gate, const bf16_t* w_up, int E, int F, int K, const Act& x,
-                               const int32_t* x_rows, const int32_t* group_off, int max_rows, const Act& act,
-                               hipStream_t st);
+hipError_t gemm_grouped_swiglu(const bf16_t* w_gate_up, int E, int F, int K, const Act& x, const int32_t* x_rows,
+                               const int32_t* group_off, int max_rows, const Act& act, hipStream_t st);
 hipError_t gemm_grouped_store(const bf16_t* w, int E, int N, int K, const Act& x,
                               const int32_t* group_off, int max_rows, float* y, hipStream_t st);
 
@@ -110,6 +108,9 @@ struct RopeArgs {
 hipError_t qk_rope_append(const RopeArgs& a, hipStream_t st);
 // row-major [N, K] bf16 -> packed streaming layout (rows padded to 32 with zeros); K % 16 == 0
 hipError_t pack_weight(const bf16_t* src, bf16_t* dst, int N, int K, hipStream_t st);
+// row-major gate [F, K] and up [F, K] -> one packed [2F, K] matrix whose 32-row tile t holds gate rows
+// 16t..16t+15 followed by up rows 16t..16t+15 (F % 16 == 0)
+hipError_t pack_gate_up(const bf16_t* gate, const bf16_t* up, bf16_t* dst, int F, int K, hipStream_t st);
 // row-major [T, K] bf16 -> single-plane fragment order
 hipError_t pack_activation(const bf16_t* src, bf16_t* dst, int T, int K, hipStream_t st);
 // y[i] = sum_s planes[s][i], s ascending

@@ -20,8 +20,8 @@ import torch
 
 from . import binding as B
 
-PACKED = ("lm_head", "wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")   # streamed by the skinny GEMM
-PER_LAYER = ("attn_norm", "wq", "wk", "wv", "wo", "q_norm", "k_norm", "ffn_norm", "w_gate", "w_up", "w_down",
+PACKED = ("lm_head", "wq", "wk", "wv", "wo", "w_down")   # streamed by the skinny GEMM
+PER_LAYER = ("attn_norm", "wq", "wk", "wv", "wo", "q_norm", "k_norm", "ffn_norm", "w_gate_up", "w_down",
              "w_router")
 
 
@@ -37,8 +37,9 @@ class RolloutModel:
     """Weights on the device plus the library handle.
 
     cfg: mapping with the fields of rlx_model_config (without struct_size).
-    tensor(layer, name) returns the bf16 tensor (uint16 numpy bits or torch bf16);
-    layer -1 holds embed / lm_head / final_norm.
+    tensor(layer, name) returns the row-major bf16 tensor (uint16 numpy bits or torch bf16) under the
+    usual names (wq, wk, wv, wo, w_gate, w_up, w_down, ...); layer -1 holds embed / lm_head /
+    final_norm.  The streamed matrices are converted to the library's packed layout here.
     """
 
     def __init__(self, cfg: Dict, tensor: Callable[[int, str], object], device="cuda:0", progress=None):
@@ -55,9 +56,13 @@ class RolloutModel:
         self.tensors: Dict = {}
 
         def put(layer, n):
-            t = _to_bf16_cuda(tensor(layer, n), self.device)
-            if n in PACKED:          # row-major copy is dropped once the packed one exists
-                t = B.pack_matrix(t)
+            if n == "w_gate_up":
+                t = B.pack_gate_up(_to_bf16_cuda(tensor(layer, "w_gate"), self.device),
+                                   _to_bf16_cuda(tensor(layer, "w_up"), self.device))
+            else:
+                t = _to_bf16_cuda(tensor(layer, n), self.device)
+                if n in PACKED:          # row-major copy is dropped once the packed one exists
+                    t = B.pack_matrix(t)
             self.tensors[(layer, n)] = t
 
         for n in ("embed", "lm_head", "final_norm"):

@@ -48,7 +48,7 @@ def test_linear_matches_definition(amd, T, N, K):
     want = RI.bf16_bits_to_f32(xb).astype(np.float64) @ RI.bf16_bits_to_f32(wb).astype(np.float64).T
     x, w = bits_to_torch(xb), pkg.binding.pack_matrix(bits_to_torch(wb))
     y = torch.full((T, N), float("nan"), dtype=torch.float32, device="cuda:0")
-    ws = torch.empty(2 * 32 * ((T + 31) // 32) * K + 8 * T * N * 4 + 512, dtype=torch.uint8, device="cuda:0")
+    ws = torch.empty(2 * 32 * ((T + 31) // 32) * K + 16 * T * N * 4 + 1024, dtype=torch.uint8, device="cuda:0")
     pkg.binding.rlx_op_linear(x, w, y, ws)
     torch.cuda.synchronize()
     got = y.cpu().numpy().astype(np.float64)
