@@ -136,7 +136,7 @@ def main():
     ap.add_argument("--steps", type=int, default=0, help="decode steps to time (0 = the whole decode phase)")
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="dense_b64", choices=["dense_b64", "moe_b128"])
-    ap.add_argument("--split", type=int, default=-1, help="activation_split (default: 0 dense, 1 MoE)")
+    ap.add_argument("--split", type=int, default=-1, help="activation_split (default 1: two bf16 terms per activation)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel", default="auto", help="kernel class for the roofline record")
     args = ap.parse_args()
@@ -157,7 +157,7 @@ def main():
         shape, wl = RI.QWEN3_4B, RI.workload_dense_batch()
     else:
         shape, wl = RI.QWEN3_30B_A3B, RI.workload_moe_batch()
-    split = args.split if args.split >= 0 else (1 if shape.is_moe else 0)
+    split = args.split if args.split >= 0 else 1     # the setting the parity tests at this shape pass with
     n_decode = int(wl.n_decode[0])
     bsz = wl.batch
     plen = wl.prompt_lens

@@ -19,3 +19,26 @@ def model_from_shape(s: RI.ModelShape, model_seed: int = 0, device="cuda:0", pro
     """Upload the keyed synthetic weights of `s` (same bf16 bit patterns the oracle upcasts)."""
     return RolloutModel(config_from_shape(s, activation_split), lambda l, n: RI.tensor_bf16(s, model_seed, l, n),
                         device, progress)
+
+
+def generate_tensors(s: RI.ModelShape, model_seed: int = 0, threads: int = 8, progress=None) -> dict:
+    """All bf16 bit patterns of a synthetic model, {(layer, name): uint16 array}, generated on several
+    host threads (NumPy's generators release the GIL)."""
+    from concurrent.futures import ThreadPoolExecutor
+    keys = [(l, n) for l in [RI.GLOBAL_LAYER] + list(range(s.n_layers)) for n in RI.tensor_names(s, l)]
+    out = {}
+
+    def make(key):
+        return key, RI.tensor_bf16(s, model_seed, key[0], key[1])
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        for i, (key, bits) in enumerate(ex.map(make, keys)):
+            out[key] = bits
+            if progress and i % 32 == 0:
+                progress(i, len(keys))
+    return out
+
+
+def model_from_tensors(s: RI.ModelShape, tensors: dict, device="cuda:0", activation_split: int = 1,
+                       progress=None) -> RolloutModel:
+    return RolloutModel(config_from_shape(s, activation_split), lambda l, n: tensors[(l, n)], device, progress)

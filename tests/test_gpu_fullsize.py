@@ -1,0 +1,121 @@
+"""Parity at the benchmark's full shapes, in the launch configuration bench.py times (same batch, same
+kernels), on sampled sequences the oracle can recompute one by one.  The dense 4B shape runs with all 36
+layers; the 30B-A3B MoE shape runs as a 2-layer slice of the same per-layer shape (all 128 experts, top-8,
+batch 128), because generating and holding its 61 GB of synthetic weights on the host takes too long for a test."""
+import sys
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import rollout_inputs as RI
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_BAR, LOGPROB_BAR, TIE_GAP = 0.05, 0.02, 1e-3
+
+
+def say(msg):
+    print("[gpu-case %s] %s" % (time.strftime("%H:%M:%S"), msg), flush=True)
+    sys.stdout.flush()
+
+
+def _prefill_all(eng, wl, budget, rows_of_interest):
+    """Chunked prefill of the whole batch; returns {row: (token, logprob, logits, routing rows)}."""
+    got = {}
+    plen = wl.prompt_lens
+    i = 0
+    while i < wl.batch:
+        j, tot = i, 0
+        while j < wl.batch and tot + int(plen[j]) <= budget:
+            tot += int(plen[j]); j += 1
+        rows = list(range(i, j))
+        o = eng.prefill(rows, wl.prompt_tokens[i:j], want_logits=True, want_routing=True)
+        torch.cuda.synchronize()
+        offs = np.concatenate([[0], np.cumsum(plen[i:j])])
+        for k, r in enumerate(rows):
+            if r in rows_of_interest:
+                rt = None if o.routing is None else o.routing[offs[k]:offs[k + 1]].cpu().numpy()
+                got[r] = (int(o.tokens[k]), float(o.logprobs[k]), o.logits[k].cpu().numpy(), rt)
+        say("prefilled rows %d..%d (%d tokens)" % (i, j - 1, tot))
+        i = j
+    return got
+
+
+def _run_case(shape, wl, split, n_steps, sample_rows, budget=8192):
+    import paper_2604_11554_amd as pkg
+    from paper_2604_11554_amd import synthetic
+    pkg.binding.lib()
+    say("generating %s weights on the host" % shape.name)
+    tensors = synthetic.generate_tensors(shape, 0, threads=12, progress=lambda i, n: say("  tensor %d/%d" % (i, n)))
+    say("uploading")
+    model = synthetic.model_from_tensors(shape, tensors, activation_split=split)
+    plen = wl.prompt_lens
+    mb = (int(plen.max()) + n_steps + 16) // 16 + 1
+    eng = pkg.RolloutEngine(model, n_blocks=int(sum((int(n) + n_steps + 31) // 16 for n in plen)) + 8,
+                            max_seqs=wl.batch, max_chunk_tokens=budget, max_blocks_per_seq=mb)
+    for i in range(wl.batch):
+        eng.add_sequence(int(wl.seeds[i]), 1.0, reserve_tokens=int(plen[i]) + n_steps + 8)
+    got = _prefill_all(eng, wl, budget, set(sample_rows))
+    steps = []                                    # per decode step: tokens, logprobs, logits, routing of sampled rows
+    idx = torch.tensor(sample_rows, device="cuda:0")
+    for s in range(n_steps):
+        o = eng.decode_step(want_logits=True, want_routing=True)
+        torch.cuda.synchronize()
+        steps.append((o.tokens[idx].cpu().numpy().copy(), o.logprobs[idx].cpu().numpy().copy(),
+                      o.logits[idx].cpu().numpy().copy(),
+                      None if o.routing is None else o.routing[idx].cpu().numpy().copy()))
+        say("decode step %d done" % s)
+    # ---- oracle: teacher-forced on the GPU's own tokens, replaying the GPU's routing (routing replay) so
+    # that a tolerated near-tie does not hide everything after it; its own router choice is still reported
+    om = O.OracleModel(shape, 0, cache_layers=False, tensors=tensors)
+    seqs, replay = [], []
+    for k, r in enumerate(sample_rows):
+        toks = list(wl.prompt_tokens[r]) + [got[r][0]] + [int(st[0][k]) for st in steps[:-1]]
+        seqs.append(np.array(toks, np.int32))
+        if shape.is_moe:
+            replay.append(np.concatenate([got[r][3]] + [st[3][k][None] for st in steps], axis=0))
+    at = [np.arange(int(plen[r]) - 1, int(plen[r]) + n_steps) for r in sample_rows]
+    say("oracle forward of %d sampled sequences (%s tokens)" % (len(seqs), [len(s) for s in seqs]))
+    res = O.forward_full(om, seqs, forced_routing=replay if shape.is_moe else None, logits_at=at,
+                         progress=lambda l: say("  oracle layer %d" % l))
+    stats = dict(dlogit=0.0, dlogprob=0.0, tie_flips=0, routes=0)
+    for k, r in enumerate(sample_rows):
+        z_o = res[k]["logits"]
+        lp_o = O.log_softmax(z_o)
+        emitted = [got[r][0]] + [int(st[0][k]) for st in steps]
+        z_g = [got[r][2]] + [st[2][k] for st in steps]
+        lp_g = [got[r][1]] + [float(st[1][k]) for st in steps]
+        for p in range(n_steps + 1):
+            stats["dlogit"] = max(stats["dlogit"], float(np.abs(z_g[p] - z_o[p]).max()))
+            stats["dlogprob"] = max(stats["dlogprob"], abs(lp_g[p] - float(lp_o[p, emitted[p]])))
+            # the GPU's draw must be (nearly) the oracle's best perturbed score
+            g = O.gumbel_noise(int(wl.seeds[r]), int(plen[r]) + p, shape.vocab)
+            sc = z_o[p].astype(np.float64) + g
+            assert sc[emitted[p]] >= sc.max() - 2 * LOGIT_BAR, "row %d step %d: bad draw" % (r, p)
+        if shape.is_moe:
+            own, gaps = res[k]["own_routing"], res[k]["gate_gap"]
+            bad = (np.sort(replay[k], -1) != np.sort(own, -1)).any(-1)
+            stats["routes"] += bad.size
+            stats["tie_flips"] += int(bad.sum())
+            assert (gaps[bad] < TIE_GAP).all(), "routing differs at gate gap %.2e" % float(gaps[bad].max())
+    say("%s sampled-row stats %s" % (shape.name, stats))
+    assert stats["dlogit"] <= LOGIT_BAR and stats["dlogprob"] <= LOGPROB_BAR
+    model.close()
+    return stats
+
+
+def test_dense_4b_shape_batch64_sampled_rows():
+    shape = RI.QWEN3_4B
+    wl = RI.workload_dense_batch(shape)                       # 64 sequences, prompts uniform 256..1024
+    plen = wl.prompt_lens
+    rows = [int(np.argmin(plen)), int(np.argsort(plen)[len(plen) // 2])]   # shortest and median prompt
+    _run_case(shape, wl, split=1, n_steps=3, sample_rows=rows)
+
+
+def test_moe_30b_a3b_layer_slice_batch128_sampled_rows():
+    shape = RI.QWEN3_30B_A3B.replace(name="qwen3_30b_a3b_shape_2layers", n_layers=2)
+    wl = RI.workload_moe_batch(shape, prompt_len=128)         # 128 sequences, all experts touched every step
+    _run_case(shape, wl, split=1, n_steps=3, sample_rows=[0, 77])

@@ -196,3 +196,231 @@ def test_teacher_forced_rollout_parity(amd, shape_name, split):
              "tiny_moe": RI.TINY_MOE}[shape_name]
     wl = RI.workload_tiny(shape, n_decode=32)
     teacher_forced_parity(pkg, synthetic, shape, wl, 32, split)
+
+
+# ---------------------------------------------------------------------------
+# free-running rollouts: finish rules, sharing, chunking, turns, determinism
+# ---------------------------------------------------------------------------
+
+def _engine(pkg, synthetic, shape, split=1, n_blocks=96, max_seqs=8, chunk=512, max_blocks=16, model_seed=0):
+    model = synthetic.model_from_shape(shape, model_seed, activation_split=split)
+    return model, pkg.RolloutEngine(model, n_blocks=n_blocks, max_seqs=max_seqs, max_chunk_tokens=chunk,
+                                    max_blocks_per_seq=max_blocks)
+
+
+def test_finish_rules_length_cap_and_inert_rows(amd):
+    """Length caps (forced EOS), inert finished rows, temperature 0 / 0.7: GPU free-running == oracle."""
+    pkg, synthetic = amd
+    shape = RI.TINY_DENSE
+    wl = RI.workload_tiny(shape, lens=(9, 17, 30, 12))
+    caps = [9 + 3, 17 + 1, 30 + 40, 12 + 6]           # prompt + allowed response tokens
+    temps = [1.0, 1.0, 0.0, 0.7]
+    say("finish rules: oracle")
+    om = O.OracleModel(shape, 0)
+    ro = O.OracleRollout(om, n_blocks=32)
+    ids = [ro.add_sequence(int(wl.seeds[i]), temps[i], caps[i]) for i in range(4)]
+    osteps = [ro.prefill_chunk(ids, wl.prompt_tokens)]
+    for _ in range(8):
+        osteps.append(ro.decode_step(ids))
+    say("finish rules: gpu")
+    model, eng = _engine(pkg, synthetic, shape)
+    for i in range(4):
+        eng.add_sequence(int(wl.seeds[i]), temps[i], max_ctx=caps[i])
+    out = eng.prefill([0, 1, 2, 3], wl.prompt_tokens)
+    torch.cuda.synchronize()
+    got = [(out.tokens.cpu().numpy().copy(), out.logprobs.cpu().numpy().copy())]
+    for _ in range(8):
+        out = eng.decode_step()
+        torch.cuda.synchronize()
+        got.append((out.tokens.cpu().numpy()[:4].copy(), out.logprobs.cpu().numpy().copy()))
+    for s, ((tok, lp), o) in enumerate(zip(got, osteps)):
+        assert list(tok) == o["tokens"], "step %d tokens %s vs %s" % (s, list(tok), o["tokens"])
+        assert np.abs(lp - np.array(o["logprobs"])).max() <= LOGPROB_BAR
+    assert list(eng.finished[:4].cpu().numpy()) == [int(f) for f in ro.finished]
+    assert list(eng.ctx_lens[:4].cpu().numpy()) == ro.ctx
+    # row 1 may emit exactly one token: the prefill's, forced to EOS; afterwards pad / 0.0
+    assert got[0][0][1] == shape.eos_token_id and got[1][0][1] == shape.pad_token_id and got[1][1][1] == 0.0
+    model.close()
+
+
+def test_shared_prefix_fork_matches_private_prefill(amd):
+    pkg, synthetic = amd
+    shape = RI.TINY_DENSE
+    tok = RI.workload_tiny(shape, lens=(23,)).prompt_tokens[0]
+    model, eng = _engine(pkg, synthetic, shape)
+    say("fork: private")
+    for s in (50, 51, 52):
+        eng.add_sequence(s, reserve_tokens=40)
+    priv = [eng.prefill([0, 1, 2], [tok] * 3, want_logits=True)]
+    priv_tok = [priv[0].tokens.cpu().numpy().copy()]
+    priv_z = [priv[0].logits.cpu().numpy().copy()]
+    for _ in range(5):
+        o = eng.decode_step(want_logits=True)
+        torch.cuda.synchronize()
+        priv_tok.append(o.tokens.cpu().numpy()[:3].copy())
+        priv_z.append(o.logits.cpu().numpy().copy())
+    say("fork: shared")
+    model2, eng2 = _engine(pkg, synthetic, shape)
+    base = eng2.add_sequence(0, reserve_tokens=40)
+    eng2.prefill([base], [tok[:-1]], sample_last=[False])
+    kids = [eng2.fork(base, s, reserve_tokens=40) for s in (50, 51, 52)]
+    assert eng2.block_lists[kids[0]][0] == eng2.block_lists[base][0]          # full page shared
+    assert eng2.block_lists[kids[0]][1] != eng2.block_lists[base][1]          # partial page copied
+    o = eng2.prefill(kids, [tok[-1:]] * 3, want_logits=True)
+    torch.cuda.synchronize()
+    sh_tok, sh_z = [o.tokens.cpu().numpy().copy()], [o.logits.cpu().numpy().copy()]
+    for _ in range(5):
+        eng2.tokens[base] = shape.pad_token_id
+        eng2.finished[base] = 1                                                # the donor row takes no part
+        o = eng2.decode_step(want_logits=True)
+        torch.cuda.synchronize()
+        sh_tok.append(o.tokens.cpu().numpy()[1:4].copy())
+        sh_z.append(o.logits.cpu().numpy()[1:4].copy())
+    for a, b in zip(priv_tok, sh_tok):
+        assert list(a) == list(b)
+    for a, b in zip(priv_z, sh_z):
+        assert np.abs(a - b).max() <= 2e-3          # chunk split of the prompt changes summation order only
+    # against the oracle (shared prefix == private copies is one of its own pins)
+    om = O.OracleModel(shape, 0)
+    ro = O.OracleRollout(om, n_blocks=16)
+    ids = [ro.add_sequence(s) for s in (50, 51, 52)]
+    r = ro.prefill_chunk(ids, [tok] * 3)
+    assert r["tokens"] == list(priv_tok[0])
+    model.close(); model2.close()
+
+
+@pytest.mark.parametrize("shape_name", ["tiny_dense", "tiny_moe"])
+def test_chunked_prefill_invariance(amd, shape_name):
+    pkg, synthetic = amd
+    shape = RI.TINY_DENSE if shape_name == "tiny_dense" else RI.TINY_MOE
+    tok = RI.workload_tiny(shape, lens=(37,)).prompt_tokens[0]
+    want = O.forward_full(O.OracleModel(shape, 0), [tok], logits_at=[np.array([36])])[0]
+    outs = []
+    for chunks in ([37], [16, 16, 5], [7, 30], [1] * 37):
+        say("chunked prefill %s %s" % (shape_name, chunks[:4]))
+        model, eng = _engine(pkg, synthetic, shape)
+        i = eng.add_sequence(1, reserve_tokens=64)
+        p, routes = 0, []
+        for c in chunks:
+            o = eng.prefill([i], [tok[p:p + c]], sample_last=[p + c == 37], want_logits=True, want_routing=True)
+            if o.routing is not None:
+                routes.append(o.routing.cpu().numpy())
+            p += c
+        torch.cuda.synchronize()
+        outs.append((o.logits.cpu().numpy()[0], int(o.tokens.cpu()[0]), np.concatenate(routes) if routes else None))
+        model.close()
+    for z, t, r in outs:
+        assert np.abs(z - want["logits"][0]).max() <= LOGIT_BAR
+        assert np.abs(z - outs[0][0]).max() <= 2e-3
+        assert t == outs[0][1]
+        if r is not None:
+            stable = want["gate_gap"] > TIE_GAP
+            same = (np.sort(r, -1) == np.sort(want["routing"], -1)).all(-1)
+            assert same[stable].all() and r.shape == want["routing"].shape
+
+
+def test_multi_turn_with_injected_embeddings(amd):
+    """Omni/agentic shape in small: injected embedding positions, then turns of (tool chunk -> sampled tokens)
+    with the KV carried across turns; GPU teacher-forced on the oracle's transcript."""
+    pkg, synthetic = amd
+    shape = RI.TINY_MOE
+    wl = RI.workload_omni_agentic(shape, batch=2, mm_lo=20, mm_hi=40, n_text=9, n_turns=2, tool_len=5, turn_decode=4)
+    om = O.OracleModel(shape, 0)
+    ro = O.OracleRollout(om, n_blocks=32)
+    ids = [ro.add_sequence(int(s)) for s in wl.seeds]
+    model, eng = _engine(pkg, synthetic, shape, n_blocks=32)
+    rows = [eng.add_sequence(int(s), reserve_tokens=128) for s in wl.seeds]
+    emb = []
+    for t, e in zip(wl.prompt_tokens, wl.prompt_embeds):
+        full = np.zeros((len(t), shape.d_model), np.uint16)
+        full[t < 0] = e
+        emb.append(full)
+    say("multi-turn: prompt with injected embeddings")
+    ro.prefill_chunk(ids, wl.prompt_tokens, wl.prompt_embeds, sample_last=[False, False])
+    eng.prefill(rows, wl.prompt_tokens, emb, sample_last=[False, False])
+    worst = 0.0
+    for turn in range(2):
+        tools = [wl.turns[j][turn].tool_tokens for j in range(2)]
+        o = ro.prefill_chunk(ids, tools, want_logits=True)
+        g = eng.prefill(rows, tools, forced=o["tokens"], want_logits=True)
+        torch.cuda.synchronize()
+        worst = max(worst, float(np.abs(g.logits.cpu().numpy() - np.stack(o["logits"])).max()))
+        for _ in range(wl.turns[0][turn].n_decode):     # the last sampled token is fed too: next turn needs its KV
+            o = ro.decode_step(ids, want_logits=True)
+            g = eng.decode_step(forced=torch.tensor(o["tokens"], dtype=torch.int32, device="cuda:0"),
+                                want_logits=True)
+            torch.cuda.synchronize()
+            worst = max(worst, float(np.abs(g.logits.cpu().numpy()[:2] - np.stack(o["logits"])).max()))
+    say("multi-turn worst |dlogit| %.5f" % worst)
+    assert worst <= LOGIT_BAR
+    assert list(eng.ctx_lens[:2].cpu().numpy()) == ro.ctx
+    model.close()
+
+
+def test_determinism_block_permutation_and_compaction(amd):
+    pkg, synthetic = amd
+    shape = RI.TINY_MOE
+    wl = RI.workload_tiny(shape, lens=(11, 40, 25, 18))
+
+    def run(perm=None, compact_at=None, caps=(1 << 30,) * 4):
+        model, eng = _engine(pkg, synthetic, shape, n_blocks=64)
+        if perm is not None:
+            eng.free_blocks = list(perm)
+        for i in range(4):
+            eng.add_sequence(int(wl.seeds[i]), max_ctx=caps[i], reserve_tokens=len(wl.prompt_tokens[i]) + 12)
+        o = eng.prefill([0, 1, 2, 3], wl.prompt_tokens, want_logits=True)
+        torch.cuda.synchronize()
+        hist = {i: [(int(o.tokens[i]), o.logits[i].cpu().numpy().copy())] for i in range(4)}
+        alive = [0, 1, 2, 3]
+        for s in range(8):
+            if compact_at == s:
+                keep = eng.compact()
+                alive = [alive[k] for k in keep]
+            o = eng.decode_step(want_logits=True)
+            torch.cuda.synchronize()
+            for r, i in enumerate(alive):
+                hist[i].append((int(o.tokens[r]), o.logits[r].cpu().numpy().copy()))
+        model.close()
+        return hist
+
+    say("determinism: two identical runs")
+    a, b = run(), run()
+    for i in range(4):
+        for (ta, za), (tb, zb) in zip(a[i], b[i]):
+            assert ta == tb and np.array_equal(za, zb)                 # bitwise: fixed reduction orders
+    say("determinism: permuted physical pages")
+    c = run(perm=np.random.default_rng(3).permutation(64))
+    for i in range(4):
+        for (ta, za), (tc, zc) in zip(a[i], c[i]):
+            assert ta == tc and np.array_equal(za, zc)
+    say("compaction: rows 0 and 3 capped, batch compacted mid-run")
+    caps = (11 + 3, 1 << 30, 1 << 30, 18 + 2)
+    d, e = run(caps=caps), run(caps=caps, compact_at=4)
+    for i in (1, 2):                                                     # survivors: same draws in any slot
+        n = min(len(d[i]), len(e[i]))
+        assert [t for t, _ in d[i][:n]] == [t for t, _ in e[i][:n]]
+        for (_, zd), (_, ze) in zip(d[i][:n], e[i][:n]):
+            assert np.abs(zd - ze).max() <= 2e-3
+
+
+def test_error_codes(amd):
+    pkg, synthetic = amd
+    B = pkg.binding
+    shape = RI.TINY_DENSE
+    cfg = synthetic.config_from_shape(shape)
+    bad = dict(cfg, head_dim=48)
+    with pytest.raises(B.RlxError) as e:
+        pkg.RolloutModel(bad, lambda l, n: RI.tensor_bf16(shape, 0, l, n))
+    assert e.value.code in (B.RLX_EUNSUPPORTED, B.RLX_EINVAL)
+    model, eng = _engine(pkg, synthetic, shape)
+    eng.add_sequence(1, reserve_tokens=32)
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda:0")
+    keep = eng.workspace
+    eng.workspace = small
+    with pytest.raises(B.RlxError) as e:
+        eng.decode_step()
+    assert e.value.code == B.RLX_ENOMEM and "workspace" in str(e.value)
+    eng.workspace = keep
+    eng.prefill([0], [RI.workload_tiny(shape, lens=(5,)).prompt_tokens[0]])   # the handle still works after an error
+    torch.cuda.synchronize()
+    model.close()
