@@ -17,7 +17,7 @@
  *  - All matrices are bf16 with logical shape [out_features, in_features] (y = x W^T).
  *    The projection matrices and the LM head are passed in the library's packed
  *    streaming layout, produced from row-major storage by rlx_pack_weight; the
- *    embedding table, the norm gains and the MoE router stay row-major.
+ *    embedding table and the norm gains stay row-major.
  *  - The caller owns every buffer (weights, KV pool, workspace, inputs, outputs);
  *    weights must outlive the model handle.  The library allocates device memory
  *    only in rlx_model_create (a few KB of pointer tables) and frees it in
@@ -77,7 +77,7 @@ typedef struct {
  *   wq (P) [n_q_heads*head_dim, d_model]; wk, wv (P) [n_kv_heads*head_dim, d_model]
  *   wo (P) [d_model, n_q_heads*head_dim]
  *   dense: w_gate_up (G) gate and up [d_ff, d_model] each; w_down (P) [d_model, d_ff]; w_router NULL
- *   MoE:   w_router [n_experts, d_model]; w_gate_up (G) gate and up [n_experts, d_ff_expert, d_model] each;
+ *   MoE:   w_router (P) [n_experts, d_model]; w_gate_up (G) gate and up [n_experts, d_ff_expert, d_model] each;
  *          w_down (P) [n_experts, d_model, d_ff_expert]
  * (G): the gate and up matrices of a SwiGLU block interleaved into one packed [2 f, k]
  * matrix by rlx_pack_gate_up.
@@ -228,8 +228,8 @@ RLX_API int rlx_op_linear(const void* x, const void* w, float* y, int32_t n_toke
 #define RLX_K_OPROJ 6       /* output projection                              */
 #define RLX_K_GATEUP 7      /* gate/up projection + SwiGLU (dense or grouped) */
 #define RLX_K_DOWN 8        /* down projection (dense or grouped)             */
-#define RLX_K_ROUTER 9      /* MoE router + top-k + capture                   */
-#define RLX_K_GROUP 10      /* MoE grouping of (token, slot) pairs by expert  */
+#define RLX_K_ROUTER 9      /* MoE router logits                              */
+#define RLX_K_GROUP 10      /* MoE top-k + capture + grouping by expert       */
 #define RLX_K_LMHEAD 11     /* LM head + log-sum-exp / Gumbel-max partials    */
 /*
  * From now on every stride-th launch of `kernel_class` is bracketed with

@@ -69,7 +69,7 @@ struct Workspace {
   TokenMeta meta;
   float* h;          // [T, d]
   bf16_t* xb;        // [planes][T, d]; every bf16 activation buffer below has `planes` copies
-  float* xf;         // [T, d] (MoE)
+  float* router;     // [planes][T, E] router logits (MoE)
   float* qkv;        // [planes][T, qkv_dim]
   bf16_t* q;         // [T, q_dim]
   bf16_t* ob;        // [T, q_dim]
@@ -107,10 +107,11 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
   w.meta.qtile_seq = (int32_t*)take((size_t)QT * 4);
   w.meta.qtile_q0 = (int32_t*)take((size_t)QT * 4);
   w.meta.n_qtiles = (int32_t*)take(4);
+  w.meta.tickets = (uint32_t*)take(8 * 4);
   w.h = (float*)take((size_t)T * c.d_model * 4);
   const int PL = c.activation_split ? 2 : 1;
   w.xb = (bf16_t*)take(frag_act_elems(T, c.d_model, PL) * 2);
-  w.xf = c.n_experts ? (float*)take((size_t)T * c.d_model * 4) : nullptr;
+  w.router = c.n_experts ? (float*)take((size_t)plane_rows(T) * c.n_experts * 4) : nullptr;
   w.qkv = (float*)take((size_t)plane_rows(T) * qkv_dim * 4);
   w.q = (bf16_t*)take((size_t)PL * T * qdim * 2);
   w.ob = (bf16_t*)take(frag_act_elems(T, qdim, PL) * 2);
@@ -208,7 +209,7 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
     RLX_LAUNCH(RLX_K_OPROJ, gemm_store(linear1(m->wo[l], d, qdim), ob, T, w.planes, d, s_o, st));
     pend_planes = w.planes; pend_n = s_o;
 
-    RLX_LAUNCH(RLX_K_NORM, norm(m->ffn_norm[l], nullptr, T, xb, w.xf));
+    RLX_LAUNCH(RLX_K_NORM, norm(m->ffn_norm[l], nullptr, T, xb, nullptr));
     if (c.n_experts == 0) {
       const Act act = make_act(w.act, T, c.d_ff, PL);
       RLX_LAUNCH(RLX_K_GATEUP, gemm_swiglu(m->w_gate_up[l], c.d_ff, d, xb, T, act, st));
@@ -216,13 +217,13 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
       RLX_LAUNCH(RLX_K_DOWN, gemm_store(linear1(m->w_down[l], d, c.d_ff), act, T, w.planes, d, s_d, st));
       pend_planes = w.planes; pend_n = s_d;
     } else {
+      const int s_r = small ? gemm_plan_splits(c.n_experts, d, gemm_max_splits()) : 1;
+      RLX_LAUNCH(RLX_K_ROUTER, gemm_store(linear1(m->w_router[l], c.n_experts, d), xb, T, w.router, c.n_experts, s_r, st));
       RouterArgs ra = {};
-      ra.xf = w.xf; ra.w_router = m->w_router[l]; ra.T = T; ra.d = d; ra.E = c.n_experts; ra.top_k = c.top_k;
+      ra.logits = w.router; ra.n_planes = s_r; ra.T = T; ra.E = c.n_experts; ra.top_k = c.top_k;
       ra.topk_idx = w.topk_idx; ra.topk_w = w.topk_w; ra.routing_out = io.out_routing; ra.layer = l;
       ra.n_layers = c.n_layers; ra.tok_live = w.meta.tok_live;
-      RLX_LAUNCH(RLX_K_ROUTER, moe_router(ra, st));
-      RLX_LAUNCH(RLX_K_GROUP, moe_group(w.topk_idx, T, c.top_k, c.n_experts, w.counts, w.group_off, w.sorted_token,
-                                        w.pair_pos, st));
+      RLX_LAUNCH(RLX_K_GROUP, moe_route(ra, w.group_off, w.sorted_token, w.pair_pos, w.meta.tickets, st));
       const Act act = make_act(w.act, T * c.top_k, c.d_ff_expert, PL);
       RLX_LAUNCH(RLX_K_GATEUP, gemm_grouped_swiglu(m->w_gate_up[l], c.n_experts, c.d_ff_expert, d, xb,
                                                    w.sorted_token, w.group_off, T, act, st));

@@ -8,6 +8,7 @@ namespace {
 
 __global__ void meta_decode_kernel(TokenMeta m, int n, const int32_t* ctx, const uint8_t* fin) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < 8) m.tickets[i] = 0u;
   if (i >= n) return;
   uint8_t live = fin[i] ? 0 : 1;
   m.tok_seq[i] = i;
@@ -22,6 +23,7 @@ __global__ void meta_decode_kernel(TokenMeta m, int n, const int32_t* ctx, const
 __global__ void meta_prefill_kernel(TokenMeta m, int n_seqs, int total, const int32_t* cu, const int32_t* ctx,
                                     const uint8_t* sample_last) {
   __shared__ int tile_base[1025];
+  if (threadIdx.x < 8) m.tickets[threadIdx.x] = 0u;
   // per-token fields: binary search of the owning sequence
   for (int t = threadIdx.x; t < total; t += blockDim.x) {
     int lo = 0, hi = n_seqs - 1;

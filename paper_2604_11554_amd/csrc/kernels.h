@@ -63,6 +63,7 @@ struct TokenMeta {        // per packed token, built on the device at the start 
   int32_t* qtile_seq;     // prefill attention tiles: sequence, first query index
   int32_t* qtile_q0;
   int32_t* n_qtiles;      // [1]
+  uint32_t* tickets;      // [8] counters zeroed at the start of every call
 };
 hipError_t meta_decode(const TokenMeta& m, int n_seqs, const int32_t* ctx_lens, const uint8_t* finished,
                        hipStream_t st);
@@ -144,19 +145,19 @@ hipError_t attention_prefill(const AttnArgs& a, hipStream_t st);
 
 // ---- moe.hip ----
 struct RouterArgs {
-  const float* xf;           // [T, d] fp32 normalised hidden
-  const bf16_t* w_router;    // [E, d]
-  int T, d, E, top_k;
+  const float* logits;       // [n_planes][T, E] router logits (split-K planes, summed in plane order)
+  int n_planes;
+  int T, E, top_k;
   int32_t* topk_idx;         // [T, top_k]
   float* topk_w;             // [T, top_k]
   int32_t* routing_out;      // optional [T, n_layers, top_k] (this layer's slice is written)
   int layer, n_layers;
   const uint8_t* tok_live;   // rows that are inert leave routing_out untouched
 };
-hipError_t moe_router(const RouterArgs& a, hipStream_t st);
-// stable grouping of the T*top_k (token, slot) pairs by expert
-hipError_t moe_group(const int32_t* topk_idx, int T, int top_k, int E, int32_t* counts, int32_t* group_off,
-                     int32_t* sorted_token, int32_t* pair_pos, hipStream_t st);
+// top-k + renormalised weights + routing capture + stable grouping of the T*top_k (token, slot) pairs by expert
+// `ticket`: one zeroed counter in device memory (left zero again on completion)
+hipError_t moe_route(const RouterArgs& a, int32_t* group_off, int32_t* sorted_token, int32_t* pair_pos,
+                     unsigned int* ticket, hipStream_t st);
 
 // ---- sampling.hip ----
 struct FinalizeArgs {

@@ -1,4 +1,5 @@
-// MoE routing: router logits in fp32, softmax top-k with renormalised weights,
+// MoE routing: router logits come from the skinny GEMM (activations as two bf16 terms, fp32
+// accumulate, split-K planes); here: softmax top-k with renormalised weights,
 // capture of the chosen expert ids (the record Rollout Routing Replay consumes,
 // paper Sec. 5.5), and a stable, deterministic grouping of (token, slot) pairs by expert.
 #include "kernels.h"
@@ -8,45 +9,36 @@ namespace {
 
 constexpr int MAX_E = 256;
 
-// one workgroup per token: 4 waves take experts round-robin, lanes stride over d
-__global__ __launch_bounds__(256) void moe_router_kernel(RouterArgs a) {
-  __shared__ float logit[MAX_E];
-  const int t = blockIdx.x;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const float* x = a.xf + (size_t)t * a.d;
-  for (int e = wave; e < a.E; e += 4) {
-    const bf16_t* w = a.w_router + (size_t)e * a.d;
-    float acc = 0.f;
-    for (int k = lane * 8; k < a.d; k += 64 * 8) {
-      u32x4 wv = *reinterpret_cast<const u32x4*>(w + k);
-      f32x4 x0 = *reinterpret_cast<const f32x4*>(x + k);
-      f32x4 x1 = *reinterpret_cast<const f32x4*>(x + k + 4);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        float wl = __uint_as_float(wv[j] << 16), wh = __uint_as_float(wv[j] & 0xFFFF0000u);
-        float xa = (j < 2) ? x0[2 * j] : x1[2 * j - 4];
-        float xb = (j < 2) ? x0[2 * j + 1] : x1[2 * j - 3];
-        acc += xa * wl;
-        acc += xb * wh;
-      }
-    }
-    acc = wave_sum(acc);
-    if (lane == 0) logit[e] = acc;
-  }
-  __syncthreads();
-  if (wave != 0) return;
-
-  // wave 0: top-k by (logit descending, id ascending); lane holds ids lane, lane+64, ...
+// Top-k of one token by one wave: lane holds experts lane, lane+64, ...; selection by (logit descending,
+// id ascending); weights = softmax over the chosen logits (== softmax over all experts, renormalised).
+__device__ __forceinline__ void wave_topk(const RouterArgs& a, int t, int lane, int32_t* idx_out, float* w_out) {
+  // all plane loads go out first (clamped addresses), then the sums in plane order
+  constexpr int MAXP = 16;
   float v[MAX_E / 64];
+  float part[MAX_E / 64][MAXP];
 #pragma unroll
-  for (int j = 0; j < MAX_E / 64; ++j) v[j] = (lane + 64 * j < a.E) ? logit[lane + 64 * j] : -INFINITY;
+  for (int j = 0; j < MAX_E / 64; ++j) {
+    const int e = lane + 64 * j;
+    const int ec = e < a.E ? e : 0;
+#pragma unroll
+    for (int s = 0; s < MAXP; ++s) {
+      const int sc = s < a.n_planes ? s : 0;
+      part[j][s] = a.logits[((size_t)sc * a.T + t) * a.E + ec];
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < MAX_E / 64; ++j) {
+    float acc = 0.f;
+#pragma unroll
+    for (int s = 0; s < MAXP; ++s) acc += s < a.n_planes ? part[j][s] : 0.f;
+    v[j] = (lane + 64 * j) < a.E ? acc : -INFINITY;
+  }
   float mx = -INFINITY;
 #pragma unroll
   for (int j = 0; j < MAX_E / 64; ++j) mx = fmaxf(mx, v[j]);
   mx = wave_max(mx);
-  float sel_e[8];
-  int sel_i[8];
-  float denom = 0.f;
+  float my_e = 0.f, denom = 0.f;
+  int my_i = 0;
   for (int k = 0; k < a.top_k; ++k) {
     float bv = -INFINITY; int bi = 0x7FFFFFFF;
 #pragma unroll
@@ -58,9 +50,9 @@ __global__ __launch_bounds__(256) void moe_router_kernel(RouterArgs a) {
       int oi = __shfl_xor(bi, o, WAVE);
       if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
     }
-    sel_i[k] = bi;
-    sel_e[k] = __expf(bv - mx);
-    denom += sel_e[k];
+    const float ev = __expf(bv - mx);
+    denom += ev;
+    if (lane == k) { my_e = ev; my_i = bi; }
     if ((bi & 63) == lane) {
 #pragma unroll
       for (int j = 0; j < MAX_E / 64; ++j)
@@ -68,83 +60,110 @@ __global__ __launch_bounds__(256) void moe_router_kernel(RouterArgs a) {
     }
   }
   if (lane < a.top_k) {
-    // softmax over all experts then renormalised over the chosen ones == softmax over the chosen logits
-    int idx = 0; float w = 0.f;
-    for (int k = 0; k < a.top_k; ++k)
-      if (k == lane) { idx = sel_i[k]; w = sel_e[k] / denom; }
-    a.topk_idx[t * a.top_k + lane] = idx;
-    a.topk_w[t * a.top_k + lane] = w;
+    idx_out[lane] = my_i;
+    w_out[lane] = my_e / denom;
     if (a.routing_out && (!a.tok_live || a.tok_live[t]))
-      a.routing_out[((size_t)t * a.n_layers + a.layer) * a.top_k + lane] = idx;
+      a.routing_out[((size_t)t * a.n_layers + a.layer) * a.top_k + lane] = my_i;
   }
 }
 
-__global__ __launch_bounds__(256) void moe_count_kernel(const int32_t* idx, int n_pairs, int32_t* counts) {
-  __shared__ int sh[4];
-  const int e = blockIdx.x;
-  int c = 0;
-  for (int p = threadIdx.x; p < n_pairs; p += 256) c += (idx[p] == e);
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, WAVE);
-  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = c;
-  __syncthreads();
-  if (threadIdx.x == 0) counts[e] = sh[0] + sh[1] + sh[2] + sh[3];
-}
-
-// workgroup e writes its pairs, in pair order, at [off_e, off_e + count_e)
-__global__ __launch_bounds__(256) void moe_scatter_kernel(const int32_t* idx, int n_pairs, int top_k, int E,
-                                                          const int32_t* counts, int32_t* group_off,
-                                                          int32_t* sorted_token, int32_t* pair_pos) {
-  __shared__ int sh[4];
-  __shared__ int base_sh;
-  const int e = blockIdx.x;
+// Stable counting sort of the T*top_k (token, slot) pairs by expert, by one workgroup of four waves.
+// Wave w owns the contiguous segment w of the pair list.  Pass 1: per-wave histograms.  Scan: offsets by
+// (expert, wave).  Pass 2: a pair's position = offset + its rank among equal experts, in pair order (the
+// lanes holding the same expert are found with one ballot per id bit).
+__device__ void group_pairs_by_expert(const int32_t* idx, int n_pairs, int top_k, int E, int32_t* group_off,
+                                      int32_t* sorted_token, int32_t* pair_pos, int32_t* hist /*[4][MAX_E]*/,
+                                      int32_t* base /*[4][MAX_E]*/) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int c = 0;
-  for (int i = threadIdx.x; i < e; i += 256) c += counts[i];
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, WAVE);
-  if (lane == 0) sh[wave] = c;
+  for (int i = threadIdx.x; i < 4 * MAX_E; i += 256) hist[i] = 0;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    int off = sh[0] + sh[1] + sh[2] + sh[3];
-    base_sh = off;
-    group_off[e] = off;
-    if (e == E - 1) group_off[E] = off + counts[e];
+  const int seg = ((n_pairs + 3) / 4 + 63) / 64 * 64;       // segment length, a multiple of the wave size
+  const int p_begin = wave * seg, p_end = min(n_pairs, p_begin + seg);
+  for (int p0 = p_begin; p0 < p_end; p0 += 64) {
+    const int p = p0 + lane;
+    if (p < p_end) {
+      const int e = idx[p];
+      if (e >= 0 && e < E) atomicAdd(&hist[wave * MAX_E + e], 1);
+    }
   }
   __syncthreads();
-  int base = base_sh;
-  for (int p0 = 0; p0 < n_pairs; p0 += 256) {
-    int p = p0 + threadIdx.x;
-    bool hit = p < n_pairs && idx[p] == e;
-    unsigned long long bal = __ballot(hit);
-    int before = __popcll(bal & ((1ull << lane) - 1ull));
-    int wcount = __popcll(bal);
-    __syncthreads();                       // previous iteration's reads of sh are done
-    if (lane == 0) sh[wave] = wcount;
-    __syncthreads();
-    int woff = 0;
-    for (int w = 0; w < wave; ++w) woff += sh[w];
-    if (hit) {
-      int pos = base + woff + before;
+  if (wave == 0) {   // exclusive scan over experts of the four-wave totals; lane holds experts 4*lane .. 4*lane+3
+    int tot[4], run = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int e = 4 * lane + j;
+      tot[j] = hist[e] + hist[MAX_E + e] + hist[2 * MAX_E + e] + hist[3 * MAX_E + e];
+      run += tot[j];
+    }
+    int incl = run;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      int v = __shfl_up(incl, o, WAVE);
+      if (lane >= o) incl += v;
+    }
+    int off = incl - run;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int e = 4 * lane + j;
+      int b0 = off;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) { base[w * MAX_E + e] = b0; b0 += hist[w * MAX_E + e]; }
+      if (e < E) group_off[e] = off;
+      off += tot[j];
+    }
+    if (lane == 63) group_off[E] = incl;
+  }
+  __syncthreads();
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  for (int p0 = p_begin; p0 < p_end; p0 += 64) {
+    const int p = p0 + lane;
+    const bool ok = p < p_end;
+    int e = ok ? idx[p] : -1;
+    if (e < 0 || e >= E) e = -1;
+    unsigned long long same = __ballot(e >= 0);
+#pragma unroll
+    for (int bit = 0; bit < 8; ++bit) {
+      const unsigned long long bal = __ballot((e >> bit) & 1);
+      same &= ((e >> bit) & 1) ? bal : ~bal;
+    }
+    if (e >= 0) {
+      const int b0 = base[wave * MAX_E + e];
+      const int pos = b0 + __popcll(same & lt);
       sorted_token[pos] = p / top_k;
       pair_pos[p] = pos;
+      if ((same >> lane) >> 1 == 0) base[wave * MAX_E + e] = b0 + __popcll(same);   // highest lane of the group
     }
-    base += sh[0] + sh[1] + sh[2] + sh[3];
   }
+}
+
+// grid = ceil(T / 4): every wave does the top-k of one token; the workgroup that finishes last (atomic
+// ticket) groups all pairs by expert.  `ticket` must be zero on entry and is reset for the next launch.
+__global__ __launch_bounds__(256) void moe_route_kernel(RouterArgs a, int32_t* group_off, int32_t* sorted_token,
+                                                        int32_t* pair_pos, unsigned int* ticket) {
+  __shared__ int32_t hist[4 * MAX_E];
+  __shared__ int32_t base[4 * MAX_E];
+  __shared__ bool last;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t < a.T) wave_topk(a, t, threadIdx.x & 63, a.topk_idx + (size_t)t * a.top_k, a.topk_w + (size_t)t * a.top_k);
+  __threadfence();                     // this workgroup's indices are visible device-wide before the ticket
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned int n = atomicAdd(ticket, 1u);
+    last = (n == gridDim.x - 1);
+  }
+  __syncthreads();
+  if (!last) return;
+  __threadfence();                     // acquire: see every other workgroup's indices
+  group_pairs_by_expert(a.topk_idx, a.T * a.top_k, a.top_k, a.E, group_off, sorted_token, pair_pos, hist, base);
+  if (threadIdx.x == 0) *ticket = 0u;
 }
 
 }  // namespace
 
-hipError_t moe_router(const RouterArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL(moe_router_kernel, dim3(a.T), dim3(256), 0, st, a);
-  return hipGetLastError();
-}
-
-hipError_t moe_group(const int32_t* topk_idx, int T, int top_k, int E, int32_t* counts, int32_t* group_off,
-                     int32_t* sorted_token, int32_t* pair_pos, hipStream_t st) {
-  hipLaunchKernelGGL(moe_count_kernel, dim3(E), dim3(256), 0, st, topk_idx, T * top_k, counts);
-  hipLaunchKernelGGL(moe_scatter_kernel, dim3(E), dim3(256), 0, st, topk_idx, T * top_k, top_k, E, counts, group_off,
-                     sorted_token, pair_pos);
+hipError_t moe_route(const RouterArgs& a, int32_t* group_off, int32_t* sorted_token, int32_t* pair_pos,
+                     unsigned int* ticket, hipStream_t st) {
+  hipLaunchKernelGGL(moe_route_kernel, dim3((a.T + 3) / 4), dim3(256), 0, st, a, group_off, sorted_token, pair_pos,
+                     ticket);
   return hipGetLastError();
 }
 

@@ -20,7 +20,7 @@ import torch
 
 from . import binding as B
 
-PACKED = ("lm_head", "wq", "wk", "wv", "wo", "w_down")   # streamed by the skinny GEMM
+PACKED = ("lm_head", "wq", "wk", "wv", "wo", "w_down", "w_router")   # streamed by the skinny GEMM
 PER_LAYER = ("attn_norm", "wq", "wk", "wv", "wo", "q_norm", "k_norm", "ffn_norm", "w_gate_up", "w_down",
              "w_router")
 
