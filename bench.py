@@ -82,6 +82,26 @@ def step_bytes(shape, ctx_sum_plus_b, batch, touched=None):
     return w + kv_tok * ctx_sum_plus_b + kv_tok * batch
 
 
+def traffic_record(workload, kernel_class):
+    """Measured-over-algorithmic HBM byte ratio of the dominant kernel from the committed counter summary, or
+    None when there is none for this workload/kernel or the kernel source has changed since it was taken."""
+    import hashlib
+    if kernel_class != "attn":
+        return None
+    path = os.path.join(ROOT, "profiles", "attn_decode_%s_traffic.txt" % workload)
+    src = os.path.join(ROOT, "paper_2604_11554_amd", "csrc", "attention.hip")
+    if not (os.path.exists(path) and os.path.exists(src)):
+        return None
+    rec = {}
+    for line in open(path):
+        if "=" in line and not line.startswith("#"):
+            k, v = line.split("=", 1)
+            rec[k.strip()] = v.strip()
+    if rec.get("source_sha256") != hashlib.sha256(open(src, "rb").read()).hexdigest():
+        return None
+    return float(rec["ratio_measured_over_algorithmic"])
+
+
 def cpu_baseline(shape, wl, budget_s=25.0):
     """The oracle's decode step timed on the host: 1- and 3-layer slices of the same shape with the
     full batch and start-of-decode context lengths (synthetic KV contents), scaled to all layers."""
@@ -139,6 +159,8 @@ def main():
     ap.add_argument("--split", type=int, default=-1, help="activation_split (default 1: two bf16 terms per activation)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel", default="auto", help="kernel class for the roofline record")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 256 MiB device copy (reference of known size for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -176,6 +198,13 @@ def main():
                             max_blocks_per_seq=max_blocks)
     for i in range(bsz):
         eng.add_sequence(int(wl.seeds[i]), float(wl.temperature[i]), max_ctx=int(plen[i]) + n_decode)
+
+    if args.copy_probe:
+        src = torch.ones(64 << 20, dtype=torch.float32, device=dev)      # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- prefill (untimed for the metric; reported) ----
     torch.cuda.synchronize()
@@ -260,8 +289,17 @@ def main():
         step = (i * stride) // launches_per_step
         ach_bytes.append(kernel_bytes(shape, dom, int((ctx0 + step + 1).sum()), touched)
                          if dom in ("attn", "qkv", "oproj", "gateup", "down", "lmhead") else 0)
+    # cost of an empty event pair on this stream (the brackets themselves), subtracted from every sample
+    null_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(64)]
+    for a_, b_ in null_ev:
+        a_.record(); b_.record()
+    torch.cuda.synchronize()
+    ev_overhead = float(np.median([a_.elapsed_time(b_) for a_, b_ in null_ev]))
+    durs = [max(d - ev_overhead, 1e-4) for d in durs]
     kern_ms = float(np.mean(durs)) if durs else float("nan")
     achieved = float(np.sum(ach_bytes)) / (float(np.sum(durs)) * 1e-3) / 1e9 if durs else float("nan")
+    ratio = traffic_record(args.workload, dom)
+    traffic = None if ratio is None or not durs else ratio * float(np.mean(ach_bytes))
     step_b = np.mean([step_bytes(shape, int((ctx0 + s + 1).sum()), bsz, touched) for s in range(K)])
     step_gbs = step_b / (ms_step * 1e-3) / 1e9
     fin = int(eng.finished[:bsz].sum().item())
@@ -281,8 +319,10 @@ def main():
         "step_roofline": {"bound": "hbm", "achieved": step_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                           "frac": step_gbs / HBM_PEAK_GBS, "bytes_per_step": float(step_b)},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "avg_launch_ms": kern_ms,
-                     "launches_timed": len(durs), "per_step_ms_by_class": per_class},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "avg_launch_ms": kern_ms,
+                     "bytes_per_launch": float(np.mean(ach_bytes)) if durs else None,
+                     "event_pair_overhead_ms": ev_overhead, "launches_timed": len(durs),
+                     "per_step_ms_by_class": per_class},
     }
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(shape, wl)
