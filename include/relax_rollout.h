@@ -223,8 +223,8 @@ RLX_API int rlx_op_linear(const void* x, const void* w, float* y, int32_t n_toke
 #define RLX_K_NORM 1        /* residual add + RMSNorm                         */
 #define RLX_K_QKV 2         /* q|k|v projection                               */
 #define RLX_K_ROPE 3        /* q/k norm + rotary embedding + KV append        */
-#define RLX_K_ATTN 4        /* paged attention (decode: per-split partials)   */
-#define RLX_K_ATTN_MERGE 5  /* decode: merge of the splits                    */
+#define RLX_K_ATTN 4        /* paged attention (decode: per-share partials)   */
+#define RLX_K_ATTN_MERGE 5  /* decode: merge of pairs that straddle shares     */
 #define RLX_K_OPROJ 6       /* output projection                              */
 #define RLX_K_GATEUP 7      /* gate/up projection + SwiGLU (dense or grouped) */
 #define RLX_K_DOWN 8        /* down projection (dense or grouped)             */

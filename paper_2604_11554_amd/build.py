@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librelax_rollout.so")
-SOURCES = ["api.hip", "gemm.hip", "elementwise.hip", "attention.hip", "moe.hip", "sampling.hip"]
+SOURCES = ["api.hip", "gemm.hip", "elementwise.hip", "attention.hip", "attention_decode.hip", "moe.hip", "sampling.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 

@@ -61,6 +61,7 @@ struct rlx_model {
   std::vector<const bf16_t*> attn_norm, wq, wk, wv, wo, q_norm, k_norm, ffn_norm, w_gate_up, w_down, w_router;
   double* inv_freq;   // device, [head_dim / 2]
   int device;
+  int attn_wgs;       // decode attention grid: two workgroups per compute unit
 };
 
 namespace {
@@ -73,7 +74,8 @@ struct Workspace {
   float* qkv;        // [planes][T, qkv_dim]
   bf16_t* q;         // [T, q_dim]
   bf16_t* ob;        // [T, q_dim]
-  float* attn_part;  // [S][Hq][n_splits][hd+2]
+  float* attn_part;  // [attn_wgs][2][Hq/Hkv][hd+4] decode partials of straddling (sequence, KV head) pairs
+  int32_t *attn_prefix, *attn_wg_seq, *attn_hdr;   // decode attention plan
   float* planes;     // split-K planes of the o / down projections
   bf16_t* act;       // dense [T, F]; MoE [T*top_k, Fe]
   float* moe_y;      // [T*top_k, d]
@@ -83,6 +85,8 @@ struct Workspace {
   float* lm_part;    // [S][tiles][4]
   size_t bytes;
 };
+
+constexpr int ATTN_WGS_MAX = 1024;   // decode attention grid limit (plan arrays are sized for it)
 
 int plane_rows(int T) { return T <= 256 ? gemm_max_splits() * T : T; }
 
@@ -108,6 +112,7 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
   w.meta.qtile_q0 = (int32_t*)take((size_t)QT * 4);
   w.meta.n_qtiles = (int32_t*)take(4);
   w.meta.tickets = (uint32_t*)take(8 * 4);
+  w.meta.rope_cs = (float2*)take((size_t)S * (c.head_dim / 2) * sizeof(float2));
   w.h = (float*)take((size_t)T * c.d_model * 4);
   const int PL = c.activation_split ? 2 : 1;
   w.xb = (bf16_t*)take(frag_act_elems(T, c.d_model, PL) * 2);
@@ -115,8 +120,10 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
   w.qkv = (float*)take((size_t)plane_rows(T) * qkv_dim * 4);
   w.q = (bf16_t*)take((size_t)PL * T * qdim * 2);
   w.ob = (bf16_t*)take(frag_act_elems(T, qdim, PL) * 2);
-  const int n_splits = (max_blocks * 16 + ATTN_SPLIT_TOKENS - 1) / ATTN_SPLIT_TOKENS;
-  w.attn_part = (float*)take((size_t)S * c.n_q_heads * n_splits * (c.head_dim + 2) * 4);
+  w.attn_part = (float*)take((size_t)ATTN_WGS_MAX * 2 * (c.n_q_heads / c.n_kv_heads) * (c.head_dim + 4) * 4);
+  w.attn_prefix = (int32_t*)take((size_t)(S + 1) * 4);
+  w.attn_wg_seq = (int32_t*)take((size_t)ATTN_WGS_MAX * 4);
+  w.attn_hdr = (int32_t*)take(2 * 4);
   w.planes = (float*)take((size_t)plane_rows(T) * c.d_model * 4);
   if (c.n_experts) {
     const size_t P = (size_t)T * c.top_k;
@@ -185,25 +192,34 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
     const int s_qkv = small ? gemm_plan_splits(qkv_dim, d, gemm_max_splits()) : 1;
     RLX_LAUNCH(RLX_K_QKV, gemm_store(wqkv, xb, T, w.qkv, qkv_dim, s_qkv, st));
 
+    bf16_t* pool_layer = pool + (size_t)l * n_blocks * block_elems(c);
     RopeArgs r = {};
     r.qkv = w.qkv; r.n_planes = s_qkv;
     r.q_gain = c.qk_norm ? m->q_norm[l] : nullptr; r.k_gain = c.qk_norm ? m->k_norm[l] : nullptr;
-    r.inv_freq = m->inv_freq; r.T = T; r.Hq = c.n_q_heads; r.Hkv = c.n_kv_heads; r.hd = c.head_dim;
+    r.inv_freq = m->inv_freq; r.rope_cs = io.decode ? w.meta.rope_cs : nullptr;
+    r.T = T; r.Hq = c.n_q_heads; r.Hkv = c.n_kv_heads; r.hd = c.head_dim;
     r.eps = c.rms_eps; r.tok_seq = w.meta.tok_seq; r.tok_pos = w.meta.tok_pos; r.tok_live = w.meta.tok_live;
     r.block_table = io.block_table; r.max_blocks = io.max_blocks;
-    r.pool_layer = pool + (size_t)l * n_blocks * block_elems(c); r.n_blocks = n_blocks; r.q_out = qb;
+    r.pool_layer = pool_layer; r.n_blocks = n_blocks; r.q_out = qb;
     RLX_LAUNCH(RLX_K_ROPE, qk_rope_append(r, st));
-
-    AttnArgs at = {};
-    at.q = qb; at.pool_layer = r.pool_layer; at.n_blocks = n_blocks;
-    at.Hq = c.n_q_heads; at.Hkv = c.n_kv_heads; at.hd = c.head_dim;
-    at.block_table = io.block_table; at.max_blocks = io.max_blocks; at.ctx_lens = io.ctx_lens;
-    at.n_seqs = io.n_seqs; at.tok_live = w.meta.tok_live; at.part = w.attn_part;
-    at.n_splits = (io.max_blocks * 16 + ATTN_SPLIT_TOKENS - 1) / ATTN_SPLIT_TOKENS;
-    at.cu_seqlens = io.cu_seqlens; at.qtile_seq = w.meta.qtile_seq; at.qtile_q0 = w.meta.qtile_q0;
-    at.n_qtiles = w.meta.n_qtiles; at.max_qtiles = T / 16 + io.n_seqs + 1; at.o = ob;
-    RLX_LAUNCH(RLX_K_ATTN, io.decode ? attention_decode(at, st) : attention_prefill(at, st));
-    if (io.decode) RLX_LAUNCH(RLX_K_ATTN_MERGE, attention_decode_merge(at, st));
+    if (io.decode) {
+      AttnDecodeArgs at = {};
+      at.q = qb; at.pool_layer = pool_layer; at.n_blocks = n_blocks;
+      at.Hq = c.n_q_heads; at.Hkv = c.n_kv_heads; at.hd = c.head_dim;
+      at.block_table = io.block_table; at.max_blocks = io.max_blocks; at.ctx_lens = io.ctx_lens;
+      at.n_seqs = io.n_seqs; at.unit_prefix = w.attn_prefix; at.wg_seq = w.attn_wg_seq; at.plan_hdr = w.attn_hdr;
+      at.n_wgs = m->attn_wgs; at.part = w.attn_part; at.o = ob;
+      RLX_LAUNCH(RLX_K_ATTN, attention_decode(at, st));
+      RLX_LAUNCH(RLX_K_ATTN_MERGE, attention_decode_merge(at, st));
+    } else {
+      AttnArgs at = {};
+      at.q = qb; at.pool_layer = pool_layer; at.n_blocks = n_blocks;
+      at.Hq = c.n_q_heads; at.Hkv = c.n_kv_heads; at.hd = c.head_dim;
+      at.block_table = io.block_table; at.max_blocks = io.max_blocks; at.ctx_lens = io.ctx_lens;
+      at.cu_seqlens = io.cu_seqlens; at.qtile_seq = w.meta.qtile_seq; at.qtile_q0 = w.meta.qtile_q0;
+      at.n_qtiles = w.meta.n_qtiles; at.max_qtiles = T / 16 + io.n_seqs + 1; at.o = ob;
+      RLX_LAUNCH(RLX_K_ATTN, attention_prefill(at, st));
+    }
 
     const int s_o = small ? gemm_plan_splits(d, qdim, gemm_max_splits()) : 1;
     RLX_LAUNCH(RLX_K_OPROJ, gemm_store(linear1(m->wo[l], d, qdim), ob, T, w.planes, d, s_o, st));
@@ -333,6 +349,9 @@ int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* wt, rlx_mod
   std::vector<double> inv(c.head_dim / 2);
   for (int i = 0; i < c.head_dim / 2; ++i) inv[i] = pow((double)c.rope_theta, -2.0 * i / c.head_dim);
   hipError_t e = hipGetDevice(&m->device);
+  int n_cu = 0;
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, m->device);
+  m->attn_wgs = 2 * n_cu < ATTN_WGS_MAX ? (2 * n_cu > 0 ? 2 * n_cu : 1) : ATTN_WGS_MAX;
   if (e == hipSuccess) e = hipMalloc((void**)&m->inv_freq, inv.size() * sizeof(double));
   if (e == hipSuccess) e = hipMemcpy(m->inv_freq, inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice);
   if (e != hipSuccess) {
@@ -419,7 +438,9 @@ int rollout_decode_step(const rlx_model* m, void* kv_pool, int64_t n_blocks, voi
   if (w.bytes > workspace_bytes)
     return fail(RLX_ENOMEM, "workspace too small: need %zu bytes, have %zu", w.bytes, workspace_bytes);
   hipStream_t st = (hipStream_t)stream;
-  RLX_HIP(meta_decode(w.meta, n_seqs, ctx_lens_inout, finished_inout, st));
+  RLX_HIP(meta_decode(w.meta, n_seqs, ctx_lens_inout, finished_inout, m->inv_freq, m->cfg.head_dim, st));
+  RLX_HIP(attention_decode_plan(n_seqs, ctx_lens_inout, w.meta.tok_live, m->cfg.n_kv_heads, m->attn_wgs, w.attn_prefix,
+                                w.attn_wg_seq, w.attn_hdr, st));
   StepIO io = {};
   io.n_seqs = n_seqs; io.T = n_seqs; io.decode = true;
   io.tokens = tokens_inout; io.ctx_lens = ctx_lens_inout; io.ctx_lens_rw = ctx_lens_inout;

@@ -1,0 +1,354 @@
+// Decode attention over the paged bf16 KV pool, load-balanced by key count.
+//
+// One new token per sequence; the 16 MFMA columns of a tile are the query heads of one KV head
+// (group <= 16), so a KV page is read once for all heads of its group.  The work of a step is the
+// sequence of 32-key units of all (sequence, KV head) pairs laid end to end; every workgroup takes an
+// equal, contiguous share of it (the plan is built once per step, contexts being the same for every
+// layer), so the grid is exactly resident (two workgroups per compute unit) and every workgroup streams
+// for the whole kernel instead of paying its start-up and wind-down latency per 256 keys.  Within a
+// share the four waves take units round-robin, each keeping the next unit's pages in flight while it
+// works on the current one.  Where a (sequence, KV head) pair lies inside one share its output is
+// final; where it straddles shares each part leaves (o, m, l) and a small second kernel merges the
+// parts in share order (deterministic).
+#include "attn_core.h"
+
+namespace rlx {
+namespace {
+
+template <int HD>
+struct PageRegs {
+  bf16x8 k0[HD / 32], k1[HD / 32], vf[HD / 16];
+  bool ok0, ok1;
+};
+
+// A run: up to 64 consecutive units of one (sequence, KV head) inside this workgroup's share (64 units = one
+// register window of the block table).  A segment -- the part of a pair that lies in the share -- is one or
+// more runs; the online softmax state lives across the runs of a segment.  All fields are wave-uniform.
+struct Run {
+  int seq, kvh, ctx, np;     // np: units of the whole pair
+  int pb, pe;                // units [pb, pe) of the pair are this share's segment
+  int lo, hi;                // units [lo, hi) of the pair are this run
+  bool seg_start, seg_end, valid;
+};
+
+template <int HD, int PL>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_decode_kernel(AttnDecodeArgs a) {
+  constexpr int DT = HD / 16, KS = HD / 32, PS = HD + 4;
+  __shared__ f32x4 lds_o[2 * DT * WAVE];
+  __shared__ float lds_ml[2 * 2 * WAVE];
+  __shared__ u32x4 lds_q[PL * KS * WAVE];            // query fragments of the current segment, MFMA operand order
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c16 = lane & 15, g = lane >> 4;
+  const int group = a.Hq / a.Hkv;
+  const bool col_ok = c16 < group;
+  const int w = blockIdx.x;
+  const int C = a.plan_hdr[0], U = a.plan_hdr[1];
+  int u = w * C;
+  const int u_end = min(U, u + C);
+  if (u >= u_end) return;                            // uniform over the workgroup
+  int seq = a.wg_seq[w];
+  const float scale = rsqrtf((float)HD);
+  const size_t page = (size_t)2 * 16 * HD;
+
+  // ---- run generator: the per-sequence plan entries are held in a 64-lane register window ----
+  int seq0 = seq;
+  int32_t wpre = a.unit_prefix[min(seq0 + lane, a.n_seqs)];
+  int32_t wctx = a.ctx_lens[min(seq0 + lane, a.n_seqs - 1)];
+  int rem_lo = 0, rem_hi = 0;                        // rest of the current segment
+  Run seg = {};
+  auto next_run = [&](Run& r) {
+    if (rem_lo < rem_hi) {                           // the segment continues in another table window
+      r = seg;
+      r.lo = rem_lo; r.hi = min(rem_hi, rem_lo + 64);
+      r.seg_start = false; r.seg_end = r.hi == rem_hi;
+      rem_lo = r.hi;
+      return;
+    }
+    r.valid = false;
+    while (u < u_end && seq < a.n_seqs) {
+      if (seq - seq0 > 62) {                         // slide the window (rare: 63 sequences inside one share)
+        seq0 = seq;
+        wpre = a.unit_prefix[min(seq0 + lane, a.n_seqs)];
+        wctx = a.ctx_lens[min(seq0 + lane, a.n_seqs - 1)];
+      }
+      const int p0 = __builtin_amdgcn_readlane(wpre, seq - seq0);
+      const int np = __builtin_amdgcn_readlane(wpre, seq - seq0 + 1) - p0;
+      if (np == 0) { ++seq; continue; }              // inert sequence: no units
+      const int base = a.Hkv * p0;
+      const int kvh = (u - base) / np;
+      if (kvh >= a.Hkv) return;                      // inconsistent plan: stop rather than index past the pool
+      const int xs = base + kvh * np;                // first unit of this (sequence, KV head)
+      seg.seq = seq; seg.kvh = kvh; seg.np = np;
+      seg.ctx = __builtin_amdgcn_readlane(wctx, seq - seq0);
+      seg.pb = u - xs; seg.pe = min(np, u_end - xs);
+      seg.valid = true;
+      r = seg;
+      r.lo = seg.pb; r.hi = min(seg.pe, seg.pb + 64);
+      r.seg_start = true; r.seg_end = r.hi == seg.pe;
+      rem_lo = r.hi; rem_hi = seg.pe;
+      u = xs + seg.pe;
+      if (seg.pe == np && kvh == a.Hkv - 1) ++seq;
+      return;
+    }
+  };
+  // block-table window of a run: lane holds the entries of blocks 2 lo + lane and 2 lo + 64 + lane
+  auto load_window = [&](const Run& r, int32_t& t0, int32_t& t1) {
+    const int32_t* table = a.block_table + (size_t)r.seq * a.max_blocks;
+    const int jb = 2 * r.lo + lane;
+    const int j0 = min(jb, a.max_blocks - 1), j1 = min(jb + 64, a.max_blocks - 1);
+    t0 = table[j0]; t1 = table[j1];                  // unconditional, clamped; masked below
+    if (jb >= a.max_blocks) t0 = -1;
+    if (jb + 64 >= a.max_blocks) t1 = -1;
+  };
+  // the waves share the fetch of a segment's query fragments; they stay in LDS (registers hold two units of pages)
+  auto stage_queries = [&](const Run& r) {
+    const int head = r.kvh * group + c16;
+    for (int f = wave; f < PL * KS; f += 4) {
+      const int p = f / KS, ks = f % KS;
+      const u32x4 z = {0u, 0u, 0u, 0u};
+      lds_q[f * WAVE + lane] = col_ok ? *reinterpret_cast<const u32x4*>(a.q.p + p * a.q.plane +
+                                                                       ((size_t)r.seq * a.Hq + head) * HD + 32 * ks + 8 * g)
+                                      : z;
+    }
+  };
+  auto qf = [&](int p, int, int ks) { return __builtin_bit_cast(bf16x8, lds_q[(p * KS + ks) * WAVE + lane]); };
+
+  Run cur, nxt;
+  next_run(cur);
+  if (!cur.valid) return;
+  int32_t tb0, tb1, tbn0, tbn1;
+  load_window(cur, tb0, tb1);
+  stage_queries(cur);
+  __syncthreads();
+
+  // page loads of unit i of run r (table window t0/t1), all unconditional
+  auto issue = [&](const Run& r, int32_t t0, int32_t t1, int i, PageRegs<HD>& pr) {
+    const int rel = 2 * (i - r.lo);                  // uniform, 0 .. 126
+    const int32_t sel = rel < 64 ? t0 : t1;
+    int64_t b0 = __builtin_amdgcn_readlane(sel, rel & 63);
+    int64_t b1 = __builtin_amdgcn_readlane(sel, (rel + 1) & 63);
+    const bool has1 = (2 * i + 1) * 16 < r.ctx + 1;
+    pr.ok0 = b0 >= 0 && b0 < a.n_blocks;
+    pr.ok1 = has1 && b1 >= 0 && b1 < a.n_blocks;
+    if (!pr.ok0) b0 = 0;                             // keep the loads in bounds; scores are masked
+    if (!pr.ok1) b1 = b0;
+    const bf16_t* kp0 = a.pool_layer + ((size_t)b0 * a.Hkv + r.kvh) * page;
+    const bf16_t* kp1 = a.pool_layer + ((size_t)b1 * a.Hkv + r.kvh) * page;
+    const bf16_t* vp0 = kp0 + 16 * HD;
+    const bf16_t* vp1 = kp1 + 16 * HD;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      pr.k0[ks] = load_bf16x8(kp0 + c16 * HD + 32 * ks + 8 * g);
+      pr.k1[ks] = load_bf16x8(kp1 + c16 * HD + 32 * ks + 8 * g);
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+      pr.vf[dt] = load_2x4(vp0 + (size_t)(16 * dt + c16) * 16 + 4 * g, vp1 + (size_t)(16 * dt + c16) * 16 + 4 * g);
+  };
+
+  WaveState<HD, 1> st;
+  PageRegs<HD> ra, rb;
+  issue(cur, tb0, tb1, min(cur.lo + wave, cur.hi - 1), ra);
+  bool first_seg = true;
+
+  for (;;) {                                         // one run per iteration; uniform
+    next_run(nxt);
+    const bool more = nxt.valid;
+    if (!more) nxt = cur;                            // keeps the look-ahead loads below in bounds
+    load_window(nxt, tbn0, tbn1);
+    if (cur.seg_start) st.reset();
+    const int key_end = cur.ctx + 1;
+    const int pos_col[1] = {cur.ctx};
+    auto step = [&](int i, const PageRegs<HD>& pr, bool valid) {
+      pair_step<HD, 1, PL>(st, pr.k0, pr.k1, pr.vf, qf, 32 * i, 32 * i + 16, pr.ok0 && valid, pr.ok1 && valid, key_end,
+                           pos_col, scale, g);
+    };
+
+    // Two register sets alternate: while one unit is multiplied the next one's pages are in flight.  The loop
+    // body has no branch around a load (a unit index past the wave's last one is clamped and its step masked),
+    // so the hardware counters let each step wait for its own pages only.  The slot after the wave's last unit
+    // fetches its first unit of the next run, so the stream does not drain between runs.
+    const int first = cur.lo + wave;
+    const int n_my = first < cur.hi ? (cur.hi - first + 3) / 4 : 0;
+    const int last = first + 4 * (n_my - 1);
+    const int nfirst = min(nxt.lo + wave, nxt.hi - 1);
+    for (int k = 0; k < n_my; k += 2) {
+      const int i = first + 4 * k;
+      issue(cur, tb0, tb1, min(i + 4, last), rb);
+      asm volatile("" ::: "memory");                 // query fragments are re-read from LDS, not kept in registers
+      __builtin_amdgcn_sched_barrier(0);             // the next unit's loads go out before this unit's math
+      step(i, ra, true);
+      {
+        const bool beyond = i + 8 > last;
+        Run rs = cur;
+        if (beyond) rs = nxt;
+        issue(rs, beyond ? tbn0 : tb0, beyond ? tbn1 : tb1, beyond ? nfirst : i + 8, ra);
+      }
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_sched_barrier(0);
+      step(i + 4, rb, k + 1 < n_my);
+    }
+    if (n_my == 0) issue(nxt, tbn0, tbn1, nfirst, ra);   // this wave had no unit in the run
+
+    if (cur.seg_end) {
+      st.finish_denominators();
+      merge_waves<HD, 1>(st, lds_o, lds_ml, wave, lane);
+      if (wave == 0 && col_ok) {
+        const int head = cur.kvh * group + c16;
+        if (cur.pb == 0 && cur.pe == cur.np) {
+          store_column<HD, 1, PL>(st, 0, a.o, cur.seq, head, g);
+        } else {                                     // lane holds column c16, rows d = 16 dt + 4 g + {0..3}
+          float* dst = a.part + ((size_t)(w * 2 + (first_seg ? 0 : 1)) * group + c16) * PS;
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4*>(dst + 16 * dt + 4 * g) = st.o[0][dt];
+          if (g == 0) { dst[HD] = st.m[0]; dst[HD + 1] = st.l[0]; }
+        }
+      }
+      first_seg = false;
+    }
+    if (!more) break;
+    if (nxt.seg_start) stage_queries(nxt);           // every wave is past the merge: the old fragments are dead
+    __syncthreads();                                 // new fragments visible; wave 0 is done with the merge buffers
+    cur = nxt; tb0 = tbn0; tb1 = tbn1;
+  }
+}
+
+// One 64-thread workgroup per (sequence, KV head): inert rows are zeroed, pairs that straddle shares are
+// merged in share order; pairs that one share covered are already final.
+template <int HD>
+__global__ __launch_bounds__(64) void attn_decode_merge_kernel(AttnDecodeArgs a) {
+  constexpr int PS = HD + 4;
+  const int seq = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
+  const int lane = threadIdx.x;
+  const int group = a.Hq / a.Hkv, PL = a.o.planes, mtiles = a.o.mtiles();
+  const int np = a.unit_prefix[seq + 1] - a.unit_prefix[seq];
+  const int C = a.plan_hdr[0];
+  const int xs = a.Hkv * a.unit_prefix[seq] + kvh * np;
+  const int w_first = np ? xs / C : 0, w_last = np ? (xs + np - 1) / C : 0;
+  if (np && w_first == w_last) return;
+  for (int uu = lane; uu < group * HD / 8; uu += 64) {
+    const int j = uu / (HD / 8), d0 = (uu % (HD / 8)) * 8;
+    float m = -INFINITY, l = 0.f;
+    float o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = 0.f;
+    if (np) {
+      for (int w0 = w_first; w0 <= w_last; w0 += 4) {
+        f32x4 va[4], vb[4];
+        float ms[4], ls[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {                // loads first (clamped), merges after
+          const int wc = w0 + q <= w_last ? w0 + q : w_last;
+          const int slot = xs <= wc * C ? 0 : 1;     // first segment of its share or not
+          const float* p = a.part + ((size_t)(wc * 2 + slot) * group + j) * PS;
+          va[q] = *reinterpret_cast<const f32x4*>(p + d0);
+          vb[q] = *reinterpret_cast<const f32x4*>(p + d0 + 4);
+          ms[q] = p[HD]; ls[q] = p[HD + 1];
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if (w0 + q > w_last || ms[q] == -INFINITY) continue;
+          const float mn = fmaxf(m, ms[q]);
+          const float aa = (m == -INFINITY) ? 0.f : __expf(m - mn);
+          const float ab = __expf(ms[q] - mn);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            o[e] = o[e] * aa + va[q][e] * ab;
+            o[4 + e] = o[4 + e] * aa + vb[q][e] * ab;
+          }
+          l = l * aa + ls[q] * ab;
+          m = mn;
+        }
+      }
+    }
+    bf16_t hi[8], lo[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) split_bf16(l > 0.f ? o[e] / l : 0.f, hi[e], lo[e]);
+    bf16_t* dst = a.o.p + frag_act_offset(seq, (kvh * group + j) * HD + d0, 0, mtiles, PL);
+    u32x4 pk = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16),
+                (uint32_t)hi[4] | ((uint32_t)hi[5] << 16), (uint32_t)hi[6] | ((uint32_t)hi[7] << 16)};
+    *reinterpret_cast<u32x4*>(dst) = pk;
+    if (PL == 2) {
+      u32x4 pk2 = {(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16),
+                   (uint32_t)lo[4] | ((uint32_t)lo[5] << 16), (uint32_t)lo[6] | ((uint32_t)lo[7] << 16)};
+      *reinterpret_cast<u32x4*>(dst + 512) = pk2;
+    }
+  }
+}
+
+// One workgroup: exclusive prefix of the per-sequence unit counts, the share size, and the sequence in which
+// each share starts.
+__global__ __launch_bounds__(1024) void attn_plan_kernel(int n_seqs, const int32_t* ctx, const uint8_t* live, int Hkv,
+                                                          int n_wgs, int32_t* unit_prefix, int32_t* wg_seq,
+                                                          int32_t* hdr) {
+  __shared__ int sh[1024];
+  __shared__ int carry;
+  const int tid = threadIdx.x;
+  if (tid == 0) carry = 0;
+  __syncthreads();
+  for (int base = 0; base < n_seqs; base += 1024) {
+    const int i = base + tid;
+    const int v = (i < n_seqs && live[i]) ? (ctx[i] + 1 + 31) / 32 : 0;
+    sh[tid] = v;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+      const int t = tid >= o ? sh[tid - o] : 0;
+      __syncthreads();
+      sh[tid] += t;
+      __syncthreads();
+    }
+    if (i < n_seqs) unit_prefix[i] = carry + sh[tid] - v;
+    __syncthreads();
+    if (tid == 1023) carry += sh[1023];
+    __syncthreads();
+  }
+  const int per_head = carry;
+  if (tid == 0) unit_prefix[n_seqs] = per_head;
+  __syncthreads();                                   // the prefix is read back below
+  const int total = per_head * Hkv;
+  int C = 4 * ((total + 4 * n_wgs - 1) / (4 * n_wgs));   // a multiple of four: the four waves get equal counts
+  if (C < 4) C = 4;
+  if (tid == 0) { hdr[0] = C; hdr[1] = total; }
+  for (int w = tid; w < n_wgs; w += 1024) {
+    const int u0 = w * C;
+    int lo = 0, hi = n_seqs - 1;                     // largest s with Hkv * prefix[s] <= u0
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (Hkv * unit_prefix[mid] <= u0) lo = mid; else hi = mid - 1;
+    }
+    wg_seq[w] = u0 < total ? lo : n_seqs;
+  }
+}
+
+}  // namespace
+
+hipError_t attention_decode_plan(int n_seqs, const int32_t* ctx_lens, const uint8_t* tok_live, int Hkv, int n_wgs,
+                                 int32_t* unit_prefix, int32_t* wg_seq, int32_t* hdr, hipStream_t st) {
+  hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(1024), 0, st, n_seqs, ctx_lens, tok_live, Hkv, n_wgs, unit_prefix,
+                     wg_seq, hdr);
+  return hipGetLastError();
+}
+
+hipError_t attention_decode(const AttnDecodeArgs& a, hipStream_t st) {
+  dim3 grid(a.n_wgs);
+  const bool two = a.q.planes == 2;
+  if (a.hd == 128) {
+    if (two) hipLaunchKernelGGL((attn_decode_kernel<128, 2>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((attn_decode_kernel<128, 1>), grid, dim3(256), 0, st, a);
+  } else {
+    if (two) hipLaunchKernelGGL((attn_decode_kernel<64, 2>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((attn_decode_kernel<64, 1>), grid, dim3(256), 0, st, a);
+  }
+  return hipGetLastError();
+}
+
+hipError_t attention_decode_merge(const AttnDecodeArgs& a, hipStream_t st) {
+  dim3 grid(a.n_seqs * a.Hkv);
+  if (a.hd == 128) hipLaunchKernelGGL((attn_decode_merge_kernel<128>), grid, dim3(64), 0, st, a);
+  else hipLaunchKernelGGL((attn_decode_merge_kernel<64>), grid, dim3(64), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace rlx

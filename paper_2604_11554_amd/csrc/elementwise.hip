@@ -2,20 +2,31 @@
 // (residual add / split-K reduce / MoE combine) + RMSNorm, fused per-head q/k
 // RMSNorm + rotary embedding + paged KV append, KV page copy.
 #include "kernels.h"
+#include "rope.h"
 
 namespace rlx {
 namespace {
 
-__global__ void meta_decode_kernel(TokenMeta m, int n, const int32_t* ctx, const uint8_t* fin) {
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < 8) m.tickets[i] = 0u;
-  if (i >= n) return;
+// grid = n sequences, 64 threads: thread 0 writes the row's metadata, lane i < hd/2 the rotary factors of the
+// row's new position (the same for every layer, so they are computed once per step and not per layer)
+__global__ void meta_decode_kernel(TokenMeta m, int n, const int32_t* ctx, const uint8_t* fin, const double* inv_freq,
+                                   int half) {
+  const int i = blockIdx.x;
+  const int gi = blockIdx.x * blockDim.x + threadIdx.x;
+  if (gi < 8) m.tickets[gi] = 0u;
+  const int pos = ctx[i];
+  for (int j = threadIdx.x; j < half; j += blockDim.x) {
+    float c, s;
+    rope_cos_sin(pos, inv_freq, true, j, c, s);
+    m.rope_cs[(size_t)i * half + j] = float2{c, s};
+  }
+  if (threadIdx.x != 0) return;
   uint8_t live = fin[i] ? 0 : 1;
   m.tok_seq[i] = i;
-  m.tok_pos[i] = ctx[i];
+  m.tok_pos[i] = pos;
   m.tok_live[i] = live;
   m.sample_row[i] = i;
-  m.sample_pos[i] = ctx[i] + 1;
+  m.sample_pos[i] = pos + 1;
   m.sample_on[i] = live;
 }
 
@@ -211,21 +222,8 @@ __global__ __launch_bounds__(256) void qk_rope_append_kernel(RopeArgs a) {
   const bool act = lane < half;
   const int li = act ? lane : 0;
 
-  // all plane loads first, then the adds in plane order
-  float x0 = 0.f, x1 = 0.f;
-  for (int p0 = 0; p0 < a.n_planes; p0 += 8) {
-    float u0[8], u1[8];
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const bool ok = act && p0 + q < a.n_planes;
-      const size_t off = ok ? (size_t)(p0 + q) * plane : 0;
-      u0[q] = src[off + li];
-      u1[q] = src[off + li + half];
-      if (!ok) { u0[q] = 0.f; u1[q] = 0.f; }
-    }
-#pragma unroll
-    for (int q = 0; q < 8; ++q) { x0 += u0[q]; x1 += u1[q]; }
-  }
+  float x0, x1;
+  sum_head_planes(src, plane, a.n_planes, act, li, half, x0, x1);
 
   const bool is_q = h < a.Hq, is_k = !is_q && h < a.Hq + a.Hkv;
   int64_t blk = -1;
@@ -237,23 +235,14 @@ __global__ __launch_bounds__(256) void qk_rope_append_kernel(RopeArgs a) {
   const int slot = pos & 15;
 
   if (is_q || is_k) {
-    float c = 1.f, s = 0.f;
-    if (act) {
-      double ang = (double)pos * a.inv_freq[lane];
-      double sd, cd;
-      sincos(ang, &sd, &cd);
-      c = (float)cd; s = (float)sd;
+    float c, s, y0, y1;
+    if (a.rope_cs) {
+      const float2 cs = a.rope_cs[(size_t)t * half + li];
+      c = cs.x; s = cs.y;
+    } else {
+      rope_cos_sin(pos, a.inv_freq, act, li, c, s);
     }
-    const bf16_t* gain = is_q ? a.q_gain : a.k_gain;
-    if (gain) {
-      float ss = wave_sum(x0 * x0 + x1 * x1);
-      float rstd = 1.0f / sqrtf(ss / (float)hd + a.eps);
-      if (act) {
-        x0 = x0 * rstd * bf16_to_f32(gain[lane]);
-        x1 = x1 * rstd * bf16_to_f32(gain[lane + half]);
-      }
-    }
-    float y0 = x0 * c - x1 * s, y1 = x1 * c + x0 * s;
+    head_norm_rope(x0, x1, is_q ? a.q_gain : a.k_gain, hd, a.eps, act, lane, c, s, y0, y1);
     if (act) {
       if (is_q) {
         bf16_t* dst = a.q_out.p + ((size_t)t * a.Hq + h) * hd;
@@ -340,8 +329,9 @@ __global__ void kv_copy_kernel(bf16_t* pool, int64_t n_blocks, size_t block_elem
 }  // namespace
 
 hipError_t meta_decode(const TokenMeta& m, int n_seqs, const int32_t* ctx_lens, const uint8_t* finished,
-                       hipStream_t st) {
-  hipLaunchKernelGGL(meta_decode_kernel, dim3((n_seqs + 255) / 256), dim3(256), 0, st, m, n_seqs, ctx_lens, finished);
+                       const double* inv_freq, int head_dim, hipStream_t st) {
+  hipLaunchKernelGGL(meta_decode_kernel, dim3(n_seqs), dim3(64), 0, st, m, n_seqs, ctx_lens, finished, inv_freq,
+                     head_dim / 2);
   return hipGetLastError();
 }
 

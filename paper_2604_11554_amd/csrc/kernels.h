@@ -64,9 +64,10 @@ struct TokenMeta {        // per packed token, built on the device at the start 
   int32_t* qtile_q0;
   int32_t* n_qtiles;      // [1]
   uint32_t* tickets;      // [8] counters zeroed at the start of every call
+  float2* rope_cs;        // [n_seqs][hd/2] decode: (cos, sin) of the new position's rotary angles
 };
 hipError_t meta_decode(const TokenMeta& m, int n_seqs, const int32_t* ctx_lens, const uint8_t* finished,
-                       hipStream_t st);
+                       const double* inv_freq, int head_dim, hipStream_t st);
 hipError_t meta_prefill(const TokenMeta& m, int n_seqs, int total_tokens, const int32_t* cu_seqlens,
                         const int32_t* ctx_lens, const uint8_t* sample_last, hipStream_t st);
 hipError_t embed_tokens(const bf16_t* embed, int vocab, int d, const int32_t* tokens, const bf16_t* input_embeds,
@@ -98,6 +99,7 @@ struct RopeArgs {
   const bf16_t* q_gain;      // [hd] or null
   const bf16_t* k_gain;
   const double* inv_freq;    // [hd/2]
+  const float2* rope_cs;     // optional [T][hd/2] precomputed (cos, sin) of each token's position
   int T, Hq, Hkv, hd;
   float eps;
   const int32_t* tok_seq; const int32_t* tok_pos; const uint8_t* tok_live;
@@ -119,29 +121,41 @@ hipError_t sum_planes(const float* planes, int n_planes, size_t n, float* y, hip
 hipError_t kv_copy_blocks(bf16_t* pool, int64_t n_blocks, int n_layers, size_t block_elems, const int32_t* src,
                           const int32_t* dst, int n, hipStream_t st);
 
-// ---- attention.hip ----
-constexpr int ATTN_SPLIT_TOKENS = 256;   // keys per decode split
-struct AttnArgs {
+// ---- attention.hip (prefill), attention_decode.hip ----
+struct AttnArgs {            // prefill
   RowAct q;                  // [planes][T, Hq*hd]
   const bf16_t* pool_layer;
   int64_t n_blocks;
   int Hq, Hkv, hd;
   const int32_t* block_table; int max_blocks;
   const int32_t* ctx_lens;   // cached length before this call, per sequence
-  // decode
-  int n_seqs;
-  const uint8_t* tok_live;
-  float* part;               // [n_seqs][Hq][n_splits][hd+2]
-  int n_splits;
-  // prefill
   const int32_t* cu_seqlens;
   const int32_t* qtile_seq; const int32_t* qtile_q0; const int32_t* n_qtiles;
   int max_qtiles;
   Act o;                     // [T, Hq*hd] in fragment order (input of the output projection)
 };
-hipError_t attention_decode(const AttnArgs& a, hipStream_t st);        // per-split partials
-hipError_t attention_decode_merge(const AttnArgs& a, hipStream_t st);  // splits -> o
 hipError_t attention_prefill(const AttnArgs& a, hipStream_t st);
+
+struct AttnDecodeArgs {      // one new token per sequence: row = sequence slot
+  RowAct q;                  // [planes][n_seqs, Hq*hd] rotated queries
+  const bf16_t* pool_layer;  // this layer's pages (the new token's K and V already appended)
+  int64_t n_blocks;
+  int Hq, Hkv, hd;
+  const int32_t* block_table; int max_blocks;
+  const int32_t* ctx_lens;   // cached length before this call = position of the new token
+  int n_seqs;
+  // plan of the step (attention_decode_plan): 32-key units of all (sequence, KV head) pairs end to end
+  const int32_t* unit_prefix;  // [n_seqs + 1] exclusive prefix of the per-sequence unit counts (0 for inert rows)
+  const int32_t* wg_seq;       // [n_wgs] sequence in which workgroup w's share starts
+  const int32_t* plan_hdr;     // [2] units per share, total units
+  int n_wgs;                   // grid size: shares of the unit sequence
+  float* part;               // [n_wgs][2][Hq/Hkv][hd+4] partial (o, m, l) of a share's first / other straddling pair
+  Act o;                     // [n_seqs, Hq*hd] in fragment order (input of the output projection)
+};
+hipError_t attention_decode_plan(int n_seqs, const int32_t* ctx_lens, const uint8_t* tok_live, int Hkv, int n_wgs,
+                                 int32_t* unit_prefix, int32_t* wg_seq, int32_t* hdr, hipStream_t st);
+hipError_t attention_decode(const AttnDecodeArgs& a, hipStream_t st);
+hipError_t attention_decode_merge(const AttnDecodeArgs& a, hipStream_t st);   // straddling pairs, inert rows
 
 // ---- moe.hip ----
 struct RouterArgs {
