@@ -123,34 +123,38 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   stage_queries(cur);
   __syncthreads();
 
-  // page loads of unit i of run r (table window t0/t1), all unconditional
-  auto issue = [&](const Run& r, int32_t t0, int32_t t1, int i, PageRegs<HD>& pr) {
+  // Page loads of unit i of run r (table window t0/t1).  They are unconditional: a slot with no unit behind it
+  // (`live` false, i clamped into the run) reads one fixed row of the pool with every lane, which costs cache
+  // hits and no memory traffic.
+  auto issue = [&](const Run& r, int32_t t0, int32_t t1, int i, bool live, PageRegs<HD>& pr) {
     const int rel = 2 * (i - r.lo);                  // uniform, 0 .. 126
     const int32_t sel = rel < 64 ? t0 : t1;
     int64_t b0 = __builtin_amdgcn_readlane(sel, rel & 63);
     int64_t b1 = __builtin_amdgcn_readlane(sel, (rel + 1) & 63);
     const bool has1 = (2 * i + 1) * 16 < r.ctx + 1;
-    pr.ok0 = b0 >= 0 && b0 < a.n_blocks;
-    pr.ok1 = has1 && b1 >= 0 && b1 < a.n_blocks;
+    pr.ok0 = live && b0 >= 0 && b0 < a.n_blocks;
+    pr.ok1 = live && has1 && b1 >= 0 && b1 < a.n_blocks;
     if (!pr.ok0) b0 = 0;                             // keep the loads in bounds; scores are masked
     if (!pr.ok1) b1 = b0;
     const bf16_t* kp0 = a.pool_layer + ((size_t)b0 * a.Hkv + r.kvh) * page;
     const bf16_t* kp1 = a.pool_layer + ((size_t)b1 * a.Hkv + r.kvh) * page;
     const bf16_t* vp0 = kp0 + 16 * HD;
     const bf16_t* vp1 = kp1 + 16 * HD;
+    const int koff0 = pr.ok0 ? c16 * HD + 8 * g : 0, koff1 = pr.ok1 ? c16 * HD + 8 * g : 0;
+    const int voff0 = pr.ok0 ? c16 * 16 + 4 * g : 0, voff1 = pr.ok1 ? c16 * 16 + 4 * g : 0;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      pr.k0[ks] = load_bf16x8(kp0 + c16 * HD + 32 * ks + 8 * g);
-      pr.k1[ks] = load_bf16x8(kp1 + c16 * HD + 32 * ks + 8 * g);
+      pr.k0[ks] = load_bf16x8(kp0 + koff0 + 32 * ks);
+      pr.k1[ks] = load_bf16x8(kp1 + koff1 + 32 * ks);
     }
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
-      pr.vf[dt] = load_2x4(vp0 + (size_t)(16 * dt + c16) * 16 + 4 * g, vp1 + (size_t)(16 * dt + c16) * 16 + 4 * g);
+      pr.vf[dt] = load_2x4(vp0 + 256 * dt + voff0, vp1 + 256 * dt + voff1);
   };
 
   WaveState<HD, 1> st;
   PageRegs<HD> ra, rb;
-  issue(cur, tb0, tb1, min(cur.lo + wave, cur.hi - 1), ra);
+  issue(cur, tb0, tb1, min(cur.lo + wave, cur.hi - 1), cur.lo + wave < cur.hi, ra);
   bool first_seg = true;
 
   for (;;) {                                         // one run per iteration; uniform
@@ -174,9 +178,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int n_my = first < cur.hi ? (cur.hi - first + 3) / 4 : 0;
     const int last = first + 4 * (n_my - 1);
     const int nfirst = min(nxt.lo + wave, nxt.hi - 1);
+    const bool nlive = more && nxt.lo + wave < nxt.hi;
     for (int k = 0; k < n_my; k += 2) {
       const int i = first + 4 * k;
-      issue(cur, tb0, tb1, min(i + 4, last), rb);
+      issue(cur, tb0, tb1, min(i + 4, last), i + 4 <= last, rb);
       asm volatile("" ::: "memory");                 // query fragments are re-read from LDS, not kept in registers
       __builtin_amdgcn_sched_barrier(0);             // the next unit's loads go out before this unit's math
       step(i, ra, true);
@@ -184,13 +189,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         const bool beyond = i + 8 > last;
         Run rs = cur;
         if (beyond) rs = nxt;
-        issue(rs, beyond ? tbn0 : tb0, beyond ? tbn1 : tb1, beyond ? nfirst : i + 8, ra);
+        issue(rs, beyond ? tbn0 : tb0, beyond ? tbn1 : tb1, beyond ? nfirst : i + 8, !beyond || nlive, ra);
       }
       asm volatile("" ::: "memory");
       __builtin_amdgcn_sched_barrier(0);
       step(i + 4, rb, k + 1 < n_my);
     }
-    if (n_my == 0) issue(nxt, tbn0, tbn1, nfirst, ra);   // this wave had no unit in the run
+    if (n_my == 0) issue(nxt, tbn0, tbn1, nfirst, nlive, ra);   // this wave had no unit in the run
 
     if (cur.seg_end) {
       st.finish_denominators();
