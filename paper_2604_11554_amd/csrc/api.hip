@@ -61,6 +61,7 @@ struct rlx_model {
   std::vector<const bf16_t*> attn_norm, wq, wk, wv, wo, q_norm, k_norm, ffn_norm, w_gate_up, w_down, w_router;
   double* inv_freq;   // device, [head_dim / 2]
   int device;
+  int n_units;        // compute units of the device
   int attn_wgs;       // decode attention grid: two workgroups per compute unit
 };
 
@@ -189,7 +190,7 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
     wqkv.seg[1] = m->wk[l]; wqkv.rows[1] = kvdim;
     wqkv.seg[2] = m->wv[l]; wqkv.rows[2] = kvdim;
     wqkv.N = qkv_dim; wqkv.K = d;
-    const int s_qkv = small ? gemm_plan_splits(qkv_dim, d, gemm_max_splits()) : 1;
+    const int s_qkv = small ? gemm_plan_splits(qkv_dim, d, gemm_max_splits(), m->n_units) : 1;
     RLX_LAUNCH(RLX_K_QKV, gemm_store(wqkv, xb, T, w.qkv, qkv_dim, s_qkv, st));
 
     bf16_t* pool_layer = pool + (size_t)l * n_blocks * block_elems(c);
@@ -221,7 +222,7 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
       RLX_LAUNCH(RLX_K_ATTN, attention_prefill(at, st));
     }
 
-    const int s_o = small ? gemm_plan_splits(d, qdim, gemm_max_splits()) : 1;
+    const int s_o = small ? gemm_plan_splits(d, qdim, gemm_max_splits(), m->n_units) : 1;
     RLX_LAUNCH(RLX_K_OPROJ, gemm_store(linear1(m->wo[l], d, qdim), ob, T, w.planes, d, s_o, st));
     pend_planes = w.planes; pend_n = s_o;
 
@@ -229,11 +230,11 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
     if (c.n_experts == 0) {
       const Act act = make_act(w.act, T, c.d_ff, PL);
       RLX_LAUNCH(RLX_K_GATEUP, gemm_swiglu(m->w_gate_up[l], c.d_ff, d, xb, T, act, st));
-      const int s_d = small ? gemm_plan_splits(d, c.d_ff, gemm_max_splits()) : 1;
+      const int s_d = small ? gemm_plan_splits(d, c.d_ff, gemm_max_splits(), m->n_units) : 1;
       RLX_LAUNCH(RLX_K_DOWN, gemm_store(linear1(m->w_down[l], d, c.d_ff), act, T, w.planes, d, s_d, st));
       pend_planes = w.planes; pend_n = s_d;
     } else {
-      const int s_r = small ? gemm_plan_splits(c.n_experts, d, gemm_max_splits()) : 1;
+      const int s_r = small ? gemm_plan_splits(c.n_experts, d, gemm_max_splits(), m->n_units) : 1;
       RLX_LAUNCH(RLX_K_ROUTER, gemm_store(linear1(m->w_router[l], c.n_experts, d), xb, T, w.router, c.n_experts, s_r, st));
       RouterArgs ra = {};
       ra.logits = w.router; ra.n_planes = s_r; ra.T = T; ra.E = c.n_experts; ra.top_k = c.top_k;
@@ -351,6 +352,7 @@ int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* wt, rlx_mod
   hipError_t e = hipGetDevice(&m->device);
   int n_cu = 0;
   if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, m->device);
+  m->n_units = n_cu > 0 ? n_cu : 1;
   m->attn_wgs = 2 * n_cu < ATTN_WGS_MAX ? (2 * n_cu > 0 ? 2 * n_cu : 1) : ATTN_WGS_MAX;
   if (e == hipSuccess) e = hipMalloc((void**)&m->inv_freq, inv.size() * sizeof(double));
   if (e == hipSuccess) e = hipMemcpy(m->inv_freq, inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice);
@@ -500,7 +502,10 @@ int rlx_op_linear(const void* x, const void* w, float* y, int32_t n_tokens, int3
     return fail(RLX_EINVAL, "rlx_op_linear: bad argument (k %% 16 == 0, n %% 4 == 0 required)");
   if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !workspace || !aligned16(workspace))
     return fail(RLX_EINVAL, "rlx_op_linear: NULL workspace or 16-byte alignment");
-  const int splits = n_tokens <= 256 ? gemm_plan_splits(n, k, gemm_max_splits()) : 1;
+  int dev = 0, n_units = 0;
+  RLX_HIP(hipGetDevice(&dev));
+  RLX_HIP(hipDeviceGetAttribute(&n_units, hipDeviceAttributeMultiprocessorCount, dev));
+  const int splits = n_tokens <= 256 ? gemm_plan_splits(n, k, gemm_max_splits(), n_units > 0 ? n_units : 1) : 1;
   hipStream_t st = (hipStream_t)stream;
   const size_t xb = align_up(frag_act_elems(n_tokens, k, 1) * 2);
   const size_t pb = splits > 1 ? align_up((size_t)splits * n_tokens * n * 4) : 0;

@@ -397,19 +397,20 @@ void fill_x(GemmArgs& a, const Act& x) {
 
 int gemm_max_splits() { return 16; }
 
-// split-K planning in units of 16 k-steps (one activation chunk)
-static int split_units(int K) { return (K / 16 + 15) / 16; }
+// Split-K planning.  A compute unit takes in only so many bytes per microsecond however many waves it holds, so
+// what counts is that every unit gets the same number of bytes: the grid is kept at or just under one workgroup
+// per unit (a grid of 1.2 workgroups per unit takes as long as one of 2), with as few planes as that allows.
+static int ksteps_for(int K, int splits) { return (K / 16 + splits - 1) / splits; }
 
-int gemm_plan_splits(int N, int K, int max_splits) {
-  // workgroups cover 128 rows; aim for one per CU (measured: the kernel time is flat in the split count
-  // beyond that, and fewer planes mean less traffic); a split is a whole number of units, none empty
-  const int wgs = ((N + 31) / 32 + GEMM_WAVES - 1) / GEMM_WAVES;
-  const int units = split_units(K);
-  int want = 1;
-  while (want < max_splits && wgs * want < 256) want *= 2;
-  if (want > units) want = units;
-  const int per = (units + want - 1) / want;
-  return (units + per - 1) / per;
+int gemm_plan_splits(int N, int K, int max_splits, int n_units) {
+  const int groups = ((N + 31) / 32 + GEMM_WAVES - 1) / GEMM_WAVES;   // workgroups per split: 128 rows each
+  const int KS = K / 16;
+  int want = n_units / groups;                      // floor: never more workgroups than units
+  if (want > max_splits) want = max_splits;
+  if (want > KS / 8) want = KS / 8;                 // at least eight k-steps per split
+  if (want < 1) want = 1;
+  const int per = ksteps_for(K, want);
+  return (KS + per - 1) / per;                      // no empty split
 }
 
 hipError_t gemm_store(const LinearW& w, const Act& x, int T, float* y, int ldy, int splits, hipStream_t st) {
@@ -418,7 +419,7 @@ hipError_t gemm_store(const LinearW& w, const Act& x, int T, float* y, int ldy, 
   int tiles = 0;
   for (int i = 0; i < 3; ++i) { a.w[i] = w.seg[i]; a.w_tiles[i] = (w.rows[i] + 31) / 32; tiles += a.w_tiles[i]; }
   a.N = w.N; a.K = w.K; a.T = T;
-  a.ksteps_per_split = (split_units(w.K) + splits - 1) / splits * 16;   // same rule as gemm_plan_splits
+  a.ksteps_per_split = ksteps_for(w.K, splits);   // same rule as gemm_plan_splits
   a.y = y; a.ldy = ldy;
   launch_mt<EPI_STORE>(a, tiles, splits, pick_mt(T), x.planes, st);
   return hipGetLastError();
