@@ -128,6 +128,15 @@ RLX_API int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* w, 
 RLX_API int rlx_model_destroy(rlx_model* m);
 
 /*
+ * Tuning knob: the number of workgroups of the decode attention kernel.  A decode step lays the 32-key units of
+ * all (sequence, KV head) pairs end to end and gives each workgroup an equal, contiguous share; the default is
+ * two workgroups per compute unit (the grid that is exactly resident).  1 <= n_workgroups <= 1024; results do
+ * not depend on it beyond the order in which partial softmax states are merged.  Not thread-safe against calls
+ * that use the model.
+ */
+RLX_API int rlx_model_set_attention_grid(rlx_model* m, int32_t n_workgroups);
+
+/*
  * Size in bytes of a KV pool of n_blocks pages (bf16).  Layout, private to the
  * library: [layer][block][kv_head]{ K[16][head_dim], V^T[head_dim][16] }.
  * The caller allocates it (256-byte aligned) and passes n_blocks to every call.

@@ -365,6 +365,14 @@ int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* wt, rlx_mod
   return RLX_OK;
 }
 
+int rlx_model_set_attention_grid(rlx_model* m, int32_t n_workgroups) {
+  if (!m) return fail(RLX_EINVAL, "model is NULL");
+  if (n_workgroups < 1 || n_workgroups > ATTN_WGS_MAX)
+    return fail(RLX_EINVAL, "rlx_model_set_attention_grid: n_workgroups %d outside 1..%d", n_workgroups, ATTN_WGS_MAX);
+  m->attn_wgs = n_workgroups;
+  return RLX_OK;
+}
+
 int rlx_model_destroy(rlx_model* m) {
   if (!m) return RLX_OK;
   hipError_t e = m->inv_freq ? hipFree(m->inv_freq) : hipSuccess;

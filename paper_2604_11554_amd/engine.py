@@ -90,6 +90,10 @@ class RolloutModel:
     def weight_bytes(self) -> int:
         return sum(t.numel() * 2 for t in self.tensors.values())
 
+    def set_attention_grid(self, n_workgroups: int) -> None:
+        """Workgroups of the decode attention kernel (default: two per compute unit)."""
+        B.rlx_model_set_attention_grid(self.handle, n_workgroups)
+
     def close(self):
         if getattr(self, "handle", None):
             B.rlx_model_destroy(self.handle)

@@ -160,16 +160,19 @@ def compare_rollouts(gsteps, osteps, wl, is_moe):
     return stats
 
 
-def teacher_forced_parity(pkg, synthetic, shape, wl, n_decode, split, model_seed=0):
+def teacher_forced_parity(pkg, synthetic, shape, wl, n_decode, split, model_seed=0, attention_grid=None, osteps=None):
     """Free-running oracle rollout -> GPU teacher-forced on its tokens -> compare.  If the GPU took a
     different expert set anywhere, the oracle is re-run replaying the GPU's routing (the paper's routing
     replay) so that everything downstream of a tolerated near-tie can still be checked."""
     omodel = O.OracleModel(shape, model_seed)
-    say("%s: oracle rollout" % shape.name)
-    osteps = oracle_rollout(omodel, wl, n_decode)
+    if osteps is None:
+        say("%s: oracle rollout" % shape.name)
+        osteps = oracle_rollout(omodel, wl, n_decode)
     forced = [st["tokens"] for st in osteps]
-    say("%s: gpu rollout (activation_split=%d)" % (shape.name, split))
+    say("%s: gpu rollout (activation_split=%d, attention grid %s)" % (shape.name, split, attention_grid))
     model = synthetic.model_from_shape(shape, model_seed, activation_split=split)
+    if attention_grid is not None:
+        model.set_attention_grid(attention_grid)
     mb = (int(wl.prompt_lens.max()) + n_decode + 15) // 16 + 1
     eng = pkg.RolloutEngine(model, n_blocks=wl.batch * mb, max_seqs=max(8, wl.batch),
                             max_chunk_tokens=int(wl.prompt_lens.sum()), max_blocks_per_seq=mb)
@@ -201,6 +204,28 @@ def test_teacher_forced_rollout_parity(amd, shape_name, split):
 # ---------------------------------------------------------------------------
 # free-running rollouts: finish rules, sharing, chunking, turns, determinism
 # ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("case", ["long_and_short", "many_short"])
+def test_decode_attention_shares(amd, case):
+    """Decode attention lays the 32-key units of all (sequence, KV head) pairs end to end and cuts the line into
+    equal shares, one per workgroup.  Covered here: one share that holds everything (a pair longer than one
+    block-table window of 64 units; more than 63 sequences inside one share), shares that cut pairs in two or
+    more places, more shares than units, and contexts of 1, 31, 32 and 33 keys."""
+    pkg, synthetic = amd
+    shape = RI.TINY_DENSE
+    if case == "long_and_short":
+        wl = RI.workload_tiny(shape, n_decode=5, lens=(5, 40, 700, 2300, 17, 1100, 1, 31, 32, 33), seed_base=5000)
+        grids = (1, 3, 37, 1024)
+    else:
+        lens = tuple(int(n) for n in np.random.default_rng(7).integers(1, 24, size=80))
+        wl = RI.workload_tiny(shape, n_decode=4, lens=lens, seed_base=6000)
+        grids = (1, 2, 512)
+    omodel = O.OracleModel(shape, 0)
+    say("%s: oracle rollout" % case)
+    osteps = oracle_rollout(omodel, wl, int(wl.n_decode[0]))
+    for g in grids:
+        teacher_forced_parity(pkg, synthetic, shape, wl, int(wl.n_decode[0]), 1, attention_grid=g, osteps=osteps)
+
 
 def _engine(pkg, synthetic, shape, split=1, n_blocks=96, max_seqs=8, chunk=512, max_blocks=16, model_seed=0):
     model = synthetic.model_from_shape(shape, model_seed, activation_split=split)
@@ -421,6 +446,10 @@ def test_error_codes(amd):
         eng.decode_step()
     assert e.value.code == B.RLX_ENOMEM and "workspace" in str(e.value)
     eng.workspace = keep
+    for n in (0, -3, 1025):
+        with pytest.raises(B.RlxError) as e:
+            model.set_attention_grid(n)
+        assert e.value.code == B.RLX_EINVAL
     eng.prefill([0], [RI.workload_tiny(shape, lens=(5,)).prompt_tokens[0]])   # the handle still works after an error
     torch.cuda.synchronize()
     model.close()
