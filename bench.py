@@ -89,15 +89,15 @@ def traffic_record(workload, kernel_class):
     if kernel_class != "attn":
         return None
     path = os.path.join(ROOT, "profiles", "attn_decode_%s_traffic.txt" % workload)
-    src = os.path.join(ROOT, "paper_2604_11554_amd", "csrc", "attention.hip")
-    if not (os.path.exists(path) and os.path.exists(src)):
+    srcs = [os.path.join(ROOT, "paper_2604_11554_amd", "csrc", f) for f in ("attention_decode.hip", "attn_core.h")]
+    if not (os.path.exists(path) and all(os.path.exists(f) for f in srcs)):
         return None
     rec = {}
     for line in open(path):
         if "=" in line and not line.startswith("#"):
             k, v = line.split("=", 1)
             rec[k.strip()] = v.strip()
-    if rec.get("source_sha256") != hashlib.sha256(open(src, "rb").read()).hexdigest():
+    if rec.get("source_sha256") != hashlib.sha256(b"".join(open(f, "rb").read() for f in srcs)).hexdigest():
         return None
     return float(rec["ratio_measured_over_algorithmic"])
 
