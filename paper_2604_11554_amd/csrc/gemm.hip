@@ -198,20 +198,30 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
 
+  // One batch of U k-steps.  The activation fragments of k-step u + 1 are read from LDS while the matrix cores
+  // work on k-step u (two register sets): with one wave per SIMD nothing else would hide the LDS latency.
   auto compute = [&](int buf, int kk0, int ks0, const u32x4 (&wf)[U]) {
+    u32x4 xq[2][MT * PL];
+    auto fetch = [&](int u, u32x4 (&dst)[MT * PL]) {
+#pragma unroll
+      for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int p = 0; p < PL; ++p) dst[m * PL + p] = lds[(buf * FRAGS + ((kk0 + u) * MT + m) * PL + p) * 64 + lane];
+    };
+    fetch(0, xq[0]);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
+      if (u + 1 < U) fetch(u + 1, xq[(u + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);          // the reads above are issued before the multiplies below
       const bool ok = ks0 + u < ks_e;             // uniform; past the end the weights count as zero
       const u32x4 z = {0u, 0u, 0u, 0u};
       const bf16x8 w1 = __builtin_bit_cast(bf16x8, ok ? wf[u] : z);
 #pragma unroll
       for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int p = PL - 1; p >= 0; --p) {       // small term first
-          u32x4 xv = lds[(buf * FRAGS + ((kk0 + u) * MT + m) * PL + p) * 64 + lane];
-          bf16x8 xf = __builtin_bit_cast(bf16x8, xv);
-          acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, xf, acc[m], 0, 0, 0);
-        }
+        for (int p = PL - 1; p >= 0; --p)         // small term first
+          acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, __builtin_bit_cast(bf16x8, xq[u & 1][m * PL + p]), acc[m],
+                                                           0, 0, 0);
     }
   };
 
