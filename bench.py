@@ -84,19 +84,19 @@ def step_bytes(shape, ctx_sum_plus_b, batch, touched=None):
 
 def traffic_record(workload, kernel_class):
     """Measured-over-algorithmic HBM byte ratio of the dominant kernel from the committed counter summary, or
-    None when there is none for this workload/kernel or the kernel source has changed since it was taken."""
+    None when there is none for this workload/kernel or the kernel's sources have changed since it was taken."""
     import hashlib
-    if kernel_class != "attn":
-        return None
-    path = os.path.join(ROOT, "profiles", "attn_decode_%s_traffic.txt" % workload)
-    srcs = [os.path.join(ROOT, "paper_2604_11554_amd", "csrc", f) for f in ("attention_decode.hip", "attn_core.h")]
-    if not (os.path.exists(path) and all(os.path.exists(f) for f in srcs)):
+    path = os.path.join(ROOT, "profiles", "%s_decode_%s_traffic.txt" % (kernel_class, workload))
+    if not os.path.exists(path):
         return None
     rec = {}
     for line in open(path):
         if "=" in line and not line.startswith("#"):
             k, v = line.split("=", 1)
             rec[k.strip()] = v.strip()
+    srcs = [os.path.join(ROOT, "paper_2604_11554_amd", "csrc", f.strip()) for f in rec.get("sources", "").split(",") if f.strip()]
+    if not srcs or not all(os.path.exists(f) for f in srcs):
+        return None
     if rec.get("source_sha256") != hashlib.sha256(b"".join(open(f, "rb").read() for f in srcs)).hexdigest():
         return None
     return float(rec["ratio_measured_over_algorithmic"])
