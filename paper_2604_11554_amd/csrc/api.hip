@@ -242,10 +242,11 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
       ra.n_layers = c.n_layers; ra.tok_live = w.meta.tok_live;
       RLX_LAUNCH(RLX_K_GROUP, moe_route(ra, w.group_off, w.sorted_token, w.pair_pos, w.meta.tickets, st));
       const Act act = make_act(w.act, T * c.top_k, c.d_ff_expert, PL);
+      const int rows_per_expert = (int)(((long long)T * c.top_k + c.n_experts - 1) / c.n_experts);
       RLX_LAUNCH(RLX_K_GATEUP, gemm_grouped_swiglu(m->w_gate_up[l], c.n_experts, c.d_ff_expert, d, xb,
-                                                   w.sorted_token, w.group_off, T, act, st));
+                                                   w.sorted_token, w.group_off, T, rows_per_expert, act, st));
       RLX_LAUNCH(RLX_K_DOWN, gemm_grouped_store(m->w_down[l], c.n_experts, d, c.d_ff_expert, act, w.group_off, T,
-                                                w.moe_y, st));
+                                                rows_per_expert, w.moe_y, st));
       pend_moe = true;
     }
   }

@@ -446,8 +446,15 @@ hipError_t gemm_swiglu(const bf16_t* w_gate_up, int F, int K, const Act& x, int 
   return hipGetLastError();
 }
 
+// Token-tile height of the expert-grouped kernels.  An expert's weights are streamed once per tile of 32 * mt rows
+// and every tile reads 32 * mt activation rows whether or not they exist, so the tile should just cover the rows an
+// expert is expected to get (decode: a handful; prefill: hundreds); the grid covers max_rows and workgroups past an
+// expert's last row exit at once.
+static int grouped_mt(int expected_rows) { return expected_rows <= 16 ? 1 : (expected_rows <= 40 ? 2 : 4); }
+
 hipError_t gemm_grouped_swiglu(const bf16_t* w_gate_up, int E, int F, int K, const Act& x, const int32_t* x_rows,
-                               const int32_t* group_off, int max_rows, const Act& act, hipStream_t st) {
+                               const int32_t* group_off, int max_rows, int expected_rows, const Act& act,
+                               hipStream_t st) {
   GemmArgs a = {};
   fill_x(a, x);
   a.x_rows = x_rows;
@@ -456,12 +463,12 @@ hipError_t gemm_grouped_swiglu(const bf16_t* w_gate_up, int E, int F, int K, con
   a.ksteps_per_split = K / 16;
   a.act = act.p; a.act_mtiles = act.mtiles();
   a.group_off = group_off; a.w_expert_stride = packed_weight_elems(2 * F, K);
-  launch_mt<EPI_SWIGLU>(a, a.w_tiles[0], E, max_rows <= 32 ? 1 : 2, x.planes, st);
+  launch_mt<EPI_SWIGLU>(a, a.w_tiles[0], E, grouped_mt(expected_rows), x.planes, st);
   return hipGetLastError();
 }
 
 hipError_t gemm_grouped_store(const bf16_t* w, int E, int N, int K, const Act& x, const int32_t* group_off,
-                              int max_rows, float* y, hipStream_t st) {
+                              int max_rows, int expected_rows, float* y, hipStream_t st) {
   GemmArgs a = {};
   fill_x(a, x);
   a.w[0] = w; a.w_tiles[0] = (N + 31) / 32;
@@ -469,7 +476,7 @@ hipError_t gemm_grouped_store(const bf16_t* w, int E, int N, int K, const Act& x
   a.ksteps_per_split = K / 16;
   a.y = y; a.ldy = N;
   a.group_off = group_off; a.w_expert_stride = packed_weight_elems(N, K);
-  launch_mt<EPI_STORE>(a, a.w_tiles[0], E, max_rows <= 32 ? 1 : 2, x.planes, st);
+  launch_mt<EPI_STORE>(a, a.w_tiles[0], E, grouped_mt(expected_rows), x.planes, st);
   return hipGetLastError();
 }
 

@@ -47,11 +47,13 @@ int lmhead_tiles(int vocab);
 // LM head with fused per-tile log-sum-exp and Gumbel-max partials: part[t][tile][4]
 hipError_t gemm_lmhead(const bf16_t* w_lm, int V, int K, const Act& x, int T, float* logits, float* part,
                        const uint64_t* seeds, const float* temperature, const int32_t* sample_pos, hipStream_t st);
-// expert-grouped forms: rows [group_off[e], group_off[e+1]) belong to expert e = blockIdx.y
+// expert-grouped forms: rows [group_off[e], group_off[e+1]) belong to expert e = blockIdx.y; max_rows bounds the rows
+// of one expert, expected_rows (pairs / experts) picks the token-tile height
 hipError_t gemm_grouped_swiglu(const bf16_t* w_gate_up, int E, int F, int K, const Act& x, const int32_t* x_rows,
-                               const int32_t* group_off, int max_rows, const Act& act, hipStream_t st);
+                               const int32_t* group_off, int max_rows, int expected_rows, const Act& act,
+                               hipStream_t st);
 hipError_t gemm_grouped_store(const bf16_t* w, int E, int N, int K, const Act& x,
-                              const int32_t* group_off, int max_rows, float* y, hipStream_t st);
+                              const int32_t* group_off, int max_rows, int expected_rows, float* y, hipStream_t st);
 
 // ---- elementwise.hip ----
 struct TokenMeta {        // per packed token, built on the device at the start of a call
