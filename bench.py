@@ -82,6 +82,22 @@ def step_bytes(shape, ctx_sum_plus_b, batch, touched=None):
     return w + kv_tok * ctx_sum_plus_b + kv_tok * batch
 
 
+def prefill_flops(shape, plen):
+    """Useful floating-point operations of prefilling prompts of the given lengths (2 per multiply-add; the
+    two-term activations double the MFMA work actually issued, which is not counted)."""
+    s = shape
+    qdim, kvdim = s.n_q_heads * s.head_dim, s.n_kv_heads * s.head_dim
+    per_tok = s.d_model * (qdim + 2 * kvdim) + qdim * s.d_model
+    if s.is_moe:
+        per_tok += s.d_model * s.n_experts + s.top_k * 3 * s.d_model * s.d_ff_expert
+    else:
+        per_tok += 3 * s.d_model * s.d_ff
+    lin = 2.0 * per_tok * s.n_layers * float(np.sum(plen))
+    attn = sum(2.0 * 2 * qdim * (n * (n + 1) / 2.0) for n in plen) * s.n_layers      # causal q.k and p.v
+    head = 2.0 * s.vocab * s.d_model * len(plen)                                     # only the sampled rows
+    return lin + attn + head
+
+
 def traffic_record(workload, kernel_class):
     """Measured-over-algorithmic HBM byte ratio of the dominant kernel from the committed counter summary, or
     None when there is none for this workload/kernel or the kernel's sources have changed since it was taken."""
@@ -219,7 +235,9 @@ def main():
         i = j
     torch.cuda.synchronize()
     t_prefill = time.perf_counter() - t0
-    log("prefill: %d tokens in %.2f s (%.0f tok/s)" % (plen.sum(), t_prefill, plen.sum() / t_prefill))
+    log("prefill: %d tokens in %.2f s (%.0f tok/s, %.0f TFLOP/s useful = %.1f%% of the bf16 MFMA peak)" % (
+        plen.sum(), t_prefill, plen.sum() / t_prefill, prefill_flops(shape, plen) / t_prefill / 1e12,
+        100 * prefill_flops(shape, plen) / t_prefill / 1e12 / 2500.0))
 
     total_steps = n_decode - 1
     K = args.steps if args.steps > 0 else total_steps - 0
@@ -316,6 +334,10 @@ def main():
                                "temperature 1 Gumbel-max" % (args.workload, shape.name, bsz, plen.min(), plen.max(),
                                                               n_decode),
                    "activation_split": split, "prefill_tokens_per_s": float(plen.sum() / t_prefill)},
+        # the prefill chunks that filled the cache before the timed decode steps (MFMA-bound part of the path)
+        "prefill": {"tokens": int(plen.sum()), "seconds": t_prefill, "tokens_per_s": float(plen.sum() / t_prefill),
+                    "bound": "mfma", "achieved": prefill_flops(shape, plen) / t_prefill / 1e12, "peak": 2500.0,
+                    "unit": "TFLOP/s", "frac": prefill_flops(shape, plen) / t_prefill / 1e12 / 2500.0},
         "step_roofline": {"bound": "hbm", "achieved": step_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                           "frac": step_gbs / HBM_PEAK_GBS, "bytes_per_step": float(step_b)},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -203,6 +203,30 @@ RLX_API int rollout_prefill_chunk(const rlx_model* m, void* kv_pool, int64_t n_b
                           int32_t* out_routing, float* out_logits, void* stream);
 
 /*
+ * Teacher-forced scoring of a chunk with optional routing replay: the log-probability forward that consumes
+ * what the rollout recorded (paper Sec. 3.3: per-token log-probabilities; Sec. 5.5: Rollout Routing Replay,
+ * the experts chosen during generation are replayed in the later forward pass).  The chunk's tokens are
+ * appended to the cache exactly as in rollout_prefill_chunk (so long sequences can be scored chunk by chunk);
+ * nothing is sampled.  For every chunk position t with 0 <= target_ids[t] < vocab,
+ *   out_logprobs[t] = log_softmax(z_t / T_i)[target_ids[t]],  z_t = logits after position t, i = its sequence;
+ * other positions get 0.
+ *   target_ids      int32 [total_tokens] (normally the next token of the same sequence; -1 = not scored)
+ *   temperature     float [n_seqs] (<= 0 scores with T = 1)
+ *   replay_routing  NULL or int32 [total_tokens, n_layers, top_k]: MoE layers use these experts instead of their
+ *                   own top-k; the mixing weights are the layer's own gate probabilities renormalised over the
+ *                   replayed set (an id outside [0, n_experts) is replaced by 0).  Ignored for dense models.
+ *   out_logprobs    float [total_tokens]
+ *   out_routing     NULL or int32 [total_tokens, n_layers, top_k]: the experts used
+ * token_ids, input_embeds, cu_seqlens, ctx_lens, block_table as in rollout_prefill_chunk.
+ */
+RLX_API int rollout_score_chunk(const rlx_model* m, void* kv_pool, int64_t n_blocks, void* workspace,
+                        size_t workspace_bytes, int32_t n_seqs, int32_t total_tokens, const int32_t* token_ids,
+                        const void* input_embeds, const int32_t* cu_seqlens, const int32_t* ctx_lens,
+                        const int32_t* block_table, int32_t max_blocks_per_seq, const int32_t* target_ids,
+                        const float* temperature, const int32_t* replay_routing, float* out_logprobs,
+                        int32_t* out_routing, void* stream);
+
+/*
  * One decode step for n_seqs sequences: each live row consumes tokens_inout[i] at
  * position ctx_lens_inout[i] (appending its K/V there) and emits the next token.
  *   tokens_inout    int32 [n_seqs]  in: last emitted token; out: new token (pad if finished)

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "librelax_rollout.so")
 RLX_OK, RLX_EINVAL, RLX_ENOMEM, RLX_EHIP, RLX_EUNSUPPORTED = 0, -1, -2, -3, -4
 
 EXPORTS = ["rlx_packed_weight_bytes", "rlx_pack_weight", "rlx_pack_gate_up", "rlx_model_create", "rlx_model_destroy", "rlx_model_set_attention_grid", "rlx_kv_pool_bytes", "rlx_workspace_bytes",
-           "rlx_kv_copy_blocks", "rollout_prefill_chunk", "rollout_decode_step", "rlx_op_linear",
+           "rlx_kv_copy_blocks", "rollout_prefill_chunk", "rollout_score_chunk", "rollout_decode_step", "rlx_op_linear",
            "rlx_profile_kernel", "rlx_last_error"]
 
 KERNEL_CLASSES = dict(norm=1, qkv=2, rope=3, attn=4, attn_merge=5, oproj=6, gateup=7, down=8, router=9, group=10,
@@ -76,6 +76,7 @@ def lib() -> C.CDLL:
         l.rlx_workspace_bytes.argtypes = [vp, i32, i32, i32, C.POINTER(sz)]
         l.rlx_kv_copy_blocks.argtypes = [vp, vp, i64, vp, vp, i32, vp]
         l.rollout_prefill_chunk.argtypes = [vp, vp, i64, vp, sz, i32, i32] + [vp] * 5 + [i32] + [vp] * 12
+        l.rollout_score_chunk.argtypes = [vp, vp, i64, vp, sz, i32, i32] + [vp] * 5 + [i32] + [vp] * 6
         l.rollout_decode_step.argtypes = [vp, vp, i64, vp, sz, i32, vp, vp, vp, i32] + [vp] * 10
         l.rlx_op_linear.argtypes = [vp, vp, vp, i32, i32, i32, vp, sz, vp]
         l.rlx_profile_kernel.argtypes = [i32, vp, vp, i32, i32]
@@ -190,6 +191,18 @@ def rollout_prefill_chunk(model, kv_pool, n_blocks, workspace, n_seqs, total_tok
         _ptr(temperature, torch.float32), _ptr(max_ctx_len, torch.int32), _ptr(forced_tokens, torch.int32),
         _ptr(out_tokens, torch.int32), _ptr(out_logprobs, torch.float32), _ptr(finished_out, torch.uint8),
         _ptr(out_sampled, torch.int32), _ptr(out_routing, torch.int32), _ptr(out_logits, torch.float32),
+        _stream(stream)))
+
+
+def rollout_score_chunk(model, kv_pool, n_blocks, workspace, n_seqs, total_tokens, token_ids, input_embeds, cu_seqlens,
+                        ctx_lens, block_table, max_blocks_per_seq, target_ids, temperature, replay_routing,
+                        out_logprobs, out_routing=None, stream=None) -> None:
+    _check(lib().rollout_score_chunk(
+        model, _ptr(kv_pool), n_blocks, _ptr(workspace), workspace.numel() * workspace.element_size(),
+        n_seqs, total_tokens, _ptr(token_ids, torch.int32), _ptr(input_embeds, torch.bfloat16),
+        _ptr(cu_seqlens, torch.int32), _ptr(ctx_lens, torch.int32), _ptr(block_table, torch.int32),
+        max_blocks_per_seq, _ptr(target_ids, torch.int32), _ptr(temperature, torch.float32),
+        _ptr(replay_routing, torch.int32), _ptr(out_logprobs, torch.float32), _ptr(out_routing, torch.int32),
         _stream(stream)))
 
 

@@ -87,6 +87,7 @@ struct Workspace {
   size_t bytes;
 };
 
+constexpr int SCORE_ROWS = 256;      // rows per LM-head pass of rollout_score_chunk
 constexpr int ATTN_WGS_MAX = 1024;   // decode attention grid limit (plan arrays are sized for it)
 
 int plane_rows(int T) { return T <= 256 ? gemm_max_splits() * T : T; }
@@ -113,6 +114,7 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
   w.meta.qtile_q0 = (int32_t*)take((size_t)QT * 4);
   w.meta.n_qtiles = (int32_t*)take(4);
   w.meta.tickets = (uint32_t*)take(8 * 4);
+  w.meta.tok_iota = (int32_t*)take((size_t)T * 4);
   w.meta.rope_cs = (float2*)take((size_t)S * (c.head_dim / 2) * sizeof(float2));
   w.h = (float*)take((size_t)T * c.d_model * 4);
   const int PL = c.activation_split ? 2 : 1;
@@ -139,8 +141,9 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
   } else {
     w.act = (bf16_t*)take(frag_act_elems(T, c.d_ff, PL) * 2);
   }
-  w.x_lm = (bf16_t*)take(frag_act_elems(S, c.d_model, PL) * 2);
-  w.lm_part = (float*)take((size_t)S * lmhead_tiles(c.vocab) * 4 * 4);
+  const int lm_rows = S > SCORE_ROWS ? S : SCORE_ROWS;   // sampled rows of a call, or one block of scored rows
+  w.x_lm = (bf16_t*)take(frag_act_elems(lm_rows, c.d_model, PL) * 2);
+  w.lm_part = (float*)take((size_t)lm_rows * lmhead_tiles(c.vocab) * 4 * 4);
   w.bytes = off;
   return w;
 }
@@ -157,6 +160,9 @@ struct StepIO {
   int32_t* out_tokens; float* out_logprobs; uint8_t* finished; int32_t* out_sampled;
   int32_t* out_routing; float* out_logits;
   int32_t* ctx_lens_rw;   // decode only
+  // scoring (rollout_score_chunk): every chunk position is scored against score_targets, nothing is sampled
+  bool score; const int32_t* score_targets; float* score_logprobs;
+  const int32_t* replay_routing;   // optional [T, n_layers, top_k]
 };
 
 int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspace& w, const StepIO& io,
@@ -239,7 +245,7 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
       RouterArgs ra = {};
       ra.logits = w.router; ra.n_planes = s_r; ra.T = T; ra.E = c.n_experts; ra.top_k = c.top_k;
       ra.topk_idx = w.topk_idx; ra.topk_w = w.topk_w; ra.routing_out = io.out_routing; ra.layer = l;
-      ra.n_layers = c.n_layers; ra.tok_live = w.meta.tok_live;
+      ra.n_layers = c.n_layers; ra.tok_live = w.meta.tok_live; ra.replay_idx = io.replay_routing;
       RLX_LAUNCH(RLX_K_GROUP, moe_route(ra, w.group_off, w.sorted_token, w.pair_pos, w.meta.tickets, st));
       const Act act = make_act(w.act, T * c.top_k, c.d_ff_expert, PL);
       const int rows_per_expert = (int)(((long long)T * c.top_k + c.n_experts - 1) / c.n_experts);
@@ -251,12 +257,33 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
     }
   }
 
+  if (io.score) {
+    // every position is scored: final norm + LM head (log-sum-exp partials only, no draw) + target logit, in
+    // blocks of SCORE_ROWS rows; each block applies the residual still pending from the last sub-layer to its rows
+    const float* pp = pend_planes; const int pn = pend_n; const bool pm = pend_moe;
+    for (int r0 = 0; r0 < T; r0 += SCORE_ROWS) {
+      const int n = T - r0 < SCORE_ROWS ? T - r0 : SCORE_ROWS;
+      const Act x_lm = make_act(w.x_lm, n, d, PL);
+      pend_planes = pp; pend_n = pn; pend_moe = pm;
+      RLX_HIP(norm(m->final_norm, w.meta.tok_iota + r0, n, x_lm, nullptr));
+      RLX_LAUNCH(RLX_K_LMHEAD, gemm_lmhead(m->lm_head, c.vocab, d, x_lm, n, nullptr, w.lm_part, nullptr, io.temperature,
+                                           nullptr, w.meta.tok_seq + r0, false, st));
+      FinalizeArgs f = {};
+      f.n_rows = n; f.n_tiles = lmhead_tiles(c.vocab); f.vocab = c.vocab; f.d = d;
+      f.part = w.lm_part; f.x = x_lm; f.w_lm = m->lm_head;
+      f.temperature = io.temperature; f.forced = io.score_targets + r0; f.row_seq = w.meta.tok_seq + r0;
+      f.eos = c.eos_token_id; f.pad = c.pad_token_id; f.out_logprobs = io.score_logprobs + r0; f.score = 1;
+      RLX_HIP(sample_finalize(f, st));
+    }
+    return RLX_OK;
+  }
+
   // final norm of the rows that emit a token, LM head with fused log-sum-exp / Gumbel-max partials
   const int S = io.n_seqs;
   const Act x_lm = make_act(w.x_lm, S, d, PL);
   RLX_HIP(norm(m->final_norm, w.meta.sample_row, S, x_lm, nullptr));
   RLX_LAUNCH(RLX_K_LMHEAD, gemm_lmhead(m->lm_head, c.vocab, d, x_lm, S, io.out_logits, w.lm_part, io.seeds,
-                                       io.temperature, w.meta.sample_pos, st));
+                                       io.temperature, w.meta.sample_pos, nullptr, true, st));
   FinalizeArgs f = {};
   f.n_rows = S; f.n_tiles = lmhead_tiles(c.vocab); f.vocab = c.vocab; f.d = d;
   f.part = w.lm_part; f.x = x_lm; f.w_lm = m->lm_head;
@@ -392,7 +419,14 @@ int rlx_workspace_bytes(const rlx_model* m, int32_t max_seqs, int32_t max_tokens
                         size_t* bytes_out) {
   if (!m || !bytes_out || max_seqs <= 0 || max_tokens < max_seqs || max_blocks_per_seq <= 0)
     return fail(RLX_EINVAL, "bad argument (need 0 < max_seqs <= max_tokens, max_blocks_per_seq > 0)");
-  *bytes_out = carve(m->cfg, nullptr, max_seqs, max_tokens, max_blocks_per_seq).bytes;
+  // calls with at most 256 tokens keep up to 16 split-K planes per token, longer ones a single plane: the
+  // need is monotonic in the token count on either side of that switch, not across it
+  size_t b = carve(m->cfg, nullptr, max_seqs, max_tokens, max_blocks_per_seq).bytes;
+  if (max_tokens > 256) {
+    const size_t b2 = carve(m->cfg, nullptr, max_seqs < 256 ? max_seqs : 256, 256, max_blocks_per_seq).bytes;
+    if (b2 > b) b = b2;
+  }
+  *bytes_out = b;
   return RLX_OK;
 }
 
@@ -431,6 +465,34 @@ int rollout_prefill_chunk(const rlx_model* m, void* kv_pool, int64_t n_blocks, v
   io.seeds = seeds; io.temperature = temperature; io.max_ctx_len = max_ctx_len; io.forced = forced_tokens;
   io.out_tokens = out_tokens; io.out_logprobs = out_logprobs; io.finished = finished_out;
   io.out_sampled = out_sampled; io.out_routing = m->cfg.n_experts ? out_routing : nullptr; io.out_logits = out_logits;
+  return run_layers(m, (bf16_t*)kv_pool, n_blocks, w, io, st);
+}
+
+int rollout_score_chunk(const rlx_model* m, void* kv_pool, int64_t n_blocks, void* workspace, size_t workspace_bytes,
+                        int32_t n_seqs, int32_t total_tokens, const int32_t* token_ids, const void* input_embeds,
+                        const int32_t* cu_seqlens, const int32_t* ctx_lens, const int32_t* block_table,
+                        int32_t max_blocks_per_seq, const int32_t* target_ids, const float* temperature,
+                        const int32_t* replay_routing, float* out_logprobs, int32_t* out_routing, void* stream) {
+  int rc = check_common(m, kv_pool, n_blocks, workspace, n_seqs, max_blocks_per_seq);
+  if (rc) return rc;
+  if (total_tokens <= 0 || total_tokens > (1 << 24)) return fail(RLX_EINVAL, "total_tokens %d out of range", total_tokens);
+  if (!token_ids || !cu_seqlens || !ctx_lens || !block_table || !target_ids || !temperature || !out_logprobs)
+    return fail(RLX_EINVAL, "NULL array argument");
+  if (input_embeds && !aligned16(input_embeds)) return fail(RLX_EINVAL, "input_embeds not 16-byte aligned");
+  const int T = total_tokens > n_seqs ? total_tokens : n_seqs;
+  Workspace w = carve(m->cfg, (char*)workspace, n_seqs, T, max_blocks_per_seq);
+  if (w.bytes > workspace_bytes)
+    return fail(RLX_ENOMEM, "workspace too small: need %zu bytes, have %zu", w.bytes, workspace_bytes);
+  hipStream_t st = (hipStream_t)stream;
+  RLX_HIP(meta_prefill(w.meta, n_seqs, total_tokens, cu_seqlens, ctx_lens, nullptr, st));
+  StepIO io = {};
+  io.n_seqs = n_seqs; io.T = total_tokens; io.decode = false;
+  io.tokens = token_ids; io.input_embeds = (const bf16_t*)input_embeds; io.cu_seqlens = cu_seqlens;
+  io.ctx_lens = ctx_lens; io.block_table = block_table; io.max_blocks = max_blocks_per_seq;
+  io.temperature = temperature;
+  io.out_routing = m->cfg.n_experts ? out_routing : nullptr;
+  io.score = true; io.score_targets = target_ids; io.score_logprobs = out_logprobs;
+  io.replay_routing = m->cfg.n_experts ? replay_routing : nullptr;
   return run_layers(m, (bf16_t*)kv_pool, n_blocks, w, io, st);
 }
 

@@ -45,12 +45,13 @@ __global__ void meta_prefill_kernel(TokenMeta m, int n_seqs, int total, const in
     m.tok_seq[t] = lo;
     m.tok_pos[t] = ctx[lo] + (t - cu[lo]);
     m.tok_live[t] = 1;
+    m.tok_iota[t] = t;
   }
   for (int i = threadIdx.x; i < n_seqs; i += blockDim.x) {
     int len = cu[i + 1] - cu[i];
     m.sample_row[i] = len > 0 ? cu[i + 1] - 1 : 0;
     m.sample_pos[i] = ctx[i] + len;
-    m.sample_on[i] = (sample_last[i] && len > 0) ? 1 : 0;
+    m.sample_on[i] = (sample_last && sample_last[i] && len > 0) ? 1 : 0;
   }
   // query tiles of 16 positions, sequence by sequence (n_seqs <= 1024 per chunk of the scan)
   __syncthreads();

@@ -42,6 +42,8 @@ struct GemmArgs {
   const uint64_t* seeds;
   const float* temperature;
   const int32_t* sample_pos;
+  const int32_t* row_seq;     // optional: row t takes its temperature from entry row_seq[t] (scoring: token -> sequence)
+  int draw;                   // 0: no Gumbel-max draw (scoring): the random words are not generated
   // expert-grouped form: blockIdx.y is the expert, its rows are [group_off[e], group_off[e+1])
   const int32_t* group_off;
   size_t w_expert_stride;     // packed elements between consecutive experts' matrices
@@ -315,16 +317,17 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
       float mx = -INFINITY, se = 0.f, best = -INFINITY;
       int besti = 0x7FFFFFFF;
       if (ok) {
-        const float temp = a.temperature[t];
+        const float temp = a.temperature[a.row_seq ? a.row_seq[t] : t];
         const float invt = temp > 0.f ? 1.f / temp : 1.f;
-        const uint64_t seed = a.seeds[t];
-        const uint32_t pos = (uint32_t)a.sample_pos[t];
+        const bool draw = a.draw != 0 && temp > 0.f;          // uniform over the launch when draw == 0
+        const uint64_t seed = a.draw ? a.seeds[t] : 0;
+        const uint32_t pos = a.draw ? (uint32_t)a.sample_pos[t] : 0u;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int nrow = n0 + 8 * q + 4 * half;  // multiple of 4: one Philox block covers the four ids
           if (nrow >= a.N) continue;
-          uint32_t rnd[4];
-          philox4x32_10((uint32_t)(nrow >> 2), pos, 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32), rnd);
+          uint32_t rnd[4] = {0u, 0u, 0u, 0u};
+          if (a.draw) philox4x32_10((uint32_t)(nrow >> 2), pos, 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32), rnd);
           f32x4 v = {acc[m][4 * q], acc[m][4 * q + 1], acc[m][4 * q + 2], acc[m][4 * q + 3]};
           if (a.logits) {
             if (nrow + 3 < a.N) {
@@ -339,7 +342,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
           for (int j = 0; j < 4; ++j) {
             if (nrow + j < a.N) {
               const float z = v[j] * invt;
-              const float sc = temp > 0.f ? z + gumbel_from_u32(rnd[j]) : z;
+              const float sc = draw ? z + gumbel_from_u32(rnd[j]) : z;
               if (sc > best) { best = sc; besti = nrow + j; }   // ascending ids: ties keep the smaller one
               const float nm = fmaxf(mx, z);
               se = se * __expf(mx - nm) + __expf(z - nm);
@@ -484,13 +487,14 @@ int lmhead_tiles(int vocab) { return (vocab + 31) / 32; }
 
 hipError_t gemm_lmhead(const bf16_t* w_lm, int V, int K, const Act& x, int T, float* logits, float* part,
                        const uint64_t* seeds, const float* temperature, const int32_t* sample_pos,
-                       hipStream_t st) {
+                       const int32_t* row_seq, bool draw, hipStream_t st) {
   GemmArgs a = {};
   fill_x(a, x);
   a.w[0] = w_lm; a.w_tiles[0] = (V + 31) / 32;
   a.N = V; a.K = K; a.T = T;
   a.ksteps_per_split = K / 16;
   a.logits = logits; a.part = part; a.seeds = seeds; a.temperature = temperature; a.sample_pos = sample_pos;
+  a.row_seq = row_seq; a.draw = draw ? 1 : 0;
   launch_mt<EPI_LMHEAD>(a, a.w_tiles[0], 1, pick_mt(T), x.planes, st);
   return hipGetLastError();
 }

@@ -45,8 +45,10 @@ hipError_t gemm_store(const LinearW& w, const Act& x, int T, float* y, int ldy, 
 hipError_t gemm_swiglu(const bf16_t* w_gate_up, int F, int K, const Act& x, int T, const Act& act, hipStream_t st);
 int lmhead_tiles(int vocab);
 // LM head with fused per-tile log-sum-exp and Gumbel-max partials: part[t][tile][4]
+// row_seq (optional): row t reads temperature[row_seq[t]]; draw = false skips the Gumbel-max draw (scoring)
 hipError_t gemm_lmhead(const bf16_t* w_lm, int V, int K, const Act& x, int T, float* logits, float* part,
-                       const uint64_t* seeds, const float* temperature, const int32_t* sample_pos, hipStream_t st);
+                       const uint64_t* seeds, const float* temperature, const int32_t* sample_pos,
+                       const int32_t* row_seq, bool draw, hipStream_t st);
 // expert-grouped forms: rows [group_off[e], group_off[e+1]) belong to expert e = blockIdx.y; max_rows bounds the rows
 // of one expert, expected_rows (pairs / experts) picks the token-tile height
 hipError_t gemm_grouped_swiglu(const bf16_t* w_gate_up, int E, int F, int K, const Act& x, const int32_t* x_rows,
@@ -67,6 +69,7 @@ struct TokenMeta {        // per packed token, built on the device at the start 
   int32_t* qtile_q0;
   int32_t* n_qtiles;      // [1]
   uint32_t* tickets;      // [8] counters zeroed at the start of every call
+  int32_t* tok_iota;      // prefill: [T] 0, 1, 2, ... (row lists of the per-token scoring pass)
   float2* rope_cs;        // [n_seqs][hd/2] decode: (cos, sin) of the new position's rotary angles
 };
 hipError_t meta_decode(const TokenMeta& m, int n_seqs, const int32_t* ctx_lens, const uint8_t* finished,
@@ -170,6 +173,7 @@ struct RouterArgs {
   int32_t* routing_out;      // optional [T, n_layers, top_k] (this layer's slice is written)
   int layer, n_layers;
   const uint8_t* tok_live;   // rows that are inert leave routing_out untouched
+  const int32_t* replay_idx; // optional [T, n_layers, top_k]: use these experts instead of the layer's own top-k
 };
 // top-k + renormalised weights + routing capture + stable grouping of the T*top_k (token, slot) pairs by expert
 // `ticket`: one zeroed counter in device memory (left zero again on completion)
@@ -189,6 +193,10 @@ struct FinalizeArgs {
   uint8_t* finished;          // decode: in/out; prefill: out
   int32_t* ctx_lens;          // decode: incremented for rows live at entry; null for prefill
   int is_decode;
+  // scoring form: row r scores token forced[r] (>= 0) with temperature[row_seq[r]] and writes only
+  // out_logprobs[r] (0 where forced[r] < 0); no length cap, no state update
+  int score;
+  const int32_t* row_seq;
 };
 hipError_t sample_finalize(const FinalizeArgs& a, hipStream_t st);
 

@@ -39,21 +39,34 @@ __device__ __forceinline__ void wave_topk(const RouterArgs& a, int t, int lane, 
   mx = wave_max(mx);
   float my_e = 0.f, denom = 0.f;
   int my_i = 0;
+  const int32_t* replay = a.replay_idx ? a.replay_idx + ((size_t)t * a.n_layers + a.layer) * a.top_k : nullptr;
   for (int k = 0; k < a.top_k; ++k) {
     float bv = -INFINITY; int bi = 0x7FFFFFFF;
+    if (replay) {
+      // routing replay (paper Sec. 5.5): the expert is given; its weight still comes from this layer's own gate
+      // logits, renormalised over the replayed set.  An id outside [0, E) falls back to expert 0.
+      bi = replay[k];
+      if (bi < 0 || bi >= a.E) bi = 0;
+      float mine = -INFINITY;
 #pragma unroll
-    for (int j = 0; j < MAX_E / 64; ++j)
-      if (v[j] > bv) { bv = v[j]; bi = lane + 64 * j; }      // ascending id within the lane
+      for (int j = 0; j < MAX_E / 64; ++j)
+        if (j == (bi >> 6)) mine = v[j];
+      bv = __shfl(mine, bi & 63, WAVE);
+    } else {
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      float ov = __shfl_xor(bv, o, WAVE);
-      int oi = __shfl_xor(bi, o, WAVE);
-      if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+      for (int j = 0; j < MAX_E / 64; ++j)
+        if (v[j] > bv) { bv = v[j]; bi = lane + 64 * j; }      // ascending id within the lane
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        float ov = __shfl_xor(bv, o, WAVE);
+        int oi = __shfl_xor(bi, o, WAVE);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+      }
     }
     const float ev = __expf(bv - mx);
     denom += ev;
     if (lane == k) { my_e = ev; my_i = bi; }
-    if ((bi & 63) == lane) {
+    if (!replay && (bi & 63) == lane) {
 #pragma unroll
       for (int j = 0; j < MAX_E / 64; ++j)
         if (j == (bi >> 6)) v[j] = -INFINITY;

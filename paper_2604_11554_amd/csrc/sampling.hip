@@ -23,7 +23,11 @@ __global__ __launch_bounds__(256) void sample_finalize_kernel(FinalizeArgs a) {
   __shared__ Part sh[256];
   __shared__ float dsh[4];
   const int r = blockIdx.x;
-  const bool on = a.sample_on[r] != 0;
+  if (a.score && (a.forced[r] < 0 || a.forced[r] >= a.vocab)) {   // nothing to score at this position
+    if (threadIdx.x == 0) a.out_logprobs[r] = 0.f;
+    return;
+  }
+  const bool on = a.score || a.sample_on[r] != 0;
   if (!on) {                                  // inert row
     if (threadIdx.x == 0) {
       a.out_tokens[r] = a.pad;
@@ -55,8 +59,10 @@ __global__ __launch_bounds__(256) void sample_finalize_kernel(FinalizeArgs a) {
   const int sampled = p.besti;
   int tok = sampled;
   if (a.forced && a.forced[r] >= 0 && a.forced[r] < a.vocab) tok = a.forced[r];
-  const int pos = a.sample_pos[r];
-  if (pos >= a.max_ctx_len[r] - 1) tok = a.eos;
+  if (!a.score) {
+    const int pos = a.sample_pos[r];
+    if (pos >= a.max_ctx_len[r] - 1) tok = a.eos;
+  }
   if (tok < 0 || tok >= a.vocab) tok = a.eos;   // cannot happen with a non-empty vocabulary; keeps the read in bounds
 
   // logit of the emitted token: the same bf16 operands as the LM-head tiles, fp32 accumulate
@@ -73,10 +79,11 @@ __global__ __launch_bounds__(256) void sample_finalize_kernel(FinalizeArgs a) {
   __syncthreads();
   if (threadIdx.x == 0) {
     float z = dsh[0] + dsh[1] + dsh[2] + dsh[3];
-    float temp = a.temperature[r];
+    float temp = a.temperature[a.row_seq ? a.row_seq[r] : r];
     float invt = temp > 0.f ? 1.f / temp : 1.f;
-    a.out_tokens[r] = tok;
     a.out_logprobs[r] = z * invt - lse;
+    if (a.score) return;
+    a.out_tokens[r] = tok;
     if (a.out_sampled) a.out_sampled[r] = sampled;
     uint8_t fin = (tok == a.eos) ? 1 : 0;
     if (a.is_decode) {

@@ -257,6 +257,52 @@ class RolloutEngine:
         self.finished[idx] = torch.where(on, fin, self.finished[idx])
         return StepOutput(out_tok, out_lp, smp, routing, logits)
 
+    def score(self, rows: Sequence[int], toks: Sequence[np.ndarray], targets: Sequence[np.ndarray],
+              replay_routing: Sequence[Optional[np.ndarray]] = None, embeds: Sequence[Optional[np.ndarray]] = None,
+              want_routing=False):
+        """Teacher-forced scoring of one chunk per listed row (appends the chunk to the row's cache).
+        targets[j][p] is the token whose log-probability is wanted after position p of the chunk (-1: none);
+        replay_routing[j]: int32 [len, n_layers, top_k] experts to replay (all rows or none).  Returns
+        (log-probs float32 [total], routing used or None), packed in row order."""
+        dev = self.m.device
+        n = len(rows)
+        lens = [len(t) for t in toks]
+        total = int(sum(lens))
+        if total > self.max_chunk_tokens or n > self.max_seqs:
+            raise ValueError("chunk of %d tokens / %d rows exceeds the workspace" % (total, n))
+        cfg = self.m.cfg
+        idx = torch.tensor(list(rows), dtype=torch.long, device=dev)
+        tok = torch.from_numpy(np.concatenate([np.asarray(t, np.int32) for t in toks])).to(dev)
+        tgt = torch.from_numpy(np.concatenate([np.asarray(t, np.int32) for t in targets])).to(dev)
+        if tgt.numel() != total:
+            raise ValueError("targets must align with the chunk tokens")
+        emb = None
+        if embeds is not None and any(e is not None for e in embeds):
+            full = np.zeros((total, cfg["d_model"]), np.uint16)
+            o = 0
+            for e, ln in zip(embeds, lens):
+                if e is not None:
+                    full[o:o + ln] = e
+                o += ln
+            emb = torch.from_numpy(full.view(np.int16)).to(dev).view(torch.bfloat16)
+        rep = None
+        if replay_routing is not None and self.is_moe:
+            if any(r is None for r in replay_routing):
+                raise ValueError("replay_routing must cover every row of the chunk")
+            rep = torch.from_numpy(np.concatenate([np.asarray(r, np.int32) for r in replay_routing])).to(dev).contiguous()
+            if tuple(rep.shape) != (total, cfg["n_layers"], cfg["top_k"]):
+                raise ValueError("replay_routing must be [tokens, n_layers, top_k]")
+        cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device=dev)
+        ctx = self.ctx_lens[idx].contiguous()
+        bt = self.block_table[idx].contiguous()
+        lp = torch.empty(total, dtype=torch.float32, device=dev)
+        routing = (torch.zeros((total, cfg["n_layers"], cfg["top_k"]), dtype=torch.int32, device=dev)
+                   if (want_routing and self.is_moe) else None)
+        B.rollout_score_chunk(self.m.handle, self.kv_pool, self.n_blocks, self.workspace, n, total, tok, emb, cu, ctx,
+                              bt, self.max_blocks, tgt, self.temperature[idx].contiguous(), rep, lp, routing)
+        self.ctx_lens[idx] = ctx + torch.tensor(lens, dtype=torch.int32, device=dev)
+        return lp, routing
+
     def decode_step(self, forced: Optional[torch.Tensor] = None, out_logprobs: Optional[torch.Tensor] = None,
                     want_logits=False, want_routing=False, want_sampled=False,
                     out_routing: Optional[torch.Tensor] = None) -> StepOutput:
