@@ -31,7 +31,7 @@ def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
-def gpu_random_model(pkg, synthetic, shape, split, seed=0):
+def gpu_random_model(pkg, synthetic, shape, split, seed=0, fmt="bf16"):
     """Random-init weights of the named shape generated on the device (same distributions as
     rollout_inputs: matrices N(0, 0.02), gains 1 + N(0, 0.02), router N(0, 1/d))."""
     import torch
@@ -48,9 +48,9 @@ def gpu_random_model(pkg, synthetic, shape, split, seed=0):
             t.mul_(0.02).add_(1.0)
         else:
             t.mul_(1.0 / np.sqrt(shape.d_model))
-        return t.to(torch.bfloat16)
+        return t.to(torch.float16 if fmt == "f16" else torch.bfloat16)
 
-    return pkg.RolloutModel(synthetic.config_from_shape(shape, split), tensor)
+    return pkg.RolloutModel(synthetic.config_from_shape(shape, split, fmt), tensor)
 
 
 def kernel_bytes(shape, cls, ctx_sum_plus_b, touched=None):
@@ -118,7 +118,7 @@ def traffic_record(workload, kernel_class):
     return float(rec["ratio_measured_over_algorithmic"])
 
 
-def cpu_baseline(shape, wl, budget_s=25.0):
+def cpu_baseline(shape, wl, budget_s=25.0, fmt="bf16"):
     """The oracle's decode step timed on the host: 1- and 3-layer slices of the same shape with the
     full batch and start-of-decode context lengths (synthetic KV contents), scaled to all layers."""
     import oracle as O
@@ -130,13 +130,13 @@ def cpu_baseline(shape, wl, budget_s=25.0):
     tensors = {}
     for l in [RI.GLOBAL_LAYER] + list(range(nl)):
         for n in RI.tensor_names(sub, l):
-            tensors[(l, n)] = RI.tensor_bf16(sub, 0, l, n)
+            tensors[(l, n)] = RI.tensor_bits(sub, 0, l, n, fmt)
     rng = np.random.default_rng(0)
     times = {}
     bs = min(wl.batch, 16)          # bounded sample: the first 16 sequences of the batch
     for k in (1, nl):
         shp = shape.replace(n_layers=k)
-        model = O.OracleModel(shp, 0, tensors={key: v for key, v in tensors.items() if key[0] < k})
+        model = O.OracleModel(shp, 0, tensors={key: v for key, v in tensors.items() if key[0] < k}, fmt=fmt)
         model.globals
         for l in range(k):
             model.layer(l)
@@ -172,7 +172,10 @@ def main():
     ap.add_argument("--steps", type=int, default=0, help="decode steps to time (0 = the whole decode phase)")
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="dense_b64", choices=["dense_b64", "moe_b128"])
-    ap.add_argument("--split", type=int, default=-1, help="activation_split (default 1: two bf16 terms per activation)")
+    ap.add_argument("--split", type=int, default=-1,
+                    help="activation_split (default: 1 for bf16, two terms per activation; 0 for f16, one term)")
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"],
+                    help="16-bit format of weights, KV pages and activation terms (f16: the FP16 precision option)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel", default="auto", help="kernel class for the roofline record")
     ap.add_argument("--copy-probe", action="store_true",
@@ -195,15 +198,16 @@ def main():
         shape, wl = RI.QWEN3_4B, RI.workload_dense_batch()
     else:
         shape, wl = RI.QWEN3_30B_A3B, RI.workload_moe_batch()
-    split = args.split if args.split >= 0 else 1     # the setting the parity tests at this shape pass with
+    # the settings the parity tests at this shape pass with
+    split = args.split if args.split >= 0 else (1 if args.dtype == "bf16" else 0)
     n_decode = int(wl.n_decode[0])
     bsz = wl.batch
     plen = wl.prompt_lens
-    log("workload %s: %s, batch %d, prompts %d..%d, decode %d, activation_split %d" % (
-        args.workload, shape.name, bsz, plen.min(), plen.max(), n_decode, split))
+    log("workload %s: %s, batch %d, prompts %d..%d, decode %d, %s, activation_split %d" % (
+        args.workload, shape.name, bsz, plen.min(), plen.max(), n_decode, args.dtype, split))
 
     t0 = time.perf_counter()
-    model = gpu_random_model(pkg, synthetic, shape, split)
+    model = gpu_random_model(pkg, synthetic, shape, split, fmt=args.dtype)
     torch.cuda.synchronize()
     log("weights on device: %.2f GB in %.1f s" % (model.weight_bytes() / 1e9, time.perf_counter() - t0))
 
@@ -329,7 +333,7 @@ def main():
         "metric": "rollout decode tokens/sec on 1 MI355X; % of HBM roofline per step",
         "value": toks_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": "%s: %s, batch %d, prompts uniform %d..%d, %d decoded tokens, paged bf16 KV block 16, "
                                "temperature 1 Gumbel-max" % (args.workload, shape.name, bsz, plen.min(), plen.max(),
                                                               n_decode),
@@ -347,7 +351,7 @@ def main():
                      "per_step_ms_by_class": per_class},
     }
     if not args.no_cpu_baseline:
-        rec["cpu_baseline"] = cpu_baseline(shape, wl)
+        rec["cpu_baseline"] = cpu_baseline(shape, wl, fmt=args.dtype)
     print(json.dumps(rec), flush=True)
 
 

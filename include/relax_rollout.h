@@ -14,7 +14,9 @@
  *
  * Conventions
  *  - Every array argument is a DEVICE pointer unless its comment says HOST.
- *  - All matrices are bf16 with logical shape [out_features, in_features] (y = x W^T).
+ *  - All matrices are 16-bit floats (bf16, or IEEE fp16 for a model created with RLX_DTYPE_F16: the FP16
+ *    precision option of the paper's FP16-vs-BF16 ablation) with logical shape [out_features, in_features]
+ *    (y = x W^T).  One model uses one format for its weights, gains, embeddings and KV pages.
  *    The projection matrices and the LM head are passed in the library's packed
  *    streaming layout, produced from row-major storage by rlx_pack_weight; the
  *    embedding table and the norm gains stay row-major.
@@ -49,6 +51,9 @@ extern "C" {
 #define RLX_EHIP (-3)         /* a HIP runtime call failed                        */
 #define RLX_EUNSUPPORTED (-4) /* shape outside what the kernels are built for     */
 
+#define RLX_DTYPE_BF16 0
+#define RLX_DTYPE_F16 1
+
 typedef struct rlx_model rlx_model;
 
 /* Shape of the policy.  Plain data, passed by const pointer. */
@@ -63,13 +68,20 @@ typedef struct {
   float rope_theta;      /* rotary base; pair (i, i+head_dim/2) turns by pos*theta^(-2i/head_dim) */
   int32_t qk_norm;       /* 1: per-head RMSNorm of q and k before the rotary embedding */
   int32_t eos_token_id, pad_token_id;
-  int32_t activation_split; /* 0: activations enter every matrix product as one bf16 value;
-                               1: as two bf16 terms (hi + lo, 16 significand bits, twice the MFMA work) */
+  int32_t activation_split; /* 0: activations enter every matrix product as one 16-bit value (8 significand
+                               bits for bf16, 11 for fp16);
+                               1: as two bf16 terms (hi + lo, 16 significand bits; twice the MFMA work and
+                               twice the activation traffic).  Must be 0 for RLX_DTYPE_F16: the low term of
+                               an fp16 pair would mostly be subnormal (RLX_EUNSUPPORTED) */
+  int32_t dtype;            /* RLX_DTYPE_BF16 or RLX_DTYPE_F16: format of every weight tensor, of input_embeds
+                               and of the KV pool.  fp16 values past 65504 in magnitude (weights, keys, values or
+                               activations entering a matrix product) become infinities: the caller picks fp16
+                               only for models whose activations stay in range */
 } rlx_model_config;
 
 /*
  * Weights.  Scalars point at device tensors; the per-layer members are HOST arrays
- * of n_layers device pointers (copied at create).  Logical shapes (bf16); (P) marks
+ * of n_layers device pointers (copied at create).  Logical shapes (elements of the model's dtype); (P) marks
  * the tensors that must be in the packed layout (each expert matrix packed on its
  * own, experts stored back to back):
  *   embed [vocab, d_model]; lm_head (P) [vocab, d_model]; final_norm [d_model]
@@ -105,7 +117,7 @@ typedef struct {
  * Packed streaming layout of a [n, k] matrix (k a multiple of 16): rows are padded
  * to a multiple of 32 with zeros and stored as (n/32) x (k/16) blocks of 1 KB, block
  * (i, j) holding rows 32i..32i+31, columns 16j..16j+15 in the operand order of the
- * 32x32x16 bf16 MFMA (16-byte group g of a block = row 32i + g mod 32, columns
+ * 32x32x16 MFMA on 16-bit operands (16-byte group g of a block = row 32i + g mod 32, columns
  * 16j + 8 (g div 32) .. +7), so that a wavefront streams a row tile as one contiguous
  * run.  rlx_pack_weight converts `count` row-major matrices stored back to back
  * (src, device) into `count` packed matrices stored back to back (dst, device, of
@@ -137,7 +149,7 @@ RLX_API int rlx_model_destroy(rlx_model* m);
 RLX_API int rlx_model_set_attention_grid(rlx_model* m, int32_t n_workgroups);
 
 /*
- * Size in bytes of a KV pool of n_blocks pages (bf16).  Layout, private to the
+ * Size in bytes of a KV pool of n_blocks pages (2 bytes per element, the model's dtype).  Layout, private to the
  * library: [layer][block][kv_head]{ K[16][head_dim], V^T[head_dim][16] }.
  * The caller allocates it (256-byte aligned) and passes n_blocks to every call.
  */
@@ -179,7 +191,7 @@ RLX_API int rlx_kv_copy_blocks(const rlx_model* m, void* kv_pool, int64_t n_bloc
  * Append a chunk of known tokens to each of n_seqs sequences (varlen, packed) and,
  * where sample_last[i] != 0, emit the next token from the chunk's last position.
  *   token_ids     int32 [total_tokens]; -1 = take the row of input_embeds instead
- *   input_embeds  bf16 [total_tokens, d_model] or NULL (rows used only where id == -1)
+ *   input_embeds  [total_tokens, d_model] in the model's dtype, or NULL (rows used only where id == -1)
  *   cu_seqlens    int32 [n_seqs+1], cu_seqlens[0] = 0, cu_seqlens[n_seqs] = total_tokens
  *   ctx_lens      int32 [n_seqs] tokens already cached before this chunk (not modified)
  *   sample_last   uint8 [n_seqs]

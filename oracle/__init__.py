@@ -16,7 +16,8 @@ Arithmetic is float32 by default (every function follows the dtype of its
 inputs, so tests can also run it in float64); weights are bf16 bit patterns
 upcast exactly.  The workloads fix the KV cache as bf16, so keys and values are
 rounded to bf16 (nearest-even) once, when stored; everything else stays in the
-working dtype.
+working dtype.  The FP16 precision option (paper App. "FP16 vs. BF16 precision
+ablation") replaces bf16 by IEEE fp16 in both places and nothing else.
 
 Nothing in the product path may import this package: only tests/, the smoke
 check and the benchmark's CPU-baseline leg use it.  It shares no code with the
@@ -30,8 +31,8 @@ checkpoint is available offline).
 from .layers import (rmsnorm, rope, attention, attention_bruteforce, silu, swiglu_ffn, moe_gate, moe_ffn,
                      moe_ffn_bruteforce, log_softmax)
 from .philox import philox4x32_10, uniform_u32, gumbel_noise, sample_gumbel_max
-from .model import OracleModel, forward_full, OracleRollout, round_to_bf16
+from .model import OracleModel, forward_full, OracleRollout, round_to_bf16, round_to_f16
 
 __all__ = ["rmsnorm", "rope", "attention", "attention_bruteforce", "silu", "swiglu_ffn", "moe_gate",
            "moe_ffn", "moe_ffn_bruteforce", "log_softmax", "philox4x32_10", "uniform_u32", "gumbel_noise",
-           "sample_gumbel_max", "OracleModel", "forward_full", "OracleRollout", "round_to_bf16"]
+           "sample_gumbel_max", "OracleModel", "forward_full", "OracleRollout", "round_to_bf16", "round_to_f16"]

@@ -13,7 +13,7 @@ from typing import Dict, List, Optional, Sequence
 
 import numpy as np
 
-from rollout_inputs import GLOBAL_LAYER, ModelShape, bf16_bits_to_f32, layer_tensors_bf16
+from rollout_inputs import GLOBAL_LAYER, ModelShape, bits_to_f32, layer_tensors
 
 from . import layers as L
 from .philox import sample_gumbel_max
@@ -29,21 +29,34 @@ def round_to_bf16(x: np.ndarray) -> np.ndarray:
     return u.view(np.float32).astype(x.dtype)
 
 
-class OracleModel:
-    """Weights of one synthetic policy, upcast from bf16 bit patterns.
+def round_to_f16(x: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even to the IEEE fp16 grid (11 significand bits, subnormals below 2^-14,
+    infinities past 65504), result kept in x's dtype: the KV store of the FP16 precision option
+    (paper App. "FP16 vs. BF16 precision ablation").  NumPy's float16 conversion is the rounding."""
+    with np.errstate(over="ignore"):
+        return np.asarray(x).astype(np.float16).astype(np.asarray(x).dtype)
 
-    kv_bf16: keys/values are rounded to bf16 when stored (what the workloads specify);
-    False keeps them in the working dtype (used by pins that need exact algebra).
+
+KV_ROUNDING = {"bf16": round_to_bf16, "f16": round_to_f16}
+
+
+class OracleModel:
+    """Weights of one synthetic policy, upcast exactly from 16-bit patterns of format `fmt`
+    ("bf16", or "f16" for the FP16 precision option: weights and the KV store are fp16).
+
+    kv_bf16: keys/values are rounded to the model's 16-bit format when stored (what the workloads
+    specify); False keeps them in the working dtype (used by pins that need exact algebra).
 
     Layers are materialised on demand; with cache_layers=False only one layer is
     resident at a time (needed for the 30B-shape model on a small host).
-    `tensors` may supply the bf16 bit patterns directly: {(layer, name): uint16 array}.
+    `tensors` may supply the bit patterns directly: {(layer, name): uint16 array}.
     """
 
     def __init__(self, shape: ModelShape, model_seed: int = 0, cache_layers: bool = True,
-                 dtype=np.float32, tensors: Optional[Dict] = None, kv_bf16: bool = True):
+                 dtype=np.float32, tensors: Optional[Dict] = None, kv_bf16: bool = True, fmt: str = "bf16"):
         self.shape = shape
-        self.kv_bf16 = kv_bf16
+        self.fmt = fmt
+        self.kv_round = KV_ROUNDING[fmt] if kv_bf16 else None
         self.model_seed = model_seed
         self.dtype = np.dtype(dtype)
         self.cache_layers = cache_layers
@@ -54,8 +67,8 @@ class OracleModel:
         if self._tensors is not None:
             bits = {n: b for (l, n), b in self._tensors.items() if l == layer}
         else:
-            bits = layer_tensors_bf16(self.shape, self.model_seed, layer)
-        return {n: bf16_bits_to_f32(b).astype(self.dtype, copy=False) for n, b in bits.items()}
+            bits = layer_tensors(self.shape, self.model_seed, layer, self.fmt)
+        return {n: bits_to_f32(b, self.fmt).astype(self.dtype, copy=False) for n, b in bits.items()}
 
     def layer(self, layer: int) -> Dict[str, np.ndarray]:
         if layer in self._cache:
@@ -77,20 +90,20 @@ class OracleModel:
 
 def _embed(model: OracleModel, tokens: np.ndarray, embeds: Optional[np.ndarray]) -> np.ndarray:
     """h[p] = embed[token p], or the injected embedding row where token == -1
-    (rows of `embeds`, bf16 bit patterns, are consumed in order)."""
+    (rows of `embeds`, bit patterns of the model's format, are consumed in order)."""
     g = model.globals
     tokens = np.asarray(tokens)
     h = np.empty((len(tokens), model.shape.d_model), dtype=model.dtype)
     inj = tokens < 0
     h[~inj] = g["embed"][tokens[~inj]]
     if inj.any():
-        e = bf16_bits_to_f32(np.asarray(embeds)).astype(model.dtype)
+        e = bits_to_f32(np.asarray(embeds), model.fmt).astype(model.dtype)
         assert e.shape[0] == int(inj.sum()), "one embedding row per injected position"
         h[inj] = e
     return h
 
 
-def _qkv(shape: ModelShape, w: Dict[str, np.ndarray], h: np.ndarray, pos: np.ndarray, kv_bf16: bool):
+def _qkv(shape: ModelShape, w: Dict[str, np.ndarray], h: np.ndarray, pos: np.ndarray, kv_round):
     x = L.rmsnorm(h, w["attn_norm"], shape.rms_eps)
     n = h.shape[0]
     q = (x @ w["wq"].T).reshape(n, shape.n_q_heads, shape.head_dim)
@@ -101,8 +114,8 @@ def _qkv(shape: ModelShape, w: Dict[str, np.ndarray], h: np.ndarray, pos: np.nda
         k = L.rmsnorm(k, w["k_norm"], shape.rms_eps)
     q = L.rope(q, pos, shape.rope_theta)
     k = L.rope(k, pos, shape.rope_theta)
-    if kv_bf16:
-        k, v = round_to_bf16(k), round_to_bf16(v)
+    if kv_round is not None:
+        k, v = kv_round(k), kv_round(v)
     return q, k, v
 
 
@@ -150,7 +163,7 @@ def forward_full(model: OracleModel, tokens: Sequence[np.ndarray], embeds: Seque
         for i in range(nseq):
             h = hs[i]
             n = h.shape[0]
-            q, k, v = _qkv(s, w, h, np.arange(n), model.kv_bf16)
+            q, k, v = _qkv(s, w, h, np.arange(n), model.kv_round)
             o = L.attention(q, k, v).reshape(n, s.q_dim)
             h = h + o @ w["wo"].T
             fr = None if forced_routing[i] is None else forced_routing[i][:, l, :]
@@ -258,7 +271,7 @@ class OracleRollout:
             for j, i in enumerate(seq_ids):
                 h = hs[j]
                 n, p0 = h.shape[0], self.ctx[i]
-                q, k, v = _qkv(s, w, h, np.arange(p0, p0 + n), m.kv_bf16)
+                q, k, v = _qkv(s, w, h, np.arange(p0, p0 + n), m.kv_round)
                 blk, slot = self._slots(i, p0, n)
                 self.kpool[l, blk, slot] = k
                 self.vpool[l, blk, slot] = v

@@ -39,7 +39,8 @@ class ModelConfig(C.Structure):
                 ("n_experts", C.c_int32), ("top_k", C.c_int32), ("d_ff_expert", C.c_int32),
                 ("vocab", C.c_int32), ("kv_block_size", C.c_int32),
                 ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("qk_norm", C.c_int32),
-                ("eos_token_id", C.c_int32), ("pad_token_id", C.c_int32), ("activation_split", C.c_int32)]
+                ("eos_token_id", C.c_int32), ("pad_token_id", C.c_int32), ("activation_split", C.c_int32),
+                ("dtype", C.c_int32)]
 
 
 _PP = C.POINTER(C.c_void_p)
@@ -92,12 +93,17 @@ def _check(rc: int) -> None:
         raise RlxError(rc, lib().rlx_last_error().decode("utf-8", "replace"))
 
 
+# the library's 16-bit element formats (RLX_DTYPE_BF16 / RLX_DTYPE_F16) as torch dtypes
+RLX_DTYPE_BF16, RLX_DTYPE_F16 = 0, 1
+H16 = (torch.bfloat16, torch.float16)
+
+
 def _ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
     if t is None:
         return None
     if not t.is_cuda or not t.is_contiguous():
         raise ValueError("expected a contiguous CUDA tensor")
-    if dtype is not None and t.dtype != dtype:
+    if dtype is not None and t.dtype not in (dtype if isinstance(dtype, tuple) else (dtype,)):
         raise ValueError("expected dtype %s, got %s" % (dtype, t.dtype))
     return t.data_ptr()
 
@@ -118,32 +124,32 @@ def rlx_packed_weight_bytes(n: int, k: int) -> int:
 
 
 def rlx_pack_weight(src: torch.Tensor, dst: torch.Tensor, count: int, n: int, k: int, stream=None) -> None:
-    _check(lib().rlx_pack_weight(_ptr(src, torch.bfloat16), _ptr(dst, torch.bfloat16), count, n, k, _stream(stream)))
+    _check(lib().rlx_pack_weight(_ptr(src, H16), _ptr(dst, H16), count, n, k, _stream(stream)))
 
 
 def pack_matrix(w: torch.Tensor) -> torch.Tensor:
-    """Row-major bf16 [.., n, k] (leading dims = stacked matrices) -> packed streaming layout."""
+    """Row-major 16-bit [.., n, k] (leading dims = stacked matrices) -> packed streaming layout."""
     n, k = w.shape[-2], w.shape[-1]
     count = int(w.numel() // (n * k))
     per = rlx_packed_weight_bytes(n, k) // 2
-    dst = torch.empty(count * per, dtype=torch.bfloat16, device=w.device)
+    dst = torch.empty(count * per, dtype=w.dtype, device=w.device)
     rlx_pack_weight(w.contiguous(), dst, count, n, k)
     return dst
 
 
 def rlx_pack_gate_up(gate, up, dst, count: int, f: int, k: int, stream=None) -> None:
-    _check(lib().rlx_pack_gate_up(_ptr(gate, torch.bfloat16), _ptr(up, torch.bfloat16), _ptr(dst, torch.bfloat16),
+    _check(lib().rlx_pack_gate_up(_ptr(gate, H16), _ptr(up, H16), _ptr(dst, H16),
                                   count, f, k, _stream(stream)))
 
 
 def pack_gate_up(gate: torch.Tensor, up: torch.Tensor) -> torch.Tensor:
-    """Row-major bf16 gate/up [.., f, k] -> interleaved packed [2f, k] matrices."""
+    """Row-major 16-bit gate/up [.., f, k] -> interleaved packed [2f, k] matrices."""
     f, k = gate.shape[-2], gate.shape[-1]
     if up.shape != gate.shape:
         raise ValueError("gate and up must have the same shape")
     count = int(gate.numel() // (f * k))
     per = rlx_packed_weight_bytes(2 * f, k) // 2
-    dst = torch.empty(count * per, dtype=torch.bfloat16, device=gate.device)
+    dst = torch.empty(count * per, dtype=gate.dtype, device=gate.device)
     rlx_pack_gate_up(gate.contiguous(), up.contiguous(), dst, count, f, k)
     return dst
 
@@ -185,7 +191,7 @@ def rollout_prefill_chunk(model, kv_pool, n_blocks, workspace, n_seqs, total_tok
                           out_routing=None, out_logits=None, stream=None) -> None:
     _check(lib().rollout_prefill_chunk(
         model, _ptr(kv_pool), n_blocks, _ptr(workspace), workspace.numel() * workspace.element_size(),
-        n_seqs, total_tokens, _ptr(token_ids, torch.int32), _ptr(input_embeds, torch.bfloat16),
+        n_seqs, total_tokens, _ptr(token_ids, torch.int32), _ptr(input_embeds, H16),
         _ptr(cu_seqlens, torch.int32), _ptr(ctx_lens, torch.int32), _ptr(block_table, torch.int32),
         max_blocks_per_seq, _ptr(sample_last, torch.uint8), _ptr(seeds, torch.int64),
         _ptr(temperature, torch.float32), _ptr(max_ctx_len, torch.int32), _ptr(forced_tokens, torch.int32),
@@ -199,7 +205,7 @@ def rollout_score_chunk(model, kv_pool, n_blocks, workspace, n_seqs, total_token
                         out_logprobs, out_routing=None, stream=None) -> None:
     _check(lib().rollout_score_chunk(
         model, _ptr(kv_pool), n_blocks, _ptr(workspace), workspace.numel() * workspace.element_size(),
-        n_seqs, total_tokens, _ptr(token_ids, torch.int32), _ptr(input_embeds, torch.bfloat16),
+        n_seqs, total_tokens, _ptr(token_ids, torch.int32), _ptr(input_embeds, H16),
         _ptr(cu_seqlens, torch.int32), _ptr(ctx_lens, torch.int32), _ptr(block_table, torch.int32),
         max_blocks_per_seq, _ptr(target_ids, torch.int32), _ptr(temperature, torch.float32),
         _ptr(replay_routing, torch.int32), _ptr(out_logprobs, torch.float32), _ptr(out_routing, torch.int32),
@@ -266,5 +272,5 @@ def make_pointer_table(tensors: Sequence[Optional[torch.Tensor]]):
     """Host array of device pointers for one per-layer member of rlx_weights."""
     arr = (C.c_void_p * len(tensors))()
     for i, t in enumerate(tensors):
-        arr[i] = _ptr(t, torch.bfloat16)
+        arr[i] = _ptr(t, H16)
     return arr

@@ -57,8 +57,8 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 struct rlx_model {
   rlx_model_config cfg;
-  const bf16_t *embed, *lm_head, *final_norm;
-  std::vector<const bf16_t*> attn_norm, wq, wk, wv, wo, q_norm, k_norm, ffn_norm, w_gate_up, w_down, w_router;
+  const h16_t *embed, *lm_head, *final_norm;
+  std::vector<const h16_t*> attn_norm, wq, wk, wv, wo, q_norm, k_norm, ffn_norm, w_gate_up, w_down, w_router;
   double* inv_freq;   // device, [head_dim / 2]
   int device;
   int n_units;        // compute units of the device
@@ -70,19 +70,19 @@ namespace {
 struct Workspace {
   TokenMeta meta;
   float* h;          // [T, d]
-  bf16_t* xb;        // [planes][T, d]; every bf16 activation buffer below has `planes` copies
+  h16_t* xb;        // [planes][T, d]; every bf16 activation buffer below has `planes` copies
   float* router;     // [planes][T, E] router logits (MoE)
   float* qkv;        // [planes][T, qkv_dim]
-  bf16_t* q;         // [T, q_dim]
-  bf16_t* ob;        // [T, q_dim]
+  h16_t* q;         // [T, q_dim]
+  h16_t* ob;        // [T, q_dim]
   float* attn_part;  // [attn_wgs][2][Hq/Hkv][hd+4] decode partials of straddling (sequence, KV head) pairs
   int32_t *attn_prefix, *attn_wg_seq, *attn_hdr;   // decode attention plan
   float* planes;     // split-K planes of the o / down projections
-  bf16_t* act;       // dense [T, F]; MoE [T*top_k, Fe]
+  h16_t* act;       // dense [T, F]; MoE [T*top_k, Fe]
   float* moe_y;      // [T*top_k, d]
   int32_t* topk_idx; float* topk_w;
   int32_t *counts, *group_off, *sorted_token, *pair_pos;
-  bf16_t* x_lm;      // [S, d]
+  h16_t* x_lm;      // [S, d]
   float* lm_part;    // [S][tiles][4]
   size_t bytes;
 };
@@ -118,11 +118,11 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
   w.meta.rope_cs = (float2*)take((size_t)S * (c.head_dim / 2) * sizeof(float2));
   w.h = (float*)take((size_t)T * c.d_model * 4);
   const int PL = c.activation_split ? 2 : 1;
-  w.xb = (bf16_t*)take(frag_act_elems(T, c.d_model, PL) * 2);
+  w.xb = (h16_t*)take(frag_act_elems(T, c.d_model, PL) * 2);
   w.router = c.n_experts ? (float*)take((size_t)plane_rows(T) * c.n_experts * 4) : nullptr;
   w.qkv = (float*)take((size_t)plane_rows(T) * qkv_dim * 4);
-  w.q = (bf16_t*)take((size_t)PL * T * qdim * 2);
-  w.ob = (bf16_t*)take(frag_act_elems(T, qdim, PL) * 2);
+  w.q = (h16_t*)take((size_t)PL * T * qdim * 2);
+  w.ob = (h16_t*)take(frag_act_elems(T, qdim, PL) * 2);
   w.attn_part = (float*)take((size_t)ATTN_WGS_MAX * 2 * (c.n_q_heads / c.n_kv_heads) * (c.head_dim + 4) * 4);
   w.attn_prefix = (int32_t*)take((size_t)(S + 1) * 4);
   w.attn_wg_seq = (int32_t*)take((size_t)ATTN_WGS_MAX * 4);
@@ -130,7 +130,7 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
   w.planes = (float*)take((size_t)plane_rows(T) * c.d_model * 4);
   if (c.n_experts) {
     const size_t P = (size_t)T * c.top_k;
-    w.act = (bf16_t*)take(frag_act_elems((int)P, c.d_ff_expert, PL) * 2);
+    w.act = (h16_t*)take(frag_act_elems((int)P, c.d_ff_expert, PL) * 2);
     w.moe_y = (float*)take(P * c.d_model * 4);
     w.topk_idx = (int32_t*)take(P * 4);
     w.topk_w = (float*)take(P * 4);
@@ -139,10 +139,10 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
     w.sorted_token = (int32_t*)take(P * 4);
     w.pair_pos = (int32_t*)take(P * 4);
   } else {
-    w.act = (bf16_t*)take(frag_act_elems(T, c.d_ff, PL) * 2);
+    w.act = (h16_t*)take(frag_act_elems(T, c.d_ff, PL) * 2);
   }
   const int lm_rows = S > SCORE_ROWS ? S : SCORE_ROWS;   // sampled rows of a call, or one block of scored rows
-  w.x_lm = (bf16_t*)take(frag_act_elems(lm_rows, c.d_model, PL) * 2);
+  w.x_lm = (h16_t*)take(frag_act_elems(lm_rows, c.d_model, PL) * 2);
   w.lm_part = (float*)take((size_t)lm_rows * lmhead_tiles(c.vocab) * 4 * 4);
   w.bytes = off;
   return w;
@@ -153,7 +153,7 @@ size_t block_elems(const rlx_model_config& c) { return (size_t)c.n_kv_heads * 2 
 struct StepIO {
   int n_seqs, T;
   bool decode;
-  const int32_t* tokens; const bf16_t* input_embeds;
+  const int32_t* tokens; const h16_t* input_embeds;
   const int32_t* cu_seqlens; const int32_t* ctx_lens;
   const int32_t* block_table; int max_blocks;
   const uint64_t* seeds; const float* temperature; const int32_t* max_ctx_len; const int32_t* forced;
@@ -165,21 +165,22 @@ struct StepIO {
   const int32_t* replay_routing;   // optional [T, n_layers, top_k]
 };
 
-int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspace& w, const StepIO& io,
+int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspace& w, const StepIO& io,
                hipStream_t st) {
   const rlx_model_config& c = m->cfg;
   const int d = c.d_model, T = io.T;
   const int qdim = c.n_q_heads * c.head_dim, kvdim = c.n_kv_heads * c.head_dim, qkv_dim = qdim + 2 * kvdim;
   const bool small = T <= 256;
   const int PL = c.activation_split ? 2 : 1;
-  const Act xb = make_act(w.xb, T, d, PL), ob = make_act(w.ob, T, qdim, PL);
-  const RowAct qb = {w.q, (size_t)T * qdim, qdim, PL};
+  const int FMT = c.dtype;
+  const Act xb = make_act(w.xb, T, d, PL, FMT), ob = make_act(w.ob, T, qdim, PL, FMT);
+  const RowAct qb = {w.q, (size_t)T * qdim, qdim, PL, FMT};
 
-  RLX_HIP(embed_tokens(m->embed, c.vocab, d, io.tokens, io.input_embeds, T, w.h, st));
+  RLX_HIP(embed_tokens(m->embed, c.vocab, d, io.tokens, io.input_embeds, T, w.h, FMT, st));
 
   // residual contribution produced by the previous sub-layer, folded into the next norm
   const float* pend_planes = nullptr; int pend_n = 0; bool pend_moe = false;
-  auto norm = [&](const bf16_t* gain, const int32_t* rows, int n_rows, const Act& x, float* xf) -> hipError_t {
+  auto norm = [&](const h16_t* gain, const int32_t* rows, int n_rows, const Act& x, float* xf) -> hipError_t {
     NormArgs a = {};
     a.h = w.h; a.gain = gain; a.d = d; a.T = n_rows; a.T_total = T; a.eps = c.rms_eps; a.rows = rows;
     a.add = pend_planes; a.n_planes = pend_n;
@@ -199,7 +200,7 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
     const int s_qkv = small ? gemm_plan_splits(qkv_dim, d, gemm_max_splits(), m->n_units) : 1;
     RLX_LAUNCH(RLX_K_QKV, gemm_store(wqkv, xb, T, w.qkv, qkv_dim, s_qkv, st));
 
-    bf16_t* pool_layer = pool + (size_t)l * n_blocks * block_elems(c);
+    h16_t* pool_layer = pool + (size_t)l * n_blocks * block_elems(c);
     RopeArgs r = {};
     r.qkv = w.qkv; r.n_planes = s_qkv;
     r.q_gain = c.qk_norm ? m->q_norm[l] : nullptr; r.k_gain = c.qk_norm ? m->k_norm[l] : nullptr;
@@ -234,7 +235,7 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
 
     RLX_LAUNCH(RLX_K_NORM, norm(m->ffn_norm[l], nullptr, T, xb, nullptr));
     if (c.n_experts == 0) {
-      const Act act = make_act(w.act, T, c.d_ff, PL);
+      const Act act = make_act(w.act, T, c.d_ff, PL, FMT);
       RLX_LAUNCH(RLX_K_GATEUP, gemm_swiglu(m->w_gate_up[l], c.d_ff, d, xb, T, act, st));
       const int s_d = small ? gemm_plan_splits(d, c.d_ff, gemm_max_splits(), m->n_units) : 1;
       RLX_LAUNCH(RLX_K_DOWN, gemm_store(linear1(m->w_down[l], d, c.d_ff), act, T, w.planes, d, s_d, st));
@@ -247,7 +248,7 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
       ra.topk_idx = w.topk_idx; ra.topk_w = w.topk_w; ra.routing_out = io.out_routing; ra.layer = l;
       ra.n_layers = c.n_layers; ra.tok_live = w.meta.tok_live; ra.replay_idx = io.replay_routing;
       RLX_LAUNCH(RLX_K_GROUP, moe_route(ra, w.group_off, w.sorted_token, w.pair_pos, w.meta.tickets, st));
-      const Act act = make_act(w.act, T * c.top_k, c.d_ff_expert, PL);
+      const Act act = make_act(w.act, T * c.top_k, c.d_ff_expert, PL, FMT);
       const int rows_per_expert = (int)(((long long)T * c.top_k + c.n_experts - 1) / c.n_experts);
       RLX_LAUNCH(RLX_K_GATEUP, gemm_grouped_swiglu(m->w_gate_up[l], c.n_experts, c.d_ff_expert, d, xb,
                                                    w.sorted_token, w.group_off, T, rows_per_expert, act, st));
@@ -263,7 +264,7 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
     const float* pp = pend_planes; const int pn = pend_n; const bool pm = pend_moe;
     for (int r0 = 0; r0 < T; r0 += SCORE_ROWS) {
       const int n = T - r0 < SCORE_ROWS ? T - r0 : SCORE_ROWS;
-      const Act x_lm = make_act(w.x_lm, n, d, PL);
+      const Act x_lm = make_act(w.x_lm, n, d, PL, FMT);
       pend_planes = pp; pend_n = pn; pend_moe = pm;
       RLX_HIP(norm(m->final_norm, w.meta.tok_iota + r0, n, x_lm, nullptr));
       RLX_LAUNCH(RLX_K_LMHEAD, gemm_lmhead(m->lm_head, c.vocab, d, x_lm, n, nullptr, w.lm_part, nullptr, io.temperature,
@@ -280,7 +281,7 @@ int run_layers(const rlx_model* m, bf16_t* pool, int64_t n_blocks, const Workspa
 
   // final norm of the rows that emit a token, LM head with fused log-sum-exp / Gumbel-max partials
   const int S = io.n_seqs;
-  const Act x_lm = make_act(w.x_lm, S, d, PL);
+  const Act x_lm = make_act(w.x_lm, S, d, PL, FMT);
   RLX_HIP(norm(m->final_norm, w.meta.sample_row, S, x_lm, nullptr));
   RLX_LAUNCH(RLX_K_LMHEAD, gemm_lmhead(m->lm_head, c.vocab, d, x_lm, S, io.out_logits, w.lm_part, io.seeds,
                                        io.temperature, w.meta.sample_pos, nullptr, true, st));
@@ -341,6 +342,9 @@ int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* wt, rlx_mod
   if (!(c.rms_eps >= 0.f) || !(c.rope_theta > 0.f)) return fail(RLX_EINVAL, "rms_eps / rope_theta");
   if (c.activation_split != 0 && c.activation_split != 1) return fail(RLX_EINVAL, "activation_split must be 0 or 1");
   if (c.qk_norm != 0 && c.qk_norm != 1) return fail(RLX_EINVAL, "qk_norm must be 0 or 1");
+  if (c.dtype != RLX_DTYPE_BF16 && c.dtype != RLX_DTYPE_F16) return fail(RLX_EINVAL, "dtype must be RLX_DTYPE_BF16 or RLX_DTYPE_F16");
+  if (c.dtype == RLX_DTYPE_F16 && c.activation_split)
+    return fail(RLX_EUNSUPPORTED, "fp16 models carry activations as one term: activation_split must be 0");
   if (!wt->embed || !wt->lm_head || !wt->final_norm) return fail(RLX_EINVAL, "NULL global weight");
   if (!aligned16(wt->embed) || !aligned16(wt->lm_head) || !aligned16(wt->final_norm))
     return fail(RLX_EINVAL, "weights must be 16-byte aligned");
@@ -353,15 +357,15 @@ int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* wt, rlx_mod
   rlx_model* m = new (std::nothrow) rlx_model();
   if (!m) return fail(RLX_ENOMEM, "host allocation failed");
   m->cfg = c;
-  m->embed = (const bf16_t*)wt->embed; m->lm_head = (const bf16_t*)wt->lm_head;
-  m->final_norm = (const bf16_t*)wt->final_norm;
+  m->embed = (const h16_t*)wt->embed; m->lm_head = (const h16_t*)wt->lm_head;
+  m->final_norm = (const h16_t*)wt->final_norm;
   m->inv_freq = nullptr;
-  auto copy = [&](std::vector<const bf16_t*>& dst, const void* const* src) -> bool {
+  auto copy = [&](std::vector<const h16_t*>& dst, const void* const* src) -> bool {
     dst.resize(c.n_layers, nullptr);
     if (!src) return true;
     for (int l = 0; l < c.n_layers; ++l) {
       if (!src[l] || !aligned16(src[l])) return false;
-      dst[l] = (const bf16_t*)src[l];
+      dst[l] = (const h16_t*)src[l];
     }
     return true;
   };
@@ -433,7 +437,7 @@ int rlx_workspace_bytes(const rlx_model* m, int32_t max_seqs, int32_t max_tokens
 int rlx_kv_copy_blocks(const rlx_model* m, void* kv_pool, int64_t n_blocks, const int32_t* src, const int32_t* dst,
                        int32_t n, void* stream) {
   if (!m || !kv_pool || n_blocks <= 0 || n < 0 || (n > 0 && (!src || !dst))) return fail(RLX_EINVAL, "bad argument");
-  RLX_HIP(kv_copy_blocks((bf16_t*)kv_pool, n_blocks, m->cfg.n_layers, block_elems(m->cfg), src, dst, n,
+  RLX_HIP(kv_copy_blocks((h16_t*)kv_pool, n_blocks, m->cfg.n_layers, block_elems(m->cfg), src, dst, n,
                          (hipStream_t)stream));
   return RLX_OK;
 }
@@ -460,12 +464,12 @@ int rollout_prefill_chunk(const rlx_model* m, void* kv_pool, int64_t n_blocks, v
   RLX_HIP(meta_prefill(w.meta, n_seqs, total_tokens, cu_seqlens, ctx_lens, sample_last, st));
   StepIO io = {};
   io.n_seqs = n_seqs; io.T = total_tokens; io.decode = false;
-  io.tokens = token_ids; io.input_embeds = (const bf16_t*)input_embeds; io.cu_seqlens = cu_seqlens;
+  io.tokens = token_ids; io.input_embeds = (const h16_t*)input_embeds; io.cu_seqlens = cu_seqlens;
   io.ctx_lens = ctx_lens; io.block_table = block_table; io.max_blocks = max_blocks_per_seq;
   io.seeds = seeds; io.temperature = temperature; io.max_ctx_len = max_ctx_len; io.forced = forced_tokens;
   io.out_tokens = out_tokens; io.out_logprobs = out_logprobs; io.finished = finished_out;
   io.out_sampled = out_sampled; io.out_routing = m->cfg.n_experts ? out_routing : nullptr; io.out_logits = out_logits;
-  return run_layers(m, (bf16_t*)kv_pool, n_blocks, w, io, st);
+  return run_layers(m, (h16_t*)kv_pool, n_blocks, w, io, st);
 }
 
 int rollout_score_chunk(const rlx_model* m, void* kv_pool, int64_t n_blocks, void* workspace, size_t workspace_bytes,
@@ -487,13 +491,13 @@ int rollout_score_chunk(const rlx_model* m, void* kv_pool, int64_t n_blocks, voi
   RLX_HIP(meta_prefill(w.meta, n_seqs, total_tokens, cu_seqlens, ctx_lens, nullptr, st));
   StepIO io = {};
   io.n_seqs = n_seqs; io.T = total_tokens; io.decode = false;
-  io.tokens = token_ids; io.input_embeds = (const bf16_t*)input_embeds; io.cu_seqlens = cu_seqlens;
+  io.tokens = token_ids; io.input_embeds = (const h16_t*)input_embeds; io.cu_seqlens = cu_seqlens;
   io.ctx_lens = ctx_lens; io.block_table = block_table; io.max_blocks = max_blocks_per_seq;
   io.temperature = temperature;
   io.out_routing = m->cfg.n_experts ? out_routing : nullptr;
   io.score = true; io.score_targets = target_ids; io.score_logprobs = out_logprobs;
   io.replay_routing = m->cfg.n_experts ? replay_routing : nullptr;
-  return run_layers(m, (bf16_t*)kv_pool, n_blocks, w, io, st);
+  return run_layers(m, (h16_t*)kv_pool, n_blocks, w, io, st);
 }
 
 int rollout_decode_step(const rlx_model* m, void* kv_pool, int64_t n_blocks, void* workspace, size_t workspace_bytes,
@@ -521,7 +525,7 @@ int rollout_decode_step(const rlx_model* m, void* kv_pool, int64_t n_blocks, voi
   io.seeds = seeds; io.temperature = temperature; io.max_ctx_len = max_ctx_len; io.forced = forced_tokens;
   io.out_tokens = tokens_inout; io.out_logprobs = out_logprobs; io.finished = finished_inout;
   io.out_sampled = out_sampled; io.out_routing = m->cfg.n_experts ? out_routing : nullptr; io.out_logits = out_logits;
-  return run_layers(m, (bf16_t*)kv_pool, n_blocks, w, io, st);
+  return run_layers(m, (h16_t*)kv_pool, n_blocks, w, io, st);
 }
 
 int rlx_profile_kernel(int32_t kernel_class, void* const* start_events, void* const* stop_events, int32_t n_events,
@@ -551,7 +555,7 @@ int rlx_pack_weight(const void* src, void* dst, int32_t count, int32_t n, int32_
   if (!aligned16(src) || !aligned16(dst)) return fail(RLX_EINVAL, "rlx_pack_weight: 16-byte alignment");
   const size_t pe = packed_weight_elems(n, k);
   for (int i = 0; i < count; ++i)
-    RLX_HIP(pack_weight((const bf16_t*)src + (size_t)i * n * k, (bf16_t*)dst + (size_t)i * pe, n, k,
+    RLX_HIP(pack_weight((const h16_t*)src + (size_t)i * n * k, (h16_t*)dst + (size_t)i * pe, n, k,
                         (hipStream_t)stream));
   return RLX_OK;
 }
@@ -562,8 +566,8 @@ int rlx_pack_gate_up(const void* gate, const void* up, void* dst, int32_t count,
   if (!aligned16(gate) || !aligned16(up) || !aligned16(dst)) return fail(RLX_EINVAL, "rlx_pack_gate_up: 16-byte alignment");
   const size_t pe = packed_weight_elems(2 * f, k);
   for (int i = 0; i < count; ++i)
-    RLX_HIP(pack_gate_up((const bf16_t*)gate + (size_t)i * f * k, (const bf16_t*)up + (size_t)i * f * k,
-                         (bf16_t*)dst + (size_t)i * pe, f, k, (hipStream_t)stream));
+    RLX_HIP(pack_gate_up((const h16_t*)gate + (size_t)i * f * k, (const h16_t*)up + (size_t)i * f * k,
+                         (h16_t*)dst + (size_t)i * pe, f, k, (hipStream_t)stream));
   return RLX_OK;
 }
 
@@ -581,10 +585,10 @@ int rlx_op_linear(const void* x, const void* w, float* y, int32_t n_tokens, int3
   const size_t xb = align_up(frag_act_elems(n_tokens, k, 1) * 2);
   const size_t pb = splits > 1 ? align_up((size_t)splits * n_tokens * n * 4) : 0;
   if (workspace_bytes < xb + pb) return fail(RLX_ENOMEM, "rlx_op_linear: workspace needs %zu bytes", xb + pb);
-  bf16_t* xp = (bf16_t*)workspace;
+  h16_t* xp = (h16_t*)workspace;
   float* planes = (float*)((char*)workspace + xb);
-  RLX_HIP(pack_activation((const bf16_t*)x, xp, n_tokens, k, st));
-  const Act xa = make_act(xp, n_tokens, k, 1);
+  RLX_HIP(pack_activation((const h16_t*)x, xp, n_tokens, k, st));
+  const Act xa = make_act(xp, n_tokens, k, 1, DT_BF16);
   if (splits == 1) {
     RLX_HIP(gemm_store(linear1(w, n, k), xa, n_tokens, y, n, 1, st));
     return RLX_OK;

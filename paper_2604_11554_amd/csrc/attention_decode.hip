@@ -17,7 +17,7 @@ namespace {
 
 template <int HD>
 struct PageRegs {
-  bf16x8 k0[HD / 32], k1[HD / 32], vf[HD / 16];
+  h16x8 k0[HD / 32], k1[HD / 32], vf[HD / 16];
   bool ok0, ok1;
 };
 
@@ -31,7 +31,7 @@ struct Run {
   bool seg_start, seg_end, valid;
 };
 
-template <int HD, int PL>
+template <int HD, int PL, int FMT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_decode_kernel(AttnDecodeArgs a) {
   constexpr int DT = HD / 16, KS = HD / 32, PS = HD + 4;
   __shared__ f32x4 lds_o[2 * DT * WAVE];
@@ -113,7 +113,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                                       : z;
     }
   };
-  auto qf = [&](int p, int, int ks) { return __builtin_bit_cast(bf16x8, lds_q[(p * KS + ks) * WAVE + lane]); };
+  auto qf = [&](int p, int, int ks) { return __builtin_bit_cast(h16x8, lds_q[(p * KS + ks) * WAVE + lane]); };
 
   Run cur, nxt;
   next_run(cur);
@@ -136,16 +136,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     pr.ok1 = live && has1 && b1 >= 0 && b1 < a.n_blocks;
     if (!pr.ok0) b0 = 0;                             // keep the loads in bounds; scores are masked
     if (!pr.ok1) b1 = b0;
-    const bf16_t* kp0 = a.pool_layer + ((size_t)b0 * a.Hkv + r.kvh) * page;
-    const bf16_t* kp1 = a.pool_layer + ((size_t)b1 * a.Hkv + r.kvh) * page;
-    const bf16_t* vp0 = kp0 + 16 * HD;
-    const bf16_t* vp1 = kp1 + 16 * HD;
+    const h16_t* kp0 = a.pool_layer + ((size_t)b0 * a.Hkv + r.kvh) * page;
+    const h16_t* kp1 = a.pool_layer + ((size_t)b1 * a.Hkv + r.kvh) * page;
+    const h16_t* vp0 = kp0 + 16 * HD;
+    const h16_t* vp1 = kp1 + 16 * HD;
     const int koff0 = pr.ok0 ? c16 * HD + 8 * g : 0, koff1 = pr.ok1 ? c16 * HD + 8 * g : 0;
     const int voff0 = pr.ok0 ? c16 * 16 + 4 * g : 0, voff1 = pr.ok1 ? c16 * 16 + 4 * g : 0;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      pr.k0[ks] = load_bf16x8(kp0 + koff0 + 32 * ks);
-      pr.k1[ks] = load_bf16x8(kp1 + koff1 + 32 * ks);
+      pr.k0[ks] = load_h16x8(kp0 + koff0 + 32 * ks);
+      pr.k1[ks] = load_h16x8(kp1 + koff1 + 32 * ks);
     }
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -166,7 +166,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int key_end = cur.ctx + 1;
     const int pos_col[1] = {cur.ctx};
     auto step = [&](int i, const PageRegs<HD>& pr, bool valid) {
-      pair_step<HD, 1, PL>(st, pr.k0, pr.k1, pr.vf, qf, 32 * i, 32 * i + 16, pr.ok0 && valid, pr.ok1 && valid, key_end,
+      pair_step<HD, 1, PL, FMT>(st, pr.k0, pr.k1, pr.vf, qf, 32 * i, 32 * i + 16, pr.ok0 && valid, pr.ok1 && valid, key_end,
                            pos_col, scale, g);
     };
 
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       if (wave == 0 && col_ok) {
         const int head = cur.kvh * group + c16;
         if (cur.pb == 0 && cur.pe == cur.np) {
-          store_column<HD, 1, PL>(st, 0, a.o, cur.seq, head, g);
+          store_column<HD, 1, PL, FMT>(st, 0, a.o, cur.seq, head, g);
         } else {                                     // lane holds column c16, rows d = 16 dt + 4 g + {0..3}
           float* dst = a.part + ((size_t)(w * 2 + (first_seg ? 0 : 1)) * group + c16) * PS;
 #pragma unroll
@@ -268,10 +268,10 @@ __global__ __launch_bounds__(64) void attn_decode_merge_kernel(AttnDecodeArgs a)
         }
       }
     }
-    bf16_t hi[8], lo[8];
+    h16_t hi[8], lo[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) split_bf16(l > 0.f ? o[e] / l : 0.f, hi[e], lo[e]);
-    bf16_t* dst = a.o.p + frag_act_offset(seq, (kvh * group + j) * HD + d0, 0, mtiles, PL);
+    for (int e = 0; e < 8; ++e) split_h16(l > 0.f ? o[e] / l : 0.f, hi[e], lo[e], a.o.dtype);
+    h16_t* dst = a.o.p + frag_act_offset(seq, (kvh * group + j) * HD + d0, 0, mtiles, PL);
     u32x4 pk = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16),
                 (uint32_t)hi[4] | ((uint32_t)hi[5] << 16), (uint32_t)hi[6] | ((uint32_t)hi[7] << 16)};
     *reinterpret_cast<u32x4*>(dst) = pk;
@@ -339,12 +339,16 @@ hipError_t attention_decode_plan(int n_seqs, const int32_t* ctx_lens, const uint
 hipError_t attention_decode(const AttnDecodeArgs& a, hipStream_t st) {
   dim3 grid(a.n_wgs);
   const bool two = a.q.planes == 2;
-  if (a.hd == 128) {
-    if (two) hipLaunchKernelGGL((attn_decode_kernel<128, 2>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((attn_decode_kernel<128, 1>), grid, dim3(256), 0, st, a);
+  // formats built: bf16 with one or two terms, fp16 with one term (checked when the model is created)
+  if (a.o.dtype == DT_F16) {
+    if (a.hd == 128) hipLaunchKernelGGL((attn_decode_kernel<128, 1, DT_F16>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((attn_decode_kernel<64, 1, DT_F16>), grid, dim3(256), 0, st, a);
+  } else if (a.hd == 128) {
+    if (two) hipLaunchKernelGGL((attn_decode_kernel<128, 2, DT_BF16>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((attn_decode_kernel<128, 1, DT_BF16>), grid, dim3(256), 0, st, a);
   } else {
-    if (two) hipLaunchKernelGGL((attn_decode_kernel<64, 2>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((attn_decode_kernel<64, 1>), grid, dim3(256), 0, st, a);
+    if (two) hipLaunchKernelGGL((attn_decode_kernel<64, 2, DT_BF16>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((attn_decode_kernel<64, 1, DT_BF16>), grid, dim3(256), 0, st, a);
   }
   return hipGetLastError();
 }

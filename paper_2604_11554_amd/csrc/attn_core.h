@@ -1,4 +1,5 @@
-// Pieces shared by the prefill and decode attention kernels (gfx950, MFMA bf16 16x16x32).
+// Pieces shared by the prefill and decode attention kernels (gfx950, MFMA 16x16x32 on bf16 or fp16 operands;
+// FMT names the format of the pool and of the query / probability terms).
 //
 // Pool page of one (layer, block, kv head):  K[16 tokens][hd]  then  V^T[hd][16 tokens].
 // The transposed V page makes both contractions read 8 or 16 contiguous bytes per lane:
@@ -12,11 +13,11 @@
 
 namespace rlx {
 
-__device__ __forceinline__ bf16x8 load_2x4(const bf16_t* p0, const bf16_t* p1) {
+__device__ __forceinline__ h16x8 load_2x4(const h16_t* p0, const h16_t* p1) {
   u32x2 a = *reinterpret_cast<const u32x2*>(p0);
   u32x2 b = *reinterpret_cast<const u32x2*>(p1);
   u32x4 v = {a[0], a[1], b[0], b[1]};
-  return __builtin_bit_cast(bf16x8, v);
+  return __builtin_bit_cast(h16x8, v);
 }
 
 // running softmax state of NCT column tiles: lane holds column (lane & 15), rows d = 16 dt + 4 (lane >> 4) + {0..3}
@@ -48,9 +49,9 @@ struct WaveState {
 //   vf[dt]:    V^T rows 16 dt + (lane & 15), tokens 4 (lane >> 4) .. +4 of page 0 then of page 1
 //   qf(p, c, ks): query fragment of term p, column tile c: column (lane & 15), features 32 ks + 8 (lane >> 4) .. +8
 // A key is visible to column c when its page is valid, key < key_end and key <= pos_col[c].
-template <int HD, int NCT, int PL, typename QF>
-__device__ __forceinline__ void pair_step(WaveState<HD, NCT>& st, const bf16x8 (&k0)[HD / 32],
-                                          const bf16x8 (&k1)[HD / 32], const bf16x8 (&vf)[HD / 16], QF qf,
+template <int HD, int NCT, int PL, int FMT, typename QF>
+__device__ __forceinline__ void pair_step(WaveState<HD, NCT>& st, const h16x8 (&k0)[HD / 32],
+                                          const h16x8 (&k1)[HD / 32], const h16x8 (&vf)[HD / 16], QF qf,
                                           int key_base0, int key_base1, bool ok0, bool ok1, int key_end,
                                           const int (&pos_col)[NCT], float scale, int g) {
   constexpr int DT = HD / 16, KS = HD / 32;
@@ -63,12 +64,12 @@ __device__ __forceinline__ void pair_step(WaveState<HD, NCT>& st, const bf16x8 (
     for (int c = 0; c < NCT; ++c)
 #pragma unroll
       for (int p = PL - 1; p >= 0; --p) {   // small term first
-        const bf16x8 q = qf(p, c, ks);
-        s0[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0[ks], q, s0[c], 0, 0, 0);
-        s1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1[ks], q, s1[c], 0, 0, 0);
+        const h16x8 q = qf(p, c, ks);
+        s0[c] = mfma_16x16x32<FMT>(k0[ks], q, s0[c]);
+        s1[c] = mfma_16x16x32<FMT>(k1[ks], q, s1[c]);
       }
 
-  bf16x8 pf[PL][NCT];
+  h16x8 pf[PL][NCT];
 #pragma unroll
   for (int c = 0; c < NCT; ++c) {
     float mx = -INFINITY;
@@ -96,16 +97,16 @@ __device__ __forceinline__ void pair_step(WaveState<HD, NCT>& st, const bf16x8 (
     st.m[c] = mn;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) st.o[c][dt] *= alpha;
-    bf16_t ph[8], pl[8];
+    h16_t ph[8], pl[8];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) { split_bf16(p0[v], ph[v], pl[v]); split_bf16(p1[v], ph[4 + v], pl[4 + v]); }
+    for (int v = 0; v < 4; ++v) { split_h16<FMT>(p0[v], ph[v], pl[v]); split_h16<FMT>(p1[v], ph[4 + v], pl[4 + v]); }
     u32x4 pk = {(uint32_t)ph[0] | ((uint32_t)ph[1] << 16), (uint32_t)ph[2] | ((uint32_t)ph[3] << 16),
                 (uint32_t)ph[4] | ((uint32_t)ph[5] << 16), (uint32_t)ph[6] | ((uint32_t)ph[7] << 16)};
-    pf[0][c] = __builtin_bit_cast(bf16x8, pk);
+    pf[0][c] = __builtin_bit_cast(h16x8, pk);
     if (PL == 2) {
       u32x4 pk2 = {(uint32_t)pl[0] | ((uint32_t)pl[1] << 16), (uint32_t)pl[2] | ((uint32_t)pl[3] << 16),
                    (uint32_t)pl[4] | ((uint32_t)pl[5] << 16), (uint32_t)pl[6] | ((uint32_t)pl[7] << 16)};
-      pf[PL - 1][c] = __builtin_bit_cast(bf16x8, pk2);
+      pf[PL - 1][c] = __builtin_bit_cast(h16x8, pk2);
     }
   }
 #pragma unroll
@@ -114,7 +115,7 @@ __device__ __forceinline__ void pair_step(WaveState<HD, NCT>& st, const bf16x8 (
     for (int c = 0; c < NCT; ++c)
 #pragma unroll
       for (int p = PL - 1; p >= 0; --p)
-        st.o[c][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf[p][c], st.o[c][dt], 0, 0, 0);
+        st.o[c][dt] = mfma_16x16x32<FMT>(vf[dt], pf[p][c], st.o[c][dt]);
 }
 
 // merge the state held in LDS (written by another wave) into this wave's registers
@@ -161,8 +162,8 @@ __device__ __forceinline__ void merge_waves(WaveState<HD, NCT>& st, f32x4* lds_o
   if (wave == 0) merge_from_lds<HD, NCT>(st, lds_ml, lds_o, lane);
 }
 
-// normalised column c of `st` -> bf16 (hi, lo) terms at row `trow`, features head*HD + ..., fragment order
-template <int HD, int NCT, int PL>
+// normalised column c of `st` -> 16-bit (hi, lo) terms at row `trow`, features head*HD + ..., fragment order
+template <int HD, int NCT, int PL, int FMT>
 __device__ __forceinline__ void store_column(const WaveState<HD, NCT>& st, int c, const Act& o, int trow, int head,
                                              int g) {
   const float inv = st.l[c] > 0.f ? 1.f / st.l[c] : 0.f;
@@ -170,11 +171,11 @@ __device__ __forceinline__ void store_column(const WaveState<HD, NCT>& st, int c
 #pragma unroll
   for (int dt = 0; dt < HD / 16; ++dt) {
     f32x4 v = st.o[c][dt] * inv;
-    bf16_t hi[4], lo[4];
+    h16_t hi[4], lo[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) split_bf16(v[j], hi[j], lo[j]);
+    for (int j = 0; j < 4; ++j) split_h16<FMT>(v[j], hi[j], lo[j]);
     const int col = head * HD + 16 * dt + 4 * g;   // feature index of the output projection's K
-    bf16_t* dst = o.p + frag_act_offset(trow, col & ~7, 0, mtiles, PL) + (col & 7);
+    h16_t* dst = o.p + frag_act_offset(trow, col & ~7, 0, mtiles, PL) + (col & 7);
     u32x2 p = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
     *reinterpret_cast<u32x2*>(dst) = p;
     if (PL == 2) {

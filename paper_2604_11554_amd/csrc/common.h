@@ -5,32 +5,58 @@
 
 namespace rlx {
 
-typedef uint16_t bf16_t;  // raw bf16 bit pattern
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint16_t h16_t;   // raw bit pattern of a 16-bit float: bf16 or IEEE fp16, fixed per model
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef u32x4 h16x8;      // eight 16-bit floats as an MFMA operand (bit patterns)
 
 constexpr int WAVE = 64;
 
-__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+// element formats of weights, KV pages and activation terms
+enum { DT_BF16 = 0, DT_F16 = 1 };
 
-// round-to-nearest-even; inputs here are always finite
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+// ---- bf16: the upper half of an fp32; round-to-nearest-even, inputs always finite ----
+__device__ __forceinline__ float bf16_to_f32(h16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ h16_t f32_to_bf16(float f) {
   uint32_t u = __float_as_uint(f);
   u += 0x7FFFu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+  return (h16_t)(u >> 16);
+}
+// ---- fp16: the hardware conversions (round-to-nearest-even; magnitudes past 65504 become infinities) ----
+__device__ __forceinline__ float f16_to_f32(h16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+__device__ __forceinline__ h16_t f32_to_f16(float f) { return __builtin_bit_cast(h16_t, (_Float16)f); }
+
+// format picked at compile time (inner loops) ...
+template <int DT> __device__ __forceinline__ float h16_to_f32(h16_t b) { return DT == DT_F16 ? f16_to_f32(b) : bf16_to_f32(b); }
+template <int DT> __device__ __forceinline__ h16_t f32_to_h16(float f) { return DT == DT_F16 ? f32_to_f16(f) : f32_to_bf16(f); }
+// ... or at run time (uniform over a launch)
+__device__ __forceinline__ float h16_to_f32(h16_t b, int dt) { return dt == DT_F16 ? f16_to_f32(b) : bf16_to_f32(b); }
+__device__ __forceinline__ h16_t f32_to_h16(float f, int dt) { return dt == DT_F16 ? f32_to_f16(f) : f32_to_bf16(f); }
+
+// v ~= hi + lo with both terms in the 16-bit format: the second term carries the next significand bits
+template <int DT> __device__ __forceinline__ void split_h16(float v, h16_t& hi, h16_t& lo) {
+  hi = f32_to_h16<DT>(v);
+  lo = f32_to_h16<DT>(v - h16_to_f32<DT>(hi));
+}
+__device__ __forceinline__ void split_h16(float v, h16_t& hi, h16_t& lo, int dt) {
+  hi = f32_to_h16(v, dt);
+  lo = f32_to_h16(v - h16_to_f32(hi, dt), dt);
 }
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+// matrix-core steps on bit-pattern operands
+typedef __bf16 mfma_bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 mfma_f16x8 __attribute__((ext_vector_type(8)));
+template <int DT> __device__ __forceinline__ f32x16 mfma_32x32x16(h16x8 a, h16x8 b, f32x16 c) {
+  if (DT == DT_F16)
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(mfma_f16x8, a), __builtin_bit_cast(mfma_f16x8, b), c, 0, 0, 0);
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mfma_bf16x8, a), __builtin_bit_cast(mfma_bf16x8, b), c, 0, 0, 0);
 }
-
-// v ~= hi + lo with both terms bf16: the second term carries the next 8 significand bits
-__device__ __forceinline__ void split_bf16(float v, bf16_t& hi, bf16_t& lo) {
-  hi = f32_to_bf16(v);
-  lo = f32_to_bf16(v - bf16_to_f32(hi));
+template <int DT> __device__ __forceinline__ f32x4 mfma_16x16x32(h16x8 a, h16x8 b, f32x4 c) {
+  if (DT == DT_F16)
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(mfma_f16x8, a), __builtin_bit_cast(mfma_f16x8, b), c, 0, 0, 0);
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(mfma_bf16x8, a), __builtin_bit_cast(mfma_bf16x8, b), c, 0, 0, 0);
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -44,23 +70,17 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
-// 16-byte global load of eight bf16 as an MFMA operand
-__device__ __forceinline__ bf16x8 load_bf16x8(const bf16_t* p) {
-  u32x4 v = *reinterpret_cast<const u32x4*>(p);
-  return __builtin_bit_cast(bf16x8, v);
-}
-__device__ __forceinline__ bf16x8 zero_bf16x8() {
-  u32x4 v = {0u, 0u, 0u, 0u};
-  return __builtin_bit_cast(bf16x8, v);
-}
+// 16-byte global load of eight 16-bit elements as an MFMA operand
+__device__ __forceinline__ h16x8 load_h16x8(const h16_t* p) { return *reinterpret_cast<const u32x4*>(p); }
+__device__ __forceinline__ h16x8 zero_h16x8() { return u32x4{0u, 0u, 0u, 0u}; }
 
 // ---------------------------------------------------------------------------------
 // Streaming layouts.  Both operands of the skinny GEMM are kept in the order the
 // 32x32x16 MFMA consumes them, so that every wave-wide 16-byte load reads one
 // contiguous 1 KB block:
-//   fragment = 64 lanes x 8 bf16; lane = (row mod 32) + 32 * ((k mod 16) / 8); element = k mod 8
+//   fragment = 64 lanes x 8 elements; lane = (row mod 32) + 32 * ((k mod 16) / 8); element = k mod 8
 // Weights  [N, K]: fragment index (n / 32) * (K / 16) + k / 16           (rows padded to 32)
-// Activations [T, K] as `planes` bf16 terms: fragment index ((k / 16) * ceil(T / 32) + t / 32) * planes + p
+// Activations [T, K] as `planes` 16-bit terms: fragment index ((k / 16) * ceil(T / 32) + t / 32) * planes + p
 // K must be a multiple of 16.
 // ---------------------------------------------------------------------------------
 __host__ __device__ __forceinline__ size_t packed_weight_elems(int N, int K) {

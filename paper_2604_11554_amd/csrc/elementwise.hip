@@ -80,14 +80,15 @@ __global__ void meta_prefill_kernel(TokenMeta m, int n_seqs, int total, const in
   if (threadIdx.x == 0) m.n_qtiles[0] = base;
 }
 
-__global__ void embed_kernel(const bf16_t* embed, int vocab, int d, const int32_t* tokens, const bf16_t* inj, float* h) {
+__global__ void embed_kernel(const h16_t* embed, int vocab, int d, const int32_t* tokens, const h16_t* inj, float* h,
+                             int dtype) {
   int t = blockIdx.x;
   int tok = tokens[t];
-  const bf16_t* src;
+  const h16_t* src;
   if (tok >= 0 && tok < vocab) src = embed + (size_t)tok * d;
   else if (tok < 0 && inj) src = inj + (size_t)t * d;
   else src = nullptr;   // out-of-range id: zero row rather than a stray read
-  for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)t * d + i] = src ? bf16_to_f32(src[i]) : 0.f;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)t * d + i] = src ? h16_to_f32(src[i], dtype) : 0.f;
 }
 
 __device__ __forceinline__ float block_sum_256(float v, float* sh) {
@@ -112,6 +113,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(NormArgs a) {
   const bool adding = (a.add != nullptr) || (a.moe_y != nullptr);
   const int mtiles = a.x.mtiles();
   const bool single = nv <= 256 * NV;
+  const int dt = a.x.dtype;
   f32x4 keep[NV];
   float ss = 0.f;
   int pp[8];
@@ -187,15 +189,15 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(NormArgs a) {
       const f32x4 hv = single ? keep[j] : *reinterpret_cast<const f32x4*>(hrow + 4 * i);   // own writes
       const u32x2 gb = *reinterpret_cast<const u32x2*>(a.gain + 4 * i);
       f32x4 o;
-      o[0] = hv[0] * rstd * __uint_as_float(gb[0] << 16);
-      o[1] = hv[1] * rstd * __uint_as_float(gb[0] & 0xFFFF0000u);
-      o[2] = hv[2] * rstd * __uint_as_float(gb[1] << 16);
-      o[3] = hv[3] * rstd * __uint_as_float(gb[1] & 0xFFFF0000u);
-      bf16_t hi[4], lo[4];
+      o[0] = hv[0] * rstd * h16_to_f32((h16_t)(gb[0] & 0xFFFFu), dt);
+      o[1] = hv[1] * rstd * h16_to_f32((h16_t)(gb[0] >> 16), dt);
+      o[2] = hv[2] * rstd * h16_to_f32((h16_t)(gb[1] & 0xFFFFu), dt);
+      o[3] = hv[3] * rstd * h16_to_f32((h16_t)(gb[1] >> 16), dt);
+      h16_t hi[4], lo[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) split_bf16(o[e], hi[e], lo[e]);
+      for (int e = 0; e < 4; ++e) split_h16(o[e], hi[e], lo[e], dt);
       const int k = 4 * i;
-      bf16_t* xo = a.x.p + frag_act_offset(r, k & ~7, 0, mtiles, a.x.planes) + (k & 7);
+      h16_t* xo = a.x.p + frag_act_offset(r, k & ~7, 0, mtiles, a.x.planes) + (k & 7);
       u32x2 pk = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
       *reinterpret_cast<u32x2*>(xo) = pk;
       if (a.x.planes == 2) {
@@ -211,7 +213,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(NormArgs a) {
 __global__ __launch_bounds__(256) void qk_rope_append_kernel(RopeArgs a) {
   const int t = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int hd = a.hd, half = hd >> 1;
+  const int hd = a.hd, half = hd >> 1, dt = a.q_out.dtype;
   const int n_heads = a.Hq + 2 * a.Hkv;
   const int h = blockIdx.y * 4 + wave;
   if (h >= n_heads) return;
@@ -243,32 +245,32 @@ __global__ __launch_bounds__(256) void qk_rope_append_kernel(RopeArgs a) {
     } else {
       rope_cos_sin(pos, a.inv_freq, act, li, c, s);
     }
-    head_norm_rope(x0, x1, is_q ? a.q_gain : a.k_gain, hd, a.eps, act, lane, c, s, y0, y1);
+    head_norm_rope(x0, x1, is_q ? a.q_gain : a.k_gain, dt, hd, a.eps, act, lane, c, s, y0, y1);
     if (act) {
       if (is_q) {
-        bf16_t* dst = a.q_out.p + ((size_t)t * a.Hq + h) * hd;
-        bf16_t h0, l0, h1, l1;
-        split_bf16(y0, h0, l0);
-        split_bf16(y1, h1, l1);
+        h16_t* dst = a.q_out.p + ((size_t)t * a.Hq + h) * hd;
+        h16_t h0, l0, h1, l1;
+        split_h16(y0, h0, l0, dt);
+        split_h16(y1, h1, l1, dt);
         dst[lane] = h0;
         dst[lane + half] = h1;
         if (a.q_out.planes == 2) { dst[a.q_out.plane + lane] = l0; dst[a.q_out.plane + lane + half] = l1; }
       } else if (blk >= 0) {
         int kvh = h - a.Hq;
-        bf16_t* dst = a.pool_layer + (((size_t)blk * a.Hkv + kvh) * 2) * 16 * hd + (size_t)slot * hd;
-        dst[lane] = f32_to_bf16(y0);
-        dst[lane + half] = f32_to_bf16(y1);
+        h16_t* dst = a.pool_layer + (((size_t)blk * a.Hkv + kvh) * 2) * 16 * hd + (size_t)slot * hd;
+        dst[lane] = f32_to_h16(y0, dt);
+        dst[lane + half] = f32_to_h16(y1, dt);
       }
     }
   } else if (blk >= 0 && act) {   // value head: stored transposed, [hd][16]
     int kvh = h - a.Hq - a.Hkv;
-    bf16_t* dst = a.pool_layer + (((size_t)blk * a.Hkv + kvh) * 2 + 1) * 16 * hd;
-    dst[(size_t)lane * 16 + slot] = f32_to_bf16(x0);
-    dst[(size_t)(lane + half) * 16 + slot] = f32_to_bf16(x1);
+    h16_t* dst = a.pool_layer + (((size_t)blk * a.Hkv + kvh) * 2 + 1) * 16 * hd;
+    dst[(size_t)lane * 16 + slot] = f32_to_h16(x0, dt);
+    dst[(size_t)(lane + half) * 16 + slot] = f32_to_h16(x1, dt);
   }
 }
 
-__global__ void pack_weight_kernel(const bf16_t* src, bf16_t* dst, int N, int K) {
+__global__ void pack_weight_kernel(const h16_t* src, h16_t* dst, int N, int K) {
   // one thread per 8-element group of the packed layout
   const size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t total = packed_weight_elems(N, K) / 8;
@@ -284,7 +286,7 @@ __global__ void pack_weight_kernel(const bf16_t* src, bf16_t* dst, int N, int K)
   *reinterpret_cast<u32x4*>(dst + g * 8) = v;
 }
 
-__global__ void pack_gate_up_kernel(const bf16_t* gate, const bf16_t* up, bf16_t* dst, int F, int K) {
+__global__ void pack_gate_up_kernel(const h16_t* gate, const h16_t* up, h16_t* dst, int F, int K) {
   const size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t total = packed_weight_elems(2 * F, K) / 8;
   if (g >= total) return;
@@ -294,11 +296,11 @@ __global__ void pack_gate_up_kernel(const bf16_t* gate, const bf16_t* up, bf16_t
   const int ks = (int)(frag % KS);
   const int nt = (int)(frag / KS);
   const int r = lane & 31, k = ks * 16 + 8 * (lane >> 5);
-  const bf16_t* src = (r < 16 ? gate : up) + (size_t)(nt * 16 + (r & 15)) * K + k;
+  const h16_t* src = (r < 16 ? gate : up) + (size_t)(nt * 16 + (r & 15)) * K + k;
   *reinterpret_cast<u32x4*>(dst + g * 8) = *reinterpret_cast<const u32x4*>(src);
 }
 
-__global__ void pack_activation_kernel(const bf16_t* src, bf16_t* dst, int T, int K) {
+__global__ void pack_activation_kernel(const h16_t* src, h16_t* dst, int T, int K) {
   const size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // (t, k/8) pairs
   const int kg = K >> 3;
   if (g >= (size_t)T * kg) return;
@@ -315,7 +317,7 @@ __global__ void sum_planes_kernel(const float* planes, int n_planes, size_t n, f
   y[i] = v;
 }
 
-__global__ void kv_copy_kernel(bf16_t* pool, int64_t n_blocks, size_t block_elems, const int32_t* src,
+__global__ void kv_copy_kernel(h16_t* pool, int64_t n_blocks, size_t block_elems, const int32_t* src,
                                const int32_t* dst, int n) {
   // grid: (pairs, layers); 16-byte vector copy of one page
   int i = blockIdx.x, l = blockIdx.y;
@@ -343,9 +345,9 @@ hipError_t meta_prefill(const TokenMeta& m, int n_seqs, int total_tokens, const 
   return hipGetLastError();
 }
 
-hipError_t embed_tokens(const bf16_t* embed, int vocab, int d, const int32_t* tokens, const bf16_t* input_embeds,
-                        int T, float* h, hipStream_t st) {
-  hipLaunchKernelGGL(embed_kernel, dim3(T), dim3(256), 0, st, embed, vocab, d, tokens, input_embeds, h);
+hipError_t embed_tokens(const h16_t* embed, int vocab, int d, const int32_t* tokens, const h16_t* input_embeds,
+                        int T, float* h, int dtype, hipStream_t st) {
+  hipLaunchKernelGGL(embed_kernel, dim3(T), dim3(256), 0, st, embed, vocab, d, tokens, input_embeds, h, dtype);
   return hipGetLastError();
 }
 
@@ -359,19 +361,19 @@ hipError_t qk_rope_append(const RopeArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t pack_weight(const bf16_t* src, bf16_t* dst, int N, int K, hipStream_t st) {
+hipError_t pack_weight(const h16_t* src, h16_t* dst, int N, int K, hipStream_t st) {
   const size_t groups = packed_weight_elems(N, K) / 8;
   hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, src, dst, N, K);
   return hipGetLastError();
 }
 
-hipError_t pack_gate_up(const bf16_t* gate, const bf16_t* up, bf16_t* dst, int F, int K, hipStream_t st) {
+hipError_t pack_gate_up(const h16_t* gate, const h16_t* up, h16_t* dst, int F, int K, hipStream_t st) {
   const size_t groups = packed_weight_elems(2 * F, K) / 8;
   hipLaunchKernelGGL(pack_gate_up_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, gate, up, dst, F, K);
   return hipGetLastError();
 }
 
-hipError_t pack_activation(const bf16_t* src, bf16_t* dst, int T, int K, hipStream_t st) {
+hipError_t pack_activation(const h16_t* src, h16_t* dst, int T, int K, hipStream_t st) {
   const size_t groups = (size_t)T * (K / 8);
   hipLaunchKernelGGL(pack_activation_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, src, dst, T, K);
   return hipGetLastError();
@@ -382,7 +384,7 @@ hipError_t sum_planes(const float* planes, int n_planes, size_t n, float* y, hip
   return hipGetLastError();
 }
 
-hipError_t kv_copy_blocks(bf16_t* pool, int64_t n_blocks, int n_layers, size_t block_elems, const int32_t* src,
+hipError_t kv_copy_blocks(h16_t* pool, int64_t n_blocks, int n_layers, size_t block_elems, const int32_t* src,
                           const int32_t* dst, int n, hipStream_t st) {
   if (n <= 0) return hipSuccess;
   hipLaunchKernelGGL(kv_copy_kernel, dim3(n, n_layers), dim3(256), 0, st, pool, n_blocks, block_elems, src, dst, n);

@@ -1,4 +1,4 @@
-// Weight-streaming skinny GEMM for decode and chunked prefill (gfx950, MFMA bf16 32x32x16).
+// Weight-streaming skinny GEMM for decode and chunked prefill (gfx950, MFMA 32x32x16 on bf16 or fp16 operands).
 //
 //   y[t, n] = sum_k x[t, k] * W[n, k]        fp32 accumulate
 //
@@ -25,16 +25,16 @@ constexpr int GEMM_WAVES = 4;
 constexpr int GEMM_THREADS = GEMM_WAVES * WAVE;
 
 struct GemmArgs {
-  const bf16_t* x;        // fragment-ordered activations [T_x, K], `PL` planes
+  const h16_t* x;        // fragment-ordered activations [T_x, K], `PL` planes
   int x_mtiles;           // ceil(T_x / 32)
   const int32_t* x_rows;  // grouped gate/up: logical row r of the group reads activation row x_rows[r]
-  const bf16_t* w[3];     // packed weights, up to three stacked row segments
+  const h16_t* w[3];     // packed weights, up to three stacked row segments
   int w_tiles[3];         // 32-row tiles per segment
   int N, K, T;
   int ksteps_per_split;   // k-steps (16 wide) per blockIdx.y
   float* y;               // EPI_STORE: [splits][T][ldy]
   int ldy;
-  bf16_t* act;            // EPI_SWIGLU: fragment-ordered [act_rows, N], `PL` planes
+  h16_t* act;            // EPI_SWIGLU: fragment-ordered [act_rows, N], `PL` planes
   int act_mtiles;
   // LM-head epilogue
   float* logits;          // optional [T][N]
@@ -88,7 +88,7 @@ struct Tiling {
   static constexpr int LDS_BYTES = 2 * FRAGS * 1024;
 };
 
-template <int MT, int EPI, int PL>
+template <int MT, int EPI, int PL, int FMT>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
   using TL = Tiling<MT, PL>;
   constexpr int KC = TL::KC, U = TL::U, FRAGS = TL::FRAGS, PT = TL::PER_THREAD;
@@ -117,10 +117,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
   const int n_tiles = (a.N + 31) >> 5;
   const int nt = blockIdx.x * GEMM_WAVES + wave;
   const bool have_tile = nt < n_tiles;
-  const bf16_t* wp;
+  const h16_t* wp;
   {
     int lt = have_tile ? nt : 0;                    // a wave without a tile re-reads tile 0 and stores nothing
-    const bf16_t* base = a.w[0];                    // static member picks keep the pointers in the global space
+    const h16_t* base = a.w[0];                    // static member picks keep the pointers in the global space
     if (lt >= a.w_tiles[0]) {
       lt -= a.w_tiles[0];
       base = a.w[1];
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
 
   // ---- activation staging: each wave moves PT fragments of a chunk ----
   // fragment f of a chunk = (k-step f / (MT*PL), token tile (f / PL) % MT, plane f % PL)
-  const bf16_t* xsrc[MT];
+  const h16_t* xsrc[MT];
   bool xok[MT];
 #pragma unroll
   for (int m = 0; m < MT; ++m) {
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
       const int f = wave + GEMM_WAVES * i;
       const int ks = ks0 + f / (MT * PL), m = (f / PL) % MT, p = f % PL;
       const int ksc = ks < ks_e ? ks : ks_e - 1;
-      const bf16_t* src = xsrc[0];
+      const h16_t* src = xsrc[0];
       bool ok = xok[0];
 #pragma unroll
       for (int mm = 1; mm < MT; ++mm)
@@ -217,13 +217,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
       __builtin_amdgcn_sched_barrier(0);          // the reads above are issued before the multiplies below
       const bool ok = ks0 + u < ks_e;             // uniform; past the end the weights count as zero
       const u32x4 z = {0u, 0u, 0u, 0u};
-      const bf16x8 w1 = __builtin_bit_cast(bf16x8, ok ? wf[u] : z);
+      const h16x8 w1 = ok ? wf[u] : z;
 #pragma unroll
       for (int m = 0; m < MT; ++m)
 #pragma unroll
         for (int p = PL - 1; p >= 0; --p)         // small term first
-          acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, __builtin_bit_cast(bf16x8, xq[u & 1][m * PL + p]), acc[m],
-                                                           0, 0, 0);
+          acc[m] = mfma_32x32x16<FMT>(w1, xq[u & 1][m * PL + p], acc[m]);
     }
   };
 
@@ -294,13 +293,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
       for (int q = 0; q < 2; ++q) {
         const int feat = nt * 16 + 8 * q + 4 * half;   // four consecutive features inside one 8-group
         if (feat >= n_feat) continue;
-        bf16_t hi[4], lo[4];
+        h16_t hi[4], lo[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           float g = acc[m][4 * q + j], u = acc[m][4 * (q + 2) + j];
-          split_bf16(g / (1.f + __expf(-g)) * u, hi[j], lo[j]);
+          split_h16<FMT>(g / (1.f + __expf(-g)) * u, hi[j], lo[j]);
         }
-        bf16_t* dst = a.act + frag_act_offset(orow, feat & ~7, 0, a.act_mtiles, PL) + (feat & 7);
+        h16_t* dst = a.act + frag_act_offset(orow, feat & ~7, 0, a.act_mtiles, PL) + (feat & 7);
         u32x2 pk = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
         *reinterpret_cast<u32x2*>(dst) = pk;
         if (PL == 2) {
@@ -372,32 +371,33 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
   }
 }
 
-template <int MT, int EPI, int PL>
+template <int MT, int EPI, int PL, int FMT>
 void launch_one(const GemmArgs& a, dim3 grid, hipStream_t st) {
   static bool attr_set = false;   // raise the dynamic LDS limit once per instantiation
   constexpr int lds = Tiling<MT, PL>::LDS_BYTES;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_kernel<MT, EPI, PL>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_kernel<MT, EPI, PL, FMT>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI, PL>), grid, dim3(GEMM_THREADS), lds, st, a);
+  hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI, PL, FMT>), grid, dim3(GEMM_THREADS), lds, st, a);
+}
+
+// formats built: bf16 activations as one or two terms, fp16 activations as one term
+template <int MT, int EPI>
+void launch_fmt(const GemmArgs& a, dim3 grid, const Act& x, hipStream_t st) {
+  if (x.dtype == DT_F16) launch_one<MT, EPI, 1, DT_F16>(a, grid, st);
+  else if (x.planes == 2) launch_one<MT, EPI, 2, DT_BF16>(a, grid, st);
+  else launch_one<MT, EPI, 1, DT_BF16>(a, grid, st);
 }
 
 template <int EPI>
-void launch_mt(const GemmArgs& a, int n_tiles, int grid_y, int mt, int planes, hipStream_t st) {
+void launch_mt(const GemmArgs& a, int n_tiles, int grid_y, int mt, const Act& x, hipStream_t st) {
   const int gx = (n_tiles + GEMM_WAVES - 1) / GEMM_WAVES;
   const int mtiles = (a.T + 31) / 32;
-  if (mt == 1) {
-    dim3 g(gx, grid_y, mtiles);
-    if (planes == 2) launch_one<1, EPI, 2>(a, g, st); else launch_one<1, EPI, 1>(a, g, st);
-  } else if (mt == 2) {
-    dim3 g(gx, grid_y, (mtiles + 1) / 2);
-    if (planes == 2) launch_one<2, EPI, 2>(a, g, st); else launch_one<2, EPI, 1>(a, g, st);
-  } else {
-    dim3 g(gx, grid_y, (mtiles + 3) / 4);
-    if (planes == 2) launch_one<4, EPI, 2>(a, g, st); else launch_one<4, EPI, 1>(a, g, st);
-  }
+  if (mt == 1) launch_fmt<1, EPI>(a, dim3(gx, grid_y, mtiles), x, st);
+  else if (mt == 2) launch_fmt<2, EPI>(a, dim3(gx, grid_y, (mtiles + 1) / 2), x, st);
+  else launch_fmt<4, EPI>(a, dim3(gx, grid_y, (mtiles + 3) / 4), x, st);
 }
 
 int pick_mt(int T) { return T <= 32 ? 1 : (T <= 64 ? 2 : 4); }
@@ -434,18 +434,18 @@ hipError_t gemm_store(const LinearW& w, const Act& x, int T, float* y, int ldy, 
   a.N = w.N; a.K = w.K; a.T = T;
   a.ksteps_per_split = ksteps_for(w.K, splits);   // same rule as gemm_plan_splits
   a.y = y; a.ldy = ldy;
-  launch_mt<EPI_STORE>(a, tiles, splits, pick_mt(T), x.planes, st);
+  launch_mt<EPI_STORE>(a, tiles, splits, pick_mt(T), x, st);
   return hipGetLastError();
 }
 
-hipError_t gemm_swiglu(const bf16_t* w_gate_up, int F, int K, const Act& x, int T, const Act& act, hipStream_t st) {
+hipError_t gemm_swiglu(const h16_t* w_gate_up, int F, int K, const Act& x, int T, const Act& act, hipStream_t st) {
   GemmArgs a = {};
   fill_x(a, x);
   a.w[0] = w_gate_up; a.w_tiles[0] = F / 16;
   a.N = 2 * F; a.K = K; a.T = T;
   a.ksteps_per_split = K / 16;
   a.act = act.p; a.act_mtiles = act.mtiles();
-  launch_mt<EPI_SWIGLU>(a, a.w_tiles[0], 1, pick_mt(T), x.planes, st);
+  launch_mt<EPI_SWIGLU>(a, a.w_tiles[0], 1, pick_mt(T), x, st);
   return hipGetLastError();
 }
 
@@ -455,7 +455,7 @@ hipError_t gemm_swiglu(const bf16_t* w_gate_up, int F, int K, const Act& x, int 
 // expert's last row exit at once.
 static int grouped_mt(int expected_rows) { return expected_rows <= 16 ? 1 : (expected_rows <= 40 ? 2 : 4); }
 
-hipError_t gemm_grouped_swiglu(const bf16_t* w_gate_up, int E, int F, int K, const Act& x, const int32_t* x_rows,
+hipError_t gemm_grouped_swiglu(const h16_t* w_gate_up, int E, int F, int K, const Act& x, const int32_t* x_rows,
                                const int32_t* group_off, int max_rows, int expected_rows, const Act& act,
                                hipStream_t st) {
   GemmArgs a = {};
@@ -466,11 +466,11 @@ hipError_t gemm_grouped_swiglu(const bf16_t* w_gate_up, int E, int F, int K, con
   a.ksteps_per_split = K / 16;
   a.act = act.p; a.act_mtiles = act.mtiles();
   a.group_off = group_off; a.w_expert_stride = packed_weight_elems(2 * F, K);
-  launch_mt<EPI_SWIGLU>(a, a.w_tiles[0], E, grouped_mt(expected_rows), x.planes, st);
+  launch_mt<EPI_SWIGLU>(a, a.w_tiles[0], E, grouped_mt(expected_rows), x, st);
   return hipGetLastError();
 }
 
-hipError_t gemm_grouped_store(const bf16_t* w, int E, int N, int K, const Act& x, const int32_t* group_off,
+hipError_t gemm_grouped_store(const h16_t* w, int E, int N, int K, const Act& x, const int32_t* group_off,
                               int max_rows, int expected_rows, float* y, hipStream_t st) {
   GemmArgs a = {};
   fill_x(a, x);
@@ -479,13 +479,13 @@ hipError_t gemm_grouped_store(const bf16_t* w, int E, int N, int K, const Act& x
   a.ksteps_per_split = K / 16;
   a.y = y; a.ldy = N;
   a.group_off = group_off; a.w_expert_stride = packed_weight_elems(N, K);
-  launch_mt<EPI_STORE>(a, a.w_tiles[0], E, grouped_mt(expected_rows), x.planes, st);
+  launch_mt<EPI_STORE>(a, a.w_tiles[0], E, grouped_mt(expected_rows), x, st);
   return hipGetLastError();
 }
 
 int lmhead_tiles(int vocab) { return (vocab + 31) / 32; }
 
-hipError_t gemm_lmhead(const bf16_t* w_lm, int V, int K, const Act& x, int T, float* logits, float* part,
+hipError_t gemm_lmhead(const h16_t* w_lm, int V, int K, const Act& x, int T, float* logits, float* part,
                        const uint64_t* seeds, const float* temperature, const int32_t* sample_pos,
                        const int32_t* row_seq, bool draw, hipStream_t st) {
   GemmArgs a = {};
@@ -495,7 +495,7 @@ hipError_t gemm_lmhead(const bf16_t* w_lm, int V, int K, const Act& x, int T, fl
   a.ksteps_per_split = K / 16;
   a.logits = logits; a.part = part; a.seeds = seeds; a.temperature = temperature; a.sample_pos = sample_pos;
   a.row_seq = row_seq; a.draw = draw ? 1 : 0;
-  launch_mt<EPI_LMHEAD>(a, a.w_tiles[0], 1, pick_mt(T), x.planes, st);
+  launch_mt<EPI_LMHEAD>(a, a.w_tiles[0], 1, pick_mt(T), x, st);
   return hipGetLastError();
 }
 

@@ -7,32 +7,34 @@ namespace rlx {
 
 // Up to three row segments stacked into one logical [N, K] weight (q|k|v).
 struct LinearW {
-  const bf16_t* seg[3];
+  const h16_t* seg[3];
   int rows[3];
   int N, K;
 };
 inline LinearW linear1(const void* w, int N, int K) {
   LinearW l = {};
-  l.seg[0] = (const bf16_t*)w; l.rows[0] = N; l.N = N; l.K = K;
+  l.seg[0] = (const h16_t*)w; l.rows[0] = N; l.N = N; l.K = K;
   return l;
 }
 
-// A bf16 activation matrix [T, K] in MFMA fragment order (common.h), carried as the sum of
-// `planes` (1 or 2) bf16 terms; two terms keep 16 significand bits.
+// A 16-bit activation matrix [T, K] in MFMA fragment order (common.h), carried as the sum of
+// `planes` (1 or 2) terms of format `dtype` (DT_BF16 / DT_F16); two bf16 terms keep 16 significand bits.
+// Kernels are built for bf16 with one or two terms and for fp16 with one term (the second term of an fp16 pair
+// would mostly fall below the smallest normal fp16 number, 6.1e-5, and carry little).
 struct Act {
-  bf16_t* p;
-  int T, K, planes;
+  h16_t* p;
+  int T, K, planes, dtype;
   __host__ __device__ int mtiles() const { return (T + 31) / 32; }
 };
-inline Act make_act(bf16_t* p, int T, int K, int planes) {
-  Act a = {p, T, K, planes};
+inline Act make_act(h16_t* p, int T, int K, int planes, int dtype) {
+  Act a = {p, T, K, planes, dtype};
   return a;
 }
 // Row-major variant [planes][T, ld] (queries of the attention kernel).
 struct RowAct {
-  bf16_t* p;
+  h16_t* p;
   size_t plane;
-  int ld, planes;
+  int ld, planes, dtype;
 };
 
 // ---- gemm.hip ----
@@ -42,19 +44,19 @@ int gemm_plan_splits(int N, int K, int max_splits, int n_units);
 // y[split][t][n] (fp32, leading dimension ldy); weights packed (common.h), activations in fragment order
 hipError_t gemm_store(const LinearW& w, const Act& x, int T, float* y, int ldy, int splits, hipStream_t st);
 // act[t][f] = silu(x Wg^T) * (x Wu^T); w_gate_up is the interleaved packed pair (pack_gate_up)
-hipError_t gemm_swiglu(const bf16_t* w_gate_up, int F, int K, const Act& x, int T, const Act& act, hipStream_t st);
+hipError_t gemm_swiglu(const h16_t* w_gate_up, int F, int K, const Act& x, int T, const Act& act, hipStream_t st);
 int lmhead_tiles(int vocab);
 // LM head with fused per-tile log-sum-exp and Gumbel-max partials: part[t][tile][4]
 // row_seq (optional): row t reads temperature[row_seq[t]]; draw = false skips the Gumbel-max draw (scoring)
-hipError_t gemm_lmhead(const bf16_t* w_lm, int V, int K, const Act& x, int T, float* logits, float* part,
+hipError_t gemm_lmhead(const h16_t* w_lm, int V, int K, const Act& x, int T, float* logits, float* part,
                        const uint64_t* seeds, const float* temperature, const int32_t* sample_pos,
                        const int32_t* row_seq, bool draw, hipStream_t st);
 // expert-grouped forms: rows [group_off[e], group_off[e+1]) belong to expert e = blockIdx.y; max_rows bounds the rows
 // of one expert, expected_rows (pairs / experts) picks the token-tile height
-hipError_t gemm_grouped_swiglu(const bf16_t* w_gate_up, int E, int F, int K, const Act& x, const int32_t* x_rows,
+hipError_t gemm_grouped_swiglu(const h16_t* w_gate_up, int E, int F, int K, const Act& x, const int32_t* x_rows,
                                const int32_t* group_off, int max_rows, int expected_rows, const Act& act,
                                hipStream_t st);
-hipError_t gemm_grouped_store(const bf16_t* w, int E, int N, int K, const Act& x,
+hipError_t gemm_grouped_store(const h16_t* w, int E, int N, int K, const Act& x,
                               const int32_t* group_off, int max_rows, int expected_rows, float* y, hipStream_t st);
 
 // ---- elementwise.hip ----
@@ -76,12 +78,12 @@ hipError_t meta_decode(const TokenMeta& m, int n_seqs, const int32_t* ctx_lens, 
                        const double* inv_freq, int head_dim, hipStream_t st);
 hipError_t meta_prefill(const TokenMeta& m, int n_seqs, int total_tokens, const int32_t* cu_seqlens,
                         const int32_t* ctx_lens, const uint8_t* sample_last, hipStream_t st);
-hipError_t embed_tokens(const bf16_t* embed, int vocab, int d, const int32_t* tokens, const bf16_t* input_embeds,
-                        int T, float* h, hipStream_t st);
+hipError_t embed_tokens(const h16_t* embed, int vocab, int d, const int32_t* tokens, const h16_t* input_embeds,
+                        int T, float* h, int dtype, hipStream_t st);
 
 struct NormArgs {
   float* h;                  // [T, d] residual stream, updated in place when something is added
-  const bf16_t* gain;        // [d]
+  const h16_t* gain;        // [d], format x.dtype
   int d, T;                  // T = number of output rows
   int T_total;               // rows of h (stride of the split-K planes)
   float eps;
@@ -102,35 +104,35 @@ hipError_t rmsnorm(const NormArgs& a, hipStream_t st);
 struct RopeArgs {
   const float* qkv;          // [n_planes][T, (Hq+2Hkv)*hd] fp32 split-K planes, summed in plane order
   int n_planes;
-  const bf16_t* q_gain;      // [hd] or null
-  const bf16_t* k_gain;
+  const h16_t* q_gain;      // [hd] or null
+  const h16_t* k_gain;
   const double* inv_freq;    // [hd/2]
   const float2* rope_cs;     // optional [T][hd/2] precomputed (cos, sin) of each token's position
   int T, Hq, Hkv, hd;
   float eps;
   const int32_t* tok_seq; const int32_t* tok_pos; const uint8_t* tok_live;
   const int32_t* block_table; int max_blocks;
-  bf16_t* pool_layer;        // this layer's pages
+  h16_t* pool_layer;        // this layer's pages, elements of format q_out.dtype (as are the gains)
   int64_t n_blocks;
   RowAct q_out;              // [planes][T, Hq*hd]
 };
 hipError_t qk_rope_append(const RopeArgs& a, hipStream_t st);
-// row-major [N, K] bf16 -> packed streaming layout (rows padded to 32 with zeros); K % 16 == 0
-hipError_t pack_weight(const bf16_t* src, bf16_t* dst, int N, int K, hipStream_t st);
+// row-major [N, K] 16-bit -> packed streaming layout (rows padded to 32 with zeros); K % 16 == 0
+hipError_t pack_weight(const h16_t* src, h16_t* dst, int N, int K, hipStream_t st);
 // row-major gate [F, K] and up [F, K] -> one packed [2F, K] matrix whose 32-row tile t holds gate rows
 // 16t..16t+15 followed by up rows 16t..16t+15 (F % 16 == 0)
-hipError_t pack_gate_up(const bf16_t* gate, const bf16_t* up, bf16_t* dst, int F, int K, hipStream_t st);
-// row-major [T, K] bf16 -> single-plane fragment order
-hipError_t pack_activation(const bf16_t* src, bf16_t* dst, int T, int K, hipStream_t st);
+hipError_t pack_gate_up(const h16_t* gate, const h16_t* up, h16_t* dst, int F, int K, hipStream_t st);
+// row-major [T, K] 16-bit -> single-plane fragment order
+hipError_t pack_activation(const h16_t* src, h16_t* dst, int T, int K, hipStream_t st);
 // y[i] = sum_s planes[s][i], s ascending
 hipError_t sum_planes(const float* planes, int n_planes, size_t n, float* y, hipStream_t st);
-hipError_t kv_copy_blocks(bf16_t* pool, int64_t n_blocks, int n_layers, size_t block_elems, const int32_t* src,
+hipError_t kv_copy_blocks(h16_t* pool, int64_t n_blocks, int n_layers, size_t block_elems, const int32_t* src,
                           const int32_t* dst, int n, hipStream_t st);
 
 // ---- attention.hip (prefill), attention_decode.hip ----
 struct AttnArgs {            // prefill
   RowAct q;                  // [planes][T, Hq*hd]
-  const bf16_t* pool_layer;
+  const h16_t* pool_layer;
   int64_t n_blocks;
   int Hq, Hkv, hd;
   const int32_t* block_table; int max_blocks;
@@ -144,7 +146,7 @@ hipError_t attention_prefill(const AttnArgs& a, hipStream_t st);
 
 struct AttnDecodeArgs {      // one new token per sequence: row = sequence slot
   RowAct q;                  // [planes][n_seqs, Hq*hd] rotated queries
-  const bf16_t* pool_layer;  // this layer's pages (the new token's K and V already appended)
+  const h16_t* pool_layer;  // this layer's pages (the new token's K and V already appended)
   int64_t n_blocks;
   int Hq, Hkv, hd;
   const int32_t* block_table; int max_blocks;
@@ -185,7 +187,7 @@ struct FinalizeArgs {
   int n_rows, n_tiles, vocab, d;
   const float* part;          // [n_rows][n_tiles][4]
   Act x;                      // [planes][n_rows, d] final-normalised hidden
-  const bf16_t* w_lm;         // [vocab, d] packed
+  const h16_t* w_lm;         // [vocab, d] packed, format x.dtype
   const float* temperature; const int32_t* max_ctx_len; const int32_t* forced;
   const int32_t* sample_pos; const uint8_t* sample_on;
   int eos, pad;

@@ -38,14 +38,14 @@ __device__ __forceinline__ void rope_cos_sin(int pos, const double* inv_freq, bo
 }
 
 // optional RMSNorm over the head (gain != null), then the rotation; must be called by the whole wave
-__device__ __forceinline__ void head_norm_rope(float x0, float x1, const bf16_t* gain, int hd, float eps, bool act,
-                                               int lane, float c, float s, float& y0, float& y1) {
+__device__ __forceinline__ void head_norm_rope(float x0, float x1, const h16_t* gain, int dtype, int hd, float eps,
+                                               bool act, int lane, float c, float s, float& y0, float& y1) {
   if (gain) {
     float ss = wave_sum(x0 * x0 + x1 * x1);
     float rstd = 1.0f / sqrtf(ss / (float)hd + eps);
     if (act) {
-      x0 = x0 * rstd * bf16_to_f32(gain[lane]);
-      x1 = x1 * rstd * bf16_to_f32(gain[lane + (hd >> 1)]);
+      x0 = x0 * rstd * h16_to_f32(gain[lane], dtype);
+      x1 = x1 * rstd * h16_to_f32(gain[lane + (hd >> 1)], dtype);
     }
   }
   y0 = x0 * c - x1 * s;

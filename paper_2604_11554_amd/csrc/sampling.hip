@@ -65,14 +65,14 @@ __global__ __launch_bounds__(256) void sample_finalize_kernel(FinalizeArgs a) {
   }
   if (tok < 0 || tok >= a.vocab) tok = a.eos;   // cannot happen with a non-empty vocabulary; keeps the read in bounds
 
-  // logit of the emitted token: the same bf16 operands as the LM-head tiles, fp32 accumulate
+  // logit of the emitted token: the same 16-bit operands as the LM-head tiles, fp32 accumulate
   const int mtiles = a.x.mtiles();
   float acc = 0.f;
   for (int k = threadIdx.x; k < a.d; k += 256) {
-    const bf16_t* x = a.x.p + frag_act_offset(r, k & ~7, 0, mtiles, a.x.planes) + (k & 7);
-    float xv = bf16_to_f32(x[0]);
-    if (a.x.planes == 2) xv += bf16_to_f32(x[512]);
-    acc += xv * bf16_to_f32(a.w_lm[packed_weight_offset(tok, k, a.d)]);
+    const h16_t* x = a.x.p + frag_act_offset(r, k & ~7, 0, mtiles, a.x.planes) + (k & 7);
+    float xv = h16_to_f32(x[0], a.x.dtype);
+    if (a.x.planes == 2) xv += h16_to_f32(x[512], a.x.dtype);
+    acc += xv * h16_to_f32(a.w_lm[packed_weight_offset(tok, k, a.d)], a.x.dtype);
   }
   acc = wave_sum(acc);
   if ((threadIdx.x & 63) == 0) dsh[threadIdx.x >> 6] = acc;

@@ -25,19 +25,20 @@ PER_LAYER = ("attn_norm", "wq", "wk", "wv", "wo", "q_norm", "k_norm", "ffn_norm"
              "w_router")
 
 
-def _to_bf16_cuda(a, device) -> torch.Tensor:
-    """uint16 bit patterns (numpy) or a bf16 tensor -> contiguous bf16 CUDA tensor."""
+def _to_h16_cuda(a, device, dtype) -> torch.Tensor:
+    """uint16 bit patterns (numpy) or a tensor -> contiguous CUDA tensor of the model's 16-bit dtype."""
     if isinstance(a, torch.Tensor):
-        return a.to(device=device, dtype=torch.bfloat16).contiguous()
+        return a.to(device=device, dtype=dtype).contiguous()
     t = torch.from_numpy(np.ascontiguousarray(a).view(np.int16))
-    return t.to(device).view(torch.bfloat16)
+    return t.to(device).view(dtype)
 
 
 class RolloutModel:
     """Weights on the device plus the library handle.
 
     cfg: mapping with the fields of rlx_model_config (without struct_size).
-    tensor(layer, name) returns the row-major bf16 tensor (uint16 numpy bits or torch bf16) under the
+    cfg["dtype"] (default bf16) names the 16-bit format of every tensor: binding.RLX_DTYPE_BF16 / RLX_DTYPE_F16.
+    tensor(layer, name) returns the row-major tensor (uint16 numpy bits or a torch tensor) under the
     usual names (wq, wk, wv, wo, w_gate, w_up, w_down, ...); layer -1 holds embed / lm_head /
     final_norm.  The streamed matrices are converted to the library's packed layout here.
     """
@@ -51,16 +52,18 @@ class RolloutModel:
         for k, v in self.cfg.items():
             setattr(c, k, v)
         self._c = c
+        self.torch_dtype = torch.float16 if c.dtype == B.RLX_DTYPE_F16 else torch.bfloat16
+        td = self.torch_dtype
         moe = c.n_experts > 0
         names = [n for n in PER_LAYER if (n not in ("q_norm", "k_norm") or c.qk_norm) and (n != "w_router" or moe)]
         self.tensors: Dict = {}
 
         def put(layer, n):
             if n == "w_gate_up":
-                t = B.pack_gate_up(_to_bf16_cuda(tensor(layer, "w_gate"), self.device),
-                                   _to_bf16_cuda(tensor(layer, "w_up"), self.device))
+                t = B.pack_gate_up(_to_h16_cuda(tensor(layer, "w_gate"), self.device, td),
+                                   _to_h16_cuda(tensor(layer, "w_up"), self.device, td))
             else:
-                t = _to_bf16_cuda(tensor(layer, n), self.device)
+                t = _to_h16_cuda(tensor(layer, n), self.device, td)
                 if n in PACKED:          # row-major copy is dropped once the packed one exists
                     t = B.pack_matrix(t)
             self.tensors[(layer, n)] = t
@@ -231,7 +234,7 @@ class RolloutEngine:
                 if e is not None:
                     full[o:o + ln] = e
                 o += ln
-            emb = torch.from_numpy(full.view(np.int16)).to(dev).view(torch.bfloat16)
+            emb = torch.from_numpy(full.view(np.int16)).to(dev).view(self.m.torch_dtype)
         cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device=dev)
         ctx = self.ctx_lens[idx].contiguous()
         bt = self.block_table[idx].contiguous()
@@ -284,7 +287,7 @@ class RolloutEngine:
                 if e is not None:
                     full[o:o + ln] = e
                 o += ln
-            emb = torch.from_numpy(full.view(np.int16)).to(dev).view(torch.bfloat16)
+            emb = torch.from_numpy(full.view(np.int16)).to(dev).view(self.m.torch_dtype)
         rep = None
         if replay_routing is not None and self.is_moe:
             if any(r is None for r in replay_routing):

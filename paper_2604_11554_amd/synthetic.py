@@ -6,8 +6,14 @@ import rollout_inputs as RI
 from .engine import RolloutModel
 
 
-def config_from_shape(s: RI.ModelShape, activation_split: int = 1) -> dict:
-    return dict(activation_split=activation_split, n_layers=s.n_layers, d_model=s.d_model, n_q_heads=s.n_q_heads, n_kv_heads=s.n_kv_heads,
+FORMAT_IDS = {"bf16": 0, "f16": 1}   # rlx_model_config.dtype
+
+
+def config_from_shape(s: RI.ModelShape, activation_split: int = 1, fmt: str = "bf16") -> dict:
+    """fmt "f16": the FP16 precision option (one fp16 term per activation: activation_split is forced to 0)."""
+    if fmt == "f16":
+        activation_split = 0
+    return dict(dtype=FORMAT_IDS[fmt], activation_split=activation_split, n_layers=s.n_layers, d_model=s.d_model, n_q_heads=s.n_q_heads, n_kv_heads=s.n_kv_heads,
                 head_dim=s.head_dim, d_ff=s.d_ff, n_experts=s.n_experts, top_k=s.top_k,
                 d_ff_expert=s.d_ff_expert, vocab=s.vocab, kv_block_size=s.kv_block_size, rms_eps=s.rms_eps,
                 rope_theta=s.rope_theta, qk_norm=int(s.qk_norm), eos_token_id=s.eos_token_id,
@@ -15,21 +21,22 @@ def config_from_shape(s: RI.ModelShape, activation_split: int = 1) -> dict:
 
 
 def model_from_shape(s: RI.ModelShape, model_seed: int = 0, device="cuda:0", progress=None,
-                     activation_split: int = 1) -> RolloutModel:
-    """Upload the keyed synthetic weights of `s` (same bf16 bit patterns the oracle upcasts)."""
-    return RolloutModel(config_from_shape(s, activation_split), lambda l, n: RI.tensor_bf16(s, model_seed, l, n),
-                        device, progress)
+                     activation_split: int = 1, fmt: str = "bf16") -> RolloutModel:
+    """Upload the keyed synthetic weights of `s` (same bit patterns the oracle upcasts)."""
+    return RolloutModel(config_from_shape(s, activation_split, fmt),
+                        lambda l, n: RI.tensor_bits(s, model_seed, l, n, fmt), device, progress)
 
 
-def generate_tensors(s: RI.ModelShape, model_seed: int = 0, threads: int = 8, progress=None) -> dict:
-    """All bf16 bit patterns of a synthetic model, {(layer, name): uint16 array}, generated on several
+def generate_tensors(s: RI.ModelShape, model_seed: int = 0, threads: int = 8, progress=None,
+                     fmt: str = "bf16") -> dict:
+    """All bit patterns of a synthetic model, {(layer, name): uint16 array}, generated on several
     host threads (NumPy's generators release the GIL)."""
     from concurrent.futures import ThreadPoolExecutor
     keys = [(l, n) for l in [RI.GLOBAL_LAYER] + list(range(s.n_layers)) for n in RI.tensor_names(s, l)]
     out = {}
 
     def make(key):
-        return key, RI.tensor_bf16(s, model_seed, key[0], key[1])
+        return key, RI.tensor_bits(s, model_seed, key[0], key[1], fmt)
 
     with ThreadPoolExecutor(max_workers=threads) as ex:
         for i, (key, bits) in enumerate(ex.map(make, keys)):
@@ -40,5 +47,5 @@ def generate_tensors(s: RI.ModelShape, model_seed: int = 0, threads: int = 8, pr
 
 
 def model_from_tensors(s: RI.ModelShape, tensors: dict, device="cuda:0", activation_split: int = 1,
-                       progress=None) -> RolloutModel:
-    return RolloutModel(config_from_shape(s, activation_split), lambda l, n: tensors[(l, n)], device, progress)
+                       progress=None, fmt: str = "bf16") -> RolloutModel:
+    return RolloutModel(config_from_shape(s, activation_split, fmt), lambda l, n: tensors[(l, n)], device, progress)

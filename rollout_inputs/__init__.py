@@ -1,10 +1,10 @@
-"""Seeded synthetic inputs for the rollout-decode path: model shapes, bf16 weight
-tensors and prompt/length workloads.
+"""Seeded synthetic inputs for the rollout-decode path: model shapes, 16-bit weight
+tensors (bf16, or fp16 for the FP16 precision option) and prompt/length workloads.
 
 This module is shared by the CPU oracle's tests and by the HIP path's tests and
 benchmark.  It holds *no* arithmetic of the method itself: it only draws random
-numbers, rounds them to bf16 bit patterns and lays out integer bookkeeping
-(lengths, seeds, group structure).  Both sides consume exactly the same bf16 bit
+numbers, rounds them to 16-bit patterns and lays out integer bookkeeping
+(lengths, seeds, group structure).  Both sides consume exactly the same bit
 patterns (uint16 arrays), so neither depends on the other's conversion code.
 
 Everything is keyed: a tensor is a pure function of (model_seed, layer, name),
@@ -103,6 +103,23 @@ def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to IEEE fp16 (NumPy's conversion: round-to-nearest-even); uint16 bit patterns."""
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    """Exact upcast of fp16 bit patterns (uint16) to float32."""
+    return np.ascontiguousarray(bits, dtype=np.uint16).view(np.float16).astype(np.float32)
+
+
+FORMATS = {"bf16": (f32_to_bf16_bits, bf16_bits_to_f32), "f16": (f32_to_f16_bits, f16_bits_to_f32)}
+
+
+def bits_to_f32(bits: np.ndarray, fmt: str) -> np.ndarray:
+    return FORMATS[fmt][1](bits)
+
+
 # --------------------------------------------------------------------------
 # weight tensors
 # --------------------------------------------------------------------------
@@ -148,8 +165,9 @@ def tensor_names(shape: ModelShape, layer: int) -> Dict[str, Tuple[Tuple[int, ..
     return t
 
 
-def tensor_bf16(shape: ModelShape, model_seed: int, layer: int, name: str) -> np.ndarray:
-    """bf16 bit patterns (uint16) of one weight tensor."""
+def tensor_bits(shape: ModelShape, model_seed: int, layer: int, name: str, fmt: str = "bf16") -> np.ndarray:
+    """Bit patterns (uint16) of one weight tensor: the same float32 draws rounded to `fmt`."""
+    to_bits = FORMATS[fmt][0]
     dims, kind = tensor_names(shape, layer)[name]
     g = _rng(model_seed, layer, name)
     n = int(np.prod(dims))
@@ -166,12 +184,20 @@ def tensor_bf16(shape: ModelShape, model_seed: int, layer: int, name: str) -> np
             z *= np.float32(1.0 / np.sqrt(shape.d_model))
         else:  # pragma: no cover
             raise ValueError(kind)
-        out[a:a + z.size] = f32_to_bf16_bits(z)
+        out[a:a + z.size] = to_bits(z)
     return out.reshape(dims)
 
 
+def tensor_bf16(shape: ModelShape, model_seed: int, layer: int, name: str) -> np.ndarray:
+    return tensor_bits(shape, model_seed, layer, name, "bf16")
+
+
+def layer_tensors(shape: ModelShape, model_seed: int, layer: int, fmt: str = "bf16") -> Dict[str, np.ndarray]:
+    return {n: tensor_bits(shape, model_seed, layer, n, fmt) for n in tensor_names(shape, layer)}
+
+
 def layer_tensors_bf16(shape: ModelShape, model_seed: int, layer: int) -> Dict[str, np.ndarray]:
-    return {n: tensor_bf16(shape, model_seed, layer, n) for n in tensor_names(shape, layer)}
+    return layer_tensors(shape, model_seed, layer, "bf16")
 
 
 # --------------------------------------------------------------------------
@@ -274,7 +300,7 @@ def workload_moe_batch(shape: ModelShape = QWEN3_30B_A3B, batch: int = 128, prom
 def workload_omni_agentic(shape: ModelShape = QWEN3_30B_A3B, batch: int = 64, mm_lo: int = 1024,
                           mm_hi: int = 4096, n_text: int = 256, n_turns: int = 4, tool_len: int = 128,
                           turn_decode: int = 512, model_seed: int = 0, prompt_seed: int = 5,
-                          seed_base: int = 5000, embed_seed: int = 50) -> Workload:
+                          seed_base: int = 5000, embed_seed: int = 50, fmt: str = "bf16") -> Workload:
     """Each sequence: n_mm injected N(0,1) bf16 embedding positions, then n_text ids;
     then n_turns turns of (tool_len prefilled ids -> turn_decode sampled tokens)."""
     g = _rng(prompt_seed, GLOBAL_LAYER, "prompts")
@@ -284,7 +310,7 @@ def workload_omni_agentic(shape: ModelShape = QWEN3_30B_A3B, batch: int = 64, mm
         t = np.concatenate([np.full(int(n_mm[i]), -1, np.int32), _uniform_ids(g, n_text, shape)])
         toks.append(t)
         ge = _rng(embed_seed, i, "mm_embeds")
-        embeds.append(f32_to_bf16_bits(ge.standard_normal((int(n_mm[i]), shape.d_model), dtype=np.float32)))
+        embeds.append(FORMATS[fmt][0](ge.standard_normal((int(n_mm[i]), shape.d_model), dtype=np.float32)))
         turns.append([Turn(_uniform_ids(g, tool_len, shape), turn_decode) for _ in range(n_turns)])
     # the first response phase belongs to turn 0: prompt -> (tool, decode) x n_turns
     return Workload("omni_agentic", shape, model_seed, toks, embeds, np.zeros(batch, np.int32),

@@ -24,8 +24,8 @@ def test_every_declared_symbol_is_exported_and_bound():
 
 
 def test_struct_layouts_match_header():
-    # field order and C types as written in the header: 1 uint32, 11 int32, 2 float, 4 int32
-    assert ctypes.sizeof(B.ModelConfig) == 4 * 18
+    # field order and C types as written in the header: 1 uint32, 11 int32, 2 float, 5 int32
+    assert ctypes.sizeof(B.ModelConfig) == 4 * 19
     assert ctypes.sizeof(B.Weights) == 8 + 8 * 3 + 8 * 11
     assert B.rlx_last_error() == "" or isinstance(B.rlx_last_error(), str)
 

@@ -44,14 +44,15 @@ def _prefill_all(eng, wl, budget, rows_of_interest):
     return got
 
 
-def _run_case(shape, wl, split, n_steps, sample_rows, budget=8192):
+def _run_case(shape, wl, split, n_steps, sample_rows, budget=8192, fmt="bf16"):
     import paper_2604_11554_amd as pkg
     from paper_2604_11554_amd import synthetic
     pkg.binding.lib()
     say("generating %s weights on the host" % shape.name)
-    tensors = synthetic.generate_tensors(shape, 0, threads=12, progress=lambda i, n: say("  tensor %d/%d" % (i, n)))
+    tensors = synthetic.generate_tensors(shape, 0, threads=12, progress=lambda i, n: say("  tensor %d/%d" % (i, n)),
+                                        fmt=fmt)
     say("uploading")
-    model = synthetic.model_from_tensors(shape, tensors, activation_split=split)
+    model = synthetic.model_from_tensors(shape, tensors, activation_split=split, fmt=fmt)
     plen = wl.prompt_lens
     mb = (int(plen.max()) + n_steps + 16) // 16 + 1
     eng = pkg.RolloutEngine(model, n_blocks=int(sum((int(n) + n_steps + 31) // 16 for n in plen)) + 8,
@@ -70,7 +71,7 @@ def _run_case(shape, wl, split, n_steps, sample_rows, budget=8192):
         say("decode step %d done" % s)
     # ---- oracle: teacher-forced on the GPU's own tokens, replaying the GPU's routing (routing replay) so
     # that a tolerated near-tie does not hide everything after it; its own router choice is still reported
-    om = O.OracleModel(shape, 0, cache_layers=False, tensors=tensors)
+    om = O.OracleModel(shape, 0, cache_layers=False, tensors=tensors, fmt=fmt)
     seqs, replay = [], []
     for k, r in enumerate(sample_rows):
         toks = list(wl.prompt_tokens[r]) + [got[r][0]] + [int(st[0][k]) for st in steps[:-1]]
@@ -101,7 +102,7 @@ def _run_case(shape, wl, split, n_steps, sample_rows, budget=8192):
             stats["routes"] += bad.size
             stats["tie_flips"] += int(bad.sum())
             assert (gaps[bad] < TIE_GAP).all(), "routing differs at gate gap %.2e" % float(gaps[bad].max())
-    say("%s sampled-row stats %s" % (shape.name, stats))
+    say("%s %s sampled-row stats %s" % (shape.name, fmt, stats))
     assert stats["dlogit"] <= LOGIT_BAR and stats["dlogprob"] <= LOGPROB_BAR
     model.close()
     return stats
@@ -113,6 +114,16 @@ def test_dense_4b_shape_batch64_sampled_rows():
     plen = wl.prompt_lens
     rows = [int(np.argmin(plen)), int(np.argsort(plen)[len(plen) // 2])]   # shortest and median prompt
     _run_case(shape, wl, split=1, n_steps=3, sample_rows=rows)
+
+
+def test_dense_4b_shape_batch64_sampled_rows_fp16():
+    """The FP16 precision option (paper App. "FP16 vs. BF16 precision ablation") at the benchmark's shape:
+    fp16 weights and KV pages, one fp16 term per activation, against the oracle with the same fp16 roundings."""
+    shape = RI.QWEN3_4B
+    wl = RI.workload_dense_batch(shape)
+    plen = wl.prompt_lens
+    rows = [int(np.argmin(plen)), int(np.argsort(plen)[len(plen) // 2])]
+    _run_case(shape, wl, split=0, n_steps=3, sample_rows=rows, fmt="f16")
 
 
 def test_moe_30b_a3b_layer_slice_batch128_sampled_rows():

@@ -160,17 +160,18 @@ def compare_rollouts(gsteps, osteps, wl, is_moe):
     return stats
 
 
-def teacher_forced_parity(pkg, synthetic, shape, wl, n_decode, split, model_seed=0, attention_grid=None, osteps=None):
+def teacher_forced_parity(pkg, synthetic, shape, wl, n_decode, split, model_seed=0, attention_grid=None, osteps=None,
+                          fmt="bf16"):
     """Free-running oracle rollout -> GPU teacher-forced on its tokens -> compare.  If the GPU took a
     different expert set anywhere, the oracle is re-run replaying the GPU's routing (the paper's routing
     replay) so that everything downstream of a tolerated near-tie can still be checked."""
-    omodel = O.OracleModel(shape, model_seed)
+    omodel = O.OracleModel(shape, model_seed, fmt=fmt)
     if osteps is None:
         say("%s: oracle rollout" % shape.name)
         osteps = oracle_rollout(omodel, wl, n_decode)
     forced = [st["tokens"] for st in osteps]
     say("%s: gpu rollout (activation_split=%d, attention grid %s)" % (shape.name, split, attention_grid))
-    model = synthetic.model_from_shape(shape, model_seed, activation_split=split)
+    model = synthetic.model_from_shape(shape, model_seed, activation_split=split, fmt=fmt)
     if attention_grid is not None:
         model.set_attention_grid(attention_grid)
     mb = (int(wl.prompt_lens.max()) + n_decode + 15) // 16 + 1
@@ -186,7 +187,7 @@ def teacher_forced_parity(pkg, synthetic, shape, wl, n_decode, split, model_seed
     stats["replayed"] = n_replayed
     ctx = eng.ctx_lens[:wl.batch].cpu().numpy()
     assert list(ctx) == list(wl.prompt_lens + n_decode - 1)
-    say("%s split=%d stats %s" % (shape.name, split, stats))
+    say("%s %s split=%d stats %s" % (shape.name, fmt, split, stats))
     model.close()
     return stats
 
@@ -199,6 +200,34 @@ def test_teacher_forced_rollout_parity(amd, shape_name, split):
              "tiny_moe": RI.TINY_MOE}[shape_name]
     wl = RI.workload_tiny(shape, n_decode=32)
     teacher_forced_parity(pkg, synthetic, shape, wl, 32, split)
+
+
+# Routing bar of the fp16 option with one term per activation: the router's input carries a relative rounding
+# error of up to u = 2^-11 per element, so a gate logit g = sum_i x_i w_i moves by at most u |x| |w| to first
+# order; the test shapes have |x| ~ sqrt(d_model) = 16 (RMS-normalised rows, gains near 1) and |w| ~ 1
+# (router rows N(0, 1/d_model)), i.e. 7.8e-3.
+TIE_GAP_F16 = 2.0 ** -11 * 16.0
+
+
+@pytest.mark.parametrize("shape_name", ["tiny_dense_qkn", "tiny_moe"])
+def test_fp16_option_teacher_forced_parity(amd, shape_name, monkeypatch):
+    """The FP16 precision option (paper App. "FP16 vs. BF16 precision ablation"): fp16 weights and KV pages, one
+    fp16 term per activation, against the oracle with the same two fp16 roundings; the same logit and
+    log-probability bars as bf16."""
+    pkg, synthetic = amd
+    shape = {"tiny_dense_qkn": RI.TINY_DENSE.replace(name="tiny_dense_qkn", qk_norm=True), "tiny_moe": RI.TINY_MOE}[shape_name]
+    monkeypatch.setattr(sys.modules[__name__], "TIE_GAP", TIE_GAP_F16)
+    wl = RI.workload_tiny(shape, n_decode=32)
+    teacher_forced_parity(pkg, synthetic, shape, wl, 32, 0, fmt="f16")
+
+
+def test_fp16_option_rejects_two_term_activations(amd):
+    pkg, synthetic = amd
+    cfg = synthetic.config_from_shape(RI.TINY_DENSE, fmt="f16")
+    cfg["activation_split"] = 1
+    with pytest.raises(pkg.binding.RlxError) as e:
+        pkg.RolloutModel(cfg, lambda l, n: RI.tensor_bits(RI.TINY_DENSE, 0, l, n, "f16"))
+    assert e.value.code == pkg.binding.RLX_EUNSUPPORTED
 
 
 # ---------------------------------------------------------------------------

@@ -71,6 +71,52 @@ def test_bf16_rounding_of_the_kv_store():
     assert 0 < np.abs(a - b).max() < 0.02
 
 
+def test_fp16_option_rounding_and_model():
+    """The FP16 precision option (paper App. "FP16 vs. BF16 precision ablation"): fp16 weights, fp16 KV store."""
+    # nearest-even on the 11-bit significand grid, subnormals below 2^-14, overflow past 65504: hand-picked values
+    x = np.array([1.0, 1.0 + 2.0 ** -11, 1.0 + 2.0 ** -10, 1.0 + 3 * 2.0 ** -11, 1.0 + 2.0 ** -11 + 2.0 ** -22,
+                  65504.0, 65519.0, 65520.0, 2.0 ** -24, 2.0 ** -25, 3 * 2.0 ** -25, -(2.0 ** -14 + 2.0 ** -25),
+                  -(2.0 ** -14 + 3 * 2.0 ** -25), 0.0],
+                 np.float32)
+    want = np.array([1.0, 1.0, 1.0 + 2.0 ** -10, 1.0 + 2.0 ** -9, 1.0 + 2.0 ** -10,
+                     65504.0, 65504.0, np.inf, 2.0 ** -24, 0.0, 2.0 ** -23, -(2.0 ** -14),
+                     -(2.0 ** -14 + 2.0 ** -23), 0.0], np.float32)
+    np.testing.assert_array_equal(O.round_to_f16(x), want)
+    r = (np.random.default_rng(0).standard_normal(10000) * 3).astype(np.float64)
+    q = O.round_to_f16(r)
+    assert q.dtype == np.float64
+    big = np.abs(r) >= 2.0 ** -14
+    assert (np.abs(q - r)[big] <= np.abs(r)[big] * 2.0 ** -11).all() and (np.abs(q - r)[~big] <= 2.0 ** -25).all()
+    np.testing.assert_array_equal(O.round_to_f16(q), q)                       # idempotent
+    # independent routine: torch's float32 -> float16 conversion
+    import torch
+    r32 = r.astype(np.float32)
+    np.testing.assert_array_equal(O.round_to_f16(r32), torch.from_numpy(r32).to(torch.float16).to(torch.float32).numpy())
+    # the same draws, rounded to fp16 instead of bf16: closer to the unrounded values than bf16 is
+    wb = RI.bits_to_f32(RI.tensor_bits(DENSE, 5, 0, "wq", "bf16"), "bf16")
+    wh = RI.bits_to_f32(RI.tensor_bits(DENSE, 5, 0, "wq", "f16"), "f16")
+    assert 0 < np.abs(wb - wh).max() <= np.abs(wb).max() * 2.0 ** -8
+    np.testing.assert_array_equal(O.round_to_f16(wh), wh)
+    # the store is where the rounding happens, and incremental decoding still equals the full forward
+    model = O.OracleModel(DENSE, 5, fmt="f16")
+    tok = _prompts(DENSE, (9,))[0]
+    ro = O.OracleRollout(model, n_blocks=4)
+    i = ro.add_sequence(seed=1)
+    r0 = ro.prefill_chunk([i], [tok], want_logits=True)
+    used = ro.kpool[:, ro.blocks[i][0], :9]
+    np.testing.assert_array_equal(used, used.astype(np.float16).astype(used.dtype))
+    assert (used.view(np.uint32) & 0xFFFF != 0).any()                          # finer than the bf16 grid
+    r1 = ro.decode_step([i], want_logits=True)
+    full = O.forward_full(model, [np.array(list(tok) + [r0["tokens"][0]], np.int32)])[0]["logits"]
+    np.testing.assert_allclose(np.stack([r0["logits"][0], r1["logits"][0]]), full[8:], atol=1e-4, rtol=0)
+    # fp16 storage perturbs the logits less than bf16 storage does (same unrounded draws behind both models)
+    exact_h = O.forward_full(O.OracleModel(DENSE, 5, fmt="f16", kv_bf16=False), [tok])[0]["logits"]
+    exact_b = O.forward_full(O.OracleModel(DENSE, 5, fmt="bf16", kv_bf16=False), [tok])[0]["logits"]
+    d_h = np.abs(O.forward_full(model, [tok])[0]["logits"] - exact_h).max()
+    d_b = np.abs(O.forward_full(O.OracleModel(DENSE, 5), [tok])[0]["logits"] - exact_b).max()
+    assert 0 < d_h < d_b
+
+
 def test_float32_oracle_close_to_float64():
     toks = _prompts(MOE, (24,))
     z32 = O.forward_full(O.OracleModel(MOE, 3, dtype=np.float32, kv_bf16=False), toks)[0]
