@@ -149,6 +149,25 @@ RLX_API int rlx_model_destroy(rlx_model* m);
 RLX_API int rlx_model_set_attention_grid(rlx_model* m, int32_t n_workgroups);
 
 /*
+ * Weight refresh between steps (the inference-engine end of the weight synchronisation of paper Sec. 3.2,
+ * "Distributed Checkpoint Service", and the version v_r of the staleness rule s = v_t - v_r of Sec. 3.3,
+ * "Unified training modes via staleness control").  rlx_model_set_weights replaces every weight pointer of the
+ * model by those of `w` (same shapes, dtype and layouts as at create; the per-layer tables are copied) and
+ * records `version`; nothing is copied on the device and no stream is touched.  Calls enqueued before it keep
+ * reading the old tensors, calls made after it read the new ones, so:
+ *   - the new tensors must be complete, on the stream of the next call or synchronised, before that call;
+ *   - the old tensors may be released only once the calls enqueued before the swap have finished;
+ *   - KV pages written under the old weights stay valid storage: a sequence that continues across the swap
+ *     attends to keys and values of the old policy (a partial rollout), which is the caller's choice to allow.
+ * On error (RLX_EINVAL: NULL or misaligned pointer, struct_size) the model keeps its previous weights and
+ * version.  A model starts at version 0.  Not thread-safe against calls that use the model.
+ * rlx_model_weight_version reports the version of the installed weights, i.e. the tag v_r of every token a
+ * subsequent call emits.
+ */
+RLX_API int rlx_model_set_weights(rlx_model* m, const rlx_weights* w, uint64_t version);
+RLX_API int rlx_model_weight_version(const rlx_model* m, uint64_t* version_out);
+
+/*
  * Size in bytes of a KV pool of n_blocks pages (2 bytes per element, the model's dtype).  Layout, private to the
  * library: [layer][block][kv_head]{ K[16][head_dim], V^T[head_dim][16] }.
  * The caller allocates it (256-byte aligned) and passes n_blocks to every call.

@@ -216,6 +216,17 @@ class OracleRollout:
         self.max_ctx: List[int] = []
         self.finished: List[bool] = []
         self.last_token: List[int] = []
+        self.weight_version = 0
+
+    def set_model(self, model: OracleModel, version: int) -> None:
+        """Weight refresh between steps (paper Sec. 3.2, weight synchronisation to the inference engines;
+        Sec. 3.3, the rollout-side weight version v_r): later calls use `model`; the stored keys and values
+        of sequences in flight are kept, so such a sequence attends to entries of the previous weights."""
+        a, b = self.model.shape, model.shape
+        assert (a.n_layers, a.n_kv_heads, a.head_dim, a.vocab) == (b.n_layers, b.n_kv_heads, b.head_dim, b.vocab)
+        assert model.dtype == self.model.dtype
+        self.model = model
+        self.weight_version = int(version)
 
     # ---- sequence bookkeeping -------------------------------------------
     def add_sequence(self, seed: int, temperature: float = 1.0, max_ctx: int = 1 << 30) -> int:

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "librelax_rollout.so")
 
 RLX_OK, RLX_EINVAL, RLX_ENOMEM, RLX_EHIP, RLX_EUNSUPPORTED = 0, -1, -2, -3, -4
 
-EXPORTS = ["rlx_packed_weight_bytes", "rlx_pack_weight", "rlx_pack_gate_up", "rlx_model_create", "rlx_model_destroy", "rlx_model_set_attention_grid", "rlx_kv_pool_bytes", "rlx_workspace_bytes",
+EXPORTS = ["rlx_packed_weight_bytes", "rlx_pack_weight", "rlx_pack_gate_up", "rlx_model_create", "rlx_model_destroy", "rlx_model_set_attention_grid", "rlx_model_set_weights", "rlx_model_weight_version", "rlx_kv_pool_bytes", "rlx_workspace_bytes",
            "rlx_kv_copy_blocks", "rollout_prefill_chunk", "rollout_score_chunk", "rollout_decode_step", "rlx_op_linear",
            "rlx_profile_kernel", "rlx_last_error"]
 
@@ -73,6 +73,8 @@ def lib() -> C.CDLL:
         l.rlx_model_create.argtypes = [C.POINTER(ModelConfig), C.POINTER(Weights), C.POINTER(vp)]
         l.rlx_model_destroy.argtypes = [vp]
         l.rlx_model_set_attention_grid.argtypes = [vp, i32]
+        l.rlx_model_set_weights.argtypes = [vp, C.POINTER(Weights), C.c_uint64]
+        l.rlx_model_weight_version.argtypes = [vp, C.POINTER(C.c_uint64)]
         l.rlx_kv_pool_bytes.argtypes = [vp, i64, C.POINTER(sz)]
         l.rlx_workspace_bytes.argtypes = [vp, i32, i32, i32, C.POINTER(sz)]
         l.rlx_kv_copy_blocks.argtypes = [vp, vp, i64, vp, vp, i32, vp]
@@ -166,6 +168,16 @@ def rlx_model_destroy(model: int) -> None:
 
 def rlx_model_set_attention_grid(model: int, n_workgroups: int) -> None:
     _check(lib().rlx_model_set_attention_grid(model, n_workgroups))
+
+
+def rlx_model_set_weights(model: int, weights: Weights, version: int) -> None:
+    _check(lib().rlx_model_set_weights(model, C.byref(weights), version))
+
+
+def rlx_model_weight_version(model: int) -> int:
+    out = C.c_uint64()
+    _check(lib().rlx_model_weight_version(model, C.byref(out)))
+    return out.value
 
 
 def rlx_kv_pool_bytes(model: int, n_blocks: int) -> int:

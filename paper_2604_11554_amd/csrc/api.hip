@@ -63,6 +63,7 @@ struct rlx_model {
   int device;
   int n_units;        // compute units of the device
   int attn_wgs;       // decode attention grid: two workgroups per compute unit
+  uint64_t weight_version;   // tag of the installed weights (rlx_model_set_weights)
 };
 
 namespace {
@@ -309,6 +310,41 @@ int check_common(const rlx_model* m, const void* kv_pool, int64_t n_blocks, cons
   return RLX_OK;
 }
 
+// Checks a weight table against the model's shape and installs its pointers (all or nothing).
+int install_weights(rlx_model* m, const rlx_weights* wt) {
+  const rlx_model_config& c = m->cfg;
+  const bool moe = c.n_experts > 0;
+  if (wt->struct_size != sizeof(rlx_weights)) return fail(RLX_EINVAL, "rlx_weights.struct_size mismatch");
+  if (!wt->embed || !wt->lm_head || !wt->final_norm) return fail(RLX_EINVAL, "NULL global weight");
+  if (!aligned16(wt->embed) || !aligned16(wt->lm_head) || !aligned16(wt->final_norm))
+    return fail(RLX_EINVAL, "weights must be 16-byte aligned");
+  const void* const* req[] = {wt->attn_norm, wt->wq, wt->wk, wt->wv, wt->wo, wt->ffn_norm, wt->w_gate_up, wt->w_down};
+  for (auto p : req)
+    if (!p) return fail(RLX_EINVAL, "NULL per-layer weight table");
+  if (c.qk_norm && (!wt->q_norm || !wt->k_norm)) return fail(RLX_EINVAL, "qk_norm set but q_norm/k_norm missing");
+  if (moe && !wt->w_router) return fail(RLX_EINVAL, "MoE model without w_router");
+  struct Table { std::vector<const h16_t*>* dst; const void* const* src; };
+  std::vector<const h16_t*> t[11];
+  const Table tables[11] = {
+      {&m->attn_norm, wt->attn_norm}, {&m->wq, wt->wq}, {&m->wk, wt->wk}, {&m->wv, wt->wv}, {&m->wo, wt->wo},
+      {&m->ffn_norm, wt->ffn_norm}, {&m->w_gate_up, wt->w_gate_up}, {&m->w_down, wt->w_down},
+      {&m->q_norm, c.qk_norm ? wt->q_norm : nullptr}, {&m->k_norm, c.qk_norm ? wt->k_norm : nullptr},
+      {&m->w_router, moe ? wt->w_router : nullptr}};
+  for (int i = 0; i < 11; ++i) {
+    t[i].assign(c.n_layers, nullptr);
+    if (!tables[i].src) continue;
+    for (int l = 0; l < c.n_layers; ++l) {
+      if (!tables[i].src[l] || !aligned16(tables[i].src[l]))
+        return fail(RLX_EINVAL, "a per-layer weight pointer is NULL or not 16-byte aligned");
+      t[i][l] = (const h16_t*)tables[i].src[l];
+    }
+  }
+  for (int i = 0; i < 11; ++i) tables[i].dst->swap(t[i]);
+  m->embed = (const h16_t*)wt->embed; m->lm_head = (const h16_t*)wt->lm_head;
+  m->final_norm = (const h16_t*)wt->final_norm;
+  return RLX_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -319,7 +355,6 @@ int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* wt, rlx_mod
   if (!cfg || !wt || !out) return fail(RLX_EINVAL, "NULL argument");
   *out = nullptr;
   if (cfg->struct_size != sizeof(rlx_model_config)) return fail(RLX_EINVAL, "rlx_model_config.struct_size mismatch");
-  if (wt->struct_size != sizeof(rlx_weights)) return fail(RLX_EINVAL, "rlx_weights.struct_size mismatch");
   const rlx_model_config& c = *cfg;
   if (c.n_layers <= 0 || c.d_model <= 0 || c.n_q_heads <= 0 || c.n_kv_heads <= 0 || c.vocab <= 0)
     return fail(RLX_EINVAL, "non-positive dimension");
@@ -345,38 +380,16 @@ int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* wt, rlx_mod
   if (c.dtype != RLX_DTYPE_BF16 && c.dtype != RLX_DTYPE_F16) return fail(RLX_EINVAL, "dtype must be RLX_DTYPE_BF16 or RLX_DTYPE_F16");
   if (c.dtype == RLX_DTYPE_F16 && c.activation_split)
     return fail(RLX_EUNSUPPORTED, "fp16 models carry activations as one term: activation_split must be 0");
-  if (!wt->embed || !wt->lm_head || !wt->final_norm) return fail(RLX_EINVAL, "NULL global weight");
-  if (!aligned16(wt->embed) || !aligned16(wt->lm_head) || !aligned16(wt->final_norm))
-    return fail(RLX_EINVAL, "weights must be 16-byte aligned");
-  const void* const* req[] = {wt->attn_norm, wt->wq, wt->wk, wt->wv, wt->wo, wt->ffn_norm, wt->w_gate_up, wt->w_down};
-  for (auto p : req)
-    if (!p) return fail(RLX_EINVAL, "NULL per-layer weight table");
-  if (c.qk_norm && (!wt->q_norm || !wt->k_norm)) return fail(RLX_EINVAL, "qk_norm set but q_norm/k_norm missing");
-  if (moe && !wt->w_router) return fail(RLX_EINVAL, "MoE model without w_router");
 
   rlx_model* m = new (std::nothrow) rlx_model();
   if (!m) return fail(RLX_ENOMEM, "host allocation failed");
   m->cfg = c;
-  m->embed = (const h16_t*)wt->embed; m->lm_head = (const h16_t*)wt->lm_head;
-  m->final_norm = (const h16_t*)wt->final_norm;
   m->inv_freq = nullptr;
-  auto copy = [&](std::vector<const h16_t*>& dst, const void* const* src) -> bool {
-    dst.resize(c.n_layers, nullptr);
-    if (!src) return true;
-    for (int l = 0; l < c.n_layers; ++l) {
-      if (!src[l] || !aligned16(src[l])) return false;
-      dst[l] = (const h16_t*)src[l];
-    }
-    return true;
-  };
-  bool ok = copy(m->attn_norm, wt->attn_norm) && copy(m->wq, wt->wq) && copy(m->wk, wt->wk) && copy(m->wv, wt->wv) &&
-            copy(m->wo, wt->wo) && copy(m->ffn_norm, wt->ffn_norm) && copy(m->w_gate_up, wt->w_gate_up) &&
-            copy(m->w_down, wt->w_down) &&
-            copy(m->q_norm, c.qk_norm ? wt->q_norm : nullptr) && copy(m->k_norm, c.qk_norm ? wt->k_norm : nullptr) &&
-            copy(m->w_router, moe ? wt->w_router : nullptr);
-  if (!ok) {
+  m->weight_version = 0;
+  const int rc = install_weights(m, wt);
+  if (rc != RLX_OK) {
     delete m;
-    return fail(RLX_EINVAL, "a per-layer weight pointer is NULL or not 16-byte aligned");
+    return rc;
   }
   // rotary frequencies theta^(-2i/hd) in double
   std::vector<double> inv(c.head_dim / 2);
@@ -402,6 +415,19 @@ int rlx_model_set_attention_grid(rlx_model* m, int32_t n_workgroups) {
   if (n_workgroups < 1 || n_workgroups > ATTN_WGS_MAX)
     return fail(RLX_EINVAL, "rlx_model_set_attention_grid: n_workgroups %d outside 1..%d", n_workgroups, ATTN_WGS_MAX);
   m->attn_wgs = n_workgroups;
+  return RLX_OK;
+}
+
+int rlx_model_set_weights(rlx_model* m, const rlx_weights* w, uint64_t version) {
+  if (!m || !w) return fail(RLX_EINVAL, "rlx_model_set_weights: NULL argument");
+  const int rc = install_weights(m, w);
+  if (rc == RLX_OK) m->weight_version = version;
+  return rc;
+}
+
+int rlx_model_weight_version(const rlx_model* m, uint64_t* version_out) {
+  if (!m || !version_out) return fail(RLX_EINVAL, "rlx_model_weight_version: NULL argument");
+  *version_out = m->weight_version;
   return RLX_OK;
 }
 

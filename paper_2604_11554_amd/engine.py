@@ -53,10 +53,16 @@ class RolloutModel:
             setattr(c, k, v)
         self._c = c
         self.torch_dtype = torch.float16 if c.dtype == B.RLX_DTYPE_F16 else torch.bfloat16
-        td = self.torch_dtype
+        self._version = 0
+        self.tensors, self._tables, self._w = self._upload(tensor, progress)
+        self.handle = B.rlx_model_create(c, self._w)
+
+    def _upload(self, tensor: Callable[[int, str], object], progress=None):
+        """Device tensors (streamed matrices packed), the per-layer pointer tables and the rlx_weights struct."""
+        c, td = self._c, self.torch_dtype
         moe = c.n_experts > 0
         names = [n for n in PER_LAYER if (n not in ("q_norm", "k_norm") or c.qk_norm) and (n != "w_router" or moe)]
-        self.tensors: Dict = {}
+        tensors: Dict = {}
 
         def put(layer, n):
             if n == "w_gate_up":
@@ -66,7 +72,7 @@ class RolloutModel:
                 t = _to_h16_cuda(tensor(layer, n), self.device, td)
                 if n in PACKED:          # row-major copy is dropped once the packed one exists
                     t = B.pack_matrix(t)
-            self.tensors[(layer, n)] = t
+            tensors[(layer, n)] = t
 
         for n in ("embed", "lm_head", "final_norm"):
             put(-1, n)
@@ -78,17 +84,30 @@ class RolloutModel:
         torch.cuda.synchronize()
         w = B.Weights()
         w.struct_size = C.sizeof(B.Weights)
-        w.embed = self.tensors[(-1, "embed")].data_ptr()
-        w.lm_head = self.tensors[(-1, "lm_head")].data_ptr()
-        w.final_norm = self.tensors[(-1, "final_norm")].data_ptr()
-        self._tables = {}
+        w.embed = tensors[(-1, "embed")].data_ptr()
+        w.lm_head = tensors[(-1, "lm_head")].data_ptr()
+        w.final_norm = tensors[(-1, "final_norm")].data_ptr()
+        tables = {}
         for n in PER_LAYER:
             if n in names:
-                tab = B.make_pointer_table([self.tensors[(l, n)] for l in range(c.n_layers)])
-                self._tables[n] = tab
+                tab = B.make_pointer_table([tensors[(l, n)] for l in range(c.n_layers)])
+                tables[n] = tab
                 setattr(w, n, C.cast(tab, C.POINTER(C.c_void_p)))
-        self._w = w
-        self.handle = B.rlx_model_create(c, w)
+        return tensors, tables, w
+
+    @property
+    def weight_version(self) -> int:
+        """Version tag of the installed weights: the v_r of every token emitted from now on."""
+        return self._version
+
+    def update_weights(self, tensor: Callable[[int, str], object], version: int, progress=None) -> None:
+        """Weight refresh (paper Sec. 3.2, weight synchronisation to the inference engines): upload and pack a
+        new set of tensors beside the current one, wait for every call enqueued so far, then swap the model's
+        pointers and drop the old set.  Sequences in flight keep their KV pages (partial rollout)."""
+        tensors, tables, w = self._upload(tensor, progress)       # ends with a device synchronisation
+        B.rlx_model_set_weights(self.handle, w, version)
+        self._version = B.rlx_model_weight_version(self.handle)
+        self.tensors, self._tables, self._w = tensors, tables, w   # the old set is released here
 
     def weight_bytes(self) -> int:
         return sum(t.numel() * 2 for t in self.tensors.values())
@@ -116,10 +135,16 @@ class StepOutput:
     sampled: Optional[torch.Tensor]      # int32 [n] draw before forcing / capping
     routing: Optional[torch.Tensor]      # int32 [tokens, L, K]
     logits: Optional[torch.Tensor]       # float32 [n, V]
+    weight_version: int = 0              # v_r: version of the weights that produced these tokens
 
 
 class RolloutEngine:
     """Rows 0..n-1 of the state tensors are the live batch; a row is one sequence."""
+
+    def may_generate(self, trainer_version: int, max_staleness: int) -> bool:
+        """The producer-side staleness rule (paper Sec. 3.3): with v_t the trainer's weight version and v_r the
+        version installed here, generation continues only while s = v_t - v_r < max_staleness."""
+        return trainer_version - self.m.weight_version < max_staleness
 
     def __init__(self, model: RolloutModel, n_blocks: int, max_seqs: int, max_chunk_tokens: int,
                  max_blocks_per_seq: int):
@@ -258,7 +283,7 @@ class RolloutEngine:
         on = sl.bool()
         self.tokens[idx] = torch.where(on, out_tok, self.tokens[idx])
         self.finished[idx] = torch.where(on, fin, self.finished[idx])
-        return StepOutput(out_tok, out_lp, smp, routing, logits)
+        return StepOutput(out_tok, out_lp, smp, routing, logits, self.m.weight_version)
 
     def score(self, rows: Sequence[int], toks: Sequence[np.ndarray], targets: Sequence[np.ndarray],
               replay_routing: Sequence[Optional[np.ndarray]] = None, embeds: Sequence[Optional[np.ndarray]] = None,
@@ -322,7 +347,7 @@ class RolloutEngine:
         B.rollout_decode_step(self.m.handle, self.kv_pool, self.n_blocks, self.workspace, n, self.tokens,
                               self.ctx_lens, self.block_table, self.max_blocks, self.seeds, self.temperature,
                               self.max_ctx, self.finished, forced, lp, smp, routing, logits)
-        return StepOutput(self.tokens, lp, smp, routing, logits)
+        return StepOutput(self.tokens, lp, smp, routing, logits, self.m.weight_version)
 
     def compact(self) -> np.ndarray:
         """Drop finished rows (synchronises); returns the old row index of every kept row."""

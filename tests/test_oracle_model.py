@@ -271,3 +271,55 @@ def test_injected_embeddings_and_multi_turn_state():
     full = O.forward_full(model, [np.array(transcript, np.int32)], [wl.prompt_embeds[0]])[0]["logits"]
     for pos, z in logits:
         np.testing.assert_allclose(z, full[pos], atol=1e-4)
+
+
+def test_weight_refresh_keeps_the_store_and_uses_the_new_weights():
+    """Pins of OracleRollout.set_model: (1) refreshing with identical weights changes nothing; (2) weights that
+    differ only after the last attention (final norm, LM head) leave every stored key/value valid, so the steps after
+    the refresh equal the new model's full forward and the steps before it the old model's; (3) a refresh before the
+    first call equals a rollout of the new model alone."""
+    A = O.OracleModel(DENSE, 5)
+    same = O.OracleModel(DENSE, 5)
+    tb = {(l, n): RI.tensor_bits(DENSE, 5 if (l, n) not in ((RI.GLOBAL_LAYER, "lm_head"), (RI.GLOBAL_LAYER, "final_norm"))
+                                 else 9, l, n)
+          for l in [RI.GLOBAL_LAYER] + list(range(DENSE.n_layers)) for n in RI.tensor_names(DENSE, l)}
+    B_head = O.OracleModel(DENSE, 5, tensors=tb)
+    B_all = O.OracleModel(DENSE, 9)
+    tok = _prompts(DENSE, (11,))[0]
+    n_dec, k = 6, 3
+
+    def rollout(first, second, swap_at, forced=None):
+        ro = O.OracleRollout(first, n_blocks=4)
+        i = ro.add_sequence(seed=3)
+        outs = []
+        for s in range(n_dec):
+            if s == swap_at:
+                ro.set_model(second, 7)
+            f = None if forced is None else [forced[s]]
+            r = ro.prefill_chunk([i], [tok], forced_tokens=f, want_logits=True) if s == 0 else \
+                ro.decode_step([i], forced_tokens=f, want_logits=True)
+            outs.append((r["logits"][0], r["tokens"][0], r["logprobs"][0], ro.weight_version))
+        return outs
+
+    base = rollout(A, A, None)
+    forced = [o[1] for o in base]
+    # (1)
+    for x, y in zip(rollout(A, same, k), base):
+        np.testing.assert_array_equal(x[0], y[0])
+        assert x[1] == y[1] and x[2] == y[2]
+    # (2)
+    mixed = rollout(A, B_head, k, forced)
+    assert [o[3] for o in mixed] == [0] * k + [7] * (n_dec - k)
+    seq = np.array(list(tok) + forced[:-1], np.int32)
+    za = O.forward_full(A, [seq])[0]["logits"][len(tok) - 1:]
+    zb = O.forward_full(B_head, [seq])[0]["logits"][len(tok) - 1:]
+    assert np.abs(za - zb).max() > 0.05
+    for s in range(n_dec):
+        np.testing.assert_allclose(mixed[s][0], (za if s < k else zb)[s], atol=1e-4, rtol=0)
+    # (3)
+    for x, y in zip(rollout(A, B_all, 0), rollout(B_all, B_all, None)):
+        np.testing.assert_array_equal(x[0], y[0])
+    # a refresh of every layer mid-sequence is neither model's own rollout: old keys/values stay in the store
+    z_mid = rollout(A, B_all, k, forced)[k][0]
+    z_b = O.forward_full(B_all, [seq])[0]["logits"][len(tok) - 1 + k]
+    assert np.abs(z_mid - z_b).max() > 1e-3 and np.abs(z_mid - za[k]).max() > 1e-3
