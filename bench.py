@@ -325,6 +325,11 @@ def main():
     step_b = np.mean([step_bytes(shape, int((ctx0 + s + 1).sum()), bsz, touched) for s in range(K)])
     step_gbs = step_b / (ms_step * 1e-3) / 1e9
     fin = int(eng.finished[:bsz].sum().item())
+    # every decode step this process ran (warmup, per-class timing, timed region) and the cached positions it
+    # attended: what per-dispatch hardware counters of a profiled run average over
+    offs = list(range(W)) + [W + i for i in range(2 * len(classes))] + list(range(K))
+    log("all decode steps run: %d, mean positions attended per step (sum over sequences, new token included) %.2f" % (
+        len(offs), float(np.mean([(ctx0 + o + 1).sum() for o in offs]))))
     log("decode: %d steps, %.3f ms/step, %.0f tok/s; step bytes %.2f GB -> %.0f GB/s (%.1f%% of 8 TB/s); "
         "host wall %.2f s; finished rows %d" % (K, ms_step, toks_per_s, step_b / 1e9, step_gbs,
                                                  100 * step_gbs / HBM_PEAK_GBS, wall, fin))
@@ -334,9 +339,9 @@ def main():
         "value": toks_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": "%s: %s, batch %d, prompts uniform %d..%d, %d decoded tokens, paged bf16 KV block 16, "
+        "config": {"workload": "%s: %s, batch %d, prompts uniform %d..%d, %d decoded tokens, paged %s KV block 16, "
                                "temperature 1 Gumbel-max" % (args.workload, shape.name, bsz, plen.min(), plen.max(),
-                                                              n_decode),
+                                                              n_decode, args.dtype),
                    "activation_split": split, "prefill_tokens_per_s": float(plen.sum() / t_prefill)},
         # the prefill chunks that filled the cache before the timed decode steps (MFMA-bound part of the path)
         "prefill": {"tokens": int(plen.sum()), "seconds": t_prefill, "tokens_per_s": float(plen.sum() / t_prefill),
