@@ -5,6 +5,6 @@ rollout loop (memory and integer bookkeeping only).  The HIP library must be
 built first (`python -m paper_2604_11554_amd.build`); there is no fallback path.
 """
 from . import binding
-from .engine import RolloutEngine, RolloutModel, StepOutput
+from .engine import Completion, Request, RolloutEngine, RolloutModel, StepOutput, StreamingRollout
 
-__all__ = ["binding", "RolloutEngine", "RolloutModel", "StepOutput"]
+__all__ = ["binding", "Completion", "Request", "RolloutEngine", "RolloutModel", "StepOutput", "StreamingRollout"]

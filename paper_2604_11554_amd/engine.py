@@ -236,6 +236,41 @@ class RolloutEngine:
         self.n += 1
         return i
 
+    # ---- slots: rows that are refilled in place (continuous refill) --------------
+    def open_slots(self, n: int) -> None:
+        """Make rows 0..n-1 empty slots: inert rows (finished, no pages) that decode steps skip."""
+        if self.n:
+            raise ValueError("open_slots needs an empty engine")
+        if n > self.max_seqs:
+            raise ValueError("more slots than max_seqs")
+        self.block_lists = [[] for _ in range(n)]
+        self.block_table[:n].zero_()
+        self.ctx_lens[:n].zero_()
+        self.finished[:n].fill_(1)
+        self.n = n
+
+    def pages_free(self) -> int:
+        return len(self.free_blocks)
+
+    def refill_slot(self, row: int, seed: int, temperature: float, max_ctx: int) -> bool:
+        """Release the row's pages and start a new empty sequence in it, with pages for max_ctx positions.
+        Returns False (row left empty and inert) when the pool cannot hold it now."""
+        self.release_slot(row)
+        nb = (max_ctx + 15) // 16
+        if nb > self.max_blocks:
+            raise ValueError("sequence needs %d pages > max_blocks_per_seq %d" % (nb, self.max_blocks))
+        if nb > len(self.free_blocks):
+            return False
+        blocks = self._alloc(nb)
+        self.block_lists[row] = blocks
+        self._set_row(row, blocks, seed, temperature, max_ctx)
+        return True
+
+    def release_slot(self, row: int) -> None:
+        self._release(self.block_lists[row])
+        self.block_lists[row] = []
+        self.finished[row] = 1
+
     # ---- steps ---------------------------------------------------------------
     def prefill(self, rows: Sequence[int], toks: Sequence[np.ndarray], embeds: Sequence[Optional[np.ndarray]] = None,
                 sample_last: Sequence[bool] = None, forced: Sequence[int] = None, want_logits=False,
@@ -363,3 +398,176 @@ class RolloutEngine:
         self.block_lists = [self.block_lists[j] for j in keep]
         self.n = k
         return keep
+
+
+# ---------------------------------------------------------------------------
+# streaming rollout: continuous refill and micro-batch completion events
+# ---------------------------------------------------------------------------
+
+@dataclass
+class Request:
+    prompt: np.ndarray                   # int32 token ids
+    seed: int
+    temperature: float = 1.0
+    max_new_tokens: int = 1 << 20        # the response ends with EOS or, at this length, with a forced EOS
+
+
+@dataclass
+class Completion:
+    index: int                           # position of the request in the submitted list
+    tokens: np.ndarray                   # int32 response, final EOS included
+    logprobs: np.ndarray                 # float32, one per response token
+    weight_versions: np.ndarray          # int64 v_r per response token
+    routing: Optional[np.ndarray] = None  # int32 [prompt + response - 1, n_layers, top_k] (MoE, if asked for)
+
+
+class StreamingRollout:
+    """Streaming micro-batch scheduling on the rollout side (paper Sec. 3.3, "Streaming data flow"): the request
+    list is cut into micro-batches of `micro_batch` consecutive requests; a slot whose sequence has ended is
+    refilled with the next pending request instead of letting the batch shrink, and as soon as every member of
+    a micro-batch has ended `on_partition(partition_index, completions)` is called, completions in request order.
+
+    The device is polled every `poll_every` decode steps (one host synchronisation per poll); a sequence that ends
+    between polls idles as an inert row until the next poll.  `may_admit()` (optional) gates the admission of new
+    requests, e.g. the producer-side staleness rule `engine.may_generate(v_t, max_staleness)`; sequences already
+    running continue.  The callback may refresh the weights (`model.update_weights`): tokens are tagged with the
+    version in force when they were produced.
+
+    `engine` needs: slots via open_slots / refill_slot / release_slot, prefill, decode_step, and the state tensors
+    tokens, ctx_lens, finished.
+    """
+
+    def __init__(self, engine, requests: Sequence[Request], micro_batch: int = 32, poll_every: int = 8,
+                 on_partition: Optional[Callable[[int, List[Completion]], None]] = None,
+                 may_admit: Optional[Callable[[], bool]] = None, want_routing: bool = False, slots: Optional[int] = None):
+        if micro_batch < 1 or poll_every < 1:
+            raise ValueError("micro_batch and poll_every must be positive")
+        self.eng = engine
+        self.requests = list(requests)
+        self.micro_batch = micro_batch
+        self.poll_every = poll_every
+        self.on_partition = on_partition
+        self.may_admit = may_admit
+        self.want_routing = want_routing and engine.is_moe
+        self.slots = slots if slots is not None else engine.max_seqs
+        self.decode_steps = 0
+        self.partition_order: List[int] = []
+
+    def run(self) -> List[Completion]:
+        eng, reqs = self.eng, self.requests
+        n_req = len(reqs)
+        done: List[Optional[Completion]] = [None] * n_req
+        n_parts = (n_req + self.micro_batch - 1) // self.micro_batch
+        left = [min(self.micro_batch, n_req - p * self.micro_batch) for p in range(n_parts)]
+        eng.open_slots(self.slots)
+        owner = [-1] * self.slots                       # request index running in each slot
+        acc: Dict[int, Dict[str, list]] = {}            # per running request: lists of per-poll arrays
+        seen = np.zeros(self.slots, np.int64)           # cached length of each slot at the last poll
+        nxt = 0
+        dev = eng.m.device
+        hist_tok = torch.zeros((self.poll_every, self.slots), dtype=torch.int32, device=dev)
+        hist_lp = torch.zeros((self.poll_every, self.slots), dtype=torch.float32, device=dev)
+        cfg = eng.m.cfg
+        hist_rt = (torch.zeros((self.poll_every, self.slots, cfg["n_layers"], cfg["top_k"]), dtype=torch.int32,
+                               device=dev) if self.want_routing else None)
+
+        def finish(slot: int) -> None:
+            r = owner[slot]
+            a = acc.pop(r)
+            done[r] = Completion(r, np.concatenate(a["tok"]).astype(np.int32), np.concatenate(a["lp"]).astype(np.float32),
+                                 np.concatenate(a["ver"]).astype(np.int64),
+                                 np.concatenate(a["rt"], 0) if self.want_routing else None)
+            owner[slot] = -1
+            eng.release_slot(slot)
+            p = r // self.micro_batch
+            left[p] -= 1
+            if left[p] == 0:
+                self.partition_order.append(p)
+                if self.on_partition:
+                    lo = p * self.micro_batch
+                    self.on_partition(p, [done[i] for i in range(lo, min(lo + self.micro_batch, n_req))])
+
+        def admit() -> None:
+            nonlocal nxt
+            rows, toks = [], []
+            budget = eng.max_chunk_tokens
+            for slot in range(self.slots):
+                if nxt >= n_req or (self.may_admit is not None and not self.may_admit()):
+                    break
+                if owner[slot] >= 0:
+                    continue
+                rq = reqs[nxt]
+                if len(rq.prompt) > budget:
+                    if not rows and len(rq.prompt) > eng.max_chunk_tokens:
+                        raise ValueError("prompt of %d tokens exceeds max_chunk_tokens" % len(rq.prompt))
+                    break
+                if not eng.refill_slot(slot, rq.seed, rq.temperature, len(rq.prompt) + rq.max_new_tokens):
+                    break                                # pool full: wait for running sequences to end
+                owner[slot] = nxt
+                acc[nxt] = dict(tok=[], lp=[], ver=[], rt=[])
+                rows.append(slot)
+                toks.append(np.asarray(rq.prompt, np.int32))
+                budget -= len(rq.prompt)
+                nxt += 1
+            if not rows:
+                return
+            out = eng.prefill(rows, toks, want_routing=self.want_routing)
+            tok, lp = out.tokens.cpu().numpy(), out.logprobs.cpu().numpy()
+            rt = out.routing.cpu().numpy() if self.want_routing else None
+            offs = np.concatenate([[0], np.cumsum([len(t) for t in toks])])
+            for j, slot in enumerate(rows):
+                a = acc[owner[slot]]
+                a["tok"].append(tok[j:j + 1]); a["lp"].append(lp[j:j + 1])
+                a["ver"].append(np.array([out.weight_version]))
+                if self.want_routing:
+                    a["rt"].append(rt[offs[j]:offs[j + 1]])
+                seen[slot] = len(toks[j])
+
+        def fill() -> None:                              # as many prefill calls as the chunk budget needs
+            while True:
+                before = nxt
+                admit()
+                if nxt == before:
+                    return
+
+        def reap_first_tokens() -> bool:                 # sequences ended by the token their prefill sampled
+            fin = eng.finished[:self.slots].cpu().numpy().astype(bool)
+            ended = [slot for slot in range(self.slots) if owner[slot] >= 0 and fin[slot]]
+            for slot in ended:
+                finish(slot)
+            return bool(ended)
+
+        while True:
+            fill()
+            while reap_first_tokens():
+                fill()
+            if all(o < 0 for o in owner):
+                if nxt >= n_req:
+                    break
+                if self.may_admit is not None and not self.may_admit():
+                    raise RuntimeError("admission is closed and nothing is running: the caller must advance v_r")
+                raise MemoryError("the KV pool cannot hold the next request")
+            k = self.poll_every
+            for s in range(k):
+                eng.decode_step(out_logprobs=hist_lp[s], out_routing=None if hist_rt is None else hist_rt[s])
+                hist_tok[s].copy_(eng.tokens[:self.slots])
+            self.decode_steps += k
+            version = eng.m.weight_version
+            tok, lp = hist_tok.cpu().numpy(), hist_lp.cpu().numpy()          # synchronises
+            rt = hist_rt.cpu().numpy() if self.want_routing else None
+            ctx = eng.ctx_lens[:self.slots].cpu().numpy()
+            fin = eng.finished[:self.slots].cpu().numpy().astype(bool)
+            for slot in range(self.slots):
+                r = owner[slot]
+                if r < 0:
+                    continue
+                m = int(ctx[slot] - seen[slot])          # steps in which the row was live: its new tokens
+                seen[slot] = ctx[slot]
+                a = acc[r]
+                a["tok"].append(tok[:m, slot].copy()); a["lp"].append(lp[:m, slot].copy())
+                a["ver"].append(np.full(m, version))
+                if self.want_routing:
+                    a["rt"].append(rt[:m, slot].copy())
+                if fin[slot]:
+                    finish(slot)
+        return [c for c in done if c is not None]
