@@ -274,6 +274,42 @@ RLX_API int rollout_decode_step(const rlx_model* m, void* kv_pool, int64_t n_blo
                         int32_t* out_sampled, int32_t* out_routing, float* out_logits, void* stream);
 
 /*
+ * Decode over shared prompt prefixes.  Sequences of one sampling group (the G responses drawn for one prompt by
+ * the group-relative algorithms of paper Sec. 2.1, e.g. 8 per prompt) list the same physical pages for their
+ * prompt in their block-table rows.  rollout_decode_step reads those pages once per sequence; with a descriptor
+ * of the sharing, rollout_decode_step_shared reads them once per subgroup of 16 / (n_q_heads / n_kv_heads)
+ * sequences (their query heads fill the 16 matrix-core columns that one sequence leaves mostly empty) and merges
+ * the two parts of each sequence's softmax.  The results equal rollout_decode_step's up to the order of the
+ * floating-point merges.
+ *
+ *   rlx_shared_prefix_bytes   size of a descriptor for n_seqs sequences (device memory, caller-owned, 256-byte
+ *                             aligned).
+ *   rlx_shared_prefix_build   leader[i] (HOST int32 [n_seqs]) = first sequence of i's group (leader[i] <= i, a
+ *                             group is a run of consecutive rows with one leader; leader[i] == i for a sequence on
+ *                             its own); shared_pages[i] (HOST int32 [n_seqs]) = leading block-table entries of row
+ *                             i that are identical to its leader's and hold full pages (16 cached tokens each).
+ *                             The group shares min_i shared_pages[i] pages, rounded down to an even number.
+ *                             Writes the descriptor to `desc` and synchronises `stream`.  RLX_EINVAL for a leader
+ *                             outside 0..i or a negative count, RLX_ENOMEM if desc_bytes is too small.
+ *                             Build it again whenever rows are added, removed or moved; it does not change while
+ *                             the sequences only grow.  The library cannot check the claim of identical pages:
+ *                             a descriptor that overstates the sharing gives wrong results (never an access
+ *                             outside the pool).
+ *   rollout_decode_step_shared  as rollout_decode_step, plus shared_prefix: a descriptor built for exactly n_seqs
+ *                             rows (any other is ignored), or NULL.
+ */
+RLX_API int rlx_shared_prefix_bytes(const rlx_model* m, int32_t n_seqs, size_t* bytes_out);
+RLX_API int rlx_shared_prefix_build(const rlx_model* m, int32_t n_seqs, const int32_t* leader,
+                                    const int32_t* shared_pages, void* desc, size_t desc_bytes, void* stream);
+RLX_API int rollout_decode_step_shared(const rlx_model* m, void* kv_pool, int64_t n_blocks, void* workspace,
+                        size_t workspace_bytes, int32_t n_seqs, int32_t* tokens_inout,
+                        int32_t* ctx_lens_inout, const int32_t* block_table, int32_t max_blocks_per_seq,
+                        const uint64_t* seeds, const float* temperature, const int32_t* max_ctx_len,
+                        uint8_t* finished_inout, const int32_t* forced_tokens, float* out_logprobs,
+                        int32_t* out_sampled, int32_t* out_routing, float* out_logits,
+                        const void* shared_prefix, void* stream);
+
+/*
  * Single operators, exported for per-kernel parity tests and profiling.
  *   rlx_op_linear: y[t, n] = sum_k x[t, k] W[n, k]; x bf16 [n_tokens, k] row-major, W bf16
  *   [n, k] PACKED, y float [n_tokens, n]; runs the same weight-streaming kernel the decode
@@ -295,6 +331,7 @@ RLX_API int rlx_op_linear(const void* x, const void* w, float* y, int32_t n_toke
 #define RLX_K_ROUTER 9      /* MoE router logits                              */
 #define RLX_K_GROUP 10      /* MoE top-k + capture + grouping by expert       */
 #define RLX_K_LMHEAD 11     /* LM head + log-sum-exp / Gumbel-max partials    */
+#define RLX_K_ATTN_PREFIX 12 /* decode: attention over shared prompt prefixes   */
 /*
  * From now on every stride-th launch of `kernel_class` is bracketed with
  * hipEventRecord(start_events[i]) / hipEventRecord(stop_events[i]) on the call's

@@ -78,6 +78,8 @@ struct Workspace {
   h16_t* ob;        // [T, q_dim]
   float* attn_part;  // [attn_wgs][2][Hq/Hkv][hd+4] decode partials of straddling (sequence, KV head) pairs
   int32_t *attn_prefix, *attn_wg_seq, *attn_hdr;   // decode attention plan
+  float* attn_seq_part;   // [S][Hkv][Hq/Hkv][hd+4] own part of a pair that prefix tiles precede
+  float* attn_pre_part;   // [shared_prefix_max_tiles][16][hd+4] parts of the shared-prefix tiles
   float* planes;     // split-K planes of the o / down projections
   h16_t* act;       // dense [T, F]; MoE [T*top_k, Fe]
   float* moe_y;      // [T*top_k, d]
@@ -128,6 +130,8 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
   w.attn_prefix = (int32_t*)take((size_t)(S + 1) * 4);
   w.attn_wg_seq = (int32_t*)take((size_t)ATTN_WGS_MAX * 4);
   w.attn_hdr = (int32_t*)take(2 * 4);
+  w.attn_seq_part = (float*)take((size_t)S * c.n_q_heads * (c.head_dim + 4) * 4);
+  w.attn_pre_part = (float*)take((size_t)shared_prefix_max_tiles(S, c.n_kv_heads) * 16 * (c.head_dim + 4) * 4);
   w.planes = (float*)take((size_t)plane_rows(T) * c.d_model * 4);
   if (c.n_experts) {
     const size_t P = (size_t)T * c.top_k;
@@ -164,6 +168,7 @@ struct StepIO {
   // scoring (rollout_score_chunk): every chunk position is scored against score_targets, nothing is sampled
   bool score; const int32_t* score_targets; float* score_logprobs;
   const int32_t* replay_routing;   // optional [T, n_layers, top_k]
+  const int32_t* shared_prefix;    // decode only, optional descriptor of shared prompt prefixes
 };
 
 int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspace& w, const StepIO& io,
@@ -218,6 +223,9 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
       at.block_table = io.block_table; at.max_blocks = io.max_blocks; at.ctx_lens = io.ctx_lens;
       at.n_seqs = io.n_seqs; at.unit_prefix = w.attn_prefix; at.wg_seq = w.attn_wg_seq; at.plan_hdr = w.attn_hdr;
       at.n_wgs = m->attn_wgs; at.part = w.attn_part; at.o = ob;
+      at.shared = io.shared_prefix; at.seq_part = w.attn_seq_part; at.pre_part = w.attn_pre_part;
+      at.n_prefix_wgs = 2 * m->n_units;
+      RLX_LAUNCH(RLX_K_ATTN_PREFIX, attention_decode_prefix(at, st));
       RLX_LAUNCH(RLX_K_ATTN, attention_decode(at, st));
       RLX_LAUNCH(RLX_K_ATTN_MERGE, attention_decode_merge(at, st));
     } else {
@@ -526,24 +534,25 @@ int rollout_score_chunk(const rlx_model* m, void* kv_pool, int64_t n_blocks, voi
   return run_layers(m, (h16_t*)kv_pool, n_blocks, w, io, st);
 }
 
-int rollout_decode_step(const rlx_model* m, void* kv_pool, int64_t n_blocks, void* workspace, size_t workspace_bytes,
-                        int32_t n_seqs, int32_t* tokens_inout, int32_t* ctx_lens_inout, const int32_t* block_table,
-                        int32_t max_blocks_per_seq, const uint64_t* seeds, const float* temperature,
-                        const int32_t* max_ctx_len, uint8_t* finished_inout, const int32_t* forced_tokens,
-                        float* out_logprobs, int32_t* out_sampled, int32_t* out_routing, float* out_logits,
-                        void* stream) {
+int rollout_decode_step_shared(const rlx_model* m, void* kv_pool, int64_t n_blocks, void* workspace,
+                               size_t workspace_bytes, int32_t n_seqs, int32_t* tokens_inout, int32_t* ctx_lens_inout,
+                               const int32_t* block_table, int32_t max_blocks_per_seq, const uint64_t* seeds,
+                               const float* temperature, const int32_t* max_ctx_len, uint8_t* finished_inout,
+                               const int32_t* forced_tokens, float* out_logprobs, int32_t* out_sampled,
+                               int32_t* out_routing, float* out_logits, const void* shared_prefix, void* stream) {
   int rc = check_common(m, kv_pool, n_blocks, workspace, n_seqs, max_blocks_per_seq);
   if (rc) return rc;
   if (!tokens_inout || !ctx_lens_inout || !block_table || !seeds || !temperature || !max_ctx_len ||
       !finished_inout || !out_logprobs)
     return fail(RLX_EINVAL, "NULL array argument");
+  if (shared_prefix && !aligned16(shared_prefix)) return fail(RLX_EINVAL, "shared_prefix must be 16-byte aligned");
   Workspace w = carve(m->cfg, (char*)workspace, n_seqs, n_seqs, max_blocks_per_seq);
   if (w.bytes > workspace_bytes)
     return fail(RLX_ENOMEM, "workspace too small: need %zu bytes, have %zu", w.bytes, workspace_bytes);
   hipStream_t st = (hipStream_t)stream;
   RLX_HIP(meta_decode(w.meta, n_seqs, ctx_lens_inout, finished_inout, m->inv_freq, m->cfg.head_dim, st));
-  RLX_HIP(attention_decode_plan(n_seqs, ctx_lens_inout, w.meta.tok_live, m->cfg.n_kv_heads, m->attn_wgs, w.attn_prefix,
-                                w.attn_wg_seq, w.attn_hdr, st));
+  RLX_HIP(attention_decode_plan(n_seqs, ctx_lens_inout, w.meta.tok_live, m->cfg.n_kv_heads, m->attn_wgs,
+                                (const int32_t*)shared_prefix, w.attn_prefix, w.attn_wg_seq, w.attn_hdr, st));
   StepIO io = {};
   io.n_seqs = n_seqs; io.T = n_seqs; io.decode = true;
   io.tokens = tokens_inout; io.ctx_lens = ctx_lens_inout; io.ctx_lens_rw = ctx_lens_inout;
@@ -551,7 +560,45 @@ int rollout_decode_step(const rlx_model* m, void* kv_pool, int64_t n_blocks, voi
   io.seeds = seeds; io.temperature = temperature; io.max_ctx_len = max_ctx_len; io.forced = forced_tokens;
   io.out_tokens = tokens_inout; io.out_logprobs = out_logprobs; io.finished = finished_inout;
   io.out_sampled = out_sampled; io.out_routing = m->cfg.n_experts ? out_routing : nullptr; io.out_logits = out_logits;
+  io.shared_prefix = (const int32_t*)shared_prefix;
   return run_layers(m, (h16_t*)kv_pool, n_blocks, w, io, st);
+}
+
+int rollout_decode_step(const rlx_model* m, void* kv_pool, int64_t n_blocks, void* workspace, size_t workspace_bytes,
+                        int32_t n_seqs, int32_t* tokens_inout, int32_t* ctx_lens_inout, const int32_t* block_table,
+                        int32_t max_blocks_per_seq, const uint64_t* seeds, const float* temperature,
+                        const int32_t* max_ctx_len, uint8_t* finished_inout, const int32_t* forced_tokens,
+                        float* out_logprobs, int32_t* out_sampled, int32_t* out_routing, float* out_logits,
+                        void* stream) {
+  return rollout_decode_step_shared(m, kv_pool, n_blocks, workspace, workspace_bytes, n_seqs, tokens_inout,
+                                    ctx_lens_inout, block_table, max_blocks_per_seq, seeds, temperature, max_ctx_len,
+                                    finished_inout, forced_tokens, out_logprobs, out_sampled, out_routing, out_logits,
+                                    nullptr, stream);
+}
+
+int rlx_shared_prefix_bytes(const rlx_model* m, int32_t n_seqs, size_t* bytes_out) {
+  if (!m || !bytes_out || n_seqs <= 0 || n_seqs > (1 << 16)) return fail(RLX_EINVAL, "rlx_shared_prefix_bytes: bad argument");
+  *bytes_out = align_up(shared_prefix_words(n_seqs, m->cfg.n_kv_heads) * 4);
+  return RLX_OK;
+}
+
+int rlx_shared_prefix_build(const rlx_model* m, int32_t n_seqs, const int32_t* leader, const int32_t* shared_pages,
+                            void* desc, size_t desc_bytes, void* stream) {
+  if (!m || !leader || !shared_pages || !desc || n_seqs <= 0 || n_seqs > (1 << 16))
+    return fail(RLX_EINVAL, "rlx_shared_prefix_build: bad argument");
+  if (!aligned16(desc)) return fail(RLX_EINVAL, "rlx_shared_prefix_build: desc must be 16-byte aligned");
+  const size_t words = shared_prefix_words(n_seqs, m->cfg.n_kv_heads);
+  if (desc_bytes < words * 4) return fail(RLX_ENOMEM, "rlx_shared_prefix_build: desc needs %zu bytes", words * 4);
+  for (int i = 0; i < n_seqs; ++i)
+    if (leader[i] < 0 || leader[i] > i || shared_pages[i] < 0)
+      return fail(RLX_EINVAL, "rlx_shared_prefix_build: sequence %d: leader %d (0..%d) / shared_pages %d", i, leader[i],
+                  i, shared_pages[i]);
+  std::vector<int32_t> host(words);
+  shared_prefix_build(n_seqs, m->cfg.n_q_heads, m->cfg.n_kv_heads, leader, shared_pages, host.data());
+  hipStream_t st = (hipStream_t)stream;
+  RLX_HIP(hipMemcpyAsync(desc, host.data(), words * 4, hipMemcpyHostToDevice, st));
+  RLX_HIP(hipStreamSynchronize(st));      // the staging vector dies with this call
+  return RLX_OK;
 }
 
 int rlx_profile_kernel(int32_t kernel_class, void* const* start_events, void* const* stop_events, int32_t n_events,
@@ -561,7 +608,7 @@ int rlx_profile_kernel(int32_t kernel_class, void* const* start_events, void* co
     g_prof = ProfState();
     return used;
   }
-  if (!start_events || !stop_events || stride <= 0 || kernel_class < 0 || kernel_class > RLX_K_LMHEAD)
+  if (!start_events || !stop_events || stride <= 0 || kernel_class < 0 || kernel_class > RLX_K_ATTN_PREFIX)
     return fail(RLX_EINVAL, "rlx_profile_kernel: bad argument");
   g_prof = ProfState();
   g_prof.cls = kernel_class; g_prof.start = start_events; g_prof.stop = stop_events; g_prof.n = n_events;

@@ -10,6 +10,12 @@
 // works on the current one.  Where a (sequence, KV head) pair lies inside one share its output is
 // final; where it straddles shares each part leaves (o, m, l) and a small second kernel merges the
 // parts in share order (deterministic).
+//
+// Shared prompt prefixes (sequences of one sampling group list the same pages for their prompt): the descriptor
+// `shared` names, per sequence, how many leading units are served by prefix tiles instead.  A prefix tile is
+// (subgroup of up to 16 / group sequences, KV head, chunk of units): its 16 MFMA columns are the query heads of
+// all its member sequences, so the shared pages are read once per subgroup instead of once per sequence; the
+// per-sequence kernel starts after the shared units, and the merge kernel adds the prefix parts first.
 #include "attn_core.h"
 
 namespace rlx {
@@ -24,8 +30,34 @@ struct PageRegs {
 // A run: up to 64 consecutive units of one (sequence, KV head) inside this workgroup's share (64 units = one
 // register window of the block table).  A segment -- the part of a pair that lies in the share -- is one or
 // more runs; the online softmax state lives across the runs of a segment.  All fields are wave-uniform.
+// Views into the shared-prefix descriptor (kernels.h); `on` is false when there is none or it was built for
+// another batch size, and every index read from it is clamped by its user.
+struct SharedView {
+  bool on;
+  int n_tiles, max_tiles;
+  const int32_t *start_unit, *tile0, *n_chunks, *col0, *t_row, *t_kvh, *t_lo, *t_hi, *t_mem;
+};
+__device__ __forceinline__ SharedView shared_view(const int32_t* sp, int n_seqs, int Hkv) {
+  SharedView v = {};
+  v.on = sp != nullptr && sp[0] == n_seqs;
+  if (!v.on) return v;
+  v.max_tiles = shared_prefix_max_tiles(n_seqs, Hkv);
+  v.n_tiles = min(max(sp[1], 0), v.max_tiles);
+  const int32_t* p = sp + SP_HDR;
+  v.start_unit = p; v.tile0 = p + n_seqs; v.n_chunks = p + 2 * n_seqs; v.col0 = p + 3 * n_seqs;
+  p += 4 * (size_t)n_seqs;
+  v.t_row = p; v.t_kvh = p + v.max_tiles; v.t_lo = p + 2 * (size_t)v.max_tiles; v.t_hi = p + 3 * (size_t)v.max_tiles;
+  v.t_mem = p + 4 * (size_t)v.max_tiles;
+  return v;
+}
+// units of sequence `seq` that prefix tiles serve: never all of them (its own kernel keeps at least one unit)
+__device__ __forceinline__ int shared_units_of(const SharedView& v, int seq, int ctx) {
+  return v.on ? min(max(v.start_unit[seq], 0), ctx / 32) : 0;
+}
+
 struct Run {
-  int seq, kvh, ctx, np;     // np: units of the whole pair
+  int seq, kvh, ctx, np;     // np: units of the whole pair, counted from unit u0 of the sequence
+  int u0;                    // units before this pair's first one (served by prefix tiles)
   int pb, pe;                // units [pb, pe) of the pair are this share's segment
   int lo, hi;                // units [lo, hi) of the pair are this run
   bool seg_start, seg_end, valid;
@@ -53,9 +85,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const size_t page = (size_t)2 * 16 * HD;
 
   // ---- run generator: the per-sequence plan entries are held in a 64-lane register window ----
+  const SharedView sv = shared_view(a.shared, a.n_seqs, a.Hkv);
   int seq0 = seq;
   int32_t wpre = a.unit_prefix[min(seq0 + lane, a.n_seqs)];
   int32_t wctx = a.ctx_lens[min(seq0 + lane, a.n_seqs - 1)];
+  int32_t wst = shared_units_of(sv, min(seq0 + lane, a.n_seqs - 1), wctx);
   int rem_lo = 0, rem_hi = 0;                        // rest of the current segment
   Run seg = {};
   auto next_run = [&](Run& r) {
@@ -72,6 +106,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         seq0 = seq;
         wpre = a.unit_prefix[min(seq0 + lane, a.n_seqs)];
         wctx = a.ctx_lens[min(seq0 + lane, a.n_seqs - 1)];
+        wst = shared_units_of(sv, min(seq0 + lane, a.n_seqs - 1), wctx);
       }
       const int p0 = __builtin_amdgcn_readlane(wpre, seq - seq0);
       const int np = __builtin_amdgcn_readlane(wpre, seq - seq0 + 1) - p0;
@@ -82,6 +117,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       const int xs = base + kvh * np;                // first unit of this (sequence, KV head)
       seg.seq = seq; seg.kvh = kvh; seg.np = np;
       seg.ctx = __builtin_amdgcn_readlane(wctx, seq - seq0);
+      seg.u0 = __builtin_amdgcn_readlane(wst, seq - seq0);
       seg.pb = u - xs; seg.pe = min(np, u_end - xs);
       seg.valid = true;
       r = seg;
@@ -93,10 +129,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       return;
     }
   };
-  // block-table window of a run: lane holds the entries of blocks 2 lo + lane and 2 lo + 64 + lane
+  // block-table window of a run: lane holds the entries of blocks 2 (u0 + lo) + lane and + 64
   auto load_window = [&](const Run& r, int32_t& t0, int32_t& t1) {
     const int32_t* table = a.block_table + (size_t)r.seq * a.max_blocks;
-    const int jb = 2 * r.lo + lane;
+    const int jb = 2 * (r.u0 + r.lo) + lane;
     const int j0 = min(jb, a.max_blocks - 1), j1 = min(jb + 64, a.max_blocks - 1);
     t0 = table[j0]; t1 = table[j1];                  // unconditional, clamped; masked below
     if (jb >= a.max_blocks) t0 = -1;
@@ -131,7 +167,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int32_t sel = rel < 64 ? t0 : t1;
     int64_t b0 = __builtin_amdgcn_readlane(sel, rel & 63);
     int64_t b1 = __builtin_amdgcn_readlane(sel, (rel + 1) & 63);
-    const bool has1 = (2 * i + 1) * 16 < r.ctx + 1;
+    const bool has1 = (2 * (r.u0 + i) + 1) * 16 < r.ctx + 1;
     pr.ok0 = live && b0 >= 0 && b0 < a.n_blocks;
     pr.ok1 = live && has1 && b1 >= 0 && b1 < a.n_blocks;
     if (!pr.ok0) b0 = 0;                             // keep the loads in bounds; scores are masked
@@ -166,8 +202,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int key_end = cur.ctx + 1;
     const int pos_col[1] = {cur.ctx};
     auto step = [&](int i, const PageRegs<HD>& pr, bool valid) {
-      pair_step<HD, 1, PL, FMT>(st, pr.k0, pr.k1, pr.vf, qf, 32 * i, 32 * i + 16, pr.ok0 && valid, pr.ok1 && valid, key_end,
-                           pos_col, scale, g);
+      pair_step<HD, 1, PL, FMT>(st, pr.k0, pr.k1, pr.vf, qf, 32 * (cur.u0 + i), 32 * (cur.u0 + i) + 16, pr.ok0 && valid,
+                                pr.ok1 && valid, key_end, pos_col, scale, g);
     };
 
     // Two register sets alternate: while one unit is multiplied the next one's pages are in flight.  The loop
@@ -202,10 +238,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       merge_waves<HD, 1>(st, lds_o, lds_ml, wave, lane);
       if (wave == 0 && col_ok) {
         const int head = cur.kvh * group + c16;
-        if (cur.pb == 0 && cur.pe == cur.np) {
+        const bool whole = cur.pb == 0 && cur.pe == cur.np;
+        if (whole && cur.u0 == 0) {
           store_column<HD, 1, PL, FMT>(st, 0, a.o, cur.seq, head, g);
         } else {                                     // lane holds column c16, rows d = 16 dt + 4 g + {0..3}
-          float* dst = a.part + ((size_t)(w * 2 + (first_seg ? 0 : 1)) * group + c16) * PS;
+          float* dst = whole ? a.seq_part + (((size_t)cur.seq * a.Hkv + cur.kvh) * group + c16) * PS
+                             : a.part + ((size_t)(w * 2 + (first_seg ? 0 : 1)) * group + c16) * PS;
 #pragma unroll
           for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4*>(dst + 16 * dt + 4 * g) = st.o[0][dt];
           if (g == 0) { dst[HD] = st.m[0]; dst[HD + 1] = st.l[0]; }
@@ -220,8 +258,74 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
 }
 
-// One 64-thread workgroup per (sequence, KV head): inert rows are zeroed, pairs that straddle shares are
-// merged in share order; pairs that one share covered are already final.
+// Prefix tiles: workgroup t, t + grid, ... takes tile t of the descriptor.  The 16 columns are (member, head of
+// the KV head's group); every key of the tile's units is visible to every member (the pages are full and shared).
+// The four waves take units round-robin and are merged through LDS; (o, m, l) of all 16 columns go to pre_part.
+template <int HD, int PL, int FMT>
+__global__ __launch_bounds__(256) void attn_decode_prefix_kernel(AttnDecodeArgs a) {
+  constexpr int DT = HD / 16, KS = HD / 32, PS = HD + 4;
+  __shared__ f32x4 lds_o[2 * DT * WAVE];
+  __shared__ float lds_ml[2 * 2 * WAVE];
+  const SharedView sv = shared_view(a.shared, a.n_seqs, a.Hkv);
+  if (!sv.on) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c16 = lane & 15, g = lane >> 4;
+  const int group = a.Hq / a.Hkv;
+  const float scale = rsqrtf((float)HD);
+  const size_t page = (size_t)2 * 16 * HD;
+  for (int t = blockIdx.x; t < sv.n_tiles; t += gridDim.x) {
+    const int row = min(max(sv.t_row[t], 0), a.n_seqs - 1);
+    const int kvh = min(max(sv.t_kvh[t], 0), a.Hkv - 1);
+    const int lo = max(sv.t_lo[t], 0), hi = min(sv.t_hi[t], a.max_blocks / 2);
+    const int mem = sv.t_mem[(size_t)t * 16 + min(c16 / group, 15)];
+    const bool col_ok = mem >= 0 && mem < a.n_seqs;
+    const int head = kvh * group + c16 % group;
+    h16x8 qf[PL][KS];
+#pragma unroll
+    for (int p = 0; p < PL; ++p)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        qf[p][ks] = col_ok ? load_h16x8(a.q.p + p * a.q.plane + ((size_t)mem * a.Hq + head) * HD + 32 * ks + 8 * g)
+                           : zero_h16x8();
+    WaveState<HD, 1> st;
+    st.reset();
+    const int32_t* table = a.block_table + (size_t)row * a.max_blocks;
+    const int pos_col[1] = {0x7FFFFFFF};
+    for (int i = lo + wave; i < hi; i += 4) {          // 2 i + 1 < max_blocks by the clamp of hi
+      int64_t b0 = table[2 * i], b1 = table[2 * i + 1];
+      const bool ok0 = b0 >= 0 && b0 < a.n_blocks, ok1 = b1 >= 0 && b1 < a.n_blocks;
+      if (!ok0) b0 = 0;                                // keep the loads in bounds; scores are masked
+      if (!ok1) b1 = b0;
+      const h16_t* kp0 = a.pool_layer + ((size_t)b0 * a.Hkv + kvh) * page;
+      const h16_t* kp1 = a.pool_layer + ((size_t)b1 * a.Hkv + kvh) * page;
+      h16x8 k0[KS], k1[KS], vf[DT];
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        k0[ks] = load_h16x8(kp0 + c16 * HD + 32 * ks + 8 * g);
+        k1[ks] = load_h16x8(kp1 + c16 * HD + 32 * ks + 8 * g);
+      }
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+        vf[dt] = load_2x4(kp0 + 16 * HD + (size_t)(16 * dt + c16) * 16 + 4 * g,
+                          kp1 + 16 * HD + (size_t)(16 * dt + c16) * 16 + 4 * g);
+      pair_step<HD, 1, PL, FMT>(st, k0, k1, vf, [&](int p, int, int ks) { return qf[p][ks]; }, 32 * i, 32 * i + 16, ok0,
+                                ok1, 0x7FFFFFFF, pos_col, scale, g);
+    }
+    st.finish_denominators();
+    merge_waves<HD, 1>(st, lds_o, lds_ml, wave, lane);
+    if (wave == 0) {
+      float* dst = a.pre_part + ((size_t)t * 16 + c16) * PS;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4*>(dst + 16 * dt + 4 * g) = st.o[0][dt];
+      if (g == 0) { dst[HD] = st.m[0]; dst[HD + 1] = st.l[0]; }
+    }
+    __syncthreads();                                   // the merge buffers are free for the next tile
+  }
+}
+
+// One 64-thread workgroup per (sequence, KV head): inert rows are zeroed; a pair that one share covered and no
+// prefix precedes is already final; otherwise the parts are merged in a fixed order: prefix chunks in key order,
+// then the pair's own part (one share) or parts (share order).
 template <int HD>
 __global__ __launch_bounds__(64) void attn_decode_merge_kernel(AttnDecodeArgs a) {
   constexpr int PS = HD + 4;
@@ -232,14 +336,44 @@ __global__ __launch_bounds__(64) void attn_decode_merge_kernel(AttnDecodeArgs a)
   const int C = a.plan_hdr[0];
   const int xs = a.Hkv * a.unit_prefix[seq] + kvh * np;
   const int w_first = np ? xs / C : 0, w_last = np ? (xs + np - 1) / C : 0;
-  if (np && w_first == w_last) return;
+  const SharedView sv = shared_view(a.shared, a.n_seqs, a.Hkv);
+  const int su = np ? shared_units_of(sv, seq, a.ctx_lens[seq]) : 0;
+  if (np && w_first == w_last && su == 0) return;
+  int n_chunks = 0, tile0 = 0, col0 = 0;
+  if (su > 0) {
+    n_chunks = min(max(sv.n_chunks[seq], 0), SP_MAX_CHUNKS);
+    tile0 = max(sv.tile0[seq], 0);
+    col0 = min(max(sv.col0[seq], 0), 16 - group);
+  }
   for (int uu = lane; uu < group * HD / 8; uu += 64) {
     const int j = uu / (HD / 8), d0 = (uu % (HD / 8)) * 8;
     float m = -INFINITY, l = 0.f;
     float o[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = 0.f;
-    if (np) {
+    auto add = [&](const f32x4& va, const f32x4& vb, float ms, float ls) {
+      if (ms == -INFINITY) return;
+      const float mn = fmaxf(m, ms);
+      const float aa = (m == -INFINITY) ? 0.f : __expf(m - mn);
+      const float ab = __expf(ms - mn);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        o[e] = o[e] * aa + va[e] * ab;
+        o[4 + e] = o[4 + e] * aa + vb[e] * ab;
+      }
+      l = l * aa + ls * ab;
+      m = mn;
+    };
+    auto add_at = [&](const float* p) {
+      add(*reinterpret_cast<const f32x4*>(p + d0), *reinterpret_cast<const f32x4*>(p + d0 + 4), p[HD], p[HD + 1]);
+    };
+    for (int c = 0; c < n_chunks; ++c) {
+      const int t = min(tile0 + c * a.Hkv + kvh, sv.max_tiles - 1);
+      add_at(a.pre_part + ((size_t)t * 16 + col0 + j) * PS);
+    }
+    if (np && w_first == w_last) {
+      add_at(a.seq_part + (((size_t)seq * a.Hkv + kvh) * group + j) * PS);
+    } else if (np) {
       for (int w0 = w_first; w0 <= w_last; w0 += 4) {
         f32x4 va[4], vb[4];
         float ms[4], ls[4];
@@ -253,19 +387,8 @@ __global__ __launch_bounds__(64) void attn_decode_merge_kernel(AttnDecodeArgs a)
           ms[q] = p[HD]; ls[q] = p[HD + 1];
         }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          if (w0 + q > w_last || ms[q] == -INFINITY) continue;
-          const float mn = fmaxf(m, ms[q]);
-          const float aa = (m == -INFINITY) ? 0.f : __expf(m - mn);
-          const float ab = __expf(ms[q] - mn);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            o[e] = o[e] * aa + va[q][e] * ab;
-            o[4 + e] = o[4 + e] * aa + vb[q][e] * ab;
-          }
-          l = l * aa + ls[q] * ab;
-          m = mn;
-        }
+        for (int q = 0; q < 4; ++q)
+          if (w0 + q <= w_last) add(va[q], vb[q], ms[q], ls[q]);
       }
     }
     h16_t hi[8], lo[8];
@@ -286,16 +409,18 @@ __global__ __launch_bounds__(64) void attn_decode_merge_kernel(AttnDecodeArgs a)
 // One workgroup: exclusive prefix of the per-sequence unit counts, the share size, and the sequence in which
 // each share starts.
 __global__ __launch_bounds__(1024) void attn_plan_kernel(int n_seqs, const int32_t* ctx, const uint8_t* live, int Hkv,
-                                                          int n_wgs, int32_t* unit_prefix, int32_t* wg_seq,
-                                                          int32_t* hdr) {
+                                                          int n_wgs, const int32_t* shared, int32_t* unit_prefix,
+                                                          int32_t* wg_seq, int32_t* hdr) {
   __shared__ int sh[1024];
   __shared__ int carry;
   const int tid = threadIdx.x;
+  const SharedView sv = shared_view(shared, n_seqs, Hkv);
   if (tid == 0) carry = 0;
   __syncthreads();
   for (int base = 0; base < n_seqs; base += 1024) {
     const int i = base + tid;
-    const int v = (i < n_seqs && live[i]) ? (ctx[i] + 1 + 31) / 32 : 0;
+    // units of the sequence's own pairs: those after the ones that prefix tiles serve
+    const int v = (i < n_seqs && live[i]) ? (ctx[i] + 1 + 31) / 32 - shared_units_of(sv, i, ctx[i]) : 0;
     sh[tid] = v;
     __syncthreads();
     for (int o = 1; o < 1024; o <<= 1) {
@@ -330,9 +455,85 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(int n_seqs, const int32
 }  // namespace
 
 hipError_t attention_decode_plan(int n_seqs, const int32_t* ctx_lens, const uint8_t* tok_live, int Hkv, int n_wgs,
-                                 int32_t* unit_prefix, int32_t* wg_seq, int32_t* hdr, hipStream_t st) {
-  hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(1024), 0, st, n_seqs, ctx_lens, tok_live, Hkv, n_wgs, unit_prefix,
-                     wg_seq, hdr);
+                                 const int32_t* shared, int32_t* unit_prefix, int32_t* wg_seq, int32_t* hdr,
+                                 hipStream_t st) {
+  hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(1024), 0, st, n_seqs, ctx_lens, tok_live, Hkv, n_wgs, shared,
+                     unit_prefix, wg_seq, hdr);
+  return hipGetLastError();
+}
+
+// Host side of the descriptor.  A group is a run of consecutive sequences with the same leader (the first of them);
+// its shared units are the smallest shared page count of its members, halved.  Groups of one, groups that share
+// less than one unit, and models whose 16 columns hold a single sequence get no tiles.
+void shared_prefix_build(int n_seqs, int Hq, int Hkv, const int32_t* leader, const int32_t* shared_pages, int32_t* words) {
+  const int group = Hq / Hkv, MS = 16 / group;
+  const int max_tiles = shared_prefix_max_tiles(n_seqs, Hkv);
+  const size_t n_words = shared_prefix_words(n_seqs, Hkv);
+  for (size_t i = 0; i < n_words; ++i) words[i] = 0;
+  int32_t* start_unit = words + SP_HDR;
+  int32_t *tile0 = start_unit + n_seqs, *n_chunks = tile0 + n_seqs, *col0 = n_chunks + n_seqs;
+  int32_t* t_row = col0 + n_seqs;
+  int32_t *t_kvh = t_row + max_tiles, *t_lo = t_kvh + max_tiles, *t_hi = t_lo + max_tiles, *t_mem = t_hi + max_tiles;
+  for (int i = 0; i < max_tiles * 16; ++i) t_mem[i] = -1;
+  words[0] = n_seqs; words[2] = MS;
+  int n_tiles = 0;
+  if (MS >= 2) {
+    // first pass: groups and their subgroup count, to size the chunks so that the tiles fit
+    int n_sub_total = 0;
+    for (int b = 0; b < n_seqs;) {
+      int e = b + 1;
+      while (e < n_seqs && leader[e] == b && leader[b] == b) ++e;
+      int units = 0x7FFFFFFF;
+      for (int i = b; i < e; ++i) units = shared_pages[i] / 2 < units ? shared_pages[i] / 2 : units;
+      if (e - b >= 2 && units > 0) n_sub_total += (e - b + MS - 1) / MS;
+      b = e;
+    }
+    int chunks_cap = n_sub_total ? max_tiles / (n_sub_total * Hkv) : 0;
+    if (chunks_cap > SP_MAX_CHUNKS) chunks_cap = SP_MAX_CHUNKS;
+    for (int b = 0; b < n_seqs && chunks_cap >= 1;) {
+      int e = b + 1;
+      while (e < n_seqs && leader[e] == b && leader[b] == b) ++e;
+      int units = 0x7FFFFFFF;
+      for (int i = b; i < e; ++i) units = shared_pages[i] / 2 < units ? shared_pages[i] / 2 : units;
+      if (e - b >= 2 && units > 0) {
+        int nc = (units + 7) / 8;                      // at least eight units (256 keys) per chunk
+        if (nc > chunks_cap) nc = chunks_cap;
+        const int per = (units + nc - 1) / nc;
+        nc = (units + per - 1) / per;                  // no empty chunk
+        for (int sb = b; sb < e; sb += MS) {
+          const int se = sb + MS < e ? sb + MS : e;
+          for (int i = sb; i < se; ++i) {
+            start_unit[i] = units; tile0[i] = n_tiles; n_chunks[i] = nc; col0[i] = (i - sb) * group;
+          }
+          for (int c = 0; c < nc; ++c)
+            for (int h = 0; h < Hkv; ++h) {
+              const int t = n_tiles + c * Hkv + h;
+              t_row[t] = b; t_kvh[t] = h; t_lo[t] = c * per; t_hi[t] = (c + 1) * per < units ? (c + 1) * per : units;
+              for (int i = sb; i < se; ++i) t_mem[t * 16 + (i - sb)] = i;
+            }
+          n_tiles += nc * Hkv;
+        }
+      }
+      b = e;
+    }
+  }
+  words[1] = n_tiles;
+}
+
+hipError_t attention_decode_prefix(const AttnDecodeArgs& a, hipStream_t st) {
+  if (!a.shared) return hipSuccess;
+  dim3 grid(a.n_prefix_wgs);
+  const bool two = a.q.planes == 2;
+  if (a.o.dtype == DT_F16) {
+    if (a.hd == 128) hipLaunchKernelGGL((attn_decode_prefix_kernel<128, 1, DT_F16>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((attn_decode_prefix_kernel<64, 1, DT_F16>), grid, dim3(256), 0, st, a);
+  } else if (a.hd == 128) {
+    if (two) hipLaunchKernelGGL((attn_decode_prefix_kernel<128, 2, DT_BF16>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((attn_decode_prefix_kernel<128, 1, DT_BF16>), grid, dim3(256), 0, st, a);
+  } else {
+    if (two) hipLaunchKernelGGL((attn_decode_prefix_kernel<64, 2, DT_BF16>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((attn_decode_prefix_kernel<64, 1, DT_BF16>), grid, dim3(256), 0, st, a);
+  }
   return hipGetLastError();
 }
 

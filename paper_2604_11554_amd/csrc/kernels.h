@@ -159,11 +159,32 @@ struct AttnDecodeArgs {      // one new token per sequence: row = sequence slot
   int n_wgs;                   // grid size: shares of the unit sequence
   float* part;               // [n_wgs][2][Hq/Hkv][hd+4] partial (o, m, l) of a share's first / other straddling pair
   Act o;                     // [n_seqs, Hq*hd] in fragment order (input of the output projection)
+  // shared prompt prefixes (optional): the first units of a sequence that shares them with others are attended
+  // once per group by attention_decode_prefix; the kernels above then start at unit sp.start_unit[seq]
+  const int32_t* shared;     // descriptor built by shared_prefix_build (device), or null
+  float* seq_part;           // [n_seqs][Hkv][Hq/Hkv][hd+4] partial of a pair that one share covered but a prefix precedes
+  float* pre_part;           // [shared_prefix_max_tiles][16][hd+4] partials of the prefix tiles
+  int n_prefix_wgs;          // grid of the prefix kernel
 };
+// Descriptor of the shared prefixes of a batch, int32 words (built on the host, read by the kernels):
+//   [0] n_seqs it was built for, [1] n_tiles, [2] members per tile MS = 16 / (Hq/Hkv), [3..7] 0
+//   per sequence (4 arrays of n_seqs): start_unit, tile0 (first tile of its subgroup), n_chunks, col0 (its first column)
+//   per tile (arrays of max_tiles): row (sequence whose block-table row lists the pages), kvh, unit lo, unit hi,
+//   then members [max_tiles][16] (-1 = none).  Tile of (subgroup, chunk c, kvh) = tile0 + c * Hkv + kvh.
+constexpr int SP_HDR = 8;
+constexpr int SP_MAX_CHUNKS = 4;
+__host__ __device__ inline int shared_prefix_max_tiles(int n_seqs, int Hkv) { return n_seqs * 2 * Hkv; }
+inline size_t shared_prefix_words(int n_seqs, int Hkv) {
+  return (size_t)SP_HDR + 4 * (size_t)n_seqs + (size_t)shared_prefix_max_tiles(n_seqs, Hkv) * (4 + 16);
+}
+// fills `words` (shared_prefix_words entries) from per-sequence group leaders and shared page counts (host arrays)
+void shared_prefix_build(int n_seqs, int Hq, int Hkv, const int32_t* leader, const int32_t* shared_pages, int32_t* words);
 hipError_t attention_decode_plan(int n_seqs, const int32_t* ctx_lens, const uint8_t* tok_live, int Hkv, int n_wgs,
-                                 int32_t* unit_prefix, int32_t* wg_seq, int32_t* hdr, hipStream_t st);
+                                 const int32_t* shared, int32_t* unit_prefix, int32_t* wg_seq, int32_t* hdr,
+                                 hipStream_t st);
+hipError_t attention_decode_prefix(const AttnDecodeArgs& a, hipStream_t st);   // no-op without a descriptor
 hipError_t attention_decode(const AttnDecodeArgs& a, hipStream_t st);
-hipError_t attention_decode_merge(const AttnDecodeArgs& a, hipStream_t st);   // straddling pairs, inert rows
+hipError_t attention_decode_merge(const AttnDecodeArgs& a, hipStream_t st);   // prefix parts, straddling pairs, inert rows
 
 // ---- moe.hip ----
 struct RouterArgs {

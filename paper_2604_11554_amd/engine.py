@@ -170,6 +170,13 @@ class RolloutEngine:
         self.block_table = torch.zeros((max_seqs, max_blocks_per_seq), **i32)
         self.n = 0
         self.is_moe = model.cfg["n_experts"] > 0
+        # sampling groups: rows that list the same pages for their prompt (fork); decode steps attend to those
+        # pages once per subgroup (rollout_decode_step_shared) while share_prefix_attention is set
+        self.share_prefix_attention = True
+        self.leader: List[int] = []                       # first row of each row's group
+        self.shared_pages: List[int] = []                 # leading pages a row shares with its group
+        self._sp_desc: Optional[torch.Tensor] = None
+        self._sp_dirty = True
 
     # ---- sequences and pages -------------------------------------------------
     def _set_row(self, i, blocks, seed, temperature, max_ctx, ctx=0, token=0):
@@ -210,6 +217,9 @@ class RolloutEngine:
         blocks = self._alloc(nb)
         self.block_lists.append(blocks)
         self._set_row(i, blocks, seed, temperature, max_ctx)
+        self.leader.append(i)
+        self.shared_pages.append(0)
+        self._sp_dirty = True
         self.n += 1
         return i
 
@@ -229,6 +239,17 @@ class RolloutEngine:
         i = self.n
         self.block_lists.append(blocks)
         self._set_row(i, blocks, seed, temperature, max_ctx, ctx=ctx, token=int(self.tokens[src].item()))
+        # the new row joins src's group if that group ends at the previous row (groups are runs of rows)
+        root = self.leader[src]
+        if n_full > 0 and all(self.leader[r] == root for r in range(root, i)):
+            alone = all(self.leader[r] != root for r in range(root + 1, i))
+            self.shared_pages[root] = n_full if alone else min(self.shared_pages[root], n_full)
+            self.leader.append(root)
+            self.shared_pages.append(n_full)
+        else:
+            self.leader.append(i)
+            self.shared_pages.append(0)
+        self._sp_dirty = True
         if ctx % 16:
             s = torch.tensor([self.block_lists[src][n_full]], dtype=torch.int32, device=self.m.device)
             d = torch.tensor([own[0]], dtype=torch.int32, device=self.m.device)
@@ -244,6 +265,9 @@ class RolloutEngine:
         if n > self.max_seqs:
             raise ValueError("more slots than max_seqs")
         self.block_lists = [[] for _ in range(n)]
+        self.leader = list(range(n))
+        self.shared_pages = [0] * n
+        self._sp_dirty = True
         self.block_table[:n].zero_()
         self.ctx_lens[:n].zero_()
         self.finished[:n].fill_(1)
@@ -379,10 +403,28 @@ class RolloutEngine:
         if routing is None and want_routing and self.is_moe:
             routing = torch.zeros((n, cfg["n_layers"], cfg["top_k"]), dtype=torch.int32, device=dev)
         logits = torch.empty((n, cfg["vocab"]), dtype=torch.float32, device=dev) if want_logits else None
-        B.rollout_decode_step(self.m.handle, self.kv_pool, self.n_blocks, self.workspace, n, self.tokens,
-                              self.ctx_lens, self.block_table, self.max_blocks, self.seeds, self.temperature,
-                              self.max_ctx, self.finished, forced, lp, smp, routing, logits)
+        B.rollout_decode_step_shared(self.m.handle, self.kv_pool, self.n_blocks, self.workspace, n, self.tokens,
+                                     self.ctx_lens, self.block_table, self.max_blocks, self.seeds, self.temperature,
+                                     self.max_ctx, self.finished, forced, lp, smp, routing, logits,
+                                     self._shared_prefix())
         return StepOutput(self.tokens, lp, smp, routing, logits, self.m.weight_version)
+
+    def _shared_prefix(self) -> Optional[torch.Tensor]:
+        """Descriptor of the prompt pages that groups of rows share, rebuilt when rows were added, forked or
+        compacted; None when nothing is shared (or share_prefix_attention is off)."""
+        if not self.share_prefix_attention:
+            return None
+        if self._sp_dirty:
+            self._sp_dirty = False
+            self._sp_desc = None
+            n = self.n
+            grouped = any(self.leader[i] != i and self.shared_pages[i] >= 2 for i in range(n))
+            if grouped:
+                desc = torch.empty(B.rlx_shared_prefix_bytes(self.m.handle, n), dtype=torch.uint8,
+                                   device=self.m.device)
+                B.rlx_shared_prefix_build(self.m.handle, self.leader[:n], self.shared_pages[:n], desc)
+                self._sp_desc = desc
+        return self._sp_desc
 
     def compact(self) -> np.ndarray:
         """Drop finished rows (synchronises); returns the old row index of every kept row."""
@@ -396,6 +438,14 @@ class RolloutEngine:
                   self.block_table):
             t[:k] = t[idx].clone()
         self.block_lists = [self.block_lists[j] for j in keep]
+        # groups stay runs of rows; a group whose leader left is led by its first remaining member
+        new_leader: Dict[int, int] = {}
+        leader = []
+        for new, old in enumerate(keep):
+            leader.append(new_leader.setdefault(self.leader[old], new))
+        self.leader = leader
+        self.shared_pages = [self.shared_pages[j] for j in keep]
+        self._sp_dirty = True
         self.n = k
         return keep
 

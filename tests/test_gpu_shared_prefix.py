@@ -1,0 +1,169 @@
+"""GPU parity of decode attention over shared prompt prefixes (rollout_decode_step_shared): sampling groups whose
+members list the same pages for their prompt (the G responses per prompt of the group-relative algorithms, paper
+Sec. 2.1) against the oracle, which attends to every sequence on its own.  The prefix tiles, the per-sequence
+kernel starting after the shared units and the merge must reproduce plain attention: bars as for the rollout, and
+the shared and unshared GPU paths must agree to merge-order rounding."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import rollout_inputs as RI
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_BAR, LOGPROB_BAR, TIE_GAP = 0.05, 0.02, 1e-3
+N_STEPS, COMPACT_AT = 40, 9
+# (prompt length, members): 4 and 8 shared pages, 2 shared pages (one unit), 1 shared page (nothing to share),
+# then two sequences on their own
+GROUPS = [(75, 5), (130, 3), (33, 2), (20, 2), (50, 1), (9, 1)]
+
+
+def say(msg):
+    print("[gpu-case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def amd():
+    import paper_2604_11554_amd as pkg
+    from paper_2604_11554_amd import synthetic
+    pkg.binding.lib()            # fail loudly if the library is not built
+    return pkg, synthetic
+
+
+def _prompts(shape):
+    g = np.random.default_rng(5)
+    return [g.integers(0, shape.vocab - 2, size=n).astype(np.int32) for n, _ in GROUPS]
+
+
+def _oracle(shape, prompts, forced, replay):
+    """One oracle sequence per group member (no sharing); returns per step the result dict."""
+    om = O.OracleModel(shape, 0)
+    n = sum(m for _, m in GROUPS)
+    ro = O.OracleRollout(om, n_blocks=n * ((max(p for p, _ in GROUPS) + N_STEPS) // 16 + 2))
+    ids, toks = [], []
+    for gi, (_, mem) in enumerate(GROUPS):
+        for k in range(mem):
+            ids.append(ro.add_sequence(900 + 10 * gi + k))
+            toks.append(prompts[gi])
+    f = (lambda s: None) if forced is None else (lambda s: forced[s])
+    r = (lambda s: None) if replay is None else (lambda s: replay[s])
+    steps = [ro.prefill_chunk(ids, toks, forced_tokens=f(0), forced_routing=r(0), want_logits=True)]
+    for s in range(1, N_STEPS):
+        steps.append(ro.decode_step(ids, forced_tokens=f(s), forced_routing=r(s), want_logits=True))
+    return steps
+
+
+def _gpu(pkg, synthetic, shape, prompts, forced, share):
+    """Donor row per group (prompt minus its last token, never sampled), members forked from it; donors are dropped
+    by a compaction after COMPACT_AT steps.  Returns per step (logits, logprobs, routing) in member order."""
+    model = synthetic.model_from_shape(shape, 0, activation_split=1)
+    n_rows = sum(m + (1 if m > 1 else 0) for _, m in GROUPS)
+    eng = pkg.RolloutEngine(model, n_blocks=n_rows * 12, max_seqs=n_rows, max_chunk_tokens=512, max_blocks_per_seq=12)
+    eng.share_prefix_attention = share
+    member_rows, donors, donor_rt = [], [], []
+    for gi, (plen, mem) in enumerate(GROUPS):
+        if mem == 1:
+            member_rows.append(eng.add_sequence(900 + 10 * gi, reserve_tokens=plen + N_STEPS))
+            donor_rt.append(None)
+            continue
+        d = eng.add_sequence(0, reserve_tokens=plen)
+        o = eng.prefill([d], [prompts[gi][:-1]], sample_last=[False], want_routing=True)
+        donors.append(d)
+        for k in range(mem):
+            member_rows.append(eng.fork(d, 900 + 10 * gi + k, reserve_tokens=plen + N_STEPS))
+            donor_rt.append(None if o.routing is None else o.routing.cpu().numpy())
+    for d in donors:
+        eng.tokens[d] = shape.pad_token_id
+        eng.finished[d] = 1                                    # a donor takes no part in decoding
+    toks = [prompts[gi] if mem == 1 else prompts[gi][-1:] for gi, (_, mem) in enumerate(GROUPS) for _ in range(mem)]
+    out = eng.prefill(member_rows, toks, forced=forced[0], want_logits=True, want_routing=True)
+    torch.cuda.synchronize()
+    offs = np.concatenate([[0], np.cumsum([len(t) for t in toks])])
+    rt = None if out.routing is None else out.routing.cpu().numpy()
+    # a member's prompt routing = the donor's rows for all but the last prompt position, then its own row
+    steps = [(out.logits.cpu().numpy(), out.logprobs.cpu().numpy(),
+              None if rt is None else [rt[offs[j]:offs[j + 1]] if donor_rt[j] is None else
+                                       np.concatenate([donor_rt[j], rt[offs[j]:offs[j + 1]]], 0) for j in range(len(toks))])]
+    idx = torch.tensor(member_rows, device="cuda:0")
+    n_tiles = []
+    for s in range(1, N_STEPS):
+        if s == COMPACT_AT:
+            keep = eng.compact()                               # drops the donors; groups are led by their first member
+            pos = {int(old): new for new, old in enumerate(keep)}
+            member_rows = [pos[r] for r in member_rows]
+            idx = torch.tensor(member_rows, device="cuda:0")
+        ft = torch.full((eng.n,), -1, dtype=torch.int32, device="cuda:0")
+        ft[idx] = torch.tensor(forced[s], dtype=torch.int32, device="cuda:0")
+        out = eng.decode_step(forced=ft, want_logits=True, want_routing=True)
+        torch.cuda.synchronize()
+        desc = eng._shared_prefix()
+        n_tiles.append(0 if desc is None else int(desc[:8].view(torch.int32)[1].item()))
+        rt = None if out.routing is None else out.routing[idx].cpu().numpy()
+        steps.append((out.logits[idx].cpu().numpy(), out.logprobs[idx].cpu().numpy(),
+                      None if rt is None else [rt[j][None] for j in range(len(member_rows))]))
+    model.close()
+    return steps, n_tiles
+
+
+@pytest.mark.parametrize("shape_name", ["tiny_dense", "tiny_moe"])
+def test_group_decode_over_shared_prefix_matches_oracle(amd, shape_name):
+    pkg, synthetic = amd
+    shape = {"tiny_dense": RI.TINY_DENSE, "tiny_moe": RI.TINY_MOE}[shape_name]
+    prompts = _prompts(shape)
+    say("%s: oracle free run, one sequence per member" % shape.name)
+    osteps = _oracle(shape, prompts, None, None)
+    forced = [st["tokens"] for st in osteps]
+    say("%s: gpu with prefix tiles" % shape.name)
+    gs, tiles = _gpu(pkg, synthetic, shape, prompts, forced, share=True)
+    say("%s: gpu without" % shape.name)
+    gu, tiles_u = _gpu(pkg, synthetic, shape, prompts, forced, share=False)
+    ms = 16 // (shape.n_q_heads // shape.n_kv_heads)
+    # groups 0..2 share at least one unit: subgroups x chunks x KV heads tiles, before and after the compaction
+    sub_before = sum((m + 1 + ms - 1) // ms for (p, m) in GROUPS[:3])
+    sub_after = sum((m + ms - 1) // ms for (p, m) in GROUPS[:3])
+    assert tiles[0] >= sub_before * shape.n_kv_heads and tiles[-1] >= sub_after * shape.n_kv_heads, tiles
+    assert set(tiles_u) == {0}
+    d_paths = max(float(np.abs(a[0] - b[0]).max()) for a, b in zip(gs, gu))
+    say("%s: prefix tiles per step %d -> %d; shared vs unshared max |dlogit| %.2e" % (shape.name, tiles[0], tiles[-1], d_paths))
+    assert d_paths <= 2e-3                                      # the order of the softmax merges is all that differs
+    if shape.is_moe:   # replay the GPU's routing so that a tolerated near-tie does not hide what follows
+        osteps = _oracle(shape, prompts, forced, [g[2] for g in gs])
+        flips = routes = 0
+        for g, o in zip(gs, osteps):
+            for j in range(len(g[2])):
+                bad = (np.sort(g[2][j], -1) != np.sort(o["own_routing"][j], -1)).any(-1)
+                flips += int(bad.sum())
+                routes += bad.size
+                assert (o["gate_gap"][j][bad] < TIE_GAP).all()
+        say("%s: %d near-tie routing differences in %d routed (token, layer) pairs" % (shape.name, flips, routes))
+    dl = dp = 0.0
+    for s, (g, o) in enumerate(zip(gs, osteps)):
+        for j in range(len(o["tokens"])):
+            dl = max(dl, float(np.abs(g[0][j] - o["logits"][j]).max()))
+            dp = max(dp, abs(float(g[1][j]) - o["logprobs"][j]))
+    say("%s: against the oracle max |dlogit| %.5f, max |dlogprob| %.5f over %d steps" % (shape.name, dl, dp, N_STEPS))
+    assert dl <= LOGIT_BAR and dp <= LOGPROB_BAR
+
+
+def test_shared_prefix_descriptor_validation(amd):
+    pkg, synthetic = amd
+    B = pkg.binding
+    model = synthetic.model_from_shape(RI.TINY_DENSE, 0, activation_split=1)
+    desc = torch.empty(B.rlx_shared_prefix_bytes(model.handle, 4), dtype=torch.uint8, device="cuda:0")
+    B.rlx_shared_prefix_build(model.handle, [0, 0, 0, 3], [4, 4, 5, 0], desc)
+    hdr = desc[:32].view(torch.int32).cpu().numpy()
+    assert hdr[0] == 4 and hdr[2] == 8 and hdr[1] == 2           # one subgroup, one chunk of two units, two KV heads
+    start = desc[32:48].view(torch.int32).cpu().numpy()
+    assert list(start) == [2, 2, 2, 0]
+    for leader, pages in (([0, 2, 0, 3], [4, 4, 4, 0]), ([0, 0, 0, 3], [4, -1, 4, 0]), ([1, 0, 0, 3], [4, 4, 4, 0])):
+        with pytest.raises(B.RlxError) as e:
+            B.rlx_shared_prefix_build(model.handle, leader, pages, desc)
+        assert e.value.code == B.RLX_EINVAL
+    with pytest.raises(B.RlxError) as e:
+        B.rlx_shared_prefix_build(model.handle, [0, 0, 0, 3], [4, 4, 5, 0], desc[:64])
+    assert e.value.code == B.RLX_ENOMEM
+    model.close()
