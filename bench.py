@@ -7,6 +7,10 @@ sampling, state update).  Workloads (synthetic, seeded):
              1024 decoded tokens each (default)
   moe_b128   Qwen3-30B-A3B-shaped MoE policy, 128 sequences, 512-token prompts,
              2048 decoded tokens, routing indices captured
+  grouped_b256  the 4B shape with 32 prompts (uniform 512..2048) x 8 group members that share
+             their prompt's pages; the first 256 decode steps are timed (not the metric's
+             configuration: it measures decode attention over shared prefixes,
+             --no-shared-prefix for the per-sequence path)
 Prints ONE JSON line: decode tokens/s, ms/step, the roofline record of the dominant
 kernel (timed in situ with HIP events) and the CPU oracle timed on a bounded sample.
 """
@@ -171,7 +175,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="decode steps to time (0 = the whole decode phase)")
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="dense_b64", choices=["dense_b64", "moe_b128"])
+    ap.add_argument("--workload", default="dense_b64", choices=["dense_b64", "moe_b128", "grouped_b256"])
+    ap.add_argument("--no-shared-prefix", action="store_true",
+                    help="grouped_b256: read the shared prompt pages once per sequence instead of once per subgroup")
     ap.add_argument("--split", type=int, default=-1,
                     help="activation_split (default: 1 for bf16, two terms per activation; 0 for f16, one term)")
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"],
@@ -194,8 +200,14 @@ def main():
 
     B.lib()
     dev = "cuda:0"
+    grouped = args.workload == "grouped_b256"
     if args.workload == "dense_b64":
         shape, wl = RI.QWEN3_4B, RI.workload_dense_batch()
+    elif grouped:
+        shape, wl = RI.QWEN3_4B, RI.workload_grouped()
+        wl.n_decode[:] = 512                      # the bench times the first steps of the responses, uncapped
+        if args.steps <= 0:
+            args.steps = 256
     else:
         shape, wl = RI.QWEN3_30B_A3B, RI.workload_moe_batch()
     # the settings the parity tests at this shape pass with
@@ -214,10 +226,15 @@ def main():
     max_blocks = (int(plen.max()) + n_decode + 15) // 16 + 1
     n_blocks = int(sum((int(n) + n_decode + 15) // 16 for n in plen)) + 8
     chunk_budget = 8192
-    eng = pkg.RolloutEngine(model, n_blocks=n_blocks, max_seqs=bsz, max_chunk_tokens=chunk_budget,
+    leaders = sorted(set(int(g) for g in wl.group_of)) if grouped else []
+    if grouped:                                  # prompts are stored once per group
+        n_blocks = int(sum((int(plen[g]) + 15) // 16 for g in leaders)) + bsz * ((n_decode + 15) // 16 + 2) + 8
+    eng = pkg.RolloutEngine(model, n_blocks=n_blocks, max_seqs=bsz + len(leaders), max_chunk_tokens=chunk_budget,
                             max_blocks_per_seq=max_blocks)
-    for i in range(bsz):
-        eng.add_sequence(int(wl.seeds[i]), float(wl.temperature[i]), max_ctx=int(plen[i]) + n_decode)
+    eng.share_prefix_attention = not args.no_shared_prefix
+    if not grouped:
+        for i in range(bsz):
+            eng.add_sequence(int(wl.seeds[i]), float(wl.temperature[i]), max_ctx=int(plen[i]) + n_decode)
 
     if args.copy_probe:
         src = torch.ones(64 << 20, dtype=torch.float32, device=dev)      # 256 MiB read + 256 MiB written
@@ -229,19 +246,44 @@ def main():
     # ---- prefill (untimed for the metric; reported) ----
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    i = 0
-    while i < bsz:
-        j, tot = i, 0
-        while j < bsz and tot + int(plen[j]) <= chunk_budget:
-            tot += int(plen[j])
-            j += 1
-        eng.prefill(list(range(i, j)), wl.prompt_tokens[i:j])
-        i = j
+    shared_tok = np.zeros(bsz, np.int64)         # cached positions of each sequence that prefix tiles serve
+    shared_pages_tok = np.zeros(bsz, np.int64)   # cached positions of each sequence that lie in pages its group shares
+    pf_lens = plen                               # lengths of the sequences the prefill calls processed
+    if grouped:
+        # one donor row per prompt takes all but the last prompt token; the members fork from it (sharing its full
+        # pages) and prefill the last token themselves; the donors then leave the batch
+        donors, rows = {}, []
+        for g in leaders:                        # a group is a run of rows: donor, then its members
+            donors[g] = eng.add_sequence(0, reserve_tokens=int(plen[g]))
+            eng.prefill([donors[g]], [wl.prompt_tokens[g][:-1]], sample_last=[False])
+            for m in [k for k in range(bsz) if int(wl.group_of[k]) == g]:
+                rows.append((m, eng.fork(donors[g], int(wl.seeds[m]), float(wl.temperature[m]),
+                                         max_ctx=int(plen[m]) + n_decode)))
+        eng.prefill([r for _, r in rows], [wl.prompt_tokens[m][-1:] for m, _ in rows])
+        for g in leaders:
+            eng.finished[donors[g]] = 1
+        keep = eng.compact()
+        assert len(keep) == bsz and eng.n == bsz
+        # rows are now in group order; reorder the host-side lengths to match
+        pf_lens = np.array([int(plen[g]) - 1 for g in leaders])      # the members' single tokens are not counted
+        plen = np.array([plen[m] for m, _ in rows], dtype=plen.dtype)
+        shared_pages_tok[:] = [16 * ((int(n) - 1) // 16) for n in plen]
+        if eng.share_prefix_attention:
+            shared_tok[:] = [32 * ((int(n) - 1) // 32) for n in plen]
+    else:
+        i = 0
+        while i < bsz:
+            j, tot = i, 0
+            while j < bsz and tot + int(plen[j]) <= chunk_budget:
+                tot += int(plen[j])
+                j += 1
+            eng.prefill(list(range(i, j)), wl.prompt_tokens[i:j])
+            i = j
     torch.cuda.synchronize()
     t_prefill = time.perf_counter() - t0
     log("prefill: %d tokens in %.2f s (%.0f tok/s, %.0f TFLOP/s useful = %.1f%% of the bf16 MFMA peak)" % (
-        plen.sum(), t_prefill, plen.sum() / t_prefill, prefill_flops(shape, plen) / t_prefill / 1e12,
-        100 * prefill_flops(shape, plen) / t_prefill / 1e12 / 2500.0))
+        pf_lens.sum(), t_prefill, pf_lens.sum() / t_prefill, prefill_flops(shape, pf_lens) / t_prefill / 1e12,
+        100 * prefill_flops(shape, pf_lens) / t_prefill / 1e12 / 2500.0))
 
     total_steps = n_decode - 1
     K = args.steps if args.steps > 0 else total_steps - 0
@@ -268,6 +310,8 @@ def main():
     classes = ["qkv", "attn", "oproj", "gateup", "down", "lmhead", "norm", "rope", "attn_merge"]
     if shape.is_moe:
         classes += ["router", "group"]
+    if shared_tok.any():
+        classes += ["attn_prefix"]
     per_class = {}
     for cls in classes:
         kt = B.KernelTimer(cls, 4 * shape.n_layers, 1)
@@ -309,7 +353,8 @@ def main():
     ach_bytes = []
     for i in range(len(durs)):
         step = (i * stride) // launches_per_step
-        ach_bytes.append(kernel_bytes(shape, dom, int((ctx0 + step + 1).sum()), touched)
+        # the per-sequence attention kernel reads what the prefix tiles do not serve
+        ach_bytes.append(kernel_bytes(shape, dom, int((ctx0 + step + 1 - shared_tok).sum()), touched)
                          if dom in ("attn", "qkv", "oproj", "gateup", "down", "lmhead") else 0)
     # cost of an empty event pair on this stream (the brackets themselves), subtracted from every sample
     null_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(64)]
@@ -322,7 +367,11 @@ def main():
     achieved = float(np.sum(ach_bytes)) / (float(np.sum(durs)) * 1e-3) / 1e9 if durs else float("nan")
     ratio = traffic_record(args.workload, dom)
     traffic = None if ratio is None or not durs else ratio * float(np.mean(ach_bytes))
-    step_b = np.mean([step_bytes(shape, int((ctx0 + s + 1).sum()), bsz, touched) for s in range(K)])
+    # a page shared by the eight members of a group counts once (the strict algorithmic minimum; the prefix tiles
+    # read it once per subgroup of 16 / (n_q_heads / n_kv_heads) members); with no groups the two figures coincide
+    uniq = (ctx0 - shared_pages_tok).sum() + (shared_pages_tok.sum() // 8 if grouped else 0)
+    step_b = np.mean([step_bytes(shape, int(uniq + (s + 1) * bsz), bsz, touched) for s in range(K)])
+    step_b_logical = np.mean([step_bytes(shape, int((ctx0 + s + 1).sum()), bsz, touched) for s in range(K)])
     step_gbs = step_b / (ms_step * 1e-3) / 1e9
     fin = int(eng.finished[:bsz].sum().item())
     # every decode step this process ran (warmup, per-class timing, timed region) and the cached positions it
@@ -342,13 +391,15 @@ def main():
         "config": {"workload": "%s: %s, batch %d, prompts uniform %d..%d, %d decoded tokens, paged %s KV block 16, "
                                "temperature 1 Gumbel-max" % (args.workload, shape.name, bsz, plen.min(), plen.max(),
                                                               n_decode, args.dtype),
-                   "activation_split": split, "prefill_tokens_per_s": float(plen.sum() / t_prefill)},
+                   "activation_split": split, "prefill_tokens_per_s": float(pf_lens.sum() / t_prefill)},
         # the prefill chunks that filled the cache before the timed decode steps (MFMA-bound part of the path)
-        "prefill": {"tokens": int(plen.sum()), "seconds": t_prefill, "tokens_per_s": float(plen.sum() / t_prefill),
-                    "bound": "mfma", "achieved": prefill_flops(shape, plen) / t_prefill / 1e12, "peak": 2500.0,
-                    "unit": "TFLOP/s", "frac": prefill_flops(shape, plen) / t_prefill / 1e12 / 2500.0},
+        "prefill": {"tokens": int(pf_lens.sum()), "seconds": t_prefill, "tokens_per_s": float(pf_lens.sum() / t_prefill),
+                    "bound": "mfma", "achieved": prefill_flops(shape, pf_lens) / t_prefill / 1e12, "peak": 2500.0,
+                    "unit": "TFLOP/s", "frac": prefill_flops(shape, pf_lens) / t_prefill / 1e12 / 2500.0},
         "step_roofline": {"bound": "hbm", "achieved": step_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                          "frac": step_gbs / HBM_PEAK_GBS, "bytes_per_step": float(step_b)},
+                          "frac": step_gbs / HBM_PEAK_GBS, "bytes_per_step": float(step_b),
+                          "bytes_per_step_per_sequence_kv": float(step_b_logical),
+                          "frac_per_sequence_kv": step_b_logical / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "avg_launch_ms": kern_ms,
                      "bytes_per_launch": float(np.mean(ach_bytes)) if durs else None,
