@@ -149,6 +149,34 @@ def test_group_decode_over_shared_prefix_matches_oracle(amd, shape_name):
     assert dl <= LOGIT_BAR and dp <= LOGPROB_BAR
 
 
+def test_descriptor_of_another_batch_size_is_ignored(amd):
+    """A descriptor built for a different number of rows must not be applied: the step then equals the plain one."""
+    pkg, synthetic = amd
+    B = pkg.binding
+    shape = RI.TINY_DENSE
+    prompt = _prompts(shape)[0]
+    outs = []
+    for stale in (False, True):
+        model = synthetic.model_from_shape(shape, 0, activation_split=1)
+        eng = pkg.RolloutEngine(model, n_blocks=64, max_seqs=8, max_chunk_tokens=256, max_blocks_per_seq=12)
+        d = eng.add_sequence(0, reserve_tokens=len(prompt))
+        eng.prefill([d], [prompt[:-1]], sample_last=[False])
+        kids = [eng.fork(d, 40 + k, reserve_tokens=len(prompt) + 8) for k in range(3)]
+        eng.finished[d] = 1
+        eng.prefill(kids, [prompt[-1:]] * 3)
+        eng.share_prefix_attention = False
+        if stale:   # a descriptor for 6 rows that claims four shared pages for everyone, passed to a 4-row step
+            desc = torch.empty(B.rlx_shared_prefix_bytes(model.handle, 6), dtype=torch.uint8, device="cuda:0")
+            B.rlx_shared_prefix_build(model.handle, [0] * 6, [4] * 6, desc)
+            eng._shared_prefix = lambda: desc
+        z = []
+        for _ in range(3):
+            z.append(eng.decode_step(want_logits=True).logits.cpu().numpy().copy())
+        outs.append(np.stack(z))
+        model.close()
+    np.testing.assert_array_equal(outs[0], outs[1])
+
+
 def test_shared_prefix_descriptor_validation(amd):
     pkg, synthetic = amd
     B = pkg.binding
