@@ -15,10 +15,13 @@ import rollout_inputs as RI
 pytestmark = pytest.mark.gpu
 
 LOGIT_BAR, LOGPROB_BAR, TIE_GAP = 0.05, 0.02, 1e-3
-N_STEPS, COMPACT_AT = 40, 9
+COMPACT_AT = 9
 # (prompt length, members): 4 and 8 shared pages, 2 shared pages (one unit), 1 shared page (nothing to share),
-# then two sequences on their own
-GROUPS = [(75, 5), (130, 3), (33, 2), (20, 2), (50, 1), (9, 1)]
+# then two sequences on their own; 40 steps
+SHORT = ([(75, 5), (130, 3), (33, 2), (20, 2), (50, 1), (9, 1)], 40)
+# prefixes of 19 and 9 units: several chunks per subgroup (a chunk is at least eight units), more than one subgroup
+# at the MoE shape's two members per tile; 12 steps
+LONG = ([(620, 3), (300, 2), (40, 1)], 12)
 
 
 def say(msg):
@@ -34,12 +37,12 @@ def amd():
     return pkg, synthetic
 
 
-def _prompts(shape):
+def _prompts(shape, GROUPS):
     g = np.random.default_rng(5)
     return [g.integers(0, shape.vocab - 2, size=n).astype(np.int32) for n, _ in GROUPS]
 
 
-def _oracle(shape, prompts, forced, replay):
+def _oracle(shape, prompts, forced, replay, GROUPS, N_STEPS):
     """One oracle sequence per group member (no sharing); returns per step the result dict."""
     om = O.OracleModel(shape, 0)
     n = sum(m for _, m in GROUPS)
@@ -57,12 +60,13 @@ def _oracle(shape, prompts, forced, replay):
     return steps
 
 
-def _gpu(pkg, synthetic, shape, prompts, forced, share):
+def _gpu(pkg, synthetic, shape, prompts, forced, share, GROUPS, N_STEPS):
     """Donor row per group (prompt minus its last token, never sampled), members forked from it; donors are dropped
     by a compaction after COMPACT_AT steps.  Returns per step (logits, logprobs, routing) in member order."""
     model = synthetic.model_from_shape(shape, 0, activation_split=1)
     n_rows = sum(m + (1 if m > 1 else 0) for _, m in GROUPS)
-    eng = pkg.RolloutEngine(model, n_blocks=n_rows * 12, max_seqs=n_rows, max_chunk_tokens=512, max_blocks_per_seq=12)
+    mb = (max(p for p, _ in GROUPS) + N_STEPS) // 16 + 2
+    eng = pkg.RolloutEngine(model, n_blocks=n_rows * mb, max_seqs=n_rows, max_chunk_tokens=1024, max_blocks_per_seq=mb)
     eng.share_prefix_attention = share
     member_rows, donors, donor_rt = [], [], []
     for gi, (plen, mem) in enumerate(GROUPS):
@@ -109,29 +113,37 @@ def _gpu(pkg, synthetic, shape, prompts, forced, share):
     return steps, n_tiles
 
 
-@pytest.mark.parametrize("shape_name", ["tiny_dense", "tiny_moe"])
-def test_group_decode_over_shared_prefix_matches_oracle(amd, shape_name):
+@pytest.mark.parametrize("shape_name,case", [("tiny_dense", "short"), ("tiny_moe", "short"), ("tiny_dense", "long"),
+                                             ("tiny_moe", "long")])
+def test_group_decode_over_shared_prefix_matches_oracle(amd, shape_name, case):
     pkg, synthetic = amd
     shape = {"tiny_dense": RI.TINY_DENSE, "tiny_moe": RI.TINY_MOE}[shape_name]
-    prompts = _prompts(shape)
-    say("%s: oracle free run, one sequence per member" % shape.name)
-    osteps = _oracle(shape, prompts, None, None)
+    GROUPS, N_STEPS = SHORT if case == "short" else LONG
+    prompts = _prompts(shape, GROUPS)
+    say("%s %s: oracle free run, one sequence per member" % (shape.name, case))
+    osteps = _oracle(shape, prompts, None, None, GROUPS, N_STEPS)
     forced = [st["tokens"] for st in osteps]
     say("%s: gpu with prefix tiles" % shape.name)
-    gs, tiles = _gpu(pkg, synthetic, shape, prompts, forced, share=True)
+    gs, tiles = _gpu(pkg, synthetic, shape, prompts, forced, True, GROUPS, N_STEPS)
     say("%s: gpu without" % shape.name)
-    gu, tiles_u = _gpu(pkg, synthetic, shape, prompts, forced, share=False)
+    gu, tiles_u = _gpu(pkg, synthetic, shape, prompts, forced, False, GROUPS, N_STEPS)
     ms = 16 // (shape.n_q_heads // shape.n_kv_heads)
-    # groups 0..2 share at least one unit: subgroups x chunks x KV heads tiles, before and after the compaction
-    sub_before = sum((m + 1 + ms - 1) // ms for (p, m) in GROUPS[:3])
-    sub_after = sum((m + ms - 1) // ms for (p, m) in GROUPS[:3])
-    assert tiles[0] >= sub_before * shape.n_kv_heads and tiles[-1] >= sub_after * shape.n_kv_heads, tiles
+    # tiles = subgroups x chunks x KV heads over the groups that share at least one unit (donor included until the
+    # compaction); a chunk holds at least eight units and a subgroup has at most four
+    def n_tiles(extra):
+        n = 0
+        for p, m in GROUPS:
+            units = ((p - 1) // 16) // 2
+            if m > 1 and units > 0:
+                n += ((m + extra + ms - 1) // ms) * min(4, (units + 7) // 8) * shape.n_kv_heads
+        return n
+    assert tiles[0] == n_tiles(1) and tiles[-1] == n_tiles(0), (tiles[0], tiles[-1], n_tiles(1), n_tiles(0))
     assert set(tiles_u) == {0}
     d_paths = max(float(np.abs(a[0] - b[0]).max()) for a, b in zip(gs, gu))
     say("%s: prefix tiles per step %d -> %d; shared vs unshared max |dlogit| %.2e" % (shape.name, tiles[0], tiles[-1], d_paths))
     assert d_paths <= 2e-3                                      # the order of the softmax merges is all that differs
     if shape.is_moe:   # replay the GPU's routing so that a tolerated near-tie does not hide what follows
-        osteps = _oracle(shape, prompts, forced, [g[2] for g in gs])
+        osteps = _oracle(shape, prompts, forced, [g[2] for g in gs], GROUPS, N_STEPS)
         flips = routes = 0
         for g, o in zip(gs, osteps):
             for j in range(len(g[2])):
@@ -154,7 +166,7 @@ def test_descriptor_of_another_batch_size_is_ignored(amd):
     pkg, synthetic = amd
     B = pkg.binding
     shape = RI.TINY_DENSE
-    prompt = _prompts(shape)[0]
+    prompt = _prompts(shape, SHORT[0])[0]
     outs = []
     for stale in (False, True):
         model = synthetic.model_from_shape(shape, 0, activation_split=1)
