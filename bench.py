@@ -2,7 +2,7 @@
 """Rollout-decode benchmark on one MI355X.
 
 A "step" is one rollout_decode_step over the whole batch (all layers, LM head,
-sampling, state update).  Workloads (synthetic, seeded; see DESIGN.md):
+sampling, state update).  Workloads (synthetic, seeded):
   dense_b64  Qwen3-4B-shaped dense policy, 64 sequences, prompts uniform 256..1024,
              1024 decoded tokens each (default)
   moe_b128   Qwen3-30B-A3B-shaped MoE policy, 128 sequences, 512-token prompts,
