@@ -188,7 +188,7 @@ def main():
                     help="also run one 256 MiB device copy (reference of known size for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+        print("bench.py: the library runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
 
