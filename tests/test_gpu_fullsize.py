@@ -126,6 +126,66 @@ def test_dense_4b_shape_batch64_sampled_rows_fp16():
     _run_case(shape, wl, split=0, n_steps=3, sample_rows=rows, fmt="f16")
 
 
+def test_dense_4b_shape_sampling_groups_shared_prefix_sampled_rows():
+    """Decode over shared prompt pages at the 4B shape (head_dim 128, four members per prefix tile, several chunks
+    per prefix): two prompts x 8 group members, the tokens the GPU emits checked by the oracle's full forward of two
+    members (no sharing on the oracle's side)."""
+    import paper_2604_11554_amd as pkg
+    from paper_2604_11554_amd import synthetic
+    pkg.binding.lib()
+    shape = RI.QWEN3_4B
+    n_steps, lens, members = 3, (700, 333), 8
+    g = np.random.default_rng(21)
+    prompts = [g.integers(0, shape.vocab - 2, size=n).astype(np.int32) for n in lens]
+    say("generating %s weights on the host" % shape.name)
+    tensors = synthetic.generate_tensors(shape, 0, threads=12, progress=lambda i, n: say("  tensor %d/%d" % (i, n)))
+    model = synthetic.model_from_tensors(shape, tensors, activation_split=1)
+    mb = (max(lens) + n_steps + 16) // 16 + 1
+    n_rows = len(lens) * (members + 1)
+    eng = pkg.RolloutEngine(model, n_blocks=n_rows * mb, max_seqs=n_rows, max_chunk_tokens=1024, max_blocks_per_seq=mb)
+    rows, seeds = [], []
+    for gi, p in enumerate(prompts):
+        d = eng.add_sequence(0, reserve_tokens=len(p))
+        eng.prefill([d], [p[:-1]], sample_last=[False])
+        for k in range(members):
+            seeds.append(7000 + 10 * gi + k)
+            rows.append(eng.fork(d, seeds[-1], reserve_tokens=len(p) + n_steps + 8))
+        eng.finished[d] = 1
+    o = eng.prefill(rows, [prompts[i // members][-1:] for i in range(len(rows))], want_logits=True)
+    torch.cuda.synchronize()
+    keep = eng.compact()                                      # the donors leave; groups are runs of 8 rows
+    assert eng.n == len(rows)
+    desc = eng._shared_prefix()
+    n_tiles = int(desc[:8].view(torch.int32)[1].item())
+    # 21 and 10 shared units: 3 and 2 chunks x 2 subgroups of four members x 8 KV heads
+    assert n_tiles == (3 + 2) * 2 * shape.n_kv_heads, n_tiles
+    sample = [3, members + 6]                                 # a member of each group
+    got = {r: [(int(o.tokens[r]), float(o.logprobs[r]), o.logits[r].cpu().numpy())] for r in sample}
+    for s in range(n_steps):
+        o = eng.decode_step(want_logits=True)
+        torch.cuda.synchronize()
+        for r in sample:
+            got[r].append((int(o.tokens[r]), float(o.logprobs[r]), o.logits[r].cpu().numpy()))
+        say("decode step %d done" % s)
+    om = O.OracleModel(shape, 0, cache_layers=False, tensors=tensors)
+    seqs = [np.concatenate([prompts[r // members], [t for t, _, _ in got[r][:-1]]]).astype(np.int32) for r in sample]
+    at = [np.arange(lens[r // members] - 1, lens[r // members] + n_steps) for r in sample]
+    say("oracle forward of the two sampled members (%s tokens)" % [len(q) for q in seqs])
+    res = O.forward_full(om, seqs, logits_at=at, progress=lambda l: say("  oracle layer %d" % l))
+    dl = dp = 0.0
+    for k, r in enumerate(sample):
+        z_o = res[k]["logits"]
+        lp_o = O.log_softmax(z_o)
+        for p, (tok, lp, z) in enumerate(got[r]):
+            dl = max(dl, float(np.abs(z - z_o[p]).max()))
+            dp = max(dp, abs(lp - float(lp_o[p, tok])))
+            sc = z_o[p].astype(np.float64) + O.gumbel_noise(seeds[r], lens[r // members] + p, shape.vocab)
+            assert sc[tok] >= sc.max() - 2 * LOGIT_BAR, "row %d step %d: bad draw" % (r, p)
+    say("%s shared prefixes: max |dlogit| %.5f, max |dlogprob| %.5f" % (shape.name, dl, dp))
+    assert dl <= LOGIT_BAR and dp <= LOGPROB_BAR
+    model.close()
+
+
 def test_moe_30b_a3b_layer_slice_batch128_sampled_rows():
     shape = RI.QWEN3_30B_A3B.replace(name="qwen3_30b_a3b_shape_2layers", n_layers=2)
     wl = RI.workload_moe_batch(shape, prompt_len=128)         # 128 sequences, all experts touched every step
