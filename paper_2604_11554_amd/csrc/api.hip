@@ -71,7 +71,7 @@ namespace {
 struct Workspace {
   TokenMeta meta;
   float* h;          // [T, d]
-  h16_t* xb;        // [planes][T, d]; every bf16 activation buffer below has `planes` copies
+  h16_t* xb;        // [planes][T, d]; every 16-bit activation buffer below has `planes` copies
   float* router;     // [planes][T, E] router logits (MoE)
   float* qkv;        // [planes][T, qkv_dim]
   h16_t* q;         // [T, q_dim]

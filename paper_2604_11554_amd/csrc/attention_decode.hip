@@ -1,4 +1,4 @@
-// Decode attention over the paged bf16 KV pool, load-balanced by key count.
+// Decode attention over the paged 16-bit KV pool, load-balanced by key count.
 //
 // One new token per sequence; the 16 MFMA columns of a tile are the query heads of one KV head
 // (group <= 16), so a KV page is read once for all heads of its group.  The work of a step is the

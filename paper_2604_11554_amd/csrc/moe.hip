@@ -1,4 +1,4 @@
-// MoE routing: router logits come from the skinny GEMM (activations as two bf16 terms, fp32
+// MoE routing: router logits come from the skinny GEMM (activations as one or two 16-bit terms, fp32
 // accumulate, split-K planes); here: softmax top-k with renormalised weights,
 // capture of the chosen expert ids (the record Rollout Routing Replay consumes,
 // paper Sec. 5.5), and a stable, deterministic grouping of (token, slot) pairs by expert.

@@ -299,7 +299,7 @@ class RolloutEngine:
     def prefill(self, rows: Sequence[int], toks: Sequence[np.ndarray], embeds: Sequence[Optional[np.ndarray]] = None,
                 sample_last: Sequence[bool] = None, forced: Sequence[int] = None, want_logits=False,
                 want_routing=False, want_sampled=False) -> StepOutput:
-        """Append one chunk per listed row.  embeds[j]: bf16 bits [len(toks[j]), d] aligned with the
+        """Append one chunk per listed row.  embeds[j]: bit patterns of the model dtype [len(toks[j]), d] aligned with the
         chunk's positions (rows read only where the token id is -1), or None."""
         dev = self.m.device
         n = len(rows)
