@@ -203,7 +203,7 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
     wqkv.seg[1] = m->wk[l]; wqkv.rows[1] = kvdim;
     wqkv.seg[2] = m->wv[l]; wqkv.rows[2] = kvdim;
     wqkv.N = qkv_dim; wqkv.K = d;
-    const int s_qkv = small ? gemm_plan_splits(qkv_dim, d, gemm_max_splits(), m->n_units) : 1;
+    const int s_qkv = small ? gemm_plan_splits(qkv_dim, d, T, gemm_max_splits(), m->n_units) : 1;
     RLX_LAUNCH(RLX_K_QKV, gemm_store(wqkv, xb, T, w.qkv, qkv_dim, s_qkv, st));
 
     h16_t* pool_layer = pool + (size_t)l * n_blocks * block_elems(c);
@@ -238,7 +238,7 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
       RLX_LAUNCH(RLX_K_ATTN, attention_prefill(at, st));
     }
 
-    const int s_o = small ? gemm_plan_splits(d, qdim, gemm_max_splits(), m->n_units) : 1;
+    const int s_o = small ? gemm_plan_splits(d, qdim, T, gemm_max_splits(), m->n_units) : 1;
     RLX_LAUNCH(RLX_K_OPROJ, gemm_store(linear1(m->wo[l], d, qdim), ob, T, w.planes, d, s_o, st));
     pend_planes = w.planes; pend_n = s_o;
 
@@ -246,11 +246,11 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
     if (c.n_experts == 0) {
       const Act act = make_act(w.act, T, c.d_ff, PL, FMT);
       RLX_LAUNCH(RLX_K_GATEUP, gemm_swiglu(m->w_gate_up[l], c.d_ff, d, xb, T, act, st));
-      const int s_d = small ? gemm_plan_splits(d, c.d_ff, gemm_max_splits(), m->n_units) : 1;
+      const int s_d = small ? gemm_plan_splits(d, c.d_ff, T, gemm_max_splits(), m->n_units) : 1;
       RLX_LAUNCH(RLX_K_DOWN, gemm_store(linear1(m->w_down[l], d, c.d_ff), act, T, w.planes, d, s_d, st));
       pend_planes = w.planes; pend_n = s_d;
     } else {
-      const int s_r = small ? gemm_plan_splits(c.n_experts, d, gemm_max_splits(), m->n_units) : 1;
+      const int s_r = small ? gemm_plan_splits(c.n_experts, d, T, gemm_max_splits(), m->n_units) : 1;
       RLX_LAUNCH(RLX_K_ROUTER, gemm_store(linear1(m->w_router[l], c.n_experts, d), xb, T, w.router, c.n_experts, s_r, st));
       RouterArgs ra = {};
       ra.logits = w.router; ra.n_planes = s_r; ra.T = T; ra.E = c.n_experts; ra.top_k = c.top_k;
@@ -406,6 +406,7 @@ int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* wt, rlx_mod
   int n_cu = 0;
   if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, m->device);
   m->n_units = n_cu > 0 ? n_cu : 1;
+  gemm_set_units(m->n_units);
   m->attn_wgs = 2 * n_cu < ATTN_WGS_MAX ? (2 * n_cu > 0 ? 2 * n_cu : 1) : ATTN_WGS_MAX;
   if (e == hipSuccess) e = hipMalloc((void**)&m->inv_freq, inv.size() * sizeof(double));
   if (e == hipSuccess) e = hipMemcpy(m->inv_freq, inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice);
@@ -653,7 +654,7 @@ int rlx_op_linear(const void* x, const void* w, float* y, int32_t n_tokens, int3
   int dev = 0, n_units = 0;
   RLX_HIP(hipGetDevice(&dev));
   RLX_HIP(hipDeviceGetAttribute(&n_units, hipDeviceAttributeMultiprocessorCount, dev));
-  const int splits = n_tokens <= 256 ? gemm_plan_splits(n, k, gemm_max_splits(), n_units > 0 ? n_units : 1) : 1;
+  const int splits = n_tokens <= 256 ? gemm_plan_splits(n, k, n_tokens, gemm_max_splits(), n_units > 0 ? n_units : 1) : 1;
   hipStream_t st = (hipStream_t)stream;
   const size_t xb = align_up(frag_act_elems(n_tokens, k, 1) * 2);
   const size_t pb = splits > 1 ? align_up((size_t)splits * n_tokens * n * 4) : 0;

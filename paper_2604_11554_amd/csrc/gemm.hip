@@ -79,6 +79,124 @@ __device__ __forceinline__ float gumbel_from_u32(uint32_t r) {
   return -logf(nl);
 }
 
+// Epilogue of one 32-row weight tile `nt` over token tiles mt0 .. mt0 + MT - 1: lane holds token r32 of each token
+// tile, rows n0 + 8q + 4*half + {0..3}, q = 0..3, of the accumulators.
+template <int MT, int EPI, int PL, int FMT>
+__device__ __forceinline__ void tile_epilogue(const GemmArgs& a, const f32x16 (&acc)[MT], int nt, int n_tiles, int mt0,
+                                              int split, int row_base, int lane) {
+  const int r32 = lane & 31, half = lane >> 5;
+  const int n0 = nt * 32;
+  if (EPI == EPI_STORE) {
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+      const int t = (mt0 + m) * 32 + r32;
+      if (t >= a.T) continue;
+      float* dst = a.y + ((size_t)split * a.T + row_base + t) * a.ldy;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int nrow = n0 + 8 * q + 4 * half;
+        f32x4 v = {acc[m][4 * q], acc[m][4 * q + 1], acc[m][4 * q + 2], acc[m][4 * q + 3]};
+        if (nrow + 3 < a.N) {
+          *reinterpret_cast<f32x4*>(dst + nrow) = v;
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (nrow + j < a.N) dst[nrow + j] = v[j];
+        }
+      }
+    }
+  } else if (EPI == EPI_SWIGLU) {
+    // The packed matrix interleaves gate and up: rows 0..15 of a tile are gate rows of features
+    // 16 nt .. 16 nt + 15, rows 16..31 the matching up rows, so a lane holds both halves of a pair
+    // (register groups q and q + 2).  The output feature is the K index of the down projection.
+    const int n_feat = a.N >> 1;
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+      const int t = (mt0 + m) * 32 + r32;
+      if (t >= a.T) continue;
+      const int orow = row_base + t;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int feat = nt * 16 + 8 * q + 4 * half;   // four consecutive features inside one 8-group
+        if (feat >= n_feat) continue;
+        h16_t hi[4], lo[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float g = acc[m][4 * q + j], u = acc[m][4 * (q + 2) + j];
+          split_h16<FMT>(g / (1.f + __expf(-g)) * u, hi[j], lo[j]);
+        }
+        h16_t* dst = a.act + frag_act_offset(orow, feat & ~7, 0, a.act_mtiles, PL) + (feat & 7);
+        u32x2 pk = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
+        *reinterpret_cast<u32x2*>(dst) = pk;
+        if (PL == 2) {
+          u32x2 pk2 = {(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
+          *reinterpret_cast<u32x2*>(dst + 512) = pk2;
+        }
+      }
+    }
+  } else {  // EPI_LMHEAD: per token, reduce this tile's 32 vocabulary rows to (max, sumexp, best, argbest)
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+      const int t = (mt0 + m) * 32 + r32;
+      const bool ok = t < a.T;
+      float mx = -INFINITY, se = 0.f, best = -INFINITY;
+      int besti = 0x7FFFFFFF;
+      if (ok) {
+        const float temp = a.temperature[a.row_seq ? a.row_seq[t] : t];
+        const float invt = temp > 0.f ? 1.f / temp : 1.f;
+        const bool draw = a.draw != 0 && temp > 0.f;          // uniform over the launch when draw == 0
+        const uint64_t seed = a.draw ? a.seeds[t] : 0;
+        const uint32_t pos = a.draw ? (uint32_t)a.sample_pos[t] : 0u;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int nrow = n0 + 8 * q + 4 * half;  // multiple of 4: one Philox block covers the four ids
+          if (nrow >= a.N) continue;
+          uint32_t rnd[4] = {0u, 0u, 0u, 0u};
+          if (a.draw) philox4x32_10((uint32_t)(nrow >> 2), pos, 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32), rnd);
+          f32x4 v = {acc[m][4 * q], acc[m][4 * q + 1], acc[m][4 * q + 2], acc[m][4 * q + 3]};
+          if (a.logits) {
+            if (nrow + 3 < a.N) {
+              *reinterpret_cast<f32x4*>(a.logits + (size_t)t * a.N + nrow) = v;
+            } else {
+#pragma unroll
+              for (int j = 0; j < 4; ++j)
+                if (nrow + j < a.N) a.logits[(size_t)t * a.N + nrow + j] = v[j];
+            }
+          }
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            if (nrow + j < a.N) {
+              const float z = v[j] * invt;
+              const float sc = draw ? z + gumbel_from_u32(rnd[j]) : z;
+              if (sc > best) { best = sc; besti = nrow + j; }   // ascending ids: ties keep the smaller one
+              const float nm = fmaxf(mx, z);
+              se = se * __expf(mx - nm) + __expf(z - nm);
+              mx = nm;
+            }
+          }
+        }
+      }
+      // merge the two half-waves (rows 8q+0..3 and 8q+4..7) of the same token
+      const float omx = __shfl_xor(mx, 32, WAVE), ose = __shfl_xor(se, 32, WAVE);
+      const float obest = __shfl_xor(best, 32, WAVE);
+      const int obesti = __shfl_xor(besti, 32, WAVE);
+      if (obest > best || (obest == best && obesti < besti)) { best = obest; besti = obesti; }
+      const float nm = fmaxf(mx, omx);
+      if (nm > -INFINITY) {
+        // fixed operand order (lower half first) so both half-waves compute the same bits
+        const float lo_m = half ? omx : mx, lo_s = half ? ose : se, hi_m = half ? mx : omx, hi_s = half ? se : ose;
+        se = lo_s * (lo_m == -INFINITY ? 0.f : __expf(lo_m - nm)) + hi_s * (hi_m == -INFINITY ? 0.f : __expf(hi_m - nm));
+        mx = nm;
+      }
+      if (ok && half == 0) {
+        float* o = a.part + ((size_t)t * n_tiles + nt) * 4;
+        f32x4 pv = {mx, se, best, __int_as_float(besti)};
+        *reinterpret_cast<f32x4*>(o) = pv;
+      }
+    }
+  }
+}
+
 template <int MT, int PL>
 struct Tiling {
   static constexpr int KC = (32 / (MT * PL)) > 16 ? 16 : (32 / (MT * PL));  // k-steps per LDS chunk
@@ -257,118 +375,168 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
     }
   }
   if (!have_tile) return;
+  tile_epilogue<MT, EPI, PL, FMT>(a, acc, nt, n_tiles, mt0, split, row_base, lane);
+}
 
-  // ---- epilogue: lane holds token r32 of each tile, rows n0 + 8q + 4*half + {0..3}, q = 0..3 ----
-  const int n0 = nt * 32;
-  if (EPI == EPI_STORE) {
-#pragma unroll
-    for (int m = 0; m < MT; ++m) {
-      const int t = (mt0 + m) * 32 + r32;
-      if (t >= a.T) continue;
-      float* dst = a.y + ((size_t)split * a.T + row_base + t) * a.ldy;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int nrow = n0 + 8 * q + 4 * half;
-        f32x4 v = {acc[m][4 * q], acc[m][4 * q + 1], acc[m][4 * q + 2], acc[m][4 * q + 3]};
-        if (nrow + 3 < a.N) {
-          *reinterpret_cast<f32x4*>(dst + nrow) = v;
-        } else {
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            if (nrow + j < a.N) dst[nrow + j] = v[j];
-        }
-      }
-    }
-  } else if (EPI == EPI_SWIGLU) {
-    // The packed matrix interleaves gate and up: rows 0..15 of a tile are gate rows of features
-    // 16 nt .. 16 nt + 15, rows 16..31 the matching up rows, so a lane holds both halves of a pair
-    // (register groups q and q + 2).  The output feature is the K index of the down projection.
-    const int n_feat = a.N >> 1;
-#pragma unroll
-    for (int m = 0; m < MT; ++m) {
-      const int t = (mt0 + m) * 32 + r32;
-      if (t >= a.T) continue;
-      const int orow = row_base + t;
-#pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        const int feat = nt * 16 + 8 * q + 4 * half;   // four consecutive features inside one 8-group
-        if (feat >= n_feat) continue;
-        h16_t hi[4], lo[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          float g = acc[m][4 * q + j], u = acc[m][4 * (q + 2) + j];
-          split_h16<FMT>(g / (1.f + __expf(-g)) * u, hi[j], lo[j]);
-        }
-        h16_t* dst = a.act + frag_act_offset(orow, feat & ~7, 0, a.act_mtiles, PL) + (feat & 7);
-        u32x2 pk = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
-        *reinterpret_cast<u32x2*>(dst) = pk;
-        if (PL == 2) {
-          u32x2 pk2 = {(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
-          *reinterpret_cast<u32x2*>(dst + 512) = pk2;
-        }
-      }
-    }
-  } else {  // EPI_LMHEAD: per token, reduce this tile's 32 vocabulary rows to (max, sumexp, best, argbest)
-#pragma unroll
-    for (int m = 0; m < MT; ++m) {
-      const int t = (mt0 + m) * 32 + r32;
-      const bool ok = t < a.T;
-      float mx = -INFINITY, se = 0.f, best = -INFINITY;
-      int besti = 0x7FFFFFFF;
-      if (ok) {
-        const float temp = a.temperature[a.row_seq ? a.row_seq[t] : t];
-        const float invt = temp > 0.f ? 1.f / temp : 1.f;
-        const bool draw = a.draw != 0 && temp > 0.f;          // uniform over the launch when draw == 0
-        const uint64_t seed = a.draw ? a.seeds[t] : 0;
-        const uint32_t pos = a.draw ? (uint32_t)a.sample_pos[t] : 0u;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int nrow = n0 + 8 * q + 4 * half;  // multiple of 4: one Philox block covers the four ids
-          if (nrow >= a.N) continue;
-          uint32_t rnd[4] = {0u, 0u, 0u, 0u};
-          if (a.draw) philox4x32_10((uint32_t)(nrow >> 2), pos, 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32), rnd);
-          f32x4 v = {acc[m][4 * q], acc[m][4 * q + 1], acc[m][4 * q + 2], acc[m][4 * q + 3]};
-          if (a.logits) {
-            if (nrow + 3 < a.N) {
-              *reinterpret_cast<f32x4*>(a.logits + (size_t)t * a.N + nrow) = v;
-            } else {
-#pragma unroll
-              for (int j = 0; j < 4; ++j)
-                if (nrow + j < a.N) a.logits[(size_t)t * a.N + nrow + j] = v[j];
-            }
-          }
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            if (nrow + j < a.N) {
-              const float z = v[j] * invt;
-              const float sc = draw ? z + gumbel_from_u32(rnd[j]) : z;
-              if (sc > best) { best = sc; besti = nrow + j; }   // ascending ids: ties keep the smaller one
-              const float nm = fmaxf(mx, z);
-              se = se * __expf(mx - nm) + __expf(z - nm);
-              mx = nm;
-            }
-          }
-        }
-      }
-      // merge the two half-waves (rows 8q+0..3 and 8q+4..7) of the same token
-      const float omx = __shfl_xor(mx, 32, WAVE), ose = __shfl_xor(se, 32, WAVE);
-      const float obest = __shfl_xor(best, 32, WAVE);
-      const int obesti = __shfl_xor(besti, 32, WAVE);
-      if (obest > best || (obest == best && obesti < besti)) { best = obest; besti = obesti; }
-      const float nm = fmaxf(mx, omx);
-      if (nm > -INFINITY) {
-        // fixed operand order (lower half first) so both half-waves compute the same bits
-        const float lo_m = half ? omx : mx, lo_s = half ? ose : se, hi_m = half ? mx : omx, hi_s = half ? se : ose;
-        se = lo_s * (lo_m == -INFINITY ? 0.f : __expf(lo_m - nm)) + hi_s * (hi_m == -INFINITY ? 0.f : __expf(hi_m - nm));
-        mx = nm;
-      }
-      if (ok && half == 0) {
-        float* o = a.part + ((size_t)t * n_tiles + nt) * 4;
-        f32x4 pv = {mx, se, best, __int_as_float(besti)};
-        *reinterpret_cast<f32x4*>(o) = pv;
-      }
-    }
+// ---- large-batch form (more than 128 tokens): 256 weight rows x 256 tokens per workgroup of eight waves ----
+// With 128-token tiles and one weight tile per wave every compute unit takes in 12 KB per k-step for 32 multiplies;
+// here both operands pass through LDS (each weight fragment feeds the two token halves, each activation fragment the
+// four row groups), 24 KB per k-step feed 128 multiplies, and two waves per SIMD hide each other's LDS latency.
+// Wave w = (row group w & 3: weight tiles 2 (w & 3) + {0, 1}; token half w >> 2: token tiles 4 (w >> 2) + {0..3}).
+// Per accumulator the order is the same as in the skinny form (k ascending, small activation term first), so both
+// forms give the same bits.
+constexpr int LG_WAVES = 8, LG_THREADS = LG_WAVES * WAVE, LG_TILES = 8, LG_KC = 2;
+
+template <int PL>
+struct LargeTiling {
+  static constexpr int WFR = LG_KC * LG_TILES;          // weight fragments per stage
+  static constexpr int XFR = LG_KC * LG_TILES * PL;     // activation fragments per stage
+  static constexpr int STAGE = WFR + XFR;
+  static constexpr int LDS_BYTES = 2 * STAGE * 1024;
+};
+
+template <int EPI, int PL, int FMT>
+__global__ __launch_bounds__(LG_THREADS) void gemm_large_kernel(GemmArgs a) {
+  using TL = LargeTiling<PL>;
+  constexpr int KC = LG_KC, WFR = TL::WFR, STAGE = TL::STAGE;
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  u32x4* lds = reinterpret_cast<u32x4*>(lds_raw);   // [2][STAGE][64 lanes]
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r32 = lane & 31, half = lane >> 5;
+  const int wr = wave & 3, wt = wave >> 2;
+  const int mt_base = blockIdx.z * LG_TILES;
+  int split = blockIdx.y;
+  int row_base = 0;
+  const bool grouped = a.group_off != nullptr;
+  if (grouped) {
+    const int e = blockIdx.y;
+    row_base = a.group_off[e];
+    a.T = a.group_off[e + 1] - row_base;
+    if (mt_base * 32 >= a.T) return;                // uniform over the workgroup, before any barrier
+    a.w[0] += (size_t)e * a.w_expert_stride;
+    split = 0;
   }
+  const int KS = a.K >> 4;
+  const int n_tiles = (a.N + 31) >> 5;
+  const int nt_base = blockIdx.x * LG_TILES;
+
+  // ---- staging duties: wave w copies weight tile nt_base + w and token tile mt_base + w of every stage ----
+  const h16_t* wp;
+  int w_kstride = 512;
+  {
+    int lt = nt_base + wave;
+    if (lt >= n_tiles) { lt = 0; w_kstride = 0; }   // no such tile: one cached block, its products are never stored
+    const h16_t* base = a.w[0];
+    if (lt >= a.w_tiles[0]) {
+      lt -= a.w_tiles[0];
+      base = a.w[1];
+      if (lt >= a.w_tiles[1]) { lt -= a.w_tiles[1]; base = a.w[2]; }
+    }
+    wp = base + (size_t)lt * KS * 512 + lane * 8;
+  }
+  // a token row past the end reads row 0 / tile 0: a token's row only reaches its own outputs, which are not stored
+  const h16_t* xsrc;
+  if (grouped) {
+    const int r = (mt_base + wave) * 32 + r32;
+    const int rr = r < a.T ? r : 0;
+    const int row = a.x_rows ? a.x_rows[row_base + rr] : row_base + rr;
+    xsrc = a.x + frag_act_offset(row, 8 * half, 0, a.x_mtiles, PL);
+  } else {
+    const int mt = mt_base + wave < a.x_mtiles ? mt_base + wave : 0;
+    xsrc = a.x + (size_t)mt * PL * 512 + lane * 8;
+  }
+  const size_t x_kstride = (size_t)a.x_mtiles * PL * 512;
+  const int ks_b = split * a.ksteps_per_split;
+  int ks_e = ks_b + a.ksteps_per_split;
+  if (ks_e > KS) ks_e = KS;                          // the host never launches an empty split
+
+  struct Staged { u32x4 w[KC]; u32x4 x[KC][PL]; };
+  auto stage_load = [&](int s, Staged& r) {         // unconditional loads at clamped k-steps
+#pragma unroll
+    for (int kk = 0; kk < KC; ++kk) {
+      const int ks = ks_b + s * KC + kk;
+      const int ksc = ks < ks_e ? ks : ks_e - 1;
+      r.w[kk] = *reinterpret_cast<const u32x4*>(wp + (size_t)ksc * w_kstride);
+#pragma unroll
+      for (int p = 0; p < PL; ++p) r.x[kk][p] = *reinterpret_cast<const u32x4*>(xsrc + (size_t)ksc * x_kstride + (size_t)p * 512);
+    }
+  };
+  auto stage_store = [&](int s, const Staged& r) {  // a k-step past the end multiplies by zero weights
+    const int buf = s & 1;
+    const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int kk = 0; kk < KC; ++kk) {
+      const bool ok = ks_b + s * KC + kk < ks_e;
+      lds[(buf * STAGE + kk * LG_TILES + wave) * 64 + lane] = ok ? r.w[kk] : z;
+#pragma unroll
+      for (int p = 0; p < PL; ++p) lds[(buf * STAGE + WFR + (kk * LG_TILES + wave) * PL + p) * 64 + lane] = r.x[kk][p];
+    }
+  };
+
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[j][m][q] = 0.f;
+
+  const int n_stages = (ks_e - ks_b + KC - 1) / KC;
+  Staged st;
+  stage_load(0, st);
+  stage_store(0, st);
+  __syncthreads();
+  for (int s = 0; s < n_stages; ++s) {
+    stage_load(s + 1, st);                           // in flight while this stage is multiplied
+    __builtin_amdgcn_sched_barrier(0);
+    const int buf = s & 1;
+#pragma unroll
+    for (int kk = 0; kk < KC; ++kk) {
+      h16x8 wf[2], xf[4][PL];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) wf[j] = lds[(buf * STAGE + kk * LG_TILES + 2 * wr + j) * 64 + lane];
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int p = 0; p < PL; ++p) xf[m][p] = lds[(buf * STAGE + WFR + (kk * LG_TILES + 4 * wt + m) * PL + p) * 64 + lane];
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+#pragma unroll
+          for (int p = PL - 1; p >= 0; --p)           // small term first
+            acc[j][m] = mfma_32x32x16<FMT>(wf[j], xf[m][p], acc[j][m]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    stage_store(s + 1, st);                          // the other buffer: its readers passed the last barrier
+    __syncthreads();
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int nt = nt_base + 2 * wr + j;
+    if (nt < n_tiles) tile_epilogue<4, EPI, PL, FMT>(a, acc[j], nt, n_tiles, mt_base + 4 * wt, split, row_base, lane);
+  }
+}
+
+template <int EPI, int PL, int FMT>
+void launch_large_one(const GemmArgs& a, dim3 grid, hipStream_t st) {
+  static bool attr_set = false;
+  constexpr int lds = LargeTiling<PL>::LDS_BYTES;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_large_kernel<EPI, PL, FMT>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_large_kernel<EPI, PL, FMT>), grid, dim3(LG_THREADS), lds, st, a);
+}
+
+template <int EPI>
+void launch_large(const GemmArgs& a, int n_tiles, int grid_y, int rows, const Act& x, hipStream_t st) {
+  dim3 grid((n_tiles + LG_TILES - 1) / LG_TILES, grid_y, (rows + 32 * LG_TILES - 1) / (32 * LG_TILES));
+  if (x.dtype == DT_F16) launch_large_one<EPI, 1, DT_F16>(a, grid, st);
+  else if (x.planes == 2) launch_large_one<EPI, 2, DT_BF16>(a, grid, st);
+  else launch_large_one<EPI, 1, DT_BF16>(a, grid, st);
 }
 
 template <int MT, int EPI, int PL, int FMT>
@@ -391,8 +559,20 @@ void launch_fmt(const GemmArgs& a, dim3 grid, const Act& x, hipStream_t st) {
   else launch_one<MT, EPI, 1, DT_BF16>(a, grid, st);
 }
 
+int g_units = 256;                                   // compute units of the device (gemm_set_units)
+
 template <int EPI>
 void launch_mt(const GemmArgs& a, int n_tiles, int grid_y, int mt, const Act& x, hipStream_t st) {
+  if (mt > 4) {
+    // more than 128 tokens (per expert): 256 x 256 tiles where they fill the device at least twice over (a grid of
+    // 1.25 workgroups per unit takes as long as one of 2), else the 128-token form of the skinny kernel
+    const long wgs = (long)((n_tiles + LG_TILES - 1) / LG_TILES) * grid_y * ((a.T + 32 * LG_TILES - 1) / (32 * LG_TILES));
+    if (wgs >= 2L * g_units) {
+      launch_large<EPI>(a, n_tiles, grid_y, a.T, x, st);
+      return;
+    }
+    mt = 4;
+  }
   const int gx = (n_tiles + GEMM_WAVES - 1) / GEMM_WAVES;
   const int mtiles = (a.T + 31) / 32;
   if (mt == 1) launch_fmt<1, EPI>(a, dim3(gx, grid_y, mtiles), x, st);
@@ -400,7 +580,8 @@ void launch_mt(const GemmArgs& a, int n_tiles, int grid_y, int mt, const Act& x,
   else launch_fmt<4, EPI>(a, dim3(gx, grid_y, (mtiles + 3) / 4), x, st);
 }
 
-int pick_mt(int T) { return T <= 32 ? 1 : (T <= 64 ? 2 : 4); }
+// token tiles per workgroup; 8 selects the large-batch form
+int pick_mt(int T) { return T <= 32 ? 1 : (T <= 64 ? 2 : (T <= 128 ? 4 : 8)); }
 
 void fill_x(GemmArgs& a, const Act& x) {
   a.x = x.p; a.x_mtiles = x.mtiles();
@@ -410,20 +591,24 @@ void fill_x(GemmArgs& a, const Act& x) {
 
 int gemm_max_splits() { return 16; }
 
+void gemm_set_units(int n_units) { g_units = n_units > 0 ? n_units : 1; }
+
 // Split-K planning.  A compute unit takes in only so many bytes per microsecond however many waves it holds, so
 // what counts is that every unit gets the same number of bytes: the grid is kept at or just under one workgroup
 // per unit (a grid of 1.2 workgroups per unit takes as long as one of 2), with as few planes as that allows.
 static int ksteps_for(int K, int splits) { return (K / 16 + splits - 1) / splits; }
 
-int gemm_plan_splits(int N, int K, int max_splits, int n_units) {
-  const int groups = ((N + 31) / 32 + GEMM_WAVES - 1) / GEMM_WAVES;   // workgroups per split: 128 rows each
+int gemm_plan_splits(int N, int K, int T, int max_splits, int n_units) {
+  (void)T;                                                             // at most 256 tokens: always the skinny form
+  const int per = GEMM_WAVES;                                          // weight tiles per workgroup
+  const int groups = ((N + 31) / 32 + per - 1) / per;                 // workgroups per split
   const int KS = K / 16;
   int want = n_units / groups;                      // floor: never more workgroups than units
   if (want > max_splits) want = max_splits;
   if (want > KS / 8) want = KS / 8;                 // at least eight k-steps per split
   if (want < 1) want = 1;
-  const int per = ksteps_for(K, want);
-  return (KS + per - 1) / per;                      // no empty split
+  const int ksper = ksteps_for(K, want);
+  return (KS + ksper - 1) / ksper;                  // no empty split
 }
 
 hipError_t gemm_store(const LinearW& w, const Act& x, int T, float* y, int ldy, int splits, hipStream_t st) {
@@ -453,7 +638,9 @@ hipError_t gemm_swiglu(const h16_t* w_gate_up, int F, int K, const Act& x, int T
 // and every tile reads 32 * mt activation rows whether or not they exist, so the tile should just cover the rows an
 // expert is expected to get (decode: a handful; prefill: hundreds); the grid covers max_rows and workgroups past an
 // expert's last row exit at once.
-static int grouped_mt(int expected_rows) { return expected_rows <= 16 ? 1 : (expected_rows <= 40 ? 2 : 4); }
+static int grouped_mt(int expected_rows) {
+  return expected_rows <= 16 ? 1 : (expected_rows <= 40 ? 2 : (expected_rows <= 128 ? 4 : 8));
+}
 
 hipError_t gemm_grouped_swiglu(const h16_t* w_gate_up, int E, int F, int K, const Act& x, const int32_t* x_rows,
                                const int32_t* group_off, int max_rows, int expected_rows, const Act& act,
