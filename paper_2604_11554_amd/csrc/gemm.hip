@@ -337,10 +337,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
       const u32x4 z = {0u, 0u, 0u, 0u};
       const h16x8 w1 = ok ? wf[u] : z;
 #pragma unroll
-      for (int m = 0; m < MT; ++m)
+      for (int p = PL - 1; p >= 0; --p)           // small term first; the MT products of a term are independent
 #pragma unroll
-        for (int p = PL - 1; p >= 0; --p)         // small term first
-          acc[m] = mfma_32x32x16<FMT>(w1, xq[u & 1][m * PL + p], acc[m]);
+        for (int m = 0; m < MT; ++m) acc[m] = mfma_32x32x16<FMT>(w1, xq[u & 1][m * PL + p], acc[m]);
     }
   };
 
@@ -385,12 +384,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
 // Wave w = (row group w & 3: weight tiles 2 (w & 3) + {0, 1}; token half w >> 2: token tiles 4 (w >> 2) + {0..3}).
 // Per accumulator the order is the same as in the skinny form (k ascending, small activation term first), so both
 // forms give the same bits.
-constexpr int LG_WAVES = 8, LG_THREADS = LG_WAVES * WAVE, LG_TILES = 8, LG_KC = 2;
+constexpr int LG_WAVES = 8, LG_THREADS = LG_WAVES * WAVE, LG_TILES = 8;
 
 template <int PL>
 struct LargeTiling {
-  static constexpr int WFR = LG_KC * LG_TILES;          // weight fragments per stage
-  static constexpr int XFR = LG_KC * LG_TILES * PL;     // activation fragments per stage
+  static constexpr int KC = 2;                          // k-steps per stage (three were measured slower)
+  static constexpr int WFR = KC * LG_TILES;             // weight fragments per stage
+  static constexpr int XFR = KC * LG_TILES * PL;        // activation fragments per stage
   static constexpr int STAGE = WFR + XFR;
   static constexpr int LDS_BYTES = 2 * STAGE * 1024;
 };
@@ -398,7 +398,7 @@ struct LargeTiling {
 template <int EPI, int PL, int FMT>
 __global__ __launch_bounds__(LG_THREADS) void gemm_large_kernel(GemmArgs a) {
   using TL = LargeTiling<PL>;
-  constexpr int KC = LG_KC, WFR = TL::WFR, STAGE = TL::STAGE;
+  constexpr int KC = TL::KC, WFR = TL::WFR, STAGE = TL::STAGE;
   extern __shared__ __align__(16) unsigned char lds_raw[];
   u32x4* lds = reinterpret_cast<u32x4*>(lds_raw);   // [2][STAGE][64 lanes]
 
@@ -501,12 +501,11 @@ __global__ __launch_bounds__(LG_THREADS) void gemm_large_kernel(GemmArgs a) {
 #pragma unroll
         for (int p = 0; p < PL; ++p) xf[m][p] = lds[(buf * STAGE + WFR + (kk * LG_TILES + 4 * wt + m) * PL + p) * 64 + lane];
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int p = PL - 1; p >= 0; --p)               // small term first; eight independent products per term
 #pragma unroll
-        for (int m = 0; m < 4; ++m)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-          for (int p = PL - 1; p >= 0; --p)           // small term first
-            acc[j][m] = mfma_32x32x16<FMT>(wf[j], xf[m][p], acc[j][m]);
+          for (int m = 0; m < 4; ++m) acc[j][m] = mfma_32x32x16<FMT>(wf[j], xf[m][p], acc[j][m]);
     }
     __builtin_amdgcn_sched_barrier(0);
     stage_store(s + 1, st);                          // the other buffer: its readers passed the last barrier
