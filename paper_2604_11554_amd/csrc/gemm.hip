@@ -530,12 +530,12 @@ void launch_large_one(const GemmArgs& a, dim3 grid, hipStream_t st) {
   hipLaunchKernelGGL((gemm_large_kernel<EPI, PL, FMT>), grid, dim3(LG_THREADS), lds, st, a);
 }
 
+// Only the two-term bf16 format uses this form: with one term per activation (fp16, or bf16 without the split) the
+// 128-token skinny form was measured faster (fp16 prefill 73.8 k against 66.6 k tokens/s).
 template <int EPI>
-void launch_large(const GemmArgs& a, int n_tiles, int grid_y, int rows, const Act& x, hipStream_t st) {
+void launch_large(const GemmArgs& a, int n_tiles, int grid_y, int rows, hipStream_t st) {
   dim3 grid((n_tiles + LG_TILES - 1) / LG_TILES, grid_y, (rows + 32 * LG_TILES - 1) / (32 * LG_TILES));
-  if (x.dtype == DT_F16) launch_large_one<EPI, 1, DT_F16>(a, grid, st);
-  else if (x.planes == 2) launch_large_one<EPI, 2, DT_BF16>(a, grid, st);
-  else launch_large_one<EPI, 1, DT_BF16>(a, grid, st);
+  launch_large_one<EPI, 2, DT_BF16>(a, grid, st);
 }
 
 template <int MT, int EPI, int PL, int FMT>
@@ -563,11 +563,11 @@ int g_units = 256;                                   // compute units of the dev
 template <int EPI>
 void launch_mt(const GemmArgs& a, int n_tiles, int grid_y, int mt, const Act& x, hipStream_t st) {
   if (mt > 4) {
-    // more than 128 tokens (per expert): 256 x 256 tiles where they fill the device at least twice over (a grid of
-    // 1.25 workgroups per unit takes as long as one of 2), else the 128-token form of the skinny kernel
+    // more than 128 tokens (per expert), two-term bf16 activations: 256 x 256 tiles where they fill the device at
+    // least twice over (a grid of 1.25 workgroups per unit takes as long as one of 2), else the 128-token skinny form
     const long wgs = (long)((n_tiles + LG_TILES - 1) / LG_TILES) * grid_y * ((a.T + 32 * LG_TILES - 1) / (32 * LG_TILES));
-    if (wgs >= 2L * g_units) {
-      launch_large<EPI>(a, n_tiles, grid_y, a.T, x, st);
+    if (wgs >= 2L * g_units && x.planes == 2 && x.dtype == DT_BF16) {
+      launch_large<EPI>(a, n_tiles, grid_y, a.T, st);
       return;
     }
     mt = 4;
