@@ -132,7 +132,8 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
   w.attn_hdr = (int32_t*)take(2 * 4);
   w.attn_seq_part = (float*)take((size_t)S * c.n_q_heads * (c.head_dim + 4) * 4);
   w.attn_pre_part = (float*)take((size_t)shared_prefix_max_tiles(S, c.n_kv_heads) * 16 * (c.head_dim + 4) * 4);
-  w.planes = (float*)take((size_t)plane_rows(T) * c.d_model * 4);
+  // o / down planes: up to 16 per token for short calls, two for long ones (gemm_plan_splits_long)
+  w.planes = (float*)take((size_t)(T <= 256 ? plane_rows(T) : 2 * T) * c.d_model * 4);
   if (c.n_experts) {
     const size_t P = (size_t)T * c.top_k;
     w.act = (h16_t*)take(frag_act_elems((int)P, c.d_ff_expert, PL) * 2);
@@ -238,7 +239,8 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
       RLX_LAUNCH(RLX_K_ATTN, attention_prefill(at, st));
     }
 
-    const int s_o = small ? gemm_plan_splits(d, qdim, T, gemm_max_splits(), m->n_units) : 1;
+    const int s_o = small ? gemm_plan_splits(d, qdim, T, gemm_max_splits(), m->n_units)
+                          : gemm_plan_splits_long(d, T, xb.planes, xb.dtype, m->n_units);
     RLX_LAUNCH(RLX_K_OPROJ, gemm_store(linear1(m->wo[l], d, qdim), ob, T, w.planes, d, s_o, st));
     pend_planes = w.planes; pend_n = s_o;
 
@@ -246,7 +248,8 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
     if (c.n_experts == 0) {
       const Act act = make_act(w.act, T, c.d_ff, PL, FMT);
       RLX_LAUNCH(RLX_K_GATEUP, gemm_swiglu(m->w_gate_up[l], c.d_ff, d, xb, T, act, st));
-      const int s_d = small ? gemm_plan_splits(d, c.d_ff, T, gemm_max_splits(), m->n_units) : 1;
+      const int s_d = small ? gemm_plan_splits(d, c.d_ff, T, gemm_max_splits(), m->n_units)
+                            : gemm_plan_splits_long(d, T, xb.planes, xb.dtype, m->n_units);
       RLX_LAUNCH(RLX_K_DOWN, gemm_store(linear1(m->w_down[l], d, c.d_ff), act, T, w.planes, d, s_d, st));
       pend_planes = w.planes; pend_n = s_d;
     } else {

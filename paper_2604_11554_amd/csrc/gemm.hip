@@ -610,6 +610,14 @@ int gemm_plan_splits(int N, int K, int T, int max_splits, int n_units) {
   return (KS + ksper - 1) / ksper;                  // no empty split
 }
 
+// Long calls (prefill chunks): a narrow output (the o and down projections) gives the 256 x 256 form too few
+// workgroups; two K halves double them, at the price of a second fp32 plane that the consumer adds.
+int gemm_plan_splits_long(int N, int T, int planes, int dtype, int n_units) {
+  if (planes != 2 || dtype != DT_BF16) return 1;      // the large form is used for two-term bf16 only
+  const long wgs = (long)(((N + 31) / 32 + LG_TILES - 1) / LG_TILES) * ((T + 32 * LG_TILES - 1) / (32 * LG_TILES));
+  return (wgs < 2L * n_units && 2 * wgs >= 2L * n_units) ? 2 : 1;
+}
+
 hipError_t gemm_store(const LinearW& w, const Act& x, int T, float* y, int ldy, int splits, hipStream_t st) {
   GemmArgs a = {};
   fill_x(a, x);
