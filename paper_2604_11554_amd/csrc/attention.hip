@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
 }  // namespace
 
 hipError_t attention_prefill(const AttnArgs& a, hipStream_t st) {
-  constexpr int NCT = 2;
+  constexpr int NCT = 4;
   const int group = a.Hq / a.Hkv;
   const int passes = (group + NCT - 1) / NCT;
   dim3 grid(a.max_qtiles, a.Hkv * passes);
