@@ -588,6 +588,13 @@ void fill_x(GemmArgs& a, const Act& x) {
 
 }  // namespace
 
+// Store GEMMs of 65..128 tokens run as two 64-token groups (the weights of these small matrices are read twice,
+// the second time from cache): measured faster than one 128-token tile (MoE decode q|k|v 1.03 -> 0.75 ms per step,
+// output projection 0.91 -> 0.66, router 0.56 -> 0.44 with the split planning that knows of the two groups; the same
+// trick one size down, two 32-token groups for 33..64 tokens, was measured slower).
+static int store_mt(int T) { return (T > 64 && T <= 128) ? 2 : pick_mt(T); }
+static int store_token_groups(int T) { return (T > 64 && T <= 128) ? 2 : 1; }
+
 int gemm_max_splits() { return 16; }
 
 void gemm_set_units(int n_units) { g_units = n_units > 0 ? n_units : 1; }
@@ -600,7 +607,7 @@ static int ksteps_for(int K, int splits) { return (K / 16 + splits - 1) / splits
 int gemm_plan_splits(int N, int K, int T, int max_splits, int n_units) {
   (void)T;                                                             // at most 256 tokens: always the skinny form
   const int per = GEMM_WAVES;                                          // weight tiles per workgroup
-  const int groups = ((N + 31) / 32 + per - 1) / per;                 // workgroups per split
+  const int groups = ((N + 31) / 32 + per - 1) / per * store_token_groups(T);   // workgroups per split
   const int KS = K / 16;
   int want = n_units / groups;                      // floor: never more workgroups than units
   if (want > max_splits) want = max_splits;
@@ -626,7 +633,7 @@ hipError_t gemm_store(const LinearW& w, const Act& x, int T, float* y, int ldy, 
   a.N = w.N; a.K = w.K; a.T = T;
   a.ksteps_per_split = ksteps_for(w.K, splits);   // same rule as gemm_plan_splits
   a.y = y; a.ldy = ldy;
-  launch_mt<EPI_STORE>(a, tiles, splits, pick_mt(T), x, st);
+  launch_mt<EPI_STORE>(a, tiles, splits, store_mt(T), x, st);
   return hipGetLastError();
 }
 
