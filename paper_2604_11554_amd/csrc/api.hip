@@ -116,7 +116,6 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
   w.meta.qtile_seq = (int32_t*)take((size_t)QT * 4);
   w.meta.qtile_q0 = (int32_t*)take((size_t)QT * 4);
   w.meta.n_qtiles = (int32_t*)take(4);
-  w.meta.tickets = (uint32_t*)take(8 * 4);
   w.meta.tok_iota = (int32_t*)take((size_t)T * 4);
   w.meta.rope_cs = (float2*)take((size_t)S * (c.head_dim / 2) * sizeof(float2));
   w.h = (float*)take((size_t)T * c.d_model * 4);
@@ -259,7 +258,7 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
       ra.logits = w.router; ra.n_planes = s_r; ra.T = T; ra.E = c.n_experts; ra.top_k = c.top_k;
       ra.topk_idx = w.topk_idx; ra.topk_w = w.topk_w; ra.routing_out = io.out_routing; ra.layer = l;
       ra.n_layers = c.n_layers; ra.tok_live = w.meta.tok_live; ra.replay_idx = io.replay_routing;
-      RLX_LAUNCH(RLX_K_GROUP, moe_route(ra, w.group_off, w.sorted_token, w.pair_pos, w.meta.tickets, st));
+      RLX_LAUNCH(RLX_K_GROUP, moe_route(ra, w.group_off, w.sorted_token, w.pair_pos, st));
       const Act act = make_act(w.act, T * c.top_k, c.d_ff_expert, PL, FMT);
       const int rows_per_expert = (int)(((long long)T * c.top_k + c.n_experts - 1) / c.n_experts);
       RLX_LAUNCH(RLX_K_GATEUP, gemm_grouped_swiglu(m->w_gate_up[l], c.n_experts, c.d_ff_expert, d, xb,

@@ -12,8 +12,6 @@ namespace {
 __global__ void meta_decode_kernel(TokenMeta m, int n, const int32_t* ctx, const uint8_t* fin, const double* inv_freq,
                                    int half) {
   const int i = blockIdx.x;
-  const int gi = blockIdx.x * blockDim.x + threadIdx.x;
-  if (gi < 8) m.tickets[gi] = 0u;
   const int pos = ctx[i];
   for (int j = threadIdx.x; j < half; j += blockDim.x) {
     float c, s;
@@ -34,7 +32,6 @@ __global__ void meta_decode_kernel(TokenMeta m, int n, const int32_t* ctx, const
 __global__ void meta_prefill_kernel(TokenMeta m, int n_seqs, int total, const int32_t* cu, const int32_t* ctx,
                                     const uint8_t* sample_last) {
   __shared__ int tile_base[1025];
-  if (threadIdx.x < 8) m.tickets[threadIdx.x] = 0u;
   // per-token fields: binary search of the owning sequence
   for (int t = threadIdx.x; t < total; t += blockDim.x) {
     int lo = 0, hi = n_seqs - 1;

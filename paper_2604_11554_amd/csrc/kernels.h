@@ -73,7 +73,6 @@ struct TokenMeta {        // per packed token, built on the device at the start 
   int32_t* qtile_seq;     // prefill attention tiles: sequence, first query index
   int32_t* qtile_q0;
   int32_t* n_qtiles;      // [1]
-  uint32_t* tickets;      // [8] counters zeroed at the start of every call
   int32_t* tok_iota;      // prefill: [T] 0, 1, 2, ... (row lists of the per-token scoring pass)
   float2* rope_cs;        // [n_seqs][hd/2] decode: (cos, sin) of the new position's rotary angles
 };
@@ -201,10 +200,10 @@ struct RouterArgs {
   const uint8_t* tok_live;   // rows that are inert leave routing_out untouched
   const int32_t* replay_idx; // optional [T, n_layers, top_k]: use these experts instead of the layer's own top-k
 };
-// top-k + renormalised weights + routing capture + stable grouping of the T*top_k (token, slot) pairs by expert
-// `ticket`: one zeroed counter in device memory (left zero again on completion)
+// top-k + renormalised weights + routing capture (one launch), then the stable grouping of the T*top_k
+// (token, slot) pairs by expert (a second, one-workgroup launch)
 hipError_t moe_route(const RouterArgs& a, int32_t* group_off, int32_t* sorted_token, int32_t* pair_pos,
-                     unsigned int* ticket, hipStream_t st);
+                     hipStream_t st);
 
 // ---- sampling.hip ----
 struct FinalizeArgs {

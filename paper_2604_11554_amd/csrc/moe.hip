@@ -12,7 +12,7 @@ constexpr int MAX_E = 256;
 // Top-k of one token by one wave: lane holds experts lane, lane+64, ...; selection by (logit descending,
 // id ascending); weights = softmax over the chosen logits (== softmax over all experts, renormalised).
 __device__ __forceinline__ void wave_topk(const RouterArgs& a, int t, int lane, int32_t* idx_out, float* w_out) {
-  // all plane loads go out first (clamped addresses), then the sums in plane order
+  // all plane loads go out first (the skips are uniform over the wave), then the sums in plane order
   constexpr int MAXP = 16;
   float v[MAX_E / 64];
   float part[MAX_E / 64][MAXP];
@@ -21,10 +21,8 @@ __device__ __forceinline__ void wave_topk(const RouterArgs& a, int t, int lane, 
     const int e = lane + 64 * j;
     const int ec = e < a.E ? e : 0;
 #pragma unroll
-    for (int s = 0; s < MAXP; ++s) {
-      const int sc = s < a.n_planes ? s : 0;
-      part[j][s] = a.logits[((size_t)sc * a.T + t) * a.E + ec];
-    }
+    for (int s = 0; s < MAXP; ++s)
+      part[j][s] = (s < a.n_planes && 64 * j < a.E) ? a.logits[((size_t)s * a.T + t) * a.E + ec] : 0.f;
   }
 #pragma unroll
   for (int j = 0; j < MAX_E / 64; ++j) {
@@ -149,34 +147,26 @@ __device__ void group_pairs_by_expert(const int32_t* idx, int n_pairs, int top_k
   }
 }
 
-// grid = ceil(T / 4): every wave does the top-k of one token; the workgroup that finishes last (atomic
-// ticket) groups all pairs by expert.  `ticket` must be zero on entry and is reset for the next launch.
-__global__ __launch_bounds__(256) void moe_route_kernel(RouterArgs a, int32_t* group_off, int32_t* sorted_token,
-                                                        int32_t* pair_pos, unsigned int* ticket) {
-  __shared__ int32_t hist[4 * MAX_E];
-  __shared__ int32_t base[4 * MAX_E];
-  __shared__ bool last;
+// grid = ceil(T / 4): every wave does the top-k of one token
+__global__ __launch_bounds__(256) void moe_topk_kernel(RouterArgs a) {
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t < a.T) wave_topk(a, t, threadIdx.x & 63, a.topk_idx + (size_t)t * a.top_k, a.topk_w + (size_t)t * a.top_k);
-  __threadfence();                     // this workgroup's indices are visible device-wide before the ticket
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const unsigned int n = atomicAdd(ticket, 1u);
-    last = (n == gridDim.x - 1);
-  }
-  __syncthreads();
-  if (!last) return;
-  __threadfence();                     // acquire: see every other workgroup's indices
+}
+
+// one workgroup groups all (token, slot) pairs by expert
+__global__ __launch_bounds__(256) void moe_group_kernel(RouterArgs a, int32_t* group_off, int32_t* sorted_token,
+                                                        int32_t* pair_pos) {
+  __shared__ int32_t hist[4 * MAX_E];
+  __shared__ int32_t base[4 * MAX_E];
   group_pairs_by_expert(a.topk_idx, a.T * a.top_k, a.top_k, a.E, group_off, sorted_token, pair_pos, hist, base);
-  if (threadIdx.x == 0) *ticket = 0u;
 }
 
 }  // namespace
 
 hipError_t moe_route(const RouterArgs& a, int32_t* group_off, int32_t* sorted_token, int32_t* pair_pos,
-                     unsigned int* ticket, hipStream_t st) {
-  hipLaunchKernelGGL(moe_route_kernel, dim3((a.T + 3) / 4), dim3(256), 0, st, a, group_off, sorted_token, pair_pos,
-                     ticket);
+                     hipStream_t st) {
+  hipLaunchKernelGGL(moe_topk_kernel, dim3((a.T + 3) / 4), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(moe_group_kernel, dim3(1), dim3(256), 0, st, a, group_off, sorted_token, pair_pos);
   return hipGetLastError();
 }
 
