@@ -190,3 +190,92 @@ def test_moe_30b_a3b_layer_slice_batch128_sampled_rows():
     shape = RI.QWEN3_30B_A3B.replace(name="qwen3_30b_a3b_shape_2layers", n_layers=2)
     wl = RI.workload_moe_batch(shape, prompt_len=128)         # 128 sequences, all experts touched every step
     _run_case(shape, wl, split=1, n_steps=3, sample_rows=[0, 77])
+
+
+def test_moe_30b_a3b_layer_slice_omni_agentic_turns():
+    """The omni/agentic workload at the 30B-A3B per-layer shape (2-layer slice): sequences that start with
+    1024..4096 injected embedding positions plus 256 ids, then turns of a 128-token tool chunk followed by sampled
+    tokens, with the KV carried across turns.  The GPU samples freely; the sampled rows are then recomputed by the
+    oracle's teacher-forced full forward over everything that entered the cache (replaying the GPU's routing), and
+    every emitted token, log-probability and logit row is compared."""
+    import paper_2604_11554_amd as pkg
+    from paper_2604_11554_amd import synthetic
+    pkg.binding.lib()
+    shape = RI.QWEN3_30B_A3B.replace(name="qwen3_30b_a3b_shape_2layers", n_layers=2)
+    n_turns, n_decode, batch, budget = 2, 3, 6, 8192
+    wl = RI.workload_omni_agentic(shape, batch=batch, n_turns=n_turns, turn_decode=n_decode)
+    plen = [len(t) for t in wl.prompt_tokens]
+    sample_rows = [int(r) for r in np.argsort(plen)[:2]]     # the oracle's attention cost grows with length squared
+    say("omni/agentic: prompts of %s positions, sampled rows %s" % (plen, sample_rows))
+    tensors = synthetic.generate_tensors(shape, 0, threads=12, progress=lambda i, n: say("  tensor %d/%d" % (i, n)))
+    model = synthetic.model_from_tensors(shape, tensors, activation_split=1)
+    total = [p + n_turns * (128 + n_decode) + 8 for p in plen]
+    eng = pkg.RolloutEngine(model, n_blocks=sum((t + 31) // 16 for t in total) + 8, max_seqs=batch,
+                            max_chunk_tokens=budget, max_blocks_per_seq=(max(total) + 31) // 16 + 1)
+    rows = [eng.add_sequence(int(wl.seeds[i]), 1.0, reserve_tokens=total[i]) for i in range(batch)]
+    fed = {r: [] for r in sample_rows}           # what entered the cache: (token ids, routing rows)
+    checks = {r: [] for r in sample_rows}        # (position whose logits predict it, emitted token, logprob, logits)
+
+    def prefill(rows_, toks, embeds=None, sample=True):
+        o = eng.prefill(rows_, toks, embeds, sample_last=[sample] * len(rows_), want_logits=sample, want_routing=True)
+        torch.cuda.synchronize()
+        offs = np.concatenate([[0], np.cumsum([len(t) for t in toks])])
+        for k, r in enumerate(rows_):
+            if r in fed:
+                fed[r].append((np.asarray(toks[k], np.int32), o.routing[offs[k]:offs[k + 1]].cpu().numpy()))
+                if sample:
+                    n_in = sum(len(t) for t, _ in fed[r])
+                    checks[r].append((n_in - 1, int(o.tokens[k]), float(o.logprobs[k]), o.logits[k].cpu().numpy()))
+        return o
+
+    i = 0
+    while i < batch:                             # prompts, several sequences per chunk, nothing sampled
+        j, tot = i, 0
+        while j < batch and tot + plen[j] <= budget:
+            tot += plen[j]; j += 1
+        embeds = []
+        for r in range(i, j):
+            full = np.zeros((plen[r], shape.d_model), np.uint16)
+            full[wl.prompt_tokens[r] < 0] = wl.prompt_embeds[r]
+            embeds.append(full)
+        prefill(list(range(i, j)), wl.prompt_tokens[i:j], embeds, sample=False)
+        say("prompt chunk: rows %d..%d (%d positions)" % (i, j - 1, tot))
+        i = j
+    for turn in range(n_turns):
+        prefill(rows, [wl.turns[r][turn].tool_tokens for r in range(batch)])
+        for s in range(n_decode):                # feeds the previous token, emits the next
+            prev = eng.tokens[:batch].cpu().numpy().copy()
+            o = eng.decode_step(want_logits=True, want_routing=True)
+            torch.cuda.synchronize()
+            for r in sample_rows:
+                fed[r].append((prev[r:r + 1].astype(np.int32), o.routing[r:r + 1].cpu().numpy()))
+                n_in = sum(len(t) for t, _ in fed[r])
+                checks[r].append((n_in - 1, int(o.tokens[r]), float(o.logprobs[r]), o.logits[r].cpu().numpy()))
+        say("turn %d done" % turn)
+    assert not eng.finished[:batch].any()
+    assert eng.ctx_lens[:batch].cpu().tolist() == [p + n_turns * (128 + n_decode) for p in plen]
+
+    om = O.OracleModel(shape, 0, cache_layers=False, tensors=tensors)
+    seqs = [np.concatenate([t for t, _ in fed[r]]) for r in sample_rows]
+    replay = [np.concatenate([rt for _, rt in fed[r]], axis=0) for r in sample_rows]
+    at = [np.array([c[0] for c in checks[r]]) for r in sample_rows]
+    say("oracle forward of the sampled sequences (%s positions)" % [len(s) for s in seqs])
+    res = O.forward_full(om, seqs, embeds=[wl.prompt_embeds[r] for r in sample_rows], forced_routing=replay,
+                         logits_at=at, progress=lambda l: say("  oracle layer %d" % l))
+    stats = dict(dlogit=0.0, dlogprob=0.0, tie_flips=0, routes=0)
+    for k, r in enumerate(sample_rows):
+        z_o = res[k]["logits"]
+        lp_o = O.log_softmax(z_o)
+        for p, (pos, tok, lp, z_g) in enumerate(checks[r]):
+            stats["dlogit"] = max(stats["dlogit"], float(np.abs(z_g - z_o[p]).max()))
+            stats["dlogprob"] = max(stats["dlogprob"], abs(lp - float(lp_o[p, tok])))
+            sc = z_o[p].astype(np.float64) + O.gumbel_noise(int(wl.seeds[r]), pos + 1, shape.vocab)
+            assert sc[tok] >= sc.max() - 2 * LOGIT_BAR, "row %d check %d: bad draw" % (r, p)
+        bad = (np.sort(replay[k], -1) != np.sort(res[k]["own_routing"], -1)).any(-1)
+        stats["routes"] += bad.size
+        stats["tie_flips"] += int(bad.sum())
+        assert (res[k]["gate_gap"][bad] < TIE_GAP).all(), "routing differs at gate gap %.2e" % float(
+            res[k]["gate_gap"][bad].max())
+    say("omni/agentic sampled-row stats %s" % stats)
+    assert stats["dlogit"] <= LOGIT_BAR and stats["dlogprob"] <= LOGPROB_BAR
+    model.close()
