@@ -233,7 +233,11 @@ class RolloutEngine:
         cap = min(max_ctx, reserve_tokens if reserve_tokens is not None else max_ctx)
         nb = (cap + 15) // 16
         n_full = ctx // 16
-        own = self._alloc(max(nb - n_full, 0))
+        if nb > self.max_blocks:
+            raise ValueError("sequence needs %d pages > max_blocks_per_seq %d" % (nb, self.max_blocks))
+        if nb * 16 <= ctx:
+            raise ValueError("fork of a %d-token prefix needs room for at least one more position" % ctx)
+        own = self._alloc(nb - n_full)
         blocks = self.block_lists[src][:n_full] + own
         self.refcount[self.block_lists[src][:n_full]] += 1
         i = self.n
