@@ -98,10 +98,12 @@ __device__ __forceinline__ float block_sum_256(float v, float* sh) {
 }
 
 // One workgroup per row.  Every thread owns up to NV float4 slices of the row and issues all of its
-// loads (residual, split-K planes or the top-k expert rows) before the first add, so the kernel
-// costs about one memory round trip; the normalised row goes out in MFMA fragment order.
+// loads (residual, PR split-K planes per round, or the top-k expert rows) before the first add, so the
+// kernel costs about one memory round trip per round; the host picks NV and PR so that a row of up to
+// 4096 elements stays in registers and its planes take one round (two at 16 planes of the longest rows).
+// The normalised row goes out in MFMA fragment order.
+template <int NV, int PR>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(NormArgs a) {
-  constexpr int NV = 4;                      // d <= 4096 stays in registers; longer rows loop
   __shared__ float sh[4];
   const int r = blockIdx.x;
   const int t = a.rows ? a.rows[r] : r;
@@ -135,17 +137,17 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(NormArgs a) {
       v[j] = *reinterpret_cast<const f32x4*>(hrow + 4 * ic[j]);
     }
     if (a.add) {
-      for (int s0 = 0; s0 < a.n_planes; s0 += 4) {     // four planes per round, added in plane order
-        f32x4 p[4][NV];
+      for (int s0 = 0; s0 < a.n_planes; s0 += PR) {    // PR planes per round, added in plane order
+        f32x4 p[PR][NV];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < PR; ++q) {
           const int sc = s0 + q < a.n_planes ? s0 + q : a.n_planes - 1;
 #pragma unroll
           for (int j = 0; j < NV; ++j)
             p[q][j] = *reinterpret_cast<const f32x4*>(a.add + ((size_t)sc * a.T_total + t) * a.d + 4 * ic[j]);
         }
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
+        for (int q = 0; q < PR; ++q)
           if (s0 + q < a.n_planes) {
 #pragma unroll
             for (int j = 0; j < NV; ++j) v[j] += p[q][j];
@@ -348,8 +350,20 @@ hipError_t embed_tokens(const h16_t* embed, int vocab, int d, const int32_t* tok
   return hipGetLastError();
 }
 
+template <int NV>
+static void launch_rmsnorm(const NormArgs& a, hipStream_t st) {
+  const int np = a.add ? a.n_planes : 0;
+  if (np <= 4) hipLaunchKernelGGL((rmsnorm_kernel<NV, 4>), dim3(a.T), dim3(256), 0, st, a);
+  else if (np <= 8 || NV == 4) hipLaunchKernelGGL((rmsnorm_kernel<NV, 8>), dim3(a.T), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((rmsnorm_kernel<(NV < 4 ? NV : 1), 16>), dim3(a.T), dim3(256), 0, st, a);
+}
+
 hipError_t rmsnorm(const NormArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL(rmsnorm_kernel, dim3(a.T), dim3(256), 0, st, a);
+  const int nv = a.d >> 2;                   // float4 slices of a row; 256 threads hold NV each
+  if (nv <= 256) launch_rmsnorm<1>(a, st);
+  else if (nv <= 512) launch_rmsnorm<2>(a, st);
+  else if (nv <= 768) launch_rmsnorm<3>(a, st);
+  else launch_rmsnorm<4>(a, st);             // rows longer than 4096 elements loop
   return hipGetLastError();
 }
 
