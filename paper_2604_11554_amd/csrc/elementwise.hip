@@ -114,6 +114,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(NormArgs a) {
   const bool single = nv <= 256 * NV;
   const int dt = a.x.dtype;
   f32x4 keep[NV];
+  u32x2 gain_k[NV];                          // gains of the kept slices, loaded with the row (not after the reduction)
   float ss = 0.f;
   int pp[8];
   float pw[8];
@@ -135,6 +136,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(NormArgs a) {
       const int i = base + threadIdx.x + 256 * j;
       ic[j] = i < nv ? i : nv - 1;
       v[j] = *reinterpret_cast<const f32x4*>(hrow + 4 * ic[j]);
+      if (single) gain_k[j] = *reinterpret_cast<const u32x2*>(a.gain + 4 * ic[j]);
     }
     if (a.add) {
       for (int s0 = 0; s0 < a.n_planes; s0 += PR) {    // PR planes per round, added in plane order
@@ -186,7 +188,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(NormArgs a) {
       const int i = base + threadIdx.x + 256 * j;
       if (i >= nv) continue;
       const f32x4 hv = single ? keep[j] : *reinterpret_cast<const f32x4*>(hrow + 4 * i);   // own writes
-      const u32x2 gb = *reinterpret_cast<const u32x2*>(a.gain + 4 * i);
+      const u32x2 gb = single ? gain_k[j] : *reinterpret_cast<const u32x2*>(a.gain + 4 * i);
       f32x4 o;
       o[0] = hv[0] * rstd * h16_to_f32((h16_t)(gb[0] & 0xFFFFu), dt);
       o[1] = hv[1] * rstd * h16_to_f32((h16_t)(gb[0] >> 16), dt);

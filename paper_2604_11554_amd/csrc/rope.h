@@ -41,11 +41,13 @@ __device__ __forceinline__ void rope_cos_sin(int pos, const double* inv_freq, bo
 __device__ __forceinline__ void head_norm_rope(float x0, float x1, const h16_t* gain, int dtype, int hd, float eps,
                                                bool act, int lane, float c, float s, float& y0, float& y1) {
   if (gain) {
+    const int li = act ? lane : 0;             // the gains are loaded before the reduction, not after it
+    const h16_t g0 = gain[li], g1 = gain[li + (hd >> 1)];
     float ss = wave_sum(x0 * x0 + x1 * x1);
     float rstd = 1.0f / sqrtf(ss / (float)hd + eps);
     if (act) {
-      x0 = x0 * rstd * h16_to_f32(gain[lane], dtype);
-      x1 = x1 * rstd * h16_to_f32(gain[lane + (hd >> 1)], dtype);
+      x0 = x0 * rstd * h16_to_f32(g0, dtype);
+      x1 = x1 * rstd * h16_to_f32(g1, dtype);
     }
   }
   y0 = x0 * c - x1 * s;

@@ -9,13 +9,16 @@ namespace {
 
 struct Part { float m, s, best; int besti; };
 
-__device__ __forceinline__ Part part_merge(Part a, Part b) {   // a precedes b in vocabulary order
+// Equal perturbed scores go to the smaller token id whatever the order of the merges.
+__device__ __forceinline__ Part part_merge(Part a, Part b) {
   Part r;
   float mn = fmaxf(a.m, b.m);
   float ea = (a.m == -INFINITY) ? 0.f : __expf(a.m - mn);
   float eb = (b.m == -INFINITY) ? 0.f : __expf(b.m - mn);
   r.m = mn; r.s = a.s * ea + b.s * eb;
-  if (b.best > a.best) { r.best = b.best; r.besti = b.besti; } else { r.best = a.best; r.besti = a.besti; }
+  const bool take_b = b.best > a.best || (b.best == a.best && b.besti < a.besti);
+  r.best = take_b ? b.best : a.best;
+  r.besti = take_b ? b.besti : a.besti;
   return r;
 }
 
@@ -37,16 +40,23 @@ __global__ __launch_bounds__(256) void sample_finalize_kernel(FinalizeArgs a) {
     }
     return;
   }
-  // contiguous tile ranges per thread keep vocabulary order; then a fixed binary tree
-  const int per = (a.n_tiles + 255) / 256;
+  // thread t takes tiles t, t + 256, ... (one 16-byte record each, eight loads in flight), merged in
+  // ascending order; then a fixed binary tree over the threads
   Part p = {-INFINITY, 0.f, -INFINITY, 0x7FFFFFFF};
-  const float* base = a.part + (size_t)r * a.n_tiles * 4;
-  for (int i = 0; i < per; ++i) {
-    int tile = threadIdx.x * per + i;
-    if (tile < a.n_tiles) {
-      Part q = {base[tile * 4 + 0], base[tile * 4 + 1], base[tile * 4 + 2], __float_as_int(base[tile * 4 + 3])};
-      p = part_merge(p, q);
+  const f32x4* base = reinterpret_cast<const f32x4*>(a.part + (size_t)r * a.n_tiles * 4);
+  for (int t0 = 0; t0 < a.n_tiles; t0 += 8 * 256) {
+    f32x4 q[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int tile = t0 + u * 256 + (int)threadIdx.x;
+      q[u] = base[tile < a.n_tiles ? tile : a.n_tiles - 1];
     }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (t0 + u * 256 + (int)threadIdx.x < a.n_tiles) {
+        Part b = {q[u][0], q[u][1], q[u][2], __float_as_int(q[u][3])};
+        p = part_merge(p, b);
+      }
   }
   sh[threadIdx.x] = p;
   __syncthreads();
