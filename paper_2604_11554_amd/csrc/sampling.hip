@@ -76,13 +76,33 @@ __global__ __launch_bounds__(256) void sample_finalize_kernel(FinalizeArgs a) {
   if (tok < 0 || tok >= a.vocab) tok = a.eos;   // cannot happen with a non-empty vocabulary; keeps the read in bounds
 
   // logit of the emitted token: the same 16-bit operands as the LM-head tiles, fp32 accumulate
+  // (eight consecutive k are one 16-byte group in both layouts; a thread's loads of a round go out together)
   const int mtiles = a.x.mtiles();
+  const int dt = a.x.dtype;
+  const int ng = a.d >> 3;
   float acc = 0.f;
-  for (int k = threadIdx.x; k < a.d; k += 256) {
-    const h16_t* x = a.x.p + frag_act_offset(r, k & ~7, 0, mtiles, a.x.planes) + (k & 7);
-    float xv = h16_to_f32(x[0], a.x.dtype);
-    if (a.x.planes == 2) xv += h16_to_f32(x[512], a.x.dtype);
-    acc += xv * h16_to_f32(a.w_lm[packed_weight_offset(tok, k, a.d)], a.x.dtype);
+  for (int g0 = 0; g0 < ng; g0 += 2 * 256) {
+    h16x8 xh[2], xl[2], wv[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int gi = g0 + u * 256 + (int)threadIdx.x;
+      const int k = 8 * (gi < ng ? gi : ng - 1);
+      const h16_t* x = a.x.p + frag_act_offset(r, k, 0, mtiles, a.x.planes);
+      xh[u] = load_h16x8(x);
+      xl[u] = a.x.planes == 2 ? load_h16x8(x + 512) : zero_h16x8();
+      wv[u] = load_h16x8(a.w_lm + packed_weight_offset(tok, k, a.d));
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+      if (g0 + u * 256 + (int)threadIdx.x < ng) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int sh = 16 * (e & 1);
+          float xv = h16_to_f32((h16_t)((xh[u][e >> 1] >> sh) & 0xFFFFu), dt);
+          if (a.x.planes == 2) xv += h16_to_f32((h16_t)((xl[u][e >> 1] >> sh) & 0xFFFFu), dt);
+          acc += xv * h16_to_f32((h16_t)((wv[u][e >> 1] >> sh) & 0xFFFFu), dt);
+        }
+      }
   }
   acc = wave_sum(acc);
   if ((threadIdx.x & 63) == 0) dsh[threadIdx.x >> 6] = acc;
