@@ -84,7 +84,7 @@ struct Workspace {
   h16_t* act;       // dense [T, F]; MoE [T*top_k, Fe]
   float* moe_y;      // [T*top_k, d]
   int32_t* topk_idx; float* topk_w;
-  int32_t *counts, *group_off, *sorted_token, *pair_pos;
+  int32_t *group_ws, *group_off, *sorted_token, *pair_pos;
   h16_t* x_lm;      // [S, d]
   float* lm_part;    // [S][tiles][4]
   size_t bytes;
@@ -139,7 +139,7 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
     w.moe_y = (float*)take(P * c.d_model * 4);
     w.topk_idx = (int32_t*)take(P * 4);
     w.topk_w = (float*)take(P * 4);
-    w.counts = (int32_t*)take((size_t)c.n_experts * 4);
+    w.group_ws = (int32_t*)take(moe_group_workspace_words() * 4);
     w.group_off = (int32_t*)take((size_t)(c.n_experts + 1) * 4);
     w.sorted_token = (int32_t*)take(P * 4);
     w.pair_pos = (int32_t*)take(P * 4);
@@ -258,7 +258,7 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
       ra.logits = w.router; ra.n_planes = s_r; ra.T = T; ra.E = c.n_experts; ra.top_k = c.top_k;
       ra.topk_idx = w.topk_idx; ra.topk_w = w.topk_w; ra.routing_out = io.out_routing; ra.layer = l;
       ra.n_layers = c.n_layers; ra.tok_live = w.meta.tok_live; ra.replay_idx = io.replay_routing;
-      RLX_LAUNCH(RLX_K_GROUP, moe_route(ra, w.group_off, w.sorted_token, w.pair_pos, st));
+      RLX_LAUNCH(RLX_K_GROUP, moe_route(ra, w.group_off, w.sorted_token, w.pair_pos, w.group_ws, st));
       const Act act = make_act(w.act, T * c.top_k, c.d_ff_expert, PL, FMT);
       const int rows_per_expert = (int)(((long long)T * c.top_k + c.n_experts - 1) / c.n_experts);
       RLX_LAUNCH(RLX_K_GATEUP, gemm_grouped_swiglu(m->w_gate_up[l], c.n_experts, c.d_ff_expert, d, xb,

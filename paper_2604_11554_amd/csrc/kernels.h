@@ -201,9 +201,11 @@ struct RouterArgs {
   const int32_t* replay_idx; // optional [T, n_layers, top_k]: use these experts instead of the layer's own top-k
 };
 // top-k + renormalised weights + routing capture (one launch), then the stable grouping of the T*top_k
-// (token, slot) pairs by expert (a second, one-workgroup launch)
+// (token, slot) pairs by expert: one more launch of one workgroup for short lists, three launches of several
+// workgroups for long ones, which pass through `seg_ws` (moe_group_workspace_words() int32 words)
+size_t moe_group_workspace_words();
 hipError_t moe_route(const RouterArgs& a, int32_t* group_off, int32_t* sorted_token, int32_t* pair_pos,
-                     hipStream_t st);
+                     int32_t* seg_ws, hipStream_t st);
 
 // ---- sampling.hip ----
 struct FinalizeArgs {

@@ -78,25 +78,73 @@ __device__ __forceinline__ void wave_topk(const RouterArgs& a, int t, int lane, 
   }
 }
 
-// Stable counting sort of the T*top_k (token, slot) pairs by expert, by one workgroup of four waves.
-// Wave w owns the contiguous segment w of the pair list.  Pass 1: per-wave histograms.  Scan: offsets by
-// (expert, wave).  Pass 2: a pair's position = offset + its rank among equal experts, in pair order (the
-// lanes holding the same expert are found with one ballot per id bit).
-__device__ void group_pairs_by_expert(const int32_t* idx, int n_pairs, int top_k, int E, int32_t* group_off,
-                                      int32_t* sorted_token, int32_t* pair_pos, int32_t* hist /*[4][MAX_E]*/,
-                                      int32_t* base /*[4][MAX_E]*/) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int i = threadIdx.x; i < 4 * MAX_E; i += 256) hist[i] = 0;
-  __syncthreads();
-  const int seg = ((n_pairs + 3) / 4 + 63) / 64 * 64;       // segment length, a multiple of the wave size
-  const int p_begin = wave * seg, p_end = min(n_pairs, p_begin + seg);
+// grid = ceil(T / 4): every wave does the top-k of one token
+__global__ __launch_bounds__(256) void moe_topk_kernel(RouterArgs a) {
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t < a.T) wave_topk(a, t, threadIdx.x & 63, a.topk_idx + (size_t)t * a.top_k, a.topk_w + (size_t)t * a.top_k);
+}
+
+// Stable counting sort of the T*top_k (token, slot) pairs by expert.  The pair list is cut into contiguous
+// segments, one per wave.  Pass 1: per-segment histograms.  Scan: offsets by (expert, segment).  Pass 2: a pair's
+// position = offset + its rank among equal experts, in pair order (the lanes holding the same expert are found
+// with one ballot per id bit).  Short lists (decode) are sorted by one workgroup of four waves in one launch; long
+// ones (prefill) by GROUP_WGS workgroups in three launches, the histograms and offsets passing through `seg_ws`.
+constexpr int GROUP_WGS = 16;
+constexpr int GROUP_SEGS = 4 * GROUP_WGS;
+constexpr int GROUP_ONE_WG_PAIRS = 4096;
+
+__device__ __forceinline__ int segment_len(int n_pairs, int n_segs) {   // a multiple of the wave size
+  return ((n_pairs + n_segs - 1) / n_segs + 63) / 64 * 64;
+}
+
+__device__ __forceinline__ void count_segment(const int32_t* idx, int p_begin, int p_end, int E, int lane,
+                                              int32_t* hist_w /*[MAX_E], LDS, zeroed*/) {
   for (int p0 = p_begin; p0 < p_end; p0 += 64) {
     const int p = p0 + lane;
     if (p < p_end) {
       const int e = idx[p];
-      if (e >= 0 && e < E) atomicAdd(&hist[wave * MAX_E + e], 1);
+      if (e >= 0 && e < E) atomicAdd(&hist_w[e], 1);
     }
   }
+}
+
+__device__ __forceinline__ void place_segment(const int32_t* idx, int p_begin, int p_end, int top_k, int E, int lane,
+                                              int32_t* base_w /*[MAX_E], LDS: next free position per expert*/,
+                                              int32_t* sorted_token, int32_t* pair_pos) {
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  for (int p0 = p_begin; p0 < p_end; p0 += 64) {
+    const int p = p0 + lane;
+    const bool ok = p < p_end;
+    int e = ok ? idx[p] : -1;
+    if (e < 0 || e >= E) e = -1;
+    unsigned long long same = __ballot(e >= 0);
+#pragma unroll
+    for (int bit = 0; bit < 8; ++bit) {
+      const unsigned long long bal = __ballot((e >> bit) & 1);
+      same &= ((e >> bit) & 1) ? bal : ~bal;
+    }
+    if (e >= 0) {
+      const int b0 = base_w[e];
+      const int pos = b0 + __popcll(same & lt);
+      sorted_token[pos] = p / top_k;
+      pair_pos[p] = pos;
+      if ((same >> lane) >> 1 == 0) base_w[e] = b0 + __popcll(same);   // highest lane of the group
+    }
+  }
+}
+
+// one workgroup sorts the whole list
+__global__ __launch_bounds__(256) void moe_group_kernel(RouterArgs a, int32_t* group_off, int32_t* sorted_token,
+                                                        int32_t* pair_pos) {
+  __shared__ int32_t hist[4 * MAX_E];
+  __shared__ int32_t base[4 * MAX_E];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n_pairs = a.T * a.top_k, E = a.E;
+  for (int i = threadIdx.x; i < 4 * MAX_E; i += 256) hist[i] = 0;
+  __syncthreads();
+  const int seg = segment_len(n_pairs, 4);
+  const int p_begin = wave * seg, p_end = min(n_pairs, p_begin + seg);
+  count_segment(a.topk_idx, p_begin, p_end, E, lane, hist + wave * MAX_E);
   __syncthreads();
   if (wave == 0) {   // exclusive scan over experts of the four-wave totals; lane holds experts 4*lane .. 4*lane+3
     int tot[4], run = 0;
@@ -125,48 +173,88 @@ __device__ void group_pairs_by_expert(const int32_t* idx, int n_pairs, int top_k
     if (lane == 63) group_off[E] = incl;
   }
   __syncthreads();
-  const unsigned long long lt = (1ull << lane) - 1ull;
-  for (int p0 = p_begin; p0 < p_end; p0 += 64) {
-    const int p = p0 + lane;
-    const bool ok = p < p_end;
-    int e = ok ? idx[p] : -1;
-    if (e < 0 || e >= E) e = -1;
-    unsigned long long same = __ballot(e >= 0);
-#pragma unroll
-    for (int bit = 0; bit < 8; ++bit) {
-      const unsigned long long bal = __ballot((e >> bit) & 1);
-      same &= ((e >> bit) & 1) ? bal : ~bal;
-    }
-    if (e >= 0) {
-      const int b0 = base[wave * MAX_E + e];
-      const int pos = b0 + __popcll(same & lt);
-      sorted_token[pos] = p / top_k;
-      pair_pos[p] = pos;
-      if ((same >> lane) >> 1 == 0) base[wave * MAX_E + e] = b0 + __popcll(same);   // highest lane of the group
-    }
-  }
+  place_segment(a.topk_idx, p_begin, p_end, a.top_k, E, lane, base + wave * MAX_E, sorted_token, pair_pos);
 }
 
-// grid = ceil(T / 4): every wave does the top-k of one token
-__global__ __launch_bounds__(256) void moe_topk_kernel(RouterArgs a) {
-  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (t < a.T) wave_topk(a, t, threadIdx.x & 63, a.topk_idx + (size_t)t * a.top_k, a.topk_w + (size_t)t * a.top_k);
-}
-
-// one workgroup groups all (token, slot) pairs by expert
-__global__ __launch_bounds__(256) void moe_group_kernel(RouterArgs a, int32_t* group_off, int32_t* sorted_token,
-                                                        int32_t* pair_pos) {
+// long lists, launch 1 of 3 (grid GROUP_WGS): histogram of every segment -> seg_ws[segment][MAX_E]
+__global__ __launch_bounds__(256) void moe_group_count_kernel(RouterArgs a, int32_t* seg_ws) {
   __shared__ int32_t hist[4 * MAX_E];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n_pairs = a.T * a.top_k;
+  for (int i = threadIdx.x; i < 4 * MAX_E; i += 256) hist[i] = 0;
+  __syncthreads();
+  const int seg = segment_len(n_pairs, GROUP_SEGS), s = blockIdx.x * 4 + wave;
+  const int p_begin = min(n_pairs, s * seg), p_end = min(n_pairs, p_begin + seg);
+  count_segment(a.topk_idx, p_begin, p_end, a.E, lane, hist + wave * MAX_E);
+  __syncthreads();
+  for (int i = threadIdx.x; i < 4 * MAX_E; i += 256) seg_ws[(size_t)blockIdx.x * 4 * MAX_E + i] = hist[i];
+}
+
+// launch 2 of 3 (one workgroup, thread = expert): the counts of seg_ws become first positions, in place
+__global__ __launch_bounds__(MAX_E) void moe_group_scan_kernel(int E, int32_t* seg_ws, int32_t* group_off) {
+  __shared__ int32_t tot[MAX_E];
+  const int e = threadIdx.x;
+  int32_t cnt[GROUP_SEGS];
+#pragma unroll
+  for (int s = 0; s < GROUP_SEGS; ++s) cnt[s] = seg_ws[(size_t)s * MAX_E + e];   // all loads go out together
+  int run = 0;
+#pragma unroll
+  for (int s = 0; s < GROUP_SEGS; ++s) { const int c = cnt[s]; cnt[s] = run; run += c; }
+  tot[e] = run;
+  __syncthreads();
+  if (e < 64) {      // exclusive scan over experts, as in the one-workgroup kernel
+    int t4[4], sum = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { t4[j] = tot[4 * e + j]; sum += t4[j]; }
+    int incl = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      int v = __shfl_up(incl, o, WAVE);
+      if (e >= o) incl += v;
+    }
+    int off = incl - sum;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      tot[4 * e + j] = off;
+      if (4 * e + j < E) group_off[4 * e + j] = off;
+      off += t4[j];
+    }
+    if (e == 63) group_off[E] = incl;
+  }
+  __syncthreads();
+  const int off = tot[e];
+#pragma unroll
+  for (int s = 0; s < GROUP_SEGS; ++s) seg_ws[(size_t)s * MAX_E + e] = off + cnt[s];
+}
+
+// launch 3 of 3 (grid GROUP_WGS): every wave places the pairs of its segment
+__global__ __launch_bounds__(256) void moe_group_place_kernel(RouterArgs a, const int32_t* seg_ws, int32_t* sorted_token,
+                                                              int32_t* pair_pos) {
   __shared__ int32_t base[4 * MAX_E];
-  group_pairs_by_expert(a.topk_idx, a.T * a.top_k, a.top_k, a.E, group_off, sorted_token, pair_pos, hist, base);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n_pairs = a.T * a.top_k;
+  for (int i = threadIdx.x; i < 4 * MAX_E; i += 256) base[i] = seg_ws[(size_t)blockIdx.x * 4 * MAX_E + i];
+  __syncthreads();
+  const int seg = segment_len(n_pairs, GROUP_SEGS), s = blockIdx.x * 4 + wave;
+  const int p_begin = min(n_pairs, s * seg), p_end = min(n_pairs, p_begin + seg);
+  place_segment(a.topk_idx, p_begin, p_end, a.top_k, a.E, lane, base + wave * MAX_E, sorted_token, pair_pos);
 }
 
 }  // namespace
 
+size_t moe_group_workspace_words() { return (size_t)GROUP_SEGS * MAX_E; }
+
 hipError_t moe_route(const RouterArgs& a, int32_t* group_off, int32_t* sorted_token, int32_t* pair_pos,
-                     hipStream_t st) {
+                     int32_t* seg_ws, hipStream_t st) {
   hipLaunchKernelGGL(moe_topk_kernel, dim3((a.T + 3) / 4), dim3(256), 0, st, a);
-  hipLaunchKernelGGL(moe_group_kernel, dim3(1), dim3(256), 0, st, a, group_off, sorted_token, pair_pos);
+  if ((size_t)a.T * a.top_k <= GROUP_ONE_WG_PAIRS) {
+    hipLaunchKernelGGL(moe_group_kernel, dim3(1), dim3(256), 0, st, a, group_off, sorted_token, pair_pos);
+  } else {
+    hipLaunchKernelGGL(moe_group_count_kernel, dim3(GROUP_WGS), dim3(256), 0, st, a, seg_ws);
+    hipLaunchKernelGGL(moe_group_scan_kernel, dim3(1), dim3(MAX_E), 0, st, a.E, seg_ws, group_off);
+    hipLaunchKernelGGL(moe_group_place_kernel, dim3(GROUP_WGS), dim3(256), 0, st, a, (const int32_t*)seg_ws,
+                       sorted_token, pair_pos);
+  }
   return hipGetLastError();
 }
 
