@@ -482,35 +482,72 @@ __global__ __launch_bounds__(LG_THREADS) void gemm_large_kernel(GemmArgs a) {
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[j][m][q] = 0.f;
 
+  // The products of a stage run in four phases of eight: (k-step 0, small term), (0, large), (1, small), (1, large).
+  // Every phase first requests the fragments of the next one from LDS, so the matrix cores never wait for a read;
+  // the stage's one barrier sits before its last phase, whose reads are the next stage's first fragments: the
+  // next stage was written to the other buffer at the top of this iteration (from registers loaded one iteration
+  // earlier), and the buffer written there was last read before the previous iteration's barrier.
+  static_assert(KC == 2 && PL == 2, "the phase schedule below is written for two k-steps of two terms");
+  auto read_w = [&](int buf, int kk, h16x8 (&wf)[2]) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) wf[j] = lds[(buf * STAGE + kk * LG_TILES + 2 * wr + j) * 64 + lane];
+  };
+  auto read_x = [&](int buf, int kk, int p, h16x8 (&xf)[4]) {
+#pragma unroll
+    for (int m = 0; m < 4; ++m) xf[m] = lds[(buf * STAGE + WFR + (kk * LG_TILES + 4 * wt + m) * PL + p) * 64 + lane];
+  };
+  auto products = [&](const h16x8 (&wf)[2], const h16x8 (&xf)[4]) {   // eight independent accumulators
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int m = 0; m < 4; ++m) acc[j][m] = mfma_32x32x16<FMT>(wf[j], xf[m], acc[j][m]);
+  };
+  // order of a phase's instructions: its LDS reads go out first, then its eight matrix-core instructions
+#define reads_then_products(n_reads)                                   \
+  __builtin_amdgcn_sched_group_barrier(0x100, (n_reads), 0);           \
+  __builtin_amdgcn_sched_group_barrier(0x008, 8, 0)
+  auto lds_barrier = [&]() {                          // LDS traffic only: global loads stay in flight across it
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  };
+
   const int n_stages = (ks_e - ks_b + KC - 1) / KC;
   Staged st;
   stage_load(0, st);
   stage_store(0, st);
+  stage_load(1, st);
   __syncthreads();
+  h16x8 w0[2], w1[2], xa[4], xb[4];
+  read_w(0, 0, w0);
+  read_x(0, 0, 1, xa);
   for (int s = 0; s < n_stages; ++s) {
-    stage_load(s + 1, st);                           // in flight while this stage is multiplied
-    __builtin_amdgcn_sched_barrier(0);
     const int buf = s & 1;
-#pragma unroll
-    for (int kk = 0; kk < KC; ++kk) {
-      h16x8 wf[2], xf[4][PL];
-#pragma unroll
-      for (int j = 0; j < 2; ++j) wf[j] = lds[(buf * STAGE + kk * LG_TILES + 2 * wr + j) * 64 + lane];
-#pragma unroll
-      for (int m = 0; m < 4; ++m)
-#pragma unroll
-        for (int p = 0; p < PL; ++p) xf[m][p] = lds[(buf * STAGE + WFR + (kk * LG_TILES + 4 * wt + m) * PL + p) * 64 + lane];
-#pragma unroll
-      for (int p = PL - 1; p >= 0; --p)               // small term first; eight independent products per term
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int m = 0; m < 4; ++m) acc[j][m] = mfma_32x32x16<FMT>(wf[j], xf[m][p], acc[j][m]);
-    }
-    __builtin_amdgcn_sched_barrier(0);
     stage_store(s + 1, st);                          // the other buffer: its readers passed the last barrier
-    __syncthreads();
+    stage_load(s + 2, st);                           // in flight for one whole iteration
+    __builtin_amdgcn_sched_barrier(0);
+    read_x(buf, 0, 0, xb);
+    products(w0, xa);                                // k-step 0, small term
+    reads_then_products(4);
+    __builtin_amdgcn_sched_barrier(0);
+    read_w(buf, 1, w1);
+    read_x(buf, 1, 1, xa);
+    products(w0, xb);                                // k-step 0, large term
+    reads_then_products(6);
+    __builtin_amdgcn_sched_barrier(0);
+    read_x(buf, 1, 0, xb);
+    products(w1, xa);                                // k-step 1, small term
+    reads_then_products(4);
+    __builtin_amdgcn_sched_barrier(0);
+    lds_barrier();                                   // stage s + 1 is complete; nobody reads stage s from here on
+    __builtin_amdgcn_sched_barrier(0);
+    read_w(buf ^ 1, 0, w0);
+    read_x(buf ^ 1, 0, 1, xa);
+    products(w1, xb);                                // k-step 1, large term
+    reads_then_products(6);
+    __builtin_amdgcn_sched_barrier(0);
   }
+#undef reads_then_products
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const int nt = nt_base + 2 * wr + j;
