@@ -234,7 +234,7 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
       at.Hq = c.n_q_heads; at.Hkv = c.n_kv_heads; at.hd = c.head_dim;
       at.block_table = io.block_table; at.max_blocks = io.max_blocks; at.ctx_lens = io.ctx_lens;
       at.cu_seqlens = io.cu_seqlens; at.qtile_seq = w.meta.qtile_seq; at.qtile_q0 = w.meta.qtile_q0;
-      at.n_qtiles = w.meta.n_qtiles; at.max_qtiles = T / 16 + io.n_seqs + 1; at.o = ob;
+      at.n_qtiles = w.meta.n_qtiles; at.max_qtiles = T / ATTN_QTILE + io.n_seqs + 1; at.o = ob;
       RLX_LAUNCH(RLX_K_ATTN, attention_prefill(at, st));
     }
 

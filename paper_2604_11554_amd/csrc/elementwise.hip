@@ -50,7 +50,7 @@ __global__ void meta_prefill_kernel(TokenMeta m, int n_seqs, int total, const in
     m.sample_pos[i] = ctx[i] + len;
     m.sample_on[i] = (sample_last && sample_last[i] && len > 0) ? 1 : 0;
   }
-  // query tiles of 16 positions, sequence by sequence (n_seqs <= 1024 per chunk of the scan)
+  // query tiles of ATTN_QTILE positions, sequence by sequence (n_seqs <= 1024 per chunk of the scan)
   __syncthreads();
   int base = 0;
   for (int s0 = 0; s0 < n_seqs; s0 += 1024) {
@@ -59,7 +59,7 @@ __global__ void meta_prefill_kernel(TokenMeta m, int n_seqs, int total, const in
       int acc = base;
       for (int i = 0; i < cnt; ++i) {
         tile_base[i] = acc;
-        acc += (cu[s0 + i + 1] - cu[s0 + i] + 15) >> 4;
+        acc += (cu[s0 + i + 1] - cu[s0 + i] + ATTN_QTILE - 1) / ATTN_QTILE;
       }
       tile_base[cnt] = acc;
     }
@@ -68,7 +68,7 @@ __global__ void meta_prefill_kernel(TokenMeta m, int n_seqs, int total, const in
       int nt = tile_base[i + 1] - tile_base[i];
       for (int j = 0; j < nt; ++j) {
         m.qtile_seq[tile_base[i] + j] = s0 + i;
-        m.qtile_q0[tile_base[i] + j] = 16 * j;
+        m.qtile_q0[tile_base[i] + j] = ATTN_QTILE * j;
       }
     }
     base = tile_base[cnt];

@@ -132,6 +132,7 @@ hipError_t kv_copy_blocks(h16_t* pool, int64_t n_blocks, int n_layers, size_t bl
                           const int32_t* dst, int n, hipStream_t st);
 
 // ---- attention.hip (prefill), attention_decode.hip ----
+constexpr int ATTN_QTILE = 64;   // query positions per prefill attention workgroup (a 16-position tile per wave)
 struct AttnArgs {            // prefill
   RowAct q;                  // [planes][T, Hq*hd]
   const h16_t* pool_layer;
