@@ -1,7 +1,8 @@
 // Prefill attention over the paged 16-bit KV pool.  A workgroup takes ATTN_QTILE = 64 consecutive query positions
-// of one sequence for NCT heads of one KV group: wave w owns the 16 positions q0 + 16 w (a column tile per head,
-// causal mask per column) and walks all keys itself, so there is no merge; the pages (32 keys per step) pass
-// through LDS once for the four waves, double buffered, one barrier per step.  K rows are padded by 16 bytes in
+// of one sequence for NCT * NHG heads of one KV group: wave w owns the 16 positions q0 + 16 (w & 3) of the heads
+// NCT (w >> 2) + {0 .. NCT-1} (a column tile per head, causal mask per column) and walks all keys itself, so there
+// is no merge; the pages (32 keys per step) pass through LDS once for all waves, double buffered, one barrier per
+// step.  Two waves share a SIMD, so one wave's softmax arithmetic runs under the other's matrix products.  K rows are padded by 16 bytes in
 // LDS so that the 16 rows of a fragment read fall into different banks.  With two-term queries the small terms
 // of a wave's query fragments live in LDS too (each lane re-reads what it wrote), the large ones in registers.
 #include "attn_core.h"
@@ -9,18 +10,18 @@
 namespace rlx {
 namespace {
 
-template <int HD, int NCT, int PL, int FMT>
-__global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
+template <int HD, int NCT, int NHG, int PL, int FMT>
+__global__ __launch_bounds__(256 * NHG) void attn_prefill_kernel(AttnArgs a) {
+  constexpr int THREADS = 256 * NHG;
   constexpr int DT = HD / 16, KS = HD / 32;
   constexpr int KROW = HD + 8;                         // elements per K row in LDS
   constexpr int KPAGE = 16 * KROW, VPAGE = 16 * HD;    // elements of a page's K rows (padded) and of its V^T
   constexpr int PAGE_LDS = KPAGE + VPAGE, STAGE = 2 * PAGE_LDS;
   constexpr int PAGE_CHUNKS = 2 * 16 * HD / 8;         // 16-byte chunks of a page in the pool (K, then V^T)
-  constexpr int NLOAD = 2 * PAGE_CHUNKS / 256;         // chunks per thread and step
-  static_assert(2 * PAGE_CHUNKS % 256 == 0, "a step's pages divide evenly over the workgroup");
+  constexpr int NLOAD = (2 * PAGE_CHUNKS + THREADS - 1) / THREADS;   // chunks per thread and step
   extern __shared__ __align__(16) unsigned char lds_raw[];
   h16_t* lds_kv = reinterpret_cast<h16_t*>(lds_raw);                                   // [2][STAGE]
-  u32x4* lds_q = reinterpret_cast<u32x4*>(lds_raw + (size_t)2 * STAGE * sizeof(h16_t)); // [4 waves][NCT * KS][64]
+  u32x4* lds_q = reinterpret_cast<u32x4*>(lds_raw + (size_t)2 * STAGE * sizeof(h16_t)); // [waves][NCT * KS][64]
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c16 = lane & 15, g = lane >> 4;
@@ -28,13 +29,13 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
 
   if ((int)blockIdx.x >= a.n_qtiles[0]) return;      // uniform over the workgroup
   const int seq = a.qtile_seq[blockIdx.x];
-  const int q0 = a.qtile_q0[blockIdx.x] + 16 * wave;  // this wave's first query position
-  const int passes = (group + NCT - 1) / NCT;
+  const int q0 = a.qtile_q0[blockIdx.x] + 16 * (wave & 3);  // this wave's first query position
+  const int passes = (group + NCT * NHG - 1) / (NCT * NHG);
   const int kvh = blockIdx.y / passes;
-  const int hbase = (blockIdx.y % passes) * NCT;
+  const int hbase = ((blockIdx.y % passes) * NHG + (wave >> 2)) * NCT;
   const int ctx = a.ctx_lens[seq];
   const int nq = a.cu_seqlens[seq + 1] - a.cu_seqlens[seq];
-  const bool tile_live = q0 < nq;
+  const bool tile_live = q0 < nq && hbase < group;
   const int key_end = ctx + min(q0 + 16, nq);                                  // keys this wave's columns can see
   const int key_end_wg = ctx + min(a.qtile_q0[blockIdx.x] + ATTN_QTILE, nq);   // ... and the workgroup's last wave
 
@@ -82,7 +83,8 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
     if (!r.ok1) b1 = b0;
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) {
-      const int c = (int)threadIdx.x + 256 * i;
+      int c = (int)threadIdx.x + THREADS * i;
+      if (c >= 2 * PAGE_CHUNKS) c = 2 * PAGE_CHUNKS - 1;   // more threads than chunks: a repeated load, not stored
       const int64_t b = c < PAGE_CHUNKS ? b0 : b1;
       r.v[i] = *reinterpret_cast<const u32x4*>(a.pool_layer + ((size_t)b * a.Hkv + kvh) * page + (size_t)(c % PAGE_CHUNKS) * 8);
     }
@@ -90,7 +92,8 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
   auto stage_store = [&](int buf, const Staged& r) {
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) {
-      const int c = (int)threadIdx.x + 256 * i;
+      const int c = (int)threadIdx.x + THREADS * i;
+      if (c >= 2 * PAGE_CHUNKS) continue;
       const int pg = c / PAGE_CHUNKS, w = c % PAGE_CHUNKS;   // w < PAGE_CHUNKS / 2: a chunk of the K rows
       const int off = w < PAGE_CHUNKS / 2 ? (w / (HD / 8)) * KROW + (w % (HD / 8)) * 8 : KPAGE + (w - PAGE_CHUNKS / 2) * 8;
       *reinterpret_cast<u32x4*>(lds_kv + buf * STAGE + pg * PAGE_LDS + off) = r.v[i];
@@ -130,36 +133,36 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
 
 }  // namespace
 
-template <int HD, int NCT, int PL, int FMT>
-static void launch_prefill(const AttnArgs& a, dim3 grid, hipStream_t st) {
+template <int HD, int PL, int FMT>
+static void launch_prefill(const AttnArgs& a, hipStream_t st) {
+  constexpr int NCT = 2, NHG = 2;                    // four heads of a KV group per workgroup, two per wave
   constexpr size_t kv_bytes = (size_t)2 * 2 * (16 * (HD + 8) + 16 * HD) * sizeof(h16_t);   // two stages of two pages
-  constexpr size_t q_bytes = PL == 2 ? (size_t)4 * NCT * (HD / 32) * WAVE * 16 : 0;
+  constexpr size_t q_bytes = PL == 2 ? (size_t)4 * NHG * NCT * (HD / 32) * WAVE * 16 : 0;
   constexpr size_t lds = kv_bytes + q_bytes;
   static bool raised = false;                        // above the default limit of 64 KB per workgroup
   if (!raised) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_prefill_kernel<HD, NCT, PL, FMT>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_prefill_kernel<HD, NCT, NHG, PL, FMT>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     raised = true;
   }
-  hipLaunchKernelGGL((attn_prefill_kernel<HD, NCT, PL, FMT>), grid, dim3(256), lds, st, a);
+  const int group = a.Hq / a.Hkv;
+  const int passes = (group + NCT * NHG - 1) / (NCT * NHG);
+  hipLaunchKernelGGL((attn_prefill_kernel<HD, NCT, NHG, PL, FMT>), dim3(a.max_qtiles, a.Hkv * passes), dim3(256 * NHG),
+                     lds, st, a);
 }
 
 hipError_t attention_prefill(const AttnArgs& a, hipStream_t st) {
-  constexpr int NCT = 4;
-  const int group = a.Hq / a.Hkv;
-  const int passes = (group + NCT - 1) / NCT;
-  dim3 grid(a.max_qtiles, a.Hkv * passes);
   const bool two = a.q.planes == 2;
   // formats built: bf16 with one or two terms, fp16 with one term (checked when the model is created)
   if (a.o.dtype == DT_F16) {
-    if (a.hd == 128) launch_prefill<128, NCT, 1, DT_F16>(a, grid, st);
-    else launch_prefill<64, NCT, 1, DT_F16>(a, grid, st);
+    if (a.hd == 128) launch_prefill<128, 1, DT_F16>(a, st);
+    else launch_prefill<64, 1, DT_F16>(a, st);
   } else if (a.hd == 128) {
-    if (two) launch_prefill<128, NCT, 2, DT_BF16>(a, grid, st);
-    else launch_prefill<128, NCT, 1, DT_BF16>(a, grid, st);
+    if (two) launch_prefill<128, 2, DT_BF16>(a, st);
+    else launch_prefill<128, 1, DT_BF16>(a, st);
   } else {
-    if (two) launch_prefill<64, NCT, 2, DT_BF16>(a, grid, st);
-    else launch_prefill<64, NCT, 1, DT_BF16>(a, grid, st);
+    if (two) launch_prefill<64, 2, DT_BF16>(a, st);
+    else launch_prefill<64, 1, DT_BF16>(a, st);
   }
   return hipGetLastError();
 }
