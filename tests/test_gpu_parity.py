@@ -373,6 +373,33 @@ def test_chunked_prefill_invariance(amd, shape_name):
             assert same[stable].all() and r.shape == want["routing"].shape
 
 
+def test_long_chunk_groups_pairs_with_several_workgroups(amd):
+    """One prefill chunk of 750 tokens of the tiny MoE shape: its 6000 (token, slot) pairs are grouped by expert by
+    the several-workgroup path (lists above 4096 pairs), here with 32 experts instead of the 128 of the full-size
+    tests.  Logits at the sequence ends and every routing row against the oracle's forward."""
+    pkg, synthetic = amd
+    shape = RI.TINY_MOE
+    lens = (250, 301, 199)
+    toks = RI.workload_tiny(shape, lens=lens).prompt_tokens
+    want = O.forward_full(O.OracleModel(shape, 0), toks, logits_at=[np.array([n - 1]) for n in lens])
+    model, eng = _engine(pkg, synthetic, shape, n_blocks=96, max_seqs=4, chunk=1024, max_blocks=32)
+    rows = [eng.add_sequence(60 + i, reserve_tokens=n + 8) for i, n in enumerate(lens)]
+    say("long MoE chunk: %d tokens, %d pairs" % (sum(lens), sum(lens) * shape.top_k))
+    o = eng.prefill(rows, toks, want_logits=True, want_routing=True)
+    torch.cuda.synchronize()
+    z, rt = o.logits.cpu().numpy(), o.routing.cpu().numpy()
+    offs = np.concatenate([[0], np.cumsum(lens)])
+    flips = 0
+    for i in range(3):
+        assert np.abs(z[i] - want[i]["logits"][0]).max() <= LOGIT_BAR
+        r = rt[offs[i]:offs[i + 1]]
+        same = (np.sort(r, -1) == np.sort(want[i]["routing"], -1)).all(-1)
+        assert same[want[i]["gate_gap"] > TIE_GAP].all()
+        flips += int((~same).sum())
+    say("long MoE chunk: routing near-tie differences %d of %d" % (flips, sum(lens) * shape.n_layers))
+    model.close()
+
+
 def test_multi_turn_with_injected_embeddings(amd):
     """Omni/agentic shape in small: injected embedding positions, then turns of (tool chunk -> sampled tokens)
     with the KV carried across turns; GPU teacher-forced on the oracle's transcript."""
