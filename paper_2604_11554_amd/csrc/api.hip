@@ -128,7 +128,7 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
   w.attn_part = (float*)take((size_t)ATTN_WGS_MAX * 2 * (c.n_q_heads / c.n_kv_heads) * (c.head_dim + 4) * 4);
   w.attn_prefix = (int32_t*)take((size_t)(S + 1) * 4);
   w.attn_wg_seq = (int32_t*)take((size_t)ATTN_WGS_MAX * 4);
-  w.attn_hdr = (int32_t*)take(2 * 4);
+  w.attn_hdr = (int32_t*)take(4 * 4);
   w.attn_seq_part = (float*)take((size_t)S * c.n_q_heads * (c.head_dim + 4) * 4);
   w.attn_pre_part = (float*)take((size_t)shared_prefix_max_tiles(S, c.n_kv_heads) * 16 * (c.head_dim + 4) * 4);
   // o / down planes: up to 16 per token for short calls, two for long ones (gemm_plan_splits_long)

@@ -2,9 +2,9 @@
 //
 // One new token per sequence; the 16 MFMA columns of a tile are the query heads of one KV head
 // (group <= 16), so a KV page is read once for all heads of its group.  The work of a step is the
-// sequence of 32-key units of all (sequence, KV head) pairs laid end to end; every workgroup takes an
-// equal, contiguous share of it (the plan is built once per step, contexts being the same for every
-// layer), so the grid is exactly resident (two workgroups per compute unit) and every workgroup streams
+// sequence of 32-key units of all (sequence, KV head) pairs laid end to end; every workgroup takes a
+// contiguous share of it, all shares within four units of each other (the plan is built once per step,
+// contexts being the same for every layer), so the grid is exactly resident (two workgroups per compute unit) and every workgroup streams
 // for the whole kernel instead of paying its start-up and wind-down latency per 256 keys.  Within a
 // share the four waves take units round-robin, each keeping the next unit's pages in flight while it
 // works on the current one.  Where a (sequence, KV head) pair lies inside one share its output is
@@ -20,6 +20,7 @@
 
 namespace rlx {
 namespace {
+
 
 template <int HD>
 struct PageRegs {
@@ -55,6 +56,15 @@ __device__ __forceinline__ int shared_units_of(const SharedView& v, int seq, int
   return v.on ? min(max(v.start_unit[seq], 0), ctx / 32) : 0;
 }
 
+// Shares of two sizes: workgroups 0 .. H-1 take CA units each, the others CB = CA - 4, which may be zero (plan
+// header: CA, total, CB, H).
+struct Shares {
+  int CA, CB, H, U;
+  __device__ __forceinline__ int start(int w) const { return w < H ? w * CA : H * CA + (w - H) * CB; }
+  __device__ __forceinline__ int of_unit(int x) const { return x < H * CA ? x / CA : H + (x - H * CA) / max(CB, 1); }
+};
+__device__ __forceinline__ Shares load_shares(const int32_t* hdr) { return Shares{hdr[0], hdr[2], hdr[3], hdr[1]}; }
+
 struct Run {
   int seq, kvh, ctx, np;     // np: units of the whole pair, counted from unit u0 of the sequence
   int u0;                    // units before this pair's first one (served by prefix tiles)
@@ -76,9 +86,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int group = a.Hq / a.Hkv;
   const bool col_ok = c16 < group;
   const int w = blockIdx.x;
-  const int C = a.plan_hdr[0], U = a.plan_hdr[1];
-  int u = w * C;
-  const int u_end = min(U, u + C);
+  const Shares sh = load_shares(a.plan_hdr);
+  const int U = sh.U;
+  int u = sh.start(w);
+  const int u_end = min(U, sh.start(w + 1));
   if (u >= u_end) return;                            // uniform over the workgroup
   int seq = a.wg_seq[w];
   const float scale = rsqrtf((float)HD);
@@ -333,9 +344,9 @@ __global__ __launch_bounds__(64) void attn_decode_merge_kernel(AttnDecodeArgs a)
   const int lane = threadIdx.x;
   const int group = a.Hq / a.Hkv, PL = a.o.planes, mtiles = a.o.mtiles();
   const int np = a.unit_prefix[seq + 1] - a.unit_prefix[seq];
-  const int C = a.plan_hdr[0];
+  const Shares sh = load_shares(a.plan_hdr);
   const int xs = a.Hkv * a.unit_prefix[seq] + kvh * np;
-  const int w_first = np ? xs / C : 0, w_last = np ? (xs + np - 1) / C : 0;
+  const int w_first = np ? sh.of_unit(xs) : 0, w_last = np ? sh.of_unit(xs + np - 1) : 0;
   const SharedView sv = shared_view(a.shared, a.n_seqs, a.Hkv);
   const int su = np ? shared_units_of(sv, seq, a.ctx_lens[seq]) : 0;
   if (np && w_first == w_last && su == 0) return;
@@ -380,7 +391,7 @@ __global__ __launch_bounds__(64) void attn_decode_merge_kernel(AttnDecodeArgs a)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {                // loads first (clamped), merges after
           const int wc = w0 + q <= w_last ? w0 + q : w_last;
-          const int slot = xs <= wc * C ? 0 : 1;     // first segment of its share or not
+          const int slot = xs <= sh.start(wc) ? 0 : 1;   // first segment of its share or not
           const float* p = a.part + ((size_t)(wc * 2 + slot) * group + j) * PS;
           va[q] = *reinterpret_cast<const f32x4*>(p + d0);
           vb[q] = *reinterpret_cast<const f32x4*>(p + d0 + 4);
@@ -406,7 +417,7 @@ __global__ __launch_bounds__(64) void attn_decode_merge_kernel(AttnDecodeArgs a)
   }
 }
 
-// One workgroup: exclusive prefix of the per-sequence unit counts, the share size, and the sequence in which
+// One workgroup: exclusive prefix of the per-sequence unit counts, the two share sizes, and the sequence in which
 // each share starts.
 __global__ __launch_bounds__(1024) void attn_plan_kernel(int n_seqs, const int32_t* ctx, const uint8_t* live, int Hkv,
                                                           int n_wgs, const int32_t* shared, int32_t* unit_prefix,
@@ -438,11 +449,15 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(int n_seqs, const int32
   if (tid == 0) unit_prefix[n_seqs] = per_head;
   __syncthreads();                                   // the prefix is read back below
   const int total = per_head * Hkv;
-  int C = 4 * ((total + 4 * n_wgs - 1) / (4 * n_wgs));   // a multiple of four: the four waves get equal counts
-  if (C < 4) C = 4;
-  if (tid == 0) { hdr[0] = C; hdr[1] = total; }
+  // share sizes are multiples of four (the four waves get equal counts) that differ by at most four: the quads of
+  // the step are dealt out evenly and the first H workgroups take the remainder, one quad each.  (One size for
+  // all, rounded up, left a tenth of the workgroups without work at the benchmark's contexts.)
+  const int quads = (total + 3) / 4, q = quads / n_wgs, H = quads % n_wgs;
+  const int CA = 4 * (q + 1), CB = 4 * q;
+  if (tid == 0) { hdr[0] = CA; hdr[1] = total; hdr[2] = CB; hdr[3] = H; }
+  const Shares shr = Shares{CA, CB, H, total};
   for (int w = tid; w < n_wgs; w += 1024) {
-    const int u0 = w * C;
+    const int u0 = shr.start(w);
     int lo = 0, hi = n_seqs - 1;                     // largest s with Hkv * prefix[s] <= u0
     while (lo < hi) {
       const int mid = (lo + hi + 1) >> 1;

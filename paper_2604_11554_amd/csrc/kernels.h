@@ -158,7 +158,7 @@ struct AttnDecodeArgs {      // one new token per sequence: row = sequence slot
   // plan of the step (attention_decode_plan): 32-key units of all (sequence, KV head) pairs end to end
   const int32_t* unit_prefix;  // [n_seqs + 1] exclusive prefix of the per-sequence unit counts (0 for inert rows)
   const int32_t* wg_seq;       // [n_wgs] sequence in which workgroup w's share starts
-  const int32_t* plan_hdr;     // [2] units per share, total units
+  const int32_t* plan_hdr;     // [4] units per share of the first H workgroups, total units, units per share of the others, H
   int n_wgs;                   // grid size: shares of the unit sequence
   float* part;               // [n_wgs][2][Hq/Hkv][hd+4] partial (o, m, l) of a share's first / other straddling pair
   Act o;                     // [n_seqs, Hq*hd] in fragment order (input of the output projection)
