@@ -237,7 +237,7 @@ def test_fp16_option_rejects_two_term_activations(amd):
 @pytest.mark.parametrize("case", ["long_and_short", "many_short"])
 def test_decode_attention_shares(amd, case):
     """Decode attention lays the 32-key units of all (sequence, KV head) pairs end to end and cuts the line into
-    equal shares, one per workgroup.  Covered here: one share that holds everything (a pair longer than one
+    shares, one per workgroup, of two sizes four units apart.  Covered here: one share that holds everything (a pair longer than one
     block-table window of 64 units; more than 63 sequences inside one share), shares that cut pairs in two or
     more places, more shares than units, and contexts of 1, 31, 32 and 33 keys."""
     pkg, synthetic = amd
