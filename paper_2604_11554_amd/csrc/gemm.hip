@@ -199,7 +199,10 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs& a, const f32x16 (&
 
 template <int MT, int PL>
 struct Tiling {
-  static constexpr int KC = (32 / (MT * PL)) > 16 ? 16 : (32 / (MT * PL));  // k-steps per LDS chunk
+  // k-steps per LDS chunk: 32 fragments (64 KB for both buffers) in general.  The 32-token two-term form, which
+  // the expert-grouped decode GEMMs launch as thousands of workgroups, takes 24 (48 KB): with 64 KB only one
+  // workgroup was resident per compute unit (in-kernel timestamps), with 48 KB two are (expert down GEMM -6 %).
+  static constexpr int KC = (MT == 1 && PL == 2) ? 12 : ((32 / (MT * PL)) > 16 ? 16 : (32 / (MT * PL)));
   static constexpr int U = KC / 2;                                          // k-steps per weight batch (store form)
   static constexpr int FRAGS = KC * MT * PL;                                // 1 KB fragments per chunk
   static constexpr int PER_THREAD = FRAGS / GEMM_WAVES;                     // staged by each wave
