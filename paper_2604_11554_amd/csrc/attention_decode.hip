@@ -338,7 +338,7 @@ __global__ __launch_bounds__(256) void attn_decode_prefix_kernel(AttnDecodeArgs 
 // prefix precedes is already final; otherwise the parts are merged in a fixed order: prefix chunks in key order,
 // then the pair's own part (one share) or parts (share order).
 template <int HD>
-__global__ __launch_bounds__(64) void attn_decode_merge_kernel(AttnDecodeArgs a) {
+__global__ __launch_bounds__(256) void attn_decode_merge_kernel(AttnDecodeArgs a) {
   constexpr int PS = HD + 4;
   const int seq = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
   const int lane = threadIdx.x;
@@ -356,7 +356,7 @@ __global__ __launch_bounds__(64) void attn_decode_merge_kernel(AttnDecodeArgs a)
     tile0 = max(sv.tile0[seq], 0);
     col0 = min(max(sv.col0[seq], 0), 16 - group);
   }
-  for (int uu = lane; uu < group * HD / 8; uu += 64) {
+  for (int uu = lane; uu < group * HD / 8; uu += (int)blockDim.x) {   // one pass: the block has a thread per slice
     const int j = uu / (HD / 8), d0 = (uu % (HD / 8)) * 8;
     float m = -INFINITY, l = 0.f;
     float o[8];
@@ -571,8 +571,10 @@ hipError_t attention_decode(const AttnDecodeArgs& a, hipStream_t st) {
 
 hipError_t attention_decode_merge(const AttnDecodeArgs& a, hipStream_t st) {
   dim3 grid(a.n_seqs * a.Hkv);
-  if (a.hd == 128) hipLaunchKernelGGL((attn_decode_merge_kernel<128>), grid, dim3(64), 0, st, a);
-  else hipLaunchKernelGGL((attn_decode_merge_kernel<64>), grid, dim3(64), 0, st, a);
+  const int slices = (a.Hq / a.Hkv) * a.hd / 8;      // 8-feature slices of a pair's heads: at most 16 * 128 / 8 = 256
+  dim3 block((slices + 63) / 64 * 64);
+  if (a.hd == 128) hipLaunchKernelGGL((attn_decode_merge_kernel<128>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((attn_decode_merge_kernel<64>), grid, block, 0, st, a);
   return hipGetLastError();
 }
 

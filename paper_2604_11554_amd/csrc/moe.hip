@@ -16,6 +16,7 @@ __device__ __forceinline__ void wave_topk(const RouterArgs& a, int t, int lane, 
   constexpr int MAXP = 16;
   float v[MAX_E / 64];
   float part[MAX_E / 64][MAXP];
+  const bool live = !a.tok_live || a.tok_live[t] != 0;   // requested with the logits, not after the selection
 #pragma unroll
   for (int j = 0; j < MAX_E / 64; ++j) {
     const int e = lane + 64 * j;
@@ -73,7 +74,7 @@ __device__ __forceinline__ void wave_topk(const RouterArgs& a, int t, int lane, 
   if (lane < a.top_k) {
     idx_out[lane] = my_i;
     w_out[lane] = my_e / denom;
-    if (a.routing_out && (!a.tok_live || a.tok_live[t]))
+    if (a.routing_out && live)
       a.routing_out[((size_t)t * a.n_layers + a.layer) * a.top_k + lane] = my_i;
   }
 }
