@@ -117,7 +117,7 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
   w.meta.qtile_q0 = (int32_t*)take((size_t)QT * 4);
   w.meta.n_qtiles = (int32_t*)take(4);
   w.meta.tok_iota = (int32_t*)take((size_t)T * 4);
-  w.meta.rope_cs = (float2*)take((size_t)S * (c.head_dim / 2) * sizeof(float2));
+  w.meta.rope_cs = (float2*)take((size_t)T * (c.head_dim / 2) * sizeof(float2));
   w.h = (float*)take((size_t)T * c.d_model * 4);
   const int PL = c.activation_split ? 2 : 1;
   w.xb = (h16_t*)take(frag_act_elems(T, c.d_model, PL) * 2);
@@ -210,7 +210,7 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
     RopeArgs r = {};
     r.qkv = w.qkv; r.n_planes = s_qkv;
     r.q_gain = c.qk_norm ? m->q_norm[l] : nullptr; r.k_gain = c.qk_norm ? m->k_norm[l] : nullptr;
-    r.inv_freq = m->inv_freq; r.rope_cs = io.decode ? w.meta.rope_cs : nullptr;
+    r.rope_cs = w.meta.rope_cs;
     r.T = T; r.Hq = c.n_q_heads; r.Hkv = c.n_kv_heads; r.hd = c.head_dim;
     r.eps = c.rms_eps; r.tok_seq = w.meta.tok_seq; r.tok_pos = w.meta.tok_pos; r.tok_live = w.meta.tok_live;
     r.block_table = io.block_table; r.max_blocks = io.max_blocks;
@@ -498,7 +498,7 @@ int rollout_prefill_chunk(const rlx_model* m, void* kv_pool, int64_t n_blocks, v
   if (w.bytes > workspace_bytes)
     return fail(RLX_ENOMEM, "workspace too small: need %zu bytes, have %zu", w.bytes, workspace_bytes);
   hipStream_t st = (hipStream_t)stream;
-  RLX_HIP(meta_prefill(w.meta, n_seqs, total_tokens, cu_seqlens, ctx_lens, sample_last, st));
+  RLX_HIP(meta_prefill(w.meta, n_seqs, total_tokens, cu_seqlens, ctx_lens, sample_last, m->inv_freq, m->cfg.head_dim, st));
   StepIO io = {};
   io.n_seqs = n_seqs; io.T = total_tokens; io.decode = false;
   io.tokens = token_ids; io.input_embeds = (const h16_t*)input_embeds; io.cu_seqlens = cu_seqlens;
@@ -525,7 +525,7 @@ int rollout_score_chunk(const rlx_model* m, void* kv_pool, int64_t n_blocks, voi
   if (w.bytes > workspace_bytes)
     return fail(RLX_ENOMEM, "workspace too small: need %zu bytes, have %zu", w.bytes, workspace_bytes);
   hipStream_t st = (hipStream_t)stream;
-  RLX_HIP(meta_prefill(w.meta, n_seqs, total_tokens, cu_seqlens, ctx_lens, nullptr, st));
+  RLX_HIP(meta_prefill(w.meta, n_seqs, total_tokens, cu_seqlens, ctx_lens, nullptr, m->inv_freq, m->cfg.head_dim, st));
   StepIO io = {};
   io.n_seqs = n_seqs; io.T = total_tokens; io.decode = false;
   io.tokens = token_ids; io.input_embeds = (const h16_t*)input_embeds; io.cu_seqlens = cu_seqlens;

@@ -77,6 +77,19 @@ __global__ void meta_prefill_kernel(TokenMeta m, int n_seqs, int total, const in
   if (threadIdx.x == 0) m.n_qtiles[0] = base;
 }
 
+// grid = ceil(T / 4), a wave per token: the rotary factors of every token's position, once per call and not per
+// (layer, head); the positions come from meta_prefill_kernel
+__global__ __launch_bounds__(256) void rope_table_kernel(TokenMeta m, int total, const double* inv_freq, int half) {
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= total) return;
+  const int pos = m.tok_pos[t];
+  for (int j = threadIdx.x & 63; j < half; j += 64) {
+    float c, s;
+    rope_cos_sin(pos, inv_freq, true, j, c, s);
+    m.rope_cs[(size_t)t * half + j] = float2{c, s};
+  }
+}
+
 __global__ void embed_kernel(const h16_t* embed, int vocab, int d, const int32_t* tokens, const h16_t* inj, float* h,
                              int dtype) {
   int t = blockIdx.x;
@@ -210,7 +223,8 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(NormArgs a) {
   }
 }
 
-// grid (token, head group): each of the four waves owns one head; lane i < hd/2 owns the pair (i, i + hd/2)
+// grid (token, head group): each of the four waves owns one head; lane i < hd/2 owns the pair (i, i + hd/2).
+// The form of short calls: decode steps and chunks of up to 1024 tokens, any number of split-K planes.
 __global__ __launch_bounds__(256) void qk_rope_append_kernel(RopeArgs a) {
   const int t = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -240,12 +254,8 @@ __global__ __launch_bounds__(256) void qk_rope_append_kernel(RopeArgs a) {
 
   if (is_q || is_k) {
     float c, s, y0, y1;
-    if (a.rope_cs) {
-      const float2 cs = a.rope_cs[(size_t)t * half + li];
-      c = cs.x; s = cs.y;
-    } else {
-      rope_cos_sin(pos, a.inv_freq, act, li, c, s);
-    }
+    const float2 cs = a.rope_cs[(size_t)t * half + li];
+    c = cs.x; s = cs.y;
     head_norm_rope(x0, x1, is_q ? a.q_gain : a.k_gain, dt, hd, a.eps, act, lane, c, s, y0, y1);
     if (act) {
       if (is_q) {
@@ -268,6 +278,123 @@ __global__ __launch_bounds__(256) void qk_rope_append_kernel(RopeArgs a) {
     h16_t* dst = a.pool_layer + (((size_t)blk * a.Hkv + kvh) * 2 + 1) * 16 * hd;
     dst[(size_t)lane * 16 + slot] = f32_to_h16(x0, dt);
     dst[(size_t)(lane + half) * 16 + slot] = f32_to_h16(x1, dt);
+  }
+}
+
+// Long calls (one plane): the kernel above spends its time issuing instructions for two elements per lane, so here
+// 16 lanes share a head and a wave takes four heads of NT tokens.  Lane j of a head owns the pairs j + 16 k
+// (k < HD / 32): summing its squares as (k = 0 with 2) + (1 with 3) and then across the 16 lanes is the butterfly
+// of the 64-lane form with its first two levels done locally, and every other operation is per element, so both
+// kernels give the same bits.  Neighbouring lanes exchange codes so that the 16-bit results leave as 32-bit stores.
+template <int HD, int NT>
+__global__ __launch_bounds__(256) void qk_rope_append_wide_kernel(RopeArgs a) {
+  constexpr int half = HD / 2, PPL = HD / 32;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = lane & 15, odd = lane & 1;
+  const int dt = a.q_out.dtype;
+  const int n_heads = a.Hq + 2 * a.Hkv;
+  const int h = (blockIdx.x * 4 + wave) * 4 + (lane >> 4);
+  const bool head_ok = h < n_heads;
+  const int hc = head_ok ? h : n_heads - 1;        // lanes past the last head repeat it and store nothing
+  const bool is_q = hc < a.Hq, is_k = !is_q && hc < a.Hq + a.Hkv;
+  const h16_t* gain = is_q ? a.q_gain : a.k_gain;  // both null or both set
+  const bool normed = gain != nullptr && (is_q || is_k);
+
+  float g0[PPL], g1[PPL];
+#pragma unroll
+  for (int k = 0; k < PPL; ++k) {
+    g0[k] = normed ? h16_to_f32(gain[j + 16 * k], dt) : 1.f;
+    g1[k] = normed ? h16_to_f32(gain[j + 16 * k + half], dt) : 1.f;
+  }
+  int tc[NT], pos[NT], seq[NT];
+  bool live[NT];
+  float x0[NT][PPL], x1[NT][PPL];
+  float2 cs[NT][PPL];
+#pragma unroll
+  for (int i = 0; i < NT; ++i) {
+    const int t = blockIdx.y * NT + i;
+    tc[i] = t < a.T ? t : a.T - 1;                 // past the end: a repeated token, never stored
+    pos[i] = a.tok_pos[tc[i]];
+    seq[i] = a.tok_seq[tc[i]];
+    live[i] = t < a.T && a.tok_live[tc[i]] != 0;
+  }
+#pragma unroll
+  for (int i = 0; i < NT; ++i) {
+    const float* src = a.qkv + ((size_t)tc[i] * n_heads + hc) * HD;
+#pragma unroll
+    for (int k = 0; k < PPL; ++k) {
+      x0[i][k] = src[j + 16 * k];
+      x1[i][k] = src[j + 16 * k + half];
+      cs[i][k] = a.rope_cs[(size_t)tc[i] * half + j + 16 * k];
+    }
+  }
+  int64_t blk[NT];
+#pragma unroll
+  for (int i = 0; i < NT; ++i) {
+    blk[i] = -1;
+    if (live[i] && !is_q && head_ok) {
+      const int jb = pos[i] >> 4;
+      if (jb < a.max_blocks) blk[i] = a.block_table[(size_t)seq[i] * a.max_blocks + jb];
+      if (blk[i] < 0 || blk[i] >= a.n_blocks) blk[i] = -1;   // bad table entry: drop the append instead of faulting
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NT; ++i) {
+    const int t = blockIdx.y * NT + i;
+    if (t >= a.T) break;                           // uniform over the workgroup
+    const int slot = pos[i] & 15;
+    float u0[PPL], u1[PPL], p[PPL];
+#pragma unroll
+    for (int k = 0; k < PPL; ++k) {
+      u0[k] = 0.f + x0[i][k];                      // the plane sum of the 64-lane form with one plane
+      u1[k] = 0.f + x1[i][k];
+      p[k] = __builtin_fmaf(u1[k], u1[k], u0[k] * u0[k]);
+    }
+    float ss = PPL == 4 ? (p[0] + p[2]) + (p[1] + p[3]) : p[0] + p[1];
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) ss += __shfl_xor(ss, o, WAVE);
+    const float rstd = 1.0f / sqrtf(ss / (float)HD + a.eps);
+    uint32_t mine[PPL], theirs[PPL];               // (large | small << 16) codes: mine to store, theirs to hand over
+#pragma unroll
+    for (int k = 0; k < PPL; ++k) {
+      float v0 = u0[k], v1 = u1[k];
+      if (normed) { v0 = v0 * rstd * g0[k]; v1 = v1 * rstd * g1[k]; }
+      float y0 = v0, y1 = v1;
+      if (is_q || is_k) {
+        y0 = __builtin_fmaf(v0, cs[i][k].x, -(v1 * cs[i][k].y));
+        y1 = __builtin_fmaf(v1, cs[i][k].x, v0 * cs[i][k].y);
+      }
+      h16_t h0, l0 = 0, h1, l1 = 0;
+      if (is_q) { split_h16(y0, h0, l0, dt); split_h16(y1, h1, l1, dt); }
+      else { h0 = f32_to_h16(y0, dt); h1 = f32_to_h16(y1, dt); }
+      const uint32_t c0 = (uint32_t)h0 | ((uint32_t)l0 << 16), c1 = (uint32_t)h1 | ((uint32_t)l1 << 16);
+      mine[k] = odd ? c1 : c0;                     // even lanes store the first half, odd lanes the second
+      theirs[k] = __shfl_xor(odd ? c0 : c1, 1, WAVE);
+    }
+    if (!head_ok) continue;
+    if (is_q || is_k) {
+      h16_t* dst = nullptr;
+      if (is_q) dst = a.q_out.p + ((size_t)t * a.Hq + hc) * HD;
+      else if (blk[i] >= 0) dst = a.pool_layer + (((size_t)blk[i] * a.Hkv + (hc - a.Hq)) * 2) * 16 * HD + (size_t)slot * HD;
+      if (dst) {
+#pragma unroll
+        for (int k = 0; k < PPL; ++k) {
+          // even lane j: elements (j, j + 1) + 16 k of the first half; odd lane j: (j - 1, j) + 16 k of the second
+          const uint32_t lo_lane = odd ? theirs[k] : mine[k], hi_lane = odd ? mine[k] : theirs[k];
+          h16_t* d = dst + (odd ? half + j - 1 : j) + 16 * k;
+          *reinterpret_cast<uint32_t*>(d) = (lo_lane & 0xFFFFu) | (hi_lane << 16);
+          if (is_q && a.q_out.planes == 2)
+            *reinterpret_cast<uint32_t*>(d + a.q_out.plane) = (lo_lane >> 16) | (hi_lane & 0xFFFF0000u);
+        }
+      }
+    } else if (blk[i] >= 0) {                      // value head: stored transposed, [hd][16]
+      h16_t* dst = a.pool_layer + (((size_t)blk[i] * a.Hkv + (hc - a.Hq - a.Hkv)) * 2 + 1) * 16 * HD;
+#pragma unroll
+      for (int k = 0; k < PPL; ++k) {
+        dst[(size_t)(j + 16 * k) * 16 + slot] = f32_to_h16(u0[k], dt);
+        dst[(size_t)(j + 16 * k + half) * 16 + slot] = f32_to_h16(u1[k], dt);
+      }
+    }
   }
 }
 
@@ -340,9 +467,13 @@ hipError_t meta_decode(const TokenMeta& m, int n_seqs, const int32_t* ctx_lens, 
 }
 
 hipError_t meta_prefill(const TokenMeta& m, int n_seqs, int total_tokens, const int32_t* cu_seqlens,
-                        const int32_t* ctx_lens, const uint8_t* sample_last, hipStream_t st) {
+                        const int32_t* ctx_lens, const uint8_t* sample_last, const double* inv_freq, int head_dim,
+                        hipStream_t st) {
   hipLaunchKernelGGL(meta_prefill_kernel, dim3(1), dim3(1024), 0, st, m, n_seqs, total_tokens, cu_seqlens, ctx_lens,
                      sample_last);
+  if (total_tokens > 0)
+    hipLaunchKernelGGL(rope_table_kernel, dim3((total_tokens + 3) / 4), dim3(256), 0, st, m, total_tokens, inv_freq,
+                       head_dim / 2);
   return hipGetLastError();
 }
 
@@ -370,7 +501,14 @@ hipError_t rmsnorm(const NormArgs& a, hipStream_t st) {
 }
 
 hipError_t qk_rope_append(const RopeArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL(qk_rope_append_kernel, dim3(a.T, (a.Hq + 2 * a.Hkv + 3) / 4), dim3(256), 0, st, a);
+  const int n_heads = a.Hq + 2 * a.Hkv;
+  if (a.T > 1024 && a.n_planes == 1 && (a.hd == 128 || a.hd == 64)) {
+    const dim3 grid((n_heads + 15) / 16, (a.T + 3) / 4);
+    if (a.hd == 128) hipLaunchKernelGGL((qk_rope_append_wide_kernel<128, 4>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((qk_rope_append_wide_kernel<64, 4>), grid, dim3(256), 0, st, a);
+  } else {
+    hipLaunchKernelGGL(qk_rope_append_kernel, dim3(a.T, (n_heads + 3) / 4), dim3(256), 0, st, a);
+  }
   return hipGetLastError();
 }
 

@@ -74,12 +74,13 @@ struct TokenMeta {        // per packed token, built on the device at the start 
   int32_t* qtile_q0;
   int32_t* n_qtiles;      // [1]
   int32_t* tok_iota;      // prefill: [T] 0, 1, 2, ... (row lists of the per-token scoring pass)
-  float2* rope_cs;        // [n_seqs][hd/2] decode: (cos, sin) of the new position's rotary angles
+  float2* rope_cs;        // [T][hd/2] (cos, sin) of the rotary angles of each token's position
 };
 hipError_t meta_decode(const TokenMeta& m, int n_seqs, const int32_t* ctx_lens, const uint8_t* finished,
                        const double* inv_freq, int head_dim, hipStream_t st);
 hipError_t meta_prefill(const TokenMeta& m, int n_seqs, int total_tokens, const int32_t* cu_seqlens,
-                        const int32_t* ctx_lens, const uint8_t* sample_last, hipStream_t st);
+                        const int32_t* ctx_lens, const uint8_t* sample_last, const double* inv_freq, int head_dim,
+                        hipStream_t st);
 hipError_t embed_tokens(const h16_t* embed, int vocab, int d, const int32_t* tokens, const h16_t* input_embeds,
                         int T, float* h, int dtype, hipStream_t st);
 
@@ -108,8 +109,7 @@ struct RopeArgs {
   int n_planes;
   const h16_t* q_gain;      // [hd] or null
   const h16_t* k_gain;
-  const double* inv_freq;    // [hd/2]
-  const float2* rope_cs;     // optional [T][hd/2] precomputed (cos, sin) of each token's position
+  const float2* rope_cs;     // [T][hd/2] (cos, sin) of each token's position (meta_decode / meta_prefill)
   int T, Hq, Hkv, hd;
   float eps;
   const int32_t* tok_seq; const int32_t* tok_pos; const uint8_t* tok_live;

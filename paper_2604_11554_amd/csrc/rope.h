@@ -1,16 +1,20 @@
-// Per-head q/k preparation shared by the prefill rope kernel and the fused decode attention kernel:
-// split-K plane sum, optional per-head RMSNorm (Qwen3 qk-norm), rotary embedding in the half-split
-// convention.  One wave per head; lane i < hd/2 owns the pair (i, i + hd/2), other lanes carry zeros.
+// Per-head q/k preparation of the rope kernel: split-K plane sum, optional per-head RMSNorm (Qwen3 qk-norm),
+// rotary embedding in the half-split convention.  One wave per head; lane i < hd/2 owns the pair (i, i + hd/2), other lanes carry zeros.
 #pragma once
 #include "common.h"
 
 namespace rlx {
 
 // x0, x1 = sum over planes (ascending) of src[p * plane + i], src[p * plane + i + half]; all loads of a batch of
-// eight planes are issued before the adds
+// eight planes are issued before the adds (long calls have one plane: one load per element, same sum)
 __device__ __forceinline__ void sum_head_planes(const float* src, size_t plane, int n_planes, bool act, int li,
                                                 int half, float& x0, float& x1) {
   x0 = 0.f; x1 = 0.f;
+  if (n_planes == 1) {                           // uniform over the grid
+    const float u0 = src[li], u1 = src[li + half];
+    if (act) { x0 += u0; x1 += u1; }
+    return;
+  }
   for (int p0 = 0; p0 < n_planes; p0 += 8) {
     float u0[8], u1[8];
 #pragma unroll
@@ -37,21 +41,22 @@ __device__ __forceinline__ void rope_cos_sin(int pos, const double* inv_freq, bo
   }
 }
 
-// optional RMSNorm over the head (gain != null), then the rotation; must be called by the whole wave
+// optional RMSNorm over the head (gain != null), then the rotation; must be called by the whole wave.  The fused
+// multiply-adds are written out so that the rounding does not depend on which product the compiler chooses to fuse.
 __device__ __forceinline__ void head_norm_rope(float x0, float x1, const h16_t* gain, int dtype, int hd, float eps,
                                                bool act, int lane, float c, float s, float& y0, float& y1) {
   if (gain) {
     const int li = act ? lane : 0;             // the gains are loaded before the reduction, not after it
     const h16_t g0 = gain[li], g1 = gain[li + (hd >> 1)];
-    float ss = wave_sum(x0 * x0 + x1 * x1);
+    float ss = wave_sum(__builtin_fmaf(x1, x1, x0 * x0));
     float rstd = 1.0f / sqrtf(ss / (float)hd + eps);
     if (act) {
       x0 = x0 * rstd * h16_to_f32(g0, dtype);
       x1 = x1 * rstd * h16_to_f32(g1, dtype);
     }
   }
-  y0 = x0 * c - x1 * s;
-  y1 = x1 * c + x0 * s;
+  y0 = __builtin_fmaf(x0, c, -(x1 * s));
+  y1 = __builtin_fmaf(x1, c, x0 * s);
 }
 
 }  // namespace rlx

@@ -400,6 +400,41 @@ def test_long_chunk_groups_pairs_with_several_workgroups(amd):
     model.close()
 
 
+@pytest.mark.parametrize("shape_name", ["tiny_dense", "tiny_dense_qkn", "tiny_moe"])
+def test_calls_above_1024_tokens_write_the_same_kv_codes_as_shorter_ones(amd, shape_name):
+    """Calls of more than 1024 tokens prepare q and k (plane sum, qk-norm, rotary) and append K and V with a kernel of
+    its own (16 lanes per head, four heads per wave; here with the heads of a wave of mixed kind).  One sequence of
+    1100 tokens as one call and as calls of 600 + 500: the cached 16-bit codes of the first layer must be the same
+    bit for bit, and the last position's logits must match the oracle's and each other."""
+    pkg, synthetic = amd
+    shape = {"tiny_dense": RI.TINY_DENSE, "tiny_dense_qkn": RI.TINY_DENSE.replace(name="tiny_dense_qkn", qk_norm=True),
+             "tiny_moe": RI.TINY_MOE}[shape_name]
+    n = 1100
+    tok = RI.workload_tiny(shape, lens=(n,)).prompt_tokens[0]
+    want = O.forward_full(O.OracleModel(shape, 0), [tok], logits_at=[np.array([n - 1])])[0]
+    pools, zs = [], []
+    for chunks in ([n], [600, 500]):
+        say("rope forms %s: calls of %s tokens" % (shape_name, chunks))
+        model, eng = _engine(pkg, synthetic, shape, n_blocks=96, max_seqs=2, chunk=2048, max_blocks=80)
+        i = eng.add_sequence(5, reserve_tokens=n + 8)
+        p = 0
+        for c in chunks:
+            o = eng.prefill([i], [tok[p:p + c]], sample_last=[p + c == n], want_logits=True)
+            p += c
+        torch.cuda.synchronize()
+        zs.append(o.logits.cpu().numpy()[0])
+        pools.append(eng.kv_pool.view(torch.int16).cpu().numpy().copy())
+        model.close()
+    layer0 = 96 * shape.n_kv_heads * 2 * 16 * shape.head_dim          # 16-bit elements of the first layer's pages
+    assert (pools[0][:layer0] != 0).sum() >= n * shape.n_kv_heads * shape.head_dim   # the pages were written
+    assert np.array_equal(pools[0][:layer0], pools[1][:layer0])
+    say("rope forms %s: codes differing over all layers %d of %d, logits identical: %s" % (
+        shape_name, int((pools[0] != pools[1]).sum()), pools[0].size, bool(np.array_equal(zs[0], zs[1]))))
+    for z in zs:
+        assert np.abs(z - want["logits"][0]).max() <= LOGIT_BAR
+    assert np.abs(zs[0] - zs[1]).max() <= 2e-3
+
+
 def test_multi_turn_with_injected_embeddings(amd):
     """Omni/agentic shape in small: injected embedding positions, then turns of (tool chunk -> sampled tokens)
     with the KV carried across turns; GPU teacher-forced on the oracle's transcript."""
