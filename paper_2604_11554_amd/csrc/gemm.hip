@@ -524,6 +524,16 @@ __global__ __launch_bounds__(LG_THREADS) void gemm_large_kernel(GemmArgs a) {
   stage_store(0, st);
   stage_load(1, st);
   __syncthreads();
+  // A wave whose 128 tokens lie past the last row (the tail tile of an expert's rows, mostly) only stages: same
+  // stores, loads and barriers, no fragments and no products, which leaves its SIMD to the wave it shares it with.
+  if ((mt_base + 4 * wt) * 32 >= a.T) {             // uniform over the wave
+    for (int s = 0; s < n_stages; ++s) {
+      stage_store(s + 1, st);
+      stage_load(s + 2, st);
+      lds_barrier();
+    }
+    return;
+  }
   h16x8 w0[2], w1[2], xa[4], xb[4];
   read_w(0, 0, w0);
   read_x(0, 0, 1, xa);
