@@ -225,7 +225,7 @@ def main():
 
     max_blocks = (int(plen.max()) + n_decode + 15) // 16 + 1
     n_blocks = int(sum((int(n) + n_decode + 15) // 16 for n in plen)) + 8
-    chunk_budget = 8192
+    chunk_budget = 32768
     leaders = sorted(set(int(g) for g in wl.group_of)) if grouped else []
     if grouped:                                  # prompts are stored once per group
         n_blocks = int(sum((int(plen[g]) + 15) // 16 for g in leaders)) + bsz * ((n_decode + 15) // 16 + 2) + 8

@@ -44,7 +44,7 @@ def _prefill_all(eng, wl, budget, rows_of_interest):
     return got
 
 
-def _run_case(shape, wl, split, n_steps, sample_rows, budget=8192, fmt="bf16"):
+def _run_case(shape, wl, split, n_steps, sample_rows, budget=32768, fmt="bf16"):   # bench.py's chunk budget
     import paper_2604_11554_amd as pkg
     from paper_2604_11554_amd import synthetic
     pkg.binding.lib()
