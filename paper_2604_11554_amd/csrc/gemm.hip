@@ -275,18 +275,43 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
     }
   }
   const size_t x_kstride = (size_t)a.x_mtiles * PL * 512;   // elements between consecutive k-steps
+  // Fragment i of this wave belongs to the same token tile in every chunk.  With four token tiles the tile is picked
+  // here, once, by comparing the wave number with constants, so that the arrays above are only ever indexed by
+  // constants: the compiler turned the run-time choice among four into an indexed access, which put the arrays
+  // into scratch memory with loads from it in the main loop (with two tiles it selects, in fewer registers).
+  constexpr int NSEL = MT == 4 ? PT : 1;
+  const h16_t* xsel[NSEL];
+  bool oksel[NSEL];
+  if (MT == 4) {
+#pragma unroll
+    for (int i = 0; i < NSEL; ++i) {
+      xsel[i] = xsrc[0];
+      oksel[i] = xok[0];
+#pragma unroll
+      for (int w = 0; w < GEMM_WAVES; ++w) {
+        const int mw = ((w + GEMM_WAVES * i) / PL) % MT;      // a constant once both loops are unrolled
+        if (wave == w) { xsel[i] = xsrc[mw]; oksel[i] = xok[mw]; }
+      }
+    }
+  }
+  auto tile_of = [&](int i, const h16_t*& src, bool& ok) {
+    if (MT == 4) { src = xsel[i]; ok = oksel[i]; return; }
+    const int m = ((wave + GEMM_WAVES * i) / PL) % MT;
+    src = xsrc[0]; ok = xok[0];
+#pragma unroll
+    for (int mm = 1; mm < MT; ++mm)
+      if (m == mm) { src = xsrc[mm]; ok = xok[mm]; }
+  };
   auto stage_load = [&](int chunk, u32x4 (&r)[PT]) {
     const int ks0 = ks_b + chunk * KC;
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
       const int f = wave + GEMM_WAVES * i;
-      const int ks = ks0 + f / (MT * PL), m = (f / PL) % MT, p = f % PL;
+      const int ks = ks0 + f / (MT * PL), p = f % PL;
       const int ksc = ks < ks_e ? ks : ks_e - 1;
-      const h16_t* src = xsrc[0];
-      bool ok = xok[0];
-#pragma unroll
-      for (int mm = 1; mm < MT; ++mm)
-        if (m == mm) { src = xsrc[mm]; ok = xok[mm]; }
+      const h16_t* src;
+      bool ok;
+      tile_of(i, src, ok);
       (void)ok;
       r[i] = *reinterpret_cast<const u32x4*>(src + (size_t)ksc * x_kstride + (size_t)p * 512);
     }
@@ -298,11 +323,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
       const int f = wave + GEMM_WAVES * i;
-      const int ks = ks0 + f / (MT * PL), m = (f / PL) % MT;
-      bool ok = xok[0];
-#pragma unroll
-      for (int mm = 1; mm < MT; ++mm)
-        if (m == mm) ok = xok[mm];
+      const int ks = ks0 + f / (MT * PL);
+      const h16_t* src;
+      bool ok;
+      tile_of(i, src, ok);
+      (void)src;
       const u32x4 z = {0u, 0u, 0u, 0u};
       lds[(buf * FRAGS + f) * 64 + lane] = (ok && ks < ks_e) ? r[i] : z;
     }
@@ -564,11 +589,11 @@ __global__ __launch_bounds__(LG_THREADS) void gemm_large_kernel(GemmArgs a) {
     __builtin_amdgcn_sched_barrier(0);
   }
 #undef reads_then_products
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int nt = nt_base + 2 * wr + j;
-    if (nt < n_tiles) tile_epilogue<4, EPI, PL, FMT>(a, acc[j], nt, n_tiles, mt_base + 4 * wt, split, row_base, lane);
-  }
+  // written out, not a loop: a loop that the compiler declines to unroll (it did with the LM-head epilogue inlined
+  // twice) indexes the accumulators at run time, which moves all of them to scratch memory
+  const int nt0 = nt_base + 2 * wr;
+  if (nt0 < n_tiles) tile_epilogue<4, EPI, PL, FMT>(a, acc[0], nt0, n_tiles, mt_base + 4 * wt, split, row_base, lane);
+  if (nt0 + 1 < n_tiles) tile_epilogue<4, EPI, PL, FMT>(a, acc[1], nt0 + 1, n_tiles, mt_base + 4 * wt, split, row_base, lane);
 }
 
 template <int EPI, int PL, int FMT>
