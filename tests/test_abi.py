@@ -42,3 +42,18 @@ def test_host_side_validation_needs_no_gpu():
     out = ctypes.c_size_t()
     assert lib.rlx_kv_pool_bytes(None, 4, ctypes.byref(out)) == B.RLX_EINVAL
     assert lib.rollout_decode_step(*([None] * 2), 0, None, 0, 0, None, None, None, 0, *([None] * 10)) == B.RLX_EINVAL
+
+
+def test_build_refuses_scratch_memory_and_loops_left_rolled():
+    """The build reads hipcc's resource remarks: a kernel with scratch memory, or a loop the compiler declined to
+    unroll (accumulators indexed at run time then live in scratch), fails it."""
+    from paper_2604_11554_amd import build
+    ok = ("k.hip:5:1: remark: Function Name: _Z1av [-Rpass-analysis=kernel-resource-usage]\n"
+          "k.hip:5:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]\n")
+    assert build._resource_problems(ok) == []
+    bad = ok + ("k.hip:9:1: remark: Function Name: _Z1bv [-Rpass-analysis=kernel-resource-usage]\n"
+                "k.hip:9:1: remark:     ScratchSize [bytes/lane]: 576 [-Rpass-analysis=kernel-resource-usage]\n"
+                "k.hip:12:3: warning: loop not unrolled: the optimizer was unable to perform the requested "
+                "transformation [-Wpass-failed=transform-warning]\n")
+    got = build._resource_problems(bad)
+    assert len(got) == 2 and "_Z1bv uses 576 bytes" in got[0] and "loop not unrolled" in got[1]
