@@ -400,7 +400,7 @@ def test_long_chunk_groups_pairs_with_several_workgroups(amd):
     model.close()
 
 
-@pytest.mark.parametrize("shape_name", ["tiny_dense", "tiny_dense_qkn", "tiny_moe"])
+@pytest.mark.parametrize("shape_name", ["tiny_dense", "tiny_dense_qkn", "tiny_hd128_qkn", "tiny_moe"])
 def test_calls_above_1024_tokens_write_the_same_kv_codes_as_shorter_ones(amd, shape_name):
     """Calls of more than 1024 tokens prepare q and k (plane sum, qk-norm, rotary) and append K and V with a kernel of
     its own (16 lanes per head, four heads per wave; here with the heads of a wave of mixed kind).  One sequence of
@@ -408,6 +408,8 @@ def test_calls_above_1024_tokens_write_the_same_kv_codes_as_shorter_ones(amd, sh
     bit for bit, and the last position's logits must match the oracle's and each other."""
     pkg, synthetic = amd
     shape = {"tiny_dense": RI.TINY_DENSE, "tiny_dense_qkn": RI.TINY_DENSE.replace(name="tiny_dense_qkn", qk_norm=True),
+             "tiny_hd128_qkn": RI.TINY_DENSE.replace(name="tiny_hd128_qkn", n_q_heads=2, n_kv_heads=1, head_dim=128,
+                                                     qk_norm=True),      # the head size of the benchmark shapes
              "tiny_moe": RI.TINY_MOE}[shape_name]
     n = 1100
     tok = RI.workload_tiny(shape, lens=(n,)).prompt_tokens[0]
