@@ -9,6 +9,39 @@ namespace {
 
 constexpr int MAX_E = 256;
 
+// Largest 64-bit key of the wave, returned to every lane.  Row-wise DPP steps (shifts by 1, 2, 4, 8 inside rows of
+// 16 lanes, then the last lane of a row handed to the next row, then lane 31 to the upper half) leave the result
+// in lane 63; a lane without a source at some step keeps its own key.  A chain of short-latency register moves
+// instead of the six dependent cross-lane permutes of a butterfly, of which top-k would need eight in a row.
+__device__ __forceinline__ unsigned long long wave_max_key(unsigned long long key) {
+  uint32_t lo = (uint32_t)key, hi = (uint32_t)(key >> 32);
+#define RLX_KEY_STEP(ctrl, row_mask)                                                           \
+  {                                                                                            \
+    const uint32_t olo = (uint32_t)__builtin_amdgcn_update_dpp((int)lo, (int)lo, ctrl, row_mask, 0xF, false); \
+    const uint32_t ohi = (uint32_t)__builtin_amdgcn_update_dpp((int)hi, (int)hi, ctrl, row_mask, 0xF, false); \
+    const bool take = ohi > hi || (ohi == hi && olo > lo);                                     \
+    lo = take ? olo : lo;                                                                      \
+    hi = take ? ohi : hi;                                                                      \
+  }
+  RLX_KEY_STEP(0x111, 0xF)   // row_shr:1
+  RLX_KEY_STEP(0x112, 0xF)   // row_shr:2
+  RLX_KEY_STEP(0x114, 0xF)   // row_shr:4
+  RLX_KEY_STEP(0x118, 0xF)   // row_shr:8
+  RLX_KEY_STEP(0x142, 0xA)   // row_bcast:15 into rows 1 and 3
+  RLX_KEY_STEP(0x143, 0xC)   // row_bcast:31 into rows 2 and 3
+#undef RLX_KEY_STEP
+  const uint32_t rlo = (uint32_t)__builtin_amdgcn_readlane((int)lo, 63), rhi = (uint32_t)__builtin_amdgcn_readlane((int)hi, 63);
+  return ((unsigned long long)rhi << 32) | rlo;
+}
+// floats as unsigned integers of the same order, and back
+__device__ __forceinline__ uint32_t float_order_bits(float f) {
+  const uint32_t u = __float_as_uint(f);
+  return u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+__device__ __forceinline__ float float_from_order_bits(uint32_t o) {
+  return __uint_as_float(o ^ ((o >> 31) ? 0x80000000u : 0xFFFFFFFFu));
+}
+
 // Top-k of one token by one wave: lane holds experts lane, lane+64, ...; selection by (logit descending,
 // id ascending); weights = softmax over the chosen logits (== softmax over all experts, renormalised).
 __device__ __forceinline__ void wave_topk(const RouterArgs& a, int t, int lane, int32_t* idx_out, float* w_out) {
@@ -55,12 +88,11 @@ __device__ __forceinline__ void wave_topk(const RouterArgs& a, int t, int lane, 
 #pragma unroll
       for (int j = 0; j < MAX_E / 64; ++j)
         if (v[j] > bv) { bv = v[j]; bi = lane + 64 * j; }      // ascending id within the lane
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) {
-        float ov = __shfl_xor(bv, o, WAVE);
-        int oi = __shfl_xor(bi, o, WAVE);
-        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-      }
+      // the wave's best by (logit descending, id ascending): the largest key (ordered logit bits, ~id)
+      const unsigned long long best =
+          wave_max_key(((unsigned long long)float_order_bits(bv) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)bi));
+      bv = float_from_order_bits((uint32_t)(best >> 32));
+      bi = (int)(0xFFFFFFFFu - (uint32_t)best);
     }
     const float ev = __expf(bv - mx);
     denom += ev;
