@@ -9,7 +9,7 @@
  * fields; App. B.3: the trainer's importance ratios use them) and, for MoE
  * policies, the top-K expert indices taken at every MoE layer for every token, for
  * Rollout Routing Replay (paper Sec. 5.5).  Sequence state (a paged KV cache and
- * block table) persists across calls, so multi-turn sessions (paper Sec. 4.3) are
+ * block table) persists across calls, so multi-turn sessions (paper Sec. 4.2) are
  * a sequence of prefill_chunk / decode_step calls.
  *
  * Conventions
@@ -28,8 +28,10 @@
  *    Results are valid once the caller has synchronised the stream.
  *  - Every function returns 0 on success or a negative RLX_E* code; nothing
  *    aborts, throws or prints.  rlx_last_error() gives a thread-local message.
- *    Arguments are validated on the host before the first launch; on error no
- *    work has been enqueued.
+ *    Arguments are validated on the host before the first launch: after an
+ *    argument error (RLX_EINVAL, RLX_ENOMEM, RLX_EUNSUPPORTED) no work has been
+ *    enqueued.  RLX_EHIP reports a failed launch part-way through a call: earlier
+ *    launches of that call stay enqueued and its outputs are undefined.
  *  - A model handle is immutable after creation; concurrent calls must use
  *    distinct workspaces (and distinct sequences of the KV pool).
  */
@@ -168,6 +170,8 @@ RLX_API int rlx_model_set_weights(rlx_model* m, const rlx_weights* w, uint64_t v
 RLX_API int rlx_model_weight_version(const rlx_model* m, uint64_t* version_out);
 
 /*
+ * The KV pool is the per-session state that persists across turns of a multi-turn rollout (paper Sec. 4.2,
+ * "Custom rollout and reward": the rollout keeps session state between the model's turns and the tool outputs).
  * Size in bytes of a KV pool of n_blocks pages (2 bytes per element, the model's dtype).  Layout, private to the
  * library: [layer][block][kv_head]{ K[16][head_dim], V^T[head_dim][16] }.
  * The caller allocates it (256-byte aligned) and passes n_blocks to every call.
@@ -181,8 +185,9 @@ RLX_API int rlx_kv_pool_bytes(const rlx_model* m, int64_t n_blocks, size_t* byte
 RLX_API int rlx_workspace_bytes(const rlx_model* m, int32_t max_seqs, int32_t max_tokens, int32_t max_blocks_per_seq,
                         size_t* bytes_out);
 
-/* Copy whole KV pages src[i] -> dst[i] in every layer (copy-on-write of a shared
- * prompt's partial tail page).  src/dst: device int32 [n]. */
+/* Copy whole KV pages src[i] -> dst[i] in every layer: copy-on-write of the partial tail page of a prompt that the
+ * G responses of one sampling group share (paper Sec. 2.1, group-relative algorithms draw several responses per
+ * prompt).  src/dst: device int32 [n]; pairs with an id outside [0, n_blocks) or src == dst are skipped. */
 RLX_API int rlx_kv_copy_blocks(const rlx_model* m, void* kv_pool, int64_t n_blocks, const int32_t* src,
                        const int32_t* dst, int32_t n, void* stream);
 
@@ -207,8 +212,15 @@ RLX_API int rlx_kv_copy_blocks(const rlx_model* m, void* kv_pool, int64_t n_bloc
  */
 
 /*
+ * Prefill of one chunk: the generation stage's intake of prompt tokens, multimodal features and, between the turns
+ * of an agentic rollout, tool outputs (paper Sec. 3.1, rollout produces the responses; Sec. 4.1, "Unified data
+ * pipeline": placeholder positions are replaced by modality features; Sec. 4.2: tool results are appended to the
+ * session).  The token it emits carries the per-sample fields of Sec. 3.3 ("field-based storage": response tokens
+ * and log probabilities), and out_routing the expert indices that Sec. 5.5 records for every token.
+ *
  * Append a chunk of known tokens to each of n_seqs sequences (varlen, packed) and,
  * where sample_last[i] != 0, emit the next token from the chunk's last position.
+ * A sequence may contribute no token to a call (cu_seqlens[i] == cu_seqlens[i+1]); it then emits nothing.
  *   token_ids     int32 [total_tokens]; -1 = take the row of input_embeds instead
  *   input_embeds  [total_tokens, d_model] in the model's dtype, or NULL (rows used only where id == -1)
  *   cu_seqlens    int32 [n_seqs+1], cu_seqlens[0] = 0, cu_seqlens[n_seqs] = total_tokens
@@ -245,7 +257,10 @@ RLX_API int rollout_prefill_chunk(const rlx_model* m, void* kv_pool, int64_t n_b
  *   temperature     float [n_seqs] (<= 0 scores with T = 1)
  *   replay_routing  NULL or int32 [total_tokens, n_layers, top_k]: MoE layers use these experts instead of their
  *                   own top-k; the mixing weights are the layer's own gate probabilities renormalised over the
- *                   replayed set (an id outside [0, n_experts) is replaced by 0).  Ignored for dense models.
+ *                   replayed set.  The K ids of a token must be distinct experts; an id outside
+ *                   [0, n_experts), or one that repeats an earlier slot of the same token, is replaced by the
+ *                   layer's own best expert not yet in the token's list (so no expert ever receives a token
+ *                   twice).  Ignored for dense models.
  *   out_logprobs    float [total_tokens]
  *   out_routing     NULL or int32 [total_tokens, n_layers, top_k]: the experts used
  * token_ids, input_embeds, cu_seqlens, ctx_lens, block_table as in rollout_prefill_chunk.
@@ -258,6 +273,10 @@ RLX_API int rollout_score_chunk(const rlx_model* m, void* kv_pool, int64_t n_blo
                         int32_t* out_routing, void* stream);
 
 /*
+ * The step the whole RL iteration waits on (paper Sec. 5.3: rollout generation is the longest stage of a step):
+ * every live sequence emits one more response token with its log-probability (Sec. 3.3, per-sample fields) and,
+ * for MoE policies, the experts chosen at every layer (Sec. 5.5, recorded "for every token during inference").
+ *
  * One decode step for n_seqs sequences: each live row consumes tokens_inout[i] at
  * position ctx_lens_inout[i] (appending its K/V there) and emits the next token.
  *   tokens_inout    int32 [n_seqs]  in: last emitted token; out: new token (pad if finished)

@@ -28,11 +28,11 @@ invariants or library routines in tests/test_oracle_*.py.  Agreement with a real
 trained checkpoint of the named model family is *parity unpinned* (no such
 checkpoint is available offline).
 """
-from .layers import (rmsnorm, rope, attention, attention_bruteforce, silu, swiglu_ffn, moe_gate, moe_ffn,
-                     moe_ffn_bruteforce, log_softmax)
+from .layers import (rmsnorm, rope, attention, attention_bruteforce, silu, swiglu_ffn, moe_gate, moe_order_gap,
+                     moe_ffn, moe_ffn_bruteforce, log_softmax)
 from .philox import philox4x32_10, uniform_u32, gumbel_noise, sample_gumbel_max
 from .model import OracleModel, forward_full, OracleRollout, round_to_bf16, round_to_f16
 
-__all__ = ["rmsnorm", "rope", "attention", "attention_bruteforce", "silu", "swiglu_ffn", "moe_gate",
+__all__ = ["rmsnorm", "rope", "attention", "attention_bruteforce", "silu", "swiglu_ffn", "moe_gate", "moe_order_gap",
            "moe_ffn", "moe_ffn_bruteforce", "log_softmax", "philox4x32_10", "uniform_u32", "gumbel_noise",
            "sample_gumbel_max", "OracleModel", "forward_full", "OracleRollout", "round_to_bf16", "round_to_f16"]

@@ -95,7 +95,7 @@ def moe_gate(r: np.ndarray, top_k: int):
 
     Returns (idx [k] int32 in descending probability, ties to the smaller expert id;
     w [k] = P[idx] / sum(P[idx]) with P = softmax(r); gap = r[k-th] - r[(k+1)-th],
-    inf when k == E).
+    inf when k == E).  moe_order_gap(r, idx) gives the margin of the ORDER of the chosen ids.
     """
     e = r.shape[0]
     p = np.exp(r - r.max())
@@ -109,12 +109,19 @@ def moe_gate(r: np.ndarray, top_k: int):
     return idx, w, gap
 
 
+def moe_order_gap(r: np.ndarray, idx: np.ndarray) -> float:
+    """Smallest difference between the logits of consecutive chosen experts (idx in descending order): how far
+    the emitted ORDER of the ids is from a swap.  inf for a single id."""
+    v = np.asarray(r, dtype=np.float64)[np.asarray(idx)]
+    return float(np.min(v[:-1] - v[1:])) if len(v) > 1 else float("inf")
+
+
 def moe_ffn_bruteforce(x: np.ndarray, w_router: np.ndarray, w_gate: np.ndarray, w_up: np.ndarray,
                        w_down: np.ndarray, top_k: int, forced_idx: np.ndarray = None):
     """Sparse MoE FFN for tokens x [n, d], one token and one expert at a time.
 
     Returns (y [n, d], idx [n, k] int32 experts used, gap [n], own [n, k] int32 the
-    router's own choice).  With forced_idx [n, k] the given experts are used (routing
+    router's own choice, order_gap [n] = moe_order_gap of the router's own choice).  With forced_idx [n, k] the given experts are used (routing
     replay, paper Sec. 5.5) while the mixing weights still come from this model's
     own router probabilities, renormalised over them.
     """
@@ -123,11 +130,13 @@ def moe_ffn_bruteforce(x: np.ndarray, w_router: np.ndarray, w_gate: np.ndarray, 
     idx_out = np.empty((n, top_k), dtype=np.int32)
     own_out = np.empty((n, top_k), dtype=np.int32)
     gaps = np.empty(n, dtype=np.float64)
+    ogaps = np.empty(n, dtype=np.float64)
     r_all = x @ w_router.T
     for t in range(n):
         r = r_all[t]
         idx, w, gap = moe_gate(r, top_k)
         own_out[t] = idx
+        ogaps[t] = moe_order_gap(r, idx)
         if forced_idx is not None:
             idx = np.asarray(forced_idx[t], dtype=np.int32)
             p = np.exp(r - r.max())
@@ -138,7 +147,7 @@ def moe_ffn_bruteforce(x: np.ndarray, w_router: np.ndarray, w_gate: np.ndarray, 
             y[t] += w[j] * swiglu_ffn(x[t:t + 1], w_gate[e], w_up[e], w_down[e])[0]
         idx_out[t] = idx
         gaps[t] = gap
-    return y, idx_out, gaps, own_out
+    return y, idx_out, gaps, own_out, ogaps
 
 
 def moe_ffn(x: np.ndarray, w_router: np.ndarray, w_gate: np.ndarray, w_up: np.ndarray, w_down: np.ndarray,
@@ -153,10 +162,12 @@ def moe_ffn(x: np.ndarray, w_router: np.ndarray, w_gate: np.ndarray, w_up: np.nd
     own_out = np.empty((n, top_k), dtype=np.int32)
     w_out = np.empty((n, top_k), dtype=x.dtype)
     gaps = np.empty(n, dtype=np.float64)
+    ogaps = np.empty(n, dtype=np.float64)
     for t in range(n):
         r = r_all[t]
         idx, w, gaps[t] = moe_gate(r, top_k)
         own_out[t] = idx
+        ogaps[t] = moe_order_gap(r, idx)
         if forced_idx is not None:
             idx = np.asarray(forced_idx[t], dtype=np.int32)
             p = np.exp(r - r.max())
@@ -168,7 +179,7 @@ def moe_ffn(x: np.ndarray, w_router: np.ndarray, w_gate: np.ndarray, w_up: np.nd
         for e in np.unique(idx_out[:, j]):
             rows = np.nonzero(idx_out[:, j] == e)[0]
             y[rows] += w_out[rows, j:j + 1] * swiglu_ffn(x[rows], w_gate[e], w_up[e], w_down[e])
-    return y, idx_out, gaps, own_out
+    return y, idx_out, gaps, own_out, ogaps
 
 
 def log_softmax(z: np.ndarray) -> np.ndarray:

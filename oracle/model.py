@@ -4,7 +4,7 @@ paged-KV rollout (test infrastructure; see package docstring).
 Two independent formulations of the same function are kept on purpose:
 `forward_full` recomputes every position of a sequence with full causal attention;
 `OracleRollout` carries a paged key/value store across prefill chunks, decode
-steps and turns (per-session state that persists across turns, paper Sec. 4.3).
+steps and turns (per-session state that persists across turns, paper Sec. 4.2).
 Their agreement is one of the pins.
 """
 from __future__ import annotations
@@ -122,8 +122,9 @@ def _qkv(shape: ModelShape, w: Dict[str, np.ndarray], h: np.ndarray, pos: np.nda
 def _ffn(shape: ModelShape, w: Dict[str, np.ndarray], h: np.ndarray, forced_idx: Optional[np.ndarray]):
     x = L.rmsnorm(h, w["ffn_norm"], shape.rms_eps)
     if shape.is_moe:
-        y, idx, gap, own = L.moe_ffn(x, w["w_router"], w["w_gate"], w["w_up"], w["w_down"], shape.top_k, forced_idx)
-        return h + y, idx, gap, own
+        y, idx, gap, own, ogap = L.moe_ffn(x, w["w_router"], w["w_gate"], w["w_up"], w["w_down"], shape.top_k,
+                                           forced_idx)
+        return h + y, idx, (gap, ogap), own
     return h + L.swiglu_ffn(x, w["w_gate"], w["w_up"], w["w_down"]), None, None, None
 
 
@@ -148,7 +149,8 @@ def forward_full(model: OracleModel, tokens: Sequence[np.ndarray], embeds: Seque
     logits are wanted (None = all).  Returns per sequence a dict with
       logits  [len(logits_at[i]), V]   logits predicting the token AFTER each listed position
       routing [n_i, L, K] int32 (experts used), own_routing (the router's own choice, which
-      differs from routing only under replay), gate_gap [n_i, L]   (MoE only)
+      differs from routing only under replay), gate_gap [n_i, L] (K-th minus (K+1)-th gate logit) and
+      order_gap [n_i, L] (smallest gap between consecutive chosen logits)   (MoE only)
     """
     s = model.shape
     nseq = len(tokens)
@@ -158,6 +160,7 @@ def forward_full(model: OracleModel, tokens: Sequence[np.ndarray], embeds: Seque
     routing = [np.zeros((len(tokens[i]), s.n_layers, max(s.top_k, 1)), np.int32) for i in range(nseq)]
     own = [np.zeros((len(tokens[i]), s.n_layers, max(s.top_k, 1)), np.int32) for i in range(nseq)]
     gaps = [np.full((len(tokens[i]), s.n_layers), np.inf) for i in range(nseq)]
+    ogaps = [np.full((len(tokens[i]), s.n_layers), np.inf) for i in range(nseq)]
     for l in range(s.n_layers):
         w = model.layer(l)
         for i in range(nseq):
@@ -171,7 +174,7 @@ def forward_full(model: OracleModel, tokens: Sequence[np.ndarray], embeds: Seque
             if idx is not None:
                 routing[i][:, l, :] = idx
                 own[i][:, l, :] = own_idx
-                gaps[i][:, l] = gap
+                gaps[i][:, l], ogaps[i][:, l] = gap
             hs[i] = h
         if progress:
             progress(l)
@@ -181,6 +184,7 @@ def forward_full(model: OracleModel, tokens: Sequence[np.ndarray], embeds: Seque
         res = {"logits": _logits(model, hs[i][at]), "positions": at}
         if s.is_moe:
             res["routing"], res["gate_gap"], res["own_routing"] = routing[i], gaps[i], own[i]
+            res["order_gap"] = ogaps[i]
         out.append(res)
     return out
 
@@ -277,6 +281,7 @@ class OracleRollout:
         routing = [np.zeros((len(toks[j]), s.n_layers, max(s.top_k, 1)), np.int32) for j in range(len(seq_ids))]
         own = [np.zeros((len(toks[j]), s.n_layers, max(s.top_k, 1)), np.int32) for j in range(len(seq_ids))]
         gaps = [np.full((len(toks[j]), s.n_layers), np.inf) for j in range(len(seq_ids))]
+        ogaps = [np.full((len(toks[j]), s.n_layers), np.inf) for j in range(len(seq_ids))]
         for l in range(s.n_layers):
             w = m.layer(l)
             for j, i in enumerate(seq_ids):
@@ -294,10 +299,11 @@ class OracleRollout:
                 if idx is not None:
                     routing[j][:, l, :] = idx
                     own[j][:, l, :] = own_idx
-                    gaps[j][:, l] = gap
+                    gaps[j][:, l], ogaps[j][:, l] = gap
                 hs[j] = h
         for j, i in enumerate(seq_ids):
             self.ctx[i] += hs[j].shape[0]
+        self._order_gaps = ogaps          # of the call just made, read by the two public steps
         return hs, routing, gaps, own
 
     def _emit(self, i: int, z: np.ndarray, forced: Optional[int]):
@@ -329,7 +335,7 @@ class OracleRollout:
         forced_tokens = forced_tokens if forced_tokens is not None else [None] * n
         hs, routing, gaps, own = self._advance(seq_ids, toks, embeds, forced_routing)
         out = {"tokens": [], "logprobs": [], "sampled": [], "routing": routing, "gate_gap": gaps,
-               "own_routing": own, "logits": []}
+               "own_routing": own, "order_gap": self._order_gaps, "logits": []}
         for j, i in enumerate(seq_ids):
             if sample_last[j]:
                 z = _logits(self.model, hs[j][-1:])[0]
@@ -358,12 +364,14 @@ class OracleRollout:
         fr = None if forced_routing is None else [forced_routing[j] for j in live]
         hs, routing, gaps, own = self._advance(ids, toks, [None] * len(ids), fr)
         out = {"tokens": [s.pad_token_id] * n, "logprobs": [0.0] * n, "sampled": [-1] * n,
-               "routing": [None] * n, "gate_gap": [None] * n, "own_routing": [None] * n, "logits": [None] * n}
+               "routing": [None] * n, "gate_gap": [None] * n, "own_routing": [None] * n, "order_gap": [None] * n,
+               "logits": [None] * n}
         for jj, j in enumerate(live):
             i = seq_ids[j]
             z = _logits(self.model, hs[jj][-1:])[0]
             tok, lp, smp = self._emit(i, z, forced_tokens[j])
             out["tokens"][j], out["logprobs"][j], out["sampled"][j] = tok, lp, smp
             out["routing"][j], out["gate_gap"][j], out["own_routing"][j] = routing[jj], gaps[jj], own[jj]
+            out["order_gap"][j] = self._order_gaps[jj]
             out["logits"][j] = z if want_logits else None
         return out

@@ -46,7 +46,7 @@ __global__ void meta_prefill_kernel(TokenMeta m, int n_seqs, int total, const in
   }
   for (int i = threadIdx.x; i < n_seqs; i += blockDim.x) {
     int len = cu[i + 1] - cu[i];
-    m.sample_row[i] = len > 0 ? cu[i + 1] - 1 : 0;
+    m.sample_row[i] = len > 0 ? cu[i + 1] - 1 : -1;   // -1: no row (the final norm writes zeros, nothing is emitted)
     m.sample_pos[i] = ctx[i] + len;
     m.sample_on[i] = (sample_last && sample_last[i] && len > 0) ? 1 : 0;
   }
@@ -120,8 +120,21 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(NormArgs a) {
   __shared__ float sh[4];
   const int r = blockIdx.x;
   const int t = a.rows ? a.rows[r] : r;
-  float* hrow = a.h + (size_t)t * a.d;
   const int nv = a.d >> 2;
+  if (t < 0) {
+    // no source row (a sequence that brought no token to this call): the output row is zero and the residual
+    // stream is left alone.  Uniform over the workgroup, before any barrier.
+    for (int i = threadIdx.x; i < nv; i += 256) {
+      const int k = 4 * i;
+      h16_t* xo = a.x.p + frag_act_offset(r, k & ~7, 0, a.x.mtiles(), a.x.planes) + (k & 7);
+      const u32x2 z = {0u, 0u};
+      *reinterpret_cast<u32x2*>(xo) = z;
+      if (a.x.planes == 2) *reinterpret_cast<u32x2*>(xo + 512) = z;
+      if (a.xf) *reinterpret_cast<f32x4*>(a.xf + (size_t)r * a.d + 4 * i) = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    return;
+  }
+  float* hrow = a.h + (size_t)t * a.d;
   const bool adding = (a.add != nullptr) || (a.moe_y != nullptr);
   const int mtiles = a.x.mtiles();
   const bool single = nv <= 256 * NV;

@@ -74,17 +74,24 @@ __device__ __forceinline__ void wave_topk(const RouterArgs& a, int t, int lane, 
   const int32_t* replay = a.replay_idx ? a.replay_idx + ((size_t)t * a.n_layers + a.layer) * a.top_k : nullptr;
   for (int k = 0; k < a.top_k; ++k) {
     float bv = -INFINITY; int bi = 0x7FFFFFFF;
+    bool given = false;                                        // uniform over the wave
     if (replay) {
       // routing replay (paper Sec. 5.5): the expert is given; its weight still comes from this layer's own gate
-      // logits, renormalised over the replayed set.  An id outside [0, E) falls back to expert 0.
+      // logits, renormalised over the replayed set.  An id outside [0, E), or one already taken by an earlier
+      // slot of this token (its entry of v is -inf by then), is not used: the slot falls back to the layer's own
+      // best expert not yet taken, so that a token never reaches an expert twice.
       bi = replay[k];
-      if (bi < 0 || bi >= a.E) bi = 0;
-      float mine = -INFINITY;
+      if (bi >= 0 && bi < a.E) {
+        float mine = -INFINITY;
 #pragma unroll
-      for (int j = 0; j < MAX_E / 64; ++j)
-        if (j == (bi >> 6)) mine = v[j];
-      bv = __shfl(mine, bi & 63, WAVE);
-    } else {
+        for (int j = 0; j < MAX_E / 64; ++j)
+          if (j == (bi >> 6)) mine = v[j];
+        bv = __shfl(mine, bi & 63, WAVE);
+        given = bv != -INFINITY;
+      }
+    }
+    if (!given) {
+      bv = -INFINITY; bi = 0x7FFFFFFF;
 #pragma unroll
       for (int j = 0; j < MAX_E / 64; ++j)
         if (v[j] > bv) { bv = v[j]; bi = lane + 64 * j; }      // ascending id within the lane
@@ -97,7 +104,7 @@ __device__ __forceinline__ void wave_topk(const RouterArgs& a, int t, int lane, 
     const float ev = __expf(bv - mx);
     denom += ev;
     if (lane == k) { my_e = ev; my_i = bi; }
-    if (!replay && (bi & 63) == lane) {
+    if ((bi & 63) == lane) {
 #pragma unroll
       for (int j = 0; j < MAX_E / 64; ++j)
         if (j == (bi >> 6)) v[j] = -INFINITY;

@@ -5,7 +5,7 @@ prompt-prefix sharing and batch compaction.
 Everything numerical happens inside librelax_rollout.so; this module only owns
 memory (torch tensors) and integer bookkeeping.  The rollout stage it implements
 is the one described in paper Sec. 3.1/3.3 (generation producing responses and
-log-probabilities as per-sample fields), Sec. 4.3 (multi-turn sessions whose state
+log-probabilities as per-sample fields), Sec. 4.2 (multi-turn sessions whose state
 persists across turns) and Sec. 5.5 (expert indices recorded per MoE layer per
 token for routing replay).
 """
@@ -298,6 +298,24 @@ class RolloutEngine:
         self._release(self.block_lists[row])
         self.block_lists[row] = []
         self.finished[row] = 1
+        self._leave_group(row)
+
+    def _leave_group(self, row: int) -> None:
+        """The row stops sharing pages with its sampling group (its pages are released or replaced): it becomes a
+        group of its own, and what is left of the group is cut into the runs before and after it, each led by its
+        first row (a group is a run of consecutive rows, see rlx_shared_prefix_build)."""
+        root = self.leader[row]
+        members = [r for r in range(self.n) if self.leader[r] == root]
+        if len(members) > 1:
+            after = [r for r in members if r > row]
+            for r in after:
+                self.leader[r] = after[0]
+            for part in ([r for r in members if r < row], after):
+                if len(part) == 1:
+                    self.shared_pages[part[0]] = 0
+        self.leader[row] = row
+        self.shared_pages[row] = 0
+        self._sp_dirty = True
 
     # ---- steps ---------------------------------------------------------------
     def prefill(self, rows: Sequence[int], toks: Sequence[np.ndarray], embeds: Sequence[Optional[np.ndarray]] = None,

@@ -13,7 +13,7 @@ layer at a time.
 
 The workloads stand in for the datasets the paper trains on (math prompts with
 long chain-of-thought responses, Sec. 5.3; multimodal clips, Sec. 5.2; multi-turn
-tool use, Sec. 4.3): only their length mix and structure are mirrored; token ids
+tool use, Sec. 4.2): only their length mix and structure are mirrored; token ids
 are uniform random.
 """
 from __future__ import annotations

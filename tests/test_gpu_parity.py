@@ -122,10 +122,11 @@ def routing_flips(gsteps, osteps, key):
     return n
 
 
-def compare_rollouts(gsteps, osteps, wl, is_moe):
+def compare_rollouts(gsteps, osteps, wl, is_moe, routing_report_only=False):
     """Element-by-element comparison; returns statistics.  Routing: the GPU's expert set must equal
-    the oracle router's own choice at every (token, layer) unless the oracle's gate gap is a near-tie."""
-    stats = dict(dlogit=0.0, dlogprob=0.0, draws=0, draw_diff=0, routes=0, tie_flips=0)
+    the oracle router's own choice at every (token, layer) unless the oracle's gate gap is a near-tie
+    (routing_report_only: differences are counted with their gaps and not asserted)."""
+    stats = dict(dlogit=0.0, dlogprob=0.0, draws=0, draw_diff=0, routes=0, tie_flips=0, max_flip_gap=0.0)
     plen = wl.prompt_lens
     for s, (g, o) in enumerate(zip(gsteps, osteps)):
         for j in range(wl.batch):
@@ -151,21 +152,32 @@ def compare_rollouts(gsteps, osteps, wl, is_moe):
                 stats["routes"] += bad.size
                 stats["tie_flips"] += int(bad.sum())
                 gaps = o["gate_gap"][j]
+                if bad.any():
+                    stats["max_flip_gap"] = max(stats["max_flip_gap"], float(gaps[bad].max()))
+                if routing_report_only:
+                    continue
                 assert (gaps[bad] < TIE_GAP).all(), "%s: routing differs where the oracle's gate gap is %.2e" % (
                     tag, float(gaps[bad].max()))
-                # descending-probability order of the emitted ids, wherever the sets agree
+                # the emitted ids are in descending gate probability (slot k weighs expert k of the list): the whole
+                # ordered list equals the oracle's wherever the sets agree and no two of the oracle's chosen logits
+                # are closer than the tie gap; the first id wherever the sets agree
                 same = ~bad
                 np.testing.assert_array_equal(g["routing"][j][same][..., 0], o["own_routing"][j][same][..., 0])
+                ordered = same & (o["order_gap"][j] >= TIE_GAP)
+                stats["ordered"] = stats.get("ordered", 0) + int(ordered.sum())
+                np.testing.assert_array_equal(g["routing"][j][ordered], o["own_routing"][j][ordered])
     assert stats["draw_diff"] <= 0.01 * stats["draws"] + 1
     return stats
 
 
 def teacher_forced_parity(pkg, synthetic, shape, wl, n_decode, split, model_seed=0, attention_grid=None, osteps=None,
-                          fmt="bf16"):
+                          fmt="bf16", kv_bf16=True):
     """Free-running oracle rollout -> GPU teacher-forced on its tokens -> compare.  If the GPU took a
     different expert set anywhere, the oracle is re-run replaying the GPU's routing (the paper's routing
-    replay) so that everything downstream of a tolerated near-tie can still be checked."""
-    omodel = O.OracleModel(shape, model_seed, fmt=fmt)
+    replay) so that everything downstream of a tolerated near-tie can still be checked.
+    kv_bf16=False: the oracle keeps keys and values in fp32 (no rounding at the store); the logit and
+    log-probability bars are asserted, routing differences are reported with their gaps."""
+    omodel = O.OracleModel(shape, model_seed, fmt=fmt, kv_bf16=kv_bf16)
     if osteps is None:
         say("%s: oracle rollout" % shape.name)
         osteps = oracle_rollout(omodel, wl, n_decode)
@@ -183,11 +195,11 @@ def teacher_forced_parity(pkg, synthetic, shape, wl, n_decode, split, model_seed
         n_replayed = routing_flips(gsteps, osteps, "routing")
         say("%s: %d (token, layer) routing differences -> oracle replay of the GPU's routing" % (shape.name, n_replayed))
         osteps = oracle_rollout(omodel, wl, n_decode, forced=forced, replay=[g["routing"] for g in gsteps])
-    stats = compare_rollouts(gsteps, osteps, wl, shape.is_moe)
+    stats = compare_rollouts(gsteps, osteps, wl, shape.is_moe, routing_report_only=not kv_bf16)
     stats["replayed"] = n_replayed
     ctx = eng.ctx_lens[:wl.batch].cpu().numpy()
     assert list(ctx) == list(wl.prompt_lens + n_decode - 1)
-    say("%s %s split=%d stats %s" % (shape.name, fmt, split, stats))
+    say("%s %s split=%d %s stats %s" % (shape.name, fmt, split, "bf16-KV oracle" if kv_bf16 else "fp32-KV oracle", stats))
     model.close()
     return stats
 
@@ -200,6 +212,23 @@ def test_teacher_forced_rollout_parity(amd, shape_name, split):
              "tiny_moe": RI.TINY_MOE}[shape_name]
     wl = RI.workload_tiny(shape, n_decode=32)
     teacher_forced_parity(pkg, synthetic, shape, wl, 32, split)
+
+
+@pytest.mark.parametrize("shape_name", ["tiny_dense", "tiny_dense_qkn", "tiny_moe"])
+def test_distance_to_the_oracle_that_keeps_kv_in_fp32(amd, shape_name):
+    """The library stores keys and values as bf16 (the workloads' "paged KV bf16"); the oracle the other tests
+    compare with rounds them at the store too.  Here the oracle keeps them in fp32: the logit and log-probability
+    bars hold against it as well; expert sets that differ from that oracle's own choice are counted and their
+    largest gate gap printed (the store's rounding moves gate logits by about 2e-3, more than the 1e-3 tie rule,
+    so for routing this is a report, not a bar)."""
+    pkg, synthetic = amd
+    shape = {"tiny_dense": RI.TINY_DENSE, "tiny_dense_qkn": RI.TINY_DENSE.replace(name="tiny_dense_qkn", qk_norm=True),
+             "tiny_moe": RI.TINY_MOE}[shape_name]
+    wl = RI.workload_tiny(shape, n_decode=32)
+    stats = teacher_forced_parity(pkg, synthetic, shape, wl, 32, 1, kv_bf16=False)
+    say("DISTANCE to the fp32-KV oracle, %s: max |dlogit| %.5f, max |dlogprob| %.5f, routing differences %d of %d "
+        "(largest oracle gap among them %.2e)" % (shape.name, stats["dlogit"], stats["dlogprob"], stats["tie_flips"],
+                                                  stats["routes"], stats["max_flip_gap"]))
 
 
 # Routing bar of the fp16 option with one term per activation: the router's input carries a relative rounding

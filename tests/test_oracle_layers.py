@@ -144,13 +144,21 @@ def test_moe_ffn_grouped_equals_bruteforce_and_dense_special_case():
     e, d, f, k, n = 16, 12, 10, 4, 9
     wr, wg, wu, wd = _experts(e, d, f)
     x = RNG.standard_normal((n, d))
-    y, idx, gap, own = O.moe_ffn(x, wr, wg, wu, wd, k)
-    yb, idxb, gapb, ownb = O.moe_ffn_bruteforce(x, wr, wg, wu, wd, k)
+    y, idx, gap, own, ogap = O.moe_ffn(x, wr, wg, wu, wd, k)
+    yb, idxb, gapb, ownb, ogapb = O.moe_ffn_bruteforce(x, wr, wg, wu, wd, k)
     np.testing.assert_array_equal(own, idx)
     np.testing.assert_array_equal(ownb, idx)
     np.testing.assert_array_equal(idx, idxb)
     np.testing.assert_allclose(y, yb, rtol=1e-10, atol=1e-12)
     np.testing.assert_allclose(gap, gapb)
+    # margin of the emitted order: the smallest step of the chosen logits, by hand from a full sort
+    r_all = x @ wr.T
+    for t in range(n):
+        srt = np.sort(r_all[t])[::-1][:k]
+        np.testing.assert_allclose(ogap[t], np.diff(srt).__neg__().min(), rtol=1e-12)
+    np.testing.assert_allclose(ogap, ogapb)
+    assert O.moe_order_gap(np.array([0.5, 3.0, 1.0]), np.array([1, 2, 0])) == 0.5
+    assert O.moe_order_gap(np.array([2.0]), np.array([0])) == float("inf")
     # identical experts: mixture weights sum to one, so the layer equals one dense FFN
     wg1, wu1, wd1 = (np.repeat(a[:1], e, axis=0) for a in (wg, wu, wd))
     y1 = O.moe_ffn(x, wr, wg1, wu1, wd1, k)[0]
@@ -166,12 +174,12 @@ def test_moe_replay():
     e, d, f, k, n = 16, 12, 10, 4, 6
     wr, wg, wu, wd = _experts(e, d, f)
     x = RNG.standard_normal((n, d))
-    y, idx, _, _ = O.moe_ffn(x, wr, wg, wu, wd, k)
-    y2, idx2, _, _ = O.moe_ffn(x, wr, wg, wu, wd, k, forced_idx=idx)       # own indices: idempotent
+    y, idx, _, _, _ = O.moe_ffn(x, wr, wg, wu, wd, k)
+    y2, idx2, _, _, _ = O.moe_ffn(x, wr, wg, wu, wd, k, forced_idx=idx)       # own indices: idempotent
     np.testing.assert_array_equal(idx, idx2)
     np.testing.assert_allclose(y, y2, rtol=1e-12)
     other = (idx + 1) % e
-    y3, idx3, _, own3 = O.moe_ffn(x, wr, wg, wu, wd, k, forced_idx=other)
+    y3, idx3, _, own3, _ = O.moe_ffn(x, wr, wg, wu, wd, k, forced_idx=other)
     np.testing.assert_array_equal(idx3, other)
     np.testing.assert_array_equal(own3, idx)                  # the router's own choice is still reported
     assert np.abs(y3 - y).max() > 1e-3
