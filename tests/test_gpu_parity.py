@@ -199,7 +199,7 @@ def teacher_forced_parity(pkg, synthetic, shape, wl, n_decode, split, model_seed
     stats["replayed"] = n_replayed
     ctx = eng.ctx_lens[:wl.batch].cpu().numpy()
     assert list(ctx) == list(wl.prompt_lens + n_decode - 1)
-    say("%s %s split=%d %s stats %s" % (shape.name, fmt, split, "bf16-KV oracle" if kv_bf16 else "fp32-KV oracle", stats))
+    say("%s %s split=%d %s stats %s" % (shape.name, fmt, split, "rounded-KV oracle" if kv_bf16 else "fp32-KV oracle", stats))
     model.close()
     return stats
 
