@@ -257,6 +257,19 @@ class OracleRollout:
         self.last_token[i] = self.last_token[src]
         return i
 
+    def set_cache(self, i: int, keys: np.ndarray, values: np.ndarray, last_token: int) -> None:
+        """Give sequence i a cache of given contents instead of computing it: keys, values [L, n, Hkv, hd] (stored
+        through the model's KV rounding) become its positions 0..n-1 and `last_token` the token its next decode
+        step consumes.  For timing the decode step at a chosen context length without paying the prefill."""
+        n = keys.shape[1]
+        assert self.ctx[i] == 0 and keys.shape == values.shape
+        blk, slot = self._slots(i, 0, n)
+        rnd = self.model.kv_round or (lambda a: a)
+        self.kpool[:, blk, slot] = rnd(np.asarray(keys, self.model.dtype))
+        self.vpool[:, blk, slot] = rnd(np.asarray(values, self.model.dtype))
+        self.ctx[i] = n
+        self.last_token[i] = int(last_token)
+
     def _slots(self, i: int, p0: int, n: int):
         """(block id, slot) for positions p0..p0+n-1 of sequence i, allocating blocks."""
         need = (p0 + n + self.bs - 1) // self.bs

@@ -323,3 +323,20 @@ def test_weight_refresh_keeps_the_store_and_uses_the_new_weights():
     z_mid = rollout(A, B_all, k, forced)[k][0]
     z_b = O.forward_full(B_all, [seq])[0]["logits"][len(tok) - 1 + k]
     assert np.abs(z_mid - z_b).max() > 1e-3 and np.abs(z_mid - za[k]).max() > 1e-3
+
+
+def test_a_cache_given_from_outside_continues_like_the_one_computed():
+    """set_cache (used to time a decode step at a chosen context length): the keys and values a real prefill
+    stored, handed to a fresh rollout, give the same next step bit for bit."""
+    m = O.OracleModel(DENSE, 3)
+    t = _prompts(DENSE, (21,))
+    a = O.OracleRollout(m, 8)
+    i = a.add_sequence(5)
+    r = a.prefill_chunk([i], t)
+    kv = [a._gather(l, i, 21) for l in range(DENSE.n_layers)]
+    b = O.OracleRollout(m, 8, alloc_order=[5, 2, 7, 0, 1, 3, 4, 6])
+    j = b.add_sequence(5)
+    b.set_cache(j, np.stack([k for k, _ in kv]), np.stack([v for _, v in kv]), r["tokens"][0])
+    ra, rb = a.decode_step([i], want_logits=True), b.decode_step([j], want_logits=True)
+    np.testing.assert_array_equal(ra["logits"][0], rb["logits"][0])
+    assert ra["tokens"] == rb["tokens"] and ra["logprobs"] == rb["logprobs"] and b.ctx[j] == 22
