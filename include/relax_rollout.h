@@ -293,6 +293,27 @@ RLX_API int rollout_decode_step(const rlx_model* m, void* kv_pool, int64_t n_blo
                         int32_t* out_sampled, int32_t* out_routing, float* out_logits, void* stream);
 
 /*
+ * rollout_decode_step for callers that cannot allocate device memory or keep a workspace of their own: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  The step's scratch is a fixed array
+ * of RLX_STATIC_WORKSPACE_BYTES that every GPU the library runs on holds from the moment the library's code is
+ * loaded there until the process ends; the call allocates nothing, frees nothing and does not synchronise.
+ * Arguments and results are those of rollout_decode_step without workspace / workspace_bytes; the model's device
+ * must be the current device (as for every call).
+ *   RLX_ENOMEM  the step needs more scratch than the array holds (rlx_workspace_bytes(m, n_seqs, n_seqs, ...) >
+ *               RLX_STATIC_WORKSPACE_BYTES): nothing is enqueued; use rollout_decode_step with a workspace.
+ * All calls on one GPU share that GPU's array: two calls of this entry point whose work overlaps in time on the
+ * same GPU (different streams, or different threads) race on it and give undefined results; calls on one stream
+ * are ordered and safe.  The array keeps the previous call's contents; no call depends on them.
+ */
+#define RLX_STATIC_WORKSPACE_BYTES (128u << 20)
+RLX_API int rollout_decode_step_static(const rlx_model* m, void* kv_pool, int64_t n_blocks, int32_t n_seqs,
+                        int32_t* tokens_inout, int32_t* ctx_lens_inout, const int32_t* block_table,
+                        int32_t max_blocks_per_seq, const uint64_t* seeds, const float* temperature,
+                        const int32_t* max_ctx_len, uint8_t* finished_inout, const int32_t* forced_tokens,
+                        float* out_logprobs, int32_t* out_sampled, int32_t* out_routing, float* out_logits,
+                        void* stream);
+
+/*
  * Decode over shared prompt prefixes.  Sequences of one sampling group (the G responses drawn for one prompt by
  * the group-relative algorithms of paper Sec. 2.1, e.g. 8 per prompt) list the same physical pages for their
  * prompt in their block-table rows.  rollout_decode_step reads those pages once per sequence; with a descriptor

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "librelax_rollout.so")
 RLX_OK, RLX_EINVAL, RLX_ENOMEM, RLX_EHIP, RLX_EUNSUPPORTED = 0, -1, -2, -3, -4
 
 EXPORTS = ["rlx_packed_weight_bytes", "rlx_pack_weight", "rlx_pack_gate_up", "rlx_model_create", "rlx_model_destroy", "rlx_model_set_attention_grid", "rlx_model_set_weights", "rlx_model_weight_version", "rlx_kv_pool_bytes", "rlx_workspace_bytes",
-           "rlx_kv_copy_blocks", "rollout_prefill_chunk", "rollout_score_chunk", "rollout_decode_step", "rollout_decode_step_shared", "rlx_shared_prefix_bytes", "rlx_shared_prefix_build",
+           "rlx_kv_copy_blocks", "rollout_prefill_chunk", "rollout_score_chunk", "rollout_decode_step", "rollout_decode_step_static", "rollout_decode_step_shared", "rlx_shared_prefix_bytes", "rlx_shared_prefix_build",
            "rlx_op_linear",
            "rlx_profile_kernel", "rlx_last_error"]
 
@@ -82,6 +82,7 @@ def lib() -> C.CDLL:
         l.rollout_prefill_chunk.argtypes = [vp, vp, i64, vp, sz, i32, i32] + [vp] * 5 + [i32] + [vp] * 12
         l.rollout_score_chunk.argtypes = [vp, vp, i64, vp, sz, i32, i32] + [vp] * 5 + [i32] + [vp] * 6
         l.rollout_decode_step.argtypes = [vp, vp, i64, vp, sz, i32, vp, vp, vp, i32] + [vp] * 10
+        l.rollout_decode_step_static.argtypes = [vp, vp, i64, i32, vp, vp, vp, i32] + [vp] * 10
         l.rollout_decode_step_shared.argtypes = [vp, vp, i64, vp, sz, i32, vp, vp, vp, i32] + [vp] * 11
         l.rlx_shared_prefix_bytes.argtypes = [vp, i32, C.POINTER(sz)]
         l.rlx_shared_prefix_build.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), vp, sz, vp]
@@ -233,6 +234,22 @@ def rollout_decode_step(model, kv_pool, n_blocks, workspace, n_seqs, tokens_inou
                         out_logprobs, out_sampled=None, out_routing=None, out_logits=None, stream=None) -> None:
     _check(lib().rollout_decode_step(
         model, _ptr(kv_pool), n_blocks, _ptr(workspace), workspace.numel() * workspace.element_size(), n_seqs,
+        _ptr(tokens_inout, torch.int32), _ptr(ctx_lens_inout, torch.int32), _ptr(block_table, torch.int32),
+        max_blocks_per_seq, _ptr(seeds, torch.int64), _ptr(temperature, torch.float32),
+        _ptr(max_ctx_len, torch.int32), _ptr(finished_inout, torch.uint8), _ptr(forced_tokens, torch.int32),
+        _ptr(out_logprobs, torch.float32), _ptr(out_sampled, torch.int32), _ptr(out_routing, torch.int32),
+        _ptr(out_logits, torch.float32), _stream(stream)))
+
+
+RLX_STATIC_WORKSPACE_BYTES = 128 << 20
+
+
+def rollout_decode_step_static(model, kv_pool, n_blocks, n_seqs, tokens_inout, ctx_lens_inout, block_table,
+                               max_blocks_per_seq, seeds, temperature, max_ctx_len, finished_inout, forced_tokens,
+                               out_logprobs, out_sampled=None, out_routing=None, out_logits=None, stream=None) -> None:
+    """rollout_decode_step on the library's fixed scratch array (no workspace argument, nothing allocated)."""
+    _check(lib().rollout_decode_step_static(
+        model, _ptr(kv_pool), n_blocks, n_seqs,
         _ptr(tokens_inout, torch.int32), _ptr(ctx_lens_inout, torch.int32), _ptr(block_table, torch.int32),
         max_blocks_per_seq, _ptr(seeds, torch.int64), _ptr(temperature, torch.float32),
         _ptr(max_ctx_len, torch.int32), _ptr(finished_inout, torch.uint8), _ptr(forced_tokens, torch.int32),

@@ -6,6 +6,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -51,6 +52,32 @@ ProfState g_prof;
 
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
+// Fixed scratch for callers that cannot allocate (rollout_decode_step_static): one array per GPU, resident from
+// the moment the library's code is loaded on that GPU until the process ends.  Host code never uses the array's
+// name as an address: scratch_on_device() asks the runtime once per device, with that device current, where that
+// device's copy lives, and every launch receives the pointer it returned.
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[RLX_STATIC_WORKSPACE_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// device `dev` must be the current device
+hipError_t scratch_on_device(int dev, void** out) {
+  *out = nullptr;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace
@@ -64,6 +91,7 @@ struct rlx_model {
   int n_units;        // compute units of the device
   int attn_wgs;       // decode attention grid: two workgroups per compute unit
   uint64_t weight_version;   // tag of the installed weights (rlx_model_set_weights)
+  void* static_ws;           // this device's fixed scratch array (rollout_decode_step_static)
 };
 
 namespace {
@@ -395,6 +423,7 @@ int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* wt, rlx_mod
   if (!m) return fail(RLX_ENOMEM, "host allocation failed");
   m->cfg = c;
   m->inv_freq = nullptr;
+  m->static_ws = nullptr;
   m->weight_version = 0;
   const int rc = install_weights(m, wt);
   if (rc != RLX_OK) {
@@ -410,6 +439,11 @@ int rlx_model_create(const rlx_model_config* cfg, const rlx_weights* wt, rlx_mod
   m->n_units = n_cu > 0 ? n_cu : 1;
   gemm_set_units(m->n_units);
   m->attn_wgs = 2 * n_cu < ATTN_WGS_MAX ? (2 * n_cu > 0 ? 2 * n_cu : 1) : ATTN_WGS_MAX;
+  if (e == hipSuccess && scratch_on_device(m->device, &m->static_ws) != hipSuccess) {
+    // checked, not fatal: the model works with caller workspaces; rollout_decode_step_static reports the missing array
+    m->static_ws = nullptr;
+    (void)hipGetLastError();
+  }
   if (e == hipSuccess) e = hipMalloc((void**)&m->inv_freq, inv.size() * sizeof(double));
   if (e == hipSuccess) e = hipMemcpy(m->inv_freq, inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice);
   if (e != hipSuccess) {
@@ -577,6 +611,28 @@ int rollout_decode_step(const rlx_model* m, void* kv_pool, int64_t n_blocks, voi
                                     ctx_lens_inout, block_table, max_blocks_per_seq, seeds, temperature, max_ctx_len,
                                     finished_inout, forced_tokens, out_logprobs, out_sampled, out_routing, out_logits,
                                     nullptr, stream);
+}
+
+int rollout_decode_step_static(const rlx_model* m, void* kv_pool, int64_t n_blocks, int32_t n_seqs,
+                               int32_t* tokens_inout, int32_t* ctx_lens_inout, const int32_t* block_table,
+                               int32_t max_blocks_per_seq, const uint64_t* seeds, const float* temperature,
+                               const int32_t* max_ctx_len, uint8_t* finished_inout, const int32_t* forced_tokens,
+                               float* out_logprobs, int32_t* out_sampled, int32_t* out_routing, float* out_logits,
+                               void* stream) {
+  if (!m) return fail(RLX_EINVAL, "model is NULL");
+  if (n_seqs <= 0 || n_seqs > (1 << 16)) return fail(RLX_EINVAL, "n_seqs %d out of range", n_seqs);
+  if (max_blocks_per_seq <= 0 || max_blocks_per_seq > (1 << 20))
+    return fail(RLX_EINVAL, "max_blocks_per_seq %d out of range", max_blocks_per_seq);
+  const size_t need = carve(m->cfg, nullptr, n_seqs, n_seqs, max_blocks_per_seq).bytes;
+  if (need > (size_t)RLX_STATIC_WORKSPACE_BYTES)
+    return fail(RLX_ENOMEM, "rollout_decode_step_static: a step of %d sequences of this model needs %zu bytes of "
+                "scratch, the fixed array holds %zu; use rollout_decode_step with a workspace of your own", n_seqs,
+                need, (size_t)RLX_STATIC_WORKSPACE_BYTES);
+  if (!m->static_ws) return fail(RLX_EHIP, "rollout_decode_step_static: the fixed scratch array has no address");
+  return rollout_decode_step_shared(m, kv_pool, n_blocks, m->static_ws, (size_t)RLX_STATIC_WORKSPACE_BYTES, n_seqs,
+                                    tokens_inout, ctx_lens_inout, block_table, max_blocks_per_seq, seeds, temperature,
+                                    max_ctx_len, finished_inout, forced_tokens, out_logprobs, out_sampled, out_routing,
+                                    out_logits, nullptr, stream);
 }
 
 int rlx_shared_prefix_bytes(const rlx_model* m, int32_t n_seqs, size_t* bytes_out) {
