@@ -44,23 +44,7 @@ def log(msg):
 def gpu_random_model(pkg, synthetic, shape, split, seed=0, fmt="bf16"):
     """Random-init weights of the named shape generated on the device (same distributions as
     rollout_inputs: matrices N(0, 0.02), gains 1 + N(0, 0.02), router N(0, 1/d))."""
-    import torch
-    import rollout_inputs as RI
-    gen = torch.Generator(device="cuda:0")
-
-    def tensor(layer, name):
-        dims, kind = RI.tensor_names(shape, layer)[name]
-        gen.manual_seed((seed * 1000003 + (layer + 1) * 101 + sum(map(ord, name))) & 0x7FFFFFFF)
-        t = torch.randn(dims, generator=gen, device="cuda:0", dtype=torch.float32)
-        if kind == "matrix":
-            t.mul_(0.02)
-        elif kind == "gain":
-            t.mul_(0.02).add_(1.0)
-        else:
-            t.mul_(1.0 / np.sqrt(shape.d_model))
-        return t.to(torch.float16 if fmt == "f16" else torch.bfloat16)
-
-    return pkg.RolloutModel(synthetic.config_from_shape(shape, split, fmt), tensor)
+    return synthetic.device_random_model(shape, seed, split, fmt)
 
 
 def kernel_bytes(shape, cls, ctx_sum_plus_b, touched=None):

@@ -49,7 +49,8 @@ class OracleModel:
 
     Layers are materialised on demand; with cache_layers=False only one layer is
     resident at a time (needed for the 30B-shape model on a small host).
-    `tensors` may supply the bit patterns directly: {(layer, name): uint16 array}.
+    `tensors` may supply the bit patterns directly: {(layer, name): uint16 array}, or a function
+    layer -> {name: uint16 array} that is called when a layer is needed (weights that live elsewhere).
     """
 
     def __init__(self, shape: ModelShape, model_seed: int = 0, cache_layers: bool = True,
@@ -64,7 +65,9 @@ class OracleModel:
         self._cache: Dict[int, Dict[str, np.ndarray]] = {}
 
     def _load(self, layer: int) -> Dict[str, np.ndarray]:
-        if self._tensors is not None:
+        if callable(self._tensors):             # tensors(layer) -> {name: bit patterns}: one layer at a time
+            bits = self._tensors(layer)
+        elif self._tensors is not None:
             bits = {n: b for (l, n), b in self._tensors.items() if l == layer}
         else:
             bits = layer_tensors(self.shape, self.model_seed, layer, self.fmt)

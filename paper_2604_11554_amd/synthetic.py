@@ -27,6 +27,35 @@ def model_from_shape(s: RI.ModelShape, model_seed: int = 0, device="cuda:0", pro
                         lambda l, n: RI.tensor_bits(s, model_seed, l, n, fmt), device, progress)
 
 
+def device_random_tensor(s: RI.ModelShape, model_seed: int = 0, fmt: str = "bf16", device="cuda:0"):
+    """tensor(layer, name) -> random-init weights of shape `s` drawn on the device, a pure function of
+    (model_seed, layer, name), with the distributions of rollout_inputs (matrices N(0, 0.02), gains
+    1 + N(0, 0.02), router rows N(0, 1/d_model)) but torch's generator: for models too large to draw on the host."""
+    import numpy as np
+    import torch
+    gen = torch.Generator(device=device)
+
+    def tensor(layer, name):
+        dims, kind = RI.tensor_names(s, layer)[name]
+        gen.manual_seed((model_seed * 1000003 + (layer + 1) * 101 + sum(map(ord, name))) & 0x7FFFFFFF)
+        t = torch.randn(dims, generator=gen, device=device, dtype=torch.float32)
+        if kind == "matrix":
+            t.mul_(0.02)
+        elif kind == "gain":
+            t.mul_(0.02).add_(1.0)
+        else:
+            t.mul_(1.0 / np.sqrt(s.d_model))
+        return t.to(torch.float16 if fmt == "f16" else torch.bfloat16)
+
+    return tensor
+
+
+def device_random_model(s: RI.ModelShape, model_seed: int = 0, activation_split: int = 1, fmt: str = "bf16",
+                        device="cuda:0") -> RolloutModel:
+    return RolloutModel(config_from_shape(s, activation_split, fmt), device_random_tensor(s, model_seed, fmt, device),
+                        device)
+
+
 def generate_tensors(s: RI.ModelShape, model_seed: int = 0, threads: int = 8, progress=None,
                      fmt: str = "bf16") -> dict:
     """All bit patterns of a synthetic model, {(layer, name): uint16 array}, generated on several
