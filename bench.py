@@ -522,6 +522,8 @@ def run_grouped_full(args):
         bytes_logical += w_bytes * any_live_steps
         live_hist.append(int((~new_fin).sum()))
         ctx, fin = new_ctx, new_fin
+        if steps % 512 == 0:
+            log("  step %d: %d rows live of %d in the batch, %d tokens so far" % (steps, live_hist[-1], n, emitted - bsz))
         # compaction rule: at least a quarter of the rows finished, or 64 steps since the last one with any finished
         if (fin.mean() >= 0.25 or (since_compact >= 64 and fin.any())) and not fin.all():
             keep = eng.compact()
