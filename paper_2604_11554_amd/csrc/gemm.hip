@@ -15,6 +15,9 @@
 //
 // Epilogues: plain store (q|k|v, o and down projections, expert down projection),
 // SwiGLU (gate/up), LM head with fused log-sum-exp and Gumbel-max partials per 32-row tile.
+#include <atomic>
+#include <mutex>
+
 #include "kernels.h"
 
 namespace rlx {
@@ -598,13 +601,12 @@ __global__ __launch_bounds__(LG_THREADS) void gemm_large_kernel(GemmArgs a) {
 
 template <int EPI, int PL, int FMT>
 void launch_large_one(const GemmArgs& a, dim3 grid, hipStream_t st) {
-  static bool attr_set = false;
+  static std::once_flag attr_once;                  // raise the dynamic LDS limit once per instantiation, from any thread
   constexpr int lds = LargeTiling<PL>::LDS_BYTES;
-  if (!attr_set) {
+  std::call_once(attr_once, [] {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_large_kernel<EPI, PL, FMT>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    attr_set = true;
-  }
+  });
   hipLaunchKernelGGL((gemm_large_kernel<EPI, PL, FMT>), grid, dim3(LG_THREADS), lds, st, a);
 }
 
@@ -618,13 +620,12 @@ void launch_large(const GemmArgs& a, int n_tiles, int grid_y, int rows, hipStrea
 
 template <int MT, int EPI, int PL, int FMT>
 void launch_one(const GemmArgs& a, dim3 grid, hipStream_t st) {
-  static bool attr_set = false;   // raise the dynamic LDS limit once per instantiation
+  static std::once_flag attr_once;                  // raise the dynamic LDS limit once per instantiation, from any thread
   constexpr int lds = Tiling<MT, PL>::LDS_BYTES;
-  if (!attr_set) {
+  std::call_once(attr_once, [] {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_kernel<MT, EPI, PL, FMT>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    attr_set = true;
-  }
+  });
   hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI, PL, FMT>), grid, dim3(GEMM_THREADS), lds, st, a);
 }
 
@@ -636,7 +637,7 @@ void launch_fmt(const GemmArgs& a, dim3 grid, const Act& x, hipStream_t st) {
   else launch_one<MT, EPI, 1, DT_BF16>(a, grid, st);
 }
 
-int g_units = 256;                                   // compute units of the device (gemm_set_units)
+std::atomic<int> g_units{256};                       // compute units of the device (gemm_set_units): every model on it sets the same value
 
 template <int EPI>
 void launch_mt(const GemmArgs& a, int n_tiles, int grid_y, int mt, const Act& x, hipStream_t st) {
@@ -644,7 +645,7 @@ void launch_mt(const GemmArgs& a, int n_tiles, int grid_y, int mt, const Act& x,
     // more than 128 tokens (per expert), two-term bf16 activations: 256 x 256 tiles where they fill the device at
     // least twice over (a grid of 1.25 workgroups per unit takes as long as one of 2), else the 128-token skinny form
     const long wgs = (long)((n_tiles + LG_TILES - 1) / LG_TILES) * grid_y * ((a.T + 32 * LG_TILES - 1) / (32 * LG_TILES));
-    if (wgs >= 2L * g_units && x.planes == 2 && x.dtype == DT_BF16) {
+    if (wgs >= 2L * g_units.load(std::memory_order_relaxed) && x.planes == 2 && x.dtype == DT_BF16) {
       launch_large<EPI>(a, n_tiles, grid_y, a.T, st);
       return;
     }
@@ -675,7 +676,7 @@ static int store_token_groups(int T) { return (T > 64 && T <= 128) ? 2 : 1; }
 
 int gemm_max_splits() { return 16; }
 
-void gemm_set_units(int n_units) { g_units = n_units > 0 ? n_units : 1; }
+void gemm_set_units(int n_units) { g_units.store(n_units > 0 ? n_units : 1, std::memory_order_relaxed); }
 
 // Split-K planning.  A compute unit takes in only so many bytes per microsecond however many waves it holds, so
 // what counts is that every unit gets the same number of bytes: the grid is kept at or just under one workgroup

@@ -14,6 +14,7 @@ import rollout_inputs as RI
 pytestmark = pytest.mark.gpu
 
 LOGPROB_BAR = 0.02
+TIE_GAP = 1e-3
 LENS = (5, 33, 70, 300, 17)                 # 300 tokens: more than one 256-row LM-head block per call
 TEMPS = (1.0, 0.7, 1.0, 1.3, 1.0)
 
@@ -133,6 +134,63 @@ def test_score_with_foreign_routing_replay(amd):
     say("foreign replay: max |dlogprob| = %.4f" % worst)
     assert worst <= LOGPROB_BAR
     np.testing.assert_array_equal(routing.cpu().numpy(), np.concatenate(foreign))
+    model.close()
+
+
+def test_replay_table_with_repeated_and_invalid_ids(amd):
+    """A defective routing record (an expert listed twice for a token, ids outside the experts): every such slot
+    falls back to the layer's own best expert not yet in the token's list, so that no expert receives a token twice
+    (the grouped GEMMs hold at most one row per token and expert).  Checked: the experts used are distinct and equal
+    the record wherever the record was usable; each replaced slot holds the best expert, by the oracle's own router
+    order, among those the token had not taken by then; the log-probabilities equal the oracle's when it replays
+    the experts actually used."""
+    pkg, synthetic = amd
+    shape = RI.TINY_MOE
+    toks = _sequences(shape, 12)
+    tg = _targets(toks)
+    omodel = O.OracleModel(shape, 0)
+    own = O.forward_full(omodel, toks)
+    rec = [((r["routing"] + 5) % shape.n_experts).astype(np.int32) for r in own]
+    g = np.random.default_rng(3)
+    planted = 0
+    for r in rec:                                   # plant defects in a tenth of the (position, layer) lists
+        for t, l in zip(*np.nonzero(g.random(r.shape[:2]) < 0.1)):
+            kind = g.integers(0, 3)
+            if kind == 0:
+                r[t, l, g.integers(1, shape.top_k)] = r[t, l, 0]             # a repeat of the first id
+            elif kind == 1:
+                r[t, l, g.integers(0, shape.top_k)] = shape.n_experts + 3    # past the last expert
+            else:
+                r[t, l, 2] = -1; r[t, l, 5] = r[t, l, 4]                     # a negative id and a repeat
+            planted += 1
+    model, eng = _engine(pkg, synthetic, shape)
+    lp, routing = eng.score(list(range(len(toks))), toks, tg, replay_routing=rec, want_routing=True)
+    torch.cuda.synchronize()
+    used = np.split(routing.cpu().numpy(), np.cumsum(LENS)[:-1])
+    ores = O.forward_full(omodel, toks, forced_routing=used)
+    n_fallback = 0
+    for u, r, o in zip(used, rec, ores):
+        assert ((u >= 0) & (u < shape.n_experts)).all()
+        assert (np.sort(u, -1)[..., 1:] != np.sort(u, -1)[..., :-1]).all()      # distinct experts per token
+        for t in range(u.shape[0]):
+            for l in range(u.shape[1]):
+                taken = []
+                for k in range(shape.top_k):
+                    want = int(r[t, l, k])
+                    if 0 <= want < shape.n_experts and want not in taken:
+                        assert u[t, l, k] == want
+                    else:                           # the oracle's own order, first expert not yet taken ...
+                        best = [e for e in o["own_routing"][t, l] if e not in taken]
+                        n_fallback += 1
+                        # ... unless the token's list already holds all of its own eight, or a near-tie decides
+                        if best and o["order_gap"][t, l] >= TIE_GAP and o["gate_gap"][t, l] >= TIE_GAP:
+                            assert u[t, l, k] == best[0], (t, l, k, u[t, l], r[t, l], o["own_routing"][t, l])
+                    taken.append(int(u[t, l, k]))
+    glp, olp = _split(lp, LENS), _oracle_logprobs(ores, toks)
+    worst = max(float(np.abs(a - b).max()) for a, b in zip(glp, olp))
+    say("defective replay table: %d lists with planted defects, %d slots fell back, max |dlogprob| = %.4f" % (
+        planted, n_fallback, worst))
+    assert n_fallback >= planted and worst <= LOGPROB_BAR
     model.close()
 
 

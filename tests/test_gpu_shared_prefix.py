@@ -189,6 +189,51 @@ def test_descriptor_of_another_batch_size_is_ignored(amd):
     np.testing.assert_array_equal(outs[0], outs[1])
 
 
+def test_slot_refilled_inside_a_group_leaves_the_group(amd):
+    """release_slot / refill_slot on a row that shares prompt pages with its sampling group: the row gets pages of
+    its own, so it must stop claiming the group's pages (the descriptor of the next step is rebuilt without it and
+    the rows after it form a group of their own).  The refilled row then decodes a different prompt; every row is
+    compared with an engine that never shared anything."""
+    pkg, synthetic = amd
+    shape = RI.TINY_DENSE
+    g = np.random.default_rng(5)
+    prompt = g.integers(0, shape.vocab - 2, size=70).astype(np.int32)
+    other = g.integers(0, shape.vocab - 2, size=45).astype(np.int32)
+
+    def run(shared):
+        model = synthetic.model_from_shape(shape, 0, activation_split=1)
+        eng = pkg.RolloutEngine(model, n_blocks=96, max_seqs=8, max_chunk_tokens=512, max_blocks_per_seq=12)
+        if shared:
+            d = eng.add_sequence(0, reserve_tokens=len(prompt))
+            eng.prefill([d], [prompt[:-1]], sample_last=[False])
+            kids = [eng.fork(d, 60 + k, reserve_tokens=len(prompt) + 12) for k in range(4)]
+            eng.finished[d] = 1
+            eng.prefill(kids, [prompt[-1:]] * 4)
+        else:
+            d = eng.add_sequence(0, reserve_tokens=8)
+            eng.finished[d] = 1
+            kids = [eng.add_sequence(60 + k, reserve_tokens=len(prompt) + 12) for k in range(4)]
+            eng.prefill(kids, [prompt] * 4)
+        z = []
+        for _ in range(2):
+            z.append(eng.decode_step(want_logits=True).logits.cpu().numpy()[1:5].copy())
+        assert (eng._shared_prefix() is not None) == shared
+        # the second member ends; its row is refilled with another request
+        row = kids[1]
+        assert eng.refill_slot(row, 99, 1.0, len(other) + 12)
+        if shared:
+            assert eng.leader[row] == row and eng.shared_pages[row] == 0
+            assert eng.leader[kids[0]] == d and eng.leader[kids[2]] == kids[2] and eng.leader[kids[3]] == kids[2]
+        eng.prefill([row], [other])
+        for _ in range(3):
+            z.append(eng.decode_step(want_logits=True).logits.cpu().numpy()[1:5].copy())
+        model.close()
+        return np.stack(z)
+
+    a, b = run(True), run(False)
+    assert np.abs(a - b).max() <= 2e-3, float(np.abs(a - b).max())     # summation order of the softmax merges only
+
+
 def test_shared_prefix_descriptor_validation(amd):
     pkg, synthetic = amd
     B = pkg.binding
