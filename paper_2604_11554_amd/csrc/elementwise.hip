@@ -419,8 +419,9 @@ __global__ void pack_weight_kernel(const h16_t* src, h16_t* dst, int N, int K) {
   const int lane = (int)(g & 63);
   const size_t frag = g >> 6;
   const int KS = K >> 4;
-  const int ks = (int)(frag % KS);
-  const int nt = (int)(frag / KS);
+  const size_t in_group = frag % ((size_t)KS * W_GROUP);
+  const int ks = (int)(in_group / W_GROUP);
+  const int nt = (int)(frag / ((size_t)KS * W_GROUP)) * W_GROUP + (int)(in_group % W_GROUP);
   const int n = nt * 32 + (lane & 31), k = ks * 16 + 8 * (lane >> 5);
   u32x4 v = {0u, 0u, 0u, 0u};
   if (n < N) v = *reinterpret_cast<const u32x4*>(src + (size_t)n * K + k);
@@ -434,11 +435,13 @@ __global__ void pack_gate_up_kernel(const h16_t* gate, const h16_t* up, h16_t* d
   const int lane = (int)(g & 63);
   const size_t frag = g >> 6;
   const int KS = K >> 4;
-  const int ks = (int)(frag % KS);
-  const int nt = (int)(frag / KS);
+  const size_t in_group = frag % ((size_t)KS * W_GROUP);
+  const int ks = (int)(in_group / W_GROUP);
+  const int nt = (int)(frag / ((size_t)KS * W_GROUP)) * W_GROUP + (int)(in_group % W_GROUP);
   const int r = lane & 31, k = ks * 16 + 8 * (lane >> 5);
-  const h16_t* src = (r < 16 ? gate : up) + (size_t)(nt * 16 + (r & 15)) * K + k;
-  *reinterpret_cast<u32x4*>(dst + g * 8) = *reinterpret_cast<const u32x4*>(src);
+  u32x4 v = {0u, 0u, 0u, 0u};
+  if (nt * 16 < F) v = *reinterpret_cast<const u32x4*>((r < 16 ? gate : up) + (size_t)(nt * 16 + (r & 15)) * K + k);
+  *reinterpret_cast<u32x4*>(dst + g * 8) = v;
 }
 
 __global__ void pack_activation_kernel(const h16_t* src, h16_t* dst, int T, int K) {

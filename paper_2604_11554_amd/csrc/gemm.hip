@@ -2,10 +2,11 @@
 //
 //   y[t, n] = sum_k x[t, k] * W[n, k]        fp32 accumulate
 //
-// Both operands are stored in MFMA fragment order (see common.h), so a wave streams its
-// 32 weight rows as one contiguous run of 1 KB blocks: eight full cache lines per load
-// instruction, nothing wasted, and the texture-address path is left free for the
-// activations.  Each of the four waves of a workgroup owns one 32-row tile of W over the
+// Both operands are stored in MFMA fragment order (see common.h): every weight load of a wave
+// reads one 1 KB block, eight full cache lines, nothing wasted, and the texture-address path is
+// left free for the activations; the blocks of the four tiles of a workgroup alternate along k,
+// so the workgroup as a whole streams one contiguous run.
+// Each of the four waves of a workgroup owns one 32-row tile of W over the
 // workgroup's K range and keeps two batches of weight fragments in flight in registers
 // (HBM latency under load is several microseconds, so the bytes in flight per CU decide
 // the achieved bandwidth).  The activations of the current K chunk are shared by the four
@@ -253,7 +254,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
       base = a.w[1];
       if (lt >= a.w_tiles[1]) { lt -= a.w_tiles[1]; base = a.w[2]; }
     }
-    wp = base + (size_t)lt * KS * 512 + lane * 8;
+    wp = base + packed_tile_offset(lt, KS) + lane * 8;
   }
   const int ks_b = split * a.ksteps_per_split;
   int ks_e = ks_b + a.ksteps_per_split;
@@ -342,7 +343,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
     for (int u = 0; u < U; ++u) {
       const int ks = ks0 + u;
       const int ksc = ks < ks_e ? ks : ks_e - 1;   // clamped: always a valid block; masked when used
-      wf[u] = *reinterpret_cast<const u32x4*>(wp + (size_t)ksc * 512);
+      wf[u] = *reinterpret_cast<const u32x4*>(wp + (size_t)ksc * W_KSTRIDE);
     }
   };
 
@@ -457,7 +458,7 @@ __global__ __launch_bounds__(LG_THREADS) void gemm_large_kernel(GemmArgs a) {
 
   // ---- staging duties: wave w copies weight tile nt_base + w and token tile mt_base + w of every stage ----
   const h16_t* wp;
-  int w_kstride = 512;
+  int w_kstride = W_KSTRIDE;
   {
     int lt = nt_base + wave;
     if (lt >= n_tiles) { lt = 0; w_kstride = 0; }   // no such tile: one cached block, its products are never stored
@@ -467,7 +468,7 @@ __global__ __launch_bounds__(LG_THREADS) void gemm_large_kernel(GemmArgs a) {
       base = a.w[1];
       if (lt >= a.w_tiles[1]) { lt -= a.w_tiles[1]; base = a.w[2]; }
     }
-    wp = base + (size_t)lt * KS * 512 + lane * 8;
+    wp = base + packed_tile_offset(lt, KS) + lane * 8;
   }
   // a token row past the end reads row 0 / tile 0: a token's row only reaches its own outputs, which are not stored
   const h16_t* xsrc;
