@@ -412,6 +412,156 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
   tile_epilogue<MT, EPI, PL, FMT>(a, acc, nt, n_tiles, mt0, split, row_base, lane);
 }
 
+// ---- expert-grouped decode form: up to 32 rows per expert, J tile groups per workgroup ----
+// At decode an expert receives a handful of rows, and the skinny form above then spends a tenth of its time on
+// the activations: every workgroup stages all K of the expert's rows for the 128 weight rows it owns, so the rows
+// are fetched as often as the expert has tile groups, with gather loads that touch sixteen cache lines for eight
+// useful rows (measured at the 30B-A3B shape: gate/up 154 us with the activation loads, 144 us without, 135 us for a
+// kernel that only streams the same weights).  Here a workgroup takes J consecutive tile groups of one expert: wave w
+// owns tile w of each of them, the activation chunk in LDS serves all J, and a workgroup lives J times as long, so
+// that the routing look-up, the first chunk and the epilogue are paid a J-th as often.  With the interleaved weight
+// layout the J groups are J contiguous runs of 4 KB per k-step.  Per accumulator the products come in the order of
+// the skinny form (k ascending, small term first): the results are the same bits.
+//
+// A chunk is KC k-steps of activations in LDS; its weight batches are taken in the order (first half of the chunk:
+// tile group 0 .. J-1, second half: 0 .. J-1), U = KC / 2 k-steps each, through a ring of R batches in registers.
+// (Four groups per workgroup leave registers for 4 KB batches only, which was measured slower than one group.)
+template <int J>
+struct ExpertTiling {
+  static constexpr int KC = 16, U = 8, NBC = KC / U;
+  static constexpr int BPC = J * NBC;                    // weight batches per chunk
+  static constexpr int R = (BPC % 4 == 0) ? 4 : 3;       // ring depth: divides BPC, so ring slots are static
+  static_assert(BPC % R == 0, "ring depth must divide the batches of a chunk");
+};
+
+template <int J, int EPI, int PL, int FMT>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_expert_kernel(GemmArgs a) {
+  using TL = ExpertTiling<J>;
+  constexpr int KC = TL::KC, U = TL::U, BPC = TL::BPC, R = TL::R;
+  constexpr int FRAGS = KC * PL, PT = FRAGS / GEMM_WAVES;
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  u32x4* lds = reinterpret_cast<u32x4*>(lds_raw);   // [2][FRAGS][64 lanes]
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r32 = lane & 31, half = lane >> 5;
+  const int mt0 = blockIdx.z;                       // 32-row tile of the expert's rows
+  const int e = blockIdx.y;
+  const int row_base = a.group_off[e];
+  a.T = a.group_off[e + 1] - row_base;
+  if (mt0 * 32 >= a.T) return;                      // uniform over the workgroup, before any barrier
+  const h16_t* wbase = a.w[0] + (size_t)e * a.w_expert_stride;
+
+  const int KS = a.K >> 4;
+  const int n_tiles = (a.N + 31) >> 5;
+  // tile of this wave in tile group j: (blockIdx.x * J + j) * 4 + wave; consecutive groups lie KS * W_KSTRIDE apart
+  const int nt0 = blockIdx.x * J * W_GROUP + wave;
+  static_assert(W_GROUP == GEMM_WAVES, "a wave owns one tile of every interleaved group");
+  const h16_t* wp = wbase + packed_tile_offset(nt0, KS) + lane * 8;
+  const size_t group_stride = (size_t)KS * W_KSTRIDE;
+  // a tile group past the end of the matrix is read as the last one that exists (cache hits) and never stored
+  int jmax = ((n_tiles + W_GROUP - 1) / W_GROUP) - 1 - blockIdx.x * J;
+  if (jmax > J - 1) jmax = J - 1;
+
+  // ---- activation staging: each wave moves PT fragments of a chunk; fragment f = (k-step f / PL, plane f % PL) ----
+  const int r = mt0 * 32 + r32;
+  const bool xok = r < a.T;
+  const h16_t* xsrc;
+  {
+    const int rr = xok ? r : 0;
+    const int row = a.x_rows ? a.x_rows[row_base + rr] : row_base + rr;
+    xsrc = a.x + frag_act_offset(row, 8 * half, 0, a.x_mtiles, PL);
+  }
+  const size_t x_kstride = (size_t)a.x_mtiles * PL * 512;
+  auto stage_load = [&](int chunk, u32x4 (&rg)[PT]) {
+#pragma unroll
+    for (int i = 0; i < PT; ++i) {
+      const int f = wave + GEMM_WAVES * i;
+      const int ks = chunk * KC + f / PL, p = f % PL;
+      const int ksc = ks < KS ? ks : KS - 1;         // clamped: always a valid fragment; masked when stored
+      rg[i] = *reinterpret_cast<const u32x4*>(xsrc + (size_t)ksc * x_kstride + (size_t)p * 512);
+    }
+  };
+  auto stage_store = [&](int chunk, const u32x4 (&rg)[PT]) {
+    const int buf = chunk & 1;
+    const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < PT; ++i) {
+      const int f = wave + GEMM_WAVES * i;
+      const int ks = chunk * KC + f / PL;
+      lds[(buf * FRAGS + f) * 64 + lane] = (xok && ks < KS) ? rg[i] : z;
+    }
+  };
+
+  // ---- weight batches: batch s of chunk c = tile group s % J, k-steps c * KC + (s / J) * U .. + U ----
+  auto load_w = [&](int c, int s, u32x4 (&wf)[U]) {
+    const int j = s % J;
+    const h16_t* base = wp + (size_t)(j < jmax ? j : jmax) * group_stride;
+    const int ks0 = c * KC + (s / J) * U;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int ks = ks0 + u;
+      const int ksc = ks < KS ? ks : KS - 1;         // clamped: always a valid block; masked when used
+      wf[u] = *reinterpret_cast<const u32x4*>(base + (size_t)ksc * W_KSTRIDE);
+    }
+  };
+
+  f32x16 acc[J];
+#pragma unroll
+  for (int j = 0; j < J; ++j)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[j][q] = 0.f;
+
+  auto compute = [&](int buf, int kk0, int ks0, const u32x4 (&wf)[U], f32x16& ac) {
+    u32x4 xq[2][PL];
+    auto fetch = [&](int u, u32x4 (&dst)[PL]) {
+#pragma unroll
+      for (int p = 0; p < PL; ++p) dst[p] = lds[(buf * FRAGS + (kk0 + u) * PL + p) * 64 + lane];
+    };
+    fetch(0, xq[0]);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (u + 1 < U) fetch(u + 1, xq[(u + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);          // the reads above are issued before the multiplies below
+      const bool ok = ks0 + u < KS;               // uniform; past the end the weights count as zero
+      const u32x4 z = {0u, 0u, 0u, 0u};
+      const h16x8 w1 = ok ? wf[u] : z;
+#pragma unroll
+      for (int p = PL - 1; p >= 0; --p) ac = mfma_32x32x16<FMT>(w1, xq[u & 1][p], ac);   // small term first
+    }
+  };
+
+  const int n_chunks = (KS + KC - 1) / KC;
+  u32x4 wr[R][U];
+  u32x4 xr[PT];
+  stage_load(0, xr);
+  __builtin_amdgcn_sched_barrier(0);                // the activation loads are older than every weight load
+#pragma unroll
+  for (int s = 0; s < R - 1; ++s) load_w(0, s, wr[s]);
+  __builtin_amdgcn_sched_barrier(0);
+  stage_store(0, xr);
+  __syncthreads();
+  for (int c = 0; c < n_chunks; ++c) {
+    stage_load(c + 1, xr);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s = 0; s < BPC; ++s) {
+      // batch s + R - 1 of this chunk, or the first batches of the next one, goes out before batch s is multiplied
+      const int sn = s + R - 1;
+      if (sn < BPC) load_w(c, sn, wr[sn % R]); else load_w(c + 1, sn - BPC, wr[sn % R]);
+      __builtin_amdgcn_sched_barrier(0);
+      compute(c & 1, (s / J) * U, c * KC + (s / J) * U, wr[s % R], acc[s % J]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    stage_store(c + 1, xr);
+    __syncthreads();
+  }
+#pragma unroll
+  for (int j = 0; j < J; ++j) {
+    const int nt = nt0 + j * W_GROUP;
+    if (nt < n_tiles) tile_epilogue<1, EPI, PL, FMT>(a, reinterpret_cast<const f32x16(&)[1]>(acc[j]), nt, n_tiles, mt0, 0, row_base, lane);
+  }
+}
+
 // ---- large-batch form (more than 128 tokens): 256 weight rows x 256 tokens per workgroup of eight waves ----
 // With 128-token tiles and one weight tile per wave every compute unit takes in 12 KB per k-step for 32 multiplies;
 // here both operands pass through LDS (each weight fragment feeds the two token halves, each activation fragment the
@@ -600,6 +750,8 @@ __global__ __launch_bounds__(LG_THREADS) void gemm_large_kernel(GemmArgs a) {
   if (nt0 + 1 < n_tiles) tile_epilogue<4, EPI, PL, FMT>(a, acc[1], nt0 + 1, n_tiles, mt_base + 4 * wt, split, row_base, lane);
 }
 
+std::atomic<int> g_units{256};                       // compute units of the device (gemm_set_units): every model on it sets the same value
+
 template <int EPI, int PL, int FMT>
 void launch_large_one(const GemmArgs& a, dim3 grid, hipStream_t st) {
   static std::once_flag attr_once;                  // raise the dynamic LDS limit once per instantiation, from any thread
@@ -638,8 +790,6 @@ void launch_fmt(const GemmArgs& a, dim3 grid, const Act& x, hipStream_t st) {
   else launch_one<MT, EPI, 1, DT_BF16>(a, grid, st);
 }
 
-std::atomic<int> g_units{256};                       // compute units of the device (gemm_set_units): every model on it sets the same value
-
 template <int EPI>
 void launch_mt(const GemmArgs& a, int n_tiles, int grid_y, int mt, const Act& x, hipStream_t st) {
   if (mt > 4) {
@@ -657,6 +807,40 @@ void launch_mt(const GemmArgs& a, int n_tiles, int grid_y, int mt, const Act& x,
   if (mt == 1) launch_fmt<1, EPI>(a, dim3(gx, grid_y, mtiles), x, st);
   else if (mt == 2) launch_fmt<2, EPI>(a, dim3(gx, grid_y, (mtiles + 1) / 2), x, st);
   else launch_fmt<4, EPI>(a, dim3(gx, grid_y, (mtiles + 3) / 4), x, st);
+}
+
+// Expert-grouped decode form (two-term bf16 only; the other formats keep the skinny form).  Tile groups per
+// workgroup: three or two, whichever divides the groups of an expert and still leaves two workgroups per compute
+// unit (measured at the 30B-A3B shape: gate/up, 12 groups, 155 us with one group per workgroup, 145 with two, 146
+// with three; down, 16 groups, 77.7 / 77.0 / 78.8); a grid that cannot fill the device anyway takes two.
+template <int J, int EPI>
+void launch_expert_one(const GemmArgs& a, dim3 grid, hipStream_t st) {
+  static std::once_flag attr_once;
+  constexpr int lds = 2 * ExpertTiling<J>::KC * 2 * 1024;
+  std::call_once(attr_once, [] {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_expert_kernel<J, EPI, 2, DT_BF16>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  });
+  hipLaunchKernelGGL((gemm_expert_kernel<J, EPI, 2, DT_BF16>), grid, dim3(GEMM_THREADS), lds, st, a);
+}
+
+int expert_tile_groups(int n_tiles, int n_experts, int n_units) {
+  const int groups = (n_tiles + W_GROUP - 1) / W_GROUP;
+  for (int j = 3; j >= 2; --j)
+    if (groups % j == 0 && (long)(groups / j) * n_experts >= 2L * n_units) return j;
+  return groups >= 2 ? 2 : 1;
+}
+
+template <int EPI>
+bool launch_expert(const GemmArgs& a, int n_tiles, int n_experts, const Act& x, hipStream_t st) {
+  if (x.planes != 2 || x.dtype != DT_BF16) return false;
+  const int j = expert_tile_groups(n_tiles, n_experts, g_units.load(std::memory_order_relaxed));
+  if (j < 2) return false;
+  const int groups = (n_tiles + W_GROUP - 1) / W_GROUP;
+  const dim3 grid((groups + j - 1) / j, n_experts, (a.T + 31) / 32);
+  if (j == 2) launch_expert_one<2, EPI>(a, grid, st);
+  else launch_expert_one<3, EPI>(a, grid, st);
+  return true;
 }
 
 // token tiles per workgroup; 8 selects the large-batch form
@@ -747,6 +931,7 @@ hipError_t gemm_grouped_swiglu(const h16_t* w_gate_up, int E, int F, int K, cons
   a.ksteps_per_split = K / 16;
   a.act = act.p; a.act_mtiles = act.mtiles();
   a.group_off = group_off; a.w_expert_stride = packed_weight_elems(2 * F, K);
+  if (grouped_mt(expected_rows) == 1 && launch_expert<EPI_SWIGLU>(a, a.w_tiles[0], E, x, st)) return hipGetLastError();
   launch_mt<EPI_SWIGLU>(a, a.w_tiles[0], E, grouped_mt(expected_rows), x, st);
   return hipGetLastError();
 }
@@ -760,6 +945,7 @@ hipError_t gemm_grouped_store(const h16_t* w, int E, int N, int K, const Act& x,
   a.ksteps_per_split = K / 16;
   a.y = y; a.ldy = N;
   a.group_off = group_off; a.w_expert_stride = packed_weight_elems(N, K);
+  if (grouped_mt(expected_rows) == 1 && launch_expert<EPI_STORE>(a, a.w_tiles[0], E, x, st)) return hipGetLastError();
   launch_mt<EPI_STORE>(a, a.w_tiles[0], E, grouped_mt(expected_rows), x, st);
   return hipGetLastError();
 }
