@@ -19,6 +19,13 @@ __device__ __forceinline__ h16x8 load_2x4(const h16_t* p0, const h16_t* p1) {
   u32x4 v = {a[0], a[1], b[0], b[1]};
   return __builtin_bit_cast(h16x8, v);
 }
+// the same from pages that the launch reads once (decode attention)
+__device__ __forceinline__ h16x8 load_2x4_stream(const h16_t* p0, const h16_t* p1) {
+  u32x2 a = load_stream_8(p0);
+  u32x2 b = load_stream_8(p1);
+  u32x4 v = {a[0], a[1], b[0], b[1]};
+  return __builtin_bit_cast(h16x8, v);
+}
 
 // running softmax state of NCT column tiles: lane holds column (lane & 15), rows d = 16 dt + 4 (lane >> 4) + {0..3}
 template <int HD, int NCT>

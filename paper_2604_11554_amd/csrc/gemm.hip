@@ -343,7 +343,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
     for (int u = 0; u < U; ++u) {
       const int ks = ks0 + u;
       const int ksc = ks < ks_e ? ks : ks_e - 1;   // clamped: always a valid block; masked when used
-      wf[u] = *reinterpret_cast<const u32x4*>(wp + (size_t)ksc * W_KSTRIDE);
+      wf[u] = load_stream_16(wp + (size_t)ksc * W_KSTRIDE);
     }
   };
 
@@ -501,7 +501,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_expert_kernel(GemmArgs a) {
     for (int u = 0; u < U; ++u) {
       const int ks = ks0 + u;
       const int ksc = ks < KS ? ks : KS - 1;         // clamped: always a valid block; masked when used
-      wf[u] = *reinterpret_cast<const u32x4*>(base + (size_t)ksc * W_KSTRIDE);
+      wf[u] = load_stream_16(base + (size_t)ksc * W_KSTRIDE);
     }
   };
 
