@@ -149,16 +149,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     if (jb >= a.max_blocks) t0 = -1;
     if (jb + 64 >= a.max_blocks) t1 = -1;
   };
-  // the waves share the fetch of a segment's query fragments; they stay in LDS (registers hold two units of pages)
-  auto stage_queries = [&](const Run& r) {
-    const int head = r.kvh * group + c16;
-    for (int f = wave; f < PL * KS; f += 4) {
+  // The waves share the fetch of a segment's query fragments; they stay in LDS (registers hold two units of pages).
+  // The fragments of the next run's pair are requested a whole run ahead (the run generator looks one run ahead
+  // anyway) and only written to LDS at the switch, so that a new segment does not begin with a round trip.
+  constexpr int QPW = (PL * KS + 3) / 4;             // fragments fetched by each wave
+  auto fetch_queries = [&](const Run& r, u32x4 (&q)[QPW]) {
+    const int head = r.kvh * group + (col_ok ? c16 : 0);
+#pragma unroll
+    for (int i = 0; i < QPW; ++i) {
+      const int f = min(wave + 4 * i, PL * KS - 1);  // a slot without a fragment repeats the last one; never written
       const int p = f / KS, ks = f % KS;
-      const u32x4 z = {0u, 0u, 0u, 0u};
-      lds_q[f * WAVE + lane] = col_ok ? *reinterpret_cast<const u32x4*>(a.q.p + p * a.q.plane +
-                                                                       ((size_t)r.seq * a.Hq + head) * HD + 32 * ks + 8 * g)
-                                      : z;
+      q[i] = *reinterpret_cast<const u32x4*>(a.q.p + p * a.q.plane + ((size_t)r.seq * a.Hq + head) * HD + 32 * ks + 8 * g);
     }
+  };
+  auto put_queries = [&](const u32x4 (&q)[QPW]) {
+    const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < QPW; ++i)
+      if (wave + 4 * i < PL * KS) lds_q[(wave + 4 * i) * WAVE + lane] = col_ok ? q[i] : z;
   };
   auto qf = [&](int p, int, int ks) { return __builtin_bit_cast(h16x8, lds_q[(p * KS + ks) * WAVE + lane]); };
 
@@ -167,7 +175,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   if (!cur.valid) return;
   int32_t tb0, tb1, tbn0, tbn1;
   load_window(cur, tb0, tb1);
-  stage_queries(cur);
+  u32x4 qpre[QPW];
+  fetch_queries(cur, qpre);
+  put_queries(qpre);
   __syncthreads();
 
   // Page loads of unit i of run r (table window t0/t1).  They are unconditional: a slot with no unit behind it
@@ -209,6 +219,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const bool more = nxt.valid;
     if (!more) nxt = cur;                            // keeps the look-ahead loads below in bounds
     load_window(nxt, tbn0, tbn1);
+    fetch_queries(nxt, qpre);                        // unconditional, like every load of this loop
     if (cur.seg_start) st.reset();
     const int key_end = cur.ctx + 1;
     const int pos_col[1] = {cur.ctx};
@@ -263,7 +274,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       first_seg = false;
     }
     if (!more) break;
-    if (nxt.seg_start) stage_queries(nxt);           // every wave is past the merge: the old fragments are dead
+    if (nxt.seg_start) put_queries(qpre);            // every wave is past the merge: the old fragments are dead
     __syncthreads();                                 // new fragments visible; wave 0 is done with the merge buffers
     cur = nxt; tb0 = tbn0; tb1 = tbn1;
   }
