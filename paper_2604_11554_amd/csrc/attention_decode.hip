@@ -323,12 +323,12 @@ __global__ __launch_bounds__(256) void attn_decode_prefix_kernel(AttnDecodeArgs 
       h16x8 k0[KS], k1[KS], vf[DT];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        k0[ks] = load_stream_16(kp0 + c16 * HD + 32 * ks + 8 * g);
-        k1[ks] = load_stream_16(kp1 + c16 * HD + 32 * ks + 8 * g);
+        k0[ks] = load_h16x8(kp0 + c16 * HD + 32 * ks + 8 * g);     // the tiles of a group read these pages again:
+        k1[ks] = load_h16x8(kp1 + c16 * HD + 32 * ks + 8 * g);     // ordinary loads (the streaming mark cost 25 % here)
       }
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
-        vf[dt] = load_2x4_stream(kp0 + 16 * HD + (size_t)(16 * dt + c16) * 16 + 4 * g,
+        vf[dt] = load_2x4(kp0 + 16 * HD + (size_t)(16 * dt + c16) * 16 + 4 * g,
                           kp1 + 16 * HD + (size_t)(16 * dt + c16) * 16 + 4 * g);
       pair_step<HD, 1, PL, FMT>(st, k0, k1, vf, [&](int p, int, int ks) { return qf[p][ks]; }, 32 * i, 32 * i + 16, ok0,
                                 ok1, 0x7FFFFFFF, pos_col, scale, g);

@@ -216,7 +216,10 @@ struct Tiling {
   static constexpr int LDS_BYTES = 2 * FRAGS * 1024;
 };
 
-template <int MT, int EPI, int PL, int FMT>
+// ONCE: the launch reads every weight once (a single token tile per weight tile), so the weight loads are marked
+// non-temporal; with several token tiles the later ones find the weights in the caches, and the mark would send
+// them to memory again (decode steps of 129..256 tokens: down projection +10 % with the mark).
+template <int MT, int EPI, int PL, int FMT, bool ONCE>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
   using TL = Tiling<MT, PL>;
   constexpr int KC = TL::KC, U = TL::U, FRAGS = TL::FRAGS, PT = TL::PER_THREAD;
@@ -343,7 +346,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
     for (int u = 0; u < U; ++u) {
       const int ks = ks0 + u;
       const int ksc = ks < ks_e ? ks : ks_e - 1;   // clamped: always a valid block; masked when used
-      wf[u] = load_stream_16(wp + (size_t)ksc * W_KSTRIDE);
+      wf[u] = ONCE ? load_stream_16(wp + (size_t)ksc * W_KSTRIDE) : *reinterpret_cast<const u32x4*>(wp + (size_t)ksc * W_KSTRIDE);
     }
   };
 
@@ -771,15 +774,24 @@ void launch_large(const GemmArgs& a, int n_tiles, int grid_y, int rows, hipStrea
   launch_large_one<EPI, 2, DT_BF16>(a, grid, st);
 }
 
-template <int MT, int EPI, int PL, int FMT>
-void launch_one(const GemmArgs& a, dim3 grid, hipStream_t st) {
+template <int MT, int EPI, int PL, int FMT, bool ONCE>
+void launch_one_form(const GemmArgs& a, dim3 grid, hipStream_t st) {
   static std::once_flag attr_once;                  // raise the dynamic LDS limit once per instantiation, from any thread
   constexpr int lds = Tiling<MT, PL>::LDS_BYTES;
   std::call_once(attr_once, [] {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_kernel<MT, EPI, PL, FMT>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_kernel<MT, EPI, PL, FMT, ONCE>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   });
-  hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI, PL, FMT>), grid, dim3(GEMM_THREADS), lds, st, a);
+  hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI, PL, FMT, ONCE>), grid, dim3(GEMM_THREADS), lds, st, a);
+}
+
+// Several token tiles (grid z) share a weight tile only in the store form at 64 tokens per tile (two-group calls) and
+// in the 128-token forms; an expert group with more rows than a tile is rare enough to keep the streaming mark.
+template <int MT, int EPI, int PL, int FMT>
+void launch_one(const GemmArgs& a, dim3 grid, hipStream_t st) {
+  constexpr bool shared_tiles_possible = MT == 4 || (MT == 2 && EPI == EPI_STORE);
+  if (shared_tiles_possible && grid.z > 1 && a.group_off == nullptr) launch_one_form<MT, EPI, PL, FMT, !shared_tiles_possible>(a, grid, st);
+  else launch_one_form<MT, EPI, PL, FMT, true>(a, grid, st);
 }
 
 // formats built: bf16 activations as one or two terms, fp16 activations as one term
