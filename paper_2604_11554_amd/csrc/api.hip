@@ -231,7 +231,7 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
     wqkv.seg[1] = m->wk[l]; wqkv.rows[1] = kvdim;
     wqkv.seg[2] = m->wv[l]; wqkv.rows[2] = kvdim;
     wqkv.N = qkv_dim; wqkv.K = d;
-    const int s_qkv = small ? gemm_plan_splits(qkv_dim, d, T, gemm_max_splits(), m->n_units) : 1;
+    const int s_qkv = small ? gemm_plan_splits(qkv_dim, d, T, gemm_max_splits(), m->n_units, PL, FMT) : 1;
     RLX_LAUNCH(RLX_K_QKV, gemm_store(wqkv, xb, T, w.qkv, qkv_dim, s_qkv, st));
 
     h16_t* pool_layer = pool + (size_t)l * n_blocks * block_elems(c);
@@ -266,7 +266,7 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
       RLX_LAUNCH(RLX_K_ATTN, attention_prefill(at, st));
     }
 
-    const int s_o = small ? gemm_plan_splits(d, qdim, T, gemm_max_splits(), m->n_units)
+    const int s_o = small ? gemm_plan_splits(d, qdim, T, gemm_max_splits(), m->n_units, PL, FMT)
                           : gemm_plan_splits_long(d, T, xb.planes, xb.dtype, m->n_units);
     RLX_LAUNCH(RLX_K_OPROJ, gemm_store(linear1(m->wo[l], d, qdim), ob, T, w.planes, d, s_o, st));
     pend_planes = w.planes; pend_n = s_o;
@@ -275,12 +275,12 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
     if (c.n_experts == 0) {
       const Act act = make_act(w.act, T, c.d_ff, PL, FMT);
       RLX_LAUNCH(RLX_K_GATEUP, gemm_swiglu(m->w_gate_up[l], c.d_ff, d, xb, T, act, st));
-      const int s_d = small ? gemm_plan_splits(d, c.d_ff, T, gemm_max_splits(), m->n_units)
+      const int s_d = small ? gemm_plan_splits(d, c.d_ff, T, gemm_max_splits(), m->n_units, PL, FMT)
                             : gemm_plan_splits_long(d, T, xb.planes, xb.dtype, m->n_units);
       RLX_LAUNCH(RLX_K_DOWN, gemm_store(linear1(m->w_down[l], d, c.d_ff), act, T, w.planes, d, s_d, st));
       pend_planes = w.planes; pend_n = s_d;
     } else {
-      const int s_r = small ? gemm_plan_splits(c.n_experts, d, T, gemm_max_splits(), m->n_units) : 1;
+      const int s_r = small ? gemm_plan_splits(c.n_experts, d, T, gemm_max_splits(), m->n_units, PL, FMT) : 1;
       RLX_LAUNCH(RLX_K_ROUTER, gemm_store(linear1(m->w_router[l], c.n_experts, d), xb, T, w.router, c.n_experts, s_r, st));
       RouterArgs ra = {};
       ra.logits = w.router; ra.n_planes = s_r; ra.T = T; ra.E = c.n_experts; ra.top_k = c.top_k;
@@ -712,7 +712,7 @@ int rlx_op_linear(const void* x, const void* w, float* y, int32_t n_tokens, int3
   int dev = 0, n_units = 0;
   RLX_HIP(hipGetDevice(&dev));
   RLX_HIP(hipDeviceGetAttribute(&n_units, hipDeviceAttributeMultiprocessorCount, dev));
-  const int splits = n_tokens <= 256 ? gemm_plan_splits(n, k, n_tokens, gemm_max_splits(), n_units > 0 ? n_units : 1) : 1;
+  const int splits = n_tokens <= 256 ? gemm_plan_splits(n, k, n_tokens, gemm_max_splits(), n_units > 0 ? n_units : 1, 1, DT_BF16) : 1;
   hipStream_t st = (hipStream_t)stream;
   const size_t xb = align_up(frag_act_elems(n_tokens, k, 1) * 2);
   const size_t pb = splits > 1 ? align_up((size_t)splits * n_tokens * n * 4) : 0;

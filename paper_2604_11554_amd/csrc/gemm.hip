@@ -880,8 +880,17 @@ void gemm_set_units(int n_units) { g_units.store(n_units > 0 ? n_units : 1, std:
 // per unit (a grid of 1.2 workgroups per unit takes as long as one of 2), with as few planes as that allows.
 static int ksteps_for(int K, int splits) { return (K / 16 + splits - 1) / splits; }
 
-int gemm_plan_splits(int N, int K, int T, int max_splits, int n_units) {
-  (void)T;                                                             // at most 256 tokens: always the skinny form
+// k-steps that one round of the skinny form's main loop covers (a ring of four weight batches); a K range that is
+// not a multiple of it is padded with masked k-steps whose loads are still issued
+static int kstep_round(int T, int planes, int dtype) {
+  int mt = store_mt(T);
+  if (mt > 4) mt = 4;
+  const int pl = dtype == DT_F16 ? 1 : planes;
+  const int kc = (mt == 1 && pl == 2) ? 12 : ((32 / (mt * pl)) > 16 ? 16 : (32 / (mt * pl)));   // Tiling<MT, PL>::KC
+  return 2 * kc;
+}
+
+int gemm_plan_splits(int N, int K, int T, int max_splits, int n_units, int planes, int dtype) {
   const int per = GEMM_WAVES;                                          // weight tiles per workgroup
   const int groups = ((N + 31) / 32 + per - 1) / per * store_token_groups(T);   // workgroups per split
   const int KS = K / 16;
@@ -889,7 +898,18 @@ int gemm_plan_splits(int N, int K, int T, int max_splits, int n_units) {
   if (want > max_splits) want = max_splits;
   if (want > KS / 8) want = KS / 8;                 // at least eight k-steps per split
   if (want < 1) want = 1;
-  const int ksper = ksteps_for(K, want);
+  // A workgroup's time goes with the k-steps its loop runs, padding included, so among the split counts that fit the
+  // device the one with the fewest padded k-steps per split wins, and of several such the one with the fewest planes
+  // (measured at the 4B shape, 64 tokens: output projection, K = 4096, 12 planes 11.2 us, 8 planes 9.9 us; down
+  // projection, K = 9728, 12 planes 17.4 us, 10 planes 16.4 us: both pad 22 and 51 k-steps to 32 and 64).
+  const int round = kstep_round(T, planes, dtype);
+  int best = 1, best_padded = 0x7FFFFFFF;
+  for (int s = 1; s <= want; ++s) {
+    const int ksper = ksteps_for(K, s);
+    const int padded = (ksper + round - 1) / round * round;
+    if (padded < best_padded) { best_padded = padded; best = s; }
+  }
+  const int ksper = ksteps_for(K, best);
   return (KS + ksper - 1) / ksper;                  // no empty split
 }
 

@@ -40,8 +40,9 @@ struct RowAct {
 // ---- gemm.hip ----
 int gemm_max_splits();
 void gemm_set_units(int n_units);   // compute units of the device (sizes the choice of tile form)
-// number of split-K planes for y[T <= 256, N] = x W^T on a device with n_units compute units
-int gemm_plan_splits(int N, int K, int T, int max_splits, int n_units);
+// number of split-K planes for y[T <= 256, N] = x W^T on a device with n_units compute units; the activations come
+// as `planes` terms of format `dtype`
+int gemm_plan_splits(int N, int K, int T, int max_splits, int n_units, int planes, int dtype);
 // planes (1 or 2) for a call of more than 256 tokens: 2 where halving K lets the 256 x 256 form fill the device twice
 int gemm_plan_splits_long(int N, int T, int planes, int dtype, int n_units);
 // y[split][t][n] (fp32, leading dimension ldy); weights packed (common.h), activations in fragment order
