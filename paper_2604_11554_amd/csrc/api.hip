@@ -214,6 +214,9 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
 
   // residual contribution produced by the previous sub-layer, folded into the next norm
   const float* pend_planes = nullptr; int pend_n = 0; bool pend_moe = false;
+  // MoE decode batches: the gate/up GEMM reads the routing table itself and publishes the grouping (no grouping launch)
+  const int rows_per_expert = c.n_experts ? (int)(((long long)T * c.top_k + c.n_experts - 1) / c.n_experts) : 0;
+  const bool routed = c.n_experts && small && gemm_routed_form(c.n_experts, c.d_ff_expert, xb, T * c.top_k, rows_per_expert);
   auto norm = [&](const h16_t* gain, const int32_t* rows, int n_rows, const Act& x, float* xf) -> hipError_t {
     NormArgs a = {};
     a.h = w.h; a.gain = gain; a.d = d; a.T = n_rows; a.T_total = T; a.eps = c.rms_eps; a.rows = rows;
@@ -286,11 +289,14 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
       ra.logits = w.router; ra.n_planes = s_r; ra.T = T; ra.E = c.n_experts; ra.top_k = c.top_k;
       ra.topk_idx = w.topk_idx; ra.topk_w = w.topk_w; ra.routing_out = io.out_routing; ra.layer = l;
       ra.n_layers = c.n_layers; ra.tok_live = w.meta.tok_live; ra.replay_idx = io.replay_routing;
-      RLX_LAUNCH(RLX_K_GROUP, moe_route(ra, w.group_off, w.sorted_token, w.pair_pos, w.group_ws, st));
+      RLX_LAUNCH(RLX_K_GROUP, moe_route(ra, w.group_off, w.sorted_token, w.pair_pos, w.group_ws, !routed, st));
       const Act act = make_act(w.act, T * c.top_k, c.d_ff_expert, PL, FMT);
-      const int rows_per_expert = (int)(((long long)T * c.top_k + c.n_experts - 1) / c.n_experts);
-      RLX_LAUNCH(RLX_K_GATEUP, gemm_grouped_swiglu(m->w_gate_up[l], c.n_experts, c.d_ff_expert, d, xb,
-                                                   w.sorted_token, w.group_off, T, rows_per_expert, act, st));
+      if (routed)
+        RLX_LAUNCH(RLX_K_GATEUP, gemm_routed_swiglu(m->w_gate_up[l], c.n_experts, c.d_ff_expert, d, xb, w.topk_idx,
+                                                    T * c.top_k, c.top_k, T, act, w.group_off, w.pair_pos, st));
+      else
+        RLX_LAUNCH(RLX_K_GATEUP, gemm_grouped_swiglu(m->w_gate_up[l], c.n_experts, c.d_ff_expert, d, xb,
+                                                     w.sorted_token, w.group_off, T, rows_per_expert, act, st));
       RLX_LAUNCH(RLX_K_DOWN, gemm_grouped_store(m->w_down[l], c.n_experts, d, c.d_ff_expert, act, w.group_off, T,
                                                 rows_per_expert, w.moe_y, st));
       pend_moe = true;

@@ -51,6 +51,11 @@ struct GemmArgs {
   // expert-grouped form: blockIdx.y is the expert, its rows are [group_off[e], group_off[e+1])
   const int32_t* group_off;
   size_t w_expert_stride;     // packed elements between consecutive experts' matrices
+  // expert-grouped decode form without a grouping pass: the kernel finds its expert's rows in the routing table itself
+  const int32_t* route_idx;   // [n_pairs] expert of pair p = token * top_k + slot, or null (rows come from group_off)
+  int n_pairs, top_k;
+  int32_t* pub_group_off;     // [E + 1] written by this launch: first row of every expert in expert order
+  int32_t* pub_pair_pos;      // [n_pairs] written by this launch: row of every pair in expert order
 };
 
 enum { EPI_STORE = 0, EPI_SWIGLU = 1, EPI_LMHEAD = 2 };
@@ -449,9 +454,66 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_expert_kernel(GemmArgs a) {
   const int r32 = lane & 31, half = lane >> 5;
   const int mt0 = blockIdx.z;                       // 32-row tile of the expert's rows
   const int e = blockIdx.y;
-  const int row_base = a.group_off[e];
-  a.T = a.group_off[e + 1] - row_base;
-  if (mt0 * 32 >= a.T) return;                      // uniform over the workgroup, before any barrier
+  int row_base, my_pair = -1;
+  if (a.route_idx) {
+    // No grouping pass: the workgroup reads the routing table (a few KB, the same for every workgroup of the launch)
+    // and finds what a counting sort by expert would have told it: how many pairs go to experts before this one
+    // (row_base), how many to this one, and which, in pair order.  Thread i looks at the pairs i * PPT .. + PPT - 1,
+    // so thread order is pair order.  One round trip, as the look-up of the sorted lists was.  The first workgroup
+    // of each expert publishes the result (first row per expert, row of every pair) for the kernels that follow.
+    __shared__ int32_t route_sum[GEMM_WAVES][2];
+    __shared__ int32_t route_rows[32];              // pairs of this workgroup's tile of the expert's rows
+    const int ppt = (a.n_pairs + GEMM_THREADS - 1) / GEMM_THREADS;
+    const int p0 = (int)threadIdx.x * ppt;
+    int less = 0, eq = 0;
+    for (int i = 0; i < ppt; ++i) {
+      const int p = p0 + i;
+      const int idx = p < a.n_pairs ? a.route_idx[p] : 0x7FFFFFFF;
+      less += idx < e ? 1 : 0;
+      eq += idx == e ? 1 : 0;
+    }
+    int incl = eq;                                  // inclusive prefix of the matches over the wave's lanes
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(incl, o, WAVE);
+      if (lane >= o) incl += v;
+    }
+    less = (int)wave_sum((float)less);              // at most 4096 pairs: exact in fp32
+    if (lane == 63) { route_sum[wave][0] = less; route_sum[wave][1] = incl; }
+    if (threadIdx.x < 32) route_rows[threadIdx.x] = -1;
+    __syncthreads();
+    row_base = 0;
+    int n_rows = 0, before = 0;
+#pragma unroll
+    for (int w = 0; w < GEMM_WAVES; ++w) {
+      row_base += route_sum[w][0];
+      if (w < wave) before += route_sum[w][1];
+      n_rows += route_sum[w][1];
+    }
+    a.T = n_rows;
+    if (blockIdx.x == 0 && mt0 == 0 && threadIdx.x == 0) {   // also for an expert without rows
+      a.pub_group_off[e] = row_base;
+      if (e == (int)gridDim.y - 1) a.pub_group_off[e + 1] = row_base + n_rows;
+    }
+    if (mt0 * 32 >= a.T) return;                    // uniform over the workgroup
+    int pos = before + incl - eq - mt0 * 32;        // place, inside this tile, of the thread's first match
+    for (int i = 0; i < ppt; ++i) {
+      const int p = p0 + i;
+      if (p < a.n_pairs && a.route_idx[p] == e) {   // second look at the same few entries: cache hits
+        if (pos >= 0 && pos < 32) route_rows[pos] = p;
+        ++pos;
+      }
+    }
+    __syncthreads();
+    my_pair = route_rows[r32];                      // -1 past the expert's last row
+    if (blockIdx.x == 0) {
+      if (threadIdx.x < 32 && my_pair >= 0) a.pub_pair_pos[my_pair] = row_base + mt0 * 32 + r32;
+    }
+  } else {
+    row_base = a.group_off[e];
+    a.T = a.group_off[e + 1] - row_base;
+    if (mt0 * 32 >= a.T) return;                    // uniform over the workgroup, before any barrier
+  }
   const h16_t* wbase = a.w[0] + (size_t)e * a.w_expert_stride;
 
   const int KS = a.K >> 4;
@@ -471,7 +533,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_expert_kernel(GemmArgs a) {
   const h16_t* xsrc;
   {
     const int rr = xok ? r : 0;
-    const int row = a.x_rows ? a.x_rows[row_base + rr] : row_base + rr;
+    int row;
+    if (a.route_idx) row = my_pair >= 0 ? my_pair / a.top_k : 0;       // the pair's token
+    else row = a.x_rows ? a.x_rows[row_base + rr] : row_base + rr;
     xsrc = a.x + frag_act_offset(row, 8 * half, 0, a.x_mtiles, PL);
   }
   const size_t x_kstride = (size_t)a.x_mtiles * PL * 512;
@@ -979,6 +1043,32 @@ hipError_t gemm_grouped_store(const h16_t* w, int E, int N, int K, const Act& x,
   a.group_off = group_off; a.w_expert_stride = packed_weight_elems(N, K);
   if (grouped_mt(expected_rows) == 1 && launch_expert<EPI_STORE>(a, a.w_tiles[0], E, x, st)) return hipGetLastError();
   launch_mt<EPI_STORE>(a, a.w_tiles[0], E, grouped_mt(expected_rows), x, st);
+  return hipGetLastError();
+}
+
+// Routed form of the expert-grouped gate/up GEMM at decode: no grouping pass; every workgroup finds its expert's
+// pairs in the routing table (route_idx[token * top_k + slot] = expert), reads the token's row of x and writes act
+// in expert order (pairs of expert 0 first, in pair order: what the counting sort produces).  The launch also
+// publishes group_off[E + 1] and pair_pos[n_pairs] of that order, which the down GEMM and the combine then read.
+bool gemm_routed_form(int E, int F, const Act& x, int n_pairs, int expected_rows) {
+  if (x.planes != 2 || x.dtype != DT_BF16 || grouped_mt(expected_rows) != 1) return false;
+  if (n_pairs > 16 * GEMM_THREADS) return false;    // at most 16 table entries per thread of a workgroup
+  return expert_tile_groups(F / 16, E, g_units.load(std::memory_order_relaxed)) >= 2;
+}
+
+hipError_t gemm_routed_swiglu(const h16_t* w_gate_up, int E, int F, int K, const Act& x, const int32_t* route_idx,
+                              int n_pairs, int top_k, int max_rows, const Act& act, int32_t* group_off,
+                              int32_t* pair_pos, hipStream_t st) {
+  GemmArgs a = {};
+  fill_x(a, x);
+  a.w[0] = w_gate_up; a.w_tiles[0] = F / 16;
+  a.N = 2 * F; a.K = K; a.T = max_rows;
+  a.ksteps_per_split = K / 16;
+  a.act = act.p; a.act_mtiles = act.mtiles();
+  a.w_expert_stride = packed_weight_elems(2 * F, K);
+  a.route_idx = route_idx; a.n_pairs = n_pairs; a.top_k = top_k;
+  a.pub_group_off = group_off; a.pub_pair_pos = pair_pos;
+  if (!launch_expert<EPI_SWIGLU>(a, a.w_tiles[0], E, x, st)) return hipErrorInvalidValue;
   return hipGetLastError();
 }
 

@@ -63,6 +63,14 @@ hipError_t gemm_grouped_swiglu(const h16_t* w_gate_up, int E, int F, int K, cons
 hipError_t gemm_grouped_store(const h16_t* w, int E, int N, int K, const Act& x,
                               const int32_t* group_off, int max_rows, int expected_rows, float* y, hipStream_t st);
 
+// routed form of the gate/up GEMM (decode batches, two-term bf16): the kernel finds its expert's (token, slot) pairs
+// in the routing table route_idx[n_pairs] itself, so no grouping pass runs before it; it writes act in expert order
+// and publishes group_off[E + 1] and pair_pos[n_pairs] of that order for gemm_grouped_store and the combine.
+bool gemm_routed_form(int E, int F, const Act& x, int n_pairs, int expected_rows);
+hipError_t gemm_routed_swiglu(const h16_t* w_gate_up, int E, int F, int K, const Act& x, const int32_t* route_idx,
+                              int n_pairs, int top_k, int max_rows, const Act& act, int32_t* group_off,
+                              int32_t* pair_pos, hipStream_t st);
+
 // ---- elementwise.hip ----
 struct TokenMeta {        // per packed token, built on the device at the start of a call
   int32_t* tok_seq;       // sequence slot of token t
@@ -206,8 +214,9 @@ struct RouterArgs {
 // (token, slot) pairs by expert: one more launch of one workgroup for short lists, three launches of several
 // workgroups for long ones, which pass through `seg_ws` (moe_group_workspace_words() int32 words)
 size_t moe_group_workspace_words();
+// group = false: only the top-k launch (the routed gate/up GEMM reads topk_idx itself and publishes the grouping)
 hipError_t moe_route(const RouterArgs& a, int32_t* group_off, int32_t* sorted_token, int32_t* pair_pos,
-                     int32_t* seg_ws, hipStream_t st);
+                     int32_t* seg_ws, bool group, hipStream_t st);
 
 // ---- sampling.hip ----
 struct FinalizeArgs {

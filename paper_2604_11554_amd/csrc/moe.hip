@@ -285,8 +285,9 @@ __global__ __launch_bounds__(256) void moe_group_place_kernel(RouterArgs a, cons
 size_t moe_group_workspace_words() { return (size_t)GROUP_SEGS * MAX_E; }
 
 hipError_t moe_route(const RouterArgs& a, int32_t* group_off, int32_t* sorted_token, int32_t* pair_pos,
-                     int32_t* seg_ws, hipStream_t st) {
+                     int32_t* seg_ws, bool group, hipStream_t st) {
   hipLaunchKernelGGL(moe_topk_kernel, dim3((a.T + 3) / 4), dim3(256), 0, st, a);
+  if (!group) return hipGetLastError();
   if ((size_t)a.T * a.top_k <= GROUP_ONE_WG_PAIRS) {
     hipLaunchKernelGGL(moe_group_kernel, dim3(1), dim3(256), 0, st, a, group_off, sorted_token, pair_pos);
   } else {

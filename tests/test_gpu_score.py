@@ -137,6 +137,40 @@ def test_score_with_foreign_routing_replay(amd):
     model.close()
 
 
+def test_replay_that_sends_every_token_to_the_same_experts(amd):
+    """A short call (64 tokens: the expert GEMMs take their decode form and the gate/up kernel groups the pairs
+    itself) whose routing record names the same eight experts for every token: each of them receives 64 rows, two
+    32-row tiles, and the other experts none.  Compared with the oracle replaying the same record; the record is
+    echoed bit for bit."""
+    pkg, synthetic = amd
+    shape = RI.TINY_MOE
+    lens = (40, 24)
+    g = np.random.default_rng(21)
+    toks = [g.integers(0, shape.vocab - 2, size=n).astype(np.int32) for n in lens]
+    tg = _targets(toks)
+    omodel = O.OracleModel(shape, 0)
+    fixed = (np.arange(shape.top_k) * 3 + 1) % shape.n_experts        # eight distinct experts
+    rec = [np.broadcast_to(fixed.astype(np.int32), (n, shape.n_layers, shape.top_k)).copy() for n in lens]
+    rec[1][:, 1] = (fixed[::-1] + 1) % shape.n_experts                # another set, in another order, for one layer
+    ores = O.forward_full(omodel, toks, forced_routing=rec)
+    olp = []
+    for r, t in zip(ores, toks):
+        lp = log_softmax(r["logits"].astype(np.float64), axis=-1)
+        olp.append(np.concatenate([lp[np.arange(len(t) - 1), t[1:]], [0.0]]))
+    model = synthetic.model_from_shape(shape, 0, activation_split=1)
+    eng = pkg.RolloutEngine(model, n_blocks=16, max_seqs=4, max_chunk_tokens=sum(lens), max_blocks_per_seq=8)
+    for i in range(len(lens)):
+        eng.add_sequence(300 + i, temperature=1.0, reserve_tokens=max(lens) + 16)
+    lp, routing = eng.score([0, 1], toks, tg, replay_routing=rec, want_routing=True)
+    torch.cuda.synchronize()
+    glp = _split(lp, lens)
+    worst = max(float(np.abs(a - b).max()) for a, b in zip(glp, olp))
+    say("one expert set for all %d tokens: max |dlogprob| = %.4f" % (sum(lens), worst))
+    assert worst <= LOGPROB_BAR
+    np.testing.assert_array_equal(routing.cpu().numpy(), np.concatenate(rec))
+    model.close()
+
+
 def test_replay_table_with_repeated_and_invalid_ids(amd):
     """A defective routing record (an expert listed twice for a token, ids outside the experts): every such slot
     falls back to the layer's own best expert not yet in the token's list, so that no expert receives a token twice
