@@ -309,6 +309,27 @@ def run_batch(args, workload, with_cpu_baseline):
     total_steps = n_decode - 1
     K = min(steps if steps > 0 else total_steps, total_steps)
     W = args.warmup
+    # Fewer timed steps than the decode phase has: they are taken around the middle of the phase, not at its start.
+    # A step's cost is linear in the cached positions, so the mean step of the whole phase is the step at the mean
+    # context; the first steps of the phase, with the shortest contexts, understate it.  The response tokens before
+    # the window are random ids appended by an untimed prefill pass in place of sampled ones (same cache contents
+    # as far as cost goes); the token that the prompt prefill sampled is dropped.
+    skip = 0
+    if not grouped and not args.from_start and K + 2 < total_steps:
+        skip = (total_steps - K) // 2            # warm-up and class-timing steps run on a saved state and are undone
+    if skip > 0:
+        g = np.random.default_rng(12345)
+        filler = [g.integers(0, shape.vocab - 2, size=skip).astype(np.int32) for _ in range(bsz)]
+        t0 = time.perf_counter()
+        i = 0
+        while i < bsz:
+            j = min(bsz, i + max(1, chunk_budget // skip))
+            eng.prefill(list(range(i, j)), filler[i:j])
+            i = j
+        torch.cuda.synchronize()
+        log("response tokens 1..%d of every sequence appended as random ids (%.2f s, untimed): the timed steps emit "
+            "tokens %d..%d of %d" % (skip, time.perf_counter() - t0, skip + 2, skip + 1 + K, n_decode))
+        plen = plen + skip                       # cached positions at the start of the decode steps that follow
     lp_buf = torch.zeros((K + W + 64, bsz), dtype=torch.float32, device=dev)
     # MoE: the routing every timed step captures is kept (what Rollout Routing Replay would consume); the experts a
     # step streams are counted from it afterwards
@@ -402,9 +423,13 @@ def run_batch(args, workload, with_cpu_baseline):
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": "%s: %s, batch %d, prompts uniform %d..%d, %d decoded tokens, paged %s KV block 16, "
-                               "temperature 1 Gumbel-max" % (workload, shape.name, bsz, plen.min(), plen.max(),
+                               "temperature 1 Gumbel-max" % (workload, shape.name, bsz, wl.prompt_lens.min(), wl.prompt_lens.max(),
                                                               n_decode, args.dtype),
-                   "activation_split": split, "prefill_tokens_per_s": float(pf_lens.sum() / t_prefill)},
+                   "activation_split": split, "prefill_tokens_per_s": float(pf_lens.sum() / t_prefill),
+                   "timed_steps": ("the whole decode phase" if K == total_steps else
+                                   "%d steps from the start of the decode phase" % K if skip == 0 else
+                                   "%d steps around the middle of the decode phase, after %d response tokens per "
+                                   "sequence (random ids appended by an untimed prefill pass)" % (K, skip))},
         # the prefill chunks that filled the cache before the timed decode steps (MFMA-bound part of the path)
         "prefill": {"tokens": int(pf_lens.sum()), "seconds": t_prefill, "tokens_per_s": float(pf_lens.sum() / t_prefill),
                     "bound": "mfma", "achieved": prefill_flops(shape, pf_lens) / t_prefill / 1e12, "peak": 2500.0,
@@ -681,7 +706,9 @@ def prefill_batch_nosample(eng, wl, bsz, plen, chunk_budget, embeds):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=0, help="decode steps to time (0 = the whole decode phase)")
+    ap.add_argument("--steps", type=int, default=0, help="decode steps to time (0 = the whole decode phase); fewer than "
+                    "the phase has are taken around its middle")
+    ap.add_argument("--from-start", action="store_true", help="with --steps: time the first steps of the decode phase instead")
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="default",
                     choices=["default", "dense_b64", "moe_b128", "grouped_b256", "omni_b64"],
