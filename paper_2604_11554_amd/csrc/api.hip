@@ -113,6 +113,8 @@ struct Workspace {
   float* moe_y;      // [T*top_k, d]
   int32_t* topk_idx; float* topk_w;
   int32_t *group_ws, *group_off, *sorted_token, *pair_pos;
+  int32_t *item_expert, *item_tile;   // (expert, row tile) list of the grouped GEMMs of long calls
+  int max_items;
   h16_t* x_lm;      // [S, d]
   float* lm_part;    // [S][tiles][4]
   size_t bytes;
@@ -171,6 +173,9 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
     w.group_off = (int32_t*)take((size_t)(c.n_experts + 1) * 4);
     w.sorted_token = (int32_t*)take(P * 4);
     w.pair_pos = (int32_t*)take(P * 4);
+    w.max_items = (int)(P / 256) + c.n_experts;       // tiles of 256 rows: at most one partial tile per expert
+    w.item_expert = (int32_t*)take((size_t)w.max_items * 4);
+    w.item_tile = (int32_t*)take((size_t)w.max_items * 4);
   } else {
     w.act = (h16_t*)take(frag_act_elems(T, c.d_ff, PL) * 2);
   }
@@ -217,6 +222,11 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
   // MoE decode batches: the gate/up GEMM reads the routing table itself and publishes the grouping (no grouping launch)
   const int rows_per_expert = c.n_experts ? (int)(((long long)T * c.top_k + c.n_experts - 1) / c.n_experts) : 0;
   const bool routed = c.n_experts && small && gemm_routed_form(c.n_experts, c.d_ff_expert, xb, T * c.top_k, rows_per_expert);
+  // long calls: the grouped GEMMs run over the list of (expert, row tile) items that the grouping pass writes
+  const int item_rows = (c.n_experts && !small && moe_group_lists_items(T, c.top_k))
+                            ? gemm_grouped_item_rows(c.n_experts, c.d_ff_expert, d, xb, T * c.top_k, rows_per_expert) : 0;
+  const GroupItems items = {w.item_expert, w.item_tile, w.max_items};
+  const GroupItems* itp = item_rows == 256 ? &items : nullptr;
   auto norm = [&](const h16_t* gain, const int32_t* rows, int n_rows, const Act& x, float* xf) -> hipError_t {
     NormArgs a = {};
     a.h = w.h; a.gain = gain; a.d = d; a.T = n_rows; a.T_total = T; a.eps = c.rms_eps; a.rows = rows;
@@ -289,16 +299,17 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
       ra.logits = w.router; ra.n_planes = s_r; ra.T = T; ra.E = c.n_experts; ra.top_k = c.top_k;
       ra.topk_idx = w.topk_idx; ra.topk_w = w.topk_w; ra.routing_out = io.out_routing; ra.layer = l;
       ra.n_layers = c.n_layers; ra.tok_live = w.meta.tok_live; ra.replay_idx = io.replay_routing;
-      RLX_LAUNCH(RLX_K_GROUP, moe_route(ra, w.group_off, w.sorted_token, w.pair_pos, w.group_ws, !routed, st));
+      RLX_LAUNCH(RLX_K_GROUP, moe_route(ra, w.group_off, w.sorted_token, w.pair_pos, w.group_ws, !routed, itp ? item_rows : 0,
+                                         w.max_items, w.item_expert, w.item_tile, st));
       const Act act = make_act(w.act, T * c.top_k, c.d_ff_expert, PL, FMT);
       if (routed)
         RLX_LAUNCH(RLX_K_GATEUP, gemm_routed_swiglu(m->w_gate_up[l], c.n_experts, c.d_ff_expert, d, xb, w.topk_idx,
                                                     T * c.top_k, c.top_k, T, act, w.group_off, w.pair_pos, st));
       else
         RLX_LAUNCH(RLX_K_GATEUP, gemm_grouped_swiglu(m->w_gate_up[l], c.n_experts, c.d_ff_expert, d, xb,
-                                                     w.sorted_token, w.group_off, T, rows_per_expert, act, st));
+                                                     w.sorted_token, w.group_off, T, rows_per_expert, act, itp, st));
       RLX_LAUNCH(RLX_K_DOWN, gemm_grouped_store(m->w_down[l], c.n_experts, d, c.d_ff_expert, act, w.group_off, T,
-                                                rows_per_expert, w.moe_y, st));
+                                                rows_per_expert, w.moe_y, itp, st));
       pend_moe = true;
     }
   }

@@ -56,6 +56,9 @@ struct GemmArgs {
   int n_pairs, top_k;
   int32_t* pub_group_off;     // [E + 1] written by this launch: first row of every expert in expert order
   int32_t* pub_pair_pos;      // [n_pairs] written by this launch: row of every pair in expert order
+  // large-batch grouped form over a list of (expert, row tile) items: blockIdx.y is the item
+  const int32_t* item_expert; // [grid y] expert of the item, -1: none
+  const int32_t* item_tile;   // [grid y] tile of 256 rows of the expert's rows
 };
 
 enum { EPI_STORE = 0, EPI_SWIGLU = 1, EPI_LMHEAD = 2 };
@@ -657,12 +660,17 @@ __global__ __launch_bounds__(LG_THREADS) void gemm_large_kernel(GemmArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r32 = lane & 31, half = lane >> 5;
   const int wr = wave & 3, wt = wave >> 2;
-  const int mt_base = blockIdx.z * LG_TILES;
+  int mt_base = blockIdx.z * LG_TILES;
   int split = blockIdx.y;
   int row_base = 0;
   const bool grouped = a.group_off != nullptr;
   if (grouped) {
-    const int e = blockIdx.y;
+    int e = blockIdx.y;
+    if (a.item_expert) {                            // the grid runs over the list of (expert, row tile) items
+      e = a.item_expert[blockIdx.y];
+      if (e < 0) return;                            // uniform over the workgroup
+      mt_base = a.item_tile[blockIdx.y] * LG_TILES;
+    }
     row_base = a.group_off[e];
     a.T = a.group_off[e + 1] - row_base;
     if (mt_base * 32 >= a.T) return;                // uniform over the workgroup, before any barrier
@@ -835,6 +843,7 @@ void launch_large_one(const GemmArgs& a, dim3 grid, hipStream_t st) {
 template <int EPI>
 void launch_large(const GemmArgs& a, int n_tiles, int grid_y, int rows, hipStream_t st) {
   dim3 grid((n_tiles + LG_TILES - 1) / LG_TILES, grid_y, (rows + 32 * LG_TILES - 1) / (32 * LG_TILES));
+  if (a.item_expert) grid.z = 1;                    // grid_y is the length of the item list
   launch_large_one<EPI, 2, DT_BF16>(a, grid, st);
 }
 
@@ -1016,9 +1025,20 @@ static int grouped_mt(int expected_rows) {
   return expected_rows <= 16 ? 1 : (expected_rows <= 40 ? 2 : (expected_rows <= 128 ? 4 : 8));
 }
 
+// The item list serves the 256 x 256 form only: two-term bf16 activations, more than 128 expected rows per expert,
+// and enough items to fill the device twice (the condition under which launch_mt takes that form).
+int gemm_grouped_item_rows(int E, int F, int N, const Act& x, int n_pairs, int expected_rows) {
+  if (x.planes != 2 || x.dtype != DT_BF16 || grouped_mt(expected_rows) != 8) return 0;
+  const long items = n_pairs / (32 * LG_TILES);     // at least this many full tiles
+  const long units = g_units.load(std::memory_order_relaxed);
+  const long xg = (F / 16 + LG_TILES - 1) / LG_TILES, xd = ((N + 31) / 32 + LG_TILES - 1) / LG_TILES;
+  (void)E;
+  return (xg * items >= 2 * units && xd * items >= 2 * units) ? 32 * LG_TILES : 0;
+}
+
 hipError_t gemm_grouped_swiglu(const h16_t* w_gate_up, int E, int F, int K, const Act& x, const int32_t* x_rows,
                                const int32_t* group_off, int max_rows, int expected_rows, const Act& act,
-                               hipStream_t st) {
+                               const GroupItems* items, hipStream_t st) {
   GemmArgs a = {};
   fill_x(a, x);
   a.x_rows = x_rows;
@@ -1027,13 +1047,18 @@ hipError_t gemm_grouped_swiglu(const h16_t* w_gate_up, int E, int F, int K, cons
   a.ksteps_per_split = K / 16;
   a.act = act.p; a.act_mtiles = act.mtiles();
   a.group_off = group_off; a.w_expert_stride = packed_weight_elems(2 * F, K);
+  if (items) {
+    a.item_expert = items->expert; a.item_tile = items->tile;
+    launch_large<EPI_SWIGLU>(a, a.w_tiles[0], items->max_items, max_rows, st);
+    return hipGetLastError();
+  }
   if (grouped_mt(expected_rows) == 1 && launch_expert<EPI_SWIGLU>(a, a.w_tiles[0], E, x, st)) return hipGetLastError();
   launch_mt<EPI_SWIGLU>(a, a.w_tiles[0], E, grouped_mt(expected_rows), x, st);
   return hipGetLastError();
 }
 
 hipError_t gemm_grouped_store(const h16_t* w, int E, int N, int K, const Act& x, const int32_t* group_off,
-                              int max_rows, int expected_rows, float* y, hipStream_t st) {
+                              int max_rows, int expected_rows, float* y, const GroupItems* items, hipStream_t st) {
   GemmArgs a = {};
   fill_x(a, x);
   a.w[0] = w; a.w_tiles[0] = (N + 31) / 32;
@@ -1041,6 +1066,11 @@ hipError_t gemm_grouped_store(const h16_t* w, int E, int N, int K, const Act& x,
   a.ksteps_per_split = K / 16;
   a.y = y; a.ldy = N;
   a.group_off = group_off; a.w_expert_stride = packed_weight_elems(N, K);
+  if (items) {
+    a.item_expert = items->expert; a.item_tile = items->tile;
+    launch_large<EPI_STORE>(a, a.w_tiles[0], items->max_items, max_rows, st);
+    return hipGetLastError();
+  }
   if (grouped_mt(expected_rows) == 1 && launch_expert<EPI_STORE>(a, a.w_tiles[0], E, x, st)) return hipGetLastError();
   launch_mt<EPI_STORE>(a, a.w_tiles[0], E, grouped_mt(expected_rows), x, st);
   return hipGetLastError();

@@ -57,11 +57,17 @@ hipError_t gemm_lmhead(const h16_t* w_lm, int V, int K, const Act& x, int T, flo
                        const int32_t* row_seq, bool draw, hipStream_t st);
 // expert-grouped forms: rows [group_off[e], group_off[e+1]) belong to expert e = blockIdx.y; max_rows bounds the rows
 // of one expert, expected_rows (pairs / experts) picks the token-tile height
+// items (optional, large-batch form only: gemm_grouped_item_rows() > 0): the list of (expert, row tile) pairs from
+// moe_route; the grid then runs over the list instead of over (expert, tile index up to max_rows)
+struct GroupItems { const int32_t* expert; const int32_t* tile; int max_items; };
+// rows per tile of the form the grouped GEMMs take for this call if it can run over an item list, else 0
+int gemm_grouped_item_rows(int E, int F, int N, const Act& x, int n_pairs, int expected_rows);
 hipError_t gemm_grouped_swiglu(const h16_t* w_gate_up, int E, int F, int K, const Act& x, const int32_t* x_rows,
                                const int32_t* group_off, int max_rows, int expected_rows, const Act& act,
-                               hipStream_t st);
+                               const GroupItems* items, hipStream_t st);
 hipError_t gemm_grouped_store(const h16_t* w, int E, int N, int K, const Act& x,
-                              const int32_t* group_off, int max_rows, int expected_rows, float* y, hipStream_t st);
+                              const int32_t* group_off, int max_rows, int expected_rows, float* y,
+                              const GroupItems* items, hipStream_t st);
 
 // routed form of the gate/up GEMM (decode batches, two-term bf16): the kernel finds its expert's (token, slot) pairs
 // in the routing table route_idx[n_pairs] itself, so no grouping pass runs before it; it writes act in expert order
@@ -214,9 +220,14 @@ struct RouterArgs {
 // (token, slot) pairs by expert: one more launch of one workgroup for short lists, three launches of several
 // workgroups for long ones, which pass through `seg_ws` (moe_group_workspace_words() int32 words)
 size_t moe_group_workspace_words();
-// group = false: only the top-k launch (the routed gate/up GEMM reads topk_idx itself and publishes the grouping)
+// group = false: only the top-k launch (the routed gate/up GEMM reads topk_idx itself and publishes the grouping).
+// Long lists (moe_group_lists_items) with tile_rows > 0: item_expert / item_tile[max_items] receive the list of
+// (expert, tile of tile_rows rows) pairs that have rows, experts ascending, the rest marked -1; max_items must be at
+// least T * top_k / tile_rows + E.
+bool moe_group_lists_items(int T, int top_k);
 hipError_t moe_route(const RouterArgs& a, int32_t* group_off, int32_t* sorted_token, int32_t* pair_pos,
-                     int32_t* seg_ws, bool group, hipStream_t st);
+                     int32_t* seg_ws, bool group, int tile_rows, int max_items, int32_t* item_expert,
+                     int32_t* item_tile, hipStream_t st);
 
 // ---- sampling.hip ----
 struct FinalizeArgs {

@@ -231,8 +231,14 @@ __global__ __launch_bounds__(256) void moe_group_count_kernel(RouterArgs a, int3
 }
 
 // launch 2 of 3 (one workgroup, thread = expert): the counts of seg_ws become first positions, in place
-__global__ __launch_bounds__(MAX_E) void moe_group_scan_kernel(int E, int32_t* seg_ws, int32_t* group_off) {
+// With tile_rows > 0 it also lists the row tiles of the grouped GEMMs that follow: item i = (expert, tile of
+// tile_rows of its rows), experts ascending, then n_items .. max_items - 1 marked empty (-1).  A grid over
+// (expert, tile index up to the longest expert could have) is mostly workgroups that find nothing to do; at 32 768
+// tokens they were nine tenths of the grid and cost 3 % of the prefill.
+__global__ __launch_bounds__(MAX_E) void moe_group_scan_kernel(int E, int32_t* seg_ws, int32_t* group_off, int tile_rows,
+                                                               int max_items, int32_t* item_expert, int32_t* item_tile) {
   __shared__ int32_t tot[MAX_E];
+  __shared__ int32_t tile0[MAX_E + 1];
   const int e = threadIdx.x;
   int32_t cnt[GROUP_SEGS];
 #pragma unroll
@@ -242,6 +248,23 @@ __global__ __launch_bounds__(MAX_E) void moe_group_scan_kernel(int E, int32_t* s
   for (int s = 0; s < GROUP_SEGS; ++s) { const int c = cnt[s]; cnt[s] = run; run += c; }
   tot[e] = run;
   __syncthreads();
+  if (tile_rows > 0) {
+    if (e == 0) {    // a few hundred additions once per layer
+      int acc = 0;
+      for (int i = 0; i < MAX_E; ++i) {
+        tile0[i] = acc;
+        acc += i < E ? (tot[i] + tile_rows - 1) / tile_rows : 0;
+      }
+      tile0[MAX_E] = acc;
+    }
+    __syncthreads();
+    if (e < E) {
+      const int n = tile0[e + 1] - tile0[e];
+      for (int i = 0; i < n; ++i)
+        if (tile0[e] + i < max_items) { item_expert[tile0[e] + i] = e; item_tile[tile0[e] + i] = i; }
+    }
+    for (int i = tile0[MAX_E] + e; i < max_items; i += MAX_E) { item_expert[i] = -1; item_tile[i] = 0; }
+  }
   if (e < 64) {      // exclusive scan over experts, as in the one-workgroup kernel
     int t4[4], sum = 0;
 #pragma unroll
@@ -284,15 +307,19 @@ __global__ __launch_bounds__(256) void moe_group_place_kernel(RouterArgs a, cons
 
 size_t moe_group_workspace_words() { return (size_t)GROUP_SEGS * MAX_E; }
 
+bool moe_group_lists_items(int T, int top_k) { return (size_t)T * top_k > GROUP_ONE_WG_PAIRS; }
+
 hipError_t moe_route(const RouterArgs& a, int32_t* group_off, int32_t* sorted_token, int32_t* pair_pos,
-                     int32_t* seg_ws, bool group, hipStream_t st) {
+                     int32_t* seg_ws, bool group, int tile_rows, int max_items, int32_t* item_expert,
+                     int32_t* item_tile, hipStream_t st) {
   hipLaunchKernelGGL(moe_topk_kernel, dim3((a.T + 3) / 4), dim3(256), 0, st, a);
   if (!group) return hipGetLastError();
   if ((size_t)a.T * a.top_k <= GROUP_ONE_WG_PAIRS) {
     hipLaunchKernelGGL(moe_group_kernel, dim3(1), dim3(256), 0, st, a, group_off, sorted_token, pair_pos);
   } else {
     hipLaunchKernelGGL(moe_group_count_kernel, dim3(GROUP_WGS), dim3(256), 0, st, a, seg_ws);
-    hipLaunchKernelGGL(moe_group_scan_kernel, dim3(1), dim3(MAX_E), 0, st, a.E, seg_ws, group_off);
+    hipLaunchKernelGGL(moe_group_scan_kernel, dim3(1), dim3(MAX_E), 0, st, a.E, seg_ws, group_off, tile_rows, max_items,
+                       item_expert, item_tile);
     hipLaunchKernelGGL(moe_group_place_kernel, dim3(GROUP_WGS), dim3(256), 0, st, a, (const int32_t*)seg_ws,
                        sorted_token, pair_pos);
   }
