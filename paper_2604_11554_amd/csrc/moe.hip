@@ -248,43 +248,39 @@ __global__ __launch_bounds__(MAX_E) void moe_group_scan_kernel(int E, int32_t* s
   for (int s = 0; s < GROUP_SEGS; ++s) { const int c = cnt[s]; cnt[s] = run; run += c; }
   tot[e] = run;
   __syncthreads();
-  if (tile_rows > 0) {
-    if (e == 0) {    // a few hundred additions once per layer
-      int acc = 0;
-      for (int i = 0; i < MAX_E; ++i) {
-        tile0[i] = acc;
-        acc += i < E ? (tot[i] + tile_rows - 1) / tile_rows : 0;
-      }
-      tile0[MAX_E] = acc;
-    }
-    __syncthreads();
-    if (e < E) {
-      const int n = tile0[e + 1] - tile0[e];
-      for (int i = 0; i < n; ++i)
-        if (tile0[e] + i < max_items) { item_expert[tile0[e] + i] = e; item_tile[tile0[e] + i] = i; }
-    }
-    for (int i = tile0[MAX_E] + e; i < max_items; i += MAX_E) { item_expert[i] = -1; item_tile[i] = 0; }
-  }
-  if (e < 64) {      // exclusive scan over experts, as in the one-workgroup kernel
-    int t4[4], sum = 0;
+  const int my_tiles = (tile_rows > 0 && e < E) ? (run + tile_rows - 1) / tile_rows : 0;   // row tiles of expert e
+  if (e < 64) {      // exclusive scans over experts (rows, row tiles), as in the one-workgroup kernel
+    int t4[4], n4[4], sum = 0, nsum = 0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { t4[j] = tot[4 * e + j]; sum += t4[j]; }
-    int incl = sum;
+    for (int j = 0; j < 4; ++j) {
+      t4[j] = tot[4 * e + j];
+      sum += t4[j];
+      n4[j] = (tile_rows > 0 && 4 * e + j < E) ? (t4[j] + tile_rows - 1) / tile_rows : 0;
+      nsum += n4[j];
+    }
+    int incl = sum, nincl = nsum;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
-      int v = __shfl_up(incl, o, WAVE);
-      if (e >= o) incl += v;
+      const int v = __shfl_up(incl, o, WAVE), nv = __shfl_up(nincl, o, WAVE);
+      if (e >= o) { incl += v; nincl += nv; }
     }
-    int off = incl - sum;
+    int off = incl - sum, noff = nincl - nsum;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       tot[4 * e + j] = off;
+      tile0[4 * e + j] = noff;
       if (4 * e + j < E) group_off[4 * e + j] = off;
       off += t4[j];
+      noff += n4[j];
     }
-    if (e == 63) group_off[E] = incl;
+    if (e == 63) { group_off[E] = incl; tile0[MAX_E] = nincl; }
   }
   __syncthreads();
+  if (tile_rows > 0) {
+    for (int i = 0; i < my_tiles; ++i)
+      if (tile0[e] + i < max_items) { item_expert[tile0[e] + i] = e; item_tile[tile0[e] + i] = i; }
+    for (int i = tile0[MAX_E] + e; i < max_items; i += MAX_E) { item_expert[i] = -1; item_tile[i] = 0; }
+  }
   const int off = tot[e];
 #pragma unroll
   for (int s = 0; s < GROUP_SEGS; ++s) seg_ws[(size_t)s * MAX_E + e] = off + cnt[s];
