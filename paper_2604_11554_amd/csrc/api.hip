@@ -113,6 +113,7 @@ struct Workspace {
   float* moe_y;      // [T*top_k, d]
   int32_t* topk_idx; float* topk_w;
   int32_t *group_ws, *group_off, *sorted_token, *pair_pos;
+  float* x_ss;                        // [T][4] sums of squares of the row quarters (norm of short calls, Act::ss)
   int32_t *item_expert, *item_tile;   // (expert, row tile) list of the grouped GEMMs of long calls
   int max_items;
   h16_t* x_lm;      // [S, d]
@@ -151,6 +152,7 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
   w.h = (float*)take((size_t)T * c.d_model * 4);
   const int PL = c.activation_split ? 2 : 1;
   w.xb = (h16_t*)take(frag_act_elems(T, c.d_model, PL) * 2);
+  w.x_ss = (float*)take((size_t)T * NORM_PARTS * 4);
   w.router = c.n_experts ? (float*)take((size_t)plane_rows(T) * c.n_experts * 4) : nullptr;
   w.qkv = (float*)take((size_t)plane_rows(T) * qkv_dim * 4);
   w.q = (h16_t*)take((size_t)PL * T * qdim * 2);
@@ -212,7 +214,8 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
   const bool small = T <= 256;
   const int PL = c.activation_split ? 2 : 1;
   const int FMT = c.dtype;
-  const Act xb = make_act(w.xb, T, d, PL, FMT), ob = make_act(w.ob, T, qdim, PL, FMT);
+  Act xb = make_act(w.xb, T, d, PL, FMT);
+  const Act ob = make_act(w.ob, T, qdim, PL, FMT);
   const RowAct qb = {w.q, (size_t)T * qdim, qdim, PL, FMT};
 
   RLX_HIP(embed_tokens(m->embed, c.vocab, d, io.tokens, io.input_embeds, T, w.h, FMT, st));
@@ -225,6 +228,10 @@ int run_layers(const rlx_model* m, h16_t* pool, int64_t n_blocks, const Workspac
   // long calls: the grouped GEMMs run over the list of (expert, row tile) items that the grouping pass writes
   const int item_rows = (c.n_experts && !small && moe_group_lists_items(T, c.top_k))
                             ? gemm_grouped_item_rows(c.n_experts, c.d_ff_expert, d, xb, T * c.top_k, rows_per_expert) : 0;
+  // short calls: the norm runs as four workgroups per row and leaves the row's common factor to the GEMMs that read
+  // xb (q|k|v, gate/up, router); not for fp16 (unnormalised rows would strain its range) and not where the grouped
+  // gate/up goes through a row list
+  if (small && FMT == DT_BF16 && rmsnorm_in_parts(d) && (c.n_experts == 0 || routed)) { xb.ss = w.x_ss; xb.eps = c.rms_eps; }
   const GroupItems items = {w.item_expert, w.item_tile, w.max_items};
   const GroupItems* itp = item_rows == 256 ? &items : nullptr;
   auto norm = [&](const h16_t* gain, const int32_t* rows, int n_rows, const Act& x, float* xf) -> hipError_t {

@@ -236,6 +236,80 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(NormArgs a) {
   }
 }
 
+// Short calls: NORM_PARTS workgroups per row, each a quarter of it.  The kernel above puts a whole row (its
+// residual and up to sixteen planes, ~100 KB at the 4B shape) through one compute unit, which takes in ~40 GB/s:
+// 2.3 us of its 7-8.  A quarter of a row cannot know the row's sum of squares, so the common factor rstd is left
+// out: the kernel writes gain * h as 16-bit terms and the quarter's sum of squares (Act::ss), and the GEMM that
+// reads the row multiplies its outputs by rstd, which is the same product in another order.  PR as above.
+template <int PR>
+__global__ __launch_bounds__(256) void rmsnorm_part_kernel(NormArgs a) {
+  __shared__ float sh[4];
+  const int t = blockIdx.x, part = blockIdx.y;
+  const int nv = a.d >> 2;
+  const int nvp = (nv + NORM_PARTS - 1) / NORM_PARTS;        // float4 slices per part: at most 256 (host check)
+  const int i = part * nvp + (int)threadIdx.x;
+  const bool mine = (int)threadIdx.x < nvp && i < nv;
+  const int ic = mine ? i : part * nvp < nv ? part * nvp : 0;   // clamped: loads are unconditional, stores masked
+  float* hrow = a.h + (size_t)t * a.d;
+  const int dt = a.x.dtype;
+  f32x4 v = *reinterpret_cast<const f32x4*>(hrow + 4 * ic);
+  const u32x2 gb = *reinterpret_cast<const u32x2*>(a.gain + 4 * ic);
+  if (a.add) {
+    for (int s0 = 0; s0 < a.n_planes; s0 += PR) {            // PR planes per round, added in plane order
+      f32x4 p[PR];
+#pragma unroll
+      for (int q = 0; q < PR; ++q) {
+        const int sc = s0 + q < a.n_planes ? s0 + q : a.n_planes - 1;
+        p[q] = *reinterpret_cast<const f32x4*>(a.add + ((size_t)sc * a.T_total + t) * a.d + 4 * ic);
+      }
+#pragma unroll
+      for (int q = 0; q < PR; ++q)
+        if (s0 + q < a.n_planes) v += p[q];
+    }
+  }
+  if (a.moe_y) {
+    int pp[8];
+    float pw[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const bool ok = k < a.top_k;
+      pp[k] = ok ? a.pair_pos[t * a.top_k + k] : 0;
+      pw[k] = ok ? a.topk_w[t * a.top_k + k] : 0.f;
+    }
+    f32x4 y[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) y[k] = *reinterpret_cast<const f32x4*>(a.moe_y + (size_t)pp[k] * a.d + 4 * ic);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc += y[k] * pw[k];         // slot order k = 0..K-1; unused slots weigh 0
+    v += acc;
+  }
+  float ss = 0.f;
+  if (mine) {
+    if (a.add || a.moe_y) *reinterpret_cast<f32x4*>(hrow + 4 * i) = v;
+    ss = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+  }
+  const float tot = block_sum_256(ss, sh);
+  if (threadIdx.x == 0) a.x.ss[(size_t)NORM_PARTS * t + part] = tot;
+  if (!mine) return;
+  f32x4 o;
+  o[0] = v[0] * h16_to_f32((h16_t)(gb[0] & 0xFFFFu), dt);
+  o[1] = v[1] * h16_to_f32((h16_t)(gb[0] >> 16), dt);
+  o[2] = v[2] * h16_to_f32((h16_t)(gb[1] & 0xFFFFu), dt);
+  o[3] = v[3] * h16_to_f32((h16_t)(gb[1] >> 16), dt);
+  h16_t hi[4], lo[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) split_h16(o[e], hi[e], lo[e], dt);
+  const int k = 4 * i;
+  h16_t* xo = a.x.p + frag_act_offset(t, k & ~7, 0, a.x.mtiles(), a.x.planes) + (k & 7);
+  u32x2 pk = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
+  *reinterpret_cast<u32x2*>(xo) = pk;
+  if (a.x.planes == 2) {
+    u32x2 pk2 = {(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
+    *reinterpret_cast<u32x2*>(xo + 512) = pk2;
+  }
+}
+
 // grid (token, head group): each of the four waves owns one head; lane i < hd/2 owns the pair (i, i + hd/2).
 // The form of short calls: decode steps and chunks of up to 1024 tokens, any number of split-K planes.
 __global__ __launch_bounds__(256) void qk_rope_append_kernel(RopeArgs a) {
@@ -507,8 +581,20 @@ static void launch_rmsnorm(const NormArgs& a, hipStream_t st) {
   else hipLaunchKernelGGL((rmsnorm_kernel<(NV < 4 ? NV : 1), 16>), dim3(a.T), dim3(256), 0, st, a);
 }
 
+// rows in quarters, the common factor left to the consumer: only where the output asks for it (Act::ss)
+bool rmsnorm_in_parts(int d) { return (d >> 2) <= NORM_PARTS * 256; }
+
 hipError_t rmsnorm(const NormArgs& a, hipStream_t st) {
   const int nv = a.d >> 2;                   // float4 slices of a row; 256 threads hold NV each
+  if (a.x.ss) {
+    if (a.rows || a.xf || !rmsnorm_in_parts(a.d)) return hipErrorInvalidValue;
+    const int np = a.add ? a.n_planes : 0;
+    const dim3 grid(a.T, NORM_PARTS);
+    if (np <= 4) hipLaunchKernelGGL((rmsnorm_part_kernel<4>), grid, dim3(256), 0, st, a);
+    else if (np <= 8) hipLaunchKernelGGL((rmsnorm_part_kernel<8>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((rmsnorm_part_kernel<16>), grid, dim3(256), 0, st, a);
+    return hipGetLastError();
+  }
   if (nv <= 256) launch_rmsnorm<1>(a, st);
   else if (nv <= 512) launch_rmsnorm<2>(a, st);
   else if (nv <= 768) launch_rmsnorm<3>(a, st);

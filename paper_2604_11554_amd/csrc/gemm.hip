@@ -31,6 +31,8 @@ constexpr int GEMM_THREADS = GEMM_WAVES * WAVE;
 struct GemmArgs {
   const h16_t* x;        // fragment-ordered activations [T_x, K], `PL` planes
   int x_mtiles;           // ceil(T_x / 32)
+  const float* x_ss;      // optional: activation row t lacks the factor rstd(t) of its norm (Act::ss); outputs take it
+  float x_eps;
   const int32_t* x_rows;  // grouped gate/up: logical row r of the group reads activation row x_rows[r]
   const h16_t* w[3];     // packed weights, up to three stacked row segments
   int w_tiles[3];         // 32-row tiles per segment
@@ -96,9 +98,19 @@ __device__ __forceinline__ float gumbel_from_u32(uint32_t r) {
 
 // Epilogue of one 32-row weight tile `nt` over token tiles mt0 .. mt0 + MT - 1: lane holds token r32 of each token
 // tile, rows n0 + 8q + 4*half + {0..3}, q = 0..3, of the accumulators.
+// factor that the norm left out of activation row `tok` (Act::ss): the same expression as in the norm kernel
+__device__ __forceinline__ f32x4 row_ss(const GemmArgs& a, int tok) {
+  return *reinterpret_cast<const f32x4*>(a.x_ss + (size_t)NORM_PARTS * tok);
+}
+__device__ __forceinline__ float row_rstd(const GemmArgs& a, const f32x4& p) {
+  return 1.0f / sqrtf(((p[0] + p[1]) + (p[2] + p[3])) / (float)a.K + a.x_eps);
+}
+
+// rs[m]: factor of the lane's activation row in token tile m (row_rstd, or 1), fetched by the caller before its main
+// loop so that the round trip is not spent at the end of the kernel
 template <int MT, int EPI, int PL, int FMT>
 __device__ __forceinline__ void tile_epilogue(const GemmArgs& a, const f32x16 (&acc)[MT], int nt, int n_tiles, int mt0,
-                                              int split, int row_base, int lane) {
+                                              int split, int row_base, int lane, const float (&rs)[MT]) {
   const int r32 = lane & 31, half = lane >> 5;
   const int n0 = nt * 32;
   if (EPI == EPI_STORE) {
@@ -111,6 +123,7 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs& a, const f32x16 (&
       for (int q = 0; q < 4; ++q) {
         const int nrow = n0 + 8 * q + 4 * half;
         f32x4 v = {acc[m][4 * q], acc[m][4 * q + 1], acc[m][4 * q + 2], acc[m][4 * q + 3]};
+        if (a.x_ss) v *= rs[m];
         if (nrow + 3 < a.N) {
           *reinterpret_cast<f32x4*>(dst + nrow) = v;
         } else {
@@ -138,6 +151,7 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs& a, const f32x16 (&
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           float g = acc[m][4 * q + j], u = acc[m][4 * (q + 2) + j];
+          if (a.x_ss) { g *= rs[m]; u *= rs[m]; }
           split_h16<FMT>(g / (1.f + __expf(-g)) * u, hi[j], lo[j]);
         }
         h16_t* dst = a.act + frag_act_offset(orow, feat & ~7, 0, a.act_mtiles, PL) + (feat & 7);
@@ -290,6 +304,17 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
     }
   }
   const size_t x_kstride = (size_t)a.x_mtiles * PL * 512;   // elements between consecutive k-steps
+  // factor the norm left to this kernel's outputs (Act::ss), or 1: the sums are requested first of all, so that
+  // no later wait has to sit through the weight batches for them, and turned into the factor after the first barrier
+  f32x4 ssq[MT];
+  float rs[MT];
+#pragma unroll
+  for (int m = 0; m < MT; ++m) {
+    const int t = (mt0 + m) * 32 + r32;
+    ssq[m] = f32x4{1.f, 1.f, 1.f, 1.f};
+    if (a.x_ss && !grouped) ssq[m] = row_ss(a, t < a.T ? t : 0);
+  }
+  __builtin_amdgcn_sched_barrier(0);
   // Fragment i of this wave belongs to the same token tile in every chunk.  With four token tiles the tile is picked
   // here, once, by comparing the wave number with constants, so that the arrays above are only ever indexed by
   // constants: the compiler turned the run-time choice among four into an indexed access, which put the arrays
@@ -402,6 +427,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
   __builtin_amdgcn_sched_barrier(0);
   stage_store(0, xr);
   __syncthreads();
+  // the factors are complete here (their loads are as old as the first chunk's); the empty statement keeps the
+  // compiler from moving the fetch down to the epilogue, where it would cost a round trip at the end of the kernel
+#pragma unroll
+  for (int m = 0; m < MT; ++m) {
+    rs[m] = (a.x_ss && !grouped) ? row_rstd(a, ssq[m]) : 1.f;
+    asm volatile("" : "+v"(rs[m]));
+  }
   for (int g = 0; g < n_groups; ++g) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -420,7 +452,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_skinny_kernel(GemmArgs a) {
     }
   }
   if (!have_tile) return;
-  tile_epilogue<MT, EPI, PL, FMT>(a, acc, nt, n_tiles, mt0, split, row_base, lane);
+  tile_epilogue<MT, EPI, PL, FMT>(a, acc, nt, n_tiles, mt0, split, row_base, lane, rs);
 }
 
 // ---- expert-grouped decode form: up to 32 rows per expert, J tile groups per workgroup ----
@@ -534,12 +566,17 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_expert_kernel(GemmArgs a) {
   const int r = mt0 * 32 + r32;
   const bool xok = r < a.T;
   const h16_t* xsrc;
+  float rs[1];
+  f32x4 ssq;
   {
     const int rr = xok ? r : 0;
     int row;
     if (a.route_idx) row = my_pair >= 0 ? my_pair / a.top_k : 0;       // the pair's token
     else row = a.x_rows ? a.x_rows[row_base + rr] : row_base + rr;
     xsrc = a.x + frag_act_offset(row, 8 * half, 0, a.x_mtiles, PL);
+    ssq = f32x4{1.f, 1.f, 1.f, 1.f};
+    if (a.x_ss && a.route_idx) ssq = row_ss(a, row);              // the pair's token is the activation row
+    __builtin_amdgcn_sched_barrier(0);
   }
   const size_t x_kstride = (size_t)a.x_mtiles * PL * 512;
   auto stage_load = [&](int chunk, u32x4 (&rg)[PT]) {
@@ -610,6 +647,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_expert_kernel(GemmArgs a) {
   __builtin_amdgcn_sched_barrier(0);
   stage_store(0, xr);
   __syncthreads();
+  rs[0] = (a.x_ss && a.route_idx) ? row_rstd(a, ssq) : 1.f;   // as in the skinny form: fetched first, finished here
+  asm volatile("" : "+v"(rs[0]));
   for (int c = 0; c < n_chunks; ++c) {
     stage_load(c + 1, xr);
     __builtin_amdgcn_sched_barrier(0);
@@ -628,7 +667,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_expert_kernel(GemmArgs a) {
 #pragma unroll
   for (int j = 0; j < J; ++j) {
     const int nt = nt0 + j * W_GROUP;
-    if (nt < n_tiles) tile_epilogue<1, EPI, PL, FMT>(a, reinterpret_cast<const f32x16(&)[1]>(acc[j]), nt, n_tiles, mt0, 0, row_base, lane);
+    if (nt < n_tiles) tile_epilogue<1, EPI, PL, FMT>(a, reinterpret_cast<const f32x16(&)[1]>(acc[j]), nt, n_tiles, mt0, 0, row_base, lane, rs);
   }
 }
 
@@ -821,8 +860,14 @@ __global__ __launch_bounds__(LG_THREADS) void gemm_large_kernel(GemmArgs a) {
   // written out, not a loop: a loop that the compiler declines to unroll (it did with the LM-head epilogue inlined
   // twice) indexes the accumulators at run time, which moves all of them to scratch memory
   const int nt0 = nt_base + 2 * wr;
-  if (nt0 < n_tiles) tile_epilogue<4, EPI, PL, FMT>(a, acc[0], nt0, n_tiles, mt_base + 4 * wt, split, row_base, lane);
-  if (nt0 + 1 < n_tiles) tile_epilogue<4, EPI, PL, FMT>(a, acc[1], nt0 + 1, n_tiles, mt_base + 4 * wt, split, row_base, lane);
+  float rs[4];                                       // rows of long calls come finished from the norm: no factor
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    const int t = (mt_base + 4 * wt + m) * 32 + r32;
+    rs[m] = (a.x_ss && !grouped && t < a.T) ? row_rstd(a, row_ss(a, t)) : 1.f;
+  }
+  if (nt0 < n_tiles) tile_epilogue<4, EPI, PL, FMT>(a, acc[0], nt0, n_tiles, mt_base + 4 * wt, split, row_base, lane, rs);
+  if (nt0 + 1 < n_tiles) tile_epilogue<4, EPI, PL, FMT>(a, acc[1], nt0 + 1, n_tiles, mt_base + 4 * wt, split, row_base, lane, rs);
 }
 
 std::atomic<int> g_units{256};                       // compute units of the device (gemm_set_units): every model on it sets the same value
@@ -933,6 +978,7 @@ int pick_mt(int T) { return T <= 32 ? 1 : (T <= 64 ? 2 : (T <= 128 ? 4 : 8)); }
 
 void fill_x(GemmArgs& a, const Act& x) {
   a.x = x.p; a.x_mtiles = x.mtiles();
+  a.x_ss = x.ss; a.x_eps = x.eps;
 }
 
 }  // namespace
@@ -1039,6 +1085,7 @@ int gemm_grouped_item_rows(int E, int F, int N, const Act& x, int n_pairs, int e
 hipError_t gemm_grouped_swiglu(const h16_t* w_gate_up, int E, int F, int K, const Act& x, const int32_t* x_rows,
                                const int32_t* group_off, int max_rows, int expected_rows, const Act& act,
                                const GroupItems* items, hipStream_t st) {
+  if (x.ss && x_rows) return hipErrorInvalidValue;   // the epilogue would need the row list to find a row's factor
   GemmArgs a = {};
   fill_x(a, x);
   a.x_rows = x_rows;
@@ -1107,6 +1154,7 @@ int lmhead_tiles(int vocab) { return (vocab + 31) / 32; }
 hipError_t gemm_lmhead(const h16_t* w_lm, int V, int K, const Act& x, int T, float* logits, float* part,
                        const uint64_t* seeds, const float* temperature, const int32_t* sample_pos,
                        const int32_t* row_seq, bool draw, hipStream_t st) {
+  if (x.ss) return hipErrorInvalidValue;              // the LM-head epilogue takes finished rows only
   GemmArgs a = {};
   fill_x(a, x);
   a.w[0] = w_lm; a.w_tiles[0] = (V + 31) / 32;

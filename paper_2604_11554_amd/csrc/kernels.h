@@ -21,13 +21,21 @@ inline LinearW linear1(const void* w, int N, int K) {
 // `planes` (1 or 2) terms of format `dtype` (DT_BF16 / DT_F16); two bf16 terms keep 16 significand bits.
 // Kernels are built for bf16 with one or two terms and for fp16 with one term (the second term of an fp16 pair
 // would mostly fall below the smallest normal fp16 number, 6.1e-5, and carry little).
+// ss (optional): the rows are RMS-normalised rows WITHOUT their common factor: row t still has to be multiplied by
+// 1 / sqrt((ss[4t] + ss[4t+1]) + (ss[4t+2] + ss[4t+3])) / K + eps), the four entries being the sums of squares of
+// the four quarters of the row before the gain.  The norm kernel of short calls writes rows in this form (four
+// workgroups per row instead of one) and the GEMM that consumes them applies the factor to its outputs, which is the
+// same product in another order.
 struct Act {
   h16_t* p;
   int T, K, planes, dtype;
+  float* ss;
+  float eps;
   __host__ __device__ int mtiles() const { return (T + 31) / 32; }
 };
+constexpr int NORM_PARTS = 4;
 inline Act make_act(h16_t* p, int T, int K, int planes, int dtype) {
-  Act a = {p, T, K, planes, dtype};
+  Act a = {p, T, K, planes, dtype, nullptr, 0.f};
   return a;
 }
 // Row-major variant [planes][T, ld] (queries of the attention kernel).
@@ -118,6 +126,7 @@ struct NormArgs {
   float* xf;                 // optional fp32 copy of the normalised output
 };
 hipError_t rmsnorm(const NormArgs& a, hipStream_t st);
+bool rmsnorm_in_parts(int d);   // whether rows of d elements can be written in the form of Act::ss
 
 struct RopeArgs {
   const float* qkv;          // [n_planes][T, (Hq+2Hkv)*hd] fp32 split-K planes, summed in plane order
