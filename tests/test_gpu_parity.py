@@ -38,7 +38,8 @@ def bits_to_torch(bits, dev="cuda:0"):
 # ---------------------------------------------------------------------------
 
 @pytest.mark.parametrize("T,N,K", [(1, 32, 64), (5, 36, 256), (64, 6144, 2560), (64, 2560, 9728), (100, 688, 688),
-                                   (33, 2048, 768), (256, 1536, 2048), (300, 256, 2560), (65, 96, 320), (128, 2048, 2048)])
+                                   (33, 2048, 768), (256, 1536, 2048), (300, 256, 2560), (65, 96, 320), (128, 2048, 2048),
+                                   (64, 2560, 4096), (128, 2048, 4096), (128, 128, 2048), (64, 6144, 2576)])
 def test_linear_matches_definition(amd, T, N, K):
     pkg, _ = amd
     say("linear T=%d N=%d K=%d" % (T, N, K))
