@@ -228,6 +228,15 @@ def test_moe_30b_a3b_layer_slice_batch128_sampled_rows():
     _run_case(shape, wl, split=1, n_steps=3, sample_rows=[0, 77], also_fp32_kv=True)
 
 
+def test_moe_30b_a3b_layer_slice_batch200_short_prompts():
+    """Decode steps of 200 tokens at the 30B-A3B per-layer shape: the forms that calls of 129..256 tokens take (two
+    128-token tiles in the store GEMMs, the gate/up kernel grouping 1600 (token, slot) pairs, a pair count that no
+    workgroup size divides, about 12 rows per expert) are not reached by the benchmark batches of 64 and 128."""
+    shape = RI.QWEN3_30B_A3B.replace(name="qwen3_30b_a3b_shape_2layers", n_layers=2)
+    wl = RI.workload_moe_batch(shape, batch=200, prompt_len=24, prompt_seed=14, seed_base=14000)
+    _run_case(shape, wl, split=1, n_steps=3, sample_rows=[3, 150, 199])
+
+
 def test_moe_30b_a3b_full_depth_batch128_sampled_rows():
     """All 48 layers of the 30B-A3B shape with the benchmark's batch (128 sequences, 512-token prompts): the 61 GB of
     weights are drawn on the device, as the benchmark does; the oracle receives them one layer at a time (the same
