@@ -152,6 +152,15 @@ def test_dense_4b_shape_batch64_sampled_rows():
     _run_case(shape, wl, split=1, n_steps=3, sample_rows=rows + late, also_fp32_kv=True)
 
 
+def test_dense_4b_layer_slice_batch200_decode_forms():
+    """Decode steps of 200 tokens at the 4B per-layer shape (a 3-layer slice): the batch of the grouped workload
+    before it shrinks takes the forms of 129..256-token calls (128-token tiles twice over in every GEMM, eleven
+    split-K planes, the norm in quarters), which the 64-sequence batch does not reach."""
+    shape = RI.QWEN3_4B.replace(name="qwen3_4b_shape_3layers", n_layers=3)
+    wl = RI.workload_dense_batch(shape, batch=200, lo=20, hi=90, prompt_seed=12, seed_base=12000)
+    _run_case(shape, wl, split=1, n_steps=3, sample_rows=[0, 101, 199])
+
+
 def test_dense_4b_shape_batch64_sampled_rows_fp16():
     """The FP16 precision option (paper App. "FP16 vs. BF16 precision ablation") at the benchmark's shape:
     fp16 weights and KV pages, one fp16 term per activation, against the oracle with the same fp16 roundings."""
