@@ -369,7 +369,7 @@ RLX_API int rlx_op_linear(const void* x, const void* w, float* y, int32_t n_toke
 #define RLX_K_GATEUP 7      /* gate/up projection + SwiGLU (dense or grouped) */
 #define RLX_K_DOWN 8        /* down projection (dense or grouped)             */
 #define RLX_K_ROUTER 9      /* MoE router logits                              */
-#define RLX_K_GROUP 10      /* MoE top-k + capture + grouping by expert       */
+#define RLX_K_GROUP 10      /* MoE top-k + capture (+ grouping pass, if one runs) */
 #define RLX_K_LMHEAD 11     /* LM head + log-sum-exp / Gumbel-max partials    */
 #define RLX_K_ATTN_PREFIX 12 /* decode: attention over shared prompt prefixes   */
 /*
