@@ -16,6 +16,8 @@ sampling, state update).  Workloads (synthetic, seeded):
   omni_b64   the 30B-A3B shape, 64 sequences of 1024..4096 injected embedding positions plus
              256 ids, then 4 turns of a 128-token tool chunk followed by 512 sampled tokens,
              KV carried across turns
+--replay-report (moe_b128 or dense_b64) times nothing: it generates, then scores the responses with
+the teacher-forced entry point with and without routing replay and reports |dlogprob|.
 Prints ONE JSON line: decode tokens/s, ms/step, the roofline record of the dominant
 kernel (timed in situ with HIP events) and the CPU oracle timed on a bounded sample.
 """
@@ -703,6 +705,130 @@ def prefill_batch_nosample(eng, wl, bsz, plen, chunk_budget, embeds):
     return time.perf_counter() - t0
 
 
+def run_replay_report(args):
+    """Rollout Routing Replay on the library's own two paths (paper Sec. 5.5): sequences are generated by decode steps
+    with the routing captured, then prompt + response are scored by the teacher-forced entry point twice, once with
+    its own routing and once replaying the captured one.  Reported: |log-prob of the rollout - log-prob of the
+    scoring pass| over the response tokens, and how many routed (position, layer) pairs the scoring pass chose
+    differently on its own.  Weights are random, so the figures show the mechanism, not the paper's values."""
+    import torch
+    import paper_2604_11554_amd as pkg
+    import rollout_inputs as RI
+    from paper_2604_11554_amd import synthetic
+
+    dev = "cuda:0"
+    if args.workload == "dense_b64":
+        shape, wl = RI.QWEN3_4B, RI.workload_dense_batch()
+    else:
+        shape, wl = RI.QWEN3_30B_A3B, RI.workload_moe_batch()
+    n_gen = args.steps if args.steps > 0 else 256
+    split = args.split if args.split >= 0 else (1 if args.dtype == "bf16" else 0)
+    bsz, plen = wl.batch, wl.prompt_lens
+    log("replay report: %s, batch %d, prompts %d..%d, %d generated tokens per sequence, %s" % (
+        shape.name, bsz, plen.min(), plen.max(), n_gen, args.dtype))
+    model = gpu_random_model(pkg, synthetic, shape, split, fmt=args.dtype)
+    passes = 3 if shape.is_moe else 2            # the rollout and one row set per scoring pass
+    max_blocks = (int(plen.max()) + n_gen + 15) // 16 + 1
+    n_blocks = passes * int(sum((int(n) + n_gen + 15) // 16 + 1 for n in plen)) + 8
+    chunk_budget = 32768
+    eng = pkg.RolloutEngine(model, n_blocks=n_blocks, max_seqs=passes * bsz, max_chunk_tokens=chunk_budget,
+                            max_blocks_per_seq=max_blocks)
+    for i in range(bsz):
+        eng.add_sequence(int(wl.seeds[i]), float(wl.temperature[i]), max_ctx=int(plen[i]) + n_gen + 8)
+
+    def chunks_of(lens):
+        out, i = [], 0
+        while i < len(lens):
+            j, tot = i, 0
+            while j < len(lens) and tot + int(lens[j]) <= chunk_budget:
+                tot += int(lens[j])
+                j += 1
+            out.append((i, j))
+            i = j
+        return out
+
+    # ---- rollout: prefill, then n_gen - 1 decode steps, tokens / log-probs / routing kept ----
+    gen = torch.zeros((n_gen, bsz), dtype=torch.int32, device=dev)
+    lps = torch.zeros((n_gen, bsz), dtype=torch.float32, device=dev)
+    rout_prompt = []
+    for i, j in chunks_of(plen):
+        out = eng.prefill(list(range(i, j)), wl.prompt_tokens[i:j], want_routing=shape.is_moe)
+        gen[0, i:j] = out.tokens
+        lps[0, i:j] = out.logprobs
+        if shape.is_moe:
+            r = out.routing.cpu().numpy()
+            o = np.concatenate([[0], np.cumsum(plen[i:j])])
+            rout_prompt += [r[o[k]:o[k + 1]] for k in range(j - i)]
+    rout_dec = (torch.zeros((n_gen - 1, bsz, shape.n_layers, shape.top_k), dtype=torch.int32, device=dev)
+                if shape.is_moe else None)
+    for s in range(1, n_gen):
+        eng.decode_step(out_logprobs=lps[s], out_routing=None if rout_dec is None else rout_dec[s - 1])
+        gen[s] = eng.tokens[:bsz]
+    torch.cuda.synchronize()
+    alive = (eng.finished[:bsz] == 0).cpu().numpy()      # a sequence that sampled an end token stops being recorded
+    gen_h, lps_h = gen.cpu().numpy(), lps.cpu().numpy()
+    rout_h = None if rout_dec is None else rout_dec.cpu().numpy()
+    keep = [i for i in range(bsz) if alive[i]]
+    log("rollout done: %d of %d sequences ran all %d steps" % (len(keep), bsz, n_gen - 1))
+
+    toks = [np.concatenate([wl.prompt_tokens[i], gen_h[:-1, i]]).astype(np.int32) for i in keep]
+    tg = []
+    for i, t in zip(keep, toks):
+        x = np.full(len(t), -1, np.int32)
+        x[int(plen[i]) - 1:] = gen_h[:, i]
+        tg.append(x)
+    recorded = ([np.concatenate([rout_prompt[i], rout_h[:, i]]) for i in keep] if shape.is_moe else None)
+
+    def score_pass(replay):
+        rows = [eng.add_sequence(0, float(wl.temperature[i]), reserve_tokens=len(t) + 16) for i, t in zip(keep, toks)]
+        got, used = [], []
+        for a, b in chunks_of([len(t) for t in toks]):
+            lp, rt = eng.score(rows[a:b], toks[a:b], tg[a:b], replay_routing=None if not replay else recorded[a:b],
+                               want_routing=shape.is_moe)
+            lp = lp.cpu().numpy()
+            rt = None if rt is None else rt.cpu().numpy()
+            o = np.concatenate([[0], np.cumsum([len(t) for t in toks[a:b]])])
+            for k in range(b - a):
+                got.append(lp[o[k]:o[k + 1]])
+                if rt is not None:
+                    used.append(rt[o[k]:o[k + 1]])
+        return got, used
+
+    def stats(got):
+        d = np.concatenate([np.abs(g[int(plen[i]) - 1:].astype(np.float64) - lps_h[:, i]) for i, g in zip(keep, got)])
+        return {"tokens": int(d.size), "mean": float(d.mean()), "p99": float(np.quantile(d, 0.99)),
+                "max": float(d.max()), "share_above_1e-3": float((d > 1e-3).mean())}
+
+    rec = {"metric": "|log-prob of the rollout - log-prob of teacher-forced scoring| over the response tokens",
+           "unit": "nats", "n_gpus": 1, "steps": n_gen - 1, "warmup": 0, "higher_is_better": False,
+           "dtype": args.dtype, "data": "synthetic",
+           "config": {"workload": "replay report: %s, batch %d, prompts %d..%d, %d generated tokens per sequence" % (
+               shape.name, bsz, plen.min(), plen.max(), n_gen), "activation_split": split}}
+    own, used = score_pass(False)
+    rec["scoring_with_its_own_routing" if shape.is_moe else "scoring"] = st_own = stats(own)
+    log("scoring with its own %s: mean |dlogprob| %.2e, p99 %.2e, max %.2e, %.2f %% of %d tokens above 1e-3" % (
+        "routing" if shape.is_moe else "kernels", st_own["mean"], st_own["p99"], st_own["max"],
+        100 * st_own["share_above_1e-3"], st_own["tokens"]))
+    rec["value"] = st_own["mean"]
+    if shape.is_moe:
+        differ = sum(int((np.sort(u, axis=-1) != np.sort(r, axis=-1)).any(axis=-1).sum()) for u, r in zip(used, recorded))
+        pairs = sum(u.shape[0] * u.shape[1] for u in used)
+        rec["routed_pairs_chosen_differently"] = {"pairs": pairs, "differ": differ, "share": differ / pairs}
+        log("the scoring pass chose another expert set than the rollout at %d of %d (position, layer) pairs (%.3f %%)" % (
+            differ, pairs, 100.0 * differ / pairs))
+        rep, used = score_pass(True)
+        echoed = all((u == r).all() for u, r in zip(used, recorded))
+        rec["scoring_with_replayed_routing"] = st_rep = stats(rep)
+        rec["replayed_routing_echoed"] = bool(echoed)
+        rec["value"] = st_rep["mean"]
+        log("scoring with the rollout's routing replayed: mean |dlogprob| %.2e, p99 %.2e, max %.2e, %.2f %% above 1e-3 "
+            "(mean %.0f %% lower); replayed ids echoed: %s" % (st_rep["mean"], st_rep["p99"], st_rep["max"],
+                                                            100 * st_rep["share_above_1e-3"],
+                                                            100 * (1 - st_rep["mean"] / st_own["mean"]), echoed))
+    model.close()
+    return rec
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -722,6 +848,9 @@ def main():
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"],
                     help="16-bit format of weights, KV pages and activation terms (f16: the FP16 precision option)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--replay-report", action="store_true",
+                    help="moe_b128 / dense_b64: generate --steps tokens per sequence (default 256), score them with the "
+                         "teacher-forced entry point with and without routing replay, report |dlogprob| (no timing)")
     ap.add_argument("--kernel", default="auto", help="kernel class for the roofline record")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 256 MiB device copy (reference of known size for HBM byte counters)")
@@ -733,7 +862,11 @@ def main():
 
     from paper_2604_11554_amd import binding as B
     B.lib()
-    if args.workload == "grouped_b256" and args.full:
+    if args.replay_report:
+        if args.workload not in ("default", "moe_b128", "dense_b64"):
+            ap.error("--replay-report runs on moe_b128 (the default) or dense_b64")
+        rec = run_replay_report(args)
+    elif args.workload == "grouped_b256" and args.full:
         rec = run_grouped_full(args)
     elif args.workload == "omni_b64":
         rec = run_omni(args)
