@@ -16,6 +16,9 @@ sampling, state update).  Workloads (synthetic, seeded):
   omni_b64   the 30B-A3B shape, 64 sequences of 1024..4096 injected embedding positions plus
              256 ids, then 4 turns of a 128-token tool chunk followed by 512 sampled tokens,
              KV carried across turns
+  stream_b256  the 4B shape, 768 requests of the grouped recipe (own prompt pages) through 256 slots:
+             one batch run to completion, then all requests with every freed slot refilled
+             (wall time incl. prefill; completion event per micro-batch of 32)
 --replay-report (moe_b128 or dense_b64) times nothing: it generates, then scores the responses with
 the teacher-forced entry point with and without routing replay and reports |dlogprob|.
 Prints ONE JSON line: decode tokens/s, ms/step, the roofline record of the dominant
@@ -24,6 +27,7 @@ kernel (timed in situ with HIP events) and the CPU oracle timed on a bounded sam
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -705,6 +709,79 @@ def prefill_batch_nosample(eng, wl, bsz, plen, chunk_budget, embeds):
     return time.perf_counter() - t0
 
 
+def run_stream(args):
+    """Continuous refill against a batch that runs to completion (paper Sec. 3.3, streaming micro-batches): the same
+    long-tailed requests (the grouped workload's recipe, every request with its own prompt pages) pass through 256
+    slots, first 256 of them as one batch with no request behind them, then all of them with every freed slot
+    refilled by the next request and a completion event per micro-batch of 32.  Wall time includes the prefill calls."""
+    import torch
+    import paper_2604_11554_amd as pkg
+    import rollout_inputs as RI
+    from paper_2604_11554_amd import synthetic
+    from paper_2604_11554_amd.engine import Request, StreamingRollout
+
+    shape = RI.QWEN3_4B
+    slots = 256
+    n_req = max(slots, args.requests)
+    wl = RI.workload_grouped(n_prompts=(n_req + 7) // 8)
+    split = args.split if args.split >= 0 else (1 if args.dtype == "bf16" else 0)
+    resp = wl.n_decode.astype(np.int64)[:n_req]
+    reqs = [Request(wl.prompt_tokens[i], int(wl.seeds[i]), 1.0, int(resp[i])) for i in range(n_req)]
+    plen = np.array([len(r.prompt) for r in reqs])
+    log("workload stream_b256: %s, %d requests through %d slots, prompts %d..%d, response lengths geometric mean 2048 "
+        "capped at 8192 (drawn: mean %.0f, max %d, %d tokens in all), %s" % (
+            shape.name, n_req, slots, plen.min(), plen.max(), resp.mean(), resp.max(), resp.sum(), args.dtype))
+    model = gpu_random_model(pkg, synthetic, shape, split, fmt=args.dtype)
+    kv_tok = shape.n_layers * shape.n_kv_heads * shape.head_dim * 2 * 2
+    need = sorted(((int(p) + int(r) + 15) // 16 + 1 for p, r in zip(plen, resp)), reverse=True)
+    n_blocks = min(sum(need), int(200e9) // (16 * kv_tok)) + 8
+
+    def run(requests, label):
+        eng = pkg.RolloutEngine(model, n_blocks=n_blocks, max_seqs=slots, max_chunk_tokens=32768,
+                                max_blocks_per_seq=max(need) + 1)
+        events = []
+        step_fn, n_calls = eng.decode_step, [0]
+
+        def counted_step(*a, **k):               # a progress line every 1024 decode steps
+            n_calls[0] += 1
+            if n_calls[0] % 1024 == 0:
+                log("  %s: decode step %d, %.1f s" % (label, n_calls[0], time.perf_counter() - t0))
+            return step_fn(*a, **k)
+        eng.decode_step = counted_step
+        t0 = time.perf_counter()
+        sr = StreamingRollout(eng, requests, micro_batch=32, poll_every=16, slots=slots,
+                              on_partition=lambda p, c: events.append(time.perf_counter() - t0))
+        done = sr.run()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        toks = int(sum(len(c.tokens) for c in done))
+        sr_steps = sr.decode_steps
+        log("%s: %d requests, %d response tokens in %.1f s (%.0f tok/s), %d decode steps, %.1f rows live per step on "
+            "average, first micro-batch complete after %.1f s, last after %.1f s" % (
+                label, len(requests), toks, wall, toks / wall, sr.decode_steps, toks / max(1, sr.decode_steps),
+                events[0], events[-1]))
+        del eng.decode_step                      # the counting wrapper refers to the engine
+        del sr, eng, done
+        gc.collect()
+        torch.cuda.empty_cache()                 # the next run allocates its own page pool
+        return {"requests": len(requests), "tokens": toks, "seconds": wall, "tokens_per_s": toks / wall,
+                "decode_steps": sr_steps, "mean_live_rows": toks / max(1, sr_steps),
+                "first_micro_batch_s": events[0], "last_micro_batch_s": events[-1]}
+
+    one = run(reqs[:slots], "one batch to completion")
+    allr = run(reqs, "continuous refill")
+    rec = {"metric": METRIC, "value": allr["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": allr["decode_steps"],
+           "warmup": 0, "ms_per_step": 1e3 * allr["seconds"] / allr["decode_steps"], "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+           "config": {"workload": "stream_b256: %s, %d requests through %d slots with continuous refill, prompts %d..%d, "
+                                  "geometric response lengths (mean 2048, cap 8192), wall time incl. prefill" % (
+                                      shape.name, n_req, slots, plen.min(), plen.max()), "activation_split": split},
+           "continuous_refill": allr, "one_batch_to_completion": one,
+           "refill_over_batch": allr["tokens_per_s"] / one["tokens_per_s"]}
+    model.close()
+    return rec
+
+
 def run_replay_report(args):
     """Rollout Routing Replay on the library's own two paths (paper Sec. 5.5): sequences are generated by decode steps
     with the routing captured, then prompt + response are scored by the teacher-forced entry point twice, once with
@@ -837,10 +914,11 @@ def main():
     ap.add_argument("--from-start", action="store_true", help="with --steps: time the first steps of the decode phase instead")
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="default",
-                    choices=["default", "dense_b64", "moe_b128", "grouped_b256", "omni_b64"],
+                    choices=["default", "dense_b64", "moe_b128", "grouped_b256", "omni_b64", "stream_b256"],
                     help="default: moe_b128 as the headline and dense_b64 under \"also\" in the same JSON line")
     ap.add_argument("--full", action="store_true",
                     help="grouped_b256: geometric response lengths with forced EOS and batch compaction, to completion")
+    ap.add_argument("--requests", type=int, default=768, help="stream_b256: requests to pass through the 256 slots")
     ap.add_argument("--no-shared-prefix", action="store_true",
                     help="grouped_b256: read the shared prompt pages once per sequence instead of once per subgroup")
     ap.add_argument("--split", type=int, default=-1,
@@ -870,6 +948,8 @@ def main():
         rec = run_grouped_full(args)
     elif args.workload == "omni_b64":
         rec = run_omni(args)
+    elif args.workload == "stream_b256":
+        rec = run_stream(args)
     elif args.workload == "default":
         rec = run_batch(args, "moe_b128", not args.no_cpu_baseline)
         rec["also"] = {"dense_b64": run_batch(args, "dense_b64", False)}
