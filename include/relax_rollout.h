@@ -32,6 +32,12 @@
  *    argument error (RLX_EINVAL, RLX_ENOMEM, RLX_EUNSUPPORTED) no work has been
  *    enqueued.  RLX_EHIP reports a failed launch part-way through a call: earlier
  *    launches of that call stay enqueued and its outputs are undefined.
+ *  - Empty calls: a decode step with n_seqs == 0, and a chunk call (prefill, scoring)
+ *    with n_seqs == 0 and total_tokens == 0, are valid: they return 0, enqueue nothing
+ *    and read none of the arrays (which may be NULL).  A chunk call with sequences
+ *    needs at least one token in all (total_tokens >= 1); single sequences of a chunk
+ *    may be empty (cu_seqlens[i] == cu_seqlens[i+1]): nothing is appended or sampled for
+ *    them and their outputs are pad / 0 / 0.  Negative counts are RLX_EINVAL.
  *  - A model handle is immutable after creation; concurrent calls must use
  *    distinct workspaces (and distinct sequences of the KV pool).
  */

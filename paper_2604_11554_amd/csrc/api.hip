@@ -365,7 +365,7 @@ int check_common(const rlx_model* m, const void* kv_pool, int64_t n_blocks, cons
   if (!m) return fail(RLX_EINVAL, "model is NULL");
   if (!kv_pool || n_blocks <= 0) return fail(RLX_EINVAL, "kv_pool is NULL or n_blocks <= 0");
   if (!workspace) return fail(RLX_EINVAL, "workspace is NULL");
-  if (n_seqs <= 0 || n_seqs > (1 << 16)) return fail(RLX_EINVAL, "n_seqs %d out of range", n_seqs);
+  if (n_seqs < 0 || n_seqs > (1 << 16)) return fail(RLX_EINVAL, "n_seqs %d out of range", n_seqs);
   if (max_blocks_per_seq <= 0 || max_blocks_per_seq > (1 << 20))
     return fail(RLX_EINVAL, "max_blocks_per_seq %d out of range", max_blocks_per_seq);
   if (!aligned16(kv_pool) || !aligned16(workspace)) return fail(RLX_EINVAL, "kv_pool/workspace not 16-byte aligned");
@@ -546,7 +546,9 @@ int rollout_prefill_chunk(const rlx_model* m, void* kv_pool, int64_t n_blocks, v
                           int32_t* out_routing, float* out_logits, void* stream) {
   int rc = check_common(m, kv_pool, n_blocks, workspace, n_seqs, max_blocks_per_seq);
   if (rc) return rc;
-  if (total_tokens <= 0 || total_tokens > (1 << 24)) return fail(RLX_EINVAL, "total_tokens %d out of range", total_tokens);
+  if (n_seqs == 0 && total_tokens == 0) return RLX_OK;   // an empty call: nothing to enqueue, no array is read
+  if (n_seqs == 0 || total_tokens <= 0 || total_tokens > (1 << 24))
+    return fail(RLX_EINVAL, "total_tokens %d out of range for %d sequences", total_tokens, n_seqs);
   if (!token_ids || !cu_seqlens || !ctx_lens || !block_table || !sample_last || !seeds || !temperature ||
       !max_ctx_len || !out_tokens || !out_logprobs || !finished_out)
     return fail(RLX_EINVAL, "NULL array argument");
@@ -574,7 +576,9 @@ int rollout_score_chunk(const rlx_model* m, void* kv_pool, int64_t n_blocks, voi
                         const int32_t* replay_routing, float* out_logprobs, int32_t* out_routing, void* stream) {
   int rc = check_common(m, kv_pool, n_blocks, workspace, n_seqs, max_blocks_per_seq);
   if (rc) return rc;
-  if (total_tokens <= 0 || total_tokens > (1 << 24)) return fail(RLX_EINVAL, "total_tokens %d out of range", total_tokens);
+  if (n_seqs == 0 && total_tokens == 0) return RLX_OK;   // an empty call: nothing to enqueue, no array is read
+  if (n_seqs == 0 || total_tokens <= 0 || total_tokens > (1 << 24))
+    return fail(RLX_EINVAL, "total_tokens %d out of range for %d sequences", total_tokens, n_seqs);
   if (!token_ids || !cu_seqlens || !ctx_lens || !block_table || !target_ids || !temperature || !out_logprobs)
     return fail(RLX_EINVAL, "NULL array argument");
   if (input_embeds && !aligned16(input_embeds)) return fail(RLX_EINVAL, "input_embeds not 16-byte aligned");
@@ -603,6 +607,7 @@ int rollout_decode_step_shared(const rlx_model* m, void* kv_pool, int64_t n_bloc
                                int32_t* out_routing, float* out_logits, const void* shared_prefix, void* stream) {
   int rc = check_common(m, kv_pool, n_blocks, workspace, n_seqs, max_blocks_per_seq);
   if (rc) return rc;
+  if (n_seqs == 0) return RLX_OK;                         // an empty step: nothing to enqueue, no array is read
   if (!tokens_inout || !ctx_lens_inout || !block_table || !seeds || !temperature || !max_ctx_len ||
       !finished_inout || !out_logprobs)
     return fail(RLX_EINVAL, "NULL array argument");
@@ -644,10 +649,10 @@ int rollout_decode_step_static(const rlx_model* m, void* kv_pool, int64_t n_bloc
                                float* out_logprobs, int32_t* out_sampled, int32_t* out_routing, float* out_logits,
                                void* stream) {
   if (!m) return fail(RLX_EINVAL, "model is NULL");
-  if (n_seqs <= 0 || n_seqs > (1 << 16)) return fail(RLX_EINVAL, "n_seqs %d out of range", n_seqs);
+  if (n_seqs < 0 || n_seqs > (1 << 16)) return fail(RLX_EINVAL, "n_seqs %d out of range", n_seqs);
   if (max_blocks_per_seq <= 0 || max_blocks_per_seq > (1 << 20))
     return fail(RLX_EINVAL, "max_blocks_per_seq %d out of range", max_blocks_per_seq);
-  const size_t need = carve(m->cfg, nullptr, n_seqs, n_seqs, max_blocks_per_seq).bytes;
+  const size_t need = n_seqs ? carve(m->cfg, nullptr, n_seqs, n_seqs, max_blocks_per_seq).bytes : 0;
   if (need > (size_t)RLX_STATIC_WORKSPACE_BYTES)
     return fail(RLX_ENOMEM, "rollout_decode_step_static: a step of %d sequences of this model needs %zu bytes of "
                 "scratch, the fixed array holds %zu; use rollout_decode_step with a workspace of your own", n_seqs,

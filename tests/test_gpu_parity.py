@@ -551,6 +551,63 @@ def test_determinism_block_permutation_and_compaction(amd):
             assert np.abs(zd - ze).max() <= 2e-3
 
 
+def test_empty_calls_enqueue_nothing_and_leave_the_state_alone(amd):
+    """A decode step over no sequences and chunk calls with no sequences and no tokens succeed without reading any
+    array; negative counts and tokens without sequences are argument errors; the engine's state and the next real
+    call are unaffected.  A chunk with one empty sequence among others appends and samples nothing for it."""
+    pkg, synthetic = amd
+    B = pkg.binding
+    shape = RI.TINY_DENSE
+    model, eng = _engine(pkg, synthetic, shape)
+    wl = RI.workload_tiny(shape, lens=(5, 9))
+    for i in range(2):
+        eng.add_sequence(int(wl.seeds[i]), reserve_tokens=48)
+    out = eng.prefill([0, 1], wl.prompt_tokens)
+    torch.cuda.synchronize()
+    before = [t.clone() for t in (eng.tokens, eng.ctx_lens, eng.finished)]
+    none_i32 = torch.empty(0, dtype=torch.int32, device="cuda:0")
+    none_f32 = torch.empty(0, dtype=torch.float32, device="cuda:0")
+    none_u8 = torch.empty(0, dtype=torch.uint8, device="cuda:0")
+    none_u64 = torch.empty(0, dtype=torch.int64, device="cuda:0")
+    h = model.handle
+    say("empty decode step (workspace, shared-prefix and fixed-scratch entry points)")
+    B.rollout_decode_step(h, eng.kv_pool, eng.n_blocks, eng.workspace, 0, none_i32, none_i32, none_i32, eng.max_blocks,
+                          none_u64, none_f32, none_i32, none_u8, None, none_f32)
+    B.rollout_decode_step_shared(h, eng.kv_pool, eng.n_blocks, eng.workspace, 0, none_i32, none_i32, none_i32,
+                                 eng.max_blocks, none_u64, none_f32, none_i32, none_u8, None, none_f32)
+    B.rollout_decode_step_static(h, eng.kv_pool, eng.n_blocks, 0, none_i32, none_i32, none_i32, eng.max_blocks,
+                                 none_u64, none_f32, none_i32, none_u8, None, none_f32)
+    say("empty prefill and scoring chunks")
+    B.rollout_prefill_chunk(h, eng.kv_pool, eng.n_blocks, eng.workspace, 0, 0, none_i32, None, none_i32, none_i32,
+                            none_i32, eng.max_blocks, none_u8, none_u64, none_f32, none_i32, None, none_i32, none_f32,
+                            none_u8, None, None, None)
+    B.rollout_score_chunk(h, eng.kv_pool, eng.n_blocks, eng.workspace, 0, 0, none_i32, None, none_i32, none_i32,
+                          none_i32, eng.max_blocks, none_i32, none_f32, None, none_f32, None)
+    torch.cuda.synchronize()
+    for t, b in zip((eng.tokens, eng.ctx_lens, eng.finished), before):
+        assert torch.equal(t, b)
+    for n_seqs, total in ((-1, 0), (0, 3), (0, -2), (2, 0), (2, -1)):
+        with pytest.raises(B.RlxError) as e:
+            B.rollout_prefill_chunk(h, eng.kv_pool, eng.n_blocks, eng.workspace, n_seqs, total, none_i32, None, none_i32,
+                                    none_i32, none_i32, eng.max_blocks, none_u8, none_u64, none_f32, none_i32, None,
+                                    none_i32, none_f32, none_u8, None, None, None)
+        assert e.value.code == B.RLX_EINVAL
+    with pytest.raises(B.RlxError) as e:
+        B.rollout_decode_step(h, eng.kv_pool, eng.n_blocks, eng.workspace, -1, none_i32, none_i32, none_i32,
+                              eng.max_blocks, none_u64, none_f32, none_i32, none_u8, None, none_f32)
+    assert e.value.code == B.RLX_EINVAL
+    # an empty sequence next to a real one: its cache length stays, it emits pad / 0 and is not marked finished
+    say("chunk with one empty sequence")
+    tok1 = int(eng.tokens[1].item())
+    ctx0 = eng.ctx_lens.clone()
+    o2 = eng.prefill([0, 1], [np.zeros(0, np.int32), np.array([tok1], np.int32)], want_sampled=True)
+    torch.cuda.synchronize()
+    assert int(eng.ctx_lens[0]) == int(ctx0[0]) and int(eng.ctx_lens[1]) == int(ctx0[1]) + 1
+    assert float(o2.logprobs[0]) == 0.0 and int(o2.sampled[0]) == -1
+    assert float(o2.logprobs[1]) < 0.0 and int(o2.sampled[1]) >= 0
+    model.close()
+
+
 def test_error_codes(amd):
     pkg, synthetic = amd
     B = pkg.binding
