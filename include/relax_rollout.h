@@ -149,7 +149,7 @@ RLX_API int rlx_model_destroy(rlx_model* m);
 
 /*
  * Tuning knob: the number of workgroups of the decode attention kernel.  A decode step lays the 32-key units of
- * all (sequence, KV head) pairs end to end and gives each workgroup a contiguous share (all within four units of each other); the default is
+ * all (sequence, KV head) pairs end to end and gives each workgroup a contiguous share (all within one unit of each other); the default is
  * two workgroups per compute unit (the grid that is exactly resident).  1 <= n_workgroups <= 1024; results do
  * not depend on it beyond the order in which partial softmax states are merged.  Not thread-safe against calls
  * that use the model.

@@ -3,7 +3,7 @@
 // One new token per sequence; the 16 MFMA columns of a tile are the query heads of one KV head
 // (group <= 16), so a KV page is read once for all heads of its group.  The work of a step is the
 // sequence of 32-key units of all (sequence, KV head) pairs laid end to end; every workgroup takes a
-// contiguous share of it, all shares within four units of each other (the plan is built once per step,
+// contiguous share of it, all shares within one unit of each other (the plan is built once per step,
 // contexts being the same for every layer), so the grid is exactly resident (two workgroups per compute unit) and every workgroup streams
 // for the whole kernel instead of paying its start-up and wind-down latency per 256 keys.  Within a
 // share the four waves take units round-robin, each keeping the next unit's pages in flight while it
@@ -56,7 +56,7 @@ __device__ __forceinline__ int shared_units_of(const SharedView& v, int seq, int
   return v.on ? min(max(v.start_unit[seq], 0), ctx / 32) : 0;
 }
 
-// Shares of two sizes: workgroups 0 .. H-1 take CA units each, the others CB = CA - 4, which may be zero (plan
+// Shares of two sizes: workgroups 0 .. H-1 take CA units each, the others CB = CA - 1, which may be zero (plan
 // header: CA, total, CB, H).
 struct Shares {
   int CA, CB, H, U;
@@ -460,11 +460,14 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(int n_seqs, const int32
   if (tid == 0) unit_prefix[n_seqs] = per_head;
   __syncthreads();                                   // the prefix is read back below
   const int total = per_head * Hkv;
-  // share sizes are multiples of four (the four waves get equal counts) that differ by at most four: the quads of
-  // the step are dealt out evenly and the first H workgroups take the remainder, one quad each.  (One size for
-  // all, rounded up, left a tenth of the workgroups without work at the benchmark's contexts.)
-  const int quads = (total + 3) / 4, q = quads / n_wgs, H = quads % n_wgs;
-  const int CA = 4 * (q + 1), CB = 4 * q;
+  // share sizes differ by at most one unit: the units of the step are dealt out evenly and the first H workgroups
+  // take the remainder, one unit each.  (One size for all, rounded up, left a tenth of the workgroups without work
+  // at the benchmark's contexts; sizes in multiples of four units, so that the four waves of a share get equal
+  // counts, made the longer shares up to a tenth longer than the mean, and the waves' counts are unequal anyway
+  // wherever a pair's boundary falls inside a share.)  With as many (sequence, KV head) pairs as workgroups and
+  // equal contexts a share is exactly a pair: nothing straddles and nothing is left to merge.
+  const int q = total / n_wgs, H = total % n_wgs;
+  const int CA = q + 1, CB = q;
   if (tid == 0) { hdr[0] = CA; hdr[1] = total; hdr[2] = CB; hdr[3] = H; }
   const Shares shr = Shares{CA, CB, H, total};
   for (int w = tid; w < n_wgs; w += 1024) {
