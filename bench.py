@@ -407,7 +407,7 @@ def run_batch(args, workload, with_cpu_baseline):
     ratio, ratio_src = traffic_record(workload, dom)
     traffic = None if ratio is None or not durs else ratio * float(np.mean(ach_bytes))
     # a page shared by the eight members of a group counts once (the strict algorithmic minimum; the prefix tiles
-    # read it once per subgroup of 16 / (n_q_heads / n_kv_heads) members); with no groups the two figures coincide
+    # read it once per subgroup of 32 / (n_q_heads / n_kv_heads) members); with no groups the two figures coincide
     uniq = (ctx0 - shared_pages_tok).sum() + (shared_pages_tok.sum() // 8 if grouped else 0)
     tch = (lambda s: None) if touched is None else (lambda s: float(touched[s]))
     step_b = np.mean([step_bytes(shape, int(uniq + (s + 1) * bsz), bsz, tch(s)) for s in range(K)])

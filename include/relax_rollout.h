@@ -323,8 +323,9 @@ RLX_API int rollout_decode_step_static(const rlx_model* m, void* kv_pool, int64_
  * Decode over shared prompt prefixes.  Sequences of one sampling group (the G responses drawn for one prompt by
  * the group-relative algorithms of paper Sec. 2.1, e.g. 8 per prompt) list the same physical pages for their
  * prompt in their block-table rows.  rollout_decode_step reads those pages once per sequence; with a descriptor
- * of the sharing, rollout_decode_step_shared reads them once per subgroup of 16 / (n_q_heads / n_kv_heads)
- * sequences (their query heads fill the 16 matrix-core columns that one sequence leaves mostly empty) and merges
+ * of the sharing, rollout_decode_step_shared reads them once per subgroup of 32 / (n_q_heads / n_kv_heads)
+ * sequences, at most 16 (their query heads fill the matrix-core columns that one sequence leaves mostly empty:
+ * two column tiles of 16) and merges
  * the two parts of each sequence's softmax.  The results equal rollout_decode_step's up to the order of the
  * floating-point merges.
  *

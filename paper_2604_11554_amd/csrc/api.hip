@@ -107,7 +107,7 @@ struct Workspace {
   float* attn_part;  // [attn_wgs][2][Hq/Hkv][hd+4] decode partials of straddling (sequence, KV head) pairs
   int32_t *attn_prefix, *attn_wg_seq, *attn_hdr;   // decode attention plan
   float* attn_seq_part;   // [S][Hkv][Hq/Hkv][hd+4] own part of a pair that prefix tiles precede
-  float* attn_pre_part;   // [shared_prefix_max_tiles][16][hd+4] parts of the shared-prefix tiles
+  float* attn_pre_part;   // [shared_prefix_max_tiles][SP_COLS][hd+4] parts of the shared-prefix tiles
   float* planes;     // split-K planes of the o / down projections
   h16_t* act;       // dense [T, F]; MoE [T*top_k, Fe]
   float* moe_y;      // [T*top_k, d]
@@ -162,7 +162,7 @@ Workspace carve(const rlx_model_config& c, char* base, int S, int T, int max_blo
   w.attn_wg_seq = (int32_t*)take((size_t)ATTN_WGS_MAX * 4);
   w.attn_hdr = (int32_t*)take(4 * 4);
   w.attn_seq_part = (float*)take((size_t)S * c.n_q_heads * (c.head_dim + 4) * 4);
-  w.attn_pre_part = (float*)take((size_t)shared_prefix_max_tiles(S, c.n_kv_heads) * 16 * (c.head_dim + 4) * 4);
+  w.attn_pre_part = (float*)take((size_t)shared_prefix_max_tiles(S, c.n_kv_heads) * SP_COLS * (c.head_dim + 4) * 4);
   // o / down planes: up to 16 per token for short calls, two for long ones (gemm_plan_splits_long)
   w.planes = (float*)take((size_t)(T <= 256 ? plane_rows(T) : 2 * T) * c.d_model * 4);
   if (c.n_experts) {

@@ -13,9 +13,10 @@
 //
 // Shared prompt prefixes (sequences of one sampling group list the same pages for their prompt): the descriptor
 // `shared` names, per sequence, how many leading units are served by prefix tiles instead.  A prefix tile is
-// (subgroup of up to 16 / group sequences, KV head, chunk of units): its 16 MFMA columns are the query heads of
-// all its member sequences, so the shared pages are read once per subgroup instead of once per sequence; the
-// per-sequence kernel starts after the shared units, and the merge kernel adds the prefix parts first.
+// (subgroup of up to 32 / group sequences, KV head, chunk of units): the 32 columns of its two MFMA column tiles
+// are the query heads of all its member sequences, so the shared pages are read once per subgroup (the eight
+// responses of a prompt at the 4B shape) instead of once per sequence; the per-sequence kernel starts after the
+// shared units, and the merge kernel adds the prefix parts first.
 #include "attn_core.h"
 
 namespace rlx {
@@ -280,14 +281,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
 }
 
-// Prefix tiles: workgroup t, t + grid, ... takes tile t of the descriptor.  The 16 columns are (member, head of
+// Prefix tiles: workgroup t, t + grid, ... takes tile t of the descriptor.  The NCT x 16 columns are (member, head of
 // the KV head's group); every key of the tile's units is visible to every member (the pages are full and shared).
-// The four waves take units round-robin and are merged through LDS; (o, m, l) of all 16 columns go to pre_part.
-template <int HD, int PL, int FMT>
-__global__ __launch_bounds__(256) void attn_decode_prefix_kernel(AttnDecodeArgs a) {
-  constexpr int DT = HD / 16, KS = HD / 32, PS = HD + 4;
-  __shared__ f32x4 lds_o[2 * DT * WAVE];
-  __shared__ float lds_ml[2 * 2 * WAVE];
+// The four waves take units round-robin and are merged through LDS; (o, m, l) of all columns go to pre_part.  The
+// query fragments of a tile sit in LDS (with two column tiles they would take half the register file).
+template <int HD, int PL, int FMT, int NCT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_decode_prefix_kernel(AttnDecodeArgs a) {
+  constexpr int DT = HD / 16, KS = HD / 32, PS = HD + 4, NQ = PL * NCT * KS;
+  __shared__ f32x4 lds_o[2 * NCT * DT * WAVE];
+  __shared__ float lds_ml[2 * NCT * 2 * WAVE];
+  __shared__ u32x4 lds_q[NQ * WAVE];                 // fragment (p, c, ks) at ((p * NCT + c) * KS + ks) * 64 + lane
   const SharedView sv = shared_view(a.shared, a.n_seqs, a.Hkv);
   if (!sv.on) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -299,20 +302,33 @@ __global__ __launch_bounds__(256) void attn_decode_prefix_kernel(AttnDecodeArgs 
     const int row = min(max(sv.t_row[t], 0), a.n_seqs - 1);
     const int kvh = min(max(sv.t_kvh[t], 0), a.Hkv - 1);
     const int lo = max(sv.t_lo[t], 0), hi = min(sv.t_hi[t], a.max_blocks / 2);
-    const int mem = sv.t_mem[(size_t)t * 16 + min(c16 / group, 15)];
-    const bool col_ok = mem >= 0 && mem < a.n_seqs;
-    const int head = kvh * group + c16 % group;
-    h16x8 qf[PL][KS];
+    // the waves share the fetch of the tile's query fragments
 #pragma unroll
-    for (int p = 0; p < PL; ++p)
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        qf[p][ks] = col_ok ? load_h16x8(a.q.p + p * a.q.plane + ((size_t)mem * a.Hq + head) * HD + 32 * ks + 8 * g)
-                           : zero_h16x8();
-    WaveState<HD, 1> st;
+    for (int i = 0; i < (NQ + 3) / 4; ++i) {
+      const int f = wave + 4 * i;
+      if (f < NQ) {
+        const int p = f / (NCT * KS), c = (f / KS) % NCT, ks = f % KS;
+        const int col = 16 * c + c16, mi = col / group;
+        const int mem = mi < 16 ? sv.t_mem[(size_t)t * 16 + mi] : -1;
+        const bool col_ok = mem >= 0 && mem < a.n_seqs;
+        const int head = kvh * group + col % group;
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        u32x4 q = z;
+        if (col_ok)
+          q = *reinterpret_cast<const u32x4*>(a.q.p + p * a.q.plane + ((size_t)mem * a.Hq + head) * HD + 32 * ks + 8 * g);
+        lds_q[f * WAVE + lane] = q;
+      }
+    }
+    __syncthreads();
+    auto qf = [&](int p, int c, int ks) {
+      return __builtin_bit_cast(h16x8, lds_q[((p * NCT + c) * KS + ks) * WAVE + lane]);
+    };
+    WaveState<HD, NCT> st;
     st.reset();
     const int32_t* table = a.block_table + (size_t)row * a.max_blocks;
-    const int pos_col[1] = {0x7FFFFFFF};
+    int pos_col[NCT];
+#pragma unroll
+    for (int c = 0; c < NCT; ++c) pos_col[c] = 0x7FFFFFFF;
     for (int i = lo + wave; i < hi; i += 4) {          // 2 i + 1 < max_blocks by the clamp of hi
       int64_t b0 = table[2 * i], b1 = table[2 * i + 1];
       const bool ok0 = b0 >= 0 && b0 < a.n_blocks, ok1 = b1 >= 0 && b1 < a.n_blocks;
@@ -330,18 +346,21 @@ __global__ __launch_bounds__(256) void attn_decode_prefix_kernel(AttnDecodeArgs 
       for (int dt = 0; dt < DT; ++dt)
         vf[dt] = load_2x4(kp0 + 16 * HD + (size_t)(16 * dt + c16) * 16 + 4 * g,
                           kp1 + 16 * HD + (size_t)(16 * dt + c16) * 16 + 4 * g);
-      pair_step<HD, 1, PL, FMT>(st, k0, k1, vf, [&](int p, int, int ks) { return qf[p][ks]; }, 32 * i, 32 * i + 16, ok0,
-                                ok1, 0x7FFFFFFF, pos_col, scale, g);
+      asm volatile("" ::: "memory");                   // query fragments are re-read from LDS, not kept in registers
+      pair_step<HD, NCT, PL, FMT>(st, k0, k1, vf, qf, 32 * i, 32 * i + 16, ok0, ok1, 0x7FFFFFFF, pos_col, scale, g);
     }
     st.finish_denominators();
-    merge_waves<HD, 1>(st, lds_o, lds_ml, wave, lane);
+    merge_waves<HD, NCT>(st, lds_o, lds_ml, wave, lane);
     if (wave == 0) {
-      float* dst = a.pre_part + ((size_t)t * 16 + c16) * PS;
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4*>(dst + 16 * dt + 4 * g) = st.o[0][dt];
-      if (g == 0) { dst[HD] = st.m[0]; dst[HD + 1] = st.l[0]; }
+      for (int c = 0; c < NCT; ++c) {
+        float* dst = a.pre_part + ((size_t)t * SP_COLS + 16 * c + c16) * PS;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4*>(dst + 16 * dt + 4 * g) = st.o[c][dt];
+        if (g == 0) { dst[HD] = st.m[c]; dst[HD + 1] = st.l[c]; }
+      }
     }
-    __syncthreads();                                   // the merge buffers are free for the next tile
+    __syncthreads();                                   // the merge buffers and the fragments are free for the next tile
   }
 }
 
@@ -365,7 +384,7 @@ __global__ __launch_bounds__(256) void attn_decode_merge_kernel(AttnDecodeArgs a
   if (su > 0) {
     n_chunks = min(max(sv.n_chunks[seq], 0), SP_MAX_CHUNKS);
     tile0 = max(sv.tile0[seq], 0);
-    col0 = min(max(sv.col0[seq], 0), 16 - group);
+    col0 = min(max(sv.col0[seq], 0), SP_COLS - group);
   }
   for (int uu = lane; uu < group * HD / 8; uu += (int)blockDim.x) {   // one pass: the block has a thread per slice
     const int j = uu / (HD / 8), d0 = (uu % (HD / 8)) * 8;
@@ -391,7 +410,7 @@ __global__ __launch_bounds__(256) void attn_decode_merge_kernel(AttnDecodeArgs a
     };
     for (int c = 0; c < n_chunks; ++c) {
       const int t = min(tile0 + c * a.Hkv + kvh, sv.max_tiles - 1);
-      add_at(a.pre_part + ((size_t)t * 16 + col0 + j) * PS);
+      add_at(a.pre_part + ((size_t)t * SP_COLS + col0 + j) * PS);
     }
     if (np && w_first == w_last) {
       add_at(a.seq_part + (((size_t)seq * a.Hkv + kvh) * group + j) * PS);
@@ -493,9 +512,9 @@ hipError_t attention_decode_plan(int n_seqs, const int32_t* ctx_lens, const uint
 
 // Host side of the descriptor.  A group is a run of consecutive sequences with the same leader (the first of them);
 // its shared units are the smallest shared page count of its members, halved.  Groups of one, groups that share
-// less than one unit, and models whose 16 columns hold a single sequence get no tiles.
+// less than one unit, and models whose 32 columns hold a single sequence get no tiles.
 void shared_prefix_build(int n_seqs, int Hq, int Hkv, const int32_t* leader, const int32_t* shared_pages, int32_t* words) {
-  const int group = Hq / Hkv, MS = 16 / group;
+  const int group = Hq / Hkv, MS = shared_prefix_members(group);
   const int max_tiles = shared_prefix_max_tiles(n_seqs, Hkv);
   const size_t n_words = shared_prefix_words(n_seqs, Hkv);
   for (size_t i = 0; i < n_words; ++i) words[i] = 0;
@@ -549,19 +568,28 @@ void shared_prefix_build(int n_seqs, int Hq, int Hkv, const int32_t* leader, con
   words[1] = n_tiles;
 }
 
+template <int HD, int PL, int FMT>
+static void launch_prefix(const AttnDecodeArgs& a, dim3 grid, hipStream_t st) {
+  // one column tile holds all members when there is one query head per KV head; two otherwise
+  if (shared_prefix_members(a.Hq / a.Hkv) * (a.Hq / a.Hkv) <= 16)
+    hipLaunchKernelGGL((attn_decode_prefix_kernel<HD, PL, FMT, 1>), grid, dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL((attn_decode_prefix_kernel<HD, PL, FMT, 2>), grid, dim3(256), 0, st, a);
+}
+
 hipError_t attention_decode_prefix(const AttnDecodeArgs& a, hipStream_t st) {
   if (!a.shared) return hipSuccess;
   dim3 grid(a.n_prefix_wgs);
   const bool two = a.q.planes == 2;
   if (a.o.dtype == DT_F16) {
-    if (a.hd == 128) hipLaunchKernelGGL((attn_decode_prefix_kernel<128, 1, DT_F16>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((attn_decode_prefix_kernel<64, 1, DT_F16>), grid, dim3(256), 0, st, a);
+    if (a.hd == 128) launch_prefix<128, 1, DT_F16>(a, grid, st);
+    else launch_prefix<64, 1, DT_F16>(a, grid, st);
   } else if (a.hd == 128) {
-    if (two) hipLaunchKernelGGL((attn_decode_prefix_kernel<128, 2, DT_BF16>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((attn_decode_prefix_kernel<128, 1, DT_BF16>), grid, dim3(256), 0, st, a);
+    if (two) launch_prefix<128, 2, DT_BF16>(a, grid, st);
+    else launch_prefix<128, 1, DT_BF16>(a, grid, st);
   } else {
-    if (two) hipLaunchKernelGGL((attn_decode_prefix_kernel<64, 2, DT_BF16>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((attn_decode_prefix_kernel<64, 1, DT_BF16>), grid, dim3(256), 0, st, a);
+    if (two) launch_prefix<64, 2, DT_BF16>(a, grid, st);
+    else launch_prefix<64, 1, DT_BF16>(a, grid, st);
   }
   return hipGetLastError();
 }

@@ -190,17 +190,21 @@ struct AttnDecodeArgs {      // one new token per sequence: row = sequence slot
   // once per group by attention_decode_prefix; the kernels above then start at unit sp.start_unit[seq]
   const int32_t* shared;     // descriptor built by shared_prefix_build (device), or null
   float* seq_part;           // [n_seqs][Hkv][Hq/Hkv][hd+4] partial of a pair that one share covered but a prefix precedes
-  float* pre_part;           // [shared_prefix_max_tiles][16][hd+4] partials of the prefix tiles
+  float* pre_part;           // [shared_prefix_max_tiles][SP_COLS][hd+4] partials of the prefix tiles
   int n_prefix_wgs;          // grid of the prefix kernel
 };
 // Descriptor of the shared prefixes of a batch, int32 words (built on the host, read by the kernels):
-//   [0] n_seqs it was built for, [1] n_tiles, [2] members per tile MS = 16 / (Hq/Hkv), [3..7] 0
+//   [0] n_seqs it was built for, [1] n_tiles, [2] members per tile MS = min(16, SP_COLS / (Hq/Hkv)), [3..7] 0
 //   per sequence (4 arrays of n_seqs): start_unit, tile0 (first tile of its subgroup), n_chunks, col0 (its first column)
 //   per tile (arrays of max_tiles): row (sequence whose block-table row lists the pages), kvh, unit lo, unit hi,
 //   then members [max_tiles][16] (-1 = none).  Tile of (subgroup, chunk c, kvh) = tile0 + c * Hkv + kvh.
 constexpr int SP_HDR = 8;
 constexpr int SP_MAX_CHUNKS = 4;
-__host__ __device__ inline int shared_prefix_max_tiles(int n_seqs, int Hkv) { return n_seqs * 2 * Hkv; }
+constexpr int SP_COLS = 32;          // columns of a prefix tile: two matrix-core column tiles of 16
+__host__ __device__ inline int shared_prefix_members(int group) { return group > 0 && SP_COLS / group < 16 ? SP_COLS / group : 16; }
+// a subgroup has at least two members wherever the groups have, and at most one more subgroup per group than
+// members / 2: tiles = subgroups x chunks x Hkv fit with at least one chunk each
+__host__ __device__ inline int shared_prefix_max_tiles(int n_seqs, int Hkv) { return n_seqs * Hkv; }
 inline size_t shared_prefix_words(int n_seqs, int Hkv) {
   return (size_t)SP_HDR + 4 * (size_t)n_seqs + (size_t)shared_prefix_max_tiles(n_seqs, Hkv) * (4 + 16);
 }

@@ -202,8 +202,8 @@ def test_dense_4b_shape_sampling_groups_shared_prefix_sampled_rows():
     assert eng.n == len(rows)
     desc = eng._shared_prefix()
     n_tiles = int(desc[:8].view(torch.int32)[1].item())
-    # 21 and 10 shared units: 3 and 2 chunks x 2 subgroups of four members x 8 KV heads
-    assert n_tiles == (3 + 2) * 2 * shape.n_kv_heads, n_tiles
+    # 21 and 10 shared units: 3 and 2 chunks x one subgroup of the eight members x 8 KV heads
+    assert n_tiles == (3 + 2) * shape.n_kv_heads, n_tiles
     sample = [3, members + 6]                                 # a member of each group
     got = {r: [(int(o.tokens[r]), float(o.logprobs[r]), o.logits[r].cpu().numpy())] for r in sample}
     for s in range(n_steps):

@@ -19,8 +19,8 @@ COMPACT_AT = 9
 # (prompt length, members): 4 and 8 shared pages, 2 shared pages (one unit), 1 shared page (nothing to share),
 # then two sequences on their own; 40 steps
 SHORT = ([(75, 5), (130, 3), (33, 2), (20, 2), (50, 1), (9, 1)], 40)
-# prefixes of 19 and 9 units: several chunks per subgroup (a chunk is at least eight units), more than one subgroup
-# at the MoE shape's two members per tile; 12 steps
+# prefixes of 19 and 9 units: several chunks per subgroup (a chunk is at least eight units); 12 steps.  (More than
+# one subgroup per group: the five members plus donor of SHORT at the MoE shape's four members per tile.)
 LONG = ([(620, 3), (300, 2), (40, 1)], 12)
 
 
@@ -127,9 +127,9 @@ def test_group_decode_over_shared_prefix_matches_oracle(amd, shape_name, case):
     gs, tiles = _gpu(pkg, synthetic, shape, prompts, forced, True, GROUPS, N_STEPS)
     say("%s: gpu without" % shape.name)
     gu, tiles_u = _gpu(pkg, synthetic, shape, prompts, forced, False, GROUPS, N_STEPS)
-    ms = 16 // (shape.n_q_heads // shape.n_kv_heads)
+    ms = min(16, 32 // (shape.n_q_heads // shape.n_kv_heads))
     # tiles = subgroups x chunks x KV heads over the groups that share at least one unit (donor included until the
-    # compaction); a chunk holds at least eight units and a subgroup has at most four
+    # compaction); a chunk holds at least eight units and a subgroup has at most ms members
     def n_tiles(extra):
         n = 0
         for p, m in GROUPS:
@@ -241,7 +241,7 @@ def test_shared_prefix_descriptor_validation(amd):
     desc = torch.empty(B.rlx_shared_prefix_bytes(model.handle, 4), dtype=torch.uint8, device="cuda:0")
     B.rlx_shared_prefix_build(model.handle, [0, 0, 0, 3], [4, 4, 5, 0], desc)
     hdr = desc[:32].view(torch.int32).cpu().numpy()
-    assert hdr[0] == 4 and hdr[2] == 8 and hdr[1] == 2           # one subgroup, one chunk of two units, two KV heads
+    assert hdr[0] == 4 and hdr[2] == 16 and hdr[1] == 2          # one subgroup, one chunk of two units, two KV heads
     start = desc[32:48].view(torch.int32).cpu().numpy()
     assert list(start) == [2, 2, 2, 0]
     for leader, pages in (([0, 2, 0, 3], [4, 4, 4, 0]), ([0, 0, 0, 3], [4, -1, 4, 0]), ([1, 0, 0, 3], [4, 4, 4, 0])):
